@@ -1,0 +1,441 @@
+// Construction of the token-affinity kernel M (section 3 of the paper, Eq. 2), run once at
+// preprocessing time:  M_ij = exp(Omega_ij / tau) / sum_k exp(Omega_ik / tau), i kept, j any target id,
+// with Omega_ij the cosine similarity of embedding rows.  All affinity arithmetic here is fp64: the
+// exponent Omega / tau amplifies rounding by 1 / tau, and speed is secondary for a one-off step.
+//
+// Sparse (top-k) form: for each pruned id the k most similar kept slots are found by a blocked sweep
+// over the kept embeddings; Eq. 2 is then normalised over the retained entries of each row.  Row sums
+// are accumulated in 2^-40 fixed point so that the result does not depend on the order of the atomics.
+#include "rdk_device.hpp"
+
+namespace rdk {
+
+namespace {
+
+constexpr int kTile = 64;       // ids / slots per tile side
+constexpr int kDepth = 32;      // embedding columns per LDS stage
+constexpr double kFixScale = 1099511627776.0;  // 2^40
+
+struct BuildWs {
+    double *inv_norm;           // [N]
+    unsigned long long *zfix;   // [n]   sum of unnormalised neighbour weights, fixed point
+    int32_t *pruned_ids;        // [N-n]
+    double *nbr_a;              // [(N-n), k]  unnormalised weights exp((Omega-1)/tau)
+    int32_t *nbr_s;             // [(N-n), k]
+    double *row_sum;            // [n]   dense build
+};
+
+BuildWs carve(const rdk_kernel_desc_t &d, void *ws)
+{
+    BuildWs w;
+    char *p = (char *)ws;
+    const size_t np = (size_t)(d.N - d.n), k = (size_t)(d.k > 0 ? d.k : 0);
+    w.inv_norm = (double *)p; p += align_up((size_t)d.N * 8, 256);
+    w.zfix = (unsigned long long *)p; p += align_up((size_t)d.n * 8, 256);
+    w.pruned_ids = (int32_t *)p; p += align_up((np + 1) * 4, 256);
+    w.nbr_a = (double *)p; p += align_up((np * k + 1) * 8, 256);
+    w.nbr_s = (int32_t *)p; p += align_up((np * k + 1) * 4, 256);
+    w.row_sum = (double *)p;
+    return w;
+}
+
+__global__ void slot_of_kernel(const int32_t *kept_ids, int n, int N, int32_t *slot_of)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= N) return;
+    int lo = 0, hi = n;   // first slot whose id is >= j
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (kept_ids[mid] < j) lo = mid + 1; else hi = mid;
+    }
+    slot_of[j] = (lo < n && kept_ids[lo] == j) ? lo : -((j - lo) + 1);
+}
+
+__global__ void check_kept_kernel(const int32_t *kept_ids, int n, int N, int32_t *flag)
+{
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= n) return;
+    const int v = kept_ids[s];
+    if (v < 0 || v >= N || (s > 0 && kept_ids[s - 1] >= v)) atomicOr(flag, 1);
+}
+
+__global__ void fill_zero_kernel(unsigned long long *x, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) x[i] = 0ull;
+}
+
+__global__ void fill_flag_kernel(int32_t *x) { *x = 0; }
+
+__global__ void inv_norm_kernel(const float *E, int N, int d, double *inv_norm)
+{
+    const int j = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (j >= N) return;
+    double s = 0.0;
+    for (int c = lane_id(); c < d; c += kWave) {
+        const double v = (double)E[(int64_t)j * d + c];
+        s += v * v;
+    }
+    s = wave_sum(s);
+    if (lane_id() == 0) inv_norm[j] = 1.0 / sqrt(s);
+}
+
+__global__ void pruned_ids_kernel(const int32_t *slot_of, int N, int32_t *pruned_ids)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < N && slot_of[j] < 0) pruned_ids[-slot_of[j] - 1] = j;
+}
+
+// Cosine similarities of a 64 x 64 tile: rows = ids `row_ids[r0..]`, columns = ids `col_ids[c0..]`
+// (NULL id list = the identity).  256 threads, each a 4 x 4 micro-tile in fp64; the result is left in
+// om[64][65].  Entries outside the ranges are -2 (below any cosine).
+__device__ __forceinline__ void affinity_tile(const float *E, int d, const double *inv_norm, const int32_t *row_ids, int r0,
+                                              int n_rows, const int32_t *col_ids, int c0, int n_cols,
+                                              float (*ea)[kDepth + 1], float (*eb)[kDepth + 1], double (*om)[kTile + 1])
+{
+    const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+    double acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    for (int dc = 0; dc < d; dc += kDepth) {
+        __syncthreads();
+        for (int t = threadIdx.x; t < kTile * kDepth; t += blockDim.x) {
+            const int r = t / kDepth, c = t % kDepth;
+            float va = 0.f, vb = 0.f;
+            if (dc + c < d) {
+                if (r0 + r < n_rows) va = E[(int64_t)(row_ids ? row_ids[r0 + r] : r0 + r) * d + dc + c];
+                if (c0 + r < n_cols) vb = E[(int64_t)(col_ids ? col_ids[c0 + r] : c0 + r) * d + dc + c];
+            }
+            ea[r][c] = va;
+            eb[r][c] = vb;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int c = 0; c < kDepth; ++c) {
+            double a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = (double)ea[ty * 4 + i][c];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = (double)eb[tx * 4 + j][c];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = ty * 4 + i;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = tx * 4 + j;
+            double v = -2.0;
+            if (r0 + r < n_rows && c0 + c < n_cols) {
+                const int ir = row_ids ? row_ids[r0 + r] : r0 + r;
+                const int ic = col_ids ? col_ids[c0 + c] : c0 + c;
+                v = acc[i][j] * inv_norm[ir] * inv_norm[ic];
+            }
+            om[r][c] = v;
+        }
+    }
+    __syncthreads();
+}
+
+// Top-k kept slots per pruned id.  One workgroup owns 64 pruned ids and sweeps all kept slots in tiles
+// of 64; after each tile one thread per id merges the 64 new affinities into its sorted list (falling
+// affinity, ties by rising slot: a later slot never displaces an equal earlier one).
+__global__ __launch_bounds__(256) void topk_kernel(const float *E, int d, const double *inv_norm, const int32_t *pruned_ids,
+                                                   int n_pruned, const int32_t *kept_ids, int n, int k, double inv_tau,
+                                                   double *nbr_a, int32_t *nbr_s, unsigned long long *zfix)
+{
+    __shared__ float ea[kTile][kDepth + 1], eb[kTile][kDepth + 1];
+    __shared__ double om[kTile][kTile + 1];
+    extern __shared__ unsigned char dyn[];
+    double *best_v = (double *)dyn;                        // [64][k]
+    int32_t *best_s = (int32_t *)(best_v + kTile * k);     // [64][k]
+    const int r0 = blockIdx.x * kTile;
+    int filled = 0;
+    for (int c0 = 0; c0 < n; c0 += kTile) {
+        affinity_tile(E, d, inv_norm, pruned_ids, r0, n_pruned, kept_ids, c0, n, ea, eb, om);
+        if (threadIdx.x < kTile && r0 + threadIdx.x < n_pruned) {
+            double *bv = best_v + threadIdx.x * k;
+            int32_t *bs = best_s + threadIdx.x * k;
+            const int lim = min(kTile, n - c0);
+            for (int c = 0; c < lim; ++c) {
+                const double v = om[threadIdx.x][c];
+                if (filled < k || v > bv[k - 1]) {
+                    int pos = filled < k ? filled : k - 1;
+                    while (pos > 0 && bv[pos - 1] < v) {
+                        bv[pos] = bv[pos - 1];
+                        bs[pos] = bs[pos - 1];
+                        --pos;
+                    }
+                    bv[pos] = v;
+                    bs[pos] = c0 + c;
+                    if (filled < k) ++filled;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < kTile * k; t += blockDim.x) {
+        const int r = t / k, e = t % k;
+        if (r0 + r >= n_pruned) continue;
+        const double a = exp((best_v[r * k + e] - 1.0) * inv_tau);
+        const int s = best_s[r * k + e];
+        nbr_a[(int64_t)(r0 + r) * k + e] = a;
+        nbr_s[(int64_t)(r0 + r) * k + e] = s;
+        atomicAdd(&zfix[s], (unsigned long long)(a * kFixScale + 0.5));
+    }
+}
+
+// Normalise over the retained entries and lay the kernel out per target id: row j of the tables holds
+// kk (slot, weight) pairs; a kept id holds itself with its diagonal weight, the rest is padding.
+__global__ void sparse_finish_kernel(const int32_t *slot_of, int N, int k, int kk, const double *nbr_a, const int32_t *nbr_s,
+                                     const unsigned long long *zfix, int32_t *ell_idx, float *ell_w)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)N * kk) return;
+    const int j = (int)(t / kk), e = (int)(t % kk);
+    const int s = slot_of[j];
+    int idx = 0;
+    float w = 0.f;
+    if (s >= 0) {
+        if (e == 0) {
+            idx = s;
+            w = (float)(1.0 / (1.0 + (double)zfix[s] / kFixScale));
+        }
+    } else if (e < k) {
+        const int64_t u = -s - 1;
+        idx = nbr_s[u * k + e];
+        w = (float)(nbr_a[u * k + e] / (1.0 + (double)zfix[idx] / kFixScale));
+    }
+    ell_idx[t] = idx;
+    ell_w[t] = w;
+}
+
+__global__ void sparse_import_kernel(const int32_t *slot_of, int N, int k, int kk, const int32_t *sp_idx, const float *sp_w,
+                                     const float *self_w, int32_t *ell_idx, float *ell_w)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)N * kk) return;
+    const int j = (int)(t / kk), e = (int)(t % kk);
+    const int s = slot_of[j];
+    int idx = 0;
+    float w = 0.f;
+    if (s >= 0) {
+        if (e == 0) {
+            idx = s;
+            w = self_w[s];
+        }
+    } else if (e < k) {
+        const int64_t u = -s - 1;
+        idx = sp_idx[u * k + e];
+        w = sp_w[u * k + e];
+    }
+    ell_idx[t] = idx;
+    ell_w[t] = w;
+}
+
+__global__ void sparse_export_kernel(const int32_t *slot_of, int N, int k, int kk, const int32_t *ell_idx, const float *ell_w,
+                                     int32_t *sp_idx, float *sp_w, float *self_w)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)N * kk) return;
+    const int j = (int)(t / kk), e = (int)(t % kk);
+    const int s = slot_of[j];
+    if (s >= 0) {
+        if (e == 0) self_w[s] = ell_w[t];
+    } else if (e < k) {
+        const int64_t u = -s - 1;
+        sp_idx[u * k + e] = ell_idx[t];
+        sp_w[u * k + e] = ell_w[t];
+    }
+}
+
+// Dense Eq. 2, first pass: one workgroup owns 64 kept slots and sweeps the target ids in tiles of 64,
+// storing exp((Omega - 1) / tau) and summing each row in a fixed order.
+__global__ __launch_bounds__(256) void dense_rows_kernel(const float *E, int d, const double *inv_norm, const int32_t *kept_ids,
+                                                         int n, int N, double inv_tau, float *M, int64_t ldm, double *row_sum)
+{
+    __shared__ float ea[kTile][kDepth + 1], eb[kTile][kDepth + 1];
+    __shared__ double om[kTile][kTile + 1];
+    __shared__ double part[kTile][4];
+    const int r0 = blockIdx.x * kTile;
+    const int r = threadIdx.x / 4, cq = threadIdx.x % 4;   // 4 threads per row, 16 columns each
+    double sum = 0.0;
+    for (int c0 = 0; c0 < N; c0 += kTile) {
+        affinity_tile(E, d, inv_norm, kept_ids, r0, n, nullptr, c0, N, ea, eb, om);
+        if (r0 + r < n) {
+            for (int c = cq * 16; c < cq * 16 + 16; ++c) {
+                if (c0 + c >= N) break;
+                const double a = exp((om[r][c] - 1.0) * inv_tau);
+                sum += a;
+                M[(int64_t)(r0 + r) * ldm + c0 + c] = (float)a;
+            }
+        }
+    }
+    part[r][cq] = sum;
+    __syncthreads();
+    if (cq == 0 && r0 + r < n) row_sum[r0 + r] = (part[r][0] + part[r][1]) + (part[r][2] + part[r][3]);
+}
+
+__global__ void dense_scale_kernel(float *M, int64_t ldm, int n, int N, const double *row_sum)
+{
+    const int s = blockIdx.y;
+    const double inv = 1.0 / row_sum[s];
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += (int64_t)gridDim.x * blockDim.x)
+        M[(int64_t)s * ldm + j] = (float)((double)M[(int64_t)s * ldm + j] * inv);
+}
+
+// Row sums and sign check of a supplied dense kernel.
+__global__ void check_dense_kernel(const float *M, int64_t ldm, int N, int32_t *flag)
+{
+    const int s = blockIdx.x;
+    double sum = 0.0;
+    bool bad = false;
+    for (int j = threadIdx.x; j < N; j += blockDim.x) {
+        const float v = M[(int64_t)s * ldm + j];
+        bad |= !(v >= 0.f);
+        sum += (double)v;
+    }
+    sum = wave_sum(sum);
+    __shared__ double sh[4];
+    __shared__ int shb;
+    if (threadIdx.x == 0) shb = 0;
+    __syncthreads();
+    if (lane_id() == 0) sh[threadIdx.x / kWave] = sum;
+    if (bad) atomicOr(&shb, 1);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const double t = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+        if (shb || !(fabs(t - 1.0) <= 1e-3)) atomicOr(flag, 1);
+    }
+}
+
+// Row sums of a sparse kernel: entry (idx, w) of any id adds w to row idx.
+__global__ void check_sparse_accum_kernel(const int32_t *ell_idx, const float *ell_w, int64_t count, int n,
+                                          unsigned long long *zfix, int32_t *flag)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= count) return;
+    const float w = ell_w[t];
+    const int s = ell_idx[t];
+    if (!(w >= 0.f) || s < 0 || s >= n) {
+        atomicOr(flag, 1);
+        return;
+    }
+    if (w > 0.f) atomicAdd(&zfix[s], (unsigned long long)((double)w * kFixScale + 0.5));
+}
+
+__global__ void check_sparse_rows_kernel(const unsigned long long *zfix, int n, int32_t *flag)
+{
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s < n && !(fabs((double)zfix[s] / kFixScale - 1.0) <= 1e-3)) atomicOr(flag, 1);
+}
+
+}  // namespace
+
+size_t build_workspace_bytes(const rdk_kernel_desc_t &d)
+{
+    const size_t np = (size_t)(d.N - d.n), k = (size_t)(d.k > 0 ? d.k : 0);
+    return align_up((size_t)d.N * 8, 256) + align_up((size_t)d.n * 8, 256) + align_up((np + 1) * 4, 256) +
+           align_up((np * k + 1) * 8, 256) + align_up((np * k + 1) * 4, 256) + align_up((size_t)d.n * 8, 256) + 256;
+}
+
+rdk_status_t launch_slot_of(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *slot_of, hipStream_t st)
+{
+    hipLaunchKernelGGL(slot_of_kernel, dim3((N + 255) / 256), dim3(256), 0, st, kept_ids, n, N, slot_of);
+    RDK_LAUNCH_CHECK("slot_of_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_check_kept(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *flag, hipStream_t st)
+{
+    hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, st, flag);
+    hipLaunchKernelGGL(check_kept_kernel, dim3((n + 255) / 256), dim3(256), 0, st, kept_ids, n, N, flag);
+    RDK_LAUNCH_CHECK("check_kept_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *slot_of, int32_t *ell_idx, float *ell_w,
+                                 int32_t kk, void *ws, hipStream_t st)
+{
+    BuildWs w = carve(d, ws);
+    const int np = d.N - d.n;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((d.n + 255) / 256), dim3(256), 0, st, w.zfix, (int64_t)d.n);
+    RDK_LAUNCH_CHECK("fill_zero_kernel");
+    if (d.k > 0 && np > 0) {
+        hipLaunchKernelGGL(inv_norm_kernel, dim3((d.N + 3) / 4), dim3(256), 0, st, d.embeddings, d.N, d.d, w.inv_norm);
+        RDK_LAUNCH_CHECK("inv_norm_kernel");
+        hipLaunchKernelGGL(pruned_ids_kernel, dim3((d.N + 255) / 256), dim3(256), 0, st, slot_of, d.N, w.pruned_ids);
+        RDK_LAUNCH_CHECK("pruned_ids_kernel");
+        const size_t dyn = (size_t)kTile * d.k * (sizeof(double) + sizeof(int32_t));
+        RDK_HIP(hipFuncSetAttribute((const void *)topk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn));
+        hipLaunchKernelGGL(topk_kernel, dim3((np + kTile - 1) / kTile), dim3(256), dyn, st, d.embeddings, d.d, w.inv_norm,
+                           w.pruned_ids, np, d.kept_ids, d.n, d.k, 1.0 / (double)d.tau, w.nbr_a, w.nbr_s, w.zfix);
+        RDK_LAUNCH_CHECK("topk_kernel");
+    }
+    const int64_t count = (int64_t)d.N * kk;
+    hipLaunchKernelGGL(sparse_finish_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, slot_of, d.N, d.k, kk,
+                       w.nbr_a, w.nbr_s, w.zfix, ell_idx, ell_w);
+    RDK_LAUNCH_CHECK("sparse_finish_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_import_sparse(const rdk_kernel_desc_t &d, const int32_t *slot_of, int32_t *ell_idx, float *ell_w,
+                                  int32_t kk, hipStream_t st)
+{
+    const int64_t count = (int64_t)d.N * kk;
+    hipLaunchKernelGGL(sparse_import_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, slot_of, d.N, d.k, kk,
+                       d.sparse_idx, d.sparse_w, d.self_w, ell_idx, ell_w);
+    RDK_LAUNCH_CHECK("sparse_import_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_export_sparse(const KernelHandle &h, int32_t *idx, float *w, float *self_w, hipStream_t st)
+{
+    const int64_t count = (int64_t)h.N * h.kk;
+    hipLaunchKernelGGL(sparse_export_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, h.slot_of, h.N, h.k,
+                       h.kk, h.ell_idx, h.ell_w, idx, w, self_w);
+    RDK_LAUNCH_CHECK("sparse_export_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_build_dense(const rdk_kernel_desc_t &d, float *M, int64_t ldm, void *ws, hipStream_t st)
+{
+    BuildWs w = carve(d, ws);
+    hipLaunchKernelGGL(inv_norm_kernel, dim3((d.N + 3) / 4), dim3(256), 0, st, d.embeddings, d.N, d.d, w.inv_norm);
+    RDK_LAUNCH_CHECK("inv_norm_kernel");
+    hipLaunchKernelGGL(dense_rows_kernel, dim3((d.n + kTile - 1) / kTile), dim3(256), 0, st, d.embeddings, d.d, w.inv_norm,
+                       d.kept_ids, d.n, d.N, 1.0 / (double)d.tau, M, ldm, w.row_sum);
+    RDK_LAUNCH_CHECK("dense_rows_kernel");
+    hipLaunchKernelGGL(dense_scale_kernel, dim3(64, d.n), dim3(256), 0, st, M, ldm, d.n, d.N, w.row_sum);
+    RDK_LAUNCH_CHECK("dense_scale_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_check_stochastic_dense(const float *M, int64_t ldm, int32_t n, int32_t N, int32_t *flag, hipStream_t st)
+{
+    hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, st, flag);
+    hipLaunchKernelGGL(check_dense_kernel, dim3(n), dim3(256), 0, st, M, ldm, N, flag);
+    RDK_LAUNCH_CHECK("check_dense_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_check_stochastic_sparse(const KernelHandle &h, void *ws, int32_t *flag, hipStream_t st)
+{
+    unsigned long long *zfix = (unsigned long long *)ws;
+    hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, st, flag);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((h.n + 255) / 256), dim3(256), 0, st, zfix, (int64_t)h.n);
+    const int64_t count = (int64_t)h.N * h.kk;
+    hipLaunchKernelGGL(check_sparse_accum_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, h.ell_idx, h.ell_w,
+                       count, h.n, zfix, flag);
+    hipLaunchKernelGGL(check_sparse_rows_kernel, dim3((h.n + 255) / 256), dim3(256), 0, st, zfix, h.n, flag);
+    RDK_LAUNCH_CHECK("check_sparse_rows_kernel");
+    return RDK_OK;
+}
+
+}  // namespace rdk

@@ -1,0 +1,95 @@
+// Internal declarations shared by the translation units of the RDK HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rdk.h"
+
+namespace rdk {
+
+constexpr int kWave = 64;        // CDNA wavefront width
+constexpr int kChunk = 1024;     // ids summed by one wavefront step: 64 lanes x 4 x float4
+constexpr int kMaxSplits = 64;   // upper bound on workgroups sharing one row
+
+// Host-side description of a built kernel; every pointer points into the caller's storage blob.
+struct KernelHandle {
+    int32_t N, n, k;
+    rdk_kernel_format_t format;
+    const int32_t *kept_ids;  // [n]
+    const int32_t *slot_of;   // [N]  >= 0: kept slot;  < 0: -(pruned slot + 1)
+    // sparse: one row of k (slot, weight) pairs per TARGET id (kept ids: themselves, then zero weights)
+    const int32_t *ell_idx;   // [N, kk]
+    const float *ell_w;       // [N, kk]
+    int32_t kk;               // row length of the two tables: max(k, 1) rounded up to a multiple of 4
+    // dense fp32
+    const float *dense;       // [n, ldm]
+    int64_t ldm;
+    // dense bf16, packed for MFMA operand loads, plus the fp32 row sums of the rounded rows
+    const uint16_t *packed;
+    const float *row_sum;     // [n]
+    int32_t n_pad, N_pad;     // packed extents
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Records a HIP failure for rdk_last_hip_error() and maps it to RDK_ERR_HIP.
+rdk_status_t hip_fail(hipError_t e, const char *what);
+
+#define RDK_HIP(call)                                                   \
+    do {                                                                \
+        hipError_t e_ = (call);                                         \
+        if (e_ != hipSuccess) return ::rdk::hip_fail(e_, #call);        \
+    } while (0)
+
+#define RDK_LAUNCH_CHECK(name)                                          \
+    do {                                                                \
+        hipError_t e_ = hipGetLastError();                              \
+        if (e_ != hipSuccess) return ::rdk::hip_fail(e_, name);         \
+    } while (0)
+
+// ---- launchers implemented in the kernel translation units (all enqueue on `st`, none synchronises)
+
+struct RowInput {            // a [B, len] input of some kind
+    const void *ptr;
+    rdk_input_kind_t kind;
+    int64_t ld;
+};
+
+// rdk_build.hip
+size_t build_workspace_bytes(const rdk_kernel_desc_t &d);
+rdk_status_t launch_slot_of(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *slot_of, hipStream_t st);
+rdk_status_t launch_check_kept(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *flag, hipStream_t st);
+rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *slot_of, int32_t *ell_idx,
+                                 float *ell_w, int32_t kk, void *ws, hipStream_t st);
+rdk_status_t launch_import_sparse(const rdk_kernel_desc_t &d, const int32_t *slot_of, int32_t *ell_idx,
+                                  float *ell_w, int32_t kk, hipStream_t st);
+rdk_status_t launch_export_sparse(const KernelHandle &h, int32_t *idx, float *w, float *self_w, hipStream_t st);
+rdk_status_t launch_build_dense(const rdk_kernel_desc_t &d, float *M, int64_t ldm, void *ws, hipStream_t st);
+rdk_status_t launch_check_stochastic_dense(const float *M, int64_t ldm, int32_t n, int32_t N, int32_t *flag,
+                                           hipStream_t st);
+rdk_status_t launch_check_stochastic_sparse(const KernelHandle &h, void *ws, int32_t *flag, hipStream_t st);
+
+// rdk_linear.hip
+size_t linear_workspace_bytes(const KernelHandle &h, int32_t B);
+rdk_status_t launch_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B, float *out, int64_t ldo,
+                           void *ws, hipStream_t st);
+rdk_status_t launch_sparse(const KernelHandle &h, RowInput q, int32_t B, float *out, int64_t ldo, void *ws,
+                           hipStream_t st);
+
+// rdk_exact.hip
+size_t exact_workspace_bytes(const KernelHandle &h, int32_t B);
+size_t packed_bf16_bytes(int32_t n, int32_t N, int32_t *n_pad, int32_t *N_pad);
+rdk_status_t launch_pack_bf16(const float *M, int64_t ldm, int32_t n, int32_t N, uint16_t *packed, float *row_sum,
+                              hipStream_t st);
+rdk_status_t launch_unpack_bf16(const KernelHandle &h, float *M, int64_t ldm, hipStream_t st);
+rdk_status_t launch_exact(const KernelHandle &h, RowInput q, int32_t B, float *out, int64_t ldo, void *ws,
+                          hipStream_t st);
+
+// rdk_verify.hip
+size_t verify_workspace_bytes(const rdk_verify_desc_t &d);
+rdk_status_t launch_verify(const rdk_verify_desc_t &d, RowInput p, const float *q_prime, int64_t ldq,
+                           int32_t *draft_ids, uint8_t *accept, float *alpha, float *resid_mass,
+                           int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens, void *ws, hipStream_t st);
+rdk_status_t launch_philox_words(uint64_t seed, uint64_t offset, int32_t count, uint32_t *words, hipStream_t st);
+
+}  // namespace rdk

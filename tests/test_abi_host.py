@@ -1,0 +1,95 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares, and its
+argument validation and size queries behave (no kernel is launched, so no GPU is needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from conftest import ROOT
+
+
+@pytest.fixture(scope="module")
+def rdk():
+    from paper_2506_03206_amd import rdk as mod
+    if not os.path.exists(mod.LIB_PATH):
+        from paper_2506_03206_amd import build
+        build.build()
+    return mod
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "rdk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rdk_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(rdk):
+    names = declared_symbols()
+    assert "rdk_build_kernel" in names and "rdk_redistribute_exact" in names
+    assert "rdk_redistribute_linear" in names and "rdk_verify_sample" in names
+    L = rdk.lib()
+    for name in names:
+        assert hasattr(L, name), name
+    assert sorted(rdk.EXPORTS) == names
+
+
+def test_status_strings(rdk):
+    L = rdk.lib()
+    seen = {L.rdk_status_string(i).decode() for i in range(10)}
+    assert len(seen) == 10 and "ok" in seen
+    assert L.rdk_status_string(99).decode() == "unknown status"
+    assert L.rdk_last_hip_error().decode() == ""
+
+
+def _desc(rdk, **kw):
+    d = rdk.KernelDesc()
+    d.N, d.n, d.d, d.k, d.tau, d.format, d.validate = 1024, 256, 64, 8, 0.1, rdk.SPARSE_TOPK, 0
+    d.kept_ids, d.embeddings = 0x1000, 0x2000          # never dereferenced by the size query
+    for key, val in kw.items():
+        setattr(d, key, val)
+    return d
+
+
+def test_storage_query_and_validation(rdk):
+    L = rdk.lib()
+    sb, wb = ctypes.c_size_t(), ctypes.c_size_t()
+    q = lambda d: L.rdk_kernel_storage_bytes(ctypes.byref(d), ctypes.byref(sb), ctypes.byref(wb))
+    assert q(_desc(rdk)) == 0
+    # kept ids + slot table + two [N, 8] tables
+    assert sb.value == 1024 + 4096 + 2 * 1024 * 8 * 4
+    assert q(_desc(rdk, format=rdk.DENSE_F32)) == 0 and sb.value == 1024 + 4096 + 256 * 1024 * 4
+    assert q(_desc(rdk, format=rdk.DENSE_BF16)) == 0 and sb.value == 1024 + 4096 + 256 * 1024 * 2 + 1024
+    assert wb.value > 256 * 1024 * 4                       # the fp32 matrix that gets packed
+    assert q(_desc(rdk, format=rdk.IDENTITY, embeddings=None)) == 0 and sb.value == 1024 + 4096
+    assert q(_desc(rdk, n=0)) == 2 and q(_desc(rdk, n=2000)) == 2 and q(_desc(rdk, k=65)) == 2
+    assert q(_desc(rdk, kept_ids=None)) == 1 and q(_desc(rdk, embeddings=None)) == 1
+    assert q(_desc(rdk, tau=0.0)) == 2 and q(_desc(rdk, format=7)) == 3
+    assert q(_desc(rdk, kept_ids=0x1004)) == 9
+    assert L.rdk_kernel_storage_bytes(None, ctypes.byref(sb), ctypes.byref(wb)) == 1
+    # a supplied sparse kernel needs all three tables
+    assert q(_desc(rdk, embeddings=None, self_w=0x3000)) == 1
+    assert q(_desc(rdk, embeddings=None, self_w=0x3000, sparse_idx=0x4000, sparse_w=0x5000)) == 0
+
+
+def test_verify_argument_checks(rdk):
+    L = rdk.lib()
+    need = ctypes.c_size_t()
+    d = rdk.VerifyDesc(B=256, N=128256, gamma=8, sample_draft=1, seed=1, offset=0)
+    assert L.rdk_verify_workspace_bytes(ctypes.byref(d), ctypes.byref(need)) == 0
+    nchunks = (128256 + 1023) // 1024
+    assert need.value >= 3 * 256 * nchunks * 4
+    bad = rdk.VerifyDesc(B=10, N=64, gamma=4, sample_draft=1, seed=1, offset=0)
+    assert L.rdk_verify_workspace_bytes(ctypes.byref(bad), ctypes.byref(need)) == 2        # B % gamma != 0
+    vp = ctypes.c_void_p
+    args = lambda p=0x1000, q=0x2000, draft=0x3000, acc=0x4000, rid=0x5000, ws=0x6000, wsb=1 << 30, ldp=128256, kind=0: (
+        ctypes.byref(d), vp(p), kind, ldp, vp(q), 128256, vp(draft), vp(acc), None, None, vp(rid), None, None, vp(ws), wsb, None)
+    assert L.rdk_verify_sample(*args(p=None)) == 1
+    assert L.rdk_verify_sample(*args(acc=None)) == 1
+    assert L.rdk_verify_sample(*args(ldp=100)) == 2
+    assert L.rdk_verify_sample(*args(kind=5)) == 3
+    assert L.rdk_verify_sample(*args(p=0x1004)) == 9
+    assert L.rdk_verify_sample(*args(wsb=16)) == 6
+    assert L.rdk_verify_sample(*args(q=None)) == 7                                       # bonus draw cannot be scanned
+    assert L.rdk_philox_words(1, 0, 0, vp(0x1000), None) == 2
+    assert L.rdk_redistribute_exact(None, vp(0x1000), 0, 10, 1, vp(0x2000), 10, vp(0x3000), 10, None) == 1

@@ -1,0 +1,298 @@
+"""GPU parity: every entry point of the C-ABI library against the CPU oracle, element by element, on
+seeded inputs small enough for the oracle yet spanning several tiles and a ragged tail."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_03206_amd import synth
+from parity_util import ATOL, RTOL, RTOL_BF16, assert_close, check_sampled_ids
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rdk():
+    from paper_2506_03206_amd import rdk as mod
+    mod.lib()
+    assert torch.cuda.is_available()
+    return mod
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def bf16_tensor(x):
+    """fp32 array holding exact bf16 values -> torch bf16 tensor on the device."""
+    return torch.from_numpy(np.ascontiguousarray(x)).to(torch.bfloat16).cuda()
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    w = synth.WORKLOADS["tiny"]
+    data = synth.make(w)
+    data["w"] = w
+    data["sparse"] = oracle.build_sparse(data["E"], data["kept_ids"], w.tau, w.k)
+    data["dense"] = oracle.build_dense(data["E"], data["kept_ids"], w.tau)
+    return data
+
+
+# ragged sizes: N not a multiple of 4 (scalar paths), of 1024 (partial block), n odd, B not a multiple of 16
+RAGGED = synth.scaled(synth.WORKLOADS["tiny"], name="ragged", N=3001, n=517, seqs=7, gamma=3, k=5, d=24, seed=3)
+
+
+@pytest.fixture(scope="module")
+def ragged():
+    data = synth.make(RAGGED)
+    data["w"] = RAGGED
+    data["sparse"] = oracle.build_sparse(data["E"], data["kept_ids"], RAGGED.tau, RAGGED.k)
+    data["dense"] = oracle.build_dense(data["E"], data["kept_ids"], RAGGED.tau)
+    return data
+
+
+# --------------------------------------------------------------------------------------------- Philox
+def test_philox_stream_matches_oracle(rdk):
+    seed, offset, count = 0xDEADBEEFCAFEF00D, (1 << 32) - 300, 1000
+    words = rdk.rdk_philox_words(seed, offset, count).cpu().numpy().view(np.uint32)
+    for i in list(range(0, count, 37)) + [299, 300, 301, count - 1]:
+        idx = offset + i
+        ref = oracle.philox4x32_10([idx & 0xFFFFFFFF, idx >> 32, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
+        assert words[i].tolist() == ref.tolist()
+
+
+# --------------------------------------------------------------------------------------------- kernel construction
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+def test_build_sparse_matches_oracle(rdk, tiny, ragged, case):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.SPARSE_TOPK, embeddings=dev(data["E"]), tau=w.tau, k=w.k)
+    idx, wt, sw = [t.cpu().numpy() for t in rdk.rdk_kernel_get_sparse(kern)]
+    o_idx, o_w, o_sw = data["sparse"]
+    assert np.array_equal(idx, o_idx)            # neighbour sets and their order (fp64 affinities on both sides)
+    assert_close(wt, o_w, what="neighbour weights")
+    assert_close(sw, o_sw, what="diagonal weights")
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+def test_build_dense_matches_oracle(rdk, tiny, ragged, case):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.DENSE_F32, embeddings=dev(data["E"]), tau=w.tau)
+    M = rdk.rdk_kernel_get_dense(kern).cpu().numpy()
+    assert_close(M, data["dense"], what="dense M")
+    assert np.abs(M.astype(np.float64).sum(1) - 1).max() < 1e-5
+
+
+def test_build_validation(rdk, tiny):
+    w = tiny["w"]
+    bad = tiny["kept_ids"].copy()
+    bad[[3, 4]] = bad[[4, 3]]
+    with pytest.raises(rdk.RdkError) as e:
+        rdk.rdk_build_kernel(w.N, dev(bad), rdk.IDENTITY)
+    assert e.value.status == 4
+    M = tiny["dense"].astype(np.float32).copy()
+    M[5] *= 1.01
+    with pytest.raises(rdk.RdkError) as e:
+        rdk.rdk_build_kernel(w.N, dev(tiny["kept_ids"]), rdk.DENSE_F32, dense_M=dev(M))
+    assert e.value.status == 5
+    idx, wt, sw = tiny["sparse"]
+    with pytest.raises(rdk.RdkError) as e:
+        rdk.rdk_build_kernel(w.N, dev(tiny["kept_ids"]), rdk.SPARSE_TOPK, k=w.k,
+                             sparse=(dev(idx), dev(wt * 1.5, torch.float32), dev(sw, torch.float32)))
+    assert e.value.status == 5
+
+
+# --------------------------------------------------------------------------------------------- redistribution
+def oracle_rows(data, mode, q_kind="prob", p_kind="prob", kernel=None):
+    w = data["w"]
+    q = data["q_hat"] if q_kind == "prob" else oracle.probs_from(data["z_q"], "logit")
+    p = data["p"] if p_kind == "prob" else oracle.probs_from(data["z_p"], "logit")
+    return oracle.redistribute_batch(mode, q, data["kept_ids"], w.N, p=p, M=kernel if mode == "exact" else None,
+                                     sparse=kernel if mode == "sparse" else None)
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+@pytest.mark.parametrize("q_kind", ["prob", "logit"])
+def test_sparse_redistribution(rdk, tiny, ragged, case, q_kind):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    idx, wt, sw = data["sparse"]
+    wt32, sw32 = wt.astype(np.float32), sw.astype(np.float32)     # both sides use the same stored kernel
+    kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.SPARSE_TOPK, k=w.k,
+                                sparse=(dev(idx), dev(wt32), dev(sw32)))
+    q = dev(data["q_hat"]) if q_kind == "prob" else dev(data["z_q"])
+    out = rdk.rdk_redistribute_linear(kern, rdk.LINEAR_SPARSE, q, q_kind).cpu().numpy()
+    ref = oracle_rows(data, "sparse", q_kind, kernel=(idx, wt32, sw32))
+    assert_close(out, ref, what="sparse q'")
+    assert np.abs(out.astype(np.float64).sum(1) - 1).max() < 2e-5
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+@pytest.mark.parametrize("kinds", [("prob", "prob"), ("logit", "logit"), ("prob", "logit")])
+def test_taylor_redistribution(rdk, tiny, ragged, case, kinds):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    p_kind, q_kind = kinds
+    kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.IDENTITY)
+    q = dev(data["q_hat"]) if q_kind == "prob" else dev(data["z_q"])
+    p = dev(data["p"]) if p_kind == "prob" else dev(data["z_p"])
+    out = rdk.rdk_redistribute_linear(kern, rdk.LINEAR_TAYLOR, q, q_kind, p=p, p_kind=p_kind).cpu().numpy()
+    ref = oracle_rows(data, "taylor", q_kind, p_kind)
+    assert_close(out, ref, what="Eq. 3")
+
+
+def test_taylor_bf16_logits(rdk, tiny):
+    w = tiny["w"]
+    zp, zq = synth.bf16_round(tiny["z_p"]), synth.bf16_round(tiny["z_q"])
+    kern = rdk.rdk_build_kernel(w.N, dev(tiny["kept_ids"]), rdk.IDENTITY)
+    out = rdk.rdk_redistribute_linear(kern, rdk.LINEAR_TAYLOR, bf16_tensor(zq), "logit", p=bf16_tensor(zp),
+                                      p_kind="logit").cpu().numpy()
+    ref = oracle.redistribute_batch("taylor", oracle.probs_from(zq, "logit"), tiny["kept_ids"], w.N,
+                                    p=oracle.probs_from(zp, "logit"))
+    assert_close(out, ref, what="Eq. 3, bf16 logits")
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+def test_identity_kernel_is_tli(rdk, tiny, ragged, case):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.IDENTITY)
+    ref = oracle_rows(data, "tli")
+    for fn in (lambda: rdk.rdk_redistribute_exact(kern, dev(data["q_hat"])),
+               lambda: rdk.rdk_redistribute_linear(kern, rdk.LINEAR_SPARSE, dev(data["q_hat"]))):
+        assert_close(fn().cpu().numpy(), ref, what="identity kernel")
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+@pytest.mark.parametrize("q_kind", ["prob", "logit"])
+def test_exact_fp32(rdk, tiny, ragged, case, q_kind):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    M32 = data["dense"].astype(np.float32)
+    kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.DENSE_F32, dense_M=dev(M32))
+    q = dev(data["q_hat"]) if q_kind == "prob" else dev(data["z_q"])
+    out = rdk.rdk_redistribute_exact(kern, q, q_kind).cpu().numpy()
+    ref = oracle_rows(data, "exact", q_kind, kernel=M32)
+    assert_close(out, ref, what="exact fp32")
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+def test_exact_bf16(rdk, tiny, ragged, case):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    M32 = data["dense"].astype(np.float32)
+    kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.DENSE_BF16, dense_M=dev(M32))
+    assert np.array_equal(rdk.rdk_kernel_get_dense(kern).cpu().numpy(), synth.bf16_round(M32))
+    out = rdk.rdk_redistribute_exact(kern, dev(data["q_hat"])).cpu().numpy()
+    # tight: fp64 on the same bf16-rounded operands, rows rescaled to unit mass
+    Mb = synth.bf16_round(M32).astype(np.float64)
+    ref = np.empty((w.B, w.N))
+    for b in range(w.B):
+        qb = synth.bf16_round(oracle.tli(data["q_hat"][b]).astype(np.float32))
+        r = oracle.redistribute_dense(qb, Mb)
+        ref[b] = r / r.sum()
+    assert_close(out, ref, rtol=2e-5, atol=ATOL, what="exact bf16 vs rounded operands")
+    # loose: against the unrounded fp32 kernel
+    assert_close(out, oracle_rows(data, "exact", kernel=M32), rtol=RTOL_BF16 * 4, atol=1e-6, what="exact bf16 vs fp32 operands")
+    assert np.abs(out.astype(np.float64).sum(1) - 1).max() < 2e-5
+
+
+# --------------------------------------------------------------------------------------------- verification
+def run_verify_case(rdk, p_in, p_kind, p64, qp32, gamma, seed, offset, draft_ids=None):
+    B, N = p64.shape
+    o = rdk.rdk_verify_sample(p_in, None if qp32 is None else dev(qp32), seed, offset, gamma, p_kind,
+                              draft_ids=None if draft_ids is None else dev(draft_ids))
+    torch.cuda.synchronize()
+    ref = oracle.verify_batch(p64, None if qp32 is None else qp32.astype(np.float64), seed, offset,
+                              sample_draft=draft_ids is None, draft_ids=draft_ids, gamma=gamma)
+    us = np.array([oracle.uniforms(seed, offset + b) for b in range(B)])
+    g_resid = o.resid_ids.cpu().numpy()
+    if qp32 is None:
+        check_sampled_ids(p64, us[:, 3], g_resid, ref["resid_ids"], what="bonus")
+        assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], what="sum p")
+        assert not o.accept.any() and not o.alpha.any()
+        return o, ref
+    q64 = qp32.astype(np.float64)
+    assert_close(o.alpha.cpu().numpy(), ref["alpha"], what="alpha")
+    assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], rtol=RTOL, atol=2e-7, what="residual mass")
+    g_draft = o.draft_ids.cpu().numpy()
+    n_d = check_sampled_ids(q64, us[:, 0], g_draft, ref["draft_ids"], what="draft")
+    n_r = check_sampled_ids(np.maximum(p64 - q64, 0), us[:, 2], g_resid, ref["resid_ids"], what="residual")
+    assert n_d >= 0.95 * B and n_r >= 0.95 * B
+    # acceptance is decided exactly (fp64 product) on both sides wherever the draft token agrees
+    same = g_draft == ref["draft_ids"]
+    g_acc = o.accept.cpu().numpy()
+    if p_kind == "prob":
+        assert np.array_equal(g_acc[same], ref["accept"][same])
+    else:   # p itself is computed in fp32 on the device: allow a flip only at a near-tie
+        for b in np.nonzero(same & (g_acc != ref["accept"]))[0]:
+            d_ = g_draft[b]
+            assert abs(us[b, 1] * q64[b, d_] - p64[b, d_]) <= 1e-5 * p64[b, d_]
+    if gamma:
+        n_acc, toks = oracle.sequence_scan(g_acc, g_draft, g_resid, gamma)     # scan of the device's own flags
+        assert np.array_equal(o.n_accepted.cpu().numpy(), n_acc)
+        assert np.array_equal(o.out_tokens.cpu().numpy(), toks)
+        if same.all() and np.array_equal(g_acc, ref["accept"]) and np.array_equal(g_resid, ref["resid_ids"]):
+            assert np.array_equal(o.out_tokens.cpu().numpy(), ref["out_tokens"])
+    return o, ref
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+def test_verify_prob_inputs(rdk, tiny, ragged, case):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    idx, wt, sw = data["sparse"]
+    qp = oracle_rows(data, "sparse", kernel=(idx, wt, sw)).astype(np.float32)
+    p64 = data["p"].astype(np.float64)
+    run_verify_case(rdk, dev(data["p"]), "prob", p64, qp, w.gamma, seed=11, offset=5)
+    run_verify_case(rdk, dev(data["p"]), "prob", p64, qp, 0, seed=12, offset=(1 << 40))
+    # caller-supplied drafts, including an out-of-range one
+    drafts = np.arange(w.B, dtype=np.int32) * 7 % w.N
+    drafts[1] = -1
+    run_verify_case(rdk, dev(data["p"]), "prob", p64, qp, w.gamma, seed=13, offset=0, draft_ids=drafts)
+    # bonus draw
+    run_verify_case(rdk, dev(data["p"]), "prob", p64, None, 0, seed=14, offset=9)
+
+
+def test_verify_logit_inputs(rdk, tiny):
+    w = tiny["w"]
+    qp = oracle_rows(tiny, "taylor").astype(np.float32)
+    p64 = oracle.probs_from(tiny["z_p"], "logit")
+    run_verify_case(rdk, dev(tiny["z_p"]), "logit", p64, qp, w.gamma, seed=21, offset=0)
+    zb = synth.bf16_round(tiny["z_p"])
+    run_verify_case(rdk, bf16_tensor(zb), "logit", oracle.probs_from(zb, "logit"), qp, w.gamma, seed=22, offset=0)
+
+
+def test_verify_degenerate_rows(rdk):
+    """alpha = 1 (no residual), point masses, zero-probability drafts, long sequences (gamma > 16)."""
+    N, B = 2500, 40
+    rng = np.random.default_rng(5)
+    p = rng.gamma(0.3, size=(B, N)).astype(np.float32)
+    p[:, rng.choice(N, 800, replace=False)] = 0
+    p = (p / p.sum(1, keepdims=True)).astype(np.float32)
+    q = p.copy()                       # rows 0..9: q' == p -> alpha = 1, residual mass 0, resid id -1
+    q[10:20] = 0
+    q[10:20, 1234] = 1.0               # point-mass drafter
+    q[20:] = np.roll(p[20:], 17, axis=1)
+    o, ref = run_verify_case(rdk, dev(p), "prob", p.astype(np.float64), q, 20, seed=31, offset=0)
+    assert (o.resid_ids.cpu().numpy()[:10] == -1).all() and (ref["resid_ids"][:10] == -1).all()
+    assert o.accept.cpu().numpy()[:10].all()
+    assert (o.draft_ids.cpu().numpy()[10:20] == 1234).all()
+
+
+def test_pipeline_end_to_end(rdk, tiny):
+    """rdk_build_kernel -> rdk_redistribute_linear -> rdk_verify_sample on the device vs the oracle chain."""
+    w = tiny["w"]
+    kern = rdk.rdk_build_kernel(w.N, dev(tiny["kept_ids"]), rdk.SPARSE_TOPK, embeddings=dev(tiny["E"]), tau=w.tau, k=w.k)
+    qp = rdk.rdk_redistribute_linear(kern, rdk.LINEAR_SPARSE, dev(tiny["q_hat"]))
+    o = rdk.rdk_verify_sample(dev(tiny["p"]), qp, seed=77, offset=0, gamma=w.gamma)
+    ref_qp = oracle_rows(tiny, "sparse", kernel=tiny["sparse"])
+    assert_close(qp.cpu().numpy(), ref_qp, rtol=2e-5, what="q' from the device-built kernel")
+    ref = oracle.verify_batch(tiny["p"], ref_qp, 77, 0, gamma=w.gamma)
+    assert_close(o.alpha.cpu().numpy(), ref["alpha"], rtol=2e-5, what="alpha")
+    us = np.array([oracle.uniforms(77, b) for b in range(w.B)])
+    check_sampled_ids(ref_qp, us[:, 0], o.draft_ids.cpu().numpy(), ref["draft_ids"], what="draft")
