@@ -1,6 +1,9 @@
 // C ABI of the RDK library: argument checks, storage / workspace carving, dispatch to the launchers.
+#include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "rdk_common.hpp"
 
@@ -12,6 +15,47 @@ rdk_status_t hip_fail(hipError_t e, const char *what)
 {
     g_last_hip_error = std::string(what) + ": " + hipGetErrorString(e);
     return RDK_ERR_HIP;
+}
+
+// ---- optional event timing of selected kernels (used by benchmarks)
+namespace {
+struct TimedRecord {
+    std::string name;
+    hipEvent_t start, stop;
+};
+std::mutex g_timing_mutex;
+std::string g_timing_selected;             // "" = off, "*" = every instrumented kernel
+std::vector<TimedRecord> g_timing_records;
+std::vector<hipEvent_t> g_timing_free;
+
+hipEvent_t timing_event()
+{
+    if (!g_timing_free.empty()) {
+        hipEvent_t e = g_timing_free.back();
+        g_timing_free.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+TimedLaunch::TimedLaunch(const char *kernel_name, hipStream_t st) : stop_(nullptr), st_(st)
+{
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    if (g_timing_selected.empty()) return;
+    if (g_timing_selected != "*" && g_timing_selected != kernel_name) return;
+    hipEvent_t a = timing_event(), b = timing_event();
+    if (!a || !b) return;
+    if (hipEventRecord(a, st) != hipSuccess) return;
+    g_timing_records.push_back(TimedRecord{kernel_name, a, b});
+    stop_ = b;
+}
+
+TimedLaunch::~TimedLaunch()
+{
+    if (stop_) (void)hipEventRecord(stop_, st_);
 }
 
 namespace {
@@ -367,6 +411,39 @@ rdk_status_t rdk_verify_sample(const rdk_verify_desc_t *desc, const void *p, rdk
     RowInput pi{p, p_kind, ldp};
     return launch_verify(*desc, pi, q_prime, ldq, draft_ids, accept, alpha, resid_mass, resid_ids, n_accepted, out_tokens,
                          workspace, (hipStream_t)stream);
+}
+
+rdk_status_t rdk_timing_select(const char *kernel_name)
+{
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    g_timing_selected = kernel_name ? kernel_name : "";
+    return RDK_OK;
+}
+
+rdk_status_t rdk_timing_read(const char *kernel_name, int64_t *launches, double *total_ms)
+{
+    if (!kernel_name || !launches || !total_ms) return RDK_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    int64_t count = 0;
+    double total = 0.0;
+    std::vector<TimedRecord> keep;
+    for (TimedRecord &r : g_timing_records) {
+        if (r.name != kernel_name) {
+            keep.push_back(r);
+            continue;
+        }
+        RDK_HIP(hipEventSynchronize(r.stop));
+        float ms = 0.f;
+        RDK_HIP(hipEventElapsedTime(&ms, r.start, r.stop));
+        total += (double)ms;
+        ++count;
+        g_timing_free.push_back(r.start);
+        g_timing_free.push_back(r.stop);
+    }
+    g_timing_records.swap(keep);
+    *launches = count;
+    *total_ms = total;
+    return RDK_OK;
 }
 
 rdk_status_t rdk_philox_words(uint64_t seed, uint64_t offset, int32_t count, uint32_t *words, void *stream)

@@ -47,6 +47,15 @@ rdk_status_t hip_fail(hipError_t e, const char *what);
         if (e_ != hipSuccess) return ::rdk::hip_fail(e_, name);         \
     } while (0)
 
+// Brackets one kernel launch with HIP events when that kernel has been selected through
+// rdk_timing_select(); otherwise it does nothing.  Declare it in the scope of the launch.
+struct TimedLaunch {
+    TimedLaunch(const char *kernel_name, hipStream_t st);
+    ~TimedLaunch();
+    hipEvent_t stop_;
+    hipStream_t st_;
+};
+
 // ---- launchers implemented in the kernel translation units (all enqueue on `st`, none synchronises)
 
 struct RowInput {            // a [B, len] input of some kind

@@ -286,15 +286,24 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
         const int64_t ldd = (h.N + 3) / 4 * 4;
         dim3 grid((h.N + kColsF - 1) / kColsF, (B + kRowsF - 1) / kRowsF, splits);
         if (splits == 1) {
-            hipLaunchKernelGGL((exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
-                               B, per, out, ldo, (int64_t)0, true);
+            {
+                TimedLaunch timed("exact_f32_kernel", st);
+                hipLaunchKernelGGL((exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
+                                   B, per, out, ldo, (int64_t)0, true);
+            }
             RDK_LAUNCH_CHECK("exact_f32_kernel");
         } else {
-            hipLaunchKernelGGL((exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
-                               B, per, w.part, ldd, (int64_t)B * ldd, false);
+            {
+                TimedLaunch timed("exact_f32_kernel", st);
+                hipLaunchKernelGGL((exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
+                                   B, per, w.part, ldd, (int64_t)B * ldd, false);
+            }
             RDK_LAUNCH_CHECK("exact_f32_kernel");
-            hipLaunchKernelGGL(exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part, ldd,
-                               (int64_t)B * ldd, splits, w.qstat, h.N, out, ldo);
+            {
+                TimedLaunch timed("exact_reduce_kernel", st);
+                hipLaunchKernelGGL(exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part, ldd,
+                                   (int64_t)B * ldd, splits, w.qstat, h.N, out, ldo);
+            }
             RDK_LAUNCH_CHECK("exact_reduce_kernel");
         }
         return RDK_OK;
@@ -305,15 +314,27 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
     const int B_pad = (B + rows_per_wg - 1) / rows_per_wg * rows_per_wg;
     w.A = (uint16_t *)p; p += align_up((size_t)B_pad * h.n_pad * 2, 256);
     w.out_scale = (float *)p;
-    hipLaunchKernelGGL((prep_a_bf16_kernel<QK>), dim3(B_pad), dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.row_sum, h.n, h.n_pad,
-                       B, w.A, w.out_scale);
+    {
+        TimedLaunch timed("prep_a_bf16_kernel", st);
+        hipLaunchKernelGGL((prep_a_bf16_kernel<QK>), dim3(B_pad), dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.row_sum, h.n, h.n_pad,
+                           B, w.A, w.out_scale);
+    }
     RDK_LAUNCH_CHECK("prep_a_bf16_kernel");
     const int n_jb = (h.N + kColBlock - 1) / kColBlock;
     dim3 grid((n_jb + kColBlocksPerWg - 1) / kColBlocksPerWg, B_pad / rows_per_wg);
     const int KB = h.n_pad / kKStep;
-    if (rb == 1) hipLaunchKernelGGL((exact_bf16_kernel<1>), grid, dim3(256), 0, st, w.A, h.n_pad, h.packed, KB, h.N, B, w.out_scale, out, ldo);
-    else if (rb == 2) hipLaunchKernelGGL((exact_bf16_kernel<2>), grid, dim3(256), 0, st, w.A, h.n_pad, h.packed, KB, h.N, B, w.out_scale, out, ldo);
-    else hipLaunchKernelGGL((exact_bf16_kernel<4>), grid, dim3(256), 0, st, w.A, h.n_pad, h.packed, KB, h.N, B, w.out_scale, out, ldo);
+    {
+        TimedLaunch timed("exact_bf16_kernel", st);
+        if (rb == 1)
+            hipLaunchKernelGGL((exact_bf16_kernel<1>), grid, dim3(256), 0, st, w.A, h.n_pad, h.packed, KB, h.N, B, w.out_scale,
+                               out, ldo);
+        else if (rb == 2)
+            hipLaunchKernelGGL((exact_bf16_kernel<2>), grid, dim3(256), 0, st, w.A, h.n_pad, h.packed, KB, h.N, B, w.out_scale,
+                               out, ldo);
+        else
+            hipLaunchKernelGGL((exact_bf16_kernel<4>), grid, dim3(256), 0, st, w.A, h.n_pad, h.packed, KB, h.N, B, w.out_scale,
+                               out, ldo);
+    }
     RDK_LAUNCH_CHECK("exact_bf16_kernel");
     return RDK_OK;
 }

@@ -17,9 +17,10 @@ constexpr int kIdsPerBlock = 256;
 struct LinearWs {
     SoftStat *pstat;   // [B, p_splits]  target row softmax statistics (logit p only)
     SoftStat *qstat;   // [B]            drafter row: (max, sum exp) or (0, sum)
+    SoftStat *qpart;   // [B, q_splits]  partials of the above (sparse product)
     float *tpart;      // [B, t_splits, 4]  Taylor partial sums
     float *qT;         // [ceil(B/16), n, 16] drafter weights, position-minor (sparse product)
-    int p_splits, t_splits;
+    int p_splits, t_splits, q_splits;
 };
 
 LinearWs carve(const KernelHandle &h, int32_t B, void *ws)
@@ -27,9 +28,11 @@ LinearWs carve(const KernelHandle &h, int32_t B, void *ws)
     LinearWs w;
     w.p_splits = row_splits(B, h.N, kWaves);
     w.t_splits = w.p_splits;
+    w.q_splits = row_splits(B, h.n, kWaves);
     char *p = (char *)ws;
     w.pstat = (SoftStat *)p; p += align_up((size_t)B * w.p_splits * sizeof(SoftStat), 256);
     w.qstat = (SoftStat *)p; p += align_up((size_t)B * sizeof(SoftStat), 256);
+    w.qpart = (SoftStat *)p; p += align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256);
     w.tpart = (float *)p; p += align_up((size_t)B * w.t_splits * 4 * sizeof(float), 256);
     w.qT = (float *)p;
     return w;
@@ -81,16 +84,17 @@ __global__ __launch_bounds__(kThreads) void taylor_stats_kernel(const void *p, i
                 if (idx + 2 < N) sv.z = slot_of[idx + 2];
             }
             const int se[4] = {sv.x, sv.y, sv.z, sv.w};
+            float qraw[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) qraw[e] = load1<QK>(qr, max(se[e], 0));   // unconditional: loads stay batched
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float r = 1.0f / (fN + pe[e]);
                 bs += pe[e] * r;
-                if (se[e] >= 0) {
-                    const float qh = to_weight<QK>(load1<QK>(qr, se[e]), qm, 1.f);
-                    zq += qh;
-                    tn += qh * pe[e];
-                    an += fN * qh * r;
-                }
+                const float qh = se[e] >= 0 ? to_weight<QK>(qraw[e], qm, 1.f) : 0.f;
+                zq += qh;
+                tn += qh * pe[e];
+                an += fN * qh * r;
             }
         }
     }
@@ -166,10 +170,12 @@ __global__ __launch_bounds__(kThreads) void taylor_write_kernel(const void *p, i
             }
             const int se[4] = {sv.x, sv.y, sv.z, sv.w};
             float o[4];
+            float qraw[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) qraw[e] = load1<QK>(qr, max(se[e], 0));
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float qp = 0.f;
-                if (se[e] >= 0) qp = to_weight<QK>(load1<QK>(qr, se[e]), qm, 1.f) * inv_zq;
+                const float qp = se[e] >= 0 ? to_weight<QK>(qraw[e], qm, 1.f) * inv_zq : 0.f;
                 o[e] = (fN * qp + theta * pe[e]) / (fN + pe[e]) * inv_S;
             }
             if (vec_o && idx + 3 < N) {
@@ -203,19 +209,37 @@ __global__ __launch_bounds__(kThreads) void tli_scatter_kernel(const void *q, in
 //   qT[(pb * n + s) * 16 + r] = weight(q[pb*16 + r, s])   (zero for positions beyond B),
 // so that one neighbour of one id is a single 64-byte read serving 16 positions.
 template <int QK>
-__global__ __launch_bounds__(kThreads) void q_transpose_kernel(const void *q, int64_t ldq, int n, int B, const SoftStat *qstat,
-                                                               float *qT)
+__global__ __launch_bounds__(kThreads) void q_transpose_kernel(const void *q, int64_t ldq, int n, int B, const SoftStat *qpart,
+                                                               int q_splits, SoftStat *qstat, float *qT)
 {
     __shared__ float tile[64][kPosBlock + 1];
+    __shared__ SoftStat rowstat[kPosBlock];
     const int pb = blockIdx.y;
     const int s0 = blockIdx.x * 64;
+    {   // merge the row statistics of the 16 positions (4 per wavefront); the first slot tile publishes them
+        const int wid = threadIdx.x / kWave;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = wid * 4 + i;
+            const int64_t b = (int64_t)pb * kPosBlock + r;
+            SoftStat st;
+            st.m = 0.f;
+            st.s = 1.f;
+            if (b < B) st = merged_row_stat<QK>(qpart, q_splits, b);
+            if (lane_id() == 0) {
+                rowstat[r] = st;
+                if (blockIdx.x == 0 && b < B) qstat[b] = st;
+            }
+        }
+    }
+    __syncthreads();
     {   // read: 16 rows x 64 slots, 16 threads per row, 4 slots per thread
         const int r = threadIdx.x / 16, c4 = (threadIdx.x % 16) * 4;
         const int64_t b = (int64_t)pb * kPosBlock + r;
         float v[4] = {0.f, 0.f, 0.f, 0.f};
         if (b < B) {
             const void *qr = row_ptr<QK>(q, ldq, b);
-            const float qm = QK == RDK_PROB_F32 ? 0.f : qstat[b].m;
+            const float qm = rowstat[r].m;
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 if (s0 + c4 + e < n) v[e] = to_weight<QK>(load1<QK>(qr, s0 + c4 + e), qm, 1.f);
@@ -281,19 +305,23 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(const int32_t 
             }
             const int ie[4] = {iv.x, iv.y, iv.z, iv.w};
             const int we[4] = {__float_as_int(wv.x), __float_as_int(wv.y), __float_as_int(wv.z), __float_as_int(wv.w)};
-#define RDK_NEIGHBOUR(SRC, E)                                                            \
-    {                                                                                    \
-        const int s_ = quad_bcast<SRC>(ie[E]);                                           \
-        const float w_ = __int_as_float(quad_bcast<SRC>(we[E]));                         \
-        if (w_ != 0.f) {                                                                 \
-            const float4 g = *(const float4 *)(qslab + (int64_t)s_ * kPosBlock);         \
-            acc.x += w_ * g.x; acc.y += w_ * g.y; acc.z += w_ * g.z; acc.w += w_ * g.w;  \
-        }                                                                                \
+            // all sixteen gathers are issued before any is used; padding entries carry weight 0 and slot 0
+            float4 g[16];
+            float wt[16];
+#define RDK_GATHER(SRC, E)                                                                       \
+    {                                                                                            \
+        const int s_ = quad_bcast<SRC>(ie[E]);                                                   \
+        wt[SRC * 4 + E] = __int_as_float(quad_bcast<SRC>(we[E]));                                \
+        g[SRC * 4 + E] = *(const float4 *)(qslab + (int64_t)s_ * kPosBlock);                     \
     }
-#define RDK_QUARTER(SRC) RDK_NEIGHBOUR(SRC, 0) RDK_NEIGHBOUR(SRC, 1) RDK_NEIGHBOUR(SRC, 2) RDK_NEIGHBOUR(SRC, 3)
+#define RDK_QUARTER(SRC) RDK_GATHER(SRC, 0) RDK_GATHER(SRC, 1) RDK_GATHER(SRC, 2) RDK_GATHER(SRC, 3)
             RDK_QUARTER(0) RDK_QUARTER(1) RDK_QUARTER(2) RDK_QUARTER(3)
 #undef RDK_QUARTER
-#undef RDK_NEIGHBOUR
+#undef RDK_GATHER
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                acc.x += wt[t] * g[t].x; acc.y += wt[t] * g[t].y; acc.z += wt[t] * g[t].z; acc.w += wt[t] * g[t].w;
+            }
         }
         stage[quarter * 4 + 0][jl] = acc.x * inv_z[0];
         stage[quarter * 4 + 1][jl] = acc.y * inv_z[1];
@@ -335,11 +363,17 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     }
     const bool vec_p = rows_vectorisable(p.ptr, p.ld, p.kind);
     const bool vec_o = rows_vectorisable(out, ldo, RDK_PROB_F32);
-    hipLaunchKernelGGL((taylor_stats_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads), 0, st, p.ptr, p.ld,
-                       q.ptr, q.ld, h.slot_of, h.N, w.t_splits, vec_p, w);
+    {
+        TimedLaunch timed("taylor_stats_kernel", st);
+        hipLaunchKernelGGL((taylor_stats_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads), 0, st, p.ptr, p.ld,
+                           q.ptr, q.ld, h.slot_of, h.N, w.t_splits, vec_p, w);
+    }
     RDK_LAUNCH_CHECK("taylor_stats_kernel");
-    hipLaunchKernelGGL((taylor_write_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads), 0, st, p.ptr, p.ld,
-                       q.ptr, q.ld, h.slot_of, h.N, w.t_splits, vec_p, vec_o, w, out, ldo);
+    {
+        TimedLaunch timed("taylor_write_kernel", st);
+        hipLaunchKernelGGL((taylor_write_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads), 0, st, p.ptr, p.ld,
+                           q.ptr, q.ld, h.slot_of, h.N, w.t_splits, vec_p, vec_o, w, out, ldo);
+    }
     RDK_LAUNCH_CHECK("taylor_write_kernel");
     return RDK_OK;
 }
@@ -348,24 +382,35 @@ template <int QK>
 rdk_status_t run_sparse(const KernelHandle &h, RowInput q, int32_t B, float *out, int64_t ldo, void *ws, hipStream_t st)
 {
     LinearWs w = carve(h, B, ws);
-    rdk_status_t rc = launch_row_stats<QK>(q, h.n, B, 1, w.qstat, st);
-    if (rc != RDK_OK) return rc;
     if (h.format == RDK_IDENTITY) {
+        rdk_status_t rc1 = launch_row_stats<QK>(q, h.n, B, 1, w.qstat, st);
+        if (rc1 != RDK_OK) return rc1;
         const int bx = (h.N + kThreads * 4 - 1) / (kThreads * 4);
-        hipLaunchKernelGGL((tli_scatter_kernel<QK>), dim3(bx, B), dim3(kThreads), 0, st, q.ptr, q.ld, h.slot_of, h.N, w.qstat,
-                           out, ldo);
+        {
+            TimedLaunch timed("tli_scatter_kernel", st);
+            hipLaunchKernelGGL((tli_scatter_kernel<QK>), dim3(bx, B), dim3(kThreads), 0, st, q.ptr, q.ld, h.slot_of, h.N, w.qstat,
+                               out, ldo);
+        }
         RDK_LAUNCH_CHECK("tli_scatter_kernel");
         return RDK_OK;
     }
+    rdk_status_t rc = launch_row_stats<QK>(q, h.n, B, w.q_splits, w.qpart, st);
+    if (rc != RDK_OK) return rc;
     const int pbs = (B + kPosBlock - 1) / kPosBlock;
-    hipLaunchKernelGGL((q_transpose_kernel<QK>), dim3((h.n + 63) / 64, pbs), dim3(kThreads), 0, st, q.ptr, q.ld, h.n, B,
-                       w.qstat, w.qT);
+    {
+        TimedLaunch timed("q_transpose_kernel", st);
+        hipLaunchKernelGGL((q_transpose_kernel<QK>), dim3((h.n + 63) / 64, pbs), dim3(kThreads), 0, st, q.ptr, q.ld, h.n, B,
+                           w.qpart, w.q_splits, w.qstat, w.qT);
+    }
     RDK_LAUNCH_CHECK("q_transpose_kernel");
     const int tiles = (h.N + kIdsPerBlock - 1) / kIdsPerBlock;
     const int total = pbs * tiles;
     const int per_xcd = (total + 7) / 8;
-    hipLaunchKernelGGL(sparse_product_kernel, dim3(8 * per_xcd), dim3(kThreads), 0, st, h.ell_idx, h.ell_w, h.kk, w.qT,
-                       w.qstat, h.N, h.n, B, tiles, per_xcd, total, out, ldo, rows_vectorisable(out, ldo, RDK_PROB_F32));
+    {
+        TimedLaunch timed("sparse_product_kernel", st);
+        hipLaunchKernelGGL(sparse_product_kernel, dim3(8 * per_xcd), dim3(kThreads), 0, st, h.ell_idx, h.ell_w, h.kk, w.qT,
+                           w.qstat, h.N, h.n, B, tiles, per_xcd, total, out, ldo, rows_vectorisable(out, ldo, RDK_PROB_F32));
+    }
     RDK_LAUNCH_CHECK("sparse_product_kernel");
     return RDK_OK;
 }
@@ -377,6 +422,7 @@ size_t linear_workspace_bytes(const KernelHandle &h, int32_t B)
     const int splits = row_splits(B, h.N, kWaves);
     const size_t pbs = (B + kPosBlock - 1) / kPosBlock;
     return align_up((size_t)B * splits * sizeof(SoftStat), 256) + align_up((size_t)B * sizeof(SoftStat), 256) +
+           align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256) +
            align_up((size_t)B * splits * 4 * sizeof(float), 256) + align_up(pbs * h.n * kPosBlock * sizeof(float), 256);
 }
 

@@ -143,31 +143,30 @@ __device__ __forceinline__ int locate_block(const float *part, int nchunks, int 
 }
 
 // Within one 1024-id block, the smallest id whose inclusive prefix of weights exceeds thr_local; if
-// rounding leaves none, the last id of the block with a positive weight.  `weights(idx)` returns the
-// four weights at idx..idx+3 (zero beyond the row).
-template <class W4>
-__device__ __forceinline__ int search_block(W4 weights, int blk, double thr_local)
+// rounding leaves none, the last id of the block with a positive weight.  wv[i] holds the weights of
+// ids blk*1024 + i*256 + lane*4 .. +3 (zero beyond the row), all loaded before the scan starts.
+__device__ __forceinline__ int search_block(const float4 (&wv)[4], int blk, double thr_local)
 {
     const int lane = lane_id();
     double carried = 0.0;
     int last_positive = -1;
+#pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int64_t idx = (int64_t)blk * kChunk + i * 256 + lane * 4;
-        const float4 wv = weights(idx);
-        const double l0 = (double)wv.x, l1 = l0 + (double)wv.y, l2 = l1 + (double)wv.z, l3 = l2 + (double)wv.w;
+        const int idx = blk * kChunk + i * 256 + lane * 4;
+        const double l0 = (double)wv[i].x, l1 = l0 + (double)wv[i].y, l2 = l1 + (double)wv[i].z, l3 = l2 + (double)wv[i].w;
         const double incl = wave_inclusive_scan(l3);
         const double excl = carried + (incl - l3);
         const unsigned long long hits = __ballot(excl + l3 > thr_local);
         if (hits != 0ull) {
             const int src = __ffsll(hits) - 1;
             const int e = (excl + l0 > thr_local) ? 0 : (excl + l1 > thr_local) ? 1 : (excl + l2 > thr_local) ? 2 : 3;
-            return __shfl((int)idx + e, src, kWave);
+            return __shfl(idx + e, src, kWave);
         }
-        const int mine = wv.w > 0.f ? 3 : wv.z > 0.f ? 2 : wv.y > 0.f ? 1 : wv.x > 0.f ? 0 : -1;
+        const int mine = wv[i].w > 0.f ? 3 : wv[i].z > 0.f ? 2 : wv[i].y > 0.f ? 1 : wv[i].x > 0.f ? 0 : -1;
         const unsigned long long pos = __ballot(mine >= 0);
         if (pos != 0ull) {
             const int src = 63 - __clzll(pos);
-            last_positive = __shfl((int)idx + mine, src, kWave);
+            last_positive = __shfl(idx + mine, src, kWave);
         }
         carried += __shfl(incl, kWave - 1, kWave);
     }
@@ -190,71 +189,77 @@ __global__ void verify_finalize_kernel(rdk_verify_desc_t d, const void *p, int64
         const float *qr = HAS_Q ? q + row * ldq : nullptr;
         float m = 0.f, inv = 1.f;
         if (KIND != RDK_PROB_F32) {
-        const SoftStat rs = merged_row_stat<KIND>(w.pstat, w.stat_splits, row);
-        m = rs.m;
-        inv = 1.0f / rs.s;
-    }
+            const SoftStat rs = merged_row_stat<KIND>(w.pstat, w.stat_splits, row);
+            m = rs.m;
+            inv = 1.0f / rs.s;
+        }
         const float pfill = KIND == RDK_PROB_F32 ? 0.f : -INFINITY;
         const int per_lane = (w.nchunks + kWave - 1) / kWave;
         const float *pq = w.part_q + row * w.nchunks;
         const float *prr = w.part_r + row * w.nchunks;
         const float *pa = w.part_a + row * w.nchunks;
+        const bool draw_draft = HAS_Q && d.sample_draft;
 
+        // 1. block partials (one round trip), uniforms meanwhile
+        const double lane_r = lane_partial_sum(prr, w.nchunks, per_lane);
+        const double lane_q = draw_draft ? lane_partial_sum(pq, w.nchunks, per_lane) : 0.0;
+        const double lane_a = HAS_Q ? lane_partial_sum(pa, w.nchunks, per_lane) : 0.0;
+        int32_t dtok = (HAS_Q && !d.sample_draft) ? draft_ids[row] : -1;
         uint32_t words[4];
         position_words(d.seed, d.offset + (uint64_t)row, words);
-
-        const double lane_r = lane_partial_sum(prr, w.nchunks, per_lane);
         const double R = wave_sum(lane_r);
-        double A = 0.0;
-        int32_t dtok = -1;
-        uint8_t acc = 0;
-        if (HAS_Q) {
-            A = wave_sum(lane_partial_sum(pa, w.nchunks, per_lane));
-            if (d.sample_draft) {
-                const double lane_q = lane_partial_sum(pq, w.nchunks, per_lane);
-                const double Q = wave_sum(lane_q);
-                if (Q > 0.0) {
-                    const double thr = word_to_unit(words[0]) * Q;
-                    double before = 0.0;
-                    const int blk = locate_block(pq, w.nchunks, per_lane, lane_q, thr, before);
-                    if (blk >= 0)
-                        dtok = search_block([&](int64_t idx) { return load4<RDK_PROB_F32>(qr, idx, N, vec_q, 0.f); }, blk,
-                                            thr - before);
-                }
-            } else {
-                dtok = draft_ids[row];
-            }
-            if (dtok >= 0 && dtok < N) {
-                const double pd = (double)to_weight<KIND>(load1<KIND>(pr, dtok), m, inv);
-                const double qd = (double)qr[dtok];
-                acc = (word_to_unit(words[1]) * qd < pd) ? 1 : 0;
-            }
+        const double Q = draw_draft ? wave_sum(lane_q) : 0.0;
+        const double A = HAS_Q ? wave_sum(lane_a) : 0.0;
+
+        // 2. the blocks that hold the two prefix-sum crossings
+        double thr_d = 0.0, thr_r = 0.0, before_d = 0.0, before_r = 0.0;
+        int blk_d = -1, blk_r = -1;
+        if (draw_draft && Q > 0.0) {
+            thr_d = word_to_unit(words[0]) * Q;
+            blk_d = locate_block(pq, w.nchunks, per_lane, lane_q, thr_d, before_d);
+        }
+        if (R > 0.0) {
+            thr_r = word_to_unit(words[HAS_Q ? 2 : 3]) * R;
+            blk_r = locate_block(prr, w.nchunks, per_lane, lane_r, thr_r, before_r);
+        }
+
+        // 3. both blocks are fetched together (one round trip), then scanned
+        float4 wd[4], wp[4], wq[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t id_d = (int64_t)max(blk_d, 0) * kChunk + i * 256 + lane * 4;
+            const int64_t id_r = (int64_t)max(blk_r, 0) * kChunk + i * 256 + lane * 4;
+            if (draw_draft) wd[i] = load4<RDK_PROB_F32>(qr, id_d, N, vec_q, 0.f);
+            wp[i] = load4<KIND>(pr, id_r, N, vec_p, pfill);
+            if (HAS_Q) wq[i] = load4<RDK_PROB_F32>(qr, id_r, N, vec_q, 0.f);
+        }
+        if (blk_d >= 0) dtok = search_block(wd, blk_d, thr_d - before_d);
+        // 4. the accept test needs p and q' at the draft token: issue those loads before the second scan
+        float pd_raw = 0.f, qd = 0.f;
+        const bool d_ok = HAS_Q && dtok >= 0 && dtok < N;
+        if (d_ok) {
+            pd_raw = load1<KIND>(pr, dtok);
+            qd = qr[dtok];
         }
         int32_t rtok = -1;
-        if (R > 0.0) {
-            const double thr = word_to_unit(words[HAS_Q ? 2 : 3]) * R;
-            double before = 0.0;
-            const int blk = locate_block(prr, w.nchunks, per_lane, lane_r, thr, before);
-            if (blk >= 0)
-                rtok = search_block(
-                    [&](int64_t idx) {
-                        float4 pv = load4<KIND>(pr, idx, N, vec_p, pfill);
-                        float4 r;
-                        r.x = to_weight<KIND>(pv.x, m, inv);
-                        r.y = to_weight<KIND>(pv.y, m, inv);
-                        r.z = to_weight<KIND>(pv.z, m, inv);
-                        r.w = to_weight<KIND>(pv.w, m, inv);
-                        if (HAS_Q) {
-                            const float4 qv = load4<RDK_PROB_F32>(qr, idx, N, vec_q, 0.f);
-                            r.x = fmaxf(r.x - qv.x, 0.f);
-                            r.y = fmaxf(r.y - qv.y, 0.f);
-                            r.z = fmaxf(r.z - qv.z, 0.f);
-                            r.w = fmaxf(r.w - qv.w, 0.f);
-                        }
-                        return r;
-                    },
-                    blk, thr - before);
+        if (blk_r >= 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                wp[i].x = to_weight<KIND>(wp[i].x, m, inv);
+                wp[i].y = to_weight<KIND>(wp[i].y, m, inv);
+                wp[i].z = to_weight<KIND>(wp[i].z, m, inv);
+                wp[i].w = to_weight<KIND>(wp[i].w, m, inv);
+                if (HAS_Q) {
+                    wp[i].x = fmaxf(wp[i].x - wq[i].x, 0.f);
+                    wp[i].y = fmaxf(wp[i].y - wq[i].y, 0.f);
+                    wp[i].z = fmaxf(wp[i].z - wq[i].z, 0.f);
+                    wp[i].w = fmaxf(wp[i].w - wq[i].w, 0.f);
+                }
+            }
+            rtok = search_block(wp, blk_r, thr_r - before_r);
         }
+        uint8_t acc = 0;
+        if (d_ok) acc = (word_to_unit(words[1]) * (double)qd < (double)to_weight<KIND>(pd_raw, m, inv)) ? 1 : 0;
         if (lane == 0) {
             if (HAS_Q && d.sample_draft) draft_ids[row] = dtok;
             accept[row] = acc;
@@ -321,20 +326,29 @@ rdk_status_t run_verify(const rdk_verify_desc_t &d, RowInput p, const float *q, 
         rdk_status_t rc = launch_row_stats<KIND>(p, d.N, d.B, w.stat_splits, w.pstat, st);
         if (rc != RDK_OK) return rc;
     }
-    hipLaunchKernelGGL((verify_stream_kernel<KIND, HAS_Q>), dim3((unsigned)d.B * splits), dim3(kStreamThreads), 0, st, p.ptr,
-                       p.ld, q, ldq, d.N, splits, vec_p, vec_q, w);
+    {
+        TimedLaunch timed("verify_stream_kernel", st);
+        hipLaunchKernelGGL((verify_stream_kernel<KIND, HAS_Q>), dim3((unsigned)d.B * splits), dim3(kStreamThreads), 0, st, p.ptr,
+                           p.ld, q, ldq, d.N, splits, vec_p, vec_q, w);
+    }
     RDK_LAUNCH_CHECK("verify_stream_kernel");
     const bool scan_here = d.gamma >= 1 && d.gamma <= 16;
     const int rows_per_block = scan_here ? d.gamma : 4;
     const int blocks = (d.B + rows_per_block - 1) / rows_per_block;
-    hipLaunchKernelGGL((verify_finalize_kernel<KIND, HAS_Q>), dim3(blocks), dim3(rows_per_block * kWave), 0, st, d, p.ptr,
-                       p.ld, q, ldq, vec_p, vec_q, w, rows_per_block, scan_here, draft_ids, accept, alpha, resid_mass,
-                       resid_ids, n_accepted, out_tokens);
+    {
+        TimedLaunch timed("verify_finalize_kernel", st);
+        hipLaunchKernelGGL((verify_finalize_kernel<KIND, HAS_Q>), dim3(blocks), dim3(rows_per_block * kWave), 0, st, d, p.ptr,
+                           p.ld, q, ldq, vec_p, vec_q, w, rows_per_block, scan_here, draft_ids, accept, alpha, resid_mass,
+                           resid_ids, n_accepted, out_tokens);
+    }
     RDK_LAUNCH_CHECK("verify_finalize_kernel");
     if (d.gamma > 16 && (n_accepted || out_tokens)) {
         const int S = d.B / d.gamma;
-        hipLaunchKernelGGL(sequence_scan_kernel, dim3((S + 63) / 64), dim3(64), 0, st, S, d.gamma, draft_ids, accept,
-                           resid_ids, n_accepted, out_tokens);
+        {
+            TimedLaunch timed("sequence_scan_kernel", st);
+            hipLaunchKernelGGL(sequence_scan_kernel, dim3((S + 63) / 64), dim3(64), 0, st, S, d.gamma, draft_ids, accept,
+                               resid_ids, n_accepted, out_tokens);
+        }
         RDK_LAUNCH_CHECK("sequence_scan_kernel");
     }
     return RDK_OK;

@@ -22,6 +22,7 @@ EXPORTS = [
     "rdk_status_string", "rdk_last_hip_error", "rdk_kernel_storage_bytes", "rdk_build_kernel", "rdk_destroy_kernel",
     "rdk_kernel_get_sparse", "rdk_kernel_get_dense", "rdk_workspace_bytes", "rdk_redistribute_exact",
     "rdk_redistribute_linear", "rdk_verify_workspace_bytes", "rdk_verify_sample", "rdk_philox_words",
+    "rdk_timing_select", "rdk_timing_read",
 ]
 
 
@@ -75,6 +76,8 @@ def lib():
         L.rdk_verify_sample.argtypes = [ctypes.POINTER(VerifyDesc), vp, ctypes.c_int, i64, vp, i64, vp, vp, vp, vp, vp, vp,
                                         vp, vp, sz, vp]
         L.rdk_philox_words.argtypes = [ctypes.c_uint64, ctypes.c_uint64, i32, vp, vp]
+        L.rdk_timing_select.argtypes = [ctypes.c_char_p]
+        L.rdk_timing_read.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
         for name in EXPORTS:
             if name not in ("rdk_status_string", "rdk_last_hip_error"):
                 getattr(L, name).restype = ctypes.c_int
@@ -239,3 +242,15 @@ def rdk_philox_words(seed, offset, count, device="cuda"):
     words = torch.empty((count, 4), dtype=torch.int32, device=device)
     _check(lib().rdk_philox_words(seed, offset, count, _ptr(words), _stream()), "rdk_philox_words")
     return words
+
+
+def rdk_timing_select(kernel_name):
+    """Bracket launches of one library kernel ('*' = all hot-path kernels, None = off) with HIP events."""
+    _check(lib().rdk_timing_select(kernel_name.encode() if kernel_name else None), "rdk_timing_select")
+
+
+def rdk_timing_read(kernel_name):
+    """(launches, total milliseconds) recorded for a kernel since the last read."""
+    n, ms = ctypes.c_int64(), ctypes.c_double()
+    _check(lib().rdk_timing_read(kernel_name.encode(), ctypes.byref(n), ctypes.byref(ms)), "rdk_timing_read")
+    return n.value, ms.value

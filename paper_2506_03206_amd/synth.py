@@ -137,3 +137,23 @@ def random_row_stochastic(rng, n, N, concentration=0.3):
     """A dense random row-stochastic matrix [n,N] (Dirichlet rows), fp64."""
     g = rng.gamma(concentration, size=(n, N)) + 1e-300
     return g / g.sum(axis=1, keepdims=True)
+
+
+def random_sparse_kernel(rng, N, kept, k):
+    """A row-stochastic top-k-shaped kernel with random neighbours: for each pruned id k distinct kept
+    slots drawn uniformly and positive weights; Eq. 2's normalisation over the retained entries of each
+    row is done here in fp64.  Returns (nbr_idx [N-n,k] int32, nbr_w [N-n,k] fp32, self_w [n] fp32);
+    the same shape and access pattern as a kernel built from embeddings, at no build cost."""
+    n = kept.size
+    P = N - n
+    idx = rng.integers(0, n, size=(P, k), dtype=np.int32)
+    while k > 1:                                     # redraw the few rows that hold a slot twice
+        srt = np.sort(idx, axis=1)
+        dup = np.nonzero((srt[:, 1:] == srt[:, :-1]).any(axis=1))[0]
+        if dup.size == 0:
+            break
+        idx[dup] = rng.integers(0, n, size=(dup.size, k), dtype=np.int32)
+    a = np.exp(-5.0 - 3.0 * rng.random((P, k)))              # unnormalised affinities, as small as real ones
+    Z = 1.0 + np.bincount(idx.ravel(), weights=a.ravel(), minlength=n)
+    w = (a / Z[idx]).astype(np.float32)
+    return idx, w, (1.0 / Z).astype(np.float32)
