@@ -2,11 +2,12 @@
 """Throughput of the RDK redistribute + verify path on one MI355X.
 
 One step = one pass of the whole hot path over one batch of synthetic inputs that already sit in HBM:
-  rdk_redistribute_linear (top-k sparse kernel; Alg. 1 steps 1-2)  ->  rdk_verify_sample (Alg. 4).
+redistribution with the top-k sparse kernel (Alg. 1 steps 1-2) and verification (Alg. 4), through the fused
+entry point rdk_redistribute_verify (default) or as rdk_redistribute_linear -> rdk_verify_sample.
 Prints ONE JSON line: positions/s, the roofline of the dominant kernel (timed live with HIP events
 inside the library), and the CPU oracle timed on a bounded sample of the same workload.
 
-  python bench.py [--steps K] [--warmup W] [--mode sparse|taylor] [--workload NAME] [--no-cpu]
+  python bench.py [--steps K] [--warmup W] [--mode sparse|taylor] [--path fused|twocall] [--workload NAME] [--no-cpu]
 """
 import argparse
 import json
@@ -20,16 +21,19 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
 
-def algorithmic_bytes(kernel, w, B, kk):
-    """Bytes one launch of a kernel must move for B positions (inputs read once, outputs written once)."""
+def algorithmic_bytes(kernel, w, B, kk, fused, esz):
+    """Bytes one launch of a kernel must move for B positions (inputs read once, outputs written once).
+    esz = bytes per input element (4: fp32, 2: bf16 logits).  In the fused path the product / Eq. 3 kernels
+    read p instead of writing q'."""
     N, n = w.N, w.n
+    tables = 8 * (N - n) * kk + 4 * n + 4 * N                               # neighbour rows, diagonal, id maps: once
     return {
-        "verify_stream_kernel": B * 8 * N,                                  # read p and q'
-        "sparse_product_kernel": B * (4 * N + 4 * n) + 8 * N * kk,          # write q', read q^T, read the kernel once
-        "taylor_stats_kernel": B * (4 * N + 4 * n) + 4 * N,                 # read p, q, slot table
-        "taylor_write_kernel": B * (8 * N + 4 * n) + 4 * N,                 # read p, q, write q'
-        "q_transpose_kernel": B * 8 * n,
-        "row_stats_kernel": B * 4 * n,
+        "verify_stream_kernel": B * (esz + 4) * N,                          # read p and q'
+        "sparse_product_kernel": B * ((esz if fused else 4) * N + 4 * n) + tables,   # read q^T, p (fused) or write q'
+        "taylor_stats_kernel": B * esz * (N + n) + 4 * N,                   # read p, q, slot table
+        "taylor_write_kernel": B * (esz * (N + n) + (0 if fused else 4 * N)) + 4 * N,
+        "q_transpose_kernel": B * (esz + 4) * n,
+        "row_stats_kernel": B * esz * n,
         "verify_finalize_kernel": B * 3 * 4 * ((N + 1023) // 1024),
     }.get(kernel)
 
@@ -40,6 +44,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--mode", default="sparse", choices=["sparse", "taylor"])
+    ap.add_argument("--path", default="fused", choices=["fused", "twocall"],
+                    help="fused: rdk_redistribute_verify (q' never stored); twocall: rdk_redistribute_linear + rdk_verify_sample")
     ap.add_argument("--workload", default=None)
     ap.add_argument("--copies", type=int, default=4, help="input/output buffer sets rotated through (defeats the 256 MB cache)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline")
@@ -80,16 +86,22 @@ def main():
     C = max(1, args.copies)
     ps = [p_host.to(dev) for _ in range(C)]
     qs = [q_host.to(dev) for _ in range(C)]
-    outs = [torch.empty((B, w.N), dtype=torch.float32, device=dev) for _ in range(C)]
+    outs = [torch.empty((B, w.N), dtype=torch.float32, device=dev) for _ in range(C)] if args.path == "twocall" else None
     vout = rdk.VerifyOutputs(B, w.N, w.gamma, dev)
     kern.workspace(B)
     mode = rdk.LINEAR_SPARSE if args.mode == "sparse" else rdk.LINEAR_TAYLOR
 
+    fused = args.path == "fused"
+
     def step(i):
         c = i % C
-        rdk.rdk_redistribute_linear(kern, mode, qs[c], kind, p=ps[c] if args.mode == "taylor" else None, p_kind=kind,
-                                    out=outs[c])
-        rdk.rdk_verify_sample(ps[c], outs[c], seed=2506, offset=i * B, gamma=w.gamma, p_kind=kind, outputs=vout)
+        if fused:
+            rdk.rdk_redistribute_verify(kern, mode, ps[c], qs[c], seed=2506, offset=i * B, gamma=w.gamma, p_kind=kind,
+                                        q_kind=kind, outputs=vout)
+        else:
+            rdk.rdk_redistribute_linear(kern, mode, qs[c], kind, p=ps[c] if args.mode == "taylor" else None, p_kind=kind,
+                                        out=outs[c])
+            rdk.rdk_verify_sample(ps[c], outs[c], seed=2506, offset=i * B, gamma=w.gamma, p_kind=kind, outputs=vout)
 
     for i in range(args.warmup):
         step(i)
@@ -125,15 +137,19 @@ def main():
     ms_per_step = total_ms / args.steps
     value = B / (ms_per_step * 1e-3)
 
-    kk = (max(w.k, 1) + 3) // 4 * 4
-    alg = algorithmic_bytes(dominant, w, B, kk)
+    kk = (max(w.k, 1) + 15) // 16 * 16
+    esz = 2 if w.logits_bf16 else 4
+    alg = algorithmic_bytes(dominant, w, B, kk, fused, esz)
     avg_s = kms / cnt * 1e-3
     achieved = alg / avg_s / 1e9
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "avg_launch_us": round(avg_s * 1e6, 2),
                 "algorithmic_bytes_per_launch": alg}
-    # whole-step figure in the per-call accounting: q read, q' written then read, p read
-    step_bytes = B * (4 * w.n + 12 * w.N) + (8 * w.N * kk if args.mode == "sparse" else B * 4 * w.N)
+    # whole-step compulsory bytes: fused = read p and q once; two calls = q read, q' written then read, p read (twice for Eq. 3)
+    if fused:
+        step_bytes = B * esz * (w.N + w.n) + (8 * (w.N - w.n) * kk if args.mode == "sparse" else 0)
+    else:
+        step_bytes = B * (esz * (w.n + w.N) + 8 * w.N) + (8 * (w.N - w.n) * kk if args.mode == "sparse" else B * esz * w.N)
     extra = {"kernels": {k: {"avg_us": round(v["avg_us"], 2), "per_step": v["launches_per_step"]} for k, v in per_kernel.items()},
              "step_algorithmic_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
              "step_frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -150,7 +166,7 @@ def main():
             "dtype": "f32", "data": "synthetic",
             "config": {"workload": "%s: N=%d n=%d B=%d (%d seqs x %d drafts) k=%d, %s linear RDK + verify/sample, %s inputs"
                        % (w.name, w.N, w.n, B, w.seqs, w.gamma, w.k, args.mode, "bf16 logit" if w.logits_bf16 else "fp32 prob"),
-                       "mode": args.mode, "N": w.N, "n": w.n, "B": B, "k": w.k},
+                       "mode": args.mode, "path": args.path, "N": w.N, "n": w.n, "B": B, "k": w.k},
             "roofline": roofline, "cpu_baseline": cpu, "extra": extra}
     print(json.dumps(line))
 

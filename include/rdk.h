@@ -188,6 +188,26 @@ rdk_status_t rdk_verify_sample(const rdk_verify_desc_t *desc, const void *p, rdk
                                int32_t *n_accepted, int32_t *out_tokens, void *workspace,
                                size_t workspace_bytes, void *stream);
 
+/*
+ * Alg. 1 steps 1-2 and Alg. 4 steps 2, 4-10 in one call: the outputs of rdk_redistribute_linear(mode)
+ * followed by rdk_verify_sample on its result, without the round trip of q' through HBM.  The
+ * redistributed rows are produced tile by tile, summed against p on the spot, and re-computed for the
+ * two blocks in which the sampled ids fall.  q_prime may be NULL (then it is never written); otherwise
+ * it receives the same rows rdk_redistribute_linear writes.  Block sums run over 256 ids (sparse) or
+ * 1024 ids (Eq. 3), so fp32 rounding, and with it an id that sits on a prefix-sum step, can differ
+ * from the two-call path within the tolerance stated at rdk_verify_sample.  desc->N must equal the
+ * kernel's N; draft_ids is required (in/out as in rdk_verify_sample).  RDK_LINEAR_SPARSE needs a
+ * RDK_SPARSE_TOPK kernel with k > 0.
+ */
+rdk_status_t rdk_redistribute_verify_workspace_bytes(const rdk_kernel_t *kernel, rdk_linear_mode_t mode,
+                                                     const rdk_verify_desc_t *desc, size_t *bytes);
+rdk_status_t rdk_redistribute_verify(const rdk_kernel_t *kernel, rdk_linear_mode_t mode,
+                                     const rdk_verify_desc_t *desc, const void *p, rdk_input_kind_t p_kind,
+                                     int64_t ldp, const void *q, rdk_input_kind_t q_kind, int64_t ldq,
+                                     float *q_prime, int64_t ldo, int32_t *draft_ids, uint8_t *accept,
+                                     float *alpha, float *resid_mass, int32_t *resid_ids, int32_t *n_accepted,
+                                     int32_t *out_tokens, void *workspace, size_t workspace_bytes, void *stream);
+
 /* The four Philox words of `count` consecutive positions, [count, 4] uint32 on the device (for
  * checking the random stream against an independent implementation). */
 rdk_status_t rdk_philox_words(uint64_t seed, uint64_t offset, int32_t count, uint32_t *words,

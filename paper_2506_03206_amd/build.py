@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librdk_hip.so")
-SOURCES = ["rdk_api.hip", "rdk_build.hip", "rdk_linear.hip", "rdk_exact.hip", "rdk_verify.hip"]
+SOURCES = ["rdk_api.hip", "rdk_build.hip", "rdk_linear.hip", "rdk_sparse.hip", "rdk_exact.hip", "rdk_verify.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
          # packed fp32 instructions are kept off for every device function
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

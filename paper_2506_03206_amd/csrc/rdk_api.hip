@@ -64,10 +64,10 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 bool kind_ok(rdk_input_kind_t k) { return k == RDK_PROB_F32 || k == RDK_LOGIT_F32 || k == RDK_LOGIT_BF16; }
 
-int32_t ell_row_len(int32_t k) { return ((k < 1 ? 1 : k) + 3) / 4 * 4; }
+int32_t nbr_row_len(int32_t k) { return ((k < 1 ? 1 : k) + 15) / 16 * 16; }
 
 struct StorageLayout {
-    size_t kept_ids, slot_of, body, body2, total;
+    size_t kept_ids, slot_of, pruned_ids, body, body2, body3, total;
     int32_t kk, n_pad, N_pad;
     int64_t ldm;
 };
@@ -109,12 +109,13 @@ StorageLayout layout_of(const rdk_kernel_desc_t &d)
     size_t off = 0;
     L.kept_ids = off; off += align_up((size_t)d.n * 4, 256);
     L.slot_of = off; off += align_up((size_t)d.N * 4, 256);
-    L.kk = ell_row_len(d.k);
+    L.pruned_ids = off; off += align_up((size_t)(d.N - d.n + 1) * 4, 256);
+    L.kk = nbr_row_len(d.k);
     L.ldm = ((int64_t)d.N + 3) / 4 * 4;
     switch (d.format) {
         case RDK_SPARSE_TOPK:
-            L.body = off; off += align_up((size_t)d.N * L.kk * 4, 256);
-            L.body2 = off; off += align_up((size_t)d.N * L.kk * 4, 256);
+            L.body = off; off += align_up((size_t)(d.N - d.n) * L.kk * 8 + 512, 256);
+            L.body3 = off; off += align_up((size_t)d.n * 4, 256);
             break;
         case RDK_DENSE_F32:
             L.body = off; off += align_up((size_t)d.n * L.ldm * 4, 256);
@@ -213,15 +214,19 @@ rdk_status_t rdk_build_kernel(const rdk_kernel_desc_t *desc, void *storage, size
     RDK_HIP(hipMemcpyAsync(kept, d.kept_ids, (size_t)d.n * 4, hipMemcpyDeviceToDevice, st));
     rc = launch_slot_of(kept, d.n, d.N, slot_of, st);
     if (rc != RDK_OK) return rc;
+    int32_t *pruned = (int32_t *)(sp + L.pruned_ids);
+    h.pruned_ids = pruned;
+    rc = launch_pruned_ids(slot_of, d.N, pruned, st);
+    if (rc != RDK_OK) return rc;
 
     if (d.format == RDK_SPARSE_TOPK) {
         h.kk = L.kk;
-        int32_t *ell_idx = (int32_t *)(sp + L.body);
-        float *ell_w = (float *)(sp + L.body2);
-        h.ell_idx = ell_idx;
-        h.ell_w = ell_w;
-        if (d.self_w) rc = launch_import_sparse(d, slot_of, ell_idx, ell_w, L.kk, st);
-        else rc = launch_build_sparse(d, slot_of, ell_idx, ell_w, L.kk, ws, st);
+        int2 *nbr = (int2 *)(sp + L.body);
+        float *self_w = (float *)(sp + L.body3);
+        h.nbr = nbr;
+        h.self_w = self_w;
+        if (d.self_w) rc = launch_import_sparse(d, nbr, self_w, L.kk, st);
+        else rc = launch_build_sparse(d, pruned, nbr, self_w, L.kk, ws, st);
         if (rc != RDK_OK) return rc;
         if (d.validate && d.self_w) {
             rc = launch_check_stochastic_sparse(h, ws, flag, st);
@@ -312,8 +317,11 @@ rdk_status_t rdk_workspace_bytes(const rdk_kernel_t *kernel, int32_t B, size_t *
 {
     if (!kernel || !bytes) return RDK_ERR_NULL;
     if (B < 1) return RDK_ERR_SHAPE;
-    const size_t a = linear_workspace_bytes(kernel->h, B), b = exact_workspace_bytes(kernel->h, B);
-    *bytes = (a > b ? a : b) + 256;
+    size_t need = taylor_workspace_bytes(kernel->h, B);
+    const size_t b = exact_workspace_bytes(kernel->h, B), c = sparse_workspace_bytes(kernel->h, B);
+    if (b > need) need = b;
+    if (c > need) need = c;
+    *bytes = need + 256;
     return RDK_OK;
 }
 
@@ -341,7 +349,7 @@ rdk_status_t rdk_redistribute_exact(const rdk_kernel_t *kernel, const void *q, r
     rdk_workspace_bytes(kernel, B, &need);
     if (workspace_bytes < need) return RDK_ERR_WORKSPACE;
     RowInput qi{q, q_kind, ldq};
-    if (h.format == RDK_IDENTITY) return launch_sparse(h, qi, B, q_prime, ldo, workspace, (hipStream_t)stream);
+    if (h.format == RDK_IDENTITY) return launch_tli_scatter(h, qi, B, q_prime, ldo, workspace, (hipStream_t)stream);
     return launch_exact(h, qi, B, q_prime, ldo, workspace, (hipStream_t)stream);
 }
 
@@ -365,9 +373,10 @@ rdk_status_t rdk_redistribute_linear(const rdk_kernel_t *kernel, rdk_linear_mode
         rc = check_rows(p, p_kind, ldp, h.N);
         if (rc != RDK_OK) return rc;
         RowInput pi{p, p_kind, ldp};
-        return launch_taylor(h, pi, qi, B, q_prime, ldo, workspace, (hipStream_t)stream);
+        return launch_taylor(h, pi, qi, B, q_prime, ldo, workspace, nullptr, (hipStream_t)stream);
     }
     if (h.format != RDK_SPARSE_TOPK && h.format != RDK_IDENTITY) return RDK_ERR_UNSUPPORTED;
+    if (h.format == RDK_IDENTITY) return launch_tli_scatter(h, qi, B, q_prime, ldo, workspace, (hipStream_t)stream);
     return launch_sparse(h, qi, B, q_prime, ldo, workspace, (hipStream_t)stream);
 }
 
@@ -411,6 +420,52 @@ rdk_status_t rdk_verify_sample(const rdk_verify_desc_t *desc, const void *p, rdk
     RowInput pi{p, p_kind, ldp};
     return launch_verify(*desc, pi, q_prime, ldq, draft_ids, accept, alpha, resid_mass, resid_ids, n_accepted, out_tokens,
                          workspace, (hipStream_t)stream);
+}
+
+rdk_status_t rdk_redistribute_verify_workspace_bytes(const rdk_kernel_t *kernel, rdk_linear_mode_t mode,
+                                                     const rdk_verify_desc_t *desc, size_t *bytes)
+{
+    if (!kernel || !bytes) return RDK_ERR_NULL;
+    rdk_status_t rc = check_verify_desc(desc);
+    if (rc != RDK_OK) return rc;
+    const KernelHandle &h = kernel->h;
+    if (desc->N != h.N) return RDK_ERR_SHAPE;
+    if (mode == RDK_LINEAR_TAYLOR) *bytes = taylor_fused_workspace_bytes(h, desc->B) + 256;
+    else if (mode == RDK_LINEAR_SPARSE && h.format == RDK_SPARSE_TOPK && h.k > 0)
+        *bytes = sparse_fused_workspace_bytes(h, desc->B) + 256;
+    else return mode == RDK_LINEAR_SPARSE ? RDK_ERR_UNSUPPORTED : RDK_ERR_DTYPE;
+    return RDK_OK;
+}
+
+rdk_status_t rdk_redistribute_verify(const rdk_kernel_t *kernel, rdk_linear_mode_t mode, const rdk_verify_desc_t *desc,
+                                     const void *p, rdk_input_kind_t p_kind, int64_t ldp, const void *q,
+                                     rdk_input_kind_t q_kind, int64_t ldq, float *q_prime, int64_t ldo, int32_t *draft_ids,
+                                     uint8_t *accept, float *alpha, float *resid_mass, int32_t *resid_ids,
+                                     int32_t *n_accepted, int32_t *out_tokens, void *workspace, size_t workspace_bytes,
+                                     void *stream)
+{
+    size_t need = 0;
+    rdk_status_t rc = rdk_redistribute_verify_workspace_bytes(kernel, mode, desc, &need);
+    if (rc != RDK_OK) return rc;
+    const KernelHandle &h = kernel->h;
+    rc = check_rows(p, p_kind, ldp, h.N);
+    if (rc != RDK_OK) return rc;
+    rc = check_rows(q, q_kind, ldq, h.n);
+    if (rc != RDK_OK) return rc;
+    if (!draft_ids || !accept || !resid_ids || !workspace) return RDK_ERR_NULL;
+    if (q_prime && ldo < h.N) return RDK_ERR_SHAPE;
+    if (desc->gamma == 0 && (n_accepted || out_tokens)) return RDK_ERR_SHAPE;
+    if ((q_prime && !aligned16(q_prime)) || !aligned16(workspace)) return RDK_ERR_ALIGN;
+    if (workspace_bytes < need) return RDK_ERR_WORKSPACE;
+    FusedCall c{};
+    c.d = *desc;
+    c.p = RowInput{p, p_kind, ldp};
+    c.q = RowInput{q, q_kind, ldq};
+    c.q_prime = q_prime; c.ldo = ldo;
+    c.draft_ids = draft_ids; c.accept = accept; c.alpha = alpha; c.resid_mass = resid_mass;
+    c.resid_ids = resid_ids; c.n_accepted = n_accepted; c.out_tokens = out_tokens;
+    if (mode == RDK_LINEAR_TAYLOR) return launch_taylor(h, c.p, c.q, desc->B, q_prime, ldo, workspace, &c, (hipStream_t)stream);
+    return launch_sparse_fused(h, c, workspace, (hipStream_t)stream);
 }
 
 rdk_status_t rdk_timing_select(const char *kernel_name)

@@ -191,67 +191,49 @@ __global__ __launch_bounds__(256) void topk_kernel(const float *E, int d, const 
     }
 }
 
-// Normalise over the retained entries and lay the kernel out per target id: row j of the tables holds
-// kk (slot, weight) pairs; a kept id holds itself with its diagonal weight, the rest is padding.
-__global__ void sparse_finish_kernel(const int32_t *slot_of, int N, int k, int kk, const double *nbr_a, const int32_t *nbr_s,
-                                     const unsigned long long *zfix, int32_t *ell_idx, float *ell_w)
+// Normalise over the retained entries (Eq. 2 on the retained set).  Stored layout: per pruned slot u a
+// row of kk (kept slot, weight) pairs (the k real ones, then padding with slot 0 and weight 0), and
+// per kept slot its diagonal weight.
+__global__ void sparse_finish_kernel(int n_pruned, int n, int k, int kk, const double *nbr_a, const int32_t *nbr_s,
+                                     const unsigned long long *zfix, int2 *nbr, float *self_w)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (int64_t)N * kk) return;
-    const int j = (int)(t / kk), e = (int)(t % kk);
-    const int s = slot_of[j];
+    if (t < n) self_w[t] = (float)(1.0 / (1.0 + (double)zfix[t] / kFixScale));
+    if (t >= (int64_t)n_pruned * kk) return;
+    const int64_t u = t / kk;
+    const int e = (int)(t % kk);
     int idx = 0;
     float w = 0.f;
-    if (s >= 0) {
-        if (e == 0) {
-            idx = s;
-            w = (float)(1.0 / (1.0 + (double)zfix[s] / kFixScale));
-        }
-    } else if (e < k) {
-        const int64_t u = -s - 1;
+    if (e < k) {
         idx = nbr_s[u * k + e];
         w = (float)(nbr_a[u * k + e] / (1.0 + (double)zfix[idx] / kFixScale));
     }
-    ell_idx[t] = idx;
-    ell_w[t] = w;
+    nbr[t] = make_int2(idx, __float_as_int(w));
 }
 
-__global__ void sparse_import_kernel(const int32_t *slot_of, int N, int k, int kk, const int32_t *sp_idx, const float *sp_w,
-                                     const float *self_w, int32_t *ell_idx, float *ell_w)
+// Copy between the caller's [.., k] tables and the padded [.., kk] tables of the storage blob.
+__global__ void sparse_import_kernel(int n_pruned, int n, int k, int kk, const int32_t *sp_idx, const float *sp_w,
+                                     const float *sp_self, int2 *nbr, float *self_w)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (int64_t)N * kk) return;
-    const int j = (int)(t / kk), e = (int)(t % kk);
-    const int s = slot_of[j];
-    int idx = 0;
-    float w = 0.f;
-    if (s >= 0) {
-        if (e == 0) {
-            idx = s;
-            w = self_w[s];
-        }
-    } else if (e < k) {
-        const int64_t u = -s - 1;
-        idx = sp_idx[u * k + e];
-        w = sp_w[u * k + e];
-    }
-    ell_idx[t] = idx;
-    ell_w[t] = w;
+    if (t < n) self_w[t] = sp_self[t];
+    if (t >= (int64_t)n_pruned * kk) return;
+    const int64_t u = t / kk;
+    const int e = (int)(t % kk);
+    nbr[t] = make_int2(e < k ? sp_idx[u * k + e] : 0, __float_as_int(e < k ? sp_w[u * k + e] : 0.f));
 }
 
-__global__ void sparse_export_kernel(const int32_t *slot_of, int N, int k, int kk, const int32_t *ell_idx, const float *ell_w,
-                                     int32_t *sp_idx, float *sp_w, float *self_w)
+__global__ void sparse_export_kernel(int n_pruned, int n, int k, int kk, const int2 *nbr, const float *self_w,
+                                     int32_t *sp_idx, float *sp_w, float *sp_self)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (int64_t)N * kk) return;
-    const int j = (int)(t / kk), e = (int)(t % kk);
-    const int s = slot_of[j];
-    if (s >= 0) {
-        if (e == 0) self_w[s] = ell_w[t];
-    } else if (e < k) {
-        const int64_t u = -s - 1;
-        sp_idx[u * k + e] = ell_idx[t];
-        sp_w[u * k + e] = ell_w[t];
+    if (t < n) sp_self[t] = self_w[t];
+    if (t >= (int64_t)n_pruned * kk) return;
+    const int64_t u = t / kk;
+    const int e = (int)(t % kk);
+    if (e < k) {
+        sp_idx[u * k + e] = nbr[t].x;
+        sp_w[u * k + e] = __int_as_float(nbr[t].y);
     }
 }
 
@@ -315,14 +297,19 @@ __global__ void check_dense_kernel(const float *M, int64_t ldm, int N, int32_t *
     }
 }
 
-// Row sums of a sparse kernel: entry (idx, w) of any id adds w to row idx.
-__global__ void check_sparse_accum_kernel(const int32_t *ell_idx, const float *ell_w, int64_t count, int n,
+// Row sums of a sparse kernel: entry (idx, w) of a pruned id adds w to row idx; the diagonal adds self_w.
+__global__ void check_sparse_accum_kernel(const int2 *nbr, int64_t count, const float *self_w, int n,
                                           unsigned long long *zfix, int32_t *flag)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) {
+        const float sw = self_w[t];
+        if (!(sw >= 0.f)) atomicOr(flag, 1);
+        else atomicAdd(&zfix[t], (unsigned long long)((double)sw * kFixScale + 0.5));
+    }
     if (t >= count) return;
-    const float w = ell_w[t];
-    const int s = ell_idx[t];
+    const float w = __int_as_float(nbr[t].y);
+    const int s = nbr[t].x;
     if (!(w >= 0.f) || s < 0 || s >= n) {
         atomicOr(flag, 1);
         return;
@@ -360,8 +347,22 @@ rdk_status_t launch_check_kept(const int32_t *kept_ids, int32_t n, int32_t N, in
     return RDK_OK;
 }
 
-rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *slot_of, int32_t *ell_idx, float *ell_w,
-                                 int32_t kk, void *ws, hipStream_t st)
+rdk_status_t launch_pruned_ids(const int32_t *slot_of, int32_t N, int32_t *pruned_ids, hipStream_t st)
+{
+    hipLaunchKernelGGL(pruned_ids_kernel, dim3((N + 255) / 256), dim3(256), 0, st, slot_of, N, pruned_ids);
+    RDK_LAUNCH_CHECK("pruned_ids_kernel");
+    return RDK_OK;
+}
+
+static unsigned table_blocks(int n_pruned, int kk, int n)
+{
+    int64_t count = (int64_t)n_pruned * kk;
+    if (count < n) count = n;
+    return (unsigned)((count + 255) / 256);
+}
+
+rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *pruned_ids, int2 *nbr, float *self_w, int32_t kk,
+                                 void *ws, hipStream_t st)
 {
     BuildWs w = carve(d, ws);
     const int np = d.N - d.n;
@@ -370,36 +371,32 @@ rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *slot
     if (d.k > 0 && np > 0) {
         hipLaunchKernelGGL(inv_norm_kernel, dim3((d.N + 3) / 4), dim3(256), 0, st, d.embeddings, d.N, d.d, w.inv_norm);
         RDK_LAUNCH_CHECK("inv_norm_kernel");
-        hipLaunchKernelGGL(pruned_ids_kernel, dim3((d.N + 255) / 256), dim3(256), 0, st, slot_of, d.N, w.pruned_ids);
-        RDK_LAUNCH_CHECK("pruned_ids_kernel");
         const size_t dyn = (size_t)kTile * d.k * (sizeof(double) + sizeof(int32_t));
         RDK_HIP(hipFuncSetAttribute((const void *)topk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn));
         hipLaunchKernelGGL(topk_kernel, dim3((np + kTile - 1) / kTile), dim3(256), dyn, st, d.embeddings, d.d, w.inv_norm,
-                           w.pruned_ids, np, d.kept_ids, d.n, d.k, 1.0 / (double)d.tau, w.nbr_a, w.nbr_s, w.zfix);
+                           pruned_ids, np, d.kept_ids, d.n, d.k, 1.0 / (double)d.tau, w.nbr_a, w.nbr_s, w.zfix);
         RDK_LAUNCH_CHECK("topk_kernel");
     }
-    const int64_t count = (int64_t)d.N * kk;
-    hipLaunchKernelGGL(sparse_finish_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, slot_of, d.N, d.k, kk,
-                       w.nbr_a, w.nbr_s, w.zfix, ell_idx, ell_w);
+    hipLaunchKernelGGL(sparse_finish_kernel, dim3(table_blocks(np, kk, d.n)), dim3(256), 0, st, np, d.n, d.k, kk, w.nbr_a,
+                       w.nbr_s, w.zfix, nbr, self_w);
     RDK_LAUNCH_CHECK("sparse_finish_kernel");
     return RDK_OK;
 }
 
-rdk_status_t launch_import_sparse(const rdk_kernel_desc_t &d, const int32_t *slot_of, int32_t *ell_idx, float *ell_w,
-                                  int32_t kk, hipStream_t st)
+rdk_status_t launch_import_sparse(const rdk_kernel_desc_t &d, int2 *nbr, float *self_w, int32_t kk, hipStream_t st)
 {
-    const int64_t count = (int64_t)d.N * kk;
-    hipLaunchKernelGGL(sparse_import_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, slot_of, d.N, d.k, kk,
-                       d.sparse_idx, d.sparse_w, d.self_w, ell_idx, ell_w);
+    const int np = d.N - d.n;
+    hipLaunchKernelGGL(sparse_import_kernel, dim3(table_blocks(np, kk, d.n)), dim3(256), 0, st, np, d.n, d.k, kk,
+                       d.sparse_idx, d.sparse_w, d.self_w, nbr, self_w);
     RDK_LAUNCH_CHECK("sparse_import_kernel");
     return RDK_OK;
 }
 
 rdk_status_t launch_export_sparse(const KernelHandle &h, int32_t *idx, float *w, float *self_w, hipStream_t st)
 {
-    const int64_t count = (int64_t)h.N * h.kk;
-    hipLaunchKernelGGL(sparse_export_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, h.slot_of, h.N, h.k,
-                       h.kk, h.ell_idx, h.ell_w, idx, w, self_w);
+    const int np = h.N - h.n;
+    hipLaunchKernelGGL(sparse_export_kernel, dim3(table_blocks(np, h.kk, h.n)), dim3(256), 0, st, np, h.n, h.k, h.kk,
+                       h.nbr, h.self_w, idx, w, self_w);
     RDK_LAUNCH_CHECK("sparse_export_kernel");
     return RDK_OK;
 }
@@ -428,11 +425,11 @@ rdk_status_t launch_check_stochastic_dense(const float *M, int64_t ldm, int32_t 
 rdk_status_t launch_check_stochastic_sparse(const KernelHandle &h, void *ws, int32_t *flag, hipStream_t st)
 {
     unsigned long long *zfix = (unsigned long long *)ws;
+    const int np = h.N - h.n;
     hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, st, flag);
     hipLaunchKernelGGL(fill_zero_kernel, dim3((h.n + 255) / 256), dim3(256), 0, st, zfix, (int64_t)h.n);
-    const int64_t count = (int64_t)h.N * h.kk;
-    hipLaunchKernelGGL(check_sparse_accum_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, h.ell_idx, h.ell_w,
-                       count, h.n, zfix, flag);
+    hipLaunchKernelGGL(check_sparse_accum_kernel, dim3(table_blocks(np, h.kk, h.n)), dim3(256), 0, st, h.nbr, (int64_t)np * h.kk,
+                       h.self_w, h.n, zfix, flag);
     hipLaunchKernelGGL(check_sparse_rows_kernel, dim3((h.n + 255) / 256), dim3(256), 0, st, zfix, h.n, flag);
     RDK_LAUNCH_CHECK("check_sparse_rows_kernel");
     return RDK_OK;

@@ -17,10 +17,11 @@ struct KernelHandle {
     rdk_kernel_format_t format;
     const int32_t *kept_ids;  // [n]
     const int32_t *slot_of;   // [N]  >= 0: kept slot;  < 0: -(pruned slot + 1)
-    // sparse: one row of k (slot, weight) pairs per TARGET id (kept ids: themselves, then zero weights)
-    const int32_t *ell_idx;   // [N, kk]
-    const float *ell_w;       // [N, kk]
-    int32_t kk;               // row length of the two tables: max(k, 1) rounded up to a multiple of 4
+    // sparse: per pruned slot a row of kk (kept slot, weight) pairs, k real ones then (0, 0) padding
+    const int32_t *pruned_ids;  // [N-n] ascending target ids that are not kept
+    const int2 *nbr;            // [N-n, kk] pairs (kept slot, weight as fp32 bits): one 128-byte line per 16 entries
+    const float *self_w;        // [n] diagonal weights
+    int32_t kk;                 // row length of the two tables: k rounded up to a multiple of 16
     // dense fp32
     const float *dense;       // [n, ldm]
     int64_t ldm;
@@ -47,6 +48,24 @@ rdk_status_t hip_fail(hipError_t e, const char *what);
         if (e_ != hipSuccess) return ::rdk::hip_fail(e_, name);         \
     } while (0)
 
+struct RowInput {            // a [B, len] input of some kind
+    const void *ptr;
+    rdk_input_kind_t kind;
+    int64_t ld;
+};
+
+// One fused redistribute + verify call: inputs, the optional q' output, and the verification outputs.
+struct FusedCall {
+    rdk_verify_desc_t d;
+    RowInput p, q;
+    float *q_prime;      // may be NULL: q' is then never written
+    int64_t ldo;
+    int32_t *draft_ids;
+    uint8_t *accept;
+    float *alpha, *resid_mass;
+    int32_t *resid_ids, *n_accepted, *out_tokens;
+};
+
 // Brackets one kernel launch with HIP events when that kernel has been selected through
 // rdk_timing_select(); otherwise it does nothing.  Declare it in the scope of the launch.
 struct TimedLaunch {
@@ -58,20 +77,14 @@ struct TimedLaunch {
 
 // ---- launchers implemented in the kernel translation units (all enqueue on `st`, none synchronises)
 
-struct RowInput {            // a [B, len] input of some kind
-    const void *ptr;
-    rdk_input_kind_t kind;
-    int64_t ld;
-};
-
 // rdk_build.hip
 size_t build_workspace_bytes(const rdk_kernel_desc_t &d);
 rdk_status_t launch_slot_of(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *slot_of, hipStream_t st);
 rdk_status_t launch_check_kept(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *flag, hipStream_t st);
-rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *slot_of, int32_t *ell_idx,
-                                 float *ell_w, int32_t kk, void *ws, hipStream_t st);
-rdk_status_t launch_import_sparse(const rdk_kernel_desc_t &d, const int32_t *slot_of, int32_t *ell_idx,
-                                  float *ell_w, int32_t kk, hipStream_t st);
+rdk_status_t launch_pruned_ids(const int32_t *slot_of, int32_t N, int32_t *pruned_ids, hipStream_t st);
+rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *pruned_ids, int2 *nbr, float *self_w,
+                                 int32_t kk, void *ws, hipStream_t st);
+rdk_status_t launch_import_sparse(const rdk_kernel_desc_t &d, int2 *nbr, float *self_w, int32_t kk, hipStream_t st);
 rdk_status_t launch_export_sparse(const KernelHandle &h, int32_t *idx, float *w, float *self_w, hipStream_t st);
 rdk_status_t launch_build_dense(const rdk_kernel_desc_t &d, float *M, int64_t ldm, void *ws, hipStream_t st);
 rdk_status_t launch_check_stochastic_dense(const float *M, int64_t ldm, int32_t n, int32_t N, int32_t *flag,
@@ -79,9 +92,18 @@ rdk_status_t launch_check_stochastic_dense(const float *M, int64_t ldm, int32_t 
 rdk_status_t launch_check_stochastic_sparse(const KernelHandle &h, void *ws, int32_t *flag, hipStream_t st);
 
 // rdk_linear.hip
-size_t linear_workspace_bytes(const KernelHandle &h, int32_t B);
+size_t taylor_workspace_bytes(const KernelHandle &h, int32_t B);
+size_t taylor_fused_workspace_bytes(const KernelHandle &h, int32_t B);
+// c == NULL: Eq. 3 into `out`; else the fused redistribute + verify call (out may then be NULL)
 rdk_status_t launch_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B, float *out, int64_t ldo,
-                           void *ws, hipStream_t st);
+                           void *ws, const FusedCall *c, hipStream_t st);
+rdk_status_t launch_tli_scatter(const KernelHandle &h, RowInput q, int32_t B, float *out, int64_t ldo, void *ws,
+                                hipStream_t st);
+
+// rdk_sparse.hip
+size_t sparse_workspace_bytes(const KernelHandle &h, int32_t B);
+size_t sparse_fused_workspace_bytes(const KernelHandle &h, int32_t B);
+rdk_status_t launch_sparse_fused(const KernelHandle &h, const FusedCall &c, void *ws, hipStream_t st);
 rdk_status_t launch_sparse(const KernelHandle &h, RowInput q, int32_t B, float *out, int64_t ldo, void *ws,
                            hipStream_t st);
 

@@ -1,0 +1,257 @@
+// Per-row finish of the verification step (Alg. 4, steps 2 and 4-10), shared by the stand-alone
+// verify call and by the fused redistribute+verify calls.
+//
+// Input: for every row three partial sums per block of SUB*256 ids (sum q', sum max(0, p - q'),
+// sum min(p, q')), written by a streaming pass.  One wavefront per row then
+//   1. adds the partials in fp64 (alpha, residual mass, sum q'), draws the Philox uniforms,
+//   2. finds the blocks in which the two inverse-CDF thresholds are crossed,
+//   3. re-reads (or re-computes) those blocks and scans them in fp64 for the exact ids,
+//   4. decides acceptance in fp64, and, when a workgroup holds one whole sequence, runs the
+//      first-rejection scan.
+// Where q' comes from is the `QP` policy: memory (a materialised q' row) or a formula.
+#pragma once
+#include "rdk_rowstats.hpp"
+
+namespace rdk {
+
+struct FinalizeArgs {
+    rdk_verify_desc_t d;
+    const void *p;
+    int64_t ldp;
+    bool vec_p;
+    const SoftStat *pstat;   // [B, p_splits] (logit p only)
+    int p_splits;
+    const float *part_q, *part_r, *part_a;   // [B, nblk]
+    int nblk;
+    int rows_per_block;
+    bool scan_here;
+    int32_t *draft_ids;
+    uint8_t *accept;
+    float *alpha, *resid_mass;
+    int32_t *resid_ids, *n_accepted, *out_tokens;
+};
+
+// q' read back from memory.
+struct QpMemory {
+    static constexpr bool kSpreadRows = false;
+    const float *q;
+    int64_t ldq;
+    bool vec;
+    int N;
+    struct Row {
+        const float *qr;
+        bool vec;
+        int N;
+        __device__ __forceinline__ float4 load4(int64_t idx) const { return rdk::load4<RDK_PROB_F32>(qr, idx, N, vec, 0.f); }
+        __device__ __forceinline__ float load1(int j) const { return qr[j]; }
+    };
+    __device__ __forceinline__ Row row(int64_t b) const { return Row{q + b * ldq, vec, N}; }
+};
+
+__device__ __forceinline__ double lane_partial_sum(const float *part, int nblk, int per_lane)
+{
+    const int c0 = lane_id() * per_lane;
+    double s = 0.0;
+    for (int t = 0; t < per_lane; ++t)
+        if (c0 + t < nblk) s += (double)part[c0 + t];
+    return s;
+}
+
+// Block in which the inclusive prefix of `part` first exceeds thr (-1 if none) and the prefix before it.
+// Lane l owns the per_lane consecutive blocks from l * per_lane.
+__device__ __forceinline__ int locate_block(const float *part, int nblk, int per_lane, double lane_sum, double thr,
+                                            double &prefix_before)
+{
+    const double incl = wave_inclusive_scan(lane_sum);
+    const unsigned long long hits = __ballot(incl > thr);
+    if (hits == 0ull) return -1;
+    const int src = __ffsll(hits) - 1;
+    int blk = -1;
+    double pre = incl - lane_sum;
+    if (lane_id() == src) {
+        const int c0 = src * per_lane;
+        for (int t = 0; t < per_lane && c0 + t < nblk; ++t) {
+            const double v = (double)part[c0 + t];
+            if (pre + v > thr) {
+                blk = c0 + t;
+                break;
+            }
+            pre += v;
+        }
+    }
+    blk = __shfl(blk, src, kWave);
+    prefix_before = __shfl(pre, src, kWave);
+    return blk;
+}
+
+// Smallest id of the block whose inclusive prefix of weights exceeds thr_local; if rounding leaves none,
+// the last id of the block with a positive weight.  wv[i] = weights of ids base + i*256 + lane*4 .. +3.
+template <int SUB>
+__device__ __forceinline__ int search_block(const float4 (&wv)[SUB], int base, double thr_local)
+{
+    const int lane = lane_id();
+    double carried = 0.0;
+    int last_positive = -1;
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) {
+        const int idx = base + i * 256 + lane * 4;
+        const double l0 = (double)wv[i].x, l1 = l0 + (double)wv[i].y, l2 = l1 + (double)wv[i].z, l3 = l2 + (double)wv[i].w;
+        const double incl = wave_inclusive_scan(l3);
+        const double excl = carried + (incl - l3);
+        const unsigned long long hits = __ballot(excl + l3 > thr_local);
+        if (hits != 0ull) {
+            const int src = __ffsll(hits) - 1;
+            const int e = (excl + l0 > thr_local) ? 0 : (excl + l1 > thr_local) ? 1 : (excl + l2 > thr_local) ? 2 : 3;
+            return __shfl(idx + e, src, kWave);
+        }
+        const int mine = wv[i].w > 0.f ? 3 : wv[i].z > 0.f ? 2 : wv[i].y > 0.f ? 1 : wv[i].x > 0.f ? 0 : -1;
+        const unsigned long long pos = __ballot(mine >= 0);
+        if (pos != 0ull) {
+            const int src = 63 - __clzll(pos);
+            last_positive = __shfl(idx + mine, src, kWave);
+        }
+        carried += __shfl(incl, kWave - 1, kWave);
+    }
+    return last_positive;
+}
+
+constexpr int kFinalizeRows = 8;   // rows (wavefronts) per workgroup at most: leaves 256 VGPRs per lane
+
+template <int KIND, int SUB, bool HAS_Q, class QP>
+__global__ __launch_bounds__(kFinalizeRows * kWave) void verify_finalize_kernel(FinalizeArgs a, QP qp)
+{
+    __shared__ int32_t sh_draft[kFinalizeRows], sh_resid[kFinalizeRows];
+    __shared__ uint8_t sh_acc[kFinalizeRows];
+    const rdk_verify_desc_t &d = a.d;
+    const int wid = threadIdx.x / kWave, lane = lane_id();
+    const int64_t row = (int64_t)blockIdx.x * a.rows_per_block + wid;
+    const int N = d.N;
+    if (row < d.B) {
+        const void *pr = row_ptr<KIND>(a.p, a.ldp, row);
+        float m = 0.f, inv = 1.f;
+        if (KIND != RDK_PROB_F32) {
+            const SoftStat rs = merged_row_stat<KIND>(a.pstat, a.p_splits, row);
+            m = rs.m;
+            inv = 1.0f / rs.s;
+        }
+        const float pfill = KIND == RDK_PROB_F32 ? 0.f : -INFINITY;
+        const int per_lane = (a.nblk + kWave - 1) / kWave;
+        const float *pq = a.part_q + row * a.nblk;
+        const float *prr = a.part_r + row * a.nblk;
+        const float *pa = a.part_a + row * a.nblk;
+        const bool draw_draft = HAS_Q && d.sample_draft;
+        const typename QP::Row qrow = qp.row(row);
+
+        // 1. block partials (one round trip), uniforms meanwhile
+        const double lane_r = lane_partial_sum(prr, a.nblk, per_lane);
+        const double lane_q = draw_draft ? lane_partial_sum(pq, a.nblk, per_lane) : 0.0;
+        const double lane_a = HAS_Q ? lane_partial_sum(pa, a.nblk, per_lane) : 0.0;
+        int32_t dtok = (HAS_Q && !d.sample_draft) ? a.draft_ids[row] : -1;
+        uint32_t words[4];
+        position_words(d.seed, d.offset + (uint64_t)row, words);
+        const double R = wave_sum(lane_r);
+        const double Q = draw_draft ? wave_sum(lane_q) : 0.0;
+        const double A = HAS_Q ? wave_sum(lane_a) : 0.0;
+
+        // 2. the blocks that hold the two prefix-sum crossings
+        double thr_d = 0.0, thr_r = 0.0, before_d = 0.0, before_r = 0.0;
+        int blk_d = -1, blk_r = -1;
+        if (draw_draft && Q > 0.0) {
+            thr_d = word_to_unit(words[0]) * Q;
+            blk_d = locate_block(pq, a.nblk, per_lane, lane_q, thr_d, before_d);
+        }
+        if (R > 0.0) {
+            thr_r = word_to_unit(words[HAS_Q ? 2 : 3]) * R;
+            blk_r = locate_block(prr, a.nblk, per_lane, lane_r, thr_r, before_r);
+        }
+
+        // 3. both blocks are fetched together, then scanned
+        float4 wd[SUB], wp[SUB], wq[SUB];
+        const int base_d = max(blk_d, 0) * (SUB * 256), base_r = max(blk_r, 0) * (SUB * 256);
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+            if (draw_draft) wd[i] = qrow.load4(base_d + i * 256 + lane * 4);
+            wp[i] = load4<KIND>(pr, base_r + i * 256 + lane * 4, N, a.vec_p, pfill);
+            if (HAS_Q) wq[i] = (blk_r == blk_d && draw_draft) ? wd[i] : qrow.load4(base_r + i * 256 + lane * 4);
+        }
+        if (blk_d >= 0) dtok = search_block<SUB>(wd, base_d, thr_d - before_d);
+        // 4. the accept test needs p and q' at the draft token: issue those loads before the second scan
+        float pd_raw = 0.f, qd = 0.f;
+        const bool d_ok = HAS_Q && dtok >= 0 && dtok < N;
+        if (d_ok) {
+            pd_raw = load1<KIND>(pr, dtok);
+            qd = qrow.load1(dtok);
+        }
+        int32_t rtok = -1;
+        if (blk_r >= 0) {
+#pragma unroll
+            for (int i = 0; i < SUB; ++i) {
+                wp[i].x = to_weight<KIND>(wp[i].x, m, inv);
+                wp[i].y = to_weight<KIND>(wp[i].y, m, inv);
+                wp[i].z = to_weight<KIND>(wp[i].z, m, inv);
+                wp[i].w = to_weight<KIND>(wp[i].w, m, inv);
+                if (HAS_Q) {
+                    wp[i].x = fmaxf(wp[i].x - wq[i].x, 0.f);
+                    wp[i].y = fmaxf(wp[i].y - wq[i].y, 0.f);
+                    wp[i].z = fmaxf(wp[i].z - wq[i].z, 0.f);
+                    wp[i].w = fmaxf(wp[i].w - wq[i].w, 0.f);
+                }
+            }
+            rtok = search_block<SUB>(wp, base_r, thr_r - before_r);
+        }
+        uint8_t acc = 0;
+        if (d_ok) acc = (word_to_unit(words[1]) * (double)qd < (double)to_weight<KIND>(pd_raw, m, inv)) ? 1 : 0;
+        if (lane == 0) {
+            if (draw_draft) a.draft_ids[row] = dtok;
+            a.accept[row] = acc;
+            if (a.alpha) a.alpha[row] = (float)A;
+            if (a.resid_mass) a.resid_mass[row] = (float)R;
+            a.resid_ids[row] = rtok;
+            if (a.scan_here) {
+                sh_draft[wid] = dtok;
+                sh_resid[wid] = rtok;
+                sh_acc[wid] = acc;
+            }
+        }
+    }
+    if (a.scan_here) {  // the workgroup holds exactly one sequence: steps 4-10 of Alg. 4
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int g = d.gamma;
+            int j = 0;
+            while (j < g && sh_acc[j]) ++j;
+            if (a.n_accepted) a.n_accepted[blockIdx.x] = j;
+            if (a.out_tokens) {
+                int32_t *o = a.out_tokens + (int64_t)blockIdx.x * (g + 1);
+                for (int i = 0; i <= g; ++i) o[i] = i < j ? sh_draft[i] : (i == j && j < g) ? sh_resid[i] : -1;
+            }
+        }
+    }
+}
+
+// Per-sequence scan as a launch of its own (sequences longer than one workgroup's wavefronts).
+__global__ void sequence_scan_kernel(int S, int gamma, const int32_t *draft_ids, const uint8_t *accept,
+                                     const int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens);
+
+rdk_status_t launch_sequence_scan(const rdk_verify_desc_t &d, const int32_t *draft_ids, const uint8_t *accept,
+                                  const int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens, hipStream_t st);
+
+template <int KIND, int SUB, bool HAS_Q, class QP>
+rdk_status_t launch_finalize(FinalizeArgs a, QP qp, hipStream_t st)
+{
+    const rdk_verify_desc_t &d = a.d;
+    // a policy that re-computes q' is heavy on the vector memory pipe of its CU: give every row a CU of its own
+    a.scan_here = d.gamma >= 1 && d.gamma <= kFinalizeRows && !QP::kSpreadRows;
+    a.rows_per_block = a.scan_here ? d.gamma : (QP::kSpreadRows ? 1 : 4);
+    const int blocks = (d.B + a.rows_per_block - 1) / a.rows_per_block;
+    {
+        TimedLaunch timed("verify_finalize_kernel", st);
+        hipLaunchKernelGGL((verify_finalize_kernel<KIND, SUB, HAS_Q, QP>), dim3(blocks), dim3(a.rows_per_block * kWave), 0, st, a, qp);
+    }
+    RDK_LAUNCH_CHECK("verify_finalize_kernel");
+    if (d.gamma > 0 && !a.scan_here && (a.n_accepted || a.out_tokens))
+        return launch_sequence_scan(d, a.draft_ids, a.accept, a.resid_ids, a.n_accepted, a.out_tokens, st);
+    return RDK_OK;
+}
+
+}  // namespace rdk

@@ -1,0 +1,550 @@
+// Alg. 1, step 2 with the top-k sparse kernel:  q'[b, j] = sum_t w[j, t] * TLI(q)[b, slot[j, t]]  for a
+// pruned id j,  q'[b, j] = self_w[s] * TLI(q)[b, s]  for a kept id j (slot s).
+//
+// The product costs (N - n) * k gathered multiply-adds per position, an order of magnitude more
+// cache traffic than its compulsory HBM bytes, so everything here is arranged around the gather:
+//   * the drafter rows are first laid out position-minor, 32 positions side by side
+//     (qT[pb][slot][32]); one neighbour of one id is then ONE 128-byte cache line that serves 32
+//     positions (the vector L1 of a CU spends about 2.4 clocks per distinct line, whatever part of the
+//     line is used);
+//   * a workgroup owns 256 consecutive target ids x 32 positions; its pruned ids and kept ids are
+//     contiguous runs of pruned slots / kept slots, handled separately (16 gathers vs one coalesced read);
+//   * workgroups are numbered so that each XCD sweeps all id tiles of one position block before moving
+//     on: the 4 MB slab of that block stays in the XCD's own L2;
+//   * results are staged in LDS and leave as full 1 KB row segments.
+#include "rdk_finalize.hpp"
+
+namespace rdk {
+
+namespace {
+
+constexpr int kThreads = 512;     // product kernel: 8 wavefronts share one staged tile
+constexpr int kWaves = kThreads / kWave;
+constexpr int kPrepThreads = 256; // transposition kernel
+constexpr int kPosBlock = 32;    // positions per gather: 32 fp32 = one 128-byte line
+constexpr int kTileIds = 256;    // target ids per workgroup
+constexpr int kStageLd = kTileIds + 1;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+struct SparseWs {
+    SoftStat *qpart;   // [B, q_splits]  drafter row statistics, a few partials per row
+    float *zinv;       // [ceil(B/32) * 32]  1 / drafter row sum (Eq. 1), 0 for padding positions
+    float *qT;         // [ceil(B/32), n, 32]
+    int q_splits;
+};
+
+SparseWs carve(const KernelHandle &h, int32_t B, void *ws)
+{
+    SparseWs w;
+    w.q_splits = row_splits(B, h.n, kPrepThreads / kWave);
+    char *p = (char *)ws;
+    w.qpart = (SoftStat *)p; p += align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256);
+    w.zinv = (float *)p; p += align_up((size_t)(B + kPosBlock) * sizeof(float), 256);
+    w.qT = (float *)p;
+    return w;
+}
+
+// Sum over the 8 lanes of an aligned group.
+__device__ __forceinline__ float oct_sum(float v)
+{
+    v += __shfl_xor(v, 1, kWave);
+    v += __shfl_xor(v, 2, kWave);
+    v += __shfl_xor(v, 4, kWave);
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// qT[(pb * n + s) * 32 + r] = weight(q[pb*32 + r, s]); zero for positions beyond B.  weight = the raw
+// probability, or exp(z - row max) for logits; the division by the row sum (Eq. 1) happens in the product.
+template <int QK>
+__global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q, int64_t ldq, int n, int B,
+                                                                   const SoftStat *qpart, int q_splits, bool vec, float *zinv,
+                                                                   float *qT)
+{
+    __shared__ float tile[64][kPosBlock + 1];
+    __shared__ float rowmax[kPosBlock];
+    const int pb = blockIdx.y;
+    const int s0 = blockIdx.x * 64;
+    const int r = threadIdx.x / 8, part = threadIdx.x % 8;     // 8 threads per position
+    const int64_t b = (int64_t)pb * kPosBlock + r;
+    if (QK != RDK_PROB_F32 || blockIdx.x == 0) {
+        // row maximum (logits) and, in the first slot tile, 1 / row sum for the product kernel: partial sums of
+        // logits are relative to each partial's own maximum and are brought to the row maximum first
+        float m = QK == RDK_PROB_F32 ? 0.f : -INFINITY;
+        if (QK != RDK_PROB_F32) {
+            if (b < B)
+                for (int i = part; i < q_splits; i += 8) m = fmaxf(m, qpart[b * q_splits + i].m);
+            m = fmaxf(m, __shfl_xor(m, 1, kWave));
+            m = fmaxf(m, __shfl_xor(m, 2, kWave));
+            m = fmaxf(m, __shfl_xor(m, 4, kWave));
+            if (part == 0) rowmax[r] = m;
+        }
+        if (blockIdx.x == 0) {
+            float z = 0.f;
+            if (b < B)
+                for (int i = part; i < q_splits; i += 8) {
+                    const SoftStat st = qpart[b * q_splits + i];
+                    if (st.s > 0.f) z += QK == RDK_PROB_F32 ? st.s : st.s * expf(st.m - m);
+                }
+            z = oct_sum(z);
+            if (part == 0) zinv[b] = (b < B && z > 0.f) ? 1.0f / z : 0.f;
+        }
+        if (QK != RDK_PROB_F32) __syncthreads();
+    }
+    {   // read 32 rows x 64 slots: 8 threads per row, 8 consecutive slots each
+        const int c8 = part * 8;
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = 0.f;
+        if (b < B) {
+            const void *qr = row_ptr<QK>(q, ldq, b);
+            const float qm = QK == RDK_PROB_F32 ? 0.f : rowmax[r];
+            const float4 a0 = load4<QK>(qr, s0 + c8, n, vec, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
+            const float4 a1 = load4<QK>(qr, s0 + c8 + 4, n, vec, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
+            const float raw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = to_weight<QK>(raw[e], qm, 1.f);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tile[c8 + e][r] = v[e];
+    }
+    __syncthreads();
+    {   // write 64 slots x 32 positions: 4 threads per slot, 8 positions each
+        const int sl = threadIdx.x / 4, pq = (threadIdx.x % 4) * 8;
+        if (s0 + sl < n) {
+            float *dst = qT + ((int64_t)pb * n + s0 + sl) * kPosBlock + pq;
+            *(float4 *)dst = make_float4(tile[sl][pq], tile[sl][pq + 1], tile[sl][pq + 2], tile[sl][pq + 3]);
+            *(float4 *)(dst + 4) = make_float4(tile[sl][pq + 4], tile[sl][pq + 5], tile[sl][pq + 6], tile[sl][pq + 7]);
+        }
+    }
+}
+
+// Broadcast within each group of four lanes: every lane receives the value held by lane `SRC` of its group.
+template <int SRC>
+__device__ __forceinline__ int quad_bcast(int v)
+{
+    return __builtin_amdgcn_mov_dpp(v, SRC * 0x55, 0xf, 0xf, true);
+}
+
+struct SparseArgs {
+    const int32_t *slot_of, *pruned_ids, *kept_ids;
+    const int2 *nbr;
+    const float *self_w;
+    int kk;
+    const float *qT;
+    const float *zinv;
+    int N, n, B;
+    int tiles, per_xcd, total_work;
+    float *out;
+    int64_t ldo;
+    bool vec_o;
+};
+
+// Number of pruned ids below target id j (j may be N).
+__device__ __forceinline__ int pruned_below(const int32_t *slot_of, int j, int N, int n)
+{
+    if (j >= N) return N - n;
+    const int s = slot_of[j];
+    return s < 0 ? -s - 1 : j - s;
+}
+
+// The product for one workgroup tile, left in `stage[position][id - j0]` (already divided by the row
+// sums).  Lane layout of a wavefront: lane = 8 * i + o; i = id within a group of 8, o = which four of
+// the 32 positions.  One 128-byte line holds the 16 (slot, weight) pairs of a round: lane o of an id's
+// group fetches pairs 2o and 2o+1, and the pairs go round the group through the swizzle crossbar.
+// The kernel is bound by the latency of its dependent loads, so the next line of pairs is requested
+// before the current gathers are issued, and registers are kept low enough for 6-8 wavefronts per SIMD.
+__device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0, float (*stage)[kStageLd])
+{
+    const int wid = threadIdx.x / kWave, lane = lane_id();
+    const int o = lane & 7, i = lane >> 3;
+    const int j1 = min(a.N, j0 + kTileIds);
+    const int u_lo = pruned_below(a.slot_of, j0, a.N, a.n), u_hi = pruned_below(a.slot_of, j1, a.N, a.n);
+    const int s_lo = j0 - u_lo, s_hi = j1 - u_hi;
+    const float4 inv_z = *(const float4 *)(a.zinv + pb * kPosBlock + o * 4);
+    const float *qslab = a.qT + (int64_t)pb * a.n * kPosBlock + o * 4;
+    const int rounds = a.kk / 16;
+    const int2 *nbr_lane = a.nbr + 2 * o;
+
+    // pruned ids of the tile: pruned slots [u_lo, u_hi), 8 per wavefront step
+    int u0 = u_lo + wid * 8;
+    i32x4 ev_next = {0, 0, 0, 0};
+    if (u0 < u_hi) ev_next = *(const i32x4 *)(nbr_lane + (int64_t)min(u0 + i, u_hi - 1) * a.kk);
+    for (; u0 < u_hi; u0 += 8 * kWaves) {
+        const int u = u0 + i;
+        const bool valid = u < u_hi;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int rd = 0; rd < rounds; ++rd) {
+            const i32x4 ev = ev_next;
+            {   // request the pairs of the next round (or of the next step) now
+                const bool more = rd + 1 < rounds;
+                const int un = more ? u0 : u0 + 8 * kWaves;
+                if (un < u_hi) ev_next = *(const i32x4 *)(nbr_lane + (int64_t)min(un + i, u_hi - 1) * a.kk + (more ? (rd + 1) * 16 : 0));
+            }
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                float4 g[8];
+                float wt[8];
+#define RDK_GATHER(T)                                                                                                       \
+    {                                                                                                                       \
+        const int src_ = (half * 4 + ((T) >> 1)) << 5 | 0x18;                                                               \
+        const int s_ = half ? __builtin_amdgcn_ds_swizzle(ev[2 * ((T) & 1)], ((4 + ((T) >> 1)) << 5) | 0x18)                \
+                            : __builtin_amdgcn_ds_swizzle(ev[2 * ((T) & 1)], (((T) >> 1) << 5) | 0x18);                     \
+        wt[T] = __int_as_float(half ? __builtin_amdgcn_ds_swizzle(ev[2 * ((T) & 1) + 1], ((4 + ((T) >> 1)) << 5) | 0x18)    \
+                                    : __builtin_amdgcn_ds_swizzle(ev[2 * ((T) & 1) + 1], (((T) >> 1) << 5) | 0x18));        \
+        (void)src_;                                                                                                         \
+        g[T] = *(const float4 *)(qslab + (int64_t)s_ * kPosBlock);                                                          \
+    }
+                RDK_GATHER(0) RDK_GATHER(1) RDK_GATHER(2) RDK_GATHER(3) RDK_GATHER(4) RDK_GATHER(5) RDK_GATHER(6) RDK_GATHER(7)
+#undef RDK_GATHER
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    acc.x += wt[t] * g[t].x; acc.y += wt[t] * g[t].y; acc.z += wt[t] * g[t].z; acc.w += wt[t] * g[t].w;
+                }
+            }
+        }
+        if (valid) {
+            const int c = a.pruned_ids[u] - j0;
+            stage[o * 4 + 0][c] = acc.x * inv_z.x;
+            stage[o * 4 + 1][c] = acc.y * inv_z.y;
+            stage[o * 4 + 2][c] = acc.z * inv_z.z;
+            stage[o * 4 + 3][c] = acc.w * inv_z.w;
+        }
+    }
+    // kept ids of the tile: kept slots [s_lo, s_hi) are consecutive rows of the slab
+    for (int sb = s_lo + wid * 8; sb < s_hi; sb += 8 * kWaves) {
+        const int s = sb + i;
+        if (s < s_hi) {
+            const float sw = a.self_w[s];
+            const float4 g = *(const float4 *)(qslab + (int64_t)s * kPosBlock);
+            const int c = a.kept_ids[s] - j0;
+            stage[o * 4 + 0][c] = sw * g.x * inv_z.x;
+            stage[o * 4 + 1][c] = sw * g.y * inv_z.y;
+            stage[o * 4 + 2][c] = sw * g.z * inv_z.z;
+            stage[o * 4 + 3][c] = sw * g.w * inv_z.w;
+        }
+    }
+    __syncthreads();
+}
+
+// Consecutive workgroup ids go to consecutive XCDs; give each XCD one contiguous share of the
+// (position block major, id tile minor) work list.
+__device__ __forceinline__ bool xcd_work(const SparseArgs &a, int &pb, int &tile)
+{
+    const int xcd = blockIdx.x % 8, rank = blockIdx.x / 8;
+    const int work = xcd * a.per_xcd + rank;
+    if (rank >= a.per_xcd || work >= a.total_work) return false;
+    pb = work / a.tiles;
+    tile = work % a.tiles;
+    return true;
+}
+
+// What the fused form adds to the product: the target rows, and where the per-block sums go.
+struct FuseArgs {
+    const void *p;
+    int64_t ldp;
+    bool vec_p;
+    const SoftStat *pstat;
+    int p_splits;
+    float *part_q, *part_r, *part_a;   // [B, tiles]
+};
+
+// PK < 0: plain product (q' is written).  PK >= 0: fused with the verification sums against the target
+// rows of kind PK -- per (position, 256-id tile) the sums of q', max(0, p - q') and min(p, q') --
+// and q' is written only if WRITE_Q.
+template <int PK, bool WRITE_Q>
+__global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, FuseArgs f)
+{
+    constexpr bool FUSE = PK >= 0;
+    constexpr int PKIND = FUSE ? PK : RDK_PROB_F32;
+    __shared__ float stage[kPosBlock][kStageLd];
+    int pb, tile;
+    if (!xcd_work(a, pb, tile)) return;
+    const int j0 = tile * kTileIds;
+    // each wavefront finishes 8 of the 32 rows; a lane holds ids j0 + lane + 64 e (conflict-free LDS reads,
+    // 256-byte coalesced global accesses).  The target values are requested before the gathers start.
+    const int wid = threadIdx.x / kWave, lane = lane_id();
+    constexpr int kRowsPerWave = kPosBlock / kWaves;
+    float praw[kRowsPerWave][4];
+    if (FUSE) {
+#pragma unroll
+        for (int rr = 0; rr < kRowsPerWave; ++rr) {
+            const int64_t b = (int64_t)pb * kPosBlock + wid * kRowsPerWave + rr;
+            const void *pr = row_ptr<PKIND>(f.p, f.ldp, b < a.B ? b : 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = j0 + lane + 64 * e;
+                praw[rr][e] = (b < a.B && j < a.N) ? load1<PKIND>(pr, j) : (PKIND == RDK_PROB_F32 ? 0.f : -INFINITY);
+            }
+        }
+    }
+    sparse_tile(a, pb, j0, stage);
+#pragma unroll
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {
+        const int r = wid * kRowsPerWave + rr;
+        const int64_t b = (int64_t)pb * kPosBlock + r;
+        if (b >= a.B) break;
+        float qv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) qv[e] = (j0 + lane + 64 * e < a.N) ? stage[r][lane + 64 * e] : 0.f;
+        if (WRITE_Q) {
+            float *o = a.out + b * a.ldo + j0 + lane;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (j0 + lane + 64 * e < a.N) __builtin_nontemporal_store(qv[e], o + 64 * e);
+        }
+        if (FUSE) {
+            float m = 0.f, inv = 1.f;
+            if (PKIND != RDK_PROB_F32) {
+                const SoftStat rs = merged_row_stat<PKIND>(f.pstat, f.p_splits, b);
+                m = rs.m;
+                inv = 1.0f / rs.s;
+            }
+            float sq = 0.f, sr = 0.f, sa = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float pe = to_weight<PKIND>(praw[rr][e], m, inv);
+                sq += qv[e];
+                sr += fmaxf(pe - qv[e], 0.f);
+                sa += fminf(pe, qv[e]);
+            }
+            sq = wave_sum(sq);
+            sr = wave_sum(sr);
+            sa = wave_sum(sa);
+            if (lane == 0) {
+                const int64_t o = b * a.tiles + tile;
+                f.part_q[o] = sq;
+                f.part_r[o] = sr;
+                f.part_a[o] = sa;
+            }
+        }
+    }
+}
+
+// q' of one position recomputed from the sparse kernel (the finalize step needs two 256-id blocks of it).
+struct QpSparse {
+    static constexpr bool kSpreadRows = true;
+    SparseArgs a;
+    struct Row {
+        const int32_t *slot_of;
+        const int2 *nbr;
+        const float *self_w;
+        int kk, N;
+        const float *qcol;   // qT + (pb * n) * 32 + r : element of slot s is qcol[s * 32]
+        float inv_z;
+        __device__ __forceinline__ float value(int j) const
+        {
+            if (j >= N) return 0.f;
+            const int s = slot_of[j];
+            if (s >= 0) return self_w[s] * qcol[(int64_t)s * kPosBlock] * inv_z;
+            const int64_t u = -s - 1;
+            float acc = 0.f;
+            for (int t0 = 0; t0 < kk; t0 += 2) {   // same order of additions as the product kernel
+                const int4 ev = *(const int4 *)(nbr + u * kk + t0);
+                acc += __int_as_float(ev.y) * qcol[(int64_t)ev.x * kPosBlock];
+                acc += __int_as_float(ev.w) * qcol[(int64_t)ev.z * kPosBlock];
+            }
+            return acc * inv_z;
+        }
+        // Four consecutive ids at once, two at a time with all their loads in flight together: a kept id is
+        // treated as a row whose sixteen entries all point at its own slot, the first with the diagonal weight.
+        __device__ __forceinline__ float4 load4(int64_t idx) const
+        {
+            int se[4] = {-1, -1, -1, -1};
+            bool ok[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                ok[e] = idx + e < N;
+                if (ok[e]) se[e] = slot_of[idx + e];
+            }
+            float out[4];
+#pragma unroll
+            for (int pair = 0; pair < 2; ++pair) {
+                float acc[2] = {0.f, 0.f};
+                for (int t0 = 0; t0 < kk; t0 += 16) {
+                    int ii[2][16];
+                    float ww[2][16], gg[2][16];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int s = se[pair * 2 + h];
+                        const bool kept = s >= 0;
+                        const int64_t u = (kept || !ok[pair * 2 + h]) ? 0 : -s - 1;
+#pragma unroll
+                        for (int t = 0; t < 16; t += 2) {
+                            const int4 ev = *(const int4 *)(nbr + u * kk + t0 + t);
+                            ii[h][t] = ev.x; ww[h][t] = __int_as_float(ev.y);
+                            ii[h][t + 1] = ev.z; ww[h][t + 1] = __int_as_float(ev.w);
+                        }
+                        if (kept) {
+                            const float sw = t0 == 0 ? self_w[s] : 0.f;
+#pragma unroll
+                            for (int t = 0; t < 16; ++t) {
+                                ii[h][t] = s;
+                                ww[h][t] = t == 0 ? sw : 0.f;
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int t = 0; t < 16; ++t) gg[h][t] = qcol[(int64_t)ii[h][t] * kPosBlock];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int t = 0; t < 16; ++t) acc[h] += ww[h][t] * gg[h][t];
+                }
+                out[pair * 2 + 0] = ok[pair * 2 + 0] ? acc[0] * inv_z : 0.f;
+                out[pair * 2 + 1] = ok[pair * 2 + 1] ? acc[1] * inv_z : 0.f;
+            }
+            return make_float4(out[0], out[1], out[2], out[3]);
+        }
+        __device__ __forceinline__ float load1(int j) const { return value(j); }
+    };
+    __device__ __forceinline__ Row row(int64_t b) const
+    {
+        const int pb = (int)(b / kPosBlock), r = (int)(b % kPosBlock);
+        return Row{a.slot_of, a.nbr, a.self_w, a.kk, a.N, a.qT + (int64_t)pb * a.n * kPosBlock + r, a.zinv[b]};
+    }
+};
+
+struct SparseFusedWs {
+    SparseWs base;
+    SoftStat *pstat;
+    float *part_q, *part_r, *part_a;
+    int p_splits;
+};
+
+size_t fused_extra_bytes(const KernelHandle &h, int32_t B)
+{
+    const size_t tiles = (h.N + kTileIds - 1) / kTileIds;
+    return align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256) + 3 * align_up((size_t)B * tiles * sizeof(float), 256);
+}
+
+SparseArgs make_args(const KernelHandle &h, const SparseWs &w, int32_t B, float *out, int64_t ldo)
+{
+    SparseArgs a;
+    a.slot_of = h.slot_of; a.pruned_ids = h.pruned_ids; a.kept_ids = h.kept_ids; a.nbr = h.nbr;
+    a.self_w = h.self_w; a.kk = h.kk;
+    a.qT = w.qT; a.zinv = w.zinv;
+    a.N = h.N; a.n = h.n; a.B = B;
+    const int pbs = (B + kPosBlock - 1) / kPosBlock;
+    a.tiles = (h.N + kTileIds - 1) / kTileIds;
+    a.total_work = pbs * a.tiles;
+    a.per_xcd = (a.total_work + 7) / 8;
+    a.out = out; a.ldo = ldo; a.vec_o = out ? rows_vectorisable(out, ldo, RDK_PROB_F32) : false;
+    return a;
+}
+
+template <int QK>
+rdk_status_t prepare_q(const KernelHandle &h, RowInput q, int32_t B, const SparseWs &w, hipStream_t st)
+{
+    rdk_status_t rc = launch_row_stats<QK>(q, h.n, B, w.q_splits, w.qpart, st);
+    if (rc != RDK_OK) return rc;
+    const int pbs = (B + kPosBlock - 1) / kPosBlock;
+    {
+        TimedLaunch timed("q_transpose_kernel", st);
+        hipLaunchKernelGGL((q_transpose_kernel<QK>), dim3((h.n + 63) / 64, pbs), dim3(kPrepThreads), 0, st, q.ptr, q.ld, h.n, B,
+                           w.qpart, w.q_splits, rows_vectorisable(q.ptr, q.ld, q.kind), w.zinv, w.qT);
+    }
+    RDK_LAUNCH_CHECK("q_transpose_kernel");
+    return RDK_OK;
+}
+
+template <int QK>
+rdk_status_t run_sparse(const KernelHandle &h, RowInput q, int32_t B, float *out, int64_t ldo, void *ws, hipStream_t st)
+{
+    SparseWs w = carve(h, B, ws);
+    rdk_status_t rc = prepare_q<QK>(h, q, B, w, st);
+    if (rc != RDK_OK) return rc;
+    const SparseArgs a = make_args(h, w, B, out, ldo);
+    {
+        TimedLaunch timed("sparse_product_kernel", st);
+        hipLaunchKernelGGL((sparse_product_kernel<-1, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, FuseArgs{});
+    }
+    RDK_LAUNCH_CHECK("sparse_product_kernel");
+    return RDK_OK;
+}
+
+template <int PK, int QK>
+rdk_status_t run_sparse_fused(const KernelHandle &h, const FusedCall &c, void *ws, hipStream_t st)
+{
+    const int32_t B = c.d.B;
+    SparseWs w = carve(h, B, ws);
+    char *p = (char *)ws + sparse_workspace_bytes(h, B);
+    FuseArgs f{};
+    f.p = c.p.ptr; f.ldp = c.p.ld; f.vec_p = rows_vectorisable(c.p.ptr, c.p.ld, c.p.kind);
+    f.p_splits = row_splits(B, h.N, kStatThreads / kWave);
+    f.pstat = (SoftStat *)p; p += align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256);
+    const size_t tiles = (h.N + kTileIds - 1) / kTileIds;
+    const size_t per = align_up((size_t)B * tiles * sizeof(float), 256);
+    f.part_q = (float *)p; p += per;
+    f.part_r = (float *)p; p += per;
+    f.part_a = (float *)p;
+    rdk_status_t rc;
+    if (PK != RDK_PROB_F32) {
+        rc = launch_row_stats<PK>(c.p, h.N, B, f.p_splits, const_cast<SoftStat *>(f.pstat), st);
+        if (rc != RDK_OK) return rc;
+    }
+    rc = prepare_q<QK>(h, c.q, B, w, st);
+    if (rc != RDK_OK) return rc;
+    const SparseArgs a = make_args(h, w, B, c.q_prime, c.ldo);
+    {
+        TimedLaunch timed("sparse_product_kernel", st);
+        if (c.q_prime)
+            hipLaunchKernelGGL((sparse_product_kernel<PK, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+        else
+            hipLaunchKernelGGL((sparse_product_kernel<PK, false>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+    }
+    RDK_LAUNCH_CHECK("sparse_product_kernel");
+    FinalizeArgs fa{};
+    fa.d = c.d;
+    fa.p = c.p.ptr; fa.ldp = c.p.ld; fa.vec_p = f.vec_p;
+    fa.pstat = f.pstat; fa.p_splits = f.p_splits;
+    fa.part_q = f.part_q; fa.part_r = f.part_r; fa.part_a = f.part_a;
+    fa.nblk = (int)tiles;
+    fa.draft_ids = c.draft_ids; fa.accept = c.accept; fa.alpha = c.alpha; fa.resid_mass = c.resid_mass;
+    fa.resid_ids = c.resid_ids; fa.n_accepted = c.n_accepted; fa.out_tokens = c.out_tokens;
+    return launch_finalize<PK, 1, true, QpSparse>(fa, QpSparse{a}, st);
+}
+
+}  // namespace
+
+size_t sparse_workspace_bytes(const KernelHandle &h, int32_t B)
+{
+    const size_t pbs = (B + kPosBlock - 1) / kPosBlock;
+    return align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256) + align_up((size_t)(B + kPosBlock) * sizeof(float), 256) +
+           align_up(pbs * h.n * kPosBlock * sizeof(float), 256);
+}
+
+size_t sparse_fused_workspace_bytes(const KernelHandle &h, int32_t B) { return sparse_workspace_bytes(h, B) + fused_extra_bytes(h, B); }
+
+rdk_status_t launch_sparse(const KernelHandle &h, RowInput q, int32_t B, float *out, int64_t ldo, void *ws, hipStream_t st)
+{
+    switch (q.kind) {
+        case RDK_PROB_F32: return run_sparse<RDK_PROB_F32>(h, q, B, out, ldo, ws, st);
+        case RDK_LOGIT_F32: return run_sparse<RDK_LOGIT_F32>(h, q, B, out, ldo, ws, st);
+        case RDK_LOGIT_BF16: return run_sparse<RDK_LOGIT_BF16>(h, q, B, out, ldo, ws, st);
+    }
+    return RDK_ERR_DTYPE;
+}
+
+rdk_status_t launch_sparse_fused(const KernelHandle &h, const FusedCall &c, void *ws, hipStream_t st)
+{
+#define RDK_F(PK, QK) \
+    if (c.p.kind == PK && c.q.kind == QK) return run_sparse_fused<PK, QK>(h, c, ws, st);
+    RDK_F(RDK_PROB_F32, RDK_PROB_F32)
+    RDK_F(RDK_PROB_F32, RDK_LOGIT_F32)
+    RDK_F(RDK_PROB_F32, RDK_LOGIT_BF16)
+    RDK_F(RDK_LOGIT_F32, RDK_PROB_F32)
+    RDK_F(RDK_LOGIT_F32, RDK_LOGIT_F32)
+    RDK_F(RDK_LOGIT_F32, RDK_LOGIT_BF16)
+    RDK_F(RDK_LOGIT_BF16, RDK_PROB_F32)
+    RDK_F(RDK_LOGIT_BF16, RDK_LOGIT_F32)
+    RDK_F(RDK_LOGIT_BF16, RDK_LOGIT_BF16)
+#undef RDK_F
+    return RDK_ERR_DTYPE;
+}
+
+}  // namespace rdk

@@ -9,7 +9,7 @@
 //                     the partial sums, then re-read), the accept test, and the per-sequence scan
 // The streaming pass is bound by HBM: 8 bytes per (position, id), nothing is written but 12 bytes
 // per 1024 ids.
-#include "rdk_rowstats.hpp"
+#include "rdk_finalize.hpp"
 
 namespace rdk {
 
@@ -102,191 +102,7 @@ __global__ __launch_bounds__(kStreamThreads) void verify_stream_kernel(const voi
     }
 }
 
-// ------------------------------------------------------------------------------------------------
-// Wave-level helpers of the finalize step.
-
-// Sum of a row of block partials in fp64; lane l owns the `per_lane` consecutive blocks from l*per_lane.
-__device__ __forceinline__ double lane_partial_sum(const float *part, int nchunks, int per_lane)
-{
-    const int c0 = lane_id() * per_lane;
-    double s = 0.0;
-    for (int t = 0; t < per_lane; ++t)
-        if (c0 + t < nchunks) s += (double)part[c0 + t];
-    return s;
-}
-
-// Locates the block in which the inclusive prefix of `part` first exceeds thr.  Returns the block and
-// the prefix before it; block = -1 when no prefix exceeds thr.
-__device__ __forceinline__ int locate_block(const float *part, int nchunks, int per_lane, double lane_sum, double thr,
-                                            double &prefix_before)
-{
-    const double incl = wave_inclusive_scan(lane_sum);
-    const unsigned long long hits = __ballot(incl > thr);
-    if (hits == 0ull) return -1;
-    const int src = __ffsll(hits) - 1;
-    int blk = -1;
-    double pre = incl - lane_sum;
-    if (lane_id() == src) {
-        const int c0 = src * per_lane;
-        for (int t = 0; t < per_lane && c0 + t < nchunks; ++t) {
-            const double v = (double)part[c0 + t];
-            if (pre + v > thr) {
-                blk = c0 + t;
-                break;
-            }
-            pre += v;
-        }
-    }
-    blk = __shfl(blk, src, kWave);
-    prefix_before = __shfl(pre, src, kWave);
-    return blk;
-}
-
-// Within one 1024-id block, the smallest id whose inclusive prefix of weights exceeds thr_local; if
-// rounding leaves none, the last id of the block with a positive weight.  wv[i] holds the weights of
-// ids blk*1024 + i*256 + lane*4 .. +3 (zero beyond the row), all loaded before the scan starts.
-__device__ __forceinline__ int search_block(const float4 (&wv)[4], int blk, double thr_local)
-{
-    const int lane = lane_id();
-    double carried = 0.0;
-    int last_positive = -1;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int idx = blk * kChunk + i * 256 + lane * 4;
-        const double l0 = (double)wv[i].x, l1 = l0 + (double)wv[i].y, l2 = l1 + (double)wv[i].z, l3 = l2 + (double)wv[i].w;
-        const double incl = wave_inclusive_scan(l3);
-        const double excl = carried + (incl - l3);
-        const unsigned long long hits = __ballot(excl + l3 > thr_local);
-        if (hits != 0ull) {
-            const int src = __ffsll(hits) - 1;
-            const int e = (excl + l0 > thr_local) ? 0 : (excl + l1 > thr_local) ? 1 : (excl + l2 > thr_local) ? 2 : 3;
-            return __shfl(idx + e, src, kWave);
-        }
-        const int mine = wv[i].w > 0.f ? 3 : wv[i].z > 0.f ? 2 : wv[i].y > 0.f ? 1 : wv[i].x > 0.f ? 0 : -1;
-        const unsigned long long pos = __ballot(mine >= 0);
-        if (pos != 0ull) {
-            const int src = 63 - __clzll(pos);
-            last_positive = __shfl(idx + mine, src, kWave);
-        }
-        carried += __shfl(incl, kWave - 1, kWave);
-    }
-    return last_positive;
-}
-
-template <int KIND, bool HAS_Q>
-__global__ void verify_finalize_kernel(rdk_verify_desc_t d, const void *p, int64_t ldp, const float *q, int64_t ldq,
-                                       bool vec_p, bool vec_q, VerifyWs w, int rows_per_block, bool scan_here,
-                                       int32_t *draft_ids, uint8_t *accept, float *alpha, float *resid_mass,
-                                       int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens)
-{
-    __shared__ int32_t sh_draft[16], sh_resid[16];
-    __shared__ uint8_t sh_acc[16];
-    const int wid = threadIdx.x / kWave, lane = lane_id();
-    const int64_t row = (int64_t)blockIdx.x * rows_per_block + wid;
-    const int N = d.N;
-    if (row < d.B) {
-        const void *pr = row_ptr<KIND>(p, ldp, row);
-        const float *qr = HAS_Q ? q + row * ldq : nullptr;
-        float m = 0.f, inv = 1.f;
-        if (KIND != RDK_PROB_F32) {
-            const SoftStat rs = merged_row_stat<KIND>(w.pstat, w.stat_splits, row);
-            m = rs.m;
-            inv = 1.0f / rs.s;
-        }
-        const float pfill = KIND == RDK_PROB_F32 ? 0.f : -INFINITY;
-        const int per_lane = (w.nchunks + kWave - 1) / kWave;
-        const float *pq = w.part_q + row * w.nchunks;
-        const float *prr = w.part_r + row * w.nchunks;
-        const float *pa = w.part_a + row * w.nchunks;
-        const bool draw_draft = HAS_Q && d.sample_draft;
-
-        // 1. block partials (one round trip), uniforms meanwhile
-        const double lane_r = lane_partial_sum(prr, w.nchunks, per_lane);
-        const double lane_q = draw_draft ? lane_partial_sum(pq, w.nchunks, per_lane) : 0.0;
-        const double lane_a = HAS_Q ? lane_partial_sum(pa, w.nchunks, per_lane) : 0.0;
-        int32_t dtok = (HAS_Q && !d.sample_draft) ? draft_ids[row] : -1;
-        uint32_t words[4];
-        position_words(d.seed, d.offset + (uint64_t)row, words);
-        const double R = wave_sum(lane_r);
-        const double Q = draw_draft ? wave_sum(lane_q) : 0.0;
-        const double A = HAS_Q ? wave_sum(lane_a) : 0.0;
-
-        // 2. the blocks that hold the two prefix-sum crossings
-        double thr_d = 0.0, thr_r = 0.0, before_d = 0.0, before_r = 0.0;
-        int blk_d = -1, blk_r = -1;
-        if (draw_draft && Q > 0.0) {
-            thr_d = word_to_unit(words[0]) * Q;
-            blk_d = locate_block(pq, w.nchunks, per_lane, lane_q, thr_d, before_d);
-        }
-        if (R > 0.0) {
-            thr_r = word_to_unit(words[HAS_Q ? 2 : 3]) * R;
-            blk_r = locate_block(prr, w.nchunks, per_lane, lane_r, thr_r, before_r);
-        }
-
-        // 3. both blocks are fetched together (one round trip), then scanned
-        float4 wd[4], wp[4], wq[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int64_t id_d = (int64_t)max(blk_d, 0) * kChunk + i * 256 + lane * 4;
-            const int64_t id_r = (int64_t)max(blk_r, 0) * kChunk + i * 256 + lane * 4;
-            if (draw_draft) wd[i] = load4<RDK_PROB_F32>(qr, id_d, N, vec_q, 0.f);
-            wp[i] = load4<KIND>(pr, id_r, N, vec_p, pfill);
-            if (HAS_Q) wq[i] = load4<RDK_PROB_F32>(qr, id_r, N, vec_q, 0.f);
-        }
-        if (blk_d >= 0) dtok = search_block(wd, blk_d, thr_d - before_d);
-        // 4. the accept test needs p and q' at the draft token: issue those loads before the second scan
-        float pd_raw = 0.f, qd = 0.f;
-        const bool d_ok = HAS_Q && dtok >= 0 && dtok < N;
-        if (d_ok) {
-            pd_raw = load1<KIND>(pr, dtok);
-            qd = qr[dtok];
-        }
-        int32_t rtok = -1;
-        if (blk_r >= 0) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                wp[i].x = to_weight<KIND>(wp[i].x, m, inv);
-                wp[i].y = to_weight<KIND>(wp[i].y, m, inv);
-                wp[i].z = to_weight<KIND>(wp[i].z, m, inv);
-                wp[i].w = to_weight<KIND>(wp[i].w, m, inv);
-                if (HAS_Q) {
-                    wp[i].x = fmaxf(wp[i].x - wq[i].x, 0.f);
-                    wp[i].y = fmaxf(wp[i].y - wq[i].y, 0.f);
-                    wp[i].z = fmaxf(wp[i].z - wq[i].z, 0.f);
-                    wp[i].w = fmaxf(wp[i].w - wq[i].w, 0.f);
-                }
-            }
-            rtok = search_block(wp, blk_r, thr_r - before_r);
-        }
-        uint8_t acc = 0;
-        if (d_ok) acc = (word_to_unit(words[1]) * (double)qd < (double)to_weight<KIND>(pd_raw, m, inv)) ? 1 : 0;
-        if (lane == 0) {
-            if (HAS_Q && d.sample_draft) draft_ids[row] = dtok;
-            accept[row] = acc;
-            if (alpha) alpha[row] = (float)A;
-            if (resid_mass) resid_mass[row] = (float)R;
-            resid_ids[row] = rtok;
-            if (scan_here) {
-                sh_draft[wid] = dtok;
-                sh_resid[wid] = rtok;
-                sh_acc[wid] = acc;
-            }
-        }
-    }
-    if (scan_here) {  // the block holds exactly one sequence: steps 4-10 of Alg. 4
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            const int g = d.gamma;
-            int j = 0;
-            while (j < g && sh_acc[j]) ++j;
-            if (n_accepted) n_accepted[blockIdx.x] = j;
-            if (out_tokens) {
-                int32_t *o = out_tokens + (int64_t)blockIdx.x * (g + 1);
-                for (int i = 0; i <= g; ++i) o[i] = i < j ? sh_draft[i] : (i == j && j < g) ? sh_resid[i] : -1;
-            }
-        }
-    }
-}
+}  // namespace
 
 // Per-sequence scan as a launch of its own (sequences longer than one workgroup's waves).
 __global__ void sequence_scan_kernel(int S, int gamma, const int32_t *draft_ids, const uint8_t *accept,
@@ -303,6 +119,8 @@ __global__ void sequence_scan_kernel(int S, int gamma, const int32_t *draft_ids,
         for (int i = 0; i <= gamma; ++i) o[i] = i < j ? draft_ids[b0 + i] : (i == j && j < gamma) ? resid_ids[b0 + i] : -1;
     }
 }
+
+namespace {
 
 __global__ void philox_words_kernel(uint64_t seed, uint64_t offset, int count, uint32_t *words)
 {
@@ -332,26 +150,16 @@ rdk_status_t run_verify(const rdk_verify_desc_t &d, RowInput p, const float *q, 
                            p.ld, q, ldq, d.N, splits, vec_p, vec_q, w);
     }
     RDK_LAUNCH_CHECK("verify_stream_kernel");
-    const bool scan_here = d.gamma >= 1 && d.gamma <= 16;
-    const int rows_per_block = scan_here ? d.gamma : 4;
-    const int blocks = (d.B + rows_per_block - 1) / rows_per_block;
-    {
-        TimedLaunch timed("verify_finalize_kernel", st);
-        hipLaunchKernelGGL((verify_finalize_kernel<KIND, HAS_Q>), dim3(blocks), dim3(rows_per_block * kWave), 0, st, d, p.ptr,
-                           p.ld, q, ldq, vec_p, vec_q, w, rows_per_block, scan_here, draft_ids, accept, alpha, resid_mass,
-                           resid_ids, n_accepted, out_tokens);
-    }
-    RDK_LAUNCH_CHECK("verify_finalize_kernel");
-    if (d.gamma > 16 && (n_accepted || out_tokens)) {
-        const int S = d.B / d.gamma;
-        {
-            TimedLaunch timed("sequence_scan_kernel", st);
-            hipLaunchKernelGGL(sequence_scan_kernel, dim3((S + 63) / 64), dim3(64), 0, st, S, d.gamma, draft_ids, accept,
-                               resid_ids, n_accepted, out_tokens);
-        }
-        RDK_LAUNCH_CHECK("sequence_scan_kernel");
-    }
-    return RDK_OK;
+    FinalizeArgs fa{};
+    fa.d = d;
+    fa.p = p.ptr; fa.ldp = p.ld; fa.vec_p = vec_p;
+    fa.pstat = w.pstat; fa.p_splits = w.stat_splits;
+    fa.part_q = w.part_q; fa.part_r = w.part_r; fa.part_a = w.part_a;
+    fa.nblk = w.nchunks;
+    fa.draft_ids = draft_ids; fa.accept = accept; fa.alpha = alpha; fa.resid_mass = resid_mass;
+    fa.resid_ids = resid_ids; fa.n_accepted = n_accepted; fa.out_tokens = out_tokens;
+    QpMemory qp{q, ldq, vec_q, d.N};
+    return launch_finalize<KIND, 4, HAS_Q, QpMemory>(fa, qp, st);
 }
 
 }  // namespace
@@ -380,6 +188,19 @@ rdk_status_t launch_verify(const rdk_verify_desc_t &d, RowInput p, const float *
     }
 #undef RDK_VERIFY_CASE
     return RDK_ERR_DTYPE;
+}
+
+rdk_status_t launch_sequence_scan(const rdk_verify_desc_t &d, const int32_t *draft_ids, const uint8_t *accept,
+                                  const int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens, hipStream_t st)
+{
+    const int S = d.B / d.gamma;
+    {
+        TimedLaunch timed("sequence_scan_kernel", st);
+        hipLaunchKernelGGL(sequence_scan_kernel, dim3((S + 63) / 64), dim3(64), 0, st, S, d.gamma, draft_ids, accept, resid_ids,
+                           n_accepted, out_tokens);
+    }
+    RDK_LAUNCH_CHECK("sequence_scan_kernel");
+    return RDK_OK;
 }
 
 rdk_status_t launch_philox_words(uint64_t seed, uint64_t offset, int32_t count, uint32_t *words, hipStream_t st)

@@ -22,7 +22,7 @@ EXPORTS = [
     "rdk_status_string", "rdk_last_hip_error", "rdk_kernel_storage_bytes", "rdk_build_kernel", "rdk_destroy_kernel",
     "rdk_kernel_get_sparse", "rdk_kernel_get_dense", "rdk_workspace_bytes", "rdk_redistribute_exact",
     "rdk_redistribute_linear", "rdk_verify_workspace_bytes", "rdk_verify_sample", "rdk_philox_words",
-    "rdk_timing_select", "rdk_timing_read",
+    "rdk_timing_select", "rdk_timing_read", "rdk_redistribute_verify_workspace_bytes", "rdk_redistribute_verify",
 ]
 
 
@@ -76,6 +76,9 @@ def lib():
         L.rdk_verify_sample.argtypes = [ctypes.POINTER(VerifyDesc), vp, ctypes.c_int, i64, vp, i64, vp, vp, vp, vp, vp, vp,
                                         vp, vp, sz, vp]
         L.rdk_philox_words.argtypes = [ctypes.c_uint64, ctypes.c_uint64, i32, vp, vp]
+        L.rdk_redistribute_verify_workspace_bytes.argtypes = [vp, ctypes.c_int, ctypes.POINTER(VerifyDesc), psz]
+        L.rdk_redistribute_verify.argtypes = [vp, ctypes.c_int, ctypes.POINTER(VerifyDesc), vp, ctypes.c_int, i64, vp,
+                                              ctypes.c_int, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.rdk_timing_select.argtypes = [ctypes.c_char_p]
         L.rdk_timing_read.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
         for name in EXPORTS:
@@ -122,8 +125,8 @@ class Kernel:
         self._ws = None
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().rdk_destroy_kernel(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.rdk_destroy_kernel(self.handle)
             self.handle = None
 
     def workspace(self, B):
@@ -235,6 +238,29 @@ def rdk_verify_sample(p, q_prime, seed, offset=0, gamma=0, p_kind="prob", draft_
                                    _ptr(o.draft_ids), _ptr(o.accept), _ptr(o.alpha), _ptr(o.resid_mass), _ptr(o.resid_ids),
                                    _ptr(o.n_accepted), _ptr(o.out_tokens), _ptr(o.ws), o.ws.numel(), _stream()),
            "rdk_verify_sample")
+    return o
+
+
+def rdk_redistribute_verify(kernel, mode, p, q, seed, offset=0, gamma=0, p_kind="prob", q_kind="prob", draft_ids=None,
+                            outputs=None, q_prime=None):
+    """Fused rdk_redistribute_linear + rdk_verify_sample.  q_prime: optional [B,N] tensor that receives q'."""
+    B, N = p.shape
+    o = outputs or VerifyOutputs(B, N, gamma, p.device)
+    assert (o.B, o.N, o.gamma) == (B, N, gamma)
+    if draft_ids is not None:
+        o.draft_ids.copy_(draft_ids)
+    d = VerifyDesc(B=B, N=N, gamma=gamma, sample_draft=0 if draft_ids is not None else 1, seed=seed, offset=offset)
+    need = ctypes.c_size_t()
+    _check(lib().rdk_redistribute_verify_workspace_bytes(kernel.handle, mode, ctypes.byref(d), ctypes.byref(need)),
+           "rdk_redistribute_verify_workspace_bytes")
+    if getattr(o, "fused_ws", None) is None or o.fused_ws.numel() < need.value:
+        o.fused_ws = torch.empty(need.value, dtype=torch.uint8, device=p.device)
+    ldo = 0 if q_prime is None else _rows(q_prime)
+    _check(lib().rdk_redistribute_verify(kernel.handle, mode, ctypes.byref(d), _ptr(p), _kind_of(p, p_kind), _rows(p),
+                                         _ptr(q), _kind_of(q, q_kind), _rows(q), _ptr(q_prime), ldo, _ptr(o.draft_ids),
+                                         _ptr(o.accept), _ptr(o.alpha), _ptr(o.resid_mass), _ptr(o.resid_ids),
+                                         _ptr(o.n_accepted), _ptr(o.out_tokens), _ptr(o.fused_ws), o.fused_ws.numel(),
+                                         _stream()), "rdk_redistribute_verify")
     return o
 
 

@@ -56,12 +56,14 @@ def test_storage_query_and_validation(rdk):
     sb, wb = ctypes.c_size_t(), ctypes.c_size_t()
     q = lambda d: L.rdk_kernel_storage_bytes(ctypes.byref(d), ctypes.byref(sb), ctypes.byref(wb))
     assert q(_desc(rdk)) == 0
-    # kept ids + slot table + two [N, 8] tables
-    assert sb.value == 1024 + 4096 + 2 * 1024 * 8 * 4
-    assert q(_desc(rdk, format=rdk.DENSE_F32)) == 0 and sb.value == 1024 + 4096 + 256 * 1024 * 4
-    assert q(_desc(rdk, format=rdk.DENSE_BF16)) == 0 and sb.value == 1024 + 4096 + 256 * 1024 * 2 + 1024
+    up = lambda x: (x + 255) // 256 * 256
+    head = 1024 + 4096 + up(769 * 4)                       # kept ids, slot table, pruned ids
+    # [N-n, 16] (slot, weight) pairs (k = 8 padded to 16 entries) and the diagonal weights
+    assert sb.value == head + up(768 * 16 * 8 + 512) + 1024
+    assert q(_desc(rdk, format=rdk.DENSE_F32)) == 0 and sb.value == head + 256 * 1024 * 4
+    assert q(_desc(rdk, format=rdk.DENSE_BF16)) == 0 and sb.value == head + 256 * 1024 * 2 + 1024
     assert wb.value > 256 * 1024 * 4                       # the fp32 matrix that gets packed
-    assert q(_desc(rdk, format=rdk.IDENTITY, embeddings=None)) == 0 and sb.value == 1024 + 4096
+    assert q(_desc(rdk, format=rdk.IDENTITY, embeddings=None)) == 0 and sb.value == head
     assert q(_desc(rdk, n=0)) == 2 and q(_desc(rdk, n=2000)) == 2 and q(_desc(rdk, k=65)) == 2
     assert q(_desc(rdk, kept_ids=None)) == 1 and q(_desc(rdk, embeddings=None)) == 1
     assert q(_desc(rdk, tau=0.0)) == 2 and q(_desc(rdk, format=7)) == 3

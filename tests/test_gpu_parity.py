@@ -202,42 +202,46 @@ def test_exact_bf16(rdk, tiny, ragged, case):
 
 
 # --------------------------------------------------------------------------------------------- verification
-def run_verify_case(rdk, p_in, p_kind, p64, qp32, gamma, seed, offset, draft_ids=None):
-    B, N = p64.shape
-    o = rdk.rdk_verify_sample(p_in, None if qp32 is None else dev(qp32), seed, offset, gamma, p_kind,
-                              draft_ids=None if draft_ids is None else dev(draft_ids))
-    torch.cuda.synchronize()
-    ref = oracle.verify_batch(p64, None if qp32 is None else qp32.astype(np.float64), seed, offset,
-                              sample_draft=draft_ids is None, draft_ids=draft_ids, gamma=gamma)
+def check_verify_outputs(o, ref, p64, q64, seed, offset, gamma, p_kind, min_exact=0.95):
+    """Device outputs `o` of a verification against the oracle's `ref` for target rows p64 and drafter rows q64."""
+    B = p64.shape[0]
     us = np.array([oracle.uniforms(seed, offset + b) for b in range(B)])
     g_resid = o.resid_ids.cpu().numpy()
-    if qp32 is None:
+    if q64 is None:
         check_sampled_ids(p64, us[:, 3], g_resid, ref["resid_ids"], what="bonus")
         assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], what="sum p")
         assert not o.accept.any() and not o.alpha.any()
-        return o, ref
-    q64 = qp32.astype(np.float64)
-    assert_close(o.alpha.cpu().numpy(), ref["alpha"], what="alpha")
-    assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], rtol=RTOL, atol=2e-7, what="residual mass")
+        return
+    assert_close(o.alpha.cpu().numpy(), ref["alpha"], rtol=2 * RTOL, what="alpha")
+    assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], rtol=2 * RTOL, atol=2e-7, what="residual mass")
     g_draft = o.draft_ids.cpu().numpy()
     n_d = check_sampled_ids(q64, us[:, 0], g_draft, ref["draft_ids"], what="draft")
     n_r = check_sampled_ids(np.maximum(p64 - q64, 0), us[:, 2], g_resid, ref["resid_ids"], what="residual")
-    assert n_d >= 0.95 * B and n_r >= 0.95 * B
-    # acceptance is decided exactly (fp64 product) on both sides wherever the draft token agrees
+    assert n_d >= min_exact * B and n_r >= min_exact * B
+    # acceptance is decided exactly (fp64 product) on both sides wherever the draft token and the inputs agree
     same = g_draft == ref["draft_ids"]
     g_acc = o.accept.cpu().numpy()
-    if p_kind == "prob":
-        assert np.array_equal(g_acc[same], ref["accept"][same])
-    else:   # p itself is computed in fp32 on the device: allow a flip only at a near-tie
-        for b in np.nonzero(same & (g_acc != ref["accept"]))[0]:
-            d_ = g_draft[b]
-            assert abs(us[b, 1] * q64[b, d_] - p64[b, d_]) <= 1e-5 * p64[b, d_]
+    for b in np.nonzero(same & (g_acc != ref["accept"]))[0]:      # a flip is allowed only at a near-tie
+        d_ = g_draft[b]
+        assert d_ >= 0 and abs(us[b, 1] * q64[b, d_] - p64[b, d_]) <= 2e-5 * p64[b, d_], (b, d_)
     if gamma:
         n_acc, toks = oracle.sequence_scan(g_acc, g_draft, g_resid, gamma)     # scan of the device's own flags
         assert np.array_equal(o.n_accepted.cpu().numpy(), n_acc)
         assert np.array_equal(o.out_tokens.cpu().numpy(), toks)
         if same.all() and np.array_equal(g_acc, ref["accept"]) and np.array_equal(g_resid, ref["resid_ids"]):
             assert np.array_equal(o.out_tokens.cpu().numpy(), ref["out_tokens"])
+
+
+def run_verify_case(rdk, p_in, p_kind, p64, qp32, gamma, seed, offset, draft_ids=None):
+    o = rdk.rdk_verify_sample(p_in, None if qp32 is None else dev(qp32), seed, offset, gamma, p_kind,
+                              draft_ids=None if draft_ids is None else dev(draft_ids))
+    torch.cuda.synchronize()
+    q64 = None if qp32 is None else qp32.astype(np.float64)
+    ref = oracle.verify_batch(p64, q64, seed, offset, sample_draft=draft_ids is None, draft_ids=draft_ids, gamma=gamma)
+    check_verify_outputs(o, ref, p64, q64, seed, offset, gamma, p_kind)
+    if q64 is not None and p_kind == "prob":      # identical fp32 inputs on both sides: the accept flags must agree exactly
+        same = o.draft_ids.cpu().numpy() == ref["draft_ids"]
+        assert np.array_equal(o.accept.cpu().numpy()[same], ref["accept"][same])
     return o, ref
 
 
@@ -296,3 +300,44 @@ def test_pipeline_end_to_end(rdk, tiny):
     assert_close(o.alpha.cpu().numpy(), ref["alpha"], rtol=2e-5, what="alpha")
     us = np.array([oracle.uniforms(77, b) for b in range(w.B)])
     check_sampled_ids(ref_qp, us[:, 0], o.draft_ids.cpu().numpy(), ref["draft_ids"], what="draft")
+
+
+# --------------------------------------------------------------------------------------------- fused entry point
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+@pytest.mark.parametrize("mode", ["sparse", "taylor"])
+@pytest.mark.parametrize("kinds", [("prob", "prob"), ("logit", "logit")])
+def test_fused_redistribute_verify(rdk, tiny, ragged, case, mode, kinds):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    p_kind, q_kind = kinds
+    idx, wt, sw = data["sparse"]
+    wt32, sw32 = wt.astype(np.float32), sw.astype(np.float32)
+    if mode == "sparse":
+        kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.SPARSE_TOPK, k=w.k, sparse=(dev(idx), dev(wt32), dev(sw32)))
+        gmode = rdk.LINEAR_SPARSE
+    else:
+        kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.IDENTITY)
+        gmode = rdk.LINEAR_TAYLOR
+    p_in = dev(data["p"]) if p_kind == "prob" else dev(data["z_p"])
+    q_in = dev(data["q_hat"]) if q_kind == "prob" else dev(data["z_q"])
+    seed, offset = 4242, 17
+    # with and without materialising q'
+    qp_out = torch.zeros((w.B, w.N), dtype=torch.float32, device="cuda")
+    o1 = rdk.rdk_redistribute_verify(kern, gmode, p_in, q_in, seed, offset, w.gamma, p_kind, q_kind, q_prime=qp_out)
+    o2 = rdk.rdk_redistribute_verify(kern, gmode, p_in, q_in, seed, offset, w.gamma, p_kind, q_kind)
+    torch.cuda.synchronize()
+    two_call = rdk.rdk_redistribute_linear(kern, gmode, q_in, q_kind, p=p_in, p_kind=p_kind)
+    assert torch.equal(qp_out, two_call)                    # the same kernel code produces q' in both entry points
+    for name in ("draft_ids", "accept", "alpha", "resid_mass", "resid_ids", "n_accepted", "out_tokens"):
+        assert torch.equal(getattr(o1, name), getattr(o2, name)), name
+    # against the oracle chain
+    p64 = data["p"].astype(np.float64) if p_kind == "prob" else oracle.probs_from(data["z_p"], "logit")
+    ref_qp = oracle_rows(data, mode, q_kind, p_kind, kernel=(idx, wt32, sw32) if mode == "sparse" else None)
+    assert_close(qp_out.cpu().numpy(), ref_qp, what="fused q'")
+    ref = oracle.verify_batch(p64, ref_qp, seed, offset, gamma=w.gamma)
+    check_verify_outputs(o2, ref, p64, ref_qp, seed, offset, w.gamma, p_kind)
+    # caller-supplied drafts through the fused path
+    drafts = (np.arange(w.B, dtype=np.int32) * 11) % w.N
+    o3 = rdk.rdk_redistribute_verify(kern, gmode, p_in, q_in, seed, offset, w.gamma, p_kind, q_kind, draft_ids=dev(drafts))
+    ref3 = oracle.verify_batch(p64, ref_qp, seed, offset, sample_draft=False, draft_ids=drafts, gamma=w.gamma)
+    check_verify_outputs(o3, ref3, p64, ref_qp, seed, offset, w.gamma, p_kind)
