@@ -171,27 +171,35 @@ __global__ void unpack_bf16_kernel(const uint16_t *packed, int n, int N, int KB,
     }
 }
 
-// A operand: TLI-normalised drafter rows rounded to bf16, [B_pad, n_pad] row-major, zero padded; and
-// per row the factor 1 / sum_s bf16(q'_s) * row_sum[s], which makes the output row sum to one.
+// A operand: TLI-normalised drafter rows rounded to bf16, packed like M: for row block rb (32 positions) and
+// slot block kb (16 slots) one 1 KB record holding, for lane l = 32 * g + r, the eight values
+// q'[rb*32 + r, kb*16 + g*8 + e], e = 0..7 -- the A operand of one 32x32x16 MFMA.  Also per row the factor
+// 1 / sum_s bf16(q'_s) * row_sum[s], which makes the output row sum to one.  One workgroup per position.
 template <int QK>
 __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t ldq, const SoftStat *qstat, const float *row_sum,
-                                                          int n, int n_pad, int B, uint16_t *A, float *out_scale)
+                                                          int n, int KB, int B, uint16_t *Ap, float *out_scale)
 {
     const int b = blockIdx.x;
+    const int rb = b / 32, r = b % 32;
     double mass = 0.0;
-    if (b < B) {
-        const void *qr = row_ptr<QK>(q, ldq, b);
-        const float qm = qstat[b].m, inv = 1.0f / qstat[b].s;
-        for (int s = threadIdx.x; s < n_pad; s += blockDim.x) {
-            uint16_t h = 0;
-            if (s < n) {
-                h = f32_to_bf16_rne(to_weight<QK>(load1<QK>(qr, s), qm, 1.f) * inv);
-                mass += (double)bf16_to_f32(h) * (double)row_sum[s];
+    const void *qr = b < B ? row_ptr<QK>(q, ldq, b) : nullptr;
+    const float qm = b < B ? qstat[b].m : 0.f, inv = b < B ? 1.0f / qstat[b].s : 0.f;
+    for (int c = threadIdx.x; c < KB * 2; c += blockDim.x) {   // chunk of 8 consecutive slots
+        const int kb = c / 2, g = c % 2;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (qr) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int s = c * 8 + e;
+                uint16_t h = 0;
+                if (s < n) {
+                    h = f32_to_bf16_rne(to_weight<QK>(load1<QK>(qr, s), qm, 1.f) * inv);
+                    mass += (double)bf16_to_f32(h) * (double)row_sum[s];
+                }
+                w[e / 2] |= (uint32_t)h << (16 * (e % 2));
             }
-            A[(int64_t)b * n_pad + s] = h;
         }
-    } else {
-        for (int s = threadIdx.x; s < n_pad; s += blockDim.x) A[(int64_t)b * n_pad + s] = 0;
+        *(uint4 *)(Ap + (((int64_t)rb * KB + kb) * 64 + g * 32 + r) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
     }
     mass = wave_sum(mass);
     __shared__ double sh[4];
@@ -200,16 +208,25 @@ __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t
     if (threadIdx.x == 0 && b < B) out_scale[b] = (float)(1.0 / ((sh[0] + sh[1]) + (sh[2] + sh[3])));
 }
 
-// One workgroup = 4 wavefronts; wavefront w owns rows [32*RB*w, 32*RB*(w+1)) of the row super-block and
-// all 128 columns of the workgroup's column group.  Accumulators: RB x 4 tiles of 32 x 32 fp32.
-template <int RB>
-__global__ __launch_bounds__(256) void exact_bf16_kernel(const uint16_t *A, int n_pad, const uint16_t *packed, int KB, int N,
-                                                         int B, const float *out_scale, float *out, int64_t ldo)
+// P'[512 x 128] per workgroup: W wavefronts, wavefront w owns RB row blocks (32 positions each) and all four
+// column blocks (32 target ids each) of the workgroup's column group, i.e. RB x 4 accumulator tiles of
+// 32 x 32 fp32.  The kept slots are walked in stages of 64 (four MFMA steps):
+//   * A records come straight from global memory (L2-resident: every workgroup walks the slots at the same pace),
+//   * the 16 B records of a stage are fetched once per workgroup, parked in LDS (double buffered) and read by all
+//     wavefronts: the vector memory pipe of a CU could not feed every wavefront its own copy;
+//   * the loads of stage s+1 are issued before the MFMAs of stage s; two wavefronts per SIMD cover the rest.
+// M is streamed from HBM exactly once when all positions fit one row of workgroups (B <= 512).
+template <int W, int RB>
+__global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, const uint16_t *Mp, int KB, int N, int B,
+                                                            const float *out_scale, float *out, int64_t ldo)
 {
+    constexpr int RPW = 16 / W;   // B records a wavefront fetches per stage
+    __shared__ bf16x8 bbuf[2][16][64];
     const int wid = threadIdx.x / kWave, lane = lane_id();
     const int jb0 = blockIdx.x * kColBlocksPerWg;
-    const int row0 = (blockIdx.y * 4 + wid) * 32 * RB;
+    const int rb0 = (blockIdx.y * W + wid) * RB;
     const int n_jb = (N + kColBlock - 1) / kColBlock;
+    const int stages = KB / 4;
     f32x16 acc[RB][kColBlocksPerWg];
 #pragma unroll
     for (int r = 0; r < RB; ++r)
@@ -218,25 +235,66 @@ __global__ __launch_bounds__(256) void exact_bf16_kernel(const uint16_t *A, int 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
-    const uint16_t *a_ptr = A + (int64_t)(row0 + (lane % 32)) * n_pad + (lane / 32) * 8;
-    const uint16_t *b_ptr[kColBlocksPerWg];
+    const bf16x8 *a_ptr[RB];
 #pragma unroll
-    for (int c = 0; c < kColBlocksPerWg; ++c) {
-        const int jb = min(jb0 + c, n_jb - 1);   // clamp: surplus column blocks recompute the last one and are not stored
-        b_ptr[c] = packed + ((int64_t)jb * KB * 64 + lane) * 8;
+    for (int r = 0; r < RB; ++r) a_ptr[r] = (const bf16x8 *)Ap + ((int64_t)(rb0 + r) * KB) * 64 + lane;
+    const bf16x8 *b_src[RPW];
+    int b_rec[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        b_rec[i] = wid * RPW + i;                               // record = jb * 4 + kb within the stage
+        const int jb = min(jb0 + b_rec[i] / 4, n_jb - 1);       // surplus column blocks recompute the last one
+        b_src[i] = (const bf16x8 *)Mp + ((int64_t)jb * KB + b_rec[i] % 4) * 64 + lane;
     }
-    for (int kb = 0; kb < KB; ++kb) {
-        bf16x8 a[RB], b[kColBlocksPerWg];
+    // Loads return to a wavefront in issue order, so every load inherits the latency of the slowest one before
+    // it.  The B records come from HBM: they are requested three stages ahead and kept in a ring of registers;
+    // the A records (L2) one stage ahead, and always BEFORE the B request of the same stage, so that waiting for
+    // them never waits for the youngest B request.
+    bf16x8 a_even[RB][4], a_odd[RB][4], b_ring[3][RPW];
 #pragma unroll
-        for (int r = 0; r < RB; ++r) a[r] = *(const bf16x8 *)(a_ptr + (int64_t)r * 32 * n_pad + kb * kKStep);
+    for (int t = 0; t < 3; ++t)
 #pragma unroll
-        for (int c = 0; c < kColBlocksPerWg; ++c) b[c] = *(const bf16x8 *)(b_ptr[c] + (int64_t)kb * 64 * 8);
+        for (int i = 0; i < RPW; ++i) b_ring[t][i] = b_src[i][(int64_t)min(t, stages - 1) * 4 * 64];
 #pragma unroll
-        for (int r = 0; r < RB; ++r)
+    for (int r = 0; r < RB; ++r)
 #pragma unroll
-            for (int c = 0; c < kColBlocksPerWg; ++c)
-                acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[r], b[c], acc[r][c], 0, 0, 0);
+        for (int kb = 0; kb < 4; ++kb) a_even[r][kb] = a_ptr[r][kb * 64];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) bbuf[0][b_rec[i]][lane] = b_ring[0][i];
+    __syncthreads();
+
+    // one stage: SLOT = s % 3 selects the ring entry that is free for the request three stages ahead; ACUR / ANXT
+    // are the A registers of this and of the next stage (they swap roles every stage: no copies)
+#define RDK_STAGE(SLOT, ACUR, ANXT)                                                                                  \
+    {                                                                                                                \
+        const int cur = s & 1;                                                                                       \
+        const int64_t sa = min(s + 1, stages - 1), sb = min(s + 3, stages - 1);   /* clamped: no branches here */    \
+        _Pragma("unroll") for (int r = 0; r < RB; ++r)                                                               \
+            _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) ANXT[r][kb] = a_ptr[r][(sa * 4 + kb) * 64];             \
+        _Pragma("unroll") for (int i = 0; i < RPW; ++i) b_ring[SLOT][i] = b_src[i][sb * 4 * 64];                     \
+        __builtin_amdgcn_sched_barrier(0);   /* keep the requests ahead of the MFMAs of this stage */                \
+        bf16x8 bfrag = bbuf[cur][0][lane];                                                                           \
+        _Pragma("unroll") for (int f = 0; f < 16; ++f) {     /* f = kb * 4 + c; the next fragment is read first */   \
+            const int kb = f / 4, c = f % 4;                                                                         \
+            const bf16x8 bnow = bfrag;                                                                               \
+            if (f + 1 < 16) bfrag = bbuf[cur][((f + 1) % 4) * 4 + (f + 1) / 4][lane];                                \
+            _Pragma("unroll") for (int r = 0; r < RB; ++r)                                                           \
+                acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ACUR[r][kb], bnow, acc[r][c], 0, 0, 0);          \
+        }                                                                                                            \
+        _Pragma("unroll") for (int i = 0; i < RPW; ++i) bbuf[cur ^ 1][b_rec[i]][lane] = b_ring[(SLOT + 1) % 3][i];   \
+        __syncthreads();                                                                                             \
+        ++s;                                                                                                         \
     }
+    // the number of stages is a multiple of six (the slot count is padded for it): six stages of straight-line code
+    for (int s = 0; s < stages;) {
+        RDK_STAGE(0, a_even, a_odd)
+        RDK_STAGE(1, a_odd, a_even)
+        RDK_STAGE(2, a_even, a_odd)
+        RDK_STAGE(0, a_odd, a_even)
+        RDK_STAGE(1, a_even, a_odd)
+        RDK_STAGE(2, a_odd, a_even)
+    }
+#undef RDK_STAGE
     // D layout of the 32x32 tile: lane l holds column l % 32 and rows 8 * (v / 4) + 4 * (l / 32) + v % 4, v = 0..15
 #pragma unroll
     for (int r = 0; r < RB; ++r)
@@ -246,10 +304,18 @@ __global__ __launch_bounds__(256) void exact_bf16_kernel(const uint16_t *A, int 
             if (jb0 + c >= n_jb || j >= N) continue;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int b = row0 + r * 32 + 8 * (v / 4) + 4 * (lane / 32) + (v % 4);
+                const int b = (rb0 + r) * 32 + 8 * (v / 4) + 4 * (lane / 32) + (v % 4);
                 if (b < B) out[(int64_t)b * ldo + j] = acc[r][c][v] * out_scale[b];
             }
         }
+}
+
+// wavefronts per workgroup and row blocks per wavefront for a batch of B positions
+inline void bf16_shape(int B, int &W, int &RB)
+{
+    if (B <= 128) { W = 4; RB = 1; }
+    else if (B <= 256) { W = 8; RB = 1; }
+    else { W = 8; RB = 2; }
 }
 
 struct ExactWs {
@@ -268,8 +334,6 @@ int f32_splits(const KernelHandle &h, int B)
     if (want > 32) want = 32;
     return want < 1 ? 1 : want;
 }
-
-int bf16_row_blocks(int B) { return B <= 128 ? 1 : B <= 256 ? 2 : 4; }
 
 template <int QK>
 rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out, int64_t ldo, void *ws, hipStream_t st)
@@ -309,31 +373,29 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
         return RDK_OK;
     }
     // bf16
-    const int rb = bf16_row_blocks(B);
-    const int rows_per_wg = 128 * rb;
+    int W, RB;
+    bf16_shape(B, W, RB);
+    const int rows_per_wg = W * RB * 32;
     const int B_pad = (B + rows_per_wg - 1) / rows_per_wg * rows_per_wg;
+    const int KB = h.n_pad / kKStep;
     w.A = (uint16_t *)p; p += align_up((size_t)B_pad * h.n_pad * 2, 256);
     w.out_scale = (float *)p;
     {
         TimedLaunch timed("prep_a_bf16_kernel", st);
-        hipLaunchKernelGGL((prep_a_bf16_kernel<QK>), dim3(B_pad), dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.row_sum, h.n, h.n_pad,
-                           B, w.A, w.out_scale);
+        hipLaunchKernelGGL((prep_a_bf16_kernel<QK>), dim3(B_pad), dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.row_sum, h.n, KB, B,
+                           w.A, w.out_scale);
     }
     RDK_LAUNCH_CHECK("prep_a_bf16_kernel");
     const int n_jb = (h.N + kColBlock - 1) / kColBlock;
     dim3 grid((n_jb + kColBlocksPerWg - 1) / kColBlocksPerWg, B_pad / rows_per_wg);
-    const int KB = h.n_pad / kKStep;
     {
         TimedLaunch timed("exact_bf16_kernel", st);
-        if (rb == 1)
-            hipLaunchKernelGGL((exact_bf16_kernel<1>), grid, dim3(256), 0, st, w.A, h.n_pad, h.packed, KB, h.N, B, w.out_scale,
-                               out, ldo);
-        else if (rb == 2)
-            hipLaunchKernelGGL((exact_bf16_kernel<2>), grid, dim3(256), 0, st, w.A, h.n_pad, h.packed, KB, h.N, B, w.out_scale,
-                               out, ldo);
+        if (W == 4)
+            hipLaunchKernelGGL((exact_bf16_kernel<4, 1>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
+        else if (RB == 1)
+            hipLaunchKernelGGL((exact_bf16_kernel<8, 1>), grid, dim3(512), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
         else
-            hipLaunchKernelGGL((exact_bf16_kernel<4>), grid, dim3(256), 0, st, w.A, h.n_pad, h.packed, KB, h.N, B, w.out_scale,
-                               out, ldo);
+            hipLaunchKernelGGL((exact_bf16_kernel<8, 2>), grid, dim3(512), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
     }
     RDK_LAUNCH_CHECK("exact_bf16_kernel");
     return RDK_OK;
@@ -343,7 +405,7 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
 
 size_t packed_bf16_bytes(int32_t n, int32_t N, int32_t *n_pad, int32_t *N_pad)
 {
-    const int32_t np = (n + kKStep - 1) / kKStep * kKStep;
+    const int32_t np = (n + 24 * kKStep - 1) / (24 * kKStep) * (24 * kKStep);   // six whole stages of four MFMA steps
     const int32_t Np = (N + kColBlock - 1) / kColBlock * kColBlock;
     if (n_pad) *n_pad = np;
     if (N_pad) *N_pad = Np;
@@ -357,7 +419,9 @@ size_t exact_workspace_bytes(const KernelHandle &h, int32_t B)
         const int splits = f32_splits(h, B);
         if (splits > 1) bytes += align_up((size_t)splits * B * ((h.N + 3) / 4 * 4) * sizeof(float), 256);
     } else if (h.format == RDK_DENSE_BF16) {
-        const int rows_per_wg = 128 * bf16_row_blocks(B);
+        int W, RB;
+        bf16_shape(B, W, RB);
+        const int rows_per_wg = W * RB * 32;
         const size_t B_pad = (size_t)(B + rows_per_wg - 1) / rows_per_wg * rows_per_wg;
         bytes += align_up(B_pad * h.n_pad * 2, 256) + align_up((size_t)B * sizeof(float), 256);
     }

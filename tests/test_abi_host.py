@@ -61,7 +61,7 @@ def test_storage_query_and_validation(rdk):
     # [N-n, 16] (slot, weight) pairs (k = 8 padded to 16 entries) and the diagonal weights
     assert sb.value == head + up(768 * 16 * 8 + 512) + 1024
     assert q(_desc(rdk, format=rdk.DENSE_F32)) == 0 and sb.value == head + 256 * 1024 * 4
-    assert q(_desc(rdk, format=rdk.DENSE_BF16)) == 0 and sb.value == head + 256 * 1024 * 2 + 1024
+    assert q(_desc(rdk, format=rdk.DENSE_BF16)) == 0 and sb.value == head + 384 * 1024 * 2 + 1024
     assert wb.value > 256 * 1024 * 4                       # the fp32 matrix that gets packed
     assert q(_desc(rdk, format=rdk.IDENTITY, embeddings=None)) == 0 and sb.value == head
     assert q(_desc(rdk, n=0)) == 2 and q(_desc(rdk, n=2000)) == 2 and q(_desc(rdk, k=65)) == 2
