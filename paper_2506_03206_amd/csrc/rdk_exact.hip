@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t
 //   * A records come straight from global memory (L2-resident: every workgroup walks the slots at the same pace),
 //   * the 16 B records of a stage are fetched once per workgroup, parked in LDS (double buffered) and read by all
 //     wavefronts: the vector memory pipe of a CU could not feed every wavefront its own copy;
-//   * the loads of stage s+1 are issued before the MFMAs of stage s; two wavefronts per SIMD cover the rest.
+//   * requests run two (A) and three (B) stages ahead of the MFMAs; two wavefronts per SIMD cover the rest.
 // M is streamed from HBM exactly once when all positions fit one row of workgroups (B <= 512).
 template <int W, int RB>
 __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, const uint16_t *Mp, int KB, int N, int B,
@@ -247,9 +247,9 @@ __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, 
         b_src[i] = (const bf16x8 *)Mp + ((int64_t)jb * KB + b_rec[i] % 4) * 64 + lane;
     }
     // Loads return to a wavefront in issue order, so every load inherits the latency of the slowest one before
-    // it.  The B records come from HBM: they are requested three stages ahead and kept in a ring of registers;
-    // the A records (L2) one stage ahead, and always BEFORE the B request of the same stage, so that waiting for
-    // them never waits for the youngest B request.
+    // it.  The B records come from HBM: they are requested three stages ahead and kept in a ring of registers.
+    // The A records (L2) are requested two stages ahead, block by block as their registers fall free; the only
+    // B request older than an A record at the time it is needed is then two whole stages old.
     bf16x8 a_even[RB][4], a_odd[RB][4], b_ring[3][RPW];
 #pragma unroll
     for (int t = 0; t < 3; ++t)
@@ -258,28 +258,37 @@ __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, 
 #pragma unroll
     for (int r = 0; r < RB; ++r)
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) a_even[r][kb] = a_ptr[r][kb * 64];
+        for (int kb = 0; kb < 4; ++kb) {
+            a_even[r][kb] = a_ptr[r][kb * 64];
+            a_odd[r][kb] = a_ptr[r][((int64_t)min(1, stages - 1) * 4 + kb) * 64];
+        }
 #pragma unroll
     for (int i = 0; i < RPW; ++i) bbuf[0][b_rec[i]][lane] = b_ring[0][i];
     __syncthreads();
 
-    // one stage: SLOT = s % 3 selects the ring entry that is free for the request three stages ahead; ACUR / ANXT
-    // are the A registers of this and of the next stage (they swap roles every stage: no copies)
-#define RDK_STAGE(SLOT, ACUR, ANXT)                                                                                  \
+    // One stage.  SLOT = s % 3 is the ring entry free for the B request three stages ahead.  ACUR holds the A
+    // records of this stage; as soon as the MFMAs of one slot block are issued, its registers take the request
+    // for the same block TWO stages ahead (even and odd stages own one register set each), so twice as many A
+    // bytes are in flight as with whole-stage double buffering.  All indices are clamped: no branches.
+#define RDK_STAGE(SLOT, ACUR)                                                                                        \
     {                                                                                                                \
         const int cur = s & 1;                                                                                       \
-        const int64_t sa = min(s + 1, stages - 1), sb = min(s + 3, stages - 1);   /* clamped: no branches here */    \
-        _Pragma("unroll") for (int r = 0; r < RB; ++r)                                                               \
-            _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) ANXT[r][kb] = a_ptr[r][(sa * 4 + kb) * 64];             \
+        const int64_t sa = min(s + 2, stages - 1), sb = min(s + 3, stages - 1);                                      \
         _Pragma("unroll") for (int i = 0; i < RPW; ++i) b_ring[SLOT][i] = b_src[i][sb * 4 * 64];                     \
-        __builtin_amdgcn_sched_barrier(0);   /* keep the requests ahead of the MFMAs of this stage */                \
-        bf16x8 bfrag = bbuf[cur][0][lane];                                                                           \
-        _Pragma("unroll") for (int f = 0; f < 16; ++f) {     /* f = kb * 4 + c; the next fragment is read first */   \
+        __builtin_amdgcn_sched_barrier(0);                                                                           \
+        bf16x8 bq[3];                        /* B fragments are read from LDS two MFMA groups ahead */               \
+        bq[0] = bbuf[cur][0][lane];                                                                                  \
+        bq[1] = bbuf[cur][4][lane];                                                                                  \
+        _Pragma("unroll") for (int f = 0; f < 16; ++f) {     /* f = kb * 4 + c */                                    \
             const int kb = f / 4, c = f % 4;                                                                         \
-            const bf16x8 bnow = bfrag;                                                                               \
-            if (f + 1 < 16) bfrag = bbuf[cur][((f + 1) % 4) * 4 + (f + 1) / 4][lane];                                \
+            if (f + 2 < 16) bq[(f + 2) % 3] = bbuf[cur][((f + 2) % 4) * 4 + (f + 2) / 4][lane];                      \
             _Pragma("unroll") for (int r = 0; r < RB; ++r)                                                           \
-                acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ACUR[r][kb], bnow, acc[r][c], 0, 0, 0);          \
+                acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ACUR[r][kb], bq[f % 3], acc[r][c], 0, 0, 0);     \
+            if (c == 3) {                                                                                            \
+                __builtin_amdgcn_sched_barrier(0);                                                                   \
+                _Pragma("unroll") for (int r = 0; r < RB; ++r) ACUR[r][kb] = a_ptr[r][(sa * 4 + kb) * 64];           \
+                __builtin_amdgcn_sched_barrier(0);                                                                   \
+            }                                                                                                        \
         }                                                                                                            \
         _Pragma("unroll") for (int i = 0; i < RPW; ++i) bbuf[cur ^ 1][b_rec[i]][lane] = b_ring[(SLOT + 1) % 3][i];   \
         __syncthreads();                                                                                             \
@@ -287,12 +296,12 @@ __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, 
     }
     // the number of stages is a multiple of six (the slot count is padded for it): six stages of straight-line code
     for (int s = 0; s < stages;) {
-        RDK_STAGE(0, a_even, a_odd)
-        RDK_STAGE(1, a_odd, a_even)
-        RDK_STAGE(2, a_even, a_odd)
-        RDK_STAGE(0, a_odd, a_even)
-        RDK_STAGE(1, a_even, a_odd)
-        RDK_STAGE(2, a_odd, a_even)
+        RDK_STAGE(0, a_even)
+        RDK_STAGE(1, a_odd)
+        RDK_STAGE(2, a_even)
+        RDK_STAGE(0, a_odd)
+        RDK_STAGE(1, a_even)
+        RDK_STAGE(2, a_odd)
     }
 #undef RDK_STAGE
     // D layout of the 32x32 tile: lane l holds column l % 32 and rows 8 * (v / 4) + 4 * (l / 32) + v % 4, v = 0..15
