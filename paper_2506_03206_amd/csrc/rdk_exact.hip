@@ -214,7 +214,8 @@ __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t
 //   * A records come straight from global memory (L2-resident: every workgroup walks the slots at the same pace),
 //   * the 16 B records of a stage are fetched once per workgroup, parked in LDS (double buffered) and read by all
 //     wavefronts: the vector memory pipe of a CU could not feed every wavefront its own copy;
-//   * requests run two (A) and three (B) stages ahead of the MFMAs; two wavefronts per SIMD cover the rest.
+//   * requests run two (A) and three (B) stages ahead of the MFMAs; large batches use one wavefront per SIMD with
+//     the whole register file (accumulators in the AGPR half), which halves the LDS reads per MFMA.
 // M is streamed from HBM exactly once when all positions fit one row of workgroups (B <= 512).
 template <int W, int RB>
 __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, const uint16_t *Mp, int KB, int N, int B,
@@ -324,7 +325,7 @@ inline void bf16_shape(int B, int &W, int &RB)
 {
     if (B <= 128) { W = 4; RB = 1; }
     else if (B <= 256) { W = 8; RB = 1; }
-    else { W = 8; RB = 2; }
+    else { W = 4; RB = 4; }   // one wavefront per SIMD with all 512 registers: half the LDS reads per MFMA
 }
 
 struct ExactWs {
@@ -399,12 +400,12 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
     dim3 grid((n_jb + kColBlocksPerWg - 1) / kColBlocksPerWg, B_pad / rows_per_wg);
     {
         TimedLaunch timed("exact_bf16_kernel", st);
-        if (W == 4)
+        if (W == 4 && RB == 1)
             hipLaunchKernelGGL((exact_bf16_kernel<4, 1>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
-        else if (RB == 1)
+        else if (W == 8)
             hipLaunchKernelGGL((exact_bf16_kernel<8, 1>), grid, dim3(512), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
         else
-            hipLaunchKernelGGL((exact_bf16_kernel<8, 2>), grid, dim3(512), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
+            hipLaunchKernelGGL((exact_bf16_kernel<4, 4>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
     }
     RDK_LAUNCH_CHECK("exact_bf16_kernel");
     return RDK_OK;

@@ -201,6 +201,41 @@ def test_exact_bf16(rdk, tiny, ragged, case):
     assert np.abs(out.astype(np.float64).sum(1) - 1).max() < 2e-5
 
 
+@pytest.mark.parametrize("B", [130, 300, 530])
+def test_exact_bf16_batch_shapes(rdk, ragged, B):
+    """The dense bf16 product picks its workgroup shape from the batch size: one case per shape, the largest
+    spanning two rows of workgroups with a ragged last one."""
+    w = ragged["w"]
+    M32 = ragged["dense"].astype(np.float32)
+    kern = rdk.rdk_build_kernel(w.N, dev(ragged["kept_ids"]), rdk.DENSE_BF16, dense_M=dev(M32))
+    # Rows of integer counts c / 2^15 with c <= 255 and sum(c) = 2^15: every value and every partial sum is exact in
+    # bf16 and fp32, so the rounding of the normalised row to bf16 cannot fall on different sides of a tie on the
+    # two sides (a flipped dominant slot would move an output by half a bf16 ulp, far beyond the tolerance).
+    rng = np.random.default_rng(100 + B)
+    c = rng.integers(0, 128, size=(B, w.n))
+    for b in range(B):
+        order = rng.permutation(w.n)
+        diff, t = (1 << 15) - int(c[b].sum()), 0
+        while diff != 0:
+            i, step = order[t % w.n], (1 if diff > 0 else -1)
+            if 0 <= c[b, i] + step <= 255:
+                c[b, i] += step
+                diff -= step
+            t += 1
+    c[0] = 0
+    c[0, w.n // 2] = 1 << 15                                     # a one-hot row
+    q = (c / float(1 << 15)).astype(np.float32)
+    assert np.all(q.sum(1, dtype=np.float64) == 1.0) and np.array_equal(synth.bf16_round(q), q)
+    out = rdk.rdk_redistribute_exact(kern, dev(q)).cpu().numpy()
+    Mb = synth.bf16_round(M32).astype(np.float64)
+    ref = np.empty((B, w.N))
+    for b in range(B):
+        qb = synth.bf16_round(oracle.tli(q[b]).astype(np.float32))
+        r = oracle.redistribute_dense(qb, Mb)
+        ref[b] = r / r.sum()
+    assert_close(out, ref, rtol=2e-5, atol=ATOL, what="exact bf16, B=%d" % B)
+
+
 # --------------------------------------------------------------------------------------------- verification
 def check_verify_outputs(o, ref, p64, q64, seed, offset, gamma, p_kind, min_exact=0.95):
     """Device outputs `o` of a verification against the oracle's `ref` for target rows p64 and drafter rows q64."""
