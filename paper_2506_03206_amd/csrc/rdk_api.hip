@@ -67,7 +67,7 @@ bool kind_ok(rdk_input_kind_t k) { return k == RDK_PROB_F32 || k == RDK_LOGIT_F3
 int32_t nbr_row_len(int32_t k) { return ((k < 1 ? 1 : k) + 15) / 16 * 16; }
 
 struct StorageLayout {
-    size_t kept_ids, slot_of, pruned_ids, body, body2, body3, total;
+    size_t kept_ids, slot_of, pruned_ids, chunk_lo, body, body2, body3, total;
     int32_t kk, n_pad, N_pad;
     int64_t ldm;
 };
@@ -110,6 +110,7 @@ StorageLayout layout_of(const rdk_kernel_desc_t &d)
     L.kept_ids = off; off += align_up((size_t)d.n * 4, 256);
     L.slot_of = off; off += align_up((size_t)d.N * 4, 256);
     L.pruned_ids = off; off += align_up((size_t)(d.N - d.n + 1) * 4, 256);
+    L.chunk_lo = off; off += align_up((size_t)((d.N + kChunk - 1) / kChunk + 1) * 4, 256);
     L.kk = nbr_row_len(d.k);
     L.ldm = ((int64_t)d.N + 3) / 4 * 4;
     switch (d.format) {
@@ -217,6 +218,10 @@ rdk_status_t rdk_build_kernel(const rdk_kernel_desc_t *desc, void *storage, size
     int32_t *pruned = (int32_t *)(sp + L.pruned_ids);
     h.pruned_ids = pruned;
     rc = launch_pruned_ids(slot_of, d.N, pruned, st);
+    if (rc != RDK_OK) return rc;
+    int32_t *chunk_lo = (int32_t *)(sp + L.chunk_lo);
+    h.chunk_lo = chunk_lo;
+    rc = launch_chunk_lo(kept, d.n, d.N, chunk_lo, st);
     if (rc != RDK_OK) return rc;
 
     if (d.format == RDK_SPARSE_TOPK) {

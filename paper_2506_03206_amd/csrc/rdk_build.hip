@@ -80,6 +80,22 @@ __global__ void inv_norm_kernel(const float *E, int N, int d, double *inv_norm)
     if (lane_id() == 0) inv_norm[j] = 1.0 / sqrt(s);
 }
 
+// chunk_lo[c] = number of kept ids below c * kChunk (kept ids ascend, so the ids of chunk c hold the slots
+// chunk_lo[c] .. chunk_lo[c + 1] - 1, a contiguous piece of every drafter row).
+__global__ void chunk_lo_kernel(const int32_t *kept_ids, int n, int nchunks, int32_t *chunk_lo)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c > nchunks) return;
+    const int64_t first = (int64_t)c * kChunk;
+    int lo = 0, hi = n;   // lower bound of `first` in kept_ids
+    while (lo < hi) {
+        const int mid = (lo + hi) / 2;
+        if (kept_ids[mid] < first) lo = mid + 1;
+        else hi = mid;
+    }
+    chunk_lo[c] = lo;
+}
+
 __global__ void pruned_ids_kernel(const int32_t *slot_of, int N, int32_t *pruned_ids)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -344,6 +360,14 @@ rdk_status_t launch_check_kept(const int32_t *kept_ids, int32_t n, int32_t N, in
     hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, st, flag);
     hipLaunchKernelGGL(check_kept_kernel, dim3((n + 255) / 256), dim3(256), 0, st, kept_ids, n, N, flag);
     RDK_LAUNCH_CHECK("check_kept_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_chunk_lo(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *chunk_lo, hipStream_t st)
+{
+    const int nchunks = (N + kChunk - 1) / kChunk;
+    hipLaunchKernelGGL(chunk_lo_kernel, dim3((nchunks + 256) / 256), dim3(256), 0, st, kept_ids, n, nchunks, chunk_lo);
+    RDK_LAUNCH_CHECK("chunk_lo_kernel");
     return RDK_OK;
 }
 

@@ -16,6 +16,7 @@ struct KernelHandle {
     int32_t N, n, k;
     rdk_kernel_format_t format;
     const int32_t *kept_ids;  // [n]
+    const int32_t *chunk_lo;  // [ceil(N / kChunk) + 1]: kept ids below c * kChunk, i.e. the first slot of chunk c
     const int32_t *slot_of;   // [N]  >= 0: kept slot;  < 0: -(pruned slot + 1)
     // sparse: per pruned slot a row of kk (kept slot, weight) pairs, k real ones then (0, 0) padding
     const int32_t *pruned_ids;  // [N-n] ascending target ids that are not kept
@@ -81,6 +82,7 @@ struct TimedLaunch {
 size_t build_workspace_bytes(const rdk_kernel_desc_t &d);
 rdk_status_t launch_slot_of(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *slot_of, hipStream_t st);
 rdk_status_t launch_check_kept(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *flag, hipStream_t st);
+rdk_status_t launch_chunk_lo(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *chunk_lo, hipStream_t st);
 rdk_status_t launch_pruned_ids(const int32_t *slot_of, int32_t N, int32_t *pruned_ids, hipStream_t st);
 rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *pruned_ids, int2 *nbr, float *self_w,
                                  int32_t kk, void *ws, hipStream_t st);

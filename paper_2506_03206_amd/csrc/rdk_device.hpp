@@ -9,31 +9,68 @@ namespace rdk {
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
-// ---- 64-wide reductions through cross-lane shuffles
+// ---- 64-wide reductions and scans on the data-parallel-primitive (DPP) modifiers of the vector ALU: a lane
+// reads another lane of its row of 16 at register speed, where a shuffle goes through the LDS crossbar (an
+// order of magnitude more latency, which a lone wavefront cannot hide).  Controls: 0xB1 / 0x4E = quad
+// permutations [1,0,3,2] / [2,3,0,1], 0x141 / 0x140 = mirror within 8 / 16 lanes, 0x110 + n = shift right by n
+// within the row, 0x142 / 0x143 = lane 15 of each row to the next row / lane 31 to rows 2 and 3.
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp_move(float v)   // lanes without a source (or outside ROW_MASK) get 0
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false));
+}
+
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ double dpp_move(double v)
+{
+    const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)b, CTRL, ROW_MASK, 0xf, false);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(b >> 32), CTRL, ROW_MASK, 0xf, false);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+
+// value of lane `src` (the same for all lanes) in every lane
+__device__ __forceinline__ int lane_value(int v, int src) { return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(src)); }
+__device__ __forceinline__ float lane_value(float v, int src)
+{
+    return __builtin_bit_cast(float, lane_value(__builtin_bit_cast(int, v), src));
+}
+__device__ __forceinline__ double lane_value(double v, int src)
+{
+    const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)lane_value((int)(unsigned)b, src), hi = (unsigned)lane_value((int)(unsigned)(b >> 32), src);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+
+// sum over the 64 lanes, the same bits in every lane
 template <typename T>
 __device__ __forceinline__ T wave_sum(T v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);   // every lane holds the sum of its row of 16
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    return v;
+    v = fmaxf(v, dpp_move<0xB1>(v));
+    v = fmaxf(v, dpp_move<0x4E>(v));
+    v = fmaxf(v, dpp_move<0x141>(v));
+    v = fmaxf(v, dpp_move<0x140>(v));
+    return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
 
-// Inclusive prefix sum over the 64 lanes (Hillis-Steele on shuffles).
+// Inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row, then the row totals are handed on.
 __device__ __forceinline__ double wave_inclusive_scan(double v)
 {
-    const int lane = lane_id();
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        double t = __shfl_up(v, off, kWave);
-        if (lane >= off) v += t;
-    }
+    v += dpp_move<0x111>(v);
+    v += dpp_move<0x112>(v);
+    v += dpp_move<0x114>(v);
+    v += dpp_move<0x118>(v);
+    v += dpp_move<0x142, 0xa>(v);   // rows 1 and 3 take the total of the row before
+    v += dpp_move<0x143, 0xc>(v);   // rows 2 and 3 take the total of rows 0 and 1
     return v;
 }
 

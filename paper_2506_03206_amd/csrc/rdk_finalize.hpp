@@ -8,7 +8,10 @@
 //   3. re-reads (or re-computes) those blocks and scans them in fp64 for the exact ids,
 //   4. decides acceptance in fp64, and, when a workgroup holds one whole sequence, runs the
 //      first-rejection scan.
-// Where q' comes from is the `QP` policy: memory (a materialised q' row) or a formula.
+// Where q' comes from is the `QP` policy: memory (a materialised q' row) or a formula.  A policy hands out q' of
+// four consecutive ids in kStages steps on a `Pending` record, each step issuing the loads whose addresses the
+// step before produced; the kernel runs step k for ALL blocks it needs before step k + 1, so a chain of dependent
+// loads costs kStages round trips in total rather than per block.
 #pragma once
 #include "rdk_rowstats.hpp"
 
@@ -34,6 +37,7 @@ struct FinalizeArgs {
 // q' read back from memory.
 struct QpMemory {
     static constexpr bool kSpreadRows = false;
+    static constexpr int kStages = 1;
     const float *q;
     int64_t ldq;
     bool vec;
@@ -42,18 +46,40 @@ struct QpMemory {
         const float *qr;
         bool vec;
         int N;
-        __device__ __forceinline__ float4 load4(int64_t idx) const { return rdk::load4<RDK_PROB_F32>(qr, idx, N, vec, 0.f); }
+        struct Pending {
+            float4 v;
+        };
+        template <int K>
+        __device__ __forceinline__ void stage(Pending &t, int64_t idx) const
+        {
+            t.v = rdk::load4<RDK_PROB_F32>(qr, idx, N, vec, 0.f);
+        }
+        __device__ __forceinline__ float4 result(const Pending &t, int64_t) const { return t.v; }
         __device__ __forceinline__ float load1(int j) const { return qr[j]; }
     };
     __device__ __forceinline__ Row row(int64_t b) const { return Row{q + b * ldq, vec, N}; }
 };
 
+// Runs step K of the policy on the SUB records of one block (nothing when the block is not wanted).
+template <int K, int SUB, class Row>
+__device__ __forceinline__ void stage_block(const Row &r, typename Row::Pending (&t)[SUB], int base, bool wanted)
+{
+    if (!wanted) return;
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) r.template stage<K>(t[i], (int64_t)base + i * 256 + lane_id() * 4);
+}
+
 __device__ __forceinline__ double lane_partial_sum(const float *part, int nblk, int per_lane)
 {
     const int c0 = lane_id() * per_lane;
     double s = 0.0;
-    for (int t = 0; t < per_lane; ++t)
-        if (c0 + t < nblk) s += (double)part[c0 + t];
+    for (int t = 0; t < per_lane; t += 4) {   // four loads in flight at a time
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) v[x] = (t + x < per_lane && c0 + t + x < nblk) ? part[c0 + t + x] : 0.f;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) s += (double)v[x];
+    }
     return s;
 }
 
@@ -79,9 +105,63 @@ __device__ __forceinline__ int locate_block(const float *part, int nblk, int per
             pre += v;
         }
     }
-    blk = __shfl(blk, src, kWave);
-    prefix_before = __shfl(pre, src, kWave);
+    blk = lane_value(blk, src);
+    prefix_before = lane_value(pre, src);
     return blk;
+}
+
+// The same on partials that the lanes already hold in registers (at most kRegBlocks per lane): saves the
+// dependent re-read.  v[t] = partial of block lane * per_lane + t (0 beyond nblk).
+constexpr int kRegBlocks = 8;
+
+__device__ __forceinline__ void load_partials(const float *part, int nblk, int per_lane, float (&v)[kRegBlocks])
+{
+    const int c0 = lane_id() * per_lane;
+#pragma unroll
+    for (int t = 0; t < kRegBlocks; ++t) v[t] = (t < per_lane && c0 + t < nblk) ? part[c0 + t] : 0.f;
+}
+
+__device__ __forceinline__ double sum_partials(const float (&v)[kRegBlocks])
+{
+    double s = 0.0;
+#pragma unroll
+    for (int t = 0; t < kRegBlocks; ++t) s += (double)v[t];
+    return s;
+}
+
+__device__ __forceinline__ int locate_block_regs(const float (&v)[kRegBlocks], int nblk, int per_lane, double lane_sum, double thr,
+                                                 double &prefix_before)
+{
+    const double incl = wave_inclusive_scan(lane_sum);
+    const unsigned long long hits = __ballot(incl > thr);
+    if (hits == 0ull) return -1;
+    const int src = __ffsll(hits) - 1;
+    const int c0 = lane_id() * per_lane;
+    int blk = -1;
+    double pre = incl - lane_sum;
+#pragma unroll
+    for (int t = 0; t < kRegBlocks; ++t) {
+        const double x = (double)v[t];
+        const bool here = blk < 0 && t < per_lane && c0 + t < nblk && pre + x > thr;
+        if (here) blk = c0 + t;
+        if (blk < 0) pre += x;
+    }
+    blk = lane_value(blk, src);
+    prefix_before = lane_value(pre, src);
+    return blk;
+}
+
+// Element (i, e) of a lane's block registers: sub-block i, component e, both run-time values.
+template <int SUB>
+__device__ __forceinline__ float pick(const float4 (&w)[SUB], int i, int e)
+{
+    float r = 0.f;
+#pragma unroll
+    for (int ii = 0; ii < SUB; ++ii) {
+        const float t = e == 0 ? w[ii].x : e == 1 ? w[ii].y : e == 2 ? w[ii].z : w[ii].w;
+        r = ii == i ? t : r;
+    }
+    return r;
 }
 
 // Smallest id of the block whose inclusive prefix of weights exceeds thr_local; if rounding leaves none,
@@ -102,15 +182,15 @@ __device__ __forceinline__ int search_block(const float4 (&wv)[SUB], int base, d
         if (hits != 0ull) {
             const int src = __ffsll(hits) - 1;
             const int e = (excl + l0 > thr_local) ? 0 : (excl + l1 > thr_local) ? 1 : (excl + l2 > thr_local) ? 2 : 3;
-            return __shfl(idx + e, src, kWave);
+            return lane_value(idx + e, src);
         }
         const int mine = wv[i].w > 0.f ? 3 : wv[i].z > 0.f ? 2 : wv[i].y > 0.f ? 1 : wv[i].x > 0.f ? 0 : -1;
         const unsigned long long pos = __ballot(mine >= 0);
         if (pos != 0ull) {
             const int src = 63 - __clzll(pos);
-            last_positive = __shfl(idx + mine, src, kWave);
+            last_positive = lane_value(idx + mine, src);
         }
-        carried += __shfl(incl, kWave - 1, kWave);
+        carried += lane_value(incl, kWave - 1);
     }
     return last_positive;
 }
@@ -118,7 +198,7 @@ __device__ __forceinline__ int search_block(const float4 (&wv)[SUB], int base, d
 constexpr int kFinalizeRows = 8;   // rows (wavefronts) per workgroup at most: leaves 256 VGPRs per lane
 
 template <int KIND, int SUB, bool HAS_Q, class QP>
-__global__ __launch_bounds__(kFinalizeRows * kWave) void verify_finalize_kernel(FinalizeArgs a, QP qp)
+__global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) void verify_finalize_kernel(FinalizeArgs a, QP qp)
 {
     __shared__ int32_t sh_draft[kFinalizeRows], sh_resid[kFinalizeRows];
     __shared__ uint8_t sh_acc[kFinalizeRows];
@@ -140,12 +220,27 @@ __global__ __launch_bounds__(kFinalizeRows * kWave) void verify_finalize_kernel(
         const float *prr = a.part_r + row * a.nblk;
         const float *pa = a.part_a + row * a.nblk;
         const bool draw_draft = HAS_Q && d.sample_draft;
-        const typename QP::Row qrow = qp.row(row);
 
-        // 1. block partials (one round trip), uniforms meanwhile
-        const double lane_r = lane_partial_sum(prr, a.nblk, per_lane);
-        const double lane_q = draw_draft ? lane_partial_sum(pq, a.nblk, per_lane) : 0.0;
-        const double lane_a = HAS_Q ? lane_partial_sum(pa, a.nblk, per_lane) : 0.0;
+        // 1. block partials (one round trip; kept in registers when they fit), the row's own constants and the
+        //    uniforms meanwhile
+        const bool in_regs = per_lane <= kRegBlocks;
+        float vq[kRegBlocks], vr[kRegBlocks], va[kRegBlocks];
+        double lane_r, lane_q = 0.0, lane_a = 0.0;
+        if (in_regs) {
+            load_partials(prr, a.nblk, per_lane, vr);
+            if (draw_draft) load_partials(pq, a.nblk, per_lane, vq);
+            if (HAS_Q) load_partials(pa, a.nblk, per_lane, va);
+        }
+        const typename QP::Row qrow = qp.row(row);
+        if (in_regs) {
+            lane_r = sum_partials(vr);
+            if (draw_draft) lane_q = sum_partials(vq);
+            if (HAS_Q) lane_a = sum_partials(va);
+        } else {
+            lane_r = lane_partial_sum(prr, a.nblk, per_lane);
+            if (draw_draft) lane_q = lane_partial_sum(pq, a.nblk, per_lane);
+            if (HAS_Q) lane_a = lane_partial_sum(pa, a.nblk, per_lane);
+        }
         int32_t dtok = (HAS_Q && !d.sample_draft) ? a.draft_ids[row] : -1;
         uint32_t words[4];
         position_words(d.seed, d.offset + (uint64_t)row, words);
@@ -158,30 +253,62 @@ __global__ __launch_bounds__(kFinalizeRows * kWave) void verify_finalize_kernel(
         int blk_d = -1, blk_r = -1;
         if (draw_draft && Q > 0.0) {
             thr_d = word_to_unit(words[0]) * Q;
-            blk_d = locate_block(pq, a.nblk, per_lane, lane_q, thr_d, before_d);
+            blk_d = in_regs ? locate_block_regs(vq, a.nblk, per_lane, lane_q, thr_d, before_d)
+                            : locate_block(pq, a.nblk, per_lane, lane_q, thr_d, before_d);
         }
         if (R > 0.0) {
             thr_r = word_to_unit(words[HAS_Q ? 2 : 3]) * R;
-            blk_r = locate_block(prr, a.nblk, per_lane, lane_r, thr_r, before_r);
+            blk_r = in_regs ? locate_block_regs(vr, a.nblk, per_lane, lane_r, thr_r, before_r)
+                            : locate_block(prr, a.nblk, per_lane, lane_r, thr_r, before_r);
         }
 
-        // 3. both blocks are fetched together, then scanned
-        float4 wd[SUB], wp[SUB], wq[SUB];
+        // 3. both blocks are fetched together (q' and the target weights of each), then scanned.  A draft token
+        //    that the caller supplied may lie anywhere: its two values are requested in the same round trip.
+        float4 wd[SUB], pd[SUB], wp[SUB], wq[SUB];
         const int base_d = max(blk_d, 0) * (SUB * 256), base_r = max(blk_r, 0) * (SUB * 256);
-#pragma unroll
-        for (int i = 0; i < SUB; ++i) {
-            if (draw_draft) wd[i] = qrow.load4(base_d + i * 256 + lane * 4);
-            wp[i] = load4<KIND>(pr, base_r + i * 256 + lane * 4, N, a.vec_p, pfill);
-            if (HAS_Q) wq[i] = (blk_r == blk_d && draw_draft) ? wd[i] : qrow.load4(base_r + i * 256 + lane * 4);
-        }
-        if (blk_d >= 0) dtok = search_block<SUB>(wd, base_d, thr_d - before_d);
-        // 4. the accept test needs p and q' at the draft token: issue those loads before the second scan
-        float pd_raw = 0.f, qd = 0.f;
-        const bool d_ok = HAS_Q && dtok >= 0 && dtok < N;
-        if (d_ok) {
-            pd_raw = load1<KIND>(pr, dtok);
+        const bool same = draw_draft && blk_r == blk_d;
+        float pd_w = 0.f, qd = 0.f;
+        const bool given = HAS_Q && !d.sample_draft && dtok >= 0 && dtok < N;
+        if (given) {
+            pd_w = to_weight<KIND>(load1<KIND>(pr, dtok), m, inv);
             qd = qrow.load1(dtok);
         }
+        typename QP::Row::Pending td[SUB], tr[SUB];
+        const bool want_r = HAS_Q && !same;
+        stage_block<0, SUB>(qrow, td, base_d, draw_draft);
+        stage_block<0, SUB>(qrow, tr, base_r, want_r);
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+            if (draw_draft) pd[i] = load4<KIND>(pr, base_d + i * 256 + lane * 4, N, a.vec_p, pfill);
+            if (!same) wp[i] = load4<KIND>(pr, base_r + i * 256 + lane * 4, N, a.vec_p, pfill);
+        }
+        if (QP::kStages > 1) {
+            stage_block<1, SUB>(qrow, td, base_d, draw_draft);
+            stage_block<1, SUB>(qrow, tr, base_r, want_r);
+        }
+        if (QP::kStages > 2) {
+            stage_block<2, SUB>(qrow, td, base_d, draw_draft);
+            stage_block<2, SUB>(qrow, tr, base_r, want_r);
+        }
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+            if (draw_draft) wd[i] = qrow.result(td[i], (int64_t)base_d + i * 256 + lane * 4);
+            if (want_r) wq[i] = qrow.result(tr[i], (int64_t)base_r + i * 256 + lane * 4);
+            if (same) {
+                wp[i] = pd[i];
+                wq[i] = wd[i];
+            }
+        }
+        if (blk_d >= 0) {
+            dtok = search_block<SUB>(wd, base_d, thr_d - before_d);
+            // 4. the accept test needs p and q' at the draft token: both sit in the registers of one lane
+            if (dtok >= 0) {
+                const int off = dtok - base_d, i = off / 256, src = (off % 256) / 4, e = off % 4;
+                qd = lane_value(pick<SUB>(wd, i, e), src);
+                pd_w = to_weight<KIND>(lane_value(pick<SUB>(pd, i, e), src), m, inv);
+            }
+        }
+        const bool d_ok = HAS_Q && dtok >= 0 && dtok < N;
         int32_t rtok = -1;
         if (blk_r >= 0) {
 #pragma unroll
@@ -200,7 +327,7 @@ __global__ __launch_bounds__(kFinalizeRows * kWave) void verify_finalize_kernel(
             rtok = search_block<SUB>(wp, base_r, thr_r - before_r);
         }
         uint8_t acc = 0;
-        if (d_ok) acc = (word_to_unit(words[1]) * (double)qd < (double)to_weight<KIND>(pd_raw, m, inv)) ? 1 : 0;
+        if (d_ok) acc = (word_to_unit(words[1]) * (double)qd < (double)pd_w) ? 1 : 0;
         if (lane == 0) {
             if (draw_draft) a.draft_ids[row] = dtok;
             a.accept[row] = acc;

@@ -33,6 +33,50 @@ LinearWs carve(const KernelHandle &h, int32_t B, void *ws)
 }
 
 // ------------------------------------------------------------------------------------------------
+// The kept ids ascend, so the kept ids inside one chunk of kChunk target ids own a contiguous run of slots
+// lo .. hi-1 (chunk_lo of the kernel handle).  A wavefront reads that run of the drafter row and of kept_ids with
+// coalesced loads and scatters it through a private LDS array into id order; afterwards lane l holds the raw
+// drafter values of the ids  base + i*256 + l*4 .. +3  (i = 0..3), the same ids whose target values it loads.
+// Ids that are not kept get `fill`, a raw value of weight zero.  This replaces one gather per id.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    // LDS operations of one wavefront execute in order: only the compiler has to be kept from moving them
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int QK>
+__device__ __forceinline__ void stage_chunk(float *lds, const void *qr, bool vec_q, int n, const int32_t *kept, int lo, int hi,
+                                            int base, float4 (&qd)[4])
+{
+    const int lane = lane_id();
+    const float fill = QK == RDK_PROB_F32 ? 0.f : -INFINITY;
+    float4 *l4 = (float4 *)lds;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) l4[i * kWave + lane] = make_float4(fill, fill, fill, fill);
+    wave_lds_sync();
+    for (int s = (lo & ~3) + lane * 4; s < hi; s += 4 * kWave) {
+        int4 kv = make_int4(0, 0, 0, 0);
+        if (s + 3 < n) {
+            kv = *(const int4 *)(kept + s);
+        } else {
+            if (s + 0 < n) kv.x = kept[s + 0];
+            if (s + 1 < n) kv.y = kept[s + 1];
+            if (s + 2 < n) kv.z = kept[s + 2];
+        }
+        const float4 qv = load4<QK>(qr, s, n, vec_q, fill);
+        const int ke[4] = {kv.x, kv.y, kv.z, kv.w};
+        const float qe[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (s + e >= lo && s + e < hi) lds[(ke[e] - base) & (kChunk - 1)] = qe[e];
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qd[i] = l4[i * kWave + lane];
+}
+
 // Eq. 3, first pass.  For the ids of one split of a row:
 //   Zq += q^_s, Tn += q^_s p_j, An += N q^_s / (N + p_j)   over kept ids j (slot s),
 //   Bs += p_j / (N + p_j)                                    over all ids j.
@@ -40,9 +84,10 @@ LinearWs carve(const KernelHandle &h, int32_t B, void *ws)
 //   pt_j = N q'_j / (N + p_j) + theta p_j / (N + p_j)  with q'_j = q^_s / Zq on kept ids, 0 elsewhere.
 template <int PK, int QK>
 __global__ __launch_bounds__(kThreads) void taylor_stats_kernel(const void *p, int64_t ldp, const void *q, int64_t ldq,
-                                                                const int32_t *slot_of, int N, int splits, bool vec_p,
-                                                                LinearWs w)
+                                                                const int32_t *kept, const int32_t *chunk_lo, int N, int n,
+                                                                int splits, bool vec_p, bool vec_q, LinearWs w)
 {
+    __shared__ __attribute__((aligned(16))) float qchunk[kWaves][kChunk];
     const int64_t row = blockIdx.x / splits;
     const int split = blockIdx.x % splits;
     const int nchunks = (N + kChunk - 1) / kChunk;
@@ -50,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void taylor_stats_kernel(const void *p, i
     const int c_begin = split * cpw, c_end = min(nchunks, c_begin + cpw);
     const void *pr = row_ptr<PK>(p, ldp, row);
     const void *qr = row_ptr<QK>(q, ldq, row);
-    const int wid = threadIdx.x / kWave, lane = lane_id();
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
     float pm = 0.f, pinv = 1.f;
     if (PK != RDK_PROB_F32) {
         const SoftStat rs = merged_row_stat<PK>(w.pstat, w.p_splits, row);
@@ -62,36 +107,28 @@ __global__ __launch_bounds__(kThreads) void taylor_stats_kernel(const void *p, i
     const float fN = (float)N;
     float zq = 0.f, tn = 0.f, an = 0.f, bs = 0.f;
     for (int c = c_begin + wid; c < c_end; c += kWaves) {
-        const int64_t base = (int64_t)c * kChunk + lane * 4;
+        const int base = c * kChunk;
+        float4 pv[4], qd[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pv[i] = load4<PK>(pr, (int64_t)base + i * 256 + lane * 4, N, vec_p, pfill);
+        stage_chunk<QK>(qchunk[wid], qr, vec_q, n, kept, chunk_lo[c], chunk_lo[c + 1], base, qd);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int64_t idx = base + i * 256;
-            const float4 pv = load4<PK>(pr, idx, N, vec_p, pfill);
-            const float pe[4] = {to_weight<PK>(pv.x, pm, pinv), to_weight<PK>(pv.y, pm, pinv),
-                                 to_weight<PK>(pv.z, pm, pinv), to_weight<PK>(pv.w, pm, pinv)};
-            int4 sv = make_int4(-1, -1, -1, -1);
-            if (idx + 3 < N) {
-                sv = *(const int4 *)(slot_of + idx);
-            } else {
-                if (idx + 0 < N) sv.x = slot_of[idx + 0];
-                if (idx + 1 < N) sv.y = slot_of[idx + 1];
-                if (idx + 2 < N) sv.z = slot_of[idx + 2];
-            }
-            const int se[4] = {sv.x, sv.y, sv.z, sv.w};
-            float qraw[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) qraw[e] = load1<QK>(qr, max(se[e], 0));   // unconditional: loads stay batched
+            const float pe[4] = {to_weight<PK>(pv[i].x, pm, pinv), to_weight<PK>(pv[i].y, pm, pinv),
+                                 to_weight<PK>(pv[i].z, pm, pinv), to_weight<PK>(pv[i].w, pm, pinv)};
+            const float qe[4] = {qd[i].x, qd[i].y, qd[i].z, qd[i].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float r = 1.0f / (fN + pe[e]);
+                const float r = __builtin_amdgcn_rcpf(fN + pe[e]);
                 bs += pe[e] * r;
-                const float qh = se[e] >= 0 ? to_weight<QK>(qraw[e], qm, 1.f) : 0.f;
+                const float qh = to_weight<QK>(qe[e], qm, 1.f);   // zero on ids that are not kept
                 zq += qh;
                 tn += qh * pe[e];
-                an += fN * qh * r;
+                an += qh * r;                                      // times N at the end
             }
         }
     }
+    an *= fN;
     zq = wave_sum(zq);
     tn = wave_sum(tn);
     an = wave_sum(an);
@@ -112,9 +149,9 @@ __global__ __launch_bounds__(kThreads) void taylor_stats_kernel(const void *p, i
 struct TaylorArgs {
     const void *p, *q;
     int64_t ldp, ldq;
-    const int32_t *slot_of;
-    int N, splits;
-    bool vec_p;
+    const int32_t *slot_of, *kept, *chunk_lo;
+    int N, n, splits;
+    bool vec_p, vec_q;
     LinearWs w;
 };
 
@@ -124,45 +161,58 @@ struct TaylorRow {
     const int32_t *slot_of;
     int N;
     bool vec_p;
-    float pm, pinv, qm, inv_zq, theta, inv_S, fN;
+    float pm, pinv, qm, inv_zq, theta, inv_S, fN, nzs, ths;   // nzs = N / (Zq S), ths = theta / S
 
-    // q' of ids idx .. idx+3 (Eq. 3) and the target weights of the same ids
-    __device__ __forceinline__ float4 eval4(int64_t idx, float4 &p_out) const
+    // Eq. 3 for one id: qh = unnormalised drafter weight of the id (0 if it is not kept), pe = its target weight
+    __device__ __forceinline__ float value(float qh, float pe) const
     {
-        const float4 pv = rdk::load4<PK>(pr, idx, N, vec_p, PK == RDK_PROB_F32 ? 0.f : -INFINITY);
-        const float pe[4] = {to_weight<PK>(pv.x, pm, pinv), to_weight<PK>(pv.y, pm, pinv), to_weight<PK>(pv.z, pm, pinv),
-                             to_weight<PK>(pv.w, pm, pinv)};
-        int4 sv = make_int4(-1, -1, -1, -1);
-        if (idx + 3 < N) {
-            sv = *(const int4 *)(slot_of + idx);
+        return (nzs * qh + ths * pe) * __builtin_amdgcn_rcpf(fN + pe);
+    }
+
+    // q' of ids idx .. idx+3 (Eq. 3) in two steps: target values and slots first, then the drafter values
+    struct Pending {
+        float4 pv;
+        int4 sv;
+        float qraw[4];
+    };
+    template <int K>
+    __device__ __forceinline__ void stage(Pending &t, int64_t idx) const
+    {
+        if (K == 0) {
+            t.pv = rdk::load4<PK>(pr, idx, N, vec_p, PK == RDK_PROB_F32 ? 0.f : -INFINITY);
+            t.sv = make_int4(-1, -1, -1, -1);
+            if (idx + 3 < N) {
+                t.sv = *(const int4 *)(slot_of + idx);
+            } else {
+                if (idx + 0 < N) t.sv.x = slot_of[idx + 0];
+                if (idx + 1 < N) t.sv.y = slot_of[idx + 1];
+                if (idx + 2 < N) t.sv.z = slot_of[idx + 2];
+            }
         } else {
-            if (idx + 0 < N) sv.x = slot_of[idx + 0];
-            if (idx + 1 < N) sv.y = slot_of[idx + 1];
-            if (idx + 2 < N) sv.z = slot_of[idx + 2];
-        }
-        const int se[4] = {sv.x, sv.y, sv.z, sv.w};
-        float qraw[4], o[4];
+            const int se[4] = {t.sv.x, t.sv.y, t.sv.z, t.sv.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) qraw[e] = rdk::load1<QK>(qr, max(se[e], 0));   // unconditional: loads stay batched
+            for (int e = 0; e < 4; ++e) t.qraw[e] = rdk::load1<QK>(qr, max(se[e], 0));   // unconditional: loads stay batched
+        }
+    }
+    __device__ __forceinline__ float4 result(const Pending &t, int64_t idx) const
+    {
+        const float pe[4] = {to_weight<PK>(t.pv.x, pm, pinv), to_weight<PK>(t.pv.y, pm, pinv), to_weight<PK>(t.pv.z, pm, pinv),
+                             to_weight<PK>(t.pv.w, pm, pinv)};
+        const int se[4] = {t.sv.x, t.sv.y, t.sv.z, t.sv.w};
+        float o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float qp = se[e] >= 0 ? to_weight<QK>(qraw[e], qm, 1.f) * inv_zq : 0.f;
-            o[e] = idx + e < N ? (fN * qp + theta * pe[e]) / (fN + pe[e]) * inv_S : 0.f;
+            const float qh = se[e] >= 0 ? to_weight<QK>(t.qraw[e], qm, 1.f) : 0.f;
+            o[e] = idx + e < N ? value(qh, pe[e]) : 0.f;
         }
-        p_out = make_float4(pe[0], pe[1], pe[2], pe[3]);
         return make_float4(o[0], o[1], o[2], o[3]);
-    }
-    __device__ __forceinline__ float4 load4(int64_t idx) const
-    {
-        float4 unused;
-        return eval4(idx, unused);
     }
     __device__ __forceinline__ float load1(int j) const
     {
         const float pe = to_weight<PK>(rdk::load1<PK>(pr, j), pm, pinv);
         const int s = slot_of[j];
-        const float qp = s >= 0 ? to_weight<QK>(rdk::load1<QK>(qr, max(s, 0)), qm, 1.f) * inv_zq : 0.f;
-        return (fN * qp + theta * pe) / (fN + pe) * inv_S;
+        const float qh = s >= 0 ? to_weight<QK>(rdk::load1<QK>(qr, max(s, 0)), qm, 1.f) : 0.f;
+        return value(qh, pe);
     }
 };
 
@@ -194,46 +244,60 @@ __device__ __forceinline__ TaylorRow<PK, QK> make_taylor_row(const TaylorArgs &a
     r.theta = tn * r.inv_zq;
     r.inv_S = 1.0f / (an * r.inv_zq + r.theta * bs);
     r.fN = (float)a.N;
+    r.nzs = r.fN * r.inv_zq * r.inv_S;
+    r.ths = r.theta * r.inv_S;
     return r;
 }
 
 // Eq. 3, second pass: q'_j = ((N q0_j + theta p_j) / (N + p_j)) / sum_j pt_j.  WRITE_Q stores it; FUSE adds the
-// verification sums per 1024-id block (sum q', sum max(0, p - q'), sum min(p, q')).
-template <int PK, int QK, bool FUSE, bool WRITE_Q>
+// verification sums per 1024-id block (sum q', sum max(0, p - q'), sum min(p, q')).  Whether q' is stored (out != NULL)
+// is decided at run time, so that the sums do not depend on it by a single bit.
+template <int PK, int QK, bool FUSE>
 __global__ __launch_bounds__(kThreads) void taylor_write_kernel(TaylorArgs a, bool vec_o, float *out, int64_t ldo, float *part_q,
                                                                 float *part_r, float *part_a)
 {
+    __shared__ __attribute__((aligned(16))) float qchunk[kWaves][kChunk];
     const int64_t row = blockIdx.x / a.splits;
     const int split = blockIdx.x % a.splits;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
     const int cpw = (nchunks + a.splits - 1) / a.splits;
     const int c_begin = split * cpw, c_end = min(nchunks, c_begin + cpw);
-    const int wid = threadIdx.x / kWave, lane = lane_id();
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
     const TaylorRow<PK, QK> tr = make_taylor_row<PK, QK>(a, row);
-    float *orow = WRITE_Q ? out + row * ldo : nullptr;
+    const float pfill = PK == RDK_PROB_F32 ? 0.f : -INFINITY;
+    float *orow = out ? out + row * ldo : nullptr;
     for (int c = c_begin + wid; c < c_end; c += kWaves) {
-        const int64_t base = (int64_t)c * kChunk + lane * 4;
+        const int base = c * kChunk;
+        float4 pv[4], qd[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pv[i] = load4<PK>(tr.pr, (int64_t)base + i * 256 + lane * 4, a.N, a.vec_p, pfill);
+        stage_chunk<QK>(qchunk[wid], tr.qr, a.vec_q, a.n, a.kept, a.chunk_lo[c], a.chunk_lo[c + 1], base, qd);
         float sq = 0.f, sr = 0.f, sa = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int64_t idx = base + i * 256;
-            if (idx >= a.N) continue;
-            float4 pv;
-            const float4 o = tr.eval4(idx, pv);
-            if (WRITE_Q) {
+            const int64_t idx = (int64_t)base + i * 256 + lane * 4;
+            const float pe[4] = {to_weight<PK>(pv[i].x, tr.pm, tr.pinv), to_weight<PK>(pv[i].y, tr.pm, tr.pinv),
+                                 to_weight<PK>(pv[i].z, tr.pm, tr.pinv), to_weight<PK>(pv[i].w, tr.pm, tr.pinv)};
+            const float qe[4] = {qd[i].x, qd[i].y, qd[i].z, qd[i].w};
+            float oe[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float qh = to_weight<QK>(qe[e], tr.qm, 1.f);   // zero on ids that are not kept
+                oe[e] = tr.value(qh, pe[e]);   // ids beyond N: both weights are zero, and so is the value
+            }
+            if (orow && idx < a.N) {
                 if (vec_o && idx + 3 < a.N) {
-                    *(float4 *)(orow + idx) = o;
+                    *(float4 *)(orow + idx) = make_float4(oe[0], oe[1], oe[2], oe[3]);
                 } else {
-                    const float oe[4] = {o.x, o.y, o.z, o.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         if (idx + e < a.N) orow[idx + e] = oe[e];
                 }
             }
             if (FUSE) {
-                sq += (o.x + o.y) + (o.z + o.w);
-                sr += (fmaxf(pv.x - o.x, 0.f) + fmaxf(pv.y - o.y, 0.f)) + (fmaxf(pv.z - o.z, 0.f) + fmaxf(pv.w - o.w, 0.f));
-                sa += (fminf(pv.x, o.x) + fminf(pv.y, o.y)) + (fminf(pv.z, o.z) + fminf(pv.w, o.w));
+                sq += (oe[0] + oe[1]) + (oe[2] + oe[3]);
+                sr += (fmaxf(pe[0] - oe[0], 0.f) + fmaxf(pe[1] - oe[1], 0.f)) + (fmaxf(pe[2] - oe[2], 0.f) + fmaxf(pe[3] - oe[3], 0.f));
+                sa += (fminf(pe[0], oe[0]) + fminf(pe[1], oe[1])) + (fminf(pe[2], oe[2]) + fminf(pe[3], oe[3]));
             }
         }
         if (FUSE) {
@@ -253,6 +317,7 @@ __global__ __launch_bounds__(kThreads) void taylor_write_kernel(TaylorArgs a, bo
 template <int PK, int QK>
 struct QpTaylor {
     static constexpr bool kSpreadRows = false;
+    static constexpr int kStages = 2;
     TaylorArgs a;
     typedef TaylorRow<PK, QK> Row;
     __device__ __forceinline__ Row row(int64_t b) const { return make_taylor_row<PK, QK>(a, b); }
@@ -290,21 +355,22 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     }
     TaylorArgs a;
     a.p = p.ptr; a.q = q.ptr; a.ldp = p.ld; a.ldq = q.ld;
-    a.slot_of = h.slot_of; a.N = h.N; a.splits = w.t_splits;
+    a.slot_of = h.slot_of; a.kept = h.kept_ids; a.chunk_lo = h.chunk_lo; a.N = h.N; a.n = h.n; a.splits = w.t_splits;
     a.vec_p = rows_vectorisable(p.ptr, p.ld, p.kind);
+    a.vec_q = rows_vectorisable(q.ptr, q.ld, q.kind);
     a.w = w;
     const bool vec_o = out ? rows_vectorisable(out, ldo, RDK_PROB_F32) : false;
     {
         TimedLaunch timed("taylor_stats_kernel", st);
         hipLaunchKernelGGL((taylor_stats_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads), 0, st, p.ptr, p.ld,
-                           q.ptr, q.ld, h.slot_of, h.N, w.t_splits, a.vec_p, w);
+                           q.ptr, q.ld, h.kept_ids, h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p, a.vec_q, w);
     }
     RDK_LAUNCH_CHECK("taylor_stats_kernel");
     const dim3 grid((unsigned)B * w.t_splits);
     if (!c) {
         {
             TimedLaunch timed("taylor_write_kernel", st);
-            hipLaunchKernelGGL((taylor_write_kernel<PK, QK, false, true>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo,
+            hipLaunchKernelGGL((taylor_write_kernel<PK, QK, false>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo,
                                (float *)nullptr, (float *)nullptr, (float *)nullptr);
         }
         RDK_LAUNCH_CHECK("taylor_write_kernel");
@@ -316,12 +382,8 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     float *part_q = (float *)pp, *part_r = (float *)(pp + per), *part_a = (float *)(pp + 2 * per);
     {
         TimedLaunch timed("taylor_write_kernel", st);
-        if (out)
-            hipLaunchKernelGGL((taylor_write_kernel<PK, QK, true, true>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo,
-                               part_q, part_r, part_a);
-        else
-            hipLaunchKernelGGL((taylor_write_kernel<PK, QK, true, false>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo,
-                               part_q, part_r, part_a);
+        hipLaunchKernelGGL((taylor_write_kernel<PK, QK, true>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo, part_q, part_r,
+                           part_a);
     }
     RDK_LAUNCH_CHECK("taylor_write_kernel");
     FinalizeArgs fa{};

@@ -326,6 +326,7 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
 // q' of one position recomputed from the sparse kernel (the finalize step needs two 256-id blocks of it).
 struct QpSparse {
     static constexpr bool kSpreadRows = true;
+    static constexpr int kStages = 3;
     SparseArgs a;
     struct Row {
         const int32_t *slot_of;
@@ -348,55 +349,65 @@ struct QpSparse {
             }
             return acc * inv_z;
         }
-        // Four consecutive ids at once, two at a time with all their loads in flight together: a kept id is
-        // treated as a row whose sixteen entries all point at its own slot, the first with the diagonal weight.
-        __device__ __forceinline__ float4 load4(int64_t idx) const
+        // Four consecutive ids in three steps: slots; the first sixteen table entries of each id (a kept id is
+        // treated as a row whose entries all point at its own slot, the first with the diagonal weight); the
+        // gathers.  Rows longer than sixteen entries finish one id after the other in result().
+        struct Pending {
+            int se[4];
+            int ii[4][16];
+            float ww[4][16], gg[4][16];
+        };
+        template <int K>
+        __device__ __forceinline__ void stage(Pending &t, int64_t idx) const
         {
-            int se[4] = {-1, -1, -1, -1};
-            bool ok[4];
+            if (K == 0) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ok[e] = idx + e < N;
-                if (ok[e]) se[e] = slot_of[idx + e];
-            }
-            float out[4];
+                for (int e = 0; e < 4; ++e) t.se[e] = idx + e < N ? slot_of[idx + e] : 0;   // beyond N: computed, discarded
+            } else if (K == 1) {
 #pragma unroll
-            for (int pair = 0; pair < 2; ++pair) {
-                float acc[2] = {0.f, 0.f};
-                for (int t0 = 0; t0 < kk; t0 += 16) {
-                    int ii[2][16];
-                    float ww[2][16], gg[2][16];
+                for (int e = 0; e < 4; ++e) {
+                    const int s = t.se[e];
+                    const bool kept = s >= 0;
+                    const int64_t u = kept ? 0 : -s - 1;
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const int s = se[pair * 2 + h];
-                        const bool kept = s >= 0;
-                        const int64_t u = (kept || !ok[pair * 2 + h]) ? 0 : -s - 1;
+                    for (int x = 0; x < 16; x += 2) {
+                        const int4 ev = *(const int4 *)(nbr + u * kk + x);
+                        t.ii[e][x] = ev.x; t.ww[e][x] = __int_as_float(ev.y);
+                        t.ii[e][x + 1] = ev.z; t.ww[e][x + 1] = __int_as_float(ev.w);
+                    }
+                    const float sw = self_w[max(s, 0)];
+                    if (kept) {
 #pragma unroll
-                        for (int t = 0; t < 16; t += 2) {
-                            const int4 ev = *(const int4 *)(nbr + u * kk + t0 + t);
-                            ii[h][t] = ev.x; ww[h][t] = __int_as_float(ev.y);
-                            ii[h][t + 1] = ev.z; ww[h][t + 1] = __int_as_float(ev.w);
-                        }
-                        if (kept) {
-                            const float sw = t0 == 0 ? self_w[s] : 0.f;
-#pragma unroll
-                            for (int t = 0; t < 16; ++t) {
-                                ii[h][t] = s;
-                                ww[h][t] = t == 0 ? sw : 0.f;
-                            }
+                        for (int x = 0; x < 16; ++x) {
+                            t.ii[e][x] = s;
+                            t.ww[e][x] = x == 0 ? sw : 0.f;
                         }
                     }
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-#pragma unroll
-                        for (int t = 0; t < 16; ++t) gg[h][t] = qcol[(int64_t)ii[h][t] * kPosBlock];
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-#pragma unroll
-                        for (int t = 0; t < 16; ++t) acc[h] += ww[h][t] * gg[h][t];
                 }
-                out[pair * 2 + 0] = ok[pair * 2 + 0] ? acc[0] * inv_z : 0.f;
-                out[pair * 2 + 1] = ok[pair * 2 + 1] ? acc[1] * inv_z : 0.f;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) t.gg[e][x] = qcol[(int64_t)t.ii[e][x] * kPosBlock];
+            }
+        }
+        __device__ __forceinline__ float4 result(const Pending &t, int64_t idx) const
+        {
+            float out[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float acc = 0.f;
+#pragma unroll
+                for (int x = 0; x < 16; ++x) acc += t.ww[e][x] * t.gg[e][x];   // same order of additions as the product kernel
+                if (kk > 16 && t.se[e] < 0) {
+                    const int64_t u = -t.se[e] - 1;
+                    for (int x = 16; x < kk; x += 2) {
+                        const int4 ev = *(const int4 *)(nbr + u * kk + x);
+                        acc += __int_as_float(ev.y) * qcol[(int64_t)ev.x * kPosBlock];
+                        acc += __int_as_float(ev.w) * qcol[(int64_t)ev.z * kPosBlock];
+                    }
+                }
+                out[e] = idx + e < N ? acc * inv_z : 0.f;
             }
             return make_float4(out[0], out[1], out[2], out[3]);
         }

@@ -323,6 +323,19 @@ def test_verify_degenerate_rows(rdk):
     assert (o.draft_ids.cpu().numpy()[10:20] == 1234).all()
 
 
+def test_verify_very_large_vocab(rdk):
+    """More 1024-id blocks per row than a wavefront keeps in registers (N > 2^19): the block partials are then
+    re-read from memory when the prefix-sum crossings are located."""
+    N, B = 600011, 6
+    rng = np.random.default_rng(9)
+    z = rng.normal(0, 3, size=(2, B, N))
+    e = np.exp(z - z.max(2, keepdims=True))
+    p, q = [(x / x.sum(1, keepdims=True)).astype(np.float32) for x in e]
+    run_verify_case(rdk, dev(p), "prob", p.astype(np.float64), q, 3, seed=41, offset=2)
+    drafts = (np.arange(B, dtype=np.int32) * 50021) % N
+    run_verify_case(rdk, dev(p), "prob", p.astype(np.float64), q, 3, seed=42, offset=0, draft_ids=drafts)
+
+
 def test_pipeline_end_to_end(rdk, tiny):
     """rdk_build_kernel -> rdk_redistribute_linear -> rdk_verify_sample on the device vs the oracle chain."""
     w = tiny["w"]
