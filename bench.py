@@ -5,9 +5,11 @@ One step = one pass of the whole hot path over one batch of synthetic inputs tha
 redistribution with the top-k sparse kernel (Alg. 1 steps 1-2) and verification (Alg. 4), through the fused
 entry point rdk_redistribute_verify (default) or as rdk_redistribute_linear -> rdk_verify_sample.
 Prints ONE JSON line: positions/s, the roofline of the dominant kernel (timed live with HIP events
-inside the library), and the CPU oracle timed on a bounded sample of the same workload.
+inside the library), and the CPU oracle timed on a bounded sample of the same workload.  Unless --no-extra is
+given, "extra" also carries the other linear form (Eq. 3) on the same batch and the exact dense bf16 product
+(N=256000, n=32000, B=512) against the MFMA peak.
 
-  python bench.py [--steps K] [--warmup W] [--mode sparse|taylor] [--path fused|twocall] [--workload NAME] [--no-cpu]
+  python bench.py [--steps K] [--warmup W] [--mode sparse|taylor] [--path fused|twocall] [--workload NAME] [--no-cpu] [--no-extra]
 """
 import argparse
 import json
@@ -27,50 +29,26 @@ def algorithmic_bytes(kernel, w, B, kk, fused, esz):
     read p instead of writing q'."""
     N, n = w.N, w.n
     tables = 8 * (N - n) * kk + 4 * n + 4 * N                               # neighbour rows, diagonal, id maps: once
+    ids = 4 * n + 4 * ((N + 1023) // 1024 + 1)                              # kept ids and first slot per chunk: once
     return {
         "verify_stream_kernel": B * (esz + 4) * N,                          # read p and q'
         "sparse_product_kernel": B * ((esz if fused else 4) * N + 4 * n) + tables,   # read q^T, p (fused) or write q'
-        "taylor_stats_kernel": B * esz * (N + n) + 4 * N,                   # read p, q, slot table
-        "taylor_write_kernel": B * (esz * (N + n) + (0 if fused else 4 * N)) + 4 * N,
+        "taylor_stats_kernel": B * esz * (N + n) + ids,                     # read p, q
+        "taylor_write_kernel": B * (esz * (N + n) + (0 if fused else 4 * N)) + ids,
         "q_transpose_kernel": B * (esz + 4) * n,
         "row_stats_kernel": B * esz * n,
         "verify_finalize_kernel": B * 3 * 4 * ((N + 1023) // 1024),
     }.get(kernel)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--mode", default="sparse", choices=["sparse", "taylor"])
-    ap.add_argument("--path", default="fused", choices=["fused", "twocall"],
-                    help="fused: rdk_redistribute_verify (q' never stored); twocall: rdk_redistribute_linear + rdk_verify_sample")
-    ap.add_argument("--workload", default=None)
-    ap.add_argument("--copies", type=int, default=4, help="input/output buffer sets rotated through (defeats the 256 MB cache)")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        sys.exit("bench.py: this build is a one-GPU library (positions are independent: shard the batch); run with --gpus 1")
-
-    import torch
-    from paper_2506_03206_amd import rdk, synth
-
-    wname = args.workload or "llama3"
-    w = synth.WORKLOADS[wname]
+def run_linear(args, rdk, synth, torch, w, vocab, batch, mode_name, path, steps, warmup):
+    """Times `steps` passes of redistribution (mode_name) + verification over the batch; returns the figures."""
+    bias, kept, E = vocab
     B = w.B
-    torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-
-    t0 = time.time()
-    bias, kept, E, rng = synth.make_vocab(w)
-    batch = synth.make_batch(w, bias, kept, rng)
-    gen_s = time.time() - t0
-
     kept_d = torch.from_numpy(kept).to(dev)
     t0 = time.time()
-    if args.mode == "sparse":
+    if mode_name == "sparse":
         kern = rdk.rdk_build_kernel(w.N, kept_d, rdk.SPARSE_TOPK, embeddings=torch.from_numpy(E).to(dev), tau=w.tau, k=w.k)
     else:
         kern = rdk.rdk_build_kernel(w.N, kept_d, rdk.IDENTITY)
@@ -86,12 +64,11 @@ def main():
     C = max(1, args.copies)
     ps = [p_host.to(dev) for _ in range(C)]
     qs = [q_host.to(dev) for _ in range(C)]
-    outs = [torch.empty((B, w.N), dtype=torch.float32, device=dev) for _ in range(C)] if args.path == "twocall" else None
+    outs = [torch.empty((B, w.N), dtype=torch.float32, device=dev) for _ in range(C)] if path == "twocall" else None
     vout = rdk.VerifyOutputs(B, w.N, w.gamma, dev)
     kern.workspace(B)
-    mode = rdk.LINEAR_SPARSE if args.mode == "sparse" else rdk.LINEAR_TAYLOR
-
-    fused = args.path == "fused"
+    mode = rdk.LINEAR_SPARSE if mode_name == "sparse" else rdk.LINEAR_TAYLOR
+    fused = path == "fused"
 
     def step(i):
         c = i % C
@@ -99,11 +76,11 @@ def main():
             rdk.rdk_redistribute_verify(kern, mode, ps[c], qs[c], seed=2506, offset=i * B, gamma=w.gamma, p_kind=kind,
                                         q_kind=kind, outputs=vout)
         else:
-            rdk.rdk_redistribute_linear(kern, mode, qs[c], kind, p=ps[c] if args.mode == "taylor" else None, p_kind=kind,
+            rdk.rdk_redistribute_linear(kern, mode, qs[c], kind, p=ps[c] if mode_name == "taylor" else None, p_kind=kind,
                                         out=outs[c])
             rdk.rdk_verify_sample(ps[c], outs[c], seed=2506, offset=i * B, gamma=w.gamma, p_kind=kind, outputs=vout)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
 
@@ -127,15 +104,14 @@ def main():
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     start.record()
-    for i in range(args.steps):
-        step(args.warmup + i)
+    for i in range(steps):
+        step(warmup + i)
     stop.record()
     torch.cuda.synchronize()
     rdk.rdk_timing_select(None)
     total_ms = start.elapsed_time(stop)
     cnt, kms = rdk.rdk_timing_read(dominant)
-    ms_per_step = total_ms / args.steps
-    value = B / (ms_per_step * 1e-3)
+    ms_per_step = total_ms / steps
 
     kk = (max(w.k, 1) + 15) // 16 * 16
     esz = 2 if w.logits_bf16 else 4
@@ -147,27 +123,109 @@ def main():
                 "algorithmic_bytes_per_launch": alg}
     # whole-step compulsory bytes: fused = read p and q once; two calls = q read, q' written then read, p read (twice for Eq. 3)
     if fused:
-        step_bytes = B * esz * (w.N + w.n) + (8 * (w.N - w.n) * kk if args.mode == "sparse" else 0)
+        step_bytes = B * esz * (w.N + w.n) + (8 * (w.N - w.n) * kk if mode_name == "sparse" else 0)
     else:
-        step_bytes = B * (esz * (w.n + w.N) + 8 * w.N) + (8 * (w.N - w.n) * kk if args.mode == "sparse" else B * esz * w.N)
-    extra = {"kernels": {k: {"avg_us": round(v["avg_us"], 2), "per_step": v["launches_per_step"]} for k, v in per_kernel.items()},
-             "step_algorithmic_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-             "step_frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-             "kernel_build_s": round(build_s, 3), "input_gen_s": round(gen_s, 2),
-             "accept_rate": float(vout.accept.float().mean().item()), "mean_alpha": float(vout.alpha.mean().item())}
+        step_bytes = B * (esz * (w.n + w.N) + 8 * w.N) + (8 * (w.N - w.n) * kk if mode_name == "sparse" else B * esz * w.N)
+    return {"ms_per_step": ms_per_step, "value": B / (ms_per_step * 1e-3), "roofline": roofline,
+            "kernels": {k: {"avg_us": round(v["avg_us"], 2), "per_step": v["launches_per_step"]} for k, v in per_kernel.items()},
+            "step_algorithmic_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+            "step_frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "kernel_build_s": round(build_s, 3),
+            "accept_rate": float(vout.accept.float().mean().item()), "mean_alpha": float(vout.alpha.mean().item())}
+
+
+def run_exact_bf16(rdk, synth, torch, calls=5):
+    """Exact dense redistribution (Alg. 1 with the full M) as a bf16 MFMA contraction at N=256000, n=32000, B=512."""
+    w = synth.WORKLOADS["dense256k"]
+    dev = torch.device("cuda:0")
+    bias, kept, E, rng = synth.make_vocab(w)
+    batch = synth.make_batch(w, bias, kept, rng)
+    kern = rdk.rdk_build_kernel(w.N, torch.from_numpy(kept).to(dev), rdk.DENSE_BF16, embeddings=torch.from_numpy(E).to(dev),
+                                tau=w.tau)
+    q = torch.from_numpy(batch["q_hat"]).to(dev)
+    out = torch.empty((w.B, w.N), dtype=torch.float32, device=dev)
+    for _ in range(2):
+        rdk.rdk_redistribute_exact(kern, q, out=out)
+    torch.cuda.synchronize()
+    rdk.rdk_timing_select("exact_bf16_kernel")
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(calls):
+        rdk.rdk_redistribute_exact(kern, q, out=out)
+    stop.record()
+    torch.cuda.synchronize()
+    rdk.rdk_timing_select(None)
+    ms_call = start.elapsed_time(stop) / calls
+    cnt, kms = rdk.rdk_timing_read("exact_bf16_kernel")
+    flops = 2.0 * w.B * w.n * w.N
+    k_tf = flops / (kms / cnt * 1e-3) / 1e12
+    row_err = float((out.double().sum(1) - 1).abs().max().item())
+    del kern, out, q
+    torch.cuda.empty_cache()
+    return {"workload": "dense256k: N=%d n=%d B=%d, M bf16 %.1f GB" % (w.N, w.n, w.B, 2.0 * w.n * w.N / 1e9),
+            "ms_per_call": round(ms_call, 3), "positions_per_s": round(w.B / (ms_call * 1e-3), 1),
+            "roofline": {"kernel": "exact_bf16_kernel", "bound": "mfma", "achieved": round(k_tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": round(k_tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                         "avg_launch_us": round(kms / cnt * 1e3, 1), "algorithmic_flops_per_launch": flops},
+            "call_TFLOPs": round(flops / (ms_call * 1e-3) / 1e12, 1), "max_row_sum_error": row_err}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--mode", default="sparse", choices=["sparse", "taylor"])
+    ap.add_argument("--path", default="fused", choices=["fused", "twocall"],
+                    help="fused: rdk_redistribute_verify (q' never stored); twocall: rdk_redistribute_linear + rdk_verify_sample")
+    ap.add_argument("--workload", default=None)
+    ap.add_argument("--copies", type=int, default=4, help="input/output buffer sets rotated through (defeats the 256 MB cache)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other linear form and the exact bf16 product")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build is a one-GPU library (positions are independent: shard the batch); run with --gpus 1")
+
+    import torch
+    from paper_2506_03206_amd import rdk, synth
+
+    wname = args.workload or "llama3"
+    w = synth.WORKLOADS[wname]
+    B = w.B
+    torch.cuda.set_device(0)
+
+    t0 = time.time()
+    bias, kept, E, rng = synth.make_vocab(w)
+    batch = synth.make_batch(w, bias, kept, rng)
+    gen_s = time.time() - t0
+
+    r = run_linear(args, rdk, synth, torch, w, (bias, kept, E), batch, args.mode, args.path, args.steps, args.warmup)
+    extra = {k: r[k] for k in ("kernels", "step_algorithmic_GBs", "step_frac_of_hbm_peak", "kernel_build_s", "accept_rate",
+                               "mean_alpha")}
+    extra["input_gen_s"] = round(gen_s, 2)
+    if not args.no_extra:
+        other = "taylor" if args.mode == "sparse" else "sparse"
+        torch.cuda.empty_cache()
+        o = run_linear(args, rdk, synth, torch, w, (bias, kept, E), batch, other, args.path, max(20, args.steps // 2), args.warmup)
+        extra["other_linear_form"] = {"mode": other, "path": args.path, "positions_per_s": round(o["value"], 1),
+                                      "ms_per_step": round(o["ms_per_step"], 5), "roofline": o["roofline"], "kernels": o["kernels"],
+                                      "step_frac_of_hbm_peak": o["step_frac_of_hbm_peak"]}
+        torch.cuda.empty_cache()
+        extra["exact_bf16"] = run_exact_bf16(rdk, synth, torch)
 
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(args, w, batch, kept)
 
-    line = {"metric": "redistribute+verify positions/sec at N=%d, n=%d" % (w.N, w.n), "value": round(value, 1),
+    line = {"metric": "redistribute+verify positions/sec at N=%d, n=%d" % (w.N, w.n), "value": round(r["value"], 1),
             "unit": "positions/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-            "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "f32", "data": "synthetic",
             "config": {"workload": "%s: N=%d n=%d B=%d (%d seqs x %d drafts) k=%d, %s linear RDK + verify/sample, %s inputs"
                        % (w.name, w.N, w.n, B, w.seqs, w.gamma, w.k, args.mode, "bf16 logit" if w.logits_bf16 else "fp32 prob"),
                        "mode": args.mode, "path": args.path, "N": w.N, "n": w.n, "B": B, "k": w.k},
-            "roofline": roofline, "cpu_baseline": cpu, "extra": extra}
+            "roofline": r["roofline"], "cpu_baseline": cpu, "extra": extra}
     print(json.dumps(line))
 
 
