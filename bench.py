@@ -195,6 +195,15 @@ def main():
     B = w.B
     torch.cuda.set_device(0)
 
+    # Yardstick for hardware byte counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE): one elementwise pass that
+    # reads exactly 256 MiB and writes exactly 256 MiB; it is the only launch with 2^26 float elements.
+    cal = torch.zeros(1 << 26, dtype=torch.float32, device="cuda:0")
+    cal_out = torch.empty_like(cal)
+    torch.add(cal, 1.0, out=cal_out)
+    torch.cuda.synchronize()
+    del cal, cal_out
+    torch.cuda.empty_cache()
+
     t0 = time.time()
     bias, kept, E, rng = synth.make_vocab(w)
     batch = synth.make_batch(w, bias, kept, rng)

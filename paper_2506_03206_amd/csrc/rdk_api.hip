@@ -41,21 +41,17 @@ hipEvent_t timing_event()
 }
 }  // namespace
 
-TimedLaunch::TimedLaunch(const char *kernel_name, hipStream_t st) : stop_(nullptr), st_(st)
+bool timing_events(const char *kernel_name, hipEvent_t *start, hipEvent_t *stop)
 {
     std::lock_guard<std::mutex> lock(g_timing_mutex);
-    if (g_timing_selected.empty()) return;
-    if (g_timing_selected != "*" && g_timing_selected != kernel_name) return;
+    if (g_timing_selected.empty()) return false;
+    if (g_timing_selected != "*" && g_timing_selected != kernel_name) return false;
     hipEvent_t a = timing_event(), b = timing_event();
-    if (!a || !b) return;
-    if (hipEventRecord(a, st) != hipSuccess) return;
+    if (!a || !b) return false;
     g_timing_records.push_back(TimedRecord{kernel_name, a, b});
-    stop_ = b;
-}
-
-TimedLaunch::~TimedLaunch()
-{
-    if (stop_) (void)hipEventRecord(stop_, st_);
+    *start = a;
+    *stop = b;
+    return true;
 }
 
 namespace {

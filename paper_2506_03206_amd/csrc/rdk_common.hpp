@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of the RDK HIP library (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "rdk.h"
@@ -67,14 +68,20 @@ struct FusedCall {
     int32_t *resid_ids, *n_accepted, *out_tokens;
 };
 
-// Brackets one kernel launch with HIP events when that kernel has been selected through
-// rdk_timing_select(); otherwise it does nothing.  Declare it in the scope of the launch.
-struct TimedLaunch {
-    TimedLaunch(const char *kernel_name, hipStream_t st);
-    ~TimedLaunch();
-    hipEvent_t stop_;
-    hipStream_t st_;
-};
+// Launch of an instrumented kernel.  When the kernel has been selected through rdk_timing_select() it is launched
+// with a pair of events that take the dispatch's own begin and end timestamps (hipExtLaunchKernelGGL), so the
+// measured time is the kernel's, without launch gaps; otherwise this is a plain launch.  Same argument order as
+// hipLaunchKernelGGL after the name.
+bool timing_events(const char *kernel_name, hipEvent_t *start, hipEvent_t *stop);
+
+#define RDK_TIMED_LAUNCH(NAME, KERNEL, GRID, BLOCK, SHMEM, ST, ...)                                  \
+    do {                                                                                             \
+        hipEvent_t rdk_ev_a_ = nullptr, rdk_ev_b_ = nullptr;                                         \
+        if (rdk::timing_events(NAME, &rdk_ev_a_, &rdk_ev_b_))                                        \
+            hipExtLaunchKernelGGL(KERNEL, GRID, BLOCK, SHMEM, ST, rdk_ev_a_, rdk_ev_b_, 0, __VA_ARGS__); \
+        else                                                                                         \
+            hipLaunchKernelGGL(KERNEL, GRID, BLOCK, SHMEM, ST, __VA_ARGS__);                          \
+    } while (0)
 
 // ---- launchers implemented in the kernel translation units (all enqueue on `st`, none synchronises)
 

@@ -361,21 +361,18 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
         dim3 grid((h.N + kColsF - 1) / kColsF, (B + kRowsF - 1) / kRowsF, splits);
         if (splits == 1) {
             {
-                TimedLaunch timed("exact_f32_kernel", st);
-                hipLaunchKernelGGL((exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
+                RDK_TIMED_LAUNCH("exact_f32_kernel", (exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
                                    B, per, out, ldo, (int64_t)0, true);
             }
             RDK_LAUNCH_CHECK("exact_f32_kernel");
         } else {
             {
-                TimedLaunch timed("exact_f32_kernel", st);
-                hipLaunchKernelGGL((exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
+                RDK_TIMED_LAUNCH("exact_f32_kernel", (exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
                                    B, per, w.part, ldd, (int64_t)B * ldd, false);
             }
             RDK_LAUNCH_CHECK("exact_f32_kernel");
             {
-                TimedLaunch timed("exact_reduce_kernel", st);
-                hipLaunchKernelGGL(exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part, ldd,
+                RDK_TIMED_LAUNCH("exact_reduce_kernel", exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part, ldd,
                                    (int64_t)B * ldd, splits, w.qstat, h.N, out, ldo);
             }
             RDK_LAUNCH_CHECK("exact_reduce_kernel");
@@ -391,21 +388,19 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
     w.A = (uint16_t *)p; p += align_up((size_t)B_pad * h.n_pad * 2, 256);
     w.out_scale = (float *)p;
     {
-        TimedLaunch timed("prep_a_bf16_kernel", st);
-        hipLaunchKernelGGL((prep_a_bf16_kernel<QK>), dim3(B_pad), dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.row_sum, h.n, KB, B,
+        RDK_TIMED_LAUNCH("prep_a_bf16_kernel", (prep_a_bf16_kernel<QK>), dim3(B_pad), dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.row_sum, h.n, KB, B,
                            w.A, w.out_scale);
     }
     RDK_LAUNCH_CHECK("prep_a_bf16_kernel");
     const int n_jb = (h.N + kColBlock - 1) / kColBlock;
     dim3 grid((n_jb + kColBlocksPerWg - 1) / kColBlocksPerWg, B_pad / rows_per_wg);
     {
-        TimedLaunch timed("exact_bf16_kernel", st);
         if (W == 4 && RB == 1)
-            hipLaunchKernelGGL((exact_bf16_kernel<4, 1>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
+            RDK_TIMED_LAUNCH("exact_bf16_kernel", (exact_bf16_kernel<4, 1>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
         else if (W == 8)
-            hipLaunchKernelGGL((exact_bf16_kernel<8, 1>), grid, dim3(512), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
+            RDK_TIMED_LAUNCH("exact_bf16_kernel", (exact_bf16_kernel<8, 1>), grid, dim3(512), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
         else
-            hipLaunchKernelGGL((exact_bf16_kernel<4, 4>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
+            RDK_TIMED_LAUNCH("exact_bf16_kernel", (exact_bf16_kernel<4, 4>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
     }
     RDK_LAUNCH_CHECK("exact_bf16_kernel");
     return RDK_OK;

@@ -372,8 +372,7 @@ rdk_status_t launch_finalize(FinalizeArgs a, QP qp, hipStream_t st)
     a.rows_per_block = a.scan_here ? d.gamma : (QP::kSpreadRows ? 1 : 4);
     const int blocks = (d.B + a.rows_per_block - 1) / a.rows_per_block;
     {
-        TimedLaunch timed("verify_finalize_kernel", st);
-        hipLaunchKernelGGL((verify_finalize_kernel<KIND, SUB, HAS_Q, QP>), dim3(blocks), dim3(a.rows_per_block * kWave), 0, st, a, qp);
+        RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_kernel<KIND, SUB, HAS_Q, QP>), dim3(blocks), dim3(a.rows_per_block * kWave), 0, st, a, qp);
     }
     RDK_LAUNCH_CHECK("verify_finalize_kernel");
     if (d.gamma > 0 && !a.scan_here && (a.n_accepted || a.out_tokens))

@@ -361,16 +361,14 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     a.w = w;
     const bool vec_o = out ? rows_vectorisable(out, ldo, RDK_PROB_F32) : false;
     {
-        TimedLaunch timed("taylor_stats_kernel", st);
-        hipLaunchKernelGGL((taylor_stats_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads), 0, st, p.ptr, p.ld,
+        RDK_TIMED_LAUNCH("taylor_stats_kernel", (taylor_stats_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads), 0, st, p.ptr, p.ld,
                            q.ptr, q.ld, h.kept_ids, h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p, a.vec_q, w);
     }
     RDK_LAUNCH_CHECK("taylor_stats_kernel");
     const dim3 grid((unsigned)B * w.t_splits);
     if (!c) {
         {
-            TimedLaunch timed("taylor_write_kernel", st);
-            hipLaunchKernelGGL((taylor_write_kernel<PK, QK, false>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo,
+            RDK_TIMED_LAUNCH("taylor_write_kernel", (taylor_write_kernel<PK, QK, false>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo,
                                (float *)nullptr, (float *)nullptr, (float *)nullptr);
         }
         RDK_LAUNCH_CHECK("taylor_write_kernel");
@@ -381,8 +379,7 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     char *pp = (char *)ws + taylor_workspace_bytes(h, B);
     float *part_q = (float *)pp, *part_r = (float *)(pp + per), *part_a = (float *)(pp + 2 * per);
     {
-        TimedLaunch timed("taylor_write_kernel", st);
-        hipLaunchKernelGGL((taylor_write_kernel<PK, QK, true>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo, part_q, part_r,
+        RDK_TIMED_LAUNCH("taylor_write_kernel", (taylor_write_kernel<PK, QK, true>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo, part_q, part_r,
                            part_a);
     }
     RDK_LAUNCH_CHECK("taylor_write_kernel");
@@ -405,8 +402,7 @@ rdk_status_t run_tli(const KernelHandle &h, RowInput q, int32_t B, float *out, i
     if (rc != RDK_OK) return rc;
     const int bx = (h.N + kThreads * 4 - 1) / (kThreads * 4);
     {
-        TimedLaunch timed("tli_scatter_kernel", st);
-        hipLaunchKernelGGL((tli_scatter_kernel<QK>), dim3(bx, B), dim3(kThreads), 0, st, q.ptr, q.ld, h.slot_of, h.N, w.qstat,
+        RDK_TIMED_LAUNCH("tli_scatter_kernel", (tli_scatter_kernel<QK>), dim3(bx, B), dim3(kThreads), 0, st, q.ptr, q.ld, h.slot_of, h.N, w.qstat,
                            out, ldo);
     }
     RDK_LAUNCH_CHECK("tli_scatter_kernel");

@@ -455,8 +455,7 @@ rdk_status_t prepare_q(const KernelHandle &h, RowInput q, int32_t B, const Spars
     if (rc != RDK_OK) return rc;
     const int pbs = (B + kPosBlock - 1) / kPosBlock;
     {
-        TimedLaunch timed("q_transpose_kernel", st);
-        hipLaunchKernelGGL((q_transpose_kernel<QK>), dim3((h.n + 63) / 64, pbs), dim3(kPrepThreads), 0, st, q.ptr, q.ld, h.n, B,
+        RDK_TIMED_LAUNCH("q_transpose_kernel", (q_transpose_kernel<QK>), dim3((h.n + 63) / 64, pbs), dim3(kPrepThreads), 0, st, q.ptr, q.ld, h.n, B,
                            w.qpart, w.q_splits, rows_vectorisable(q.ptr, q.ld, q.kind), w.zinv, w.qT);
     }
     RDK_LAUNCH_CHECK("q_transpose_kernel");
@@ -471,8 +470,7 @@ rdk_status_t run_sparse(const KernelHandle &h, RowInput q, int32_t B, float *out
     if (rc != RDK_OK) return rc;
     const SparseArgs a = make_args(h, w, B, out, ldo);
     {
-        TimedLaunch timed("sparse_product_kernel", st);
-        hipLaunchKernelGGL((sparse_product_kernel<-1, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, FuseArgs{});
+        RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<-1, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, FuseArgs{});
     }
     RDK_LAUNCH_CHECK("sparse_product_kernel");
     return RDK_OK;
@@ -502,11 +500,10 @@ rdk_status_t run_sparse_fused(const KernelHandle &h, const FusedCall &c, void *w
     if (rc != RDK_OK) return rc;
     const SparseArgs a = make_args(h, w, B, c.q_prime, c.ldo);
     {
-        TimedLaunch timed("sparse_product_kernel", st);
         if (c.q_prime)
-            hipLaunchKernelGGL((sparse_product_kernel<PK, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+            RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<PK, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
         else
-            hipLaunchKernelGGL((sparse_product_kernel<PK, false>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+            RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<PK, false>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
     }
     RDK_LAUNCH_CHECK("sparse_product_kernel");
     FinalizeArgs fa{};

@@ -145,8 +145,7 @@ rdk_status_t run_verify(const rdk_verify_desc_t &d, RowInput p, const float *q, 
         if (rc != RDK_OK) return rc;
     }
     {
-        TimedLaunch timed("verify_stream_kernel", st);
-        hipLaunchKernelGGL((verify_stream_kernel<KIND, HAS_Q>), dim3((unsigned)d.B * splits), dim3(kStreamThreads), 0, st, p.ptr,
+        RDK_TIMED_LAUNCH("verify_stream_kernel", (verify_stream_kernel<KIND, HAS_Q>), dim3((unsigned)d.B * splits), dim3(kStreamThreads), 0, st, p.ptr,
                            p.ld, q, ldq, d.N, splits, vec_p, vec_q, w);
     }
     RDK_LAUNCH_CHECK("verify_stream_kernel");
@@ -195,8 +194,7 @@ rdk_status_t launch_sequence_scan(const rdk_verify_desc_t &d, const int32_t *dra
 {
     const int S = d.B / d.gamma;
     {
-        TimedLaunch timed("sequence_scan_kernel", st);
-        hipLaunchKernelGGL(sequence_scan_kernel, dim3((S + 63) / 64), dim3(64), 0, st, S, d.gamma, draft_ids, accept, resid_ids,
+        RDK_TIMED_LAUNCH("sequence_scan_kernel", sequence_scan_kernel, dim3((S + 63) / 64), dim3(64), 0, st, S, d.gamma, draft_ids, accept, resid_ids,
                            n_accepted, out_tokens);
     }
     RDK_LAUNCH_CHECK("sequence_scan_kernel");
