@@ -1,6 +1,8 @@
 """Shared helpers of the GPU parity tests: tolerances, and validity checks for sampled ids."""
 import numpy as np
 
+import oracle
+
 # fp32 paths: |g - o| <= RTOL |o| + ATOL elementwise; bf16 dense path: RTOL_BF16.
 RTOL, ATOL = 1e-5, 1e-7
 RTOL_BF16 = 2e-3
@@ -39,3 +41,33 @@ def check_sampled_ids(weights, u, gpu_ids, oracle_ids, tol=CDF_TOL, what=""):
         assert weights[b, g] > 0, "%s row %d: gpu id %d has zero weight" % (what, b, g)
         assert c[g] > thr - tol * total and (g == 0 or c[g - 1] <= thr + tol * total), (what, b, g, o)
     return exact
+
+
+def check_verify_outputs(o, ref, p64, q64, seed, offset, gamma, p_kind, min_exact=0.95):
+    """Device outputs `o` of a verification against the oracle's `ref` for target rows p64 and drafter rows q64."""
+    B = p64.shape[0]
+    us = np.array([oracle.uniforms(seed, offset + b) for b in range(B)])
+    g_resid = o.resid_ids.cpu().numpy()
+    if q64 is None:
+        check_sampled_ids(p64, us[:, 3], g_resid, ref["resid_ids"], what="bonus")
+        assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], what="sum p")
+        assert not o.accept.any() and not o.alpha.any()
+        return
+    assert_close(o.alpha.cpu().numpy(), ref["alpha"], rtol=2 * RTOL, what="alpha")
+    assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], rtol=2 * RTOL, atol=2e-7, what="residual mass")
+    g_draft = o.draft_ids.cpu().numpy()
+    n_d = check_sampled_ids(q64, us[:, 0], g_draft, ref["draft_ids"], what="draft")
+    n_r = check_sampled_ids(np.maximum(p64 - q64, 0), us[:, 2], g_resid, ref["resid_ids"], what="residual")
+    assert n_d >= min_exact * B and n_r >= min_exact * B
+    # acceptance is decided exactly (fp64 product) on both sides wherever the draft token and the inputs agree
+    same = g_draft == ref["draft_ids"]
+    g_acc = o.accept.cpu().numpy()
+    for b in np.nonzero(same & (g_acc != ref["accept"]))[0]:      # a flip is allowed only at a near-tie
+        d_ = g_draft[b]
+        assert d_ >= 0 and abs(us[b, 1] * q64[b, d_] - p64[b, d_]) <= 2e-5 * p64[b, d_], (b, d_)
+    if gamma:
+        n_acc, toks = oracle.sequence_scan(g_acc, g_draft, g_resid, gamma)     # scan of the device's own flags
+        assert np.array_equal(o.n_accepted.cpu().numpy(), n_acc)
+        assert np.array_equal(o.out_tokens.cpu().numpy(), toks)
+        if same.all() and np.array_equal(g_acc, ref["accept"]) and np.array_equal(g_resid, ref["resid_ids"]):
+            assert np.array_equal(o.out_tokens.cpu().numpy(), ref["out_tokens"])
