@@ -1,7 +1,7 @@
 // Per-row finish of the verification step (Alg. 4, steps 2 and 4-10), shared by the stand-alone
 // verify call and by the fused redistribute+verify calls.
 //
-// Input: for every row three partial sums per block of SUB*256 ids (sum q', sum max(0, p - q'),
+// Input: for every row three partial sums per block of BLOCK ids (sum q', sum max(0, p - q'),
 // sum min(p, q')), written by a streaming pass.  One wavefront per row then
 //   1. adds the partials in fp64 (alpha, residual mass, sum q'), draws the Philox uniforms,
 //   2. finds the blocks in which the two inverse-CDF thresholds are crossed,
@@ -64,7 +64,7 @@ struct QpMemory {
 template <int K, int SUB, class Row>
 __device__ __forceinline__ void stage_block(const Row &r, typename Row::Pending (&t)[SUB], int base, bool wanted)
 {
-    if (!wanted) return;
+    if (!wanted) return;   // also false for the lanes beyond a block shorter than 256 ids
 #pragma unroll
     for (int i = 0; i < SUB; ++i) r.template stage<K>(t[i], (int64_t)base + i * 256 + lane_id() * 4);
 }
@@ -111,25 +111,26 @@ __device__ __forceinline__ int locate_block(const float *part, int nblk, int per
 }
 
 // The same on partials that the lanes already hold in registers (at most kRegBlocks per lane): saves the
-// dependent re-read.  v[t] = partial of block lane * per_lane + t (0 beyond nblk).
-constexpr int kRegBlocks = 8;
-
-__device__ __forceinline__ void load_partials(const float *part, int nblk, int per_lane, float (&v)[kRegBlocks])
+// dependent re-read.  v[t] = partial of block lane * per_lane + t (0 beyond nblk); R = blocks a lane can hold.
+template <int R>
+__device__ __forceinline__ void load_partials(const float *part, int nblk, int per_lane, float (&v)[R])
 {
     const int c0 = lane_id() * per_lane;
 #pragma unroll
-    for (int t = 0; t < kRegBlocks; ++t) v[t] = (t < per_lane && c0 + t < nblk) ? part[c0 + t] : 0.f;
+    for (int t = 0; t < R; ++t) v[t] = (t < per_lane && c0 + t < nblk) ? part[c0 + t] : 0.f;
 }
 
-__device__ __forceinline__ double sum_partials(const float (&v)[kRegBlocks])
+template <int R>
+__device__ __forceinline__ double sum_partials(const float (&v)[R])
 {
     double s = 0.0;
 #pragma unroll
-    for (int t = 0; t < kRegBlocks; ++t) s += (double)v[t];
+    for (int t = 0; t < R; ++t) s += (double)v[t];
     return s;
 }
 
-__device__ __forceinline__ int locate_block_regs(const float (&v)[kRegBlocks], int nblk, int per_lane, double lane_sum, double thr,
+template <int R>
+__device__ __forceinline__ int locate_block_regs(const float (&v)[R], int nblk, int per_lane, double lane_sum, double thr,
                                                  double &prefix_before)
 {
     const double incl = wave_inclusive_scan(lane_sum);
@@ -140,7 +141,7 @@ __device__ __forceinline__ int locate_block_regs(const float (&v)[kRegBlocks], i
     int blk = -1;
     double pre = incl - lane_sum;
 #pragma unroll
-    for (int t = 0; t < kRegBlocks; ++t) {
+    for (int t = 0; t < R; ++t) {
         const double x = (double)v[t];
         const bool here = blk < 0 && t < per_lane && c0 + t < nblk && pre + x > thr;
         if (here) blk = c0 + t;
@@ -197,9 +198,13 @@ __device__ __forceinline__ int search_block(const float4 (&wv)[SUB], int base, d
 
 constexpr int kFinalizeRows = 8;   // rows (wavefronts) per workgroup at most: leaves 256 VGPRs per lane
 
-template <int KIND, int SUB, bool HAS_Q, class QP>
+// BLOCK = ids per block of partial sums: a multiple of 256, or 64 (then only 16 lanes of the wavefront hold ids).
+template <int KIND, int BLOCK, bool HAS_Q, class QP>
 __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) void verify_finalize_kernel(FinalizeArgs a, QP qp)
 {
+    constexpr int SUB = BLOCK >= 256 ? BLOCK / 256 : 1;
+    constexpr int kLanes = BLOCK >= 256 ? kWave : BLOCK / 4;      // lanes that hold ids of a block
+    constexpr int kRegBlocks = QP::kSpreadRows ? 32 : 8;          // block partials a lane keeps in registers
     __shared__ int32_t sh_draft[kFinalizeRows], sh_resid[kFinalizeRows];
     __shared__ uint8_t sh_acc[kFinalizeRows];
     const rdk_verify_desc_t &d = a.d;
@@ -265,7 +270,8 @@ __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) vo
         // 3. both blocks are fetched together (q' and the target weights of each), then scanned.  A draft token
         //    that the caller supplied may lie anywhere: its two values are requested in the same round trip.
         float4 wd[SUB], pd[SUB], wp[SUB], wq[SUB];
-        const int base_d = max(blk_d, 0) * (SUB * 256), base_r = max(blk_r, 0) * (SUB * 256);
+        const int base_d = max(blk_d, 0) * BLOCK, base_r = max(blk_r, 0) * BLOCK;
+        const bool holds = lane < kLanes;
         const bool same = draw_draft && blk_r == blk_d;
         float pd_w = 0.f, qd = 0.f;
         const bool given = HAS_Q && !d.sample_draft && dtok >= 0 && dtok < N;
@@ -275,25 +281,26 @@ __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) vo
         }
         typename QP::Row::Pending td[SUB], tr[SUB];
         const bool want_r = HAS_Q && !same;
-        stage_block<0, SUB>(qrow, td, base_d, draw_draft);
-        stage_block<0, SUB>(qrow, tr, base_r, want_r);
+        const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f), fill4 = make_float4(pfill, pfill, pfill, pfill);
+        stage_block<0, SUB>(qrow, td, base_d, draw_draft && holds);
+        stage_block<0, SUB>(qrow, tr, base_r, want_r && holds);
 #pragma unroll
         for (int i = 0; i < SUB; ++i) {
-            if (draw_draft) pd[i] = load4<KIND>(pr, base_d + i * 256 + lane * 4, N, a.vec_p, pfill);
-            if (!same) wp[i] = load4<KIND>(pr, base_r + i * 256 + lane * 4, N, a.vec_p, pfill);
+            if (draw_draft) pd[i] = holds ? load4<KIND>(pr, base_d + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
+            if (!same) wp[i] = holds ? load4<KIND>(pr, base_r + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
         }
         if (QP::kStages > 1) {
-            stage_block<1, SUB>(qrow, td, base_d, draw_draft);
-            stage_block<1, SUB>(qrow, tr, base_r, want_r);
+            stage_block<1, SUB>(qrow, td, base_d, draw_draft && holds);
+            stage_block<1, SUB>(qrow, tr, base_r, want_r && holds);
         }
         if (QP::kStages > 2) {
-            stage_block<2, SUB>(qrow, td, base_d, draw_draft);
-            stage_block<2, SUB>(qrow, tr, base_r, want_r);
+            stage_block<2, SUB>(qrow, td, base_d, draw_draft && holds);
+            stage_block<2, SUB>(qrow, tr, base_r, want_r && holds);
         }
 #pragma unroll
         for (int i = 0; i < SUB; ++i) {
-            if (draw_draft) wd[i] = qrow.result(td[i], (int64_t)base_d + i * 256 + lane * 4);
-            if (want_r) wq[i] = qrow.result(tr[i], (int64_t)base_r + i * 256 + lane * 4);
+            if (draw_draft) wd[i] = holds ? qrow.result(td[i], (int64_t)base_d + i * 256 + lane * 4) : zero4;
+            if (want_r) wq[i] = holds ? qrow.result(tr[i], (int64_t)base_r + i * 256 + lane * 4) : zero4;
             if (same) {
                 wp[i] = pd[i];
                 wq[i] = wd[i];
@@ -363,7 +370,7 @@ __global__ void sequence_scan_kernel(int S, int gamma, const int32_t *draft_ids,
 rdk_status_t launch_sequence_scan(const rdk_verify_desc_t &d, const int32_t *draft_ids, const uint8_t *accept,
                                   const int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens, hipStream_t st);
 
-template <int KIND, int SUB, bool HAS_Q, class QP>
+template <int KIND, int BLOCK, bool HAS_Q, class QP>
 rdk_status_t launch_finalize(FinalizeArgs a, QP qp, hipStream_t st)
 {
     const rdk_verify_desc_t &d = a.d;
@@ -372,7 +379,7 @@ rdk_status_t launch_finalize(FinalizeArgs a, QP qp, hipStream_t st)
     a.rows_per_block = a.scan_here ? d.gamma : (QP::kSpreadRows ? 1 : 4);
     const int blocks = (d.B + a.rows_per_block - 1) / a.rows_per_block;
     {
-        RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_kernel<KIND, SUB, HAS_Q, QP>), dim3(blocks), dim3(a.rows_per_block * kWave), 0, st, a, qp);
+        RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_kernel<KIND, BLOCK, HAS_Q, QP>), dim3(blocks), dim3(a.rows_per_block * kWave), 0, st, a, qp);
     }
     RDK_LAUNCH_CHECK("verify_finalize_kernel");
     if (d.gamma > 0 && !a.scan_here && (a.n_accepted || a.out_tokens))

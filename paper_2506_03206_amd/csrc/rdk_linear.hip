@@ -391,7 +391,7 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     fa.nblk = nchunks;
     fa.draft_ids = c->draft_ids; fa.accept = c->accept; fa.alpha = c->alpha; fa.resid_mass = c->resid_mass;
     fa.resid_ids = c->resid_ids; fa.n_accepted = c->n_accepted; fa.out_tokens = c->out_tokens;
-    return launch_finalize<PK, 4, true, QpTaylor<PK, QK>>(fa, QpTaylor<PK, QK>{a}, st);
+    return launch_finalize<PK, 1024, true, QpTaylor<PK, QK>>(fa, QpTaylor<PK, QK>{a}, st);
 }
 
 template <int QK>

@@ -23,7 +23,8 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kPrepThreads = 256; // transposition kernel
 constexpr int kPosBlock = 32;    // positions per gather: 32 fp32 = one 128-byte line
 constexpr int kTileIds = 256;    // target ids per workgroup
-constexpr int kStageLd = kTileIds + 1;
+constexpr int kStageLd = kTileIds + 4;   // rows stay 16-byte aligned for the float4 read-out
+constexpr int kSubIds = 64;       // ids per block of verification sums in the fused form: 16 lanes x 4 ids
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -248,36 +249,45 @@ struct FuseArgs {
     bool vec_p;
     const SoftStat *pstat;
     int p_splits;
-    float *part_q, *part_r, *part_a;   // [B, tiles]
+    float *part_q, *part_r, *part_a;   // [B, tiles * 4]: one entry per 64-id block
 };
 
+// sum over each row of 16 lanes, the same bits in all 16
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    return v;
+}
+
 // PK < 0: plain product (q' is written).  PK >= 0: fused with the verification sums against the target
-// rows of kind PK -- per (position, 256-id tile) the sums of q', max(0, p - q') and min(p, q') --
+// rows of kind PK -- per (position, 64-id block) the sums of q', max(0, p - q') and min(p, q') --
 // and q' is written only if WRITE_Q.
 template <int PK, bool WRITE_Q>
 __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, FuseArgs f)
 {
     constexpr bool FUSE = PK >= 0;
     constexpr int PKIND = FUSE ? PK : RDK_PROB_F32;
-    __shared__ float stage[kPosBlock][kStageLd];
+    __shared__ __attribute__((aligned(16))) float stage[kPosBlock][kStageLd];
     int pb, tile;
     if (!xcd_work(a, pb, tile)) return;
     const int j0 = tile * kTileIds;
-    // each wavefront finishes 8 of the 32 rows; a lane holds ids j0 + lane + 64 e (conflict-free LDS reads,
-    // 256-byte coalesced global accesses).  The target values are requested before the gathers start.
+    // each wavefront finishes 4 of the 32 rows; a lane holds the ids j0 + 4 lane .. + 3 (one 16-byte access per row
+    // for the target values, for the staged q' and for the store).  The target values are requested before the
+    // gathers start.
     const int wid = threadIdx.x / kWave, lane = lane_id();
     constexpr int kRowsPerWave = kPosBlock / kWaves;
-    float praw[kRowsPerWave][4];
+    const float pfill = PKIND == RDK_PROB_F32 ? 0.f : -INFINITY;
+    const int jl = j0 + 4 * lane;
+    float4 praw[kRowsPerWave];
     if (FUSE) {
 #pragma unroll
         for (int rr = 0; rr < kRowsPerWave; ++rr) {
             const int64_t b = (int64_t)pb * kPosBlock + wid * kRowsPerWave + rr;
-            const void *pr = row_ptr<PKIND>(f.p, f.ldp, b < a.B ? b : 0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = j0 + lane + 64 * e;
-                praw[rr][e] = (b < a.B && j < a.N) ? load1<PKIND>(pr, j) : (PKIND == RDK_PROB_F32 ? 0.f : -INFINITY);
-            }
+            praw[rr] = b < a.B ? load4<PKIND>(row_ptr<PKIND>(f.p, f.ldp, b), jl, a.N, f.vec_p, pfill)
+                               : make_float4(pfill, pfill, pfill, pfill);
         }
     }
     sparse_tile(a, pb, j0, stage);
@@ -286,14 +296,19 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
         const int r = wid * kRowsPerWave + rr;
         const int64_t b = (int64_t)pb * kPosBlock + r;
         if (b >= a.B) break;
-        float qv[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) qv[e] = (j0 + lane + 64 * e < a.N) ? stage[r][lane + 64 * e] : 0.f;
+        const float4 sv = *(const float4 *)&stage[r][4 * lane];
+        const float qv[4] = {jl + 0 < a.N ? sv.x : 0.f, jl + 1 < a.N ? sv.y : 0.f, jl + 2 < a.N ? sv.z : 0.f,
+                             jl + 3 < a.N ? sv.w : 0.f};
         if (WRITE_Q) {
-            float *o = a.out + b * a.ldo + j0 + lane;
+            float *o = a.out + b * a.ldo + jl;
+            if (a.vec_o && jl + 3 < a.N) {
+                const f32x4 v = {qv[0], qv[1], qv[2], qv[3]};
+                __builtin_nontemporal_store(v, (f32x4 *)o);
+            } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (j0 + lane + 64 * e < a.N) __builtin_nontemporal_store(qv[e], o + 64 * e);
+                for (int e = 0; e < 4; ++e)
+                    if (jl + e < a.N) o[e] = qv[e];
+            }
         }
         if (FUSE) {
             float m = 0.f, inv = 1.f;
@@ -302,19 +317,21 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
                 m = rs.m;
                 inv = 1.0f / rs.s;
             }
+            const float pr4[4] = {praw[rr].x, praw[rr].y, praw[rr].z, praw[rr].w};
             float sq = 0.f, sr = 0.f, sa = 0.f;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float pe = to_weight<PKIND>(praw[rr][e], m, inv);
+                const float pe = to_weight<PKIND>(pr4[e], m, inv);
                 sq += qv[e];
                 sr += fmaxf(pe - qv[e], 0.f);
                 sa += fminf(pe, qv[e]);
             }
-            sq = wave_sum(sq);
-            sr = wave_sum(sr);
-            sa = wave_sum(sa);
-            if (lane == 0) {
-                const int64_t o = b * a.tiles + tile;
+            // one block of sums per 16 lanes (64 ids): reduce inside each row of the wavefront only
+            sq = row16_sum(sq);
+            sr = row16_sum(sr);
+            sa = row16_sum(sa);
+            if ((lane & 15) == 0) {
+                const int64_t o = b * ((int64_t)a.tiles * (kTileIds / kSubIds)) + tile * (kTileIds / kSubIds) + (lane >> 4);
                 f.part_q[o] = sq;
                 f.part_r[o] = sr;
                 f.part_a[o] = sa;
@@ -323,7 +340,7 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
     }
 }
 
-// q' of one position recomputed from the sparse kernel (the finalize step needs two 256-id blocks of it).
+// q' of one position recomputed from the sparse kernel (the finalize step needs two 64-id blocks of it).
 struct QpSparse {
     static constexpr bool kSpreadRows = true;
     static constexpr int kStages = 3;
@@ -429,8 +446,8 @@ struct SparseFusedWs {
 
 size_t fused_extra_bytes(const KernelHandle &h, int32_t B)
 {
-    const size_t tiles = (h.N + kTileIds - 1) / kTileIds;
-    return align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256) + 3 * align_up((size_t)B * tiles * sizeof(float), 256);
+    const size_t blocks = (size_t)((h.N + kTileIds - 1) / kTileIds) * (kTileIds / kSubIds);
+    return align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256) + 3 * align_up((size_t)B * blocks * sizeof(float), 256);
 }
 
 SparseArgs make_args(const KernelHandle &h, const SparseWs &w, int32_t B, float *out, int64_t ldo)
@@ -486,8 +503,8 @@ rdk_status_t run_sparse_fused(const KernelHandle &h, const FusedCall &c, void *w
     f.p = c.p.ptr; f.ldp = c.p.ld; f.vec_p = rows_vectorisable(c.p.ptr, c.p.ld, c.p.kind);
     f.p_splits = row_splits(B, h.N, kStatThreads / kWave);
     f.pstat = (SoftStat *)p; p += align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256);
-    const size_t tiles = (h.N + kTileIds - 1) / kTileIds;
-    const size_t per = align_up((size_t)B * tiles * sizeof(float), 256);
+    const size_t blocks = (size_t)((h.N + kTileIds - 1) / kTileIds) * (kTileIds / kSubIds);
+    const size_t per = align_up((size_t)B * blocks * sizeof(float), 256);
     f.part_q = (float *)p; p += per;
     f.part_r = (float *)p; p += per;
     f.part_a = (float *)p;
@@ -511,10 +528,10 @@ rdk_status_t run_sparse_fused(const KernelHandle &h, const FusedCall &c, void *w
     fa.p = c.p.ptr; fa.ldp = c.p.ld; fa.vec_p = f.vec_p;
     fa.pstat = f.pstat; fa.p_splits = f.p_splits;
     fa.part_q = f.part_q; fa.part_r = f.part_r; fa.part_a = f.part_a;
-    fa.nblk = (int)tiles;
+    fa.nblk = (int)blocks;
     fa.draft_ids = c.draft_ids; fa.accept = c.accept; fa.alpha = c.alpha; fa.resid_mass = c.resid_mass;
     fa.resid_ids = c.resid_ids; fa.n_accepted = c.n_accepted; fa.out_tokens = c.out_tokens;
-    return launch_finalize<PK, 1, true, QpSparse>(fa, QpSparse{a}, st);
+    return launch_finalize<PK, kSubIds, true, QpSparse>(fa, QpSparse{a}, st);
 }
 
 }  // namespace

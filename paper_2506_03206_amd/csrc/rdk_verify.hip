@@ -158,7 +158,7 @@ rdk_status_t run_verify(const rdk_verify_desc_t &d, RowInput p, const float *q, 
     fa.draft_ids = draft_ids; fa.accept = accept; fa.alpha = alpha; fa.resid_mass = resid_mass;
     fa.resid_ids = resid_ids; fa.n_accepted = n_accepted; fa.out_tokens = out_tokens;
     QpMemory qp{q, ldq, vec_q, d.N};
-    return launch_finalize<KIND, 4, HAS_Q, QpMemory>(fa, qp, st);
+    return launch_finalize<KIND, 1024, HAS_Q, QpMemory>(fa, qp, st);
 }
 
 }  // namespace
