@@ -1,5 +1,6 @@
 // Exact redistribution (Alg. 1, step 2):  P'[b, j] = sum_s Q'[b, s] M[s, j]  with a dense kernel M.
-//   fp32 kernel:  LDS-tiled fp32 FMA product, split over the kept slots, fixed-order reduction.
+//   fp32 kernel:  fp32 matrix cores (v_mfma_f32_32x32x2_f32), M read straight from its row-major rows,
+//                 split over the kept slots, fixed-order reduction.
 //   bf16 kernel:  both operands rounded to bf16, fp32 accumulation on the matrix cores
 //                 (v_mfma_f32_32x32x16_bf16), rows rescaled so that they sum to one.
 // Step 1 (Eq. 1) is folded in: rows of Q' are the drafter rows divided by their sums.
@@ -10,85 +11,124 @@ namespace rdk {
 namespace {
 
 // ------------------------------------------------------------------------------------------------ fp32
-constexpr int kColsF = 128;   // columns (target ids) per workgroup
-constexpr int kRowsF = 64;    // positions per workgroup
-constexpr int kDepthF = 32;   // kept slots per LDS stage
+// At 64 positions the product needs 2 n N flop against 4 n N bytes of M: 32 flop per byte, more than the fp32
+// vector or matrix units deliver per HBM byte (157 TFLOP/s : 8 TB/s = 20), so this path is bound by the fp32 MFMA
+// rate, not by HBM.  The 32x32x2 MFMA takes ONE value per lane and operand: lane l supplies A[row l % 32][k = l / 32]
+// and B[k = l / 32][col l % 32].  Four MFMAs e = 0..3 share one 16-byte load of M per lane by giving column c of
+// MFMA e the target id j0 + 4 c + e: lane (c, g) then needs M[s + g][j0 + 4c .. + 3], which is contiguous in the
+// row-major M -- no packing of M, no LDS.  The results of the four MFMAs of a lane are again four consecutive ids.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+constexpr int kRowGroup = 64;    // positions per wavefront tile: two 32-row MFMA blocks
+constexpr int kColSet = 128;     // target ids per wavefront tile
+constexpr int kSlotGroup = 8;    // kept slots per A record: four MFMA steps of two slots
+constexpr int kGroupsUnroll = 3; // slot groups per unrolled loop body (depth of the load ring)
+
+// A records: for row block rb (32 positions) and slot group kq one 1 KB record; lane l = 32 g + r holds the four
+// unnormalised drafter weights of position 32 rb + r at slots 8 kq + 2 t + g, t = 0..3.  Zero beyond B and n.
 template <int QK>
-__global__ __launch_bounds__(256) void exact_f32_kernel(const void *q, int64_t ldq, const SoftStat *qstat, const float *M,
-                                                        int64_t ldm, int n, int N, int B, int slots_per_split,
-                                                        float *dst, int64_t ldd, int64_t split_stride, bool scale_here)
+__global__ void prep_a_f32_kernel(const void *q, int64_t ldq, const SoftStat *qstat, int n, int B, int KQ, int64_t records,
+                                  float *Ap)
 {
-    __shared__ float Qs[kDepthF][kRowsF + 4];
-    __shared__ float Ms[kDepthF][kColsF + 4];
-    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
-    const int j0 = blockIdx.x * kColsF, b0 = blockIdx.y * kRowsF;
-    const int s_begin = blockIdx.z * slots_per_split, s_end = min(n, s_begin + slots_per_split);
-    float acc[8][4];
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= records * kWave) return;
+    const int l = (int)(idx % kWave);
+    const int64_t rec = idx / kWave;
+    const int kq = (int)(rec % KQ);
+    const int b = (int)(rec / KQ) * 32 + l % 32, g = l / 32;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (b < B) {
+        const void *qr = row_ptr<QK>(q, ldq, b);
+        const float qm = QK == RDK_PROB_F32 ? 0.f : qstat[b].m;
 #pragma unroll
-    for (int r = 0; r < 8; ++r)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
-
-    // loader roles
-    const int q_row = threadIdx.x / 4, q_k0 = (threadIdx.x % 4) * 8;   // 64 rows x 32 slots: 8 slots per thread
-    const void *qr = (b0 + q_row < B) ? row_ptr<QK>(q, ldq, b0 + q_row) : nullptr;
-    const float qm = (qr && QK != RDK_PROB_F32) ? qstat[b0 + q_row].m : 0.f;
-
-    for (int s0 = s_begin; s0 < s_end; s0 += kDepthF) {
-        __syncthreads();
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int s = s0 + q_k0 + e;
-            Qs[q_k0 + e][q_row] = (qr && s < s_end) ? to_weight<QK>(load1<QK>(qr, s), qm, 1.f) : 0.f;
-        }
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int f = it * 256 + threadIdx.x;           // float4 index in the 32 x 128 tile
-            const int kr = f / (kColsF / 4), c4 = (f % (kColsF / 4)) * 4;
-            const int s = s0 + kr;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (s < s_end) {
-                const float *src = M + (int64_t)s * ldm + j0 + c4;
-                if (j0 + c4 + 3 < N && (ldm % 4 == 0)) {
-                    v = *(const float4 *)src;
-                } else {
-                    if (j0 + c4 + 0 < N) v.x = src[0];
-                    if (j0 + c4 + 1 < N) v.y = src[1];
-                    if (j0 + c4 + 2 < N) v.z = src[2];
-                    if (j0 + c4 + 3 < N) v.w = src[3];
-                }
-            }
-            *(float4 *)&Ms[kr][c4] = v;
-        }
-        __syncthreads();
-#pragma unroll 8
-        for (int kq = 0; kq < kDepthF; ++kq) {
-            const float4 mv = *(const float4 *)&Ms[kq][tx * 4];
-            const float4 qa = *(const float4 *)&Qs[kq][ty * 8];
-            const float4 qb = *(const float4 *)&Qs[kq][ty * 8 + 4];
-            const float qv[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                acc[r][0] += qv[r] * mv.x;
-                acc[r][1] += qv[r] * mv.y;
-                acc[r][2] += qv[r] * mv.z;
-                acc[r][3] += qv[r] * mv.w;
-            }
+        for (int t = 0; t < 4; ++t) {
+            const int s = kq * kSlotGroup + 2 * t + g;
+            if (s < n) v[t] = to_weight<QK>(load1<QK>(qr, s), qm, 1.f);
         }
     }
+    *(float4 *)(Ap + idx * 4) = make_float4(v[0], v[1], v[2], v[3]);
+}
+
+// One wavefront per (128 target ids, 64 positions, one split of the slot groups).  Loads run two slot groups
+// ahead of the MFMAs through a ring of three register sets; the split length is a multiple of three groups (the
+// A records are zero beyond n, and rows of M are clamped to the last one), so the loop body is straight-line code.
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void exact_f32_mfma_kernel(const float *Ap, const float *M, int64_t ldm, int n, int N, int B,
+                                                               int KQ, int groups_per_split, const SoftStat *qstat, float *dst,
+                                                               int64_t ldd, int64_t split_stride, bool scale_here, bool vec_d)
+{
+    const int lane = lane_id(), c = lane % 32, g = lane / 32;
+    const int j0 = blockIdx.x * kColSet, col = j0 + 4 * c;
+    const int rg = blockIdx.y;
+    const int kq0 = blockIdx.z * groups_per_split, kq_last = kq0 + groups_per_split - 1;
+    const bool full = col + 3 < N;
+    // Rows of M are padded to a multiple of four floats and 16-byte aligned, so a lane whose first id is in range
+    // may always read all four; lanes beyond N read column 0 instead (never stored): the loads need no branch.
+    const int lcol = col < N ? col : 0;
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[rb][e][v] = 0.f;
+    const float4 *a_rec[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) a_rec[rb] = (const float4 *)Ap + ((int64_t)(rg * 2 + rb) * KQ) * kWave + lane;
+
+    float4 a_ring[kGroupsUnroll][2], b_ring[kGroupsUnroll][4];
+    // everything of slot group kq (clamped to the split) into ring entry SLOT
+#define RDK_LOAD_GROUP(SLOT, KQI)                                                                                    \
+    {                                                                                                                \
+        const int kq_ = min((KQI), kq_last);                                                                         \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb) a_ring[SLOT][rb] = a_rec[rb][(int64_t)kq_ * kWave];        \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                              \
+            const int s_ = min(kq_ * kSlotGroup + 2 * t + g, n - 1);                                                 \
+            b_ring[SLOT][t] = *(const float4 *)(M + (int64_t)s_ * ldm + lcol);                                       \
+        }                                                                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                                           \
+    }
+#define RDK_MFMA_GROUP(SLOT)                                                                                         \
+    {                                                                                                                \
+        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                              \
+            const float av_[2] = {t == 0 ? a_ring[SLOT][0].x : t == 1 ? a_ring[SLOT][0].y : t == 2 ? a_ring[SLOT][0].z : a_ring[SLOT][0].w, \
+                                  t == 0 ? a_ring[SLOT][1].x : t == 1 ? a_ring[SLOT][1].y : t == 2 ? a_ring[SLOT][1].z : a_ring[SLOT][1].w}; \
+            const float bv_[4] = {b_ring[SLOT][t].x, b_ring[SLOT][t].y, b_ring[SLOT][t].z, b_ring[SLOT][t].w};       \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e)                                                            \
+                _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                     \
+                    acc[rb][e] = __builtin_amdgcn_mfma_f32_32x32x2f32(av_[rb], bv_[e], acc[rb][e], 0, 0, 0);         \
+        }                                                                                                            \
+    }
+    RDK_LOAD_GROUP(0, kq0)
+    RDK_LOAD_GROUP(1, kq0 + 1)
+    for (int kq = kq0; kq <= kq_last; kq += kGroupsUnroll) {
+        RDK_LOAD_GROUP(2, kq + 2)
+        RDK_MFMA_GROUP(0)
+        RDK_LOAD_GROUP(0, kq + 3)
+        RDK_MFMA_GROUP(1)
+        RDK_LOAD_GROUP(1, kq + 4)
+        RDK_MFMA_GROUP(2)
+    }
+#undef RDK_LOAD_GROUP
+#undef RDK_MFMA_GROUP
+    // D layout of a 32x32 tile: lane l holds column l % 32 and rows 8 * (v / 4) + 4 * (l / 32) + v % 4, v = 0..15
     float *base = dst + (int64_t)blockIdx.z * split_stride;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const int b = b0 + ty * 8 + r;
-        if (b >= B) continue;
-        const float sc = scale_here ? 1.0f / qstat[b].s : 1.f;
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int j = j0 + tx * 4 + c;
-            if (j < N) base[(int64_t)b * ldd + j] = acc[r][c] * sc;
+        for (int v = 0; v < 16; ++v) {
+            const int b = rg * kRowGroup + rb * 32 + 8 * (v / 4) + 4 * g + (v % 4);
+            if (b >= B) continue;
+            const float sc = scale_here ? 1.0f / qstat[b].s : 1.f;
+            const float o[4] = {acc[rb][0][v] * sc, acc[rb][1][v] * sc, acc[rb][2][v] * sc, acc[rb][3][v] * sc};
+            float *drow = base + (int64_t)b * ldd + col;
+            if (full && vec_d) {
+                *(float4 *)drow = make_float4(o[0], o[1], o[2], o[3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < N) drow[e] = o[e];
+            }
         }
-    }
 }
 
 // Sum of the split partials in split order, divided by the drafter row sum (Eq. 1).
@@ -106,7 +146,6 @@ __global__ void exact_reduce_kernel(const float *part, int64_t ldd, int64_t spli
 
 // ------------------------------------------------------------------------------------------------ bf16
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kKStep = 16;          // kept slots per MFMA (32x32x16)
 constexpr int kColBlock = 32;       // target ids per MFMA tile
@@ -331,18 +370,27 @@ inline void bf16_shape(int B, int &W, int &RB)
 struct ExactWs {
     SoftStat *qstat;   // [B]
     float *part;       // fp32 path: [splits, B, N_ld]
+    float *Af;         // fp32 path: A records [B_pad / 32, splits * groups, 64, 4]
     uint16_t *A;       // bf16 path: [B_pad, n_pad]
     float *out_scale;  // bf16 path: [B]
 };
 
-int f32_splits(const KernelHandle &h, int B)
+// Split of the slot groups of the fp32 path: as many wavefronts as fit the chip at two per SIMD (2048) but no more,
+// so that they all run side by side (a few left over for a second round would double the time); splits of a whole
+// number of unrolled loop bodies.  groups = slot groups per split (a multiple of kGroupsUnroll).
+int f32_splits(const KernelHandle &h, int B, int *groups)
 {
-    const int tiles = ((h.N + kColsF - 1) / kColsF) * ((B + kRowsF - 1) / kRowsF);
-    int want = (1024 + tiles - 1) / tiles;
-    const int maxs = (h.n + 8 * kDepthF - 1) / (8 * kDepthF);    // at least 256 slots per split
+    const int tiles = ((h.N + kColSet - 1) / kColSet) * ((B + kRowGroup - 1) / kRowGroup);
+    const int kq_total = (h.n + kSlotGroup - 1) / kSlotGroup;
+    int want = 2048 / tiles;
+    const int maxs = (kq_total + 4 * kGroupsUnroll - 1) / (4 * kGroupsUnroll);    // at least 96 slots per split
     if (want > maxs) want = maxs;
-    if (want > 32) want = 32;
-    return want < 1 ? 1 : want;
+    if (want > 64) want = 64;
+    if (want < 1) want = 1;
+    const int per = ((kq_total + want - 1) / want + kGroupsUnroll - 1) / kGroupsUnroll * kGroupsUnroll;
+    const int splits = (kq_total + per - 1) / per;
+    if (groups) *groups = per;
+    return splits;
 }
 
 template <int QK>
@@ -354,27 +402,31 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
     rdk_status_t rc = launch_row_stats<QK>(q, h.n, B, 1, w.qstat, st);
     if (rc != RDK_OK) return rc;
     if (h.format == RDK_DENSE_F32) {
+        int groups;
+        const int splits = f32_splits(h, B, &groups);
+        const int KQ = splits * groups;
+        const int row_groups = (B + kRowGroup - 1) / kRowGroup;
+        const int64_t records = (int64_t)row_groups * 2 * KQ;
+        w.Af = (float *)p; p += align_up((size_t)records * kWave * 4 * sizeof(float), 256);
         w.part = (float *)p;
-        const int splits = f32_splits(h, B);
-        const int per = (((h.n + splits - 1) / splits) + kDepthF - 1) / kDepthF * kDepthF;
         const int64_t ldd = (h.N + 3) / 4 * 4;
-        dim3 grid((h.N + kColsF - 1) / kColsF, (B + kRowsF - 1) / kRowsF, splits);
+        {
+            RDK_TIMED_LAUNCH("prep_a_f32_kernel", (prep_a_f32_kernel<QK>), dim3((unsigned)((records * kWave + 255) / 256)), dim3(256),
+                             0, st, q.ptr, q.ld, w.qstat, h.n, B, KQ, records, w.Af);
+        }
+        RDK_LAUNCH_CHECK("prep_a_f32_kernel");
+        dim3 grid((h.N + kColSet - 1) / kColSet, row_groups, splits);
         if (splits == 1) {
-            {
-                RDK_TIMED_LAUNCH("exact_f32_kernel", (exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
-                                   B, per, out, ldo, (int64_t)0, true);
-            }
-            RDK_LAUNCH_CHECK("exact_f32_kernel");
+            const bool vec_d = rows_vectorisable(out, ldo, RDK_PROB_F32);
+            RDK_TIMED_LAUNCH("exact_f32_mfma_kernel", exact_f32_mfma_kernel, grid, dim3(kWave), 0, st, w.Af, h.dense, h.ldm, h.n, h.N, B,
+                             KQ, groups, w.qstat, out, ldo, (int64_t)0, true, vec_d);
+            RDK_LAUNCH_CHECK("exact_f32_mfma_kernel");
         } else {
-            {
-                RDK_TIMED_LAUNCH("exact_f32_kernel", (exact_f32_kernel<QK>), grid, dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.dense, h.ldm, h.n, h.N,
-                                   B, per, w.part, ldd, (int64_t)B * ldd, false);
-            }
-            RDK_LAUNCH_CHECK("exact_f32_kernel");
-            {
-                RDK_TIMED_LAUNCH("exact_reduce_kernel", exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part, ldd,
-                                   (int64_t)B * ldd, splits, w.qstat, h.N, out, ldo);
-            }
+            RDK_TIMED_LAUNCH("exact_f32_mfma_kernel", exact_f32_mfma_kernel, grid, dim3(kWave), 0, st, w.Af, h.dense, h.ldm, h.n, h.N, B,
+                             KQ, groups, w.qstat, w.part, ldd, (int64_t)B * ldd, false, true);
+            RDK_LAUNCH_CHECK("exact_f32_mfma_kernel");
+            RDK_TIMED_LAUNCH("exact_reduce_kernel", exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part, ldd,
+                             (int64_t)B * ldd, splits, w.qstat, h.N, out, ldo);
             RDK_LAUNCH_CHECK("exact_reduce_kernel");
         }
         return RDK_OK;
@@ -421,7 +473,10 @@ size_t exact_workspace_bytes(const KernelHandle &h, int32_t B)
 {
     size_t bytes = align_up((size_t)B * sizeof(SoftStat), 256);
     if (h.format == RDK_DENSE_F32) {
-        const int splits = f32_splits(h, B);
+        int groups;
+        const int splits = f32_splits(h, B, &groups);
+        const size_t records = (size_t)((B + kRowGroup - 1) / kRowGroup) * 2 * splits * groups;
+        bytes += align_up(records * kWave * 4 * sizeof(float), 256);
         if (splits > 1) bytes += align_up((size_t)splits * B * ((h.N + 3) / 4 * 4) * sizeof(float), 256);
     } else if (h.format == RDK_DENSE_BF16) {
         int W, RB;
