@@ -6,8 +6,8 @@ redistribution with the top-k sparse kernel (Alg. 1 steps 1-2) and verification 
 entry point rdk_redistribute_verify (default) or as rdk_redistribute_linear -> rdk_verify_sample.
 Prints ONE JSON line: positions/s, the roofline of the dominant kernel (timed live with HIP events
 inside the library), and the CPU oracle timed on a bounded sample of the same workload.  Unless --no-extra is
-given, "extra" also carries the other linear form (Eq. 3) on the same batch and the exact dense bf16 product
-(N=256000, n=32000, B=512) against the MFMA peak.
+given, "extra" also carries the other linear form (Eq. 3) on the same batch and the exact dense products (bf16 at
+N=256000, n=32000, B=512; fp32 at N=32000, n=8000, B=64) against the MFMA peaks.
 
   python bench.py [--steps K] [--warmup W] [--mode sparse|taylor] [--path fused|twocall] [--workload NAME] [--no-cpu] [--no-extra]
 """
@@ -21,6 +21,7 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+MFMA_F32_PEAK_TFLOPS = 157.3    # MI355X fp32 matrix, published
 
 
 def algorithmic_bytes(kernel, w, B, kk, fused, esz):
@@ -134,20 +135,24 @@ def run_linear(args, rdk, synth, torch, w, vocab, batch, mode_name, path, steps,
             "accept_rate": float(vout.accept.float().mean().item()), "mean_alpha": float(vout.alpha.mean().item())}
 
 
-def run_exact_bf16(rdk, synth, torch, calls=5):
-    """Exact dense redistribution (Alg. 1 with the full M) as a bf16 MFMA contraction at N=256000, n=32000, B=512."""
-    w = synth.WORKLOADS["dense256k"]
+def run_exact(rdk, synth, torch, wname, fmt, calls=5):
+    """Exact dense redistribution (Alg. 1 with the full M): bf16 MFMA contraction at N=256000, n=32000, B=512, or the
+    fp32 one at N=32000, n=8000, B=64.  Both are bound by the matrix cores (the fp32 one needs 32 flop per byte of M,
+    more than fp32 peak : HBM peak = 20)."""
+    w = synth.WORKLOADS[wname]
     dev = torch.device("cuda:0")
     bias, kept, E, rng = synth.make_vocab(w)
     batch = synth.make_batch(w, bias, kept, rng)
-    kern = rdk.rdk_build_kernel(w.N, torch.from_numpy(kept).to(dev), rdk.DENSE_BF16, embeddings=torch.from_numpy(E).to(dev),
-                                tau=w.tau)
+    kern = rdk.rdk_build_kernel(w.N, torch.from_numpy(kept).to(dev), rdk.DENSE_BF16 if fmt == "bf16" else rdk.DENSE_F32,
+                                embeddings=torch.from_numpy(E).to(dev), tau=w.tau)
     q = torch.from_numpy(batch["q_hat"]).to(dev)
     out = torch.empty((w.B, w.N), dtype=torch.float32, device=dev)
     for _ in range(2):
         rdk.rdk_redistribute_exact(kern, q, out=out)
     torch.cuda.synchronize()
-    rdk.rdk_timing_select("exact_bf16_kernel")
+    kname = "exact_bf16_kernel" if fmt == "bf16" else "exact_f32_mfma_kernel"
+    peak = MFMA_BF16_PEAK_TFLOPS if fmt == "bf16" else MFMA_F32_PEAK_TFLOPS
+    rdk.rdk_timing_select(kname)
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     start.record()
     for _ in range(calls):
@@ -156,16 +161,17 @@ def run_exact_bf16(rdk, synth, torch, calls=5):
     torch.cuda.synchronize()
     rdk.rdk_timing_select(None)
     ms_call = start.elapsed_time(stop) / calls
-    cnt, kms = rdk.rdk_timing_read("exact_bf16_kernel")
+    cnt, kms = rdk.rdk_timing_read(kname)
     flops = 2.0 * w.B * w.n * w.N
     k_tf = flops / (kms / cnt * 1e-3) / 1e12
     row_err = float((out.double().sum(1) - 1).abs().max().item())
+    esz = 2 if fmt == "bf16" else 4
     del kern, out, q
     torch.cuda.empty_cache()
-    return {"workload": "dense256k: N=%d n=%d B=%d, M bf16 %.1f GB" % (w.N, w.n, w.B, 2.0 * w.n * w.N / 1e9),
+    return {"workload": "%s: N=%d n=%d B=%d, M %s %.2f GB" % (wname, w.N, w.n, w.B, fmt, esz * w.n * w.N / 1e9),
             "ms_per_call": round(ms_call, 3), "positions_per_s": round(w.B / (ms_call * 1e-3), 1),
-            "roofline": {"kernel": "exact_bf16_kernel", "bound": "mfma", "achieved": round(k_tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
-                         "unit": "TFLOP/s", "frac": round(k_tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+            "roofline": {"kernel": kname, "bound": "mfma", "achieved": round(k_tf, 1), "peak": peak,
+                         "unit": "TFLOP/s", "frac": round(k_tf / peak, 4), "traffic": None,
                          "avg_launch_us": round(kms / cnt * 1e3, 1), "algorithmic_flops_per_launch": flops},
             "call_TFLOPs": round(flops / (ms_call * 1e-3) / 1e12, 1), "max_row_sum_error": row_err}
 
@@ -221,7 +227,8 @@ def main():
                                       "ms_per_step": round(o["ms_per_step"], 5), "roofline": o["roofline"], "kernels": o["kernels"],
                                       "step_frac_of_hbm_peak": o["step_frac_of_hbm_peak"]}
         torch.cuda.empty_cache()
-        extra["exact_bf16"] = run_exact_bf16(rdk, synth, torch)
+        extra["exact_bf16"] = run_exact(rdk, synth, torch, "dense256k", "bf16")
+        extra["exact_f32"] = run_exact(rdk, synth, torch, "n32k", "f32", calls=20)
 
     cpu = None
     if not args.no_cpu:

@@ -74,6 +74,13 @@ __device__ __forceinline__ double wave_inclusive_scan(double v)
     return v;
 }
 
+// exp(x) for x <= 0 (softmax terms) through the hardware base-2 exponential: one multiply and one v_exp_f32
+// instead of the dozen instructions of the library routine, which made the logit paths ALU-bound.  The product
+// x * log2(e) is rounded once: relative error of the result about |x| * 6e-8, i.e. below 1e-6 for every term
+// larger than e^-15 of the row maximum; exp(-inf) = 0.  Every kernel uses this one function, so normalisers
+// and terms carry the same rounding.
+__device__ __forceinline__ float soft_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+
 // ---- softmax statistics (running maximum m and sum of exp(z - m)), merged pairwise
 struct SoftStat {
     float m, s;
@@ -84,7 +91,7 @@ __device__ __forceinline__ SoftStat soft_merge(SoftStat a, SoftStat b)
     float m = fmaxf(a.m, b.m);
     SoftStat r;
     r.m = m;
-    r.s = (a.s == 0.f ? 0.f : a.s * expf(a.m - m)) + (b.s == 0.f ? 0.f : b.s * expf(b.m - m));
+    r.s = (a.s == 0.f ? 0.f : a.s * soft_exp(a.m - m)) + (b.s == 0.f ? 0.f : b.s * soft_exp(b.m - m));
     return r;
 }
 
@@ -163,7 +170,7 @@ template <int KIND>
 __device__ __forceinline__ float to_weight(float x, float m, float inv)
 {
     if (KIND == RDK_PROB_F32) return x;
-    return expf(x - m) * inv;
+    return soft_exp(x - m) * inv;
 }
 
 // ---- Philox4x32-10 (Salmon et al., SC'11): counter (c0..c3), key (k0,k1), ten rounds.

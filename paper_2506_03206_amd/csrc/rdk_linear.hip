@@ -36,8 +36,8 @@ LinearWs carve(const KernelHandle &h, int32_t B, void *ws)
 // The kept ids ascend, so the kept ids inside one chunk of kChunk target ids own a contiguous run of slots
 // lo .. hi-1 (chunk_lo of the kernel handle).  A wavefront reads that run of the drafter row and of kept_ids with
 // coalesced loads and scatters it through a private LDS array into id order; afterwards lane l holds the raw
-// drafter values of the ids  base + i*256 + l*4 .. +3  (i = 0..3), the same ids whose target values it loads.
-// Ids that are not kept get `fill`, a raw value of weight zero.  This replaces one gather per id.
+// unnormalised drafter weights of the ids  base + i*256 + l*4 .. +3  (i = 0..3), the same ids whose target values it
+// loads; ids that are not kept get 0.  This replaces one gather per id.
 __device__ __forceinline__ void wave_lds_sync()
 {
     // LDS operations of one wavefront execute in order: only the compiler has to be kept from moving them
@@ -47,14 +47,13 @@ __device__ __forceinline__ void wave_lds_sync()
 }
 
 template <int QK>
-__device__ __forceinline__ void stage_chunk(float *lds, const void *qr, bool vec_q, int n, const int32_t *kept, int lo, int hi,
-                                            int base, float4 (&qd)[4])
+__device__ __forceinline__ void stage_chunk(float *lds, const void *qr, bool vec_q, int n, float qm, const int32_t *kept, int lo,
+                                            int hi, int base, float4 (&qd)[4])
 {
     const int lane = lane_id();
-    const float fill = QK == RDK_PROB_F32 ? 0.f : -INFINITY;
     float4 *l4 = (float4 *)lds;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) l4[i * kWave + lane] = make_float4(fill, fill, fill, fill);
+    for (int i = 0; i < 4; ++i) l4[i * kWave + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
     for (int s = (lo & ~3) + lane * 4; s < hi; s += 4 * kWave) {
         int4 kv = make_int4(0, 0, 0, 0);
@@ -65,12 +64,12 @@ __device__ __forceinline__ void stage_chunk(float *lds, const void *qr, bool vec
             if (s + 1 < n) kv.y = kept[s + 1];
             if (s + 2 < n) kv.z = kept[s + 2];
         }
-        const float4 qv = load4<QK>(qr, s, n, vec_q, fill);
+        const float4 qv = load4<QK>(qr, s, n, vec_q, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
         const int ke[4] = {kv.x, kv.y, kv.z, kv.w};
         const float qe[4] = {qv.x, qv.y, qv.z, qv.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (s + e >= lo && s + e < hi) lds[(ke[e] - base) & (kChunk - 1)] = qe[e];
+        for (int e = 0; e < 4; ++e)   // the weight is formed here, once per kept slot rather than once per target id
+            if (s + e >= lo && s + e < hi) lds[(ke[e] - base) & (kChunk - 1)] = to_weight<QK>(qe[e], qm, 1.f);
     }
     wave_lds_sync();
 #pragma unroll
@@ -111,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void taylor_stats_kernel(const void *p, i
         float4 pv[4], qd[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) pv[i] = load4<PK>(pr, (int64_t)base + i * 256 + lane * 4, N, vec_p, pfill);
-        stage_chunk<QK>(qchunk[wid], qr, vec_q, n, kept, chunk_lo[c], chunk_lo[c + 1], base, qd);
+        stage_chunk<QK>(qchunk[wid], qr, vec_q, n, qm, kept, chunk_lo[c], chunk_lo[c + 1], base, qd);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float pe[4] = {to_weight<PK>(pv[i].x, pm, pinv), to_weight<PK>(pv[i].y, pm, pinv),
@@ -121,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void taylor_stats_kernel(const void *p, i
             for (int e = 0; e < 4; ++e) {
                 const float r = __builtin_amdgcn_rcpf(fN + pe[e]);
                 bs += pe[e] * r;
-                const float qh = to_weight<QK>(qe[e], qm, 1.f);   // zero on ids that are not kept
+                const float qh = qe[e];                            // zero on ids that are not kept
                 zq += qh;
                 tn += qh * pe[e];
                 an += qh * r;                                      // times N at the end
@@ -271,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void taylor_write_kernel(TaylorArgs a, bo
         float4 pv[4], qd[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) pv[i] = load4<PK>(tr.pr, (int64_t)base + i * 256 + lane * 4, a.N, a.vec_p, pfill);
-        stage_chunk<QK>(qchunk[wid], tr.qr, a.vec_q, a.n, a.kept, a.chunk_lo[c], a.chunk_lo[c + 1], base, qd);
+        stage_chunk<QK>(qchunk[wid], tr.qr, a.vec_q, a.n, tr.qm, a.kept, a.chunk_lo[c], a.chunk_lo[c + 1], base, qd);
         float sq = 0.f, sr = 0.f, sa = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -282,7 +281,7 @@ __global__ __launch_bounds__(kThreads) void taylor_write_kernel(TaylorArgs a, bo
             float oe[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float qh = to_weight<QK>(qe[e], tr.qm, 1.f);   // zero on ids that are not kept
+                const float qh = qe[e];                              // zero on ids that are not kept
                 oe[e] = tr.value(qh, pe[e]);   // ids beyond N: both weights are zero, and so is the value
             }
             if (orow && idx < a.N) {

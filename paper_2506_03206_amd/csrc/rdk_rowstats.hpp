@@ -36,10 +36,10 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const void *x, 
 #pragma unroll
             for (int i = 0; i < 4; ++i) mx = fmaxf(mx, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
             if (mx > -INFINITY) {
-                float s = st.s == 0.f ? 0.f : st.s * expf(st.m - mx);
+                float s = st.s == 0.f ? 0.f : st.s * soft_exp(st.m - mx);
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    s += (expf(v[i].x - mx) + expf(v[i].y - mx)) + (expf(v[i].z - mx) + expf(v[i].w - mx));
+                    s += (soft_exp(v[i].x - mx) + soft_exp(v[i].y - mx)) + (soft_exp(v[i].z - mx) + soft_exp(v[i].w - mx));
                 st.m = mx;
                 st.s = s;
             }

@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
             if (b < B)
                 for (int i = part; i < q_splits; i += 8) {
                     const SoftStat st = qpart[b * q_splits + i];
-                    if (st.s > 0.f) z += QK == RDK_PROB_F32 ? st.s : st.s * expf(st.m - m);
+                    if (st.s > 0.f) z += QK == RDK_PROB_F32 ? st.s : st.s * soft_exp(st.m - m);
                 }
             z = oct_sum(z);
             if (part == 0) zinv[b] = (b < B && z > 0.f) ? 1.0f / z : 0.f;
