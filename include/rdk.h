@@ -193,7 +193,7 @@ rdk_status_t rdk_verify_sample(const rdk_verify_desc_t *desc, const void *p, rdk
  * followed by rdk_verify_sample on its result, without the round trip of q' through HBM.  The
  * redistributed rows are produced tile by tile, summed against p on the spot, and re-computed for the
  * two blocks in which the sampled ids fall.  q_prime may be NULL (then it is never written); otherwise
- * it receives the same rows rdk_redistribute_linear writes.  Block sums run over 256 ids (sparse) or
+ * it receives the same rows rdk_redistribute_linear writes.  Block sums run over 64 ids (sparse) or
  * 1024 ids (Eq. 3), so fp32 rounding, and with it an id that sits on a prefix-sum step, can differ
  * from the two-call path within the tolerance stated at rdk_verify_sample.  desc->N must equal the
  * kernel's N; draft_ids is required (in/out as in rdk_verify_sample).  RDK_LINEAR_SPARSE needs a
@@ -207,6 +207,25 @@ rdk_status_t rdk_redistribute_verify(const rdk_kernel_t *kernel, rdk_linear_mode
                                      float *q_prime, int64_t ldo, int32_t *draft_ids, uint8_t *accept,
                                      float *alpha, float *resid_mass, int32_t *resid_ids, int32_t *n_accepted,
                                      int32_t *out_tokens, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Alg. 4 step 2 on the drafter's side, before any target row exists: the draft token of every position is drawn
+ * from the redistributed row q' = M^T TLI(q), out-of-vocabulary ids included (the use Sec. 1 and Sec. 3 name:
+ * sampling tokens the drafter's vocabulary does not hold):
+ *   draft_ids[b] = smallest j with prefix_j(q'_b) > u0 * sum_j q'_b(j),  u0 = word 0 of Philox(seed, offset + b)
+ * -- the draw rdk_verify_sample and rdk_redistribute_verify make when sample_draft = 1, so verifying later with
+ * sample_draft = 0 and these ids gives what the fused call gives.  q_draft (optional, [B]) receives q'_b(draft_ids[b]).
+ *   RDK_SPARSE_TOPK kernel with k > 0: q' is summed per 64-id block as it is produced and only the block of the
+ *     crossing is re-computed; q_prime (optional, [B, ldo]) receives the rows if given.
+ *   any other kernel (identity, k = 0, dense fp32 / bf16): the rows are produced by the matching redistribution
+ *     into q_prime, which is then required, and drawn from there.
+ * draft_ids[b] = -1 (and q_draft[b] = 0) for a row without mass.  Workspace: rdk_sample_draft_workspace_bytes.
+ * Errors as rdk_redistribute_linear.
+ */
+rdk_status_t rdk_sample_draft_workspace_bytes(const rdk_kernel_t *kernel, int32_t B, size_t *bytes);
+rdk_status_t rdk_sample_draft(const rdk_kernel_t *kernel, const void *q, rdk_input_kind_t q_kind, int64_t ldq, int32_t B,
+                              uint64_t seed, uint64_t offset, int32_t *draft_ids, float *q_draft, float *q_prime,
+                              int64_t ldo, void *workspace, size_t workspace_bytes, void *stream);
 
 /* The four Philox words of `count` consecutive positions, [count, 4] uint32 on the device (for
  * checking the random stream against an independent implementation). */

@@ -381,6 +381,50 @@ rdk_status_t rdk_redistribute_linear(const rdk_kernel_t *kernel, rdk_linear_mode
     return launch_sparse(h, qi, B, q_prime, ldo, workspace, (hipStream_t)stream);
 }
 
+static bool sparse_product_kernel_of(const KernelHandle &h) { return h.format == RDK_SPARSE_TOPK && h.k > 0; }
+
+rdk_status_t rdk_sample_draft_workspace_bytes(const rdk_kernel_t *kernel, int32_t B, size_t *bytes)
+{
+    if (!kernel || !bytes) return RDK_ERR_NULL;
+    if (B < 1) return RDK_ERR_SHAPE;
+    const KernelHandle &h = kernel->h;
+    if (sparse_product_kernel_of(h)) {
+        *bytes = sparse_draft_workspace_bytes(h, B) + 256;
+    } else {
+        size_t redistribute = 0;
+        rdk_workspace_bytes(kernel, B, &redistribute);
+        *bytes = align_up(redistribute, 256) + draft_rows_workspace_bytes(B, h.N) + 256;
+    }
+    return RDK_OK;
+}
+
+rdk_status_t rdk_sample_draft(const rdk_kernel_t *kernel, const void *q, rdk_input_kind_t q_kind, int64_t ldq, int32_t B,
+                              uint64_t seed, uint64_t offset, int32_t *draft_ids, float *q_draft, float *q_prime, int64_t ldo,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!kernel || !draft_ids || !workspace) return RDK_ERR_NULL;
+    const KernelHandle &h = kernel->h;
+    if (B < 1) return RDK_ERR_SHAPE;
+    rdk_status_t rc = check_rows(q, q_kind, ldq, h.n);
+    if (rc != RDK_OK) return rc;
+    if (q_prime && ldo < h.N) return RDK_ERR_SHAPE;
+    if (!aligned16(workspace) || (q_prime && !aligned16(q_prime))) return RDK_ERR_ALIGN;
+    size_t need = 0;
+    rdk_sample_draft_workspace_bytes(kernel, B, &need);
+    if (workspace_bytes < need - 256) return RDK_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    RowInput qi{q, q_kind, ldq};
+    if (sparse_product_kernel_of(h)) return launch_sparse_draft(h, qi, B, seed, offset, draft_ids, q_draft, q_prime, ldo, workspace, st);
+    if (!q_prime) return RDK_ERR_NULL;
+    size_t redistribute = 0;
+    rdk_workspace_bytes(kernel, B, &redistribute);
+    if (h.format == RDK_IDENTITY || h.format == RDK_SPARSE_TOPK) rc = launch_tli_scatter(h, qi, B, q_prime, ldo, workspace, st);
+    else rc = launch_exact(h, qi, B, q_prime, ldo, workspace, st);
+    if (rc != RDK_OK) return rc;
+    return launch_draft_from_rows(q_prime, ldo, B, h.N, seed, offset, draft_ids, q_draft,
+                                  (char *)workspace + align_up(redistribute, 256), st);
+}
+
 static rdk_status_t check_verify_desc(const rdk_verify_desc_t *d)
 {
     if (!d) return RDK_ERR_NULL;

@@ -118,6 +118,12 @@ rdk_status_t launch_sparse(const KernelHandle &h, RowInput q, int32_t B, float *
 
 // rdk_exact.hip
 size_t exact_workspace_bytes(const KernelHandle &h, int32_t B);
+size_t sparse_draft_workspace_bytes(const KernelHandle &h, int32_t B);
+rdk_status_t launch_sparse_draft(const KernelHandle &h, RowInput q, int32_t B, uint64_t seed, uint64_t offset, int32_t *draft_ids,
+                                 float *q_draft, float *q_prime, int64_t ldo, void *ws, hipStream_t st);
+size_t draft_rows_workspace_bytes(int32_t B, int32_t N);
+rdk_status_t launch_draft_from_rows(const float *q_prime, int64_t ldq, int32_t B, int32_t N, uint64_t seed, uint64_t offset,
+                                    int32_t *draft_ids, float *q_draft, void *ws, hipStream_t st);
 size_t packed_bf16_bytes(int32_t n, int32_t N, int32_t *n_pad, int32_t *N_pad);
 rdk_status_t launch_pack_bf16(const float *M, int64_t ldm, int32_t n, int32_t N, uint16_t *packed, float *row_sum,
                               hipStream_t st);

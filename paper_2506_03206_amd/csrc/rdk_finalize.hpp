@@ -363,6 +363,75 @@ __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) vo
     }
 }
 
+// ---- Draft draw alone (Alg. 4 step 2 on the drafter's side, before a target row exists): one wavefront per row,
+// block sums of q' in, the drafted id and q' at that id out.
+struct DraftArgs {
+    int32_t B, N;
+    uint64_t seed, offset;
+    const float *part_q;   // [B, nblk]
+    int nblk;
+    int32_t *draft_ids;
+    float *q_draft;        // may be NULL
+};
+
+template <int BLOCK, class QP>
+__global__ __launch_bounds__(kWave) void draft_finalize_kernel(DraftArgs a, QP qp)
+{
+    constexpr int SUB = BLOCK >= 256 ? BLOCK / 256 : 1;
+    constexpr int kLanes = BLOCK >= 256 ? kWave : BLOCK / 4;
+    constexpr int kRegBlocks = 32;
+    const int64_t row = blockIdx.x;
+    const int lane = lane_id();
+    const int per_lane = (a.nblk + kWave - 1) / kWave;
+    const float *pq = a.part_q + row * a.nblk;
+    const bool in_regs = per_lane <= kRegBlocks;
+    float vq[kRegBlocks];
+    double lane_q;
+    if (in_regs) load_partials(pq, a.nblk, per_lane, vq);
+    const typename QP::Row qrow = qp.row(row);
+    lane_q = in_regs ? sum_partials(vq) : lane_partial_sum(pq, a.nblk, per_lane);
+    uint32_t words[4];
+    position_words(a.seed, a.offset + (uint64_t)row, words);
+    const double Q = wave_sum(lane_q);
+    int blk = -1;
+    double thr = 0.0, before = 0.0;
+    if (Q > 0.0) {
+        thr = word_to_unit(words[0]) * Q;
+        blk = in_regs ? locate_block_regs(vq, a.nblk, per_lane, lane_q, thr, before) : locate_block(pq, a.nblk, per_lane, lane_q, thr, before);
+    }
+    int32_t dtok = -1;
+    float qd = 0.f;
+    if (blk >= 0) {
+        const int base = blk * BLOCK;
+        const bool holds = lane < kLanes;
+        typename QP::Row::Pending td[SUB];
+        float4 wd[SUB];
+        stage_block<0, SUB>(qrow, td, base, holds);
+        if (QP::kStages > 1) stage_block<1, SUB>(qrow, td, base, holds);
+        if (QP::kStages > 2) stage_block<2, SUB>(qrow, td, base, holds);
+#pragma unroll
+        for (int i = 0; i < SUB; ++i)
+            wd[i] = holds ? qrow.result(td[i], (int64_t)base + i * 256 + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        dtok = search_block<SUB>(wd, base, thr - before);
+        if (dtok >= 0) {
+            const int off = dtok - base;
+            qd = lane_value(pick<SUB>(wd, off / 256, off % 4), (off % 256) / 4);
+        }
+    }
+    if (lane == 0) {
+        a.draft_ids[row] = dtok;
+        if (a.q_draft) a.q_draft[row] = qd;
+    }
+}
+
+template <int BLOCK, class QP>
+rdk_status_t launch_draft_finalize(const DraftArgs &a, QP qp, hipStream_t st)
+{
+    RDK_TIMED_LAUNCH("draft_finalize_kernel", (draft_finalize_kernel<BLOCK, QP>), dim3((unsigned)a.B), dim3(kWave), 0, st, a, qp);
+    RDK_LAUNCH_CHECK("draft_finalize_kernel");
+    return RDK_OK;
+}
+
 // Per-sequence scan as a launch of its own (sequences longer than one workgroup's wavefronts).
 __global__ void sequence_scan_kernel(int S, int gamma, const int32_t *draft_ids, const uint8_t *accept,
                                      const int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens);

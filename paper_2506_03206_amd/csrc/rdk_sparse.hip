@@ -262,13 +262,14 @@ __device__ __forceinline__ float row16_sum(float v)
     return v;
 }
 
-// PK < 0: plain product (q' is written).  PK >= 0: fused with the verification sums against the target
+// PK = -1: plain product (q' is written).  PK = -2: also the sum of q' per 64-id block (draft draw without a
+// target row; q' written only if WRITE_Q).  PK >= 0: fused with the verification sums against the target
 // rows of kind PK -- per (position, 64-id block) the sums of q', max(0, p - q') and min(p, q') --
 // and q' is written only if WRITE_Q.
 template <int PK, bool WRITE_Q>
 __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, FuseArgs f)
 {
-    constexpr bool FUSE = PK >= 0;
+    constexpr bool FUSE = PK >= 0, SUMS = PK != -1;
     constexpr int PKIND = FUSE ? PK : RDK_PROB_F32;
     __shared__ __attribute__((aligned(16))) float stage[kPosBlock][kStageLd];
     int pb, tile;
@@ -310,31 +311,39 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
                     if (jl + e < a.N) o[e] = qv[e];
             }
         }
-        if (FUSE) {
+        if (SUMS) {
             float m = 0.f, inv = 1.f;
-            if (PKIND != RDK_PROB_F32) {
+            if (FUSE && PKIND != RDK_PROB_F32) {
                 const SoftStat rs = merged_row_stat<PKIND>(f.pstat, f.p_splits, b);
                 m = rs.m;
                 inv = 1.0f / rs.s;
             }
-            const float pr4[4] = {praw[rr].x, praw[rr].y, praw[rr].z, praw[rr].w};
             float sq = 0.f, sr = 0.f, sa = 0.f;
+            if (FUSE) {
+                const float pr4[4] = {praw[rr].x, praw[rr].y, praw[rr].z, praw[rr].w};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float pe = to_weight<PKIND>(pr4[e], m, inv);
-                sq += qv[e];
-                sr += fmaxf(pe - qv[e], 0.f);
-                sa += fminf(pe, qv[e]);
+                for (int e = 0; e < 4; ++e) {
+                    const float pe = to_weight<PKIND>(pr4[e], m, inv);
+                    sq += qv[e];
+                    sr += fmaxf(pe - qv[e], 0.f);
+                    sa += fminf(pe, qv[e]);
+                }
+            } else {
+                sq = ((qv[0] + qv[1]) + qv[2]) + qv[3];   // the order of the fused form: same block sums, same drafts
             }
             // one block of sums per 16 lanes (64 ids): reduce inside each row of the wavefront only
             sq = row16_sum(sq);
-            sr = row16_sum(sr);
-            sa = row16_sum(sa);
+            if (FUSE) {
+                sr = row16_sum(sr);
+                sa = row16_sum(sa);
+            }
             if ((lane & 15) == 0) {
                 const int64_t o = b * ((int64_t)a.tiles * (kTileIds / kSubIds)) + tile * (kTileIds / kSubIds) + (lane >> 4);
                 f.part_q[o] = sq;
-                f.part_r[o] = sr;
-                f.part_a[o] = sa;
+                if (FUSE) {
+                    f.part_r[o] = sr;
+                    f.part_a[o] = sa;
+                }
             }
         }
     }
@@ -534,7 +543,44 @@ rdk_status_t run_sparse_fused(const KernelHandle &h, const FusedCall &c, void *w
     return launch_finalize<PK, kSubIds, true, QpSparse>(fa, QpSparse{a}, st);
 }
 
+template <int QK>
+rdk_status_t run_sparse_draft(const KernelHandle &h, RowInput q, int32_t B, uint64_t seed, uint64_t offset, int32_t *draft_ids,
+                              float *q_draft, float *q_prime, int64_t ldo, void *ws, hipStream_t st)
+{
+    SparseWs w = carve(h, B, ws);
+    FuseArgs f{};
+    f.part_q = (float *)((char *)ws + sparse_workspace_bytes(h, B));
+    rdk_status_t rc = prepare_q<QK>(h, q, B, w, st);
+    if (rc != RDK_OK) return rc;
+    const SparseArgs a = make_args(h, w, B, q_prime, ldo);
+    if (q_prime)
+        RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<-2, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+    else
+        RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<-2, false>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+    RDK_LAUNCH_CHECK("sparse_product_kernel");
+    const int blocks = a.tiles * (kTileIds / kSubIds);
+    DraftArgs da{B, h.N, seed, offset, f.part_q, blocks, draft_ids, q_draft};
+    return launch_draft_finalize<kSubIds, QpSparse>(da, QpSparse{a}, st);
+}
+
 }  // namespace
+
+size_t sparse_draft_workspace_bytes(const KernelHandle &h, int32_t B)
+{
+    const size_t blocks = (size_t)((h.N + kTileIds - 1) / kTileIds) * (kTileIds / kSubIds);
+    return sparse_workspace_bytes(h, B) + align_up((size_t)B * blocks * sizeof(float), 256);
+}
+
+rdk_status_t launch_sparse_draft(const KernelHandle &h, RowInput q, int32_t B, uint64_t seed, uint64_t offset, int32_t *draft_ids,
+                                 float *q_draft, float *q_prime, int64_t ldo, void *ws, hipStream_t st)
+{
+    switch (q.kind) {
+        case RDK_PROB_F32: return run_sparse_draft<RDK_PROB_F32>(h, q, B, seed, offset, draft_ids, q_draft, q_prime, ldo, ws, st);
+        case RDK_LOGIT_F32: return run_sparse_draft<RDK_LOGIT_F32>(h, q, B, seed, offset, draft_ids, q_draft, q_prime, ldo, ws, st);
+        case RDK_LOGIT_BF16: return run_sparse_draft<RDK_LOGIT_BF16>(h, q, B, seed, offset, draft_ids, q_draft, q_prime, ldo, ws, st);
+    }
+    return RDK_ERR_DTYPE;
+}
 
 size_t sparse_workspace_bytes(const KernelHandle &h, int32_t B)
 {

@@ -161,7 +161,46 @@ rdk_status_t run_verify(const rdk_verify_desc_t &d, RowInput p, const float *q, 
     return launch_finalize<KIND, 1024, HAS_Q, QpMemory>(fa, qp, st);
 }
 
+// Sums of each 1024-id block of materialised rows (the draft draw from a q' that sits in memory).
+__global__ __launch_bounds__(kStreamThreads) void row_block_sums_kernel(const float *q, int64_t ldq, int N, int nchunks, int splits,
+                                                                        bool vec_q, float *part_q)
+{
+    const int64_t row = blockIdx.x / splits;
+    const int split = blockIdx.x % splits;
+    const int cpw = (nchunks + splits - 1) / splits;
+    const int c_begin = split * cpw, c_end = min(nchunks, c_begin + cpw);
+    const float *qr = q + row * ldq;
+    const int wid = threadIdx.x / kWave, lane = lane_id();
+    for (int c = c_begin + wid; c < c_end; c += kWavesPerBlock) {
+        const int64_t base = (int64_t)c * kChunk + lane * 4;
+        float4 qv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qv[i] = load4<RDK_PROB_F32>(qr, base + i * 256, N, vec_q, 0.f);
+        float sq = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sq += (qv[i].x + qv[i].y) + (qv[i].z + qv[i].w);
+        sq = wave_sum(sq);
+        if (lane == 0) part_q[row * nchunks + c] = sq;
+    }
+}
+
 }  // namespace
+
+size_t draft_rows_workspace_bytes(int32_t B, int32_t N) { return align_up((size_t)B * chunks_of(N) * sizeof(float), 256); }
+
+rdk_status_t launch_draft_from_rows(const float *q_prime, int64_t ldq, int32_t B, int32_t N, uint64_t seed, uint64_t offset,
+                                    int32_t *draft_ids, float *q_draft, void *ws, hipStream_t st)
+{
+    const int nchunks = chunks_of(N);
+    const int splits = row_splits(B, N, kWavesPerBlock);
+    const bool vec_q = rows_vectorisable(q_prime, ldq, RDK_PROB_F32);
+    float *part_q = (float *)ws;
+    RDK_TIMED_LAUNCH("row_block_sums_kernel", row_block_sums_kernel, dim3((unsigned)B * splits), dim3(kStreamThreads), 0, st, q_prime, ldq, N,
+                     nchunks, splits, vec_q, part_q);
+    RDK_LAUNCH_CHECK("row_block_sums_kernel");
+    DraftArgs a{B, N, seed, offset, part_q, nchunks, draft_ids, q_draft};
+    return launch_draft_finalize<1024, QpMemory>(a, QpMemory{q_prime, ldq, vec_q, N}, st);
+}
 
 size_t verify_workspace_bytes(const rdk_verify_desc_t &d)
 {

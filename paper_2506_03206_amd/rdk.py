@@ -23,6 +23,7 @@ EXPORTS = [
     "rdk_kernel_get_sparse", "rdk_kernel_get_dense", "rdk_workspace_bytes", "rdk_redistribute_exact",
     "rdk_redistribute_linear", "rdk_verify_workspace_bytes", "rdk_verify_sample", "rdk_philox_words",
     "rdk_timing_select", "rdk_timing_read", "rdk_redistribute_verify_workspace_bytes", "rdk_redistribute_verify",
+    "rdk_sample_draft_workspace_bytes", "rdk_sample_draft",
 ]
 
 
@@ -79,9 +80,13 @@ def lib():
         L.rdk_redistribute_verify_workspace_bytes.argtypes = [vp, ctypes.c_int, ctypes.POINTER(VerifyDesc), psz]
         L.rdk_redistribute_verify.argtypes = [vp, ctypes.c_int, ctypes.POINTER(VerifyDesc), vp, ctypes.c_int, i64, vp,
                                               ctypes.c_int, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rdk_sample_draft_workspace_bytes.argtypes = [vp, i32, psz]
+        L.rdk_sample_draft.argtypes = [vp, vp, ctypes.c_int, i64, i32, ctypes.c_uint64, ctypes.c_uint64, vp, vp, vp, i64, vp, sz, vp]
         L.rdk_timing_select.argtypes = [ctypes.c_char_p]
         L.rdk_timing_read.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
         for name in EXPORTS:
+            # without declared argument types ctypes pushes 4-byte ints for 64-bit stack parameters
+            assert getattr(L, name).argtypes is not None, "argtypes missing for " + name
             if name not in ("rdk_status_string", "rdk_last_hip_error"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -262,6 +267,25 @@ def rdk_redistribute_verify(kernel, mode, p, q, seed, offset=0, gamma=0, p_kind=
                                          _ptr(o.n_accepted), _ptr(o.out_tokens), _ptr(o.fused_ws), o.fused_ws.numel(),
                                          _stream()), "rdk_redistribute_verify")
     return o
+
+
+def rdk_sample_draft(kernel, q, seed, offset=0, q_kind="prob", q_prime=None, draft_ids=None, q_draft=None):
+    """Draft tokens drawn from q' = M^T TLI(q) before any target row exists.  Returns (draft_ids [B] int32,
+    q_draft [B] fp32 = q' at the drafted id).  q_prime: [B,N] tensor that receives the rows (required unless the
+    kernel is a top-k sparse one)."""
+    B = q.shape[0]
+    if draft_ids is None:
+        draft_ids = torch.empty(B, dtype=torch.int32, device=q.device)
+    if q_draft is None:
+        q_draft = torch.empty(B, dtype=torch.float32, device=q.device)
+    need = ctypes.c_size_t()
+    _check(lib().rdk_sample_draft_workspace_bytes(kernel.handle, B, ctypes.byref(need)), "rdk_sample_draft_workspace_bytes")
+    if getattr(kernel, "_draft_ws", None) is None or kernel._draft_ws.numel() < need.value:
+        kernel._draft_ws = torch.empty(need.value, dtype=torch.uint8, device=q.device)
+    ldo = 0 if q_prime is None else _rows(q_prime)
+    _check(lib().rdk_sample_draft(kernel.handle, _ptr(q), _kind_of(q, q_kind), _rows(q), B, seed, offset, _ptr(draft_ids), _ptr(q_draft), _ptr(q_prime), ldo,
+                                  _ptr(kernel._draft_ws), kernel._draft_ws.numel(), _stream()), "rdk_sample_draft")
+    return draft_ids, q_draft
 
 
 def rdk_philox_words(seed, offset, count, device="cuda"):

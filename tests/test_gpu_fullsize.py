@@ -70,6 +70,11 @@ def test_llama3_fused_whole_batch(rdk, llama3, mode):
     assert_close(qp.cpu().numpy(), ref_qp, what="q' (%s), whole batch" % mode)
     ref = oracle.verify_batch(p64, ref_qp, seed, offset, gamma=w.gamma)
     check_verify_outputs(o, ref, p64, ref_qp, seed, offset, w.gamma, "prob")
+    if mode == "sparse":   # the draft draw on its own (no target row) gives the same ids, and q' at them
+        d, qd = rdk.rdk_sample_draft(kern, q_d, seed, offset)
+        assert torch.equal(d, o.draft_ids)
+        d = d.cpu().numpy()
+        assert_close(qd.cpu().numpy(), ref_qp[np.arange(w.B), d], what="q' at the drafted id")
 
 
 def test_llama3_device_built_topk_kernel(rdk, llama3):

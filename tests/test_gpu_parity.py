@@ -320,6 +320,55 @@ def test_pipeline_end_to_end(rdk, tiny):
     check_sampled_ids(ref_qp, us[:, 0], o.draft_ids.cpu().numpy(), ref["draft_ids"], what="draft")
 
 
+# --------------------------------------------------------------------------------------------- draft-side sampling
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+@pytest.mark.parametrize("form", ["sparse", "sparse_rows", "identity", "dense_f32"])
+def test_sample_draft(rdk, tiny, ragged, case, form):
+    """rdk_sample_draft: ids drawn from q' alone (no target row) against the oracle's inverse CDF of its own q'."""
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    idx, wt, sw = data["sparse"]
+    wt32, sw32 = wt.astype(np.float32), sw.astype(np.float32)
+    qp = torch.zeros((w.B, w.N), dtype=torch.float32, device="cuda")
+    if form in ("sparse", "sparse_rows"):
+        kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.SPARSE_TOPK, k=w.k, sparse=(dev(idx), dev(wt32), dev(sw32)))
+        ref_qp = oracle_rows(data, "sparse", kernel=(idx, wt32, sw32))
+    elif form == "identity":
+        kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.IDENTITY)
+        ref_qp = oracle_rows(data, "tli")
+    else:
+        M32 = data["dense"].astype(np.float32)
+        kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.DENSE_F32, dense_M=dev(M32))
+        ref_qp = oracle_rows(data, "exact", kernel=M32)
+    seed, offset = 909, (1 << 35) + 3
+    d, qd = rdk.rdk_sample_draft(kern, dev(data["q_hat"]), seed, offset, q_prime=None if form == "sparse" else qp)
+    torch.cuda.synchronize()
+    d, qd = d.cpu().numpy(), qd.cpu().numpy()
+    u0 = np.array([oracle.uniforms(seed, offset + b)[0] for b in range(w.B)])
+    ref_d = np.array([oracle.sample_cdf(ref_qp[b], u0[b]) for b in range(w.B)])
+    assert check_sampled_ids(ref_qp, u0, d, ref_d, what="draft from q'") >= 0.9 * w.B
+    assert_close(qd, ref_qp[np.arange(w.B), d], what="q' at the drafted id")
+    if form != "sparse":
+        assert_close(qp.cpu().numpy(), ref_qp, what="rows written on the way")
+    if form in ("sparse", "sparse_rows"):   # the fused verification draws the same ids from the same block sums
+        o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_SPARSE, dev(data["p"]), dev(data["q_hat"]), seed, offset, w.gamma)
+        assert np.array_equal(o.draft_ids.cpu().numpy(), d)
+        # and verifying these ids afterwards accepts exactly where the oracle does
+        o2 = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_SPARSE, dev(data["p"]), dev(data["q_hat"]), seed, offset, w.gamma,
+                                         draft_ids=dev(d))
+        p64 = data["p"].astype(np.float64)
+        ref = oracle.verify_batch(p64, ref_qp, seed, offset, sample_draft=False, draft_ids=d, gamma=w.gamma)
+        assert np.array_equal(o2.accept.cpu().numpy(), ref["accept"])
+
+
+def test_sample_draft_zero_row_and_errors(rdk, tiny):
+    w = tiny["w"]
+    kern = rdk.rdk_build_kernel(w.N, dev(tiny["kept_ids"]), rdk.IDENTITY)
+    with pytest.raises(rdk.RdkError) as e:                      # rows must be written somewhere for this kernel
+        rdk.rdk_sample_draft(kern, dev(tiny["q_hat"]), 1, 0)
+    assert e.value.status == 1
+
+
 # --------------------------------------------------------------------------------------------- fused entry point
 @pytest.mark.parametrize("case", ["tiny", "ragged"])
 @pytest.mark.parametrize("mode", ["sparse", "taylor"])
