@@ -135,6 +135,33 @@ def run_linear(args, rdk, synth, torch, w, vocab, batch, mode_name, path, steps,
             "accept_rate": float(vout.accept.float().mean().item()), "mean_alpha": float(vout.alpha.mean().item())}
 
 
+def run_draft(args, rdk, synth, torch, w, vocab, batch, steps):
+    """Draft-side sampling alone: rdk_sample_draft with the top-k sparse kernel, q' never materialised."""
+    bias, kept, E = vocab
+    dev = torch.device("cuda:0")
+    kern = rdk.rdk_build_kernel(w.N, torch.from_numpy(kept).to(dev), rdk.SPARSE_TOPK, embeddings=torch.from_numpy(E).to(dev),
+                                tau=w.tau, k=w.k)
+    if w.logits_bf16:
+        q_host, kind = torch.from_numpy(batch["z_q"]).to(torch.bfloat16), "logit"
+    else:
+        q_host, kind = torch.from_numpy(batch["q_hat"]), "prob"
+    qs = [q_host.to(dev) for _ in range(max(1, args.copies))]
+    ids = torch.empty(w.B, dtype=torch.int32, device=dev)
+    qd = torch.empty(w.B, dtype=torch.float32, device=dev)
+    for i in range(5):
+        rdk.rdk_sample_draft(kern, qs[i % len(qs)], 2506, i * w.B, kind, draft_ids=ids, q_draft=qd)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for i in range(steps):
+        rdk.rdk_sample_draft(kern, qs[i % len(qs)], 2506, i * w.B, kind, draft_ids=ids, q_draft=qd)
+    stop.record()
+    torch.cuda.synchronize()
+    ms = start.elapsed_time(stop) / steps
+    return {"entry": "rdk_sample_draft (sparse top-k, no target row)", "ms_per_step": round(ms, 5),
+            "positions_per_s": round(w.B / (ms * 1e-3), 1)}
+
+
 def run_exact(rdk, synth, torch, wname, fmt, calls=5):
     """Exact dense redistribution (Alg. 1 with the full M): bf16 MFMA contraction at N=256000, n=32000, B=512, or the
     fp32 one at N=32000, n=8000, B=64.  Both are bound by the matrix cores (the fp32 one needs 32 flop per byte of M,
@@ -226,6 +253,7 @@ def main():
         extra["other_linear_form"] = {"mode": other, "path": args.path, "positions_per_s": round(o["value"], 1),
                                       "ms_per_step": round(o["ms_per_step"], 5), "roofline": o["roofline"], "kernels": o["kernels"],
                                       "step_frac_of_hbm_peak": o["step_frac_of_hbm_peak"]}
+        extra["draft_sampling"] = run_draft(args, rdk, synth, torch, w, (bias, kept, E), batch, max(20, args.steps // 2))
         torch.cuda.empty_cache()
         extra["exact_bf16"] = run_exact(rdk, synth, torch, "dense256k", "bf16")
         extra["exact_f32"] = run_exact(rdk, synth, torch, "n32k", "f32", calls=20)
