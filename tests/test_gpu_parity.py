@@ -320,6 +320,39 @@ def test_pipeline_end_to_end(rdk, tiny):
     check_sampled_ids(ref_qp, us[:, 0], o.draft_ids.cpu().numpy(), ref["draft_ids"], what="draft")
 
 
+def test_entry_points_reject_bad_arguments(rdk, tiny):
+    """Every redistribute / verify entry point checks its arguments on the host and returns a status without
+    launching anything: NULL, a leading dimension shorter than the row, a misaligned pointer, a short workspace,
+    a form the kernel does not offer."""
+    import ctypes
+    w = tiny["w"]
+    L = rdk.lib()
+    q, p = dev(tiny["q_hat"]), dev(tiny["p"])
+    out = torch.empty((w.B, w.N), dtype=torch.float32, device="cuda")
+    ident = rdk.rdk_build_kernel(w.N, dev(tiny["kept_ids"]), rdk.IDENTITY)
+    ws = ident.workspace(w.B)
+    P = lambda t: ctypes.c_void_p(t.data_ptr())
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    lin = lambda **kw: L.rdk_redistribute_linear(*[kw.get(k, v) for k, v in dict(
+        kernel=ident.handle, mode=rdk.LINEAR_TAYLOR, p=P(p), p_kind=rdk.PROB_F32, ldp=w.N, q=P(q), q_kind=rdk.PROB_F32, ldq=w.n,
+        B=w.B, out=P(out), ldo=w.N, ws=P(ws), ws_bytes=ws.numel(), stream=st).items()])
+    assert lin() == 0
+    assert lin(out=None) == 1 and lin(q=None) == 1 and lin(p=None) == 1
+    assert lin(ldo=w.N - 1) == 2 and lin(ldq=w.n - 1) == 2 and lin(ldp=w.N - 4) == 2 and lin(B=0) == 2
+    assert lin(q_kind=9) == 3 and lin(mode=5) == 3
+    assert lin(ws_bytes=64) == 6
+    assert lin(q=ctypes.c_void_p(q.data_ptr() + 4)) == 9 and lin(out=ctypes.c_void_p(out.data_ptr() + 8)) == 9
+    dense = rdk.rdk_build_kernel(w.N, dev(tiny["kept_ids"]), rdk.DENSE_F32, dense_M=dev(tiny["dense"].astype(np.float32)))
+    dws = dense.workspace(w.B)
+    assert lin(kernel=dense.handle, mode=rdk.LINEAR_SPARSE, ws=P(dws), ws_bytes=dws.numel()) == 7   # no sparse product with a dense kernel
+    idx, wt, sw = tiny["sparse"]
+    sparse = rdk.rdk_build_kernel(w.N, dev(tiny["kept_ids"]), rdk.SPARSE_TOPK, k=w.k,
+                                  sparse=(dev(idx), dev(wt, torch.float32), dev(sw, torch.float32)))
+    sws = sparse.workspace(w.B)
+    assert L.rdk_redistribute_exact(sparse.handle, P(q), rdk.PROB_F32, w.n, w.B, P(out), w.N, P(sws), sws.numel(), st) == 7
+    torch.cuda.synchronize()
+
+
 # --------------------------------------------------------------------------------------------- draft-side sampling
 @pytest.mark.parametrize("case", ["tiny", "ragged"])
 @pytest.mark.parametrize("form", ["sparse", "sparse_rows", "identity", "dense_f32"])
