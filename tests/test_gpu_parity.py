@@ -353,6 +353,30 @@ def test_entry_points_reject_bad_arguments(rdk, tiny):
     torch.cuda.synchronize()
 
 
+def test_acceptance_sweep_matches_oracle(rdk):
+    """The Sec. 5.2 sweep (masked / TLI / Eq. 3 acceptance against pruning level) at a small size against the oracle."""
+    from paper_2506_03206_amd import acceptance_sweep as sw
+    N, B, keep = 6000, 8, (3000, 600, 60)
+    rows = sw.sweep(N=N, B=B, keep=keep, seed=4)
+    z_p, z_d, by_frequency = sw.make_inputs(N, B, 2.0, 1.0, 4)
+    p64 = oracle.probs_from(z_p, "logit")
+    q_full = oracle.probs_from(z_d, "logit")
+    for row, n in zip(rows, keep):
+        kept = np.sort(by_frequency[:n])
+        q_hat = q_full[:, kept]
+        masked = np.zeros((B, N))
+        masked[:, kept] = q_hat
+        a_masked = np.mean([oracle.overlap(p64[b], masked[b])[0] for b in range(B)])
+        tli = oracle.redistribute_batch("tli", q_hat, kept, N)
+        a_tli = np.mean([oracle.overlap(p64[b], tli[b])[0] for b in range(B)])
+        tay = oracle.redistribute_batch("taylor", q_hat, kept, N, p=p64)
+        a_tay = np.mean([oracle.overlap(p64[b], tay[b])[0] for b in range(B)])
+        # the device softmaxes fp32 logits itself; the drafter's probabilities come from a torch softmax (input preparation)
+        assert abs(row["alpha_masked"] - a_masked) < 2e-5 and abs(row["alpha_tli"] - a_tli) < 2e-5
+        assert abs(row["alpha_taylor"] - a_tay) < 2e-5
+        assert row["alpha_tli"] >= row["alpha_masked"] - 1e-6          # Eq. 1 only scales the kept mass up
+
+
 # --------------------------------------------------------------------------------------------- draft-side sampling
 @pytest.mark.parametrize("case", ["tiny", "ragged"])
 @pytest.mark.parametrize("form", ["sparse", "sparse_rows", "identity", "dense_f32"])
