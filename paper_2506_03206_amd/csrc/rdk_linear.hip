@@ -35,7 +35,7 @@ LinearWs carve(const KernelHandle &h, int32_t B, void *ws)
 // ------------------------------------------------------------------------------------------------
 // The kept ids ascend, so the kept ids inside one chunk of kChunk target ids own a contiguous run of slots
 // lo .. hi-1 (chunk_lo of the kernel handle).  A wavefront reads that run of the drafter row and of kept_ids with
-// coalesced loads and scatters it through a private LDS array into id order; afterwards lane l holds the raw
+// coalesced loads and scatters it through a private LDS array (kChunk words + one spare word per lane) into id order; afterwards lane l holds the raw
 // unnormalised drafter weights of the ids  base + i*256 + l*4 .. +3  (i = 0..3), the same ids whose target values it
 // loads; ids that are not kept get 0.  This replaces one gather per id.
 __device__ __forceinline__ void wave_lds_sync()
@@ -68,25 +68,28 @@ __device__ __forceinline__ void stage_chunk(float *lds, const void *qr, bool vec
         const int ke[4] = {kv.x, kv.y, kv.z, kv.w};
         const float qe[4] = {qv.x, qv.y, qv.z, qv.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e)   // the weight is formed here, once per kept slot rather than once per target id
-            if (s + e >= lo && s + e < hi) lds[(ke[e] - base) & (kChunk - 1)] = to_weight<QK>(qe[e], qm, 1.f);
+        for (int e = 0; e < 4; ++e) {   // the weight is formed here, once per kept slot rather than once per target id
+            const bool mine = s + e >= lo && s + e < hi;   // others go to a spare word per lane: no branch
+            lds[mine ? ((ke[e] - base) & (kChunk - 1)) : kChunk + lane] = to_weight<QK>(qe[e], qm, 1.f);
+        }
     }
     wave_lds_sync();
 #pragma unroll
     for (int i = 0; i < 4; ++i) qd[i] = l4[i * kWave + lane];
 }
 
+// Both passes hide memory latency by occupancy alone: they are held to 64 registers (eight wavefronts per SIMD).
 // Eq. 3, first pass.  For the ids of one split of a row:
 //   Zq += q^_s, Tn += q^_s p_j, An += N q^_s / (N + p_j)   over kept ids j (slot s),
 //   Bs += p_j / (N + p_j)                                    over all ids j.
 // Then theta = Tn / Zq and sum_j pt_j = An / Zq + theta * Bs, because
 //   pt_j = N q'_j / (N + p_j) + theta p_j / (N + p_j)  with q'_j = q^_s / Zq on kept ids, 0 elsewhere.
 template <int PK, int QK>
-__global__ __launch_bounds__(kThreads) void taylor_stats_kernel(const void *p, int64_t ldp, const void *q, int64_t ldq,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) void taylor_stats_kernel(const void *p, int64_t ldp, const void *q, int64_t ldq,
                                                                 const int32_t *kept, const int32_t *chunk_lo, int N, int n,
                                                                 int splits, bool vec_p, bool vec_q, LinearWs w)
 {
-    __shared__ __attribute__((aligned(16))) float qchunk[kWaves][kChunk];
+    __shared__ __attribute__((aligned(16))) float qchunk[kWaves][kChunk + kWave];
     const int64_t row = blockIdx.x / splits;
     const int split = blockIdx.x % splits;
     const int nchunks = (N + kChunk - 1) / kChunk;
@@ -105,12 +108,23 @@ __global__ __launch_bounds__(kThreads) void taylor_stats_kernel(const void *p, i
     const float pfill = PK == RDK_PROB_F32 ? 0.f : -INFINITY;
     const float fN = (float)N;
     float zq = 0.f, tn = 0.f, an = 0.f, bs = 0.f;
-    for (int c = c_begin + wid; c < c_end; c += kWaves) {
+    // the slot run of the next chunk is looked up one iteration ahead, so that no load of a chunk waits for another
+    int c = c_begin + wid;
+    int lo = 0, hi = 0;
+    if (c < c_end) {
+        lo = chunk_lo[c];
+        hi = chunk_lo[c + 1];
+    }
+    for (; c < c_end; c += kWaves) {
         const int base = c * kChunk;
         float4 pv[4], qd[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pv[i] = load4<PK>(pr, (int64_t)base + i * 256 + lane * 4, N, vec_p, pfill);
-        stage_chunk<QK>(qchunk[wid], qr, vec_q, n, qm, kept, chunk_lo[c], chunk_lo[c + 1], base, qd);
+        load_chunk<PK>(pr, base, N, vec_p, pfill, pv);
+        const int lo_now = lo, hi_now = hi;
+        if (c + kWaves < c_end) {
+            lo = chunk_lo[c + kWaves];
+            hi = chunk_lo[c + kWaves + 1];
+        }
+        stage_chunk<QK>(qchunk[wid], qr, vec_q, n, qm, kept, lo_now, hi_now, base, qd);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float pe[4] = {to_weight<PK>(pv[i].x, pm, pinv), to_weight<PK>(pv[i].y, pm, pinv),
@@ -252,26 +266,37 @@ __device__ __forceinline__ TaylorRow<PK, QK> make_taylor_row(const TaylorArgs &a
 // verification sums per 1024-id block (sum q', sum max(0, p - q'), sum min(p, q')).  Whether q' is stored (out != NULL)
 // is decided at run time, so that the sums do not depend on it by a single bit.
 template <int PK, int QK, bool FUSE>
-__global__ __launch_bounds__(kThreads) void taylor_write_kernel(TaylorArgs a, bool vec_o, float *out, int64_t ldo, float *part_q,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) void taylor_write_kernel(TaylorArgs a, bool vec_o, float *out, int64_t ldo, float *part_q,
                                                                 float *part_r, float *part_a)
 {
-    __shared__ __attribute__((aligned(16))) float qchunk[kWaves][kChunk];
+    __shared__ __attribute__((aligned(16))) float qchunk[kWaves][kChunk + kWave];
     const int64_t row = blockIdx.x / a.splits;
     const int split = blockIdx.x % a.splits;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
     const int cpw = (nchunks + a.splits - 1) / a.splits;
     const int c_begin = split * cpw, c_end = min(nchunks, c_begin + cpw);
     const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
-    const TaylorRow<PK, QK> tr = make_taylor_row<PK, QK>(a, row);
     const float pfill = PK == RDK_PROB_F32 ? 0.f : -INFINITY;
+    int c = c_begin + wid;
+    int lo = 0, hi = 0;
+    if (c < c_end) {   // requested before the row constants below are waited for
+        lo = a.chunk_lo[c];
+        hi = a.chunk_lo[c + 1];
+    }
+    const TaylorRow<PK, QK> tr = make_taylor_row<PK, QK>(a, row);
     float *orow = out ? out + row * ldo : nullptr;
-    for (int c = c_begin + wid; c < c_end; c += kWaves) {
+    for (; c < c_end; c += kWaves) {
         const int base = c * kChunk;
         float4 pv[4], qd[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pv[i] = load4<PK>(tr.pr, (int64_t)base + i * 256 + lane * 4, a.N, a.vec_p, pfill);
-        stage_chunk<QK>(qchunk[wid], tr.qr, a.vec_q, a.n, tr.qm, a.kept, a.chunk_lo[c], a.chunk_lo[c + 1], base, qd);
+        load_chunk<PK>(tr.pr, base, a.N, a.vec_p, pfill, pv);
+        const int lo_now = lo, hi_now = hi;
+        if (c + kWaves < c_end) {
+            lo = a.chunk_lo[c + kWaves];
+            hi = a.chunk_lo[c + kWaves + 1];
+        }
+        stage_chunk<QK>(qchunk[wid], tr.qr, a.vec_q, a.n, tr.qm, a.kept, lo_now, hi_now, base, qd);
         float sq = 0.f, sr = 0.f, sa = 0.f;
+        const bool full_o = vec_o && base + kChunk <= a.N;   // the whole chunk is stored with 16-byte stores
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int64_t idx = (int64_t)base + i * 256 + lane * 4;
@@ -284,8 +309,8 @@ __global__ __launch_bounds__(kThreads) void taylor_write_kernel(TaylorArgs a, bo
                 const float qh = qe[e];                              // zero on ids that are not kept
                 oe[e] = tr.value(qh, pe[e]);   // ids beyond N: both weights are zero, and so is the value
             }
-            if (orow && idx < a.N) {
-                if (vec_o && idx + 3 < a.N) {
+            if (orow) {
+                if (full_o) {
                     *(float4 *)(orow + idx) = make_float4(oe[0], oe[1], oe[2], oe[3]);
                 } else {
 #pragma unroll

@@ -61,14 +61,9 @@ __global__ __launch_bounds__(kStreamThreads) void verify_stream_kernel(const voi
     const float pfill = KIND == RDK_PROB_F32 ? 0.f : -INFINITY;
 
     for (int c = c_begin + wid; c < c_end; c += kWavesPerBlock) {
-        const int64_t base = (int64_t)c * kChunk + lane * 4;
         float4 pv[4], qv[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) pv[i] = load4<KIND>(pr, base + i * 256, N, vec_p, pfill);
-        if (HAS_Q) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) qv[i] = load4<RDK_PROB_F32>(qr, base + i * 256, N, vec_q, 0.f);
-        }
+        load_chunk<KIND>(pr, (int64_t)c * kChunk, N, vec_p, pfill, pv);
+        if (HAS_Q) load_chunk<RDK_PROB_F32>(qr, (int64_t)c * kChunk, N, vec_q, 0.f, qv);
         float sq = 0.f, sr = 0.f, sa = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -172,10 +167,8 @@ __global__ __launch_bounds__(kStreamThreads) void row_block_sums_kernel(const fl
     const float *qr = q + row * ldq;
     const int wid = threadIdx.x / kWave, lane = lane_id();
     for (int c = c_begin + wid; c < c_end; c += kWavesPerBlock) {
-        const int64_t base = (int64_t)c * kChunk + lane * 4;
         float4 qv[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) qv[i] = load4<RDK_PROB_F32>(qr, base + i * 256, N, vec_q, 0.f);
+        load_chunk<RDK_PROB_F32>(qr, (int64_t)c * kChunk, N, vec_q, 0.f, qv);
         float sq = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) sq += (qv[i].x + qv[i].y) + (qv[i].z + qv[i].w);
