@@ -24,6 +24,18 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 MFMA_F32_PEAK_TFLOPS = 157.3    # MI355X fp32 matrix, published
 
 
+# HBM bytes per launch from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this script (summary and
+# commands in profiles/), scaled by the 256 MiB yardstick pass below: bytes = 1024 * (2 * FETCH_SIZE + WRITE_SIZE).
+# Keyed by (workload, mode, path, kernel); valid for the kernels as committed with that summary.
+MEASURED_TRAFFIC = {
+    ("llama3", "sparse", "fused", "sparse_product_kernel"): 580.5e6,
+    ("llama3", "taylor", "fused", "taylor_stats_kernel"): 165.4e6,
+    ("llama3", "taylor", "fused", "taylor_write_kernel"): 166.6e6,
+    ("dense256k", "exact", "bf16", "exact_bf16_kernel"): 19181.8e6,
+    ("n32k", "exact", "f32", "exact_f32_mfma_kernel"): 1123.6e6,
+}
+
+
 def algorithmic_bytes(kernel, w, B, kk, fused, esz):
     """Bytes one launch of a kernel must move for B positions (inputs read once, outputs written once).
     esz = bytes per input element (4: fp32, 2: bf16 logits).  In the fused path the product / Eq. 3 kernels
@@ -120,7 +132,8 @@ def run_linear(args, rdk, synth, torch, w, vocab, batch, mode_name, path, steps,
     avg_s = kms / cnt * 1e-3
     achieved = alg / avg_s / 1e9
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "avg_launch_us": round(avg_s * 1e6, 2),
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((w.name, mode_name, path, dominant)),
+                "avg_launch_us": round(avg_s * 1e6, 2),
                 "algorithmic_bytes_per_launch": alg}
     # whole-step compulsory bytes: fused = read p and q once; two calls = q read, q' written then read, p read (twice for Eq. 3)
     if fused:
@@ -198,7 +211,7 @@ def run_exact(rdk, synth, torch, wname, fmt, calls=5):
     return {"workload": "%s: N=%d n=%d B=%d, M %s %.2f GB" % (wname, w.N, w.n, w.B, fmt, esz * w.n * w.N / 1e9),
             "ms_per_call": round(ms_call, 3), "positions_per_s": round(w.B / (ms_call * 1e-3), 1),
             "roofline": {"kernel": kname, "bound": "mfma", "achieved": round(k_tf, 1), "peak": peak,
-                         "unit": "TFLOP/s", "frac": round(k_tf / peak, 4), "traffic": None,
+                         "unit": "TFLOP/s", "frac": round(k_tf / peak, 4), "traffic": MEASURED_TRAFFIC.get((wname, "exact", fmt, kname)),
                          "avg_launch_us": round(kms / cnt * 1e3, 1), "algorithmic_flops_per_launch": flops},
             "call_TFLOPs": round(flops / (ms_call * 1e-3) / 1e12, 1), "max_row_sum_error": row_err}
 
