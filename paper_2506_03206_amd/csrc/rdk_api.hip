@@ -414,7 +414,8 @@ rdk_status_t rdk_sample_draft(const rdk_kernel_t *kernel, const void *q, rdk_inp
     if (workspace_bytes < need - 256) return RDK_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     RowInput qi{q, q_kind, ldq};
-    if (sparse_product_kernel_of(h)) return launch_sparse_draft(h, qi, B, seed, offset, draft_ids, q_draft, q_prime, ldo, workspace, st);
+    if (sparse_product_kernel_of(h))
+        return launch_sparse_draft(h, qi, B, seed, offset, draft_ids, q_draft, q_prime, ldo, workspace, st);
     if (!q_prime) return RDK_ERR_NULL;
     size_t redistribute = 0;
     rdk_workspace_bytes(kernel, B, &redistribute);

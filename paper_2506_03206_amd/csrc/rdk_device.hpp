@@ -30,7 +30,10 @@ __device__ __forceinline__ double dpp_move(double v)
 }
 
 // value of lane `src` (the same for all lanes) in every lane
-__device__ __forceinline__ int lane_value(int v, int src) { return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(src)); }
+__device__ __forceinline__ int lane_value(int v, int src)
+{
+    return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(src));
+}
 __device__ __forceinline__ float lane_value(float v, int src)
 {
     return __builtin_bit_cast(float, lane_value(__builtin_bit_cast(int, v), src));

@@ -52,7 +52,8 @@ __global__ void prep_a_f32_kernel(const void *q, int64_t ldq, const SoftStat *qs
 // One wavefront per (128 target ids, 64 positions, one split of the slot groups).  Loads run two slot groups
 // ahead of the MFMAs through a ring of three register sets; the split length is a multiple of three groups (the
 // A records are zero beyond n, and rows of M are clamped to the last one), so the loop body is straight-line code.
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void exact_f32_mfma_kernel(const float *Ap, const float *M, int64_t ldm, int n, int N, int B,
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void exact_f32_mfma_kernel(
+    const float *Ap, const float *M, int64_t ldm, int n, int N, int B,
                                                                int KQ, int groups_per_split, const SoftStat *qstat, float *dst,
                                                                int64_t ldd, int64_t split_stride, bool scale_here, bool vec_d)
 {
@@ -411,22 +412,22 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
         w.part = (float *)p;
         const int64_t ldd = (h.N + 3) / 4 * 4;
         {
-            RDK_TIMED_LAUNCH("prep_a_f32_kernel", (prep_a_f32_kernel<QK>), dim3((unsigned)((records * kWave + 255) / 256)), dim3(256),
-                             0, st, q.ptr, q.ld, w.qstat, h.n, B, KQ, records, w.Af);
+            RDK_TIMED_LAUNCH("prep_a_f32_kernel", (prep_a_f32_kernel<QK>), dim3((unsigned)((records * kWave + 255) / 256)),
+                             dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.n, B, KQ, records, w.Af);
         }
         RDK_LAUNCH_CHECK("prep_a_f32_kernel");
         dim3 grid((h.N + kColSet - 1) / kColSet, row_groups, splits);
         if (splits == 1) {
             const bool vec_d = rows_vectorisable(out, ldo, RDK_PROB_F32);
-            RDK_TIMED_LAUNCH("exact_f32_mfma_kernel", exact_f32_mfma_kernel, grid, dim3(kWave), 0, st, w.Af, h.dense, h.ldm, h.n, h.N, B,
-                             KQ, groups, w.qstat, out, ldo, (int64_t)0, true, vec_d);
+            RDK_TIMED_LAUNCH("exact_f32_mfma_kernel", exact_f32_mfma_kernel, grid, dim3(kWave), 0, st, w.Af, h.dense, h.ldm,
+                             h.n, h.N, B, KQ, groups, w.qstat, out, ldo, (int64_t)0, true, vec_d);
             RDK_LAUNCH_CHECK("exact_f32_mfma_kernel");
         } else {
-            RDK_TIMED_LAUNCH("exact_f32_mfma_kernel", exact_f32_mfma_kernel, grid, dim3(kWave), 0, st, w.Af, h.dense, h.ldm, h.n, h.N, B,
-                             KQ, groups, w.qstat, w.part, ldd, (int64_t)B * ldd, false, true);
+            RDK_TIMED_LAUNCH("exact_f32_mfma_kernel", exact_f32_mfma_kernel, grid, dim3(kWave), 0, st, w.Af, h.dense, h.ldm,
+                             h.n, h.N, B, KQ, groups, w.qstat, w.part, ldd, (int64_t)B * ldd, false, true);
             RDK_LAUNCH_CHECK("exact_f32_mfma_kernel");
-            RDK_TIMED_LAUNCH("exact_reduce_kernel", exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part, ldd,
-                             (int64_t)B * ldd, splits, w.qstat, h.N, out, ldo);
+            RDK_TIMED_LAUNCH("exact_reduce_kernel", exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part,
+                             ldd, (int64_t)B * ldd, splits, w.qstat, h.N, out, ldo);
             RDK_LAUNCH_CHECK("exact_reduce_kernel");
         }
         return RDK_OK;
@@ -440,19 +441,22 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
     w.A = (uint16_t *)p; p += align_up((size_t)B_pad * h.n_pad * 2, 256);
     w.out_scale = (float *)p;
     {
-        RDK_TIMED_LAUNCH("prep_a_bf16_kernel", (prep_a_bf16_kernel<QK>), dim3(B_pad), dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.row_sum, h.n, KB, B,
-                           w.A, w.out_scale);
+        RDK_TIMED_LAUNCH("prep_a_bf16_kernel", (prep_a_bf16_kernel<QK>), dim3(B_pad), dim3(256), 0, st, q.ptr, q.ld, w.qstat,
+                         h.row_sum, h.n, KB, B, w.A, w.out_scale);
     }
     RDK_LAUNCH_CHECK("prep_a_bf16_kernel");
     const int n_jb = (h.N + kColBlock - 1) / kColBlock;
     dim3 grid((n_jb + kColBlocksPerWg - 1) / kColBlocksPerWg, B_pad / rows_per_wg);
     {
         if (W == 4 && RB == 1)
-            RDK_TIMED_LAUNCH("exact_bf16_kernel", (exact_bf16_kernel<4, 1>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
+            RDK_TIMED_LAUNCH("exact_bf16_kernel", (exact_bf16_kernel<4, 1>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B,
+                             w.out_scale, out, ldo);
         else if (W == 8)
-            RDK_TIMED_LAUNCH("exact_bf16_kernel", (exact_bf16_kernel<8, 1>), grid, dim3(512), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
+            RDK_TIMED_LAUNCH("exact_bf16_kernel", (exact_bf16_kernel<8, 1>), grid, dim3(512), 0, st, w.A, h.packed, KB, h.N, B,
+                             w.out_scale, out, ldo);
         else
-            RDK_TIMED_LAUNCH("exact_bf16_kernel", (exact_bf16_kernel<4, 4>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B, w.out_scale, out, ldo);
+            RDK_TIMED_LAUNCH("exact_bf16_kernel", (exact_bf16_kernel<4, 4>), grid, dim3(256), 0, st, w.A, h.packed, KB, h.N, B,
+                             w.out_scale, out, ldo);
     }
     RDK_LAUNCH_CHECK("exact_bf16_kernel");
     return RDK_OK;

@@ -397,7 +397,8 @@ __global__ __launch_bounds__(kWave) void draft_finalize_kernel(DraftArgs a, QP q
     double thr = 0.0, before = 0.0;
     if (Q > 0.0) {
         thr = word_to_unit(words[0]) * Q;
-        blk = in_regs ? locate_block_regs(vq, a.nblk, per_lane, lane_q, thr, before) : locate_block(pq, a.nblk, per_lane, lane_q, thr, before);
+        blk = in_regs ? locate_block_regs(vq, a.nblk, per_lane, lane_q, thr, before)
+                      : locate_block(pq, a.nblk, per_lane, lane_q, thr, before);
     }
     int32_t dtok = -1;
     float qd = 0.f;
@@ -427,7 +428,8 @@ __global__ __launch_bounds__(kWave) void draft_finalize_kernel(DraftArgs a, QP q
 template <int BLOCK, class QP>
 rdk_status_t launch_draft_finalize(const DraftArgs &a, QP qp, hipStream_t st)
 {
-    RDK_TIMED_LAUNCH("draft_finalize_kernel", (draft_finalize_kernel<BLOCK, QP>), dim3((unsigned)a.B), dim3(kWave), 0, st, a, qp);
+    RDK_TIMED_LAUNCH("draft_finalize_kernel", (draft_finalize_kernel<BLOCK, QP>), dim3((unsigned)a.B), dim3(kWave), 0, st, a,
+                     qp);
     RDK_LAUNCH_CHECK("draft_finalize_kernel");
     return RDK_OK;
 }
@@ -448,7 +450,8 @@ rdk_status_t launch_finalize(FinalizeArgs a, QP qp, hipStream_t st)
     a.rows_per_block = a.scan_here ? d.gamma : (QP::kSpreadRows ? 1 : 4);
     const int blocks = (d.B + a.rows_per_block - 1) / a.rows_per_block;
     {
-        RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_kernel<KIND, BLOCK, HAS_Q, QP>), dim3(blocks), dim3(a.rows_per_block * kWave), 0, st, a, qp);
+        RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_kernel<KIND, BLOCK, HAS_Q, QP>), dim3(blocks),
+                         dim3(a.rows_per_block * kWave), 0, st, a, qp);
     }
     RDK_LAUNCH_CHECK("verify_finalize_kernel");
     if (d.gamma > 0 && !a.scan_here && (a.n_accepted || a.out_tokens))

@@ -35,9 +35,9 @@ LinearWs carve(const KernelHandle &h, int32_t B, void *ws)
 // ------------------------------------------------------------------------------------------------
 // The kept ids ascend, so the kept ids inside one chunk of kChunk target ids own a contiguous run of slots
 // lo .. hi-1 (chunk_lo of the kernel handle).  A wavefront reads that run of the drafter row and of kept_ids with
-// coalesced loads and scatters it through a private LDS array (kChunk words + one spare word per lane) into id order; afterwards lane l holds the raw
-// unnormalised drafter weights of the ids  base + i*256 + l*4 .. +3  (i = 0..3), the same ids whose target values it
-// loads; ids that are not kept get 0.  This replaces one gather per id.
+// coalesced loads and scatters it through a private LDS array (kChunk words + one spare word per lane) into id
+// order; afterwards lane l holds the unnormalised drafter weights of the ids  base + i*256 + l*4 .. +3  (i = 0..3),
+// the same ids whose target values it loads; ids that are not kept get 0.  This replaces one gather per id.
 __device__ __forceinline__ void wave_lds_sync()
 {
     // LDS operations of one wavefront execute in order: only the compiler has to be kept from moving them
@@ -85,7 +85,8 @@ __device__ __forceinline__ void stage_chunk(float *lds, const void *qr, bool vec
 // Then theta = Tn / Zq and sum_j pt_j = An / Zq + theta * Bs, because
 //   pt_j = N q'_j / (N + p_j) + theta p_j / (N + p_j)  with q'_j = q^_s / Zq on kept ids, 0 elsewhere.
 template <int PK, int QK>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) void taylor_stats_kernel(const void *p, int64_t ldp, const void *q, int64_t ldq,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) void taylor_stats_kernel(
+    const void *p, int64_t ldp, const void *q, int64_t ldq,
                                                                 const int32_t *kept, const int32_t *chunk_lo, int N, int n,
                                                                 int splits, bool vec_p, bool vec_q, LinearWs w)
 {
@@ -266,7 +267,8 @@ __device__ __forceinline__ TaylorRow<PK, QK> make_taylor_row(const TaylorArgs &a
 // verification sums per 1024-id block (sum q', sum max(0, p - q'), sum min(p, q')).  Whether q' is stored (out != NULL)
 // is decided at run time, so that the sums do not depend on it by a single bit.
 template <int PK, int QK, bool FUSE>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) void taylor_write_kernel(TaylorArgs a, bool vec_o, float *out, int64_t ldo, float *part_q,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) void taylor_write_kernel(
+    TaylorArgs a, bool vec_o, float *out, int64_t ldo, float *part_q,
                                                                 float *part_r, float *part_a)
 {
     __shared__ __attribute__((aligned(16))) float qchunk[kWaves][kChunk + kWave];
@@ -320,7 +322,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) v
             }
             if (FUSE) {
                 sq += (oe[0] + oe[1]) + (oe[2] + oe[3]);
-                sr += (fmaxf(pe[0] - oe[0], 0.f) + fmaxf(pe[1] - oe[1], 0.f)) + (fmaxf(pe[2] - oe[2], 0.f) + fmaxf(pe[3] - oe[3], 0.f));
+                sr += (fmaxf(pe[0] - oe[0], 0.f) + fmaxf(pe[1] - oe[1], 0.f)) +
+                      (fmaxf(pe[2] - oe[2], 0.f) + fmaxf(pe[3] - oe[3], 0.f));
                 sa += (fminf(pe[0], oe[0]) + fminf(pe[1], oe[1])) + (fminf(pe[2], oe[2]) + fminf(pe[3], oe[3]));
             }
         }
@@ -385,15 +388,15 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     a.w = w;
     const bool vec_o = out ? rows_vectorisable(out, ldo, RDK_PROB_F32) : false;
     {
-        RDK_TIMED_LAUNCH("taylor_stats_kernel", (taylor_stats_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads), 0, st, p.ptr, p.ld,
-                           q.ptr, q.ld, h.kept_ids, h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p, a.vec_q, w);
+        RDK_TIMED_LAUNCH("taylor_stats_kernel", (taylor_stats_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads),
+                         0, st, p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p, a.vec_q, w);
     }
     RDK_LAUNCH_CHECK("taylor_stats_kernel");
     const dim3 grid((unsigned)B * w.t_splits);
     if (!c) {
         {
-            RDK_TIMED_LAUNCH("taylor_write_kernel", (taylor_write_kernel<PK, QK, false>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo,
-                               (float *)nullptr, (float *)nullptr, (float *)nullptr);
+            RDK_TIMED_LAUNCH("taylor_write_kernel", (taylor_write_kernel<PK, QK, false>), grid, dim3(kThreads), 0, st, a, vec_o,
+                             out, ldo, (float *)nullptr, (float *)nullptr, (float *)nullptr);
         }
         RDK_LAUNCH_CHECK("taylor_write_kernel");
         return RDK_OK;
@@ -403,8 +406,8 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     char *pp = (char *)ws + taylor_workspace_bytes(h, B);
     float *part_q = (float *)pp, *part_r = (float *)(pp + per), *part_a = (float *)(pp + 2 * per);
     {
-        RDK_TIMED_LAUNCH("taylor_write_kernel", (taylor_write_kernel<PK, QK, true>), grid, dim3(kThreads), 0, st, a, vec_o, out, ldo, part_q, part_r,
-                           part_a);
+        RDK_TIMED_LAUNCH("taylor_write_kernel", (taylor_write_kernel<PK, QK, true>), grid, dim3(kThreads), 0, st, a, vec_o, out,
+                         ldo, part_q, part_r, part_a);
     }
     RDK_LAUNCH_CHECK("taylor_write_kernel");
     FinalizeArgs fa{};
@@ -426,8 +429,8 @@ rdk_status_t run_tli(const KernelHandle &h, RowInput q, int32_t B, float *out, i
     if (rc != RDK_OK) return rc;
     const int bx = (h.N + kThreads * 4 - 1) / (kThreads * 4);
     {
-        RDK_TIMED_LAUNCH("tli_scatter_kernel", (tli_scatter_kernel<QK>), dim3(bx, B), dim3(kThreads), 0, st, q.ptr, q.ld, h.slot_of, h.N, w.qstat,
-                           out, ldo);
+        RDK_TIMED_LAUNCH("tli_scatter_kernel", (tli_scatter_kernel<QK>), dim3(bx, B), dim3(kThreads), 0, st, q.ptr, q.ld,
+                         h.slot_of, h.N, w.qstat, out, ldo);
     }
     RDK_LAUNCH_CHECK("tli_scatter_kernel");
     return RDK_OK;

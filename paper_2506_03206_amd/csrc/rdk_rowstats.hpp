@@ -84,8 +84,8 @@ template <int KIND>
 inline rdk_status_t launch_row_stats(RowInput x, int64_t len, int32_t B, int splits, SoftStat *out, hipStream_t st)
 {
     {
-        RDK_TIMED_LAUNCH("row_stats_kernel", (row_stats_kernel<KIND>), dim3((unsigned)B * splits), dim3(kStatThreads), 0, st, x.ptr, x.ld, len,
-                           splits, rows_vectorisable(x.ptr, x.ld, x.kind), out);
+        RDK_TIMED_LAUNCH("row_stats_kernel", (row_stats_kernel<KIND>), dim3((unsigned)B * splits), dim3(kStatThreads), 0, st,
+                         x.ptr, x.ld, len, splits, rows_vectorisable(x.ptr, x.ld, x.kind), out);
     }
     RDK_LAUNCH_CHECK("row_stats_kernel");
     return RDK_OK;

@@ -182,7 +182,8 @@ __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0,
             {   // request the pairs of the next round (or of the next step) now
                 const bool more = rd + 1 < rounds;
                 const int un = more ? u0 : u0 + 8 * kWaves;
-                if (un < u_hi) ev_next = *(const i32x4 *)(nbr_lane + (int64_t)min(un + i, u_hi - 1) * a.kk + (more ? (rd + 1) * 16 : 0));
+                if (un < u_hi)
+                    ev_next = *(const i32x4 *)(nbr_lane + (int64_t)min(un + i, u_hi - 1) * a.kk + (more ? (rd + 1) * 16 : 0));
             }
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
@@ -481,8 +482,8 @@ rdk_status_t prepare_q(const KernelHandle &h, RowInput q, int32_t B, const Spars
     if (rc != RDK_OK) return rc;
     const int pbs = (B + kPosBlock - 1) / kPosBlock;
     {
-        RDK_TIMED_LAUNCH("q_transpose_kernel", (q_transpose_kernel<QK>), dim3((h.n + 63) / 64, pbs), dim3(kPrepThreads), 0, st, q.ptr, q.ld, h.n, B,
-                           w.qpart, w.q_splits, rows_vectorisable(q.ptr, q.ld, q.kind), w.zinv, w.qT);
+        RDK_TIMED_LAUNCH("q_transpose_kernel", (q_transpose_kernel<QK>), dim3((h.n + 63) / 64, pbs), dim3(kPrepThreads), 0, st,
+                         q.ptr, q.ld, h.n, B, w.qpart, w.q_splits, rows_vectorisable(q.ptr, q.ld, q.kind), w.zinv, w.qT);
     }
     RDK_LAUNCH_CHECK("q_transpose_kernel");
     return RDK_OK;
@@ -496,7 +497,8 @@ rdk_status_t run_sparse(const KernelHandle &h, RowInput q, int32_t B, float *out
     if (rc != RDK_OK) return rc;
     const SparseArgs a = make_args(h, w, B, out, ldo);
     {
-        RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<-1, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, FuseArgs{});
+        RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<-1, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st,
+                         a, FuseArgs{});
     }
     RDK_LAUNCH_CHECK("sparse_product_kernel");
     return RDK_OK;
@@ -527,9 +529,11 @@ rdk_status_t run_sparse_fused(const KernelHandle &h, const FusedCall &c, void *w
     const SparseArgs a = make_args(h, w, B, c.q_prime, c.ldo);
     {
         if (c.q_prime)
-            RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<PK, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+            RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<PK, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0,
+                             st, a, f);
         else
-            RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<PK, false>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+            RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<PK, false>), dim3(8 * a.per_xcd), dim3(kThreads),
+                             0, st, a, f);
     }
     RDK_LAUNCH_CHECK("sparse_product_kernel");
     FinalizeArgs fa{};
@@ -554,9 +558,11 @@ rdk_status_t run_sparse_draft(const KernelHandle &h, RowInput q, int32_t B, uint
     if (rc != RDK_OK) return rc;
     const SparseArgs a = make_args(h, w, B, q_prime, ldo);
     if (q_prime)
-        RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<-2, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+        RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<-2, true>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st,
+                         a, f);
     else
-        RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<-2, false>), dim3(8 * a.per_xcd), dim3(kThreads), 0, st, a, f);
+        RDK_TIMED_LAUNCH("sparse_product_kernel", (sparse_product_kernel<-2, false>), dim3(8 * a.per_xcd), dim3(kThreads), 0,
+                         st, a, f);
     RDK_LAUNCH_CHECK("sparse_product_kernel");
     const int blocks = a.tiles * (kTileIds / kSubIds);
     DraftArgs da{B, h.N, seed, offset, f.part_q, blocks, draft_ids, q_draft};

@@ -140,8 +140,8 @@ rdk_status_t run_verify(const rdk_verify_desc_t &d, RowInput p, const float *q, 
         if (rc != RDK_OK) return rc;
     }
     {
-        RDK_TIMED_LAUNCH("verify_stream_kernel", (verify_stream_kernel<KIND, HAS_Q>), dim3((unsigned)d.B * splits), dim3(kStreamThreads), 0, st, p.ptr,
-                           p.ld, q, ldq, d.N, splits, vec_p, vec_q, w);
+        RDK_TIMED_LAUNCH("verify_stream_kernel", (verify_stream_kernel<KIND, HAS_Q>), dim3((unsigned)d.B * splits),
+                         dim3(kStreamThreads), 0, st, p.ptr, p.ld, q, ldq, d.N, splits, vec_p, vec_q, w);
     }
     RDK_LAUNCH_CHECK("verify_stream_kernel");
     FinalizeArgs fa{};
@@ -188,8 +188,8 @@ rdk_status_t launch_draft_from_rows(const float *q_prime, int64_t ldq, int32_t B
     const int splits = row_splits(B, N, kWavesPerBlock);
     const bool vec_q = rows_vectorisable(q_prime, ldq, RDK_PROB_F32);
     float *part_q = (float *)ws;
-    RDK_TIMED_LAUNCH("row_block_sums_kernel", row_block_sums_kernel, dim3((unsigned)B * splits), dim3(kStreamThreads), 0, st, q_prime, ldq, N,
-                     nchunks, splits, vec_q, part_q);
+    RDK_TIMED_LAUNCH("row_block_sums_kernel", row_block_sums_kernel, dim3((unsigned)B * splits), dim3(kStreamThreads), 0, st,
+                     q_prime, ldq, N, nchunks, splits, vec_q, part_q);
     RDK_LAUNCH_CHECK("row_block_sums_kernel");
     DraftArgs a{B, N, seed, offset, part_q, nchunks, draft_ids, q_draft};
     return launch_draft_finalize<1024, QpMemory>(a, QpMemory{q_prime, ldq, vec_q, N}, st);
@@ -226,8 +226,8 @@ rdk_status_t launch_sequence_scan(const rdk_verify_desc_t &d, const int32_t *dra
 {
     const int S = d.B / d.gamma;
     {
-        RDK_TIMED_LAUNCH("sequence_scan_kernel", sequence_scan_kernel, dim3((S + 63) / 64), dim3(64), 0, st, S, d.gamma, draft_ids, accept, resid_ids,
-                           n_accepted, out_tokens);
+        RDK_TIMED_LAUNCH("sequence_scan_kernel", sequence_scan_kernel, dim3((S + 63) / 64), dim3(64), 0, st, S, d.gamma,
+                         draft_ids, accept, resid_ids, n_accepted, out_tokens);
     }
     RDK_LAUNCH_CHECK("sequence_scan_kernel");
     return RDK_OK;

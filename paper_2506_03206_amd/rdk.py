@@ -283,8 +283,9 @@ def rdk_sample_draft(kernel, q, seed, offset=0, q_kind="prob", q_prime=None, dra
     if getattr(kernel, "_draft_ws", None) is None or kernel._draft_ws.numel() < need.value:
         kernel._draft_ws = torch.empty(need.value, dtype=torch.uint8, device=q.device)
     ldo = 0 if q_prime is None else _rows(q_prime)
-    _check(lib().rdk_sample_draft(kernel.handle, _ptr(q), _kind_of(q, q_kind), _rows(q), B, seed, offset, _ptr(draft_ids), _ptr(q_draft), _ptr(q_prime), ldo,
-                                  _ptr(kernel._draft_ws), kernel._draft_ws.numel(), _stream()), "rdk_sample_draft")
+    _check(lib().rdk_sample_draft(kernel.handle, _ptr(q), _kind_of(q, q_kind), _rows(q), B, seed, offset, _ptr(draft_ids),
+                                  _ptr(q_draft), _ptr(q_prime), ldo, _ptr(kernel._draft_ws), kernel._draft_ws.numel(),
+                                  _stream()), "rdk_sample_draft")
     return draft_ids, q_draft
 
 
