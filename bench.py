@@ -231,7 +231,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        sys.exit("bench.py: this build is a one-GPU library (positions are independent: shard the batch); run with --gpus 1")
+        sys.exit("bench.py: this library runs on one GPU (positions are independent: shard the batch); run with --gpus 1")
 
     import torch
     from paper_2506_03206_amd import rdk, synth
