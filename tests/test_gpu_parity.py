@@ -379,7 +379,7 @@ def test_acceptance_sweep_matches_oracle(rdk):
 
 # --------------------------------------------------------------------------------------------- draft-side sampling
 @pytest.mark.parametrize("case", ["tiny", "ragged"])
-@pytest.mark.parametrize("form", ["sparse", "sparse_rows", "identity", "dense_f32"])
+@pytest.mark.parametrize("form", ["sparse", "sparse_rows", "identity", "dense_f32", "dense_bf16"])
 def test_sample_draft(rdk, tiny, ragged, case, form):
     """rdk_sample_draft: ids drawn from q' alone (no target row) against the oracle's inverse CDF of its own q'."""
     data = tiny if case == "tiny" else ragged
@@ -393,20 +393,29 @@ def test_sample_draft(rdk, tiny, ragged, case, form):
     elif form == "identity":
         kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.IDENTITY)
         ref_qp = oracle_rows(data, "tli")
-    else:
+    elif form == "dense_f32":
         M32 = data["dense"].astype(np.float32)
         kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.DENSE_F32, dense_M=dev(M32))
         ref_qp = oracle_rows(data, "exact", kernel=M32)
+    else:   # bf16 storage: the reference rows are the product of the rounded operands, rescaled to unit mass
+        M32 = data["dense"].astype(np.float32)
+        kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.DENSE_BF16, dense_M=dev(M32))
+        Mb = synth.bf16_round(M32).astype(np.float64)
+        ref_qp = np.empty((w.B, w.N))
+        for b in range(w.B):
+            r = oracle.redistribute_dense(synth.bf16_round(oracle.tli(data["q_hat"][b]).astype(np.float32)), Mb)
+            ref_qp[b] = r / r.sum()
+    rtol = 4e-5 if form == "dense_bf16" else RTOL
     seed, offset = 909, (1 << 35) + 3
     d, qd = rdk.rdk_sample_draft(kern, dev(data["q_hat"]), seed, offset, q_prime=None if form == "sparse" else qp)
     torch.cuda.synchronize()
     d, qd = d.cpu().numpy(), qd.cpu().numpy()
     u0 = np.array([oracle.uniforms(seed, offset + b)[0] for b in range(w.B)])
     ref_d = np.array([oracle.sample_cdf(ref_qp[b], u0[b]) for b in range(w.B)])
-    assert check_sampled_ids(ref_qp, u0, d, ref_d, what="draft from q'") >= 0.9 * w.B
-    assert_close(qd, ref_qp[np.arange(w.B), d], what="q' at the drafted id")
+    assert check_sampled_ids(ref_qp, u0, d, ref_d, tol=4e-5 if form == "dense_bf16" else 1e-5, what="draft from q'") >= 0.9 * w.B
+    assert_close(qd, ref_qp[np.arange(w.B), d], rtol=rtol, what="q' at the drafted id")
     if form != "sparse":
-        assert_close(qp.cpu().numpy(), ref_qp, what="rows written on the way")
+        assert_close(qp.cpu().numpy(), ref_qp, rtol=rtol, what="rows written on the way")
     if form in ("sparse", "sparse_rows"):   # the fused verification draws the same ids from the same block sums
         o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_SPARSE, dev(data["p"]), dev(data["q_hat"]), seed, offset, w.gamma)
         assert np.array_equal(o.draft_ids.cpu().numpy(), d)
