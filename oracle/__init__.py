@@ -53,6 +53,8 @@ def lib():
         L.orc_redistribute_sparse.restype = None
         L.orc_taylor.argtypes = [_D, _D, _I32, _i64, _i64, _D, _D, _D]
         L.orc_taylor.restype = ctypes.c_int
+        L.orc_features_from_scores.argtypes = [_D, _i64, _i64, _D]
+        L.orc_features_from_scores.restype = None
         L.orc_overlap.argtypes = [_D, _D, _i64, _D, _D]
         L.orc_overlap.restype = None
         L.orc_kernel_l1.argtypes = [_D, _D, _i64]
@@ -203,6 +205,16 @@ def sequence_scan(accept_flags, draft_ids, resid_ids, gamma):
 
 
 # ----------------------------------------------------------------------------- kernel construction
+def features_from_scores(z):
+    """Sec. 3 (Omega estimated from data): z [T,N] sampled score rows -> centred token features F [N,T]; the cosine
+    of two rows of F is the correlation of the two tokens' scores over the sample."""
+    z = _f64(z)
+    T, N = z.shape
+    F = np.empty((N, T))
+    lib().orc_features_from_scores(_p(z, _D), T, N, _p(F, _D))
+    return F
+
+
 def build_dense(E, kept_ids, tau):
     """Eq. 2 with Omega = cosine similarity of the rows of E.  Returns M [n, N] fp64."""
     E, kept_ids = _f64(E), _i32(kept_ids)

@@ -264,6 +264,22 @@ static double dot(const double *a, const double *b, int64_t d)
     return s;
 }
 
+/* Sec. 3, "Token-affinity priors": Omega is estimated from data.  Token features */
+/* from T sampled score rows z[t, :] (target logits or probabilities at T        */
+/* positions): F[j, t] = z[t, j] - mean_t z[., j].  With these rows as the        */
+/* embeddings of Eq. 2, Omega_ij (the cosine of rows i and j) is the covariance   */
+/* of the scores of tokens i and j divided by their standard deviations, i.e.     */
+/* the covariance matrix of the standardised scores.                              */
+void orc_features_from_scores(const double *z /* [T, N] */, int64_t T, int64_t N, double *F /* [N, T] */)
+{
+    for (int64_t j = 0; j < N; ++j) {
+        double mean = 0.0;
+        for (int64_t t = 0; t < T; ++t) mean += z[t * N + j];
+        mean /= (double)T;
+        for (int64_t t = 0; t < T; ++t) F[j * T + t] = z[t * N + j] - mean;
+    }
+}
+
 /* Eq. 2: M_ij = exp(Omega_ij / tau) / sum_k exp(Omega_ik / tau), i kept, j in T. */
 int orc_build_dense(const double *E, int64_t N, int64_t d, const int32_t *kept_ids, int64_t n,
                     double tau, double *M /* [n, N] */)

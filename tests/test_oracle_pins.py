@@ -390,3 +390,21 @@ def test_rdk_beats_tli_when_the_target_lives_off_the_kept_ids():
         assert abs(pp.sum() - 1) < 1e-12
         # Thm 4.1 with the sparse kernel (rows of M outside the kept ids do not matter for q0)
         assert oracle.overlap(data["p"][b], pp)[0] > 0 and oracle.overlap(data["p"][b], scat)[0] > 0
+
+
+def test_features_from_scores_give_the_correlation_matrix():
+    """Sec. 3: Omega estimated from data.  The cosine of the centred feature rows is numpy's correlation matrix of the
+    score columns, and Eq. 2 on those features is the row softmax of that matrix over the kept rows."""
+    rng = np.random.default_rng(12)
+    T, N = 40, 11
+    z = rng.normal(size=(T, N)) @ rng.normal(size=(N, N)) + rng.normal(size=N)[None, :] * 3     # correlated columns, nonzero means
+    F = oracle.features_from_scores(z)
+    assert F.shape == (N, T) and np.abs(F.sum(1)).max() < 1e-12
+    U = F / np.linalg.norm(F, axis=1, keepdims=True)
+    corr = np.corrcoef(z.T)
+    assert np.abs(U @ U.T - corr).max() < 1e-12
+    kept = np.array([0, 3, 4, 9], dtype=np.int32)
+    tau = 0.3
+    M = oracle.build_dense(F, kept, tau)
+    e = np.exp((corr[kept] - 1.0) / tau)
+    assert np.abs(M - e / e.sum(1, keepdims=True)).max() < 1e-12
