@@ -102,6 +102,18 @@ rdk_status_t rdk_kernel_storage_bytes(const rdk_kernel_desc_t *desc, size_t *sto
                                       size_t *build_workspace_bytes);
 
 /*
+ * Token features from data (Sec. 3, "Token-affinity priors": Omega is estimated from data).  z [T, ldz] holds T
+ * sampled score rows over the N target ids (target logits, fp32 or bf16, or probabilities); features [N, ldf]
+ * receives  F[j, t] = z[t, j] - mean_t z[., j].  Passed as `embeddings` (d = T, row stride T: use ldf = T) to
+ * rdk_build_kernel, Omega_ij becomes the correlation of the scores of tokens i and j over the sample, i.e. the
+ * covariance matrix of the standardised scores; it is 1 on the diagonal and at most 1 elsewhere, as Eq. 2's
+ * evaluation here assumes.  T >= 2; a token whose score never varies has no direction and must not be passed on.
+ * No workspace; enqueues on `stream`.
+ */
+rdk_status_t rdk_features_from_scores(const void *z, rdk_input_kind_t z_kind, int64_t ldz, int32_t T, int32_t N,
+                                      float *features, int64_t ldf, void *stream);
+
+/*
  * Build M into `storage` (Eq. 2; "calculated once at preprocessing time").  `storage` must stay
  * alive and untouched for the life of the kernel object; `workspace` may be reused once the
  * stream has passed the build.  *out receives the host handle.

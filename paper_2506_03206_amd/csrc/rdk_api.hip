@@ -177,6 +177,16 @@ rdk_status_t rdk_kernel_storage_bytes(const rdk_kernel_desc_t *desc, size_t *sto
     return RDK_OK;
 }
 
+rdk_status_t rdk_features_from_scores(const void *z, rdk_input_kind_t z_kind, int64_t ldz, int32_t T, int32_t N, float *features,
+                                      int64_t ldf, void *stream)
+{
+    if (!z || !features) return RDK_ERR_NULL;
+    if (!kind_ok(z_kind)) return RDK_ERR_DTYPE;
+    if (T < 2 || N < 1 || ldz < N || ldf < T) return RDK_ERR_SHAPE;
+    if (!aligned16(z) || !aligned16(features)) return RDK_ERR_ALIGN;
+    return launch_features_from_scores(z, z_kind, ldz, T, N, features, ldf, (hipStream_t)stream);
+}
+
 rdk_status_t rdk_build_kernel(const rdk_kernel_desc_t *desc, void *storage, size_t storage_bytes, void *workspace,
                               size_t workspace_bytes, void *stream, rdk_kernel_t **out)
 {

@@ -80,6 +80,41 @@ __global__ void inv_norm_kernel(const float *E, int N, int d, double *inv_norm)
     if (lane_id() == 0) inv_norm[j] = 1.0 / sqrt(s);
 }
 
+// Token features from T sampled score rows (Sec. 3: Omega estimated from data):  F[j, t] = z[t, j] - mean_t z[., j].
+// One workgroup owns 64 tokens: column means in fp64 (thread x of each quarter reads z[t, j0 + x], coalesced over x),
+// then 64 x 64 tiles are turned through LDS so that both the reads of z and the writes of F are coalesced.
+template <int KIND>
+__global__ __launch_bounds__(256) void features_from_scores_kernel(const void *z, int64_t ldz, int T, int N, float *F, int64_t ldf)
+{
+    __shared__ double part[4][64];
+    __shared__ float mean[64];
+    __shared__ float tile[64][65];
+    const int x = threadIdx.x % 64, y = threadIdx.x / 64;
+    const int j0 = blockIdx.x * 64;
+    const bool col_ok = j0 + x < N;
+    double acc = 0.0;
+    if (col_ok)
+        for (int t = y; t < T; t += 4) acc += (double)load1<KIND>(row_ptr<KIND>(z, ldz, t), j0 + x);
+    part[y][x] = acc;
+    __syncthreads();
+    if (y == 0) mean[x] = (float)(((part[0][x] + part[1][x]) + (part[2][x] + part[3][x])) / (double)T);
+    __syncthreads();
+    for (int t0 = 0; t0 < T; t0 += 64) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {   // rows t0 + y + 4 r of z, columns j0 + x
+            const int t = t0 + y + 4 * r;
+            tile[y + 4 * r][x] = (col_ok && t < T) ? load1<KIND>(row_ptr<KIND>(z, ldz, t), j0 + x) - mean[x] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {   // rows j0 + y + 4 r of F, columns t0 + x
+            const int j = j0 + y + 4 * r;
+            if (j < N && t0 + x < T) F[(int64_t)j * ldf + t0 + x] = tile[x][y + 4 * r];
+        }
+        __syncthreads();
+    }
+}
+
 // chunk_lo[c] = number of kept ids below c * kChunk (kept ids ascend, so the ids of chunk c hold the slots
 // chunk_lo[c] .. chunk_lo[c + 1] - 1, a contiguous piece of every drafter row).
 __global__ void chunk_lo_kernel(const int32_t *kept_ids, int n, int nchunks, int32_t *chunk_lo)
@@ -360,6 +395,24 @@ rdk_status_t launch_check_kept(const int32_t *kept_ids, int32_t n, int32_t N, in
     hipLaunchKernelGGL(fill_flag_kernel, dim3(1), dim3(1), 0, st, flag);
     hipLaunchKernelGGL(check_kept_kernel, dim3((n + 255) / 256), dim3(256), 0, st, kept_ids, n, N, flag);
     RDK_LAUNCH_CHECK("check_kept_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_features_from_scores(const void *z, rdk_input_kind_t kind, int64_t ldz, int32_t T, int32_t N, float *F,
+                                         int64_t ldf, hipStream_t st)
+{
+    const dim3 grid((N + 63) / 64), block(256);
+    switch (kind) {
+        case RDK_PROB_F32:
+        case RDK_LOGIT_F32:
+            hipLaunchKernelGGL((features_from_scores_kernel<RDK_LOGIT_F32>), grid, block, 0, st, z, ldz, T, N, F, ldf);
+            break;
+        case RDK_LOGIT_BF16:
+            hipLaunchKernelGGL((features_from_scores_kernel<RDK_LOGIT_BF16>), grid, block, 0, st, z, ldz, T, N, F, ldf);
+            break;
+        default: return RDK_ERR_DTYPE;
+    }
+    RDK_LAUNCH_CHECK("features_from_scores_kernel");
     return RDK_OK;
 }
 

@@ -89,6 +89,8 @@ bool timing_events(const char *kernel_name, hipEvent_t *start, hipEvent_t *stop)
 size_t build_workspace_bytes(const rdk_kernel_desc_t &d);
 rdk_status_t launch_slot_of(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *slot_of, hipStream_t st);
 rdk_status_t launch_check_kept(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *flag, hipStream_t st);
+rdk_status_t launch_features_from_scores(const void *z, rdk_input_kind_t kind, int64_t ldz, int32_t T, int32_t N, float *F,
+                                         int64_t ldf, hipStream_t st);
 rdk_status_t launch_chunk_lo(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *chunk_lo, hipStream_t st);
 rdk_status_t launch_pruned_ids(const int32_t *slot_of, int32_t N, int32_t *pruned_ids, hipStream_t st);
 rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *pruned_ids, int2 *nbr, float *self_w,

@@ -23,7 +23,7 @@ EXPORTS = [
     "rdk_kernel_get_sparse", "rdk_kernel_get_dense", "rdk_workspace_bytes", "rdk_redistribute_exact",
     "rdk_redistribute_linear", "rdk_verify_workspace_bytes", "rdk_verify_sample", "rdk_philox_words",
     "rdk_timing_select", "rdk_timing_read", "rdk_redistribute_verify_workspace_bytes", "rdk_redistribute_verify",
-    "rdk_sample_draft_workspace_bytes", "rdk_sample_draft",
+    "rdk_sample_draft_workspace_bytes", "rdk_sample_draft", "rdk_features_from_scores",
 ]
 
 
@@ -82,6 +82,7 @@ def lib():
                                               ctypes.c_int, i64, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.rdk_sample_draft_workspace_bytes.argtypes = [vp, i32, psz]
         L.rdk_sample_draft.argtypes = [vp, vp, ctypes.c_int, i64, i32, ctypes.c_uint64, ctypes.c_uint64, vp, vp, vp, i64, vp, sz, vp]
+        L.rdk_features_from_scores.argtypes = [vp, ctypes.c_int, i64, i32, i32, vp, i64, vp]
         L.rdk_timing_select.argtypes = [ctypes.c_char_p]
         L.rdk_timing_read.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
         for name in EXPORTS:
@@ -140,6 +141,16 @@ class Kernel:
         if self._ws is None or self._ws.numel() < need.value:
             self._ws = torch.empty(need.value, dtype=torch.uint8, device=self.storage.device)
         return self._ws
+
+
+def rdk_features_from_scores(z, kind="logit"):
+    """Centred token features [N, T] from T sampled score rows z [T, N] (fp32, or bf16 logits): embeddings whose
+    cosine is the correlation of the tokens' scores over the sample."""
+    T, N = z.shape
+    F = torch.empty((N, T), dtype=torch.float32, device=z.device)
+    _check(lib().rdk_features_from_scores(_ptr(z), _kind_of(z, kind), _rows(z), T, N, _ptr(F), T, _stream()),
+           "rdk_features_from_scores")
+    return F
 
 
 def rdk_build_kernel(N, kept_ids, fmt, embeddings=None, tau=0.1, k=0, dense_M=None, sparse=None, validate=True):

@@ -87,6 +87,33 @@ def test_build_dense_matches_oracle(rdk, tiny, ragged, case):
     assert np.abs(M.astype(np.float64).sum(1) - 1).max() < 1e-5
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_features_from_scores_and_kernel_from_data(rdk, ragged, dtype):
+    """Omega estimated from data (Sec. 3): centred token features from sampled target logits, then the top-k kernel
+    built from them, against the oracle's features and the oracle's kernel."""
+    w = ragged["w"]
+    T = 70
+    rng = np.random.default_rng(21)
+    z = (rng.normal(size=(T, 24)) @ rng.normal(size=(24, w.N)) + rng.normal(size=w.N)[None, :]).astype(np.float32)
+    if dtype == "bf16":
+        z = synth.bf16_round(z)
+        z_dev = bf16_tensor(z)
+    else:
+        z_dev = dev(z)
+    F = rdk.rdk_features_from_scores(z_dev)
+    ref_F = oracle.features_from_scores(z)
+    assert_close(F.cpu().numpy(), ref_F, rtol=1e-5, atol=2e-6, what="centred features")
+    kern = rdk.rdk_build_kernel(w.N, dev(ragged["kept_ids"]), rdk.SPARSE_TOPK, embeddings=F, tau=w.tau, k=w.k)
+    idx, wt, sw = [t.cpu().numpy() for t in rdk.rdk_kernel_get_sparse(kern)]
+    o_idx, o_w, o_sw, om = oracle.build_sparse(F.cpu().numpy(), ragged["kept_ids"], w.tau, w.k, return_affinities=True)
+    # neighbour lists agree wherever the oracle's ranking is not a near-tie (both sides start from the same fp32 features)
+    clear = np.min(-np.diff(om, axis=1), axis=1) > 1e-9
+    assert clear.mean() > 0.99 and np.array_equal(idx[clear], o_idx[clear])
+    if clear.all():
+        assert_close(wt, o_w, what="neighbour weights")
+        assert_close(sw, o_sw, what="diagonal weights")
+
+
 def test_build_validation(rdk, tiny):
     w = tiny["w"]
     bad = tiny["kept_ids"].copy()
