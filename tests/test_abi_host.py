@@ -95,3 +95,18 @@ def test_verify_argument_checks(rdk):
     assert L.rdk_verify_sample(*args(q=None)) == 7                                       # bonus draw cannot be scanned
     assert L.rdk_philox_words(1, 0, 0, vp(0x1000), None) == 2
     assert L.rdk_redistribute_exact(None, vp(0x1000), 0, 10, 1, vp(0x2000), 10, vp(0x3000), 10, None) == 1
+
+
+def test_draft_and_feature_argument_checks(rdk):
+    """The newer entry points validate on the host too (nothing is launched)."""
+    L = rdk.lib()
+    vp = ctypes.c_void_p
+    need = ctypes.c_size_t()
+    assert L.rdk_sample_draft_workspace_bytes(None, 8, ctypes.byref(need)) == 1
+    assert L.rdk_sample_draft(None, vp(0x1000), 0, 16, 8, 1, 0, vp(0x2000), None, None, 0, vp(0x3000), 1 << 20, None) == 1
+    feat = lambda z=0x1000, kind=1, ldz=100, T=8, N=100, F=0x2000, ldf=8: L.rdk_features_from_scores(
+        vp(z) if z else None, kind, ldz, T, N, vp(F) if F else None, ldf, None)
+    assert feat(z=None) == 1 and feat(F=None) == 1
+    assert feat(kind=4) == 3
+    assert feat(T=1) == 2 and feat(ldz=99) == 2 and feat(ldf=7) == 2 and feat(N=0) == 2
+    assert feat(z=0x1008) == 9 and feat(F=0x2004) == 9
