@@ -155,8 +155,9 @@ __device__ __forceinline__ int pruned_below(const int32_t *slot_of, int j, int N
 // sums).  Lane layout of a wavefront: lane = 8 * i + o; i = id within a group of 8, o = which four of
 // the 32 positions.  One 128-byte line holds the 16 (slot, weight) pairs of a round: lane o of an id's
 // group fetches pairs 2o and 2o+1, and the pairs go round the group through the swizzle crossbar.
-// The kernel is bound by the latency of its dependent loads, so the next line of pairs is requested
-// before the current gathers are issued, and registers are kept low enough for 6-8 wavefronts per SIMD.
+// The next line of pairs is requested before the current gathers are issued.  The kernel runs at the throughput
+// of the CU's vector memory pipe (address and data-return units about 80 % busy); occupancy beyond two workgroups
+// per CU does not change its time.
 __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0, float (*stage)[kStageLd])
 {
     const int wid = threadIdx.x / kWave, lane = lane_id();
@@ -191,12 +192,10 @@ __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0,
                 float wt[8];
 #define RDK_GATHER(T)                                                                                                       \
     {                                                                                                                       \
-        const int src_ = (half * 4 + ((T) >> 1)) << 5 | 0x18;                                                               \
         const int s_ = half ? __builtin_amdgcn_ds_swizzle(ev[2 * ((T) & 1)], ((4 + ((T) >> 1)) << 5) | 0x18)                \
                             : __builtin_amdgcn_ds_swizzle(ev[2 * ((T) & 1)], (((T) >> 1) << 5) | 0x18);                     \
         wt[T] = __int_as_float(half ? __builtin_amdgcn_ds_swizzle(ev[2 * ((T) & 1) + 1], ((4 + ((T) >> 1)) << 5) | 0x18)    \
                                     : __builtin_amdgcn_ds_swizzle(ev[2 * ((T) & 1) + 1], (((T) >> 1) << 5) | 0x18));        \
-        (void)src_;                                                                                                         \
         g[T] = *(const float4 *)(qslab + (int64_t)s_ * kPosBlock);                                                          \
     }
                 RDK_GATHER(0) RDK_GATHER(1) RDK_GATHER(2) RDK_GATHER(3) RDK_GATHER(4) RDK_GATHER(5) RDK_GATHER(6) RDK_GATHER(7)
