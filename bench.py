@@ -268,7 +268,7 @@ def main():
                                       "step_frac_of_hbm_peak": o["step_frac_of_hbm_peak"]}
         extra["draft_sampling"] = run_draft(args, rdk, synth, torch, w, (bias, kept, E), batch, max(20, args.steps // 2))
         torch.cuda.empty_cache()
-        extra["exact_bf16"] = run_exact(rdk, synth, torch, "dense256k", "bf16")
+        extra["exact_bf16"] = run_exact(rdk, synth, torch, "dense256k", "bf16", calls=10)
         extra["exact_f32"] = run_exact(rdk, synth, torch, "n32k", "f32", calls=20)
 
     cpu = None
