@@ -462,6 +462,52 @@ def test_sample_draft_zero_row_and_errors(rdk, tiny):
     assert e.value.status == 1
 
 
+def test_extreme_rows(rdk, ragged):
+    """Rows at the edges of the input domain through both fused forms: a one-hot target, a target disjoint from the
+    drafter's support (alpha = 0), drafter rows that are mostly exact zeros, and logits spanning +-60."""
+    w = ragged["w"]
+    idx, wt, sw = ragged["sparse"]
+    wt32, sw32 = wt.astype(np.float32), sw.astype(np.float32)
+    kept = ragged["kept_ids"]
+    B = 8
+    rng = np.random.default_rng(77)
+    p = rng.gamma(0.2, size=(B, w.N)).astype(np.float32)
+    q = rng.gamma(0.2, size=(B, w.n)).astype(np.float32)
+    p[0] = 0
+    p[0, kept[5]] = 1.0                                   # one-hot target on a kept id
+    p[1] = 0
+    is_kept = np.zeros(w.N, dtype=bool)
+    is_kept[kept] = True
+    p[1, np.nonzero(~is_kept)[0][::7]] = 1.0              # target mass only on pruned ids
+    q[2, 10:] = 0                                         # drafter mass on ten slots
+    q[3] = 0
+    q[3, w.n - 1] = 3.0                                   # a single slot, not normalised
+    p = (p / p.sum(1, keepdims=True)).astype(np.float32)
+    p64 = p.astype(np.float64)
+    ks = rdk.rdk_build_kernel(w.N, dev(kept), rdk.SPARSE_TOPK, k=w.k, sparse=(dev(idx), dev(wt32), dev(sw32)))
+    ki = rdk.rdk_build_kernel(w.N, dev(kept), rdk.IDENTITY)
+    for kern, gmode, mode, sparse in ((ks, rdk.LINEAR_SPARSE, "sparse", (idx, wt32, sw32)), (ki, rdk.LINEAR_TAYLOR, "taylor", None)):
+        qp = torch.empty((B, w.N), dtype=torch.float32, device="cuda")
+        o = rdk.rdk_redistribute_verify(kern, gmode, dev(p), dev(q), 5, 0, 4, q_prime=qp)
+        ref_qp = oracle.redistribute_batch(mode, q, kept, w.N, p=p64, sparse=sparse)
+        assert_close(qp.cpu().numpy(), ref_qp, what="q' (%s), extreme rows" % mode)
+        ref = oracle.verify_batch(p64, ref_qp, 5, 0, gamma=4)
+        check_verify_outputs(o, ref, p64, ref_qp, 5, 0, 4, "prob", min_exact=0.75)
+    # logits over a wide range, fp32 and bf16
+    z_p = (rng.normal(size=(B, w.N)) * 20).clip(-60, 60).astype(np.float32)
+    z_q = (rng.normal(size=(B, w.n)) * 20).clip(-60, 60).astype(np.float32)
+    for zp_dev, zq_dev, zp, zq in ((dev(z_p), dev(z_q), z_p, z_q),
+                                   (bf16_tensor(synth.bf16_round(z_p)), bf16_tensor(synth.bf16_round(z_q)),
+                                    synth.bf16_round(z_p), synth.bf16_round(z_q))):
+        pl, ql = oracle.probs_from(zp, "logit"), oracle.probs_from(zq, "logit")
+        qp = torch.empty((B, w.N), dtype=torch.float32, device="cuda")
+        o = rdk.rdk_redistribute_verify(ki, rdk.LINEAR_TAYLOR, zp_dev, zq_dev, 6, 3, 4, "logit", "logit", q_prime=qp)
+        ref_qp = oracle.redistribute_batch("taylor", ql, kept, w.N, p=pl)
+        assert_close(qp.cpu().numpy(), ref_qp, what="Eq. 3, wide logits")
+        ref = oracle.verify_batch(pl, ref_qp, 6, 3, gamma=4)
+        check_verify_outputs(o, ref, pl, ref_qp, 6, 3, 4, "logit", min_exact=0.75)
+
+
 # --------------------------------------------------------------------------------------------- fused entry point
 @pytest.mark.parametrize("case", ["tiny", "ragged"])
 @pytest.mark.parametrize("mode", ["sparse", "taylor"])
