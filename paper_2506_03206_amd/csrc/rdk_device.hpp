@@ -148,28 +148,35 @@ __device__ __forceinline__ float4 load4(const void *row, int64_t i, int64_t len,
 }
 
 // The same without any check: the caller knows the four elements are in range and the address is aligned.
-template <int KIND>
+// STREAM marks the load non-temporal: for data that is read once and should not displace what the caches hold.
+template <int KIND, bool STREAM = false>
 __device__ __forceinline__ float4 load4_full(const void *row, int64_t i)
 {
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
     if (KIND == RDK_LOGIT_BF16) {
-        const uint2 raw = *(const uint2 *)((const uint16_t *)row + i);
+        const u32x2_t *src = (const u32x2_t *)((const uint16_t *)row + i);
+        const u32x2_t raw = STREAM ? __builtin_nontemporal_load(src) : *src;
         return make_float4(__uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xFFFF0000u), __uint_as_float(raw.y << 16),
                            __uint_as_float(raw.y & 0xFFFF0000u));
     }
-    return *(const float4 *)((const float *)row + i);
+    const f32x4_t *src = (const f32x4_t *)((const float *)row + i);
+    const f32x4_t v = STREAM ? __builtin_nontemporal_load(src) : *src;
+    return make_float4(v.x, v.y, v.z, v.w);
 }
 
 // The 16 elements a lane holds of one chunk of kChunk ids (ids base + i*256 + lane*4 .. +3, i = 0..3).  A chunk that
-// lies wholly inside the row of a vectorisable input is read by four plain loads behind ONE wavefront-uniform
+// lies wholly inside the row of a vectorisable input is read by four loads behind ONE wavefront-uniform
 // branch; per-load range checks cost a dozen scalar and exec-mask instructions each and made the streaming
-// kernels issue-bound.
-template <int KIND>
+// kernels issue-bound.  The loads are non-temporal unless STREAM is false: every user reads its rows once per
+// launch, and batches are larger than the caches.
+template <int KIND, bool STREAM = true>
 __device__ __forceinline__ void load_chunk(const void *row, int64_t base, int64_t len, bool vec, float fill, float4 (&v)[4])
 {
     const int64_t first = base + lane_id() * 4;
     if (vec && base + kChunk <= len) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = load4_full<KIND>(row, first + i * 256);
+        for (int i = 0; i < 4; ++i) v[i] = load4_full<KIND, STREAM>(row, first + i * 256);
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = load4<KIND>(row, first + i * 256, len, vec, fill);

@@ -287,8 +287,13 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
 #pragma unroll
         for (int rr = 0; rr < kRowsPerWave; ++rr) {
             const int64_t b = (int64_t)pb * kPosBlock + wid * kRowsPerWave + rr;
-            praw[rr] = b < a.B ? load4<PKIND>(row_ptr<PKIND>(f.p, f.ldp, b), jl, a.N, f.vec_p, pfill)
-                               : make_float4(pfill, pfill, pfill, pfill);
+            // streamed past the caches' replacement order: the L2 of this XCD should keep the drafter slab instead
+            if (b >= a.B)
+                praw[rr] = make_float4(pfill, pfill, pfill, pfill);
+            else if (f.vec_p && jl + 3 < a.N)
+                praw[rr] = load4_full<PKIND, true>(row_ptr<PKIND>(f.p, f.ldp, b), jl);
+            else
+                praw[rr] = load4<PKIND>(row_ptr<PKIND>(f.p, f.ldp, b), jl, a.N, f.vec_p, pfill);
         }
     }
     sparse_tile(a, pb, j0, stage);
