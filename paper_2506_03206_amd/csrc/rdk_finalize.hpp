@@ -112,12 +112,30 @@ __device__ __forceinline__ int locate_block(const float *part, int nblk, int per
 
 // The same on partials that the lanes already hold in registers (at most kRegBlocks per lane): saves the
 // dependent re-read.  v[t] = partial of block lane * per_lane + t (0 beyond nblk); R = blocks a lane can hold.
+// A lane's blocks are consecutive in memory, so the lanes of one load are per_lane words apart and every load
+// instruction touches up to 64 cache lines.  When the row, the blocks per lane and the block count all are multiples
+// of four words, groups of four blocks are read by one unconditional 16-byte load each (a group is then wholly inside
+// or wholly outside the row; the address of an outside group is clamped and its values dropped): a quarter of the
+// line requests and no branch around any load.
 template <int R>
 __device__ __forceinline__ void load_partials(const float *part, int nblk, int per_lane, float (&v)[R])
 {
+    static_assert(R % 4 == 0, "a lane holds whole groups of four block sums");
     const int c0 = lane_id() * per_lane;
+    if (((uintptr_t)part & 15) == 0 && per_lane % 4 == 0 && nblk % 4 == 0 && nblk >= 4) {   // the same for all lanes
 #pragma unroll
-    for (int t = 0; t < R; ++t) v[t] = (t < per_lane && c0 + t < nblk) ? part[c0 + t] : 0.f;
+        for (int t = 0; t < R; t += 4) {
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < per_lane) {
+                const float4 y = *(const float4 *)(part + min(c0 + t, nblk - 4));
+                if (c0 + t < nblk) x = y;
+            }
+            v[t] = x.x; v[t + 1] = x.y; v[t + 2] = x.z; v[t + 3] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < R; ++t) v[t] = (t < per_lane && c0 + t < nblk) ? part[c0 + t] : 0.f;
+    }
 }
 
 template <int R>
@@ -220,7 +238,7 @@ __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) vo
             inv = 1.0f / rs.s;
         }
         const float pfill = KIND == RDK_PROB_F32 ? 0.f : -INFINITY;
-        const int per_lane = (a.nblk + kWave - 1) / kWave;
+        const int per_lane = ((a.nblk + kWave - 1) / kWave + 3) & ~3;   // blocks per lane, in whole groups of four
         const float *pq = a.part_q + row * a.nblk;
         const float *prr = a.part_r + row * a.nblk;
         const float *pa = a.part_a + row * a.nblk;
@@ -382,7 +400,7 @@ __global__ __launch_bounds__(kWave) void draft_finalize_kernel(DraftArgs a, QP q
     constexpr int kRegBlocks = 32;
     const int64_t row = blockIdx.x;
     const int lane = lane_id();
-    const int per_lane = (a.nblk + kWave - 1) / kWave;
+    const int per_lane = ((a.nblk + kWave - 1) / kWave + 3) & ~3;   // blocks per lane, in whole groups of four
     const float *pq = a.part_q + row * a.nblk;
     const bool in_regs = per_lane <= kRegBlocks;
     float vq[kRegBlocks];
