@@ -84,7 +84,9 @@ __device__ __forceinline__ void stage_chunk(float *lds, const void *qr, bool vec
 //   Bs += p_j / (N + p_j)                                    over all ids j.
 // Then theta = Tn / Zq and sum_j pt_j = An / Zq + theta * Bs, because
 //   pt_j = N q'_j / (N + p_j) + theta p_j / (N + p_j)  with q'_j = q^_s / Zq on kept ids, 0 elsewhere.
-template <int PK, int QK>
+// KEEP_P: the target rows are loaded as data that will be used again (the fused call: the second pass is their last
+// reader and a batch fits the memory-side cache); otherwise they are streamed like every other single-use row.
+template <int PK, int QK, bool KEEP_P>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) void taylor_stats_kernel(
     const void *p, int64_t ldp, const void *q, int64_t ldq,
                                                                 const int32_t *kept, const int32_t *chunk_lo, int N, int n,
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) v
     for (; c < c_end; c += kWaves) {
         const int base = c * kChunk;
         float4 pv[4], qd[4];
-        load_chunk<PK>(pr, base, N, vec_p, pfill, pv);
+        load_chunk<PK, !KEEP_P>(pr, base, N, vec_p, pfill, pv);
         const int lo_now = lo, hi_now = hi;
         if (c + kWaves < c_end) {
             lo = chunk_lo[c + kWaves];
@@ -387,9 +389,14 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     a.vec_q = rows_vectorisable(q.ptr, q.ld, q.kind);
     a.w = w;
     const bool vec_o = out ? rows_vectorisable(out, ldo, RDK_PROB_F32) : false;
-    {
-        RDK_TIMED_LAUNCH("taylor_stats_kernel", (taylor_stats_kernel<PK, QK>), dim3((unsigned)B * w.t_splits), dim3(kThreads),
-                         0, st, p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p, a.vec_q, w);
+    if (c) {
+        RDK_TIMED_LAUNCH("taylor_stats_kernel", (taylor_stats_kernel<PK, QK, true>), dim3((unsigned)B * w.t_splits),
+                         dim3(kThreads), 0, st, p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p,
+                         a.vec_q, w);
+    } else {
+        RDK_TIMED_LAUNCH("taylor_stats_kernel", (taylor_stats_kernel<PK, QK, false>), dim3((unsigned)B * w.t_splits),
+                         dim3(kThreads), 0, st, p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p,
+                         a.vec_q, w);
     }
     RDK_LAUNCH_CHECK("taylor_stats_kernel");
     const dim3 grid((unsigned)B * w.t_splits);
