@@ -1,6 +1,7 @@
 // Exact redistribution (Alg. 1, step 2):  P'[b, j] = sum_s Q'[b, s] M[s, j]  with a dense kernel M.
-//   fp32 kernel:  fp32 matrix cores (v_mfma_f32_32x32x2_f32), M read straight from its row-major rows,
-//                 split over the kept slots, fixed-order reduction.
+//   fp32 kernel:  both operands split into three bf16 parts each, six part products per term on the bf16 matrix
+//                 cores (v_mfma_f32_32x32x16_bf16) with fp32 accumulation; M read straight from its row-major
+//                 rows, split over the kept slots, fixed-order reduction.
 //   bf16 kernel:  both operands rounded to bf16, fp32 accumulation on the matrix cores
 //                 (v_mfma_f32_32x32x16_bf16), rows rescaled so that they sum to one.
 // Step 1 (Eq. 1) is folded in: rows of Q' are the drafter rows divided by their sums.
@@ -11,60 +12,88 @@ namespace rdk {
 namespace {
 
 // ------------------------------------------------------------------------------------------------ fp32
-// At 64 positions the product needs 2 n N flop against 4 n N bytes of M: 32 flop per byte, more than the fp32
-// vector or matrix units deliver per HBM byte (157 TFLOP/s : 8 TB/s = 20), so this path is bound by the fp32 MFMA
-// rate, not by HBM.  The 32x32x2 MFMA takes ONE value per lane and operand: lane l supplies A[row l % 32][k = l / 32]
-// and B[k = l / 32][col l % 32].  Four MFMAs e = 0..3 share one 16-byte load of M per lane by giving column c of
-// MFMA e the target id j0 + 4 c + e: lane (c, g) then needs M[s + g][j0 + 4c .. + 3], which is contiguous in the
-// row-major M -- no packing of M, no LDS.  The results of the four MFMAs of a lane are again four consecutive ids.
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kRowGroup = 64;    // positions per wavefront tile: two 32-row MFMA blocks
 constexpr int kColSet = 128;     // target ids per wavefront tile
-constexpr int kSlotGroup = 8;    // kept slots per A record: four MFMA steps of two slots
-constexpr int kGroupsUnroll = 3; // slot groups per unrolled loop body (depth of the load ring)
 
-// A records: for row block rb (32 positions) and slot group kq one 1 KB record; lane l = 32 g + r holds the four
-// unnormalised drafter weights of position 32 rb + r at slots 8 kq + 2 t + g, t = 0..3.  Zero beyond B and n.
+// At 64 positions the product needs 2 n N flop against 4 n N bytes of M: 32 flop per byte, more than the fp32 matrix
+// unit delivers per HBM byte (157 TFLOP/s : 8 TB/s = 20).  The bf16 matrix instruction is sixteen times as fast, and
+// an fp32 number is the exact sum of three bf16 numbers (its leading, middle and trailing eight significant bits), so
+// the product of two fp32 numbers is taken from the six largest products of their parts, all accumulated in fp32 by
+// the MFMA:
+//   x y = xh yh + (xh ym + xm yh) + (xh yl + xl yh + xm ym) + terms below 2^-24 |x y|.
+// Every part product is exact in fp32, so the result carries the rounding of an fp32 dot product.  With six bf16
+// MFMAs in place of sixteen fp32 ones per sixteen slots the path is bound by reading M, not by the matrix rate.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kSplitStep = 16;   // kept slots per bf16 MFMA
+constexpr int kSplitRing = 3;     // slot blocks in the load ring (all but one ahead of the MFMAs; deeper rings gain nothing)
+
+// Upper halves of h, m, l hold the three bf16 parts of x (x = h + m + l exactly, for normal numbers).
+__device__ __forceinline__ void split3(float x, uint32_t &h, uint32_t &m, uint32_t &l)
+{
+    h = __float_as_uint(x) & 0xFFFF0000u;
+    const float r = x - __uint_as_float(h);      // exact: at most sixteen significant bits are left
+    m = __float_as_uint(r) & 0xFFFF0000u;
+    l = __float_as_uint(r - __uint_as_float(m)); // exact, at most eight significant bits: already a bf16 number
+}
+
+// two bf16 numbers given in the upper halves of a and b, packed as (a, b) = (low half, high half)
+__device__ __forceinline__ uint32_t pack_upper(uint32_t a, uint32_t b) { return (a >> 16) | (b & 0xFFFF0000u); }
+
+// A records of this form: for row block rb (32 positions) and slot block kb (16 slots) three consecutive 1 KB
+// records, part p = 0 (leading), 1, 2; lane l = 32 g + r holds part p of the unnormalised drafter weights of
+// position 32 rb + r at slots 16 kb + 8 g + e, e = 0..7 -- the A operand of one 32x32x16 MFMA.  Zero beyond B and n.
 template <int QK>
-__global__ void prep_a_f32_kernel(const void *q, int64_t ldq, const SoftStat *qstat, int n, int B, int KQ, int64_t records,
-                                  float *Ap)
+__global__ void prep_a_split_kernel(const void *q, int64_t ldq, const SoftStat *qstat, int n, int B, int KB, int64_t records,
+                                    uint16_t *Ap)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= records * kWave) return;
     const int l = (int)(idx % kWave);
     const int64_t rec = idx / kWave;
-    const int kq = (int)(rec % KQ);
-    const int b = (int)(rec / KQ) * 32 + l % 32, g = l / 32;
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    const int kb = (int)(rec % KB);
+    const int b = (int)(rec / KB) * 32 + l % 32, g = l / 32;
+    uint32_t h[8], m[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = m[e] = lo[e] = 0u;
     if (b < B) {
         const void *qr = row_ptr<QK>(q, ldq, b);
         const float qm = QK == RDK_PROB_F32 ? 0.f : qstat[b].m;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int s = kq * kSlotGroup + 2 * t + g;
-            if (s < n) v[t] = to_weight<QK>(load1<QK>(qr, s), qm, 1.f);
+        for (int e = 0; e < 8; ++e) {
+            const int s = kb * kSplitStep + g * 8 + e;
+            if (s < n) split3(to_weight<QK>(load1<QK>(qr, s), qm, 1.f), h[e], m[e], lo[e]);
         }
     }
-    *(float4 *)(Ap + idx * 4) = make_float4(v[0], v[1], v[2], v[3]);
+    uint4 *dst = (uint4 *)(Ap + ((rec * 3) * kWave + l) * 8);
+    dst[0] = make_uint4(pack_upper(h[0], h[1]), pack_upper(h[2], h[3]), pack_upper(h[4], h[5]), pack_upper(h[6], h[7]));
+    dst[kWave] = make_uint4(pack_upper(m[0], m[1]), pack_upper(m[2], m[3]), pack_upper(m[4], m[5]), pack_upper(m[6], m[7]));
+    dst[2 * kWave] = make_uint4(pack_upper(lo[0], lo[1]), pack_upper(lo[2], lo[3]), pack_upper(lo[4], lo[5]), pack_upper(lo[6], lo[7]));
 }
 
-// One wavefront per (128 target ids, 64 positions, one split of the slot groups).  Loads run two slot groups
-// ahead of the MFMAs through a ring of three register sets; the split length is a multiple of three groups (the
-// A records are zero beyond n, and rows of M are clamped to the last one), so the loop body is straight-line code.
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void exact_f32_mfma_kernel(
-    const float *Ap, const float *M, int64_t ldm, int n, int N, int B,
-                                                               int KQ, int groups_per_split, const SoftStat *qstat, float *dst,
-                                                               int64_t ldd, int64_t split_stride, bool scale_here, bool vec_d)
+// One wavefront per (128 target ids, 64 positions, one split of the slot blocks), one wavefront per SIMD.  The B
+// operand of the 32x32x16 MFMA wants from lane l = 32 g + c the eight slots 8 g .. 8 g + 7 of column c.  Column c of
+// MFMA e (e = 0..3) is given the target id j0 + 4 c + e, so the lane reads M[s][j0 + 4c .. + 3] for its eight slots
+// s = 16 kb + 8 g + i with eight 16-byte loads of the row-major M -- no packing of M, no LDS -- splits the 32 values
+// in registers and feeds four MFMA columns; the four results of a lane are again four consecutive ids.  Loads run two slot blocks ahead through a ring of three register sets; the split
+// length is a multiple of three blocks (A is zero beyond n, rows of M are clamped to the last one).
+constexpr int kSplitWaves = 4;   // wavefronts per workgroup: neighbouring id tiles, walked in step
+
+__global__ __launch_bounds__(kSplitWaves * kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void exact_f32_split_kernel(
+    const uint16_t *Ap, const float *M, int64_t ldm, int n, int N, int B, int KB, int blocks_per_split, const SoftStat *qstat,
+    float *dst, int64_t ldd, int64_t split_stride, bool scale_here, bool vec_d)
 {
     const int lane = lane_id(), c = lane % 32, g = lane / 32;
-    const int j0 = blockIdx.x * kColSet, col = j0 + 4 * c;
+    const int tile = blockIdx.x * kSplitWaves + threadIdx.x / kWave;
+    if (tile * kColSet >= N) return;   // a whole wavefront; the kernel has no barrier
+    const int j0 = tile * kColSet, col = j0 + 4 * c;
     const int rg = blockIdx.y;
-    const int kq0 = blockIdx.z * groups_per_split, kq_last = kq0 + groups_per_split - 1;
+    const int kb0 = blockIdx.z * blocks_per_split, kb_last = kb0 + blocks_per_split - 1;
     const bool full = col + 3 < N;
-    // Rows of M are padded to a multiple of four floats and 16-byte aligned, so a lane whose first id is in range
-    // may always read all four; lanes beyond N read column 0 instead (never stored): the loads need no branch.
-    const int lcol = col < N ? col : 0;
+    const int lcol = col < N ? col : 0;   // lanes beyond N read column 0 (never stored): no branch around the loads
     f32x16 acc[2][4];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
@@ -72,45 +101,69 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
         for (int e = 0; e < 4; ++e)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[rb][e][v] = 0.f;
-    const float4 *a_rec[2];
+    const bf16x8 *a_rec[2];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) a_rec[rb] = (const float4 *)Ap + ((int64_t)(rg * 2 + rb) * KQ) * kWave + lane;
+    for (int rb = 0; rb < 2; ++rb) a_rec[rb] = (const bf16x8 *)Ap + ((int64_t)(rg * 2 + rb) * KB) * 3 * kWave + lane;
 
-    float4 a_ring[kGroupsUnroll][2], b_ring[kGroupsUnroll][4];
-    // everything of slot group kq (clamped to the split) into ring entry SLOT
-#define RDK_LOAD_GROUP(SLOT, KQI)                                                                                    \
+    bf16x8 a_ring[kSplitRing][2][3];
+    float4 b_ring[kSplitRing][8];
+#define RDK_LOAD_BLOCK(SLOT, KBI)                                                                                    \
     {                                                                                                                \
-        const int kq_ = min((KQI), kq_last);                                                                         \
-        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb) a_ring[SLOT][rb] = a_rec[rb][(int64_t)kq_ * kWave];        \
-        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                              \
-            const int s_ = min(kq_ * kSlotGroup + 2 * t + g, n - 1);                                                 \
-            b_ring[SLOT][t] = *(const float4 *)(M + (int64_t)s_ * ldm + lcol);                                       \
+        const int kb_ = min((KBI), kb_last);                                                                         \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                             \
+            _Pragma("unroll") for (int pt = 0; pt < 3; ++pt)                                                         \
+                a_ring[SLOT][rb][pt] = a_rec[rb][((int64_t)kb_ * 3 + pt) * kWave];                                   \
+        _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                              \
+            const int s_ = min(kb_ * kSplitStep + 8 * g + i, n - 1);                                                 \
+            b_ring[SLOT][i] = *(const float4 *)(M + (int64_t)s_ * ldm + lcol);                                       \
         }                                                                                                            \
         __builtin_amdgcn_sched_barrier(0);                                                                           \
     }
-#define RDK_MFMA_GROUP(SLOT)                                                                                         \
+    // the four MFMA columns of a block, two at a time: split the eight values of each, then the six part products
+    // smallest first, alternating between the four accumulators involved
+#define RDK_MFMA_BLOCK(SLOT)                                                                                         \
     {                                                                                                                \
-        _Pragma("unroll") for (int t = 0; t < 4; ++t) {                                                              \
-            const float av_[2] = {t == 0 ? a_ring[SLOT][0].x : t == 1 ? a_ring[SLOT][0].y : t == 2 ? a_ring[SLOT][0].z : a_ring[SLOT][0].w, \
-                                  t == 0 ? a_ring[SLOT][1].x : t == 1 ? a_ring[SLOT][1].y : t == 2 ? a_ring[SLOT][1].z : a_ring[SLOT][1].w}; \
-            const float bv_[4] = {b_ring[SLOT][t].x, b_ring[SLOT][t].y, b_ring[SLOT][t].z, b_ring[SLOT][t].w};       \
-            _Pragma("unroll") for (int e = 0; e < 4; ++e)                                                            \
-                _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                     \
-                    acc[rb][e] = __builtin_amdgcn_mfma_f32_32x32x2f32(av_[rb], bv_[e], acc[rb][e], 0, 0, 0);         \
+        _Pragma("unroll") for (int ep = 0; ep < 4; ep += 2) {                                                        \
+            bf16x8 bh_[2], bm_[2], bl_[2];                                                                           \
+            _Pragma("unroll") for (int ee = 0; ee < 2; ++ee) {                                                       \
+                uint32_t h_[8], m_[8], l_[8];                                                                        \
+                _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                      \
+                    const float4 bv_ = b_ring[SLOT][i];                                                              \
+                    const float x_ = (ep + ee) == 0 ? bv_.x : (ep + ee) == 1 ? bv_.y : (ep + ee) == 2 ? bv_.z : bv_.w; \
+                    split3(x_, h_[i], m_[i], l_[i]);                                                                 \
+                }                                                                                                    \
+                const u32x4 hv_ = {pack_upper(h_[0], h_[1]), pack_upper(h_[2], h_[3]), pack_upper(h_[4], h_[5]), pack_upper(h_[6], h_[7])}; \
+                const u32x4 mv_ = {pack_upper(m_[0], m_[1]), pack_upper(m_[2], m_[3]), pack_upper(m_[4], m_[5]), pack_upper(m_[6], m_[7])}; \
+                const u32x4 lv_ = {pack_upper(l_[0], l_[1]), pack_upper(l_[2], l_[3]), pack_upper(l_[4], l_[5]), pack_upper(l_[6], l_[7])}; \
+                bh_[ee] = __builtin_bit_cast(bf16x8, hv_);                                                           \
+                bm_[ee] = __builtin_bit_cast(bf16x8, mv_);                                                           \
+                bl_[ee] = __builtin_bit_cast(bf16x8, lv_);                                                           \
+            }                                                                                                        \
+            RDK_PART_PRODUCT(SLOT, ep, 1, bm_)                                                                       \
+            RDK_PART_PRODUCT(SLOT, ep, 2, bh_)                                                                       \
+            RDK_PART_PRODUCT(SLOT, ep, 0, bl_)                                                                       \
+            RDK_PART_PRODUCT(SLOT, ep, 1, bh_)                                                                       \
+            RDK_PART_PRODUCT(SLOT, ep, 0, bm_)                                                                       \
+            RDK_PART_PRODUCT(SLOT, ep, 0, bh_)                                                                       \
         }                                                                                                            \
     }
-    RDK_LOAD_GROUP(0, kq0)
-    RDK_LOAD_GROUP(1, kq0 + 1)
-    for (int kq = kq0; kq <= kq_last; kq += kGroupsUnroll) {
-        RDK_LOAD_GROUP(2, kq + 2)
-        RDK_MFMA_GROUP(0)
-        RDK_LOAD_GROUP(0, kq + 3)
-        RDK_MFMA_GROUP(1)
-        RDK_LOAD_GROUP(1, kq + 4)
-        RDK_MFMA_GROUP(2)
+#define RDK_PART_PRODUCT(SLOT, EP, APART, BPART)                                                                     \
+    _Pragma("unroll") for (int ee = 0; ee < 2; ++ee)                                                                 \
+        _Pragma("unroll") for (int rb = 0; rb < 2; ++rb)                                                             \
+            acc[rb][(EP) + ee] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_ring[SLOT][rb][APART], BPART[ee],         \
+                                                                         acc[rb][(EP) + ee], 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < kSplitRing - 1; ++t) RDK_LOAD_BLOCK(t, kb0 + t)
+    for (int kb = kb0; kb <= kb_last; kb += kSplitRing) {
+#pragma unroll
+        for (int t = 0; t < kSplitRing; ++t) {   // ring entries are compile-time constants after unrolling
+            RDK_LOAD_BLOCK((t + kSplitRing - 1) % kSplitRing, kb + t + kSplitRing - 1)
+            RDK_MFMA_BLOCK(t)
+        }
     }
-#undef RDK_LOAD_GROUP
-#undef RDK_MFMA_GROUP
+#undef RDK_LOAD_BLOCK
+#undef RDK_MFMA_BLOCK
+#undef RDK_PART_PRODUCT
     // D layout of a 32x32 tile: lane l holds column l % 32 and rows 8 * (v / 4) + 4 * (l / 32) + v % 4, v = 0..15
     float *base = dst + (int64_t)blockIdx.z * split_stride;
 #pragma unroll
@@ -146,7 +199,6 @@ __global__ void exact_reduce_kernel(const float *part, int64_t ldd, int64_t spli
 }
 
 // ------------------------------------------------------------------------------------------------ bf16
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kKStep = 16;          // kept slots per MFMA (32x32x16)
 constexpr int kColBlock = 32;       // target ids per MFMA tile
@@ -370,27 +422,26 @@ inline void bf16_shape(int B, int &W, int &RB)
 
 struct ExactWs {
     SoftStat *qstat;   // [B]
-    float *part;       // fp32 path: [splits, B, N_ld]
-    float *Af;         // fp32 path: A records [B_pad / 32, splits * groups, 64, 4]
+    float *part;       // fp32 path: [splits, B, N_ld]  (after the A records of that path)
     uint16_t *A;       // bf16 path: [B_pad, n_pad]
     float *out_scale;  // bf16 path: [B]
 };
 
-// Split of the slot groups of the fp32 path: as many wavefronts as fit the chip at two per SIMD (2048) but no more,
+// Split of the slot blocks of the fp32 path: as many wavefronts as the chip holds at one per SIMD (1024) but no more,
 // so that they all run side by side (a few left over for a second round would double the time); splits of a whole
-// number of unrolled loop bodies.  groups = slot groups per split (a multiple of kGroupsUnroll).
-int f32_splits(const KernelHandle &h, int B, int *groups)
+// number of ring turns.  blocks = slot blocks per split.
+int split_splits(const KernelHandle &h, int B, int *blocks)
 {
     const int tiles = ((h.N + kColSet - 1) / kColSet) * ((B + kRowGroup - 1) / kRowGroup);
-    const int kq_total = (h.n + kSlotGroup - 1) / kSlotGroup;
-    int want = 2048 / tiles;
-    const int maxs = (kq_total + 4 * kGroupsUnroll - 1) / (4 * kGroupsUnroll);    // at least 96 slots per split
+    const int kb_total = (h.n + kSplitStep - 1) / kSplitStep;
+    int want = 1024 / tiles;
+    const int maxs = (kb_total + 2 * kSplitRing - 1) / (2 * kSplitRing);    // at least 96 slots per split
     if (want > maxs) want = maxs;
     if (want > 64) want = 64;
     if (want < 1) want = 1;
-    const int per = ((kq_total + want - 1) / want + kGroupsUnroll - 1) / kGroupsUnroll * kGroupsUnroll;
-    const int splits = (kq_total + per - 1) / per;
-    if (groups) *groups = per;
+    const int per = ((kb_total + want - 1) / want + kSplitRing - 1) / kSplitRing * kSplitRing;
+    const int splits = (kb_total + per - 1) / per;
+    if (blocks) *blocks = per;
     return splits;
 }
 
@@ -403,29 +454,30 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
     rdk_status_t rc = launch_row_stats<QK>(q, h.n, B, 1, w.qstat, st);
     if (rc != RDK_OK) return rc;
     if (h.format == RDK_DENSE_F32) {
-        int groups;
-        const int splits = f32_splits(h, B, &groups);
-        const int KQ = splits * groups;
+        int blocks;
+        const int splits = split_splits(h, B, &blocks);
+        const int KB = splits * blocks;
         const int row_groups = (B + kRowGroup - 1) / kRowGroup;
-        const int64_t records = (int64_t)row_groups * 2 * KQ;
-        w.Af = (float *)p; p += align_up((size_t)records * kWave * 4 * sizeof(float), 256);
+        const int64_t records = (int64_t)row_groups * 2 * KB;   // of three parts each
+        uint16_t *Ap = (uint16_t *)p; p += align_up((size_t)records * 3 * kWave * 8 * sizeof(uint16_t), 256);
         w.part = (float *)p;
         const int64_t ldd = (h.N + 3) / 4 * 4;
         {
-            RDK_TIMED_LAUNCH("prep_a_f32_kernel", (prep_a_f32_kernel<QK>), dim3((unsigned)((records * kWave + 255) / 256)),
-                             dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.n, B, KQ, records, w.Af);
+            RDK_TIMED_LAUNCH("prep_a_split_kernel", (prep_a_split_kernel<QK>), dim3((unsigned)((records * kWave + 255) / 256)),
+                             dim3(256), 0, st, q.ptr, q.ld, w.qstat, h.n, B, KB, records, Ap);
         }
-        RDK_LAUNCH_CHECK("prep_a_f32_kernel");
-        dim3 grid((h.N + kColSet - 1) / kColSet, row_groups, splits);
+        RDK_LAUNCH_CHECK("prep_a_split_kernel");
+        const int tiles = (h.N + kColSet - 1) / kColSet;
+        dim3 grid((tiles + kSplitWaves - 1) / kSplitWaves, row_groups, splits);
         if (splits == 1) {
             const bool vec_d = rows_vectorisable(out, ldo, RDK_PROB_F32);
-            RDK_TIMED_LAUNCH("exact_f32_mfma_kernel", exact_f32_mfma_kernel, grid, dim3(kWave), 0, st, w.Af, h.dense, h.ldm,
-                             h.n, h.N, B, KQ, groups, w.qstat, out, ldo, (int64_t)0, true, vec_d);
-            RDK_LAUNCH_CHECK("exact_f32_mfma_kernel");
+            RDK_TIMED_LAUNCH("exact_f32_split_kernel", exact_f32_split_kernel, grid, dim3(kSplitWaves * kWave), 0, st, Ap, h.dense,
+                             h.ldm, h.n, h.N, B, KB, blocks, w.qstat, out, ldo, (int64_t)0, true, vec_d);
+            RDK_LAUNCH_CHECK("exact_f32_split_kernel");
         } else {
-            RDK_TIMED_LAUNCH("exact_f32_mfma_kernel", exact_f32_mfma_kernel, grid, dim3(kWave), 0, st, w.Af, h.dense, h.ldm,
-                             h.n, h.N, B, KQ, groups, w.qstat, w.part, ldd, (int64_t)B * ldd, false, true);
-            RDK_LAUNCH_CHECK("exact_f32_mfma_kernel");
+            RDK_TIMED_LAUNCH("exact_f32_split_kernel", exact_f32_split_kernel, grid, dim3(kSplitWaves * kWave), 0, st, Ap, h.dense,
+                             h.ldm, h.n, h.N, B, KB, blocks, w.qstat, w.part, ldd, (int64_t)B * ldd, false, true);
+            RDK_LAUNCH_CHECK("exact_f32_split_kernel");
             RDK_TIMED_LAUNCH("exact_reduce_kernel", exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part,
                              ldd, (int64_t)B * ldd, splits, w.qstat, h.N, out, ldo);
             RDK_LAUNCH_CHECK("exact_reduce_kernel");
@@ -477,10 +529,10 @@ size_t exact_workspace_bytes(const KernelHandle &h, int32_t B)
 {
     size_t bytes = align_up((size_t)B * sizeof(SoftStat), 256);
     if (h.format == RDK_DENSE_F32) {
-        int groups;
-        const int splits = f32_splits(h, B, &groups);
-        const size_t records = (size_t)((B + kRowGroup - 1) / kRowGroup) * 2 * splits * groups;
-        bytes += align_up(records * kWave * 4 * sizeof(float), 256);
+        int blocks;
+        const int splits = split_splits(h, B, &blocks);
+        const size_t records = (size_t)((B + kRowGroup - 1) / kRowGroup) * 2 * splits * blocks;
+        bytes += align_up(records * 3 * kWave * 8 * sizeof(uint16_t), 256);
         if (splits > 1) bytes += align_up((size_t)splits * B * ((h.N + 3) / 4 * 4) * sizeof(float), 256);
     } else if (h.format == RDK_DENSE_BF16) {
         int W, RB;

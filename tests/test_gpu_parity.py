@@ -207,6 +207,33 @@ def test_exact_fp32(rdk, tiny, ragged, case, q_kind):
     assert_close(out, ref, what="exact fp32")
 
 
+def test_exact_fp32_keeps_every_part(rdk, ragged):
+    """The fp32 product runs on three bf16 parts per operand.  Two cases in which a dropped or mispaired part shows
+    at once: a one-hot drafter row must return the kernel row bit for bit (the parts of an fp32 number add up to it
+    exactly), and a kernel that sends each slot to its own id must return the normalised drafter row to fp32
+    rounding (losing the trailing part of the drafter weights would cost 2^-16 of each value)."""
+    w = ragged["w"]
+    M32 = ragged["dense"].astype(np.float32)
+    kern = rdk.rdk_build_kernel(w.N, dev(ragged["kept_ids"]), rdk.DENSE_F32, dense_M=dev(M32))
+    slots = [0, 1, 7, 8, 15, 16, 255, 256, w.n - 2, w.n - 1] + list(range(20, 20 + 60))   # 70 rows: two row groups
+    q = np.zeros((len(slots), w.n), dtype=np.float32)
+    q[np.arange(len(slots)), slots] = 1.0
+    out = rdk.rdk_redistribute_exact(kern, dev(q)).cpu().numpy()
+    assert np.array_equal(out, M32[slots]), "one-hot rows must reproduce the kernel rows exactly"
+
+    P = np.zeros((w.n, w.N), dtype=np.float32)
+    P[np.arange(w.n), ragged["kept_ids"]] = 1.0
+    kern = rdk.rdk_build_kernel(w.N, dev(ragged["kept_ids"]), rdk.DENSE_F32, dense_M=dev(P))
+    rng = np.random.default_rng(11)
+    q = (rng.random((9, w.n)) * np.exp(rng.normal(0.0, 3.0, size=(9, w.n)))).astype(np.float32)   # full mantissas, wide range
+    out = rdk.rdk_redistribute_exact(kern, dev(q)).cpu().numpy()
+    for b in range(q.shape[0]):
+        ref = oracle.tli(q[b])
+        got = out[b, ragged["kept_ids"]].astype(np.float64)
+        assert np.max(np.abs(got - ref) / ref) < 5e-7, "row %d: %.3e" % (b, np.max(np.abs(got - ref) / ref))
+        assert np.count_nonzero(out[b]) == w.n
+
+
 @pytest.mark.parametrize("case", ["tiny", "ragged"])
 def test_exact_bf16(rdk, tiny, ragged, case):
     data = tiny if case == "tiny" else ragged
