@@ -31,7 +31,8 @@ MEASURED_TRAFFIC = {
     ("llama3", "sparse", "fused", "sparse_product_kernel"): 487.3e6,
     ("llama3", "taylor", "fused", "taylor_stats_kernel"): 165.3e6,
     ("llama3", "taylor", "fused", "taylor_write_kernel"): 165.5e6,
-    ("dense256k", "exact", "bf16", "exact_bf16_kernel"): 19170.1e6,
+    ("dense256k", "exact", "bf16", "exact_bf16_kernel"): 19165.5e6,
+    ("n32k", "exact", "f32", "exact_f32_split_kernel"): 1085.1e6,
 }
 
 
