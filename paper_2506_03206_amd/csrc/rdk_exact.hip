@@ -78,8 +78,10 @@ __global__ void prep_a_split_kernel(const void *q, int64_t ldq, const SoftStat *
 // operand of the 32x32x16 MFMA wants from lane l = 32 g + c the eight slots 8 g .. 8 g + 7 of column c.  Column c of
 // MFMA e (e = 0..3) is given the target id j0 + 4 c + e, so the lane reads M[s][j0 + 4c .. + 3] for its eight slots
 // s = 16 kb + 8 g + i with eight 16-byte loads of the row-major M -- no packing of M, no LDS -- splits the 32 values
-// in registers and feeds four MFMA columns; the four results of a lane are again four consecutive ids.  Loads run two slot blocks ahead through a ring of three register sets; the split
-// length is a multiple of three blocks (A is zero beyond n, rows of M are clamped to the last one).
+// in registers and feeds four MFMA columns; the four results of a lane are again four consecutive ids.  Loads run
+// two slot blocks ahead through a ring of three register sets; the split length is a multiple of three blocks (A is
+// zero beyond n, rows of M are clamped to the last one).  Tiles of 64 ids at two wavefronts per SIMD were slower
+// (0.26 ms against 0.22 ms): every wavefront reads all drafter records of its split.
 constexpr int kSplitWaves = 4;   // wavefronts per workgroup: neighbouring id tiles, walked in step
 
 __global__ __launch_bounds__(kSplitWaves * kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void exact_f32_split_kernel(
