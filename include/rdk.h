@@ -14,6 +14,9 @@
  *    `rdk_kernel_t**` are HOST pointers.
  *  - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*; NULL is the
  *    default stream).  Calls do not synchronise, except rdk_build_kernel with `validate != 0`.
+ *    The redistribution, verification and sampling calls consist of kernel launches on that stream
+ *    only (no copy, no memset, no allocation), so they may be recorded into a HIP graph and replayed;
+ *    the seed and the counter offset are then those given at capture time.
  *  - Calls that use distinct workspaces may run concurrently on distinct streams; two calls that
  *    share a workspace must be ordered by the caller.
  *  - Matrices are row-major with a leading dimension given in ELEMENTS (ld >= row length).

@@ -574,3 +574,46 @@ def test_fused_redistribute_verify(rdk, tiny, ragged, case, mode, kinds):
     o3 = rdk.rdk_redistribute_verify(kern, gmode, p_in, q_in, seed, offset, w.gamma, p_kind, q_kind, draft_ids=dev(drafts))
     ref3 = oracle.verify_batch(p64, ref_qp, seed, offset, sample_draft=False, draft_ids=drafts, gamma=w.gamma)
     check_verify_outputs(o3, ref3, p64, ref_qp, seed, offset, w.gamma, p_kind)
+
+
+# --------------------------------------------------------------------------------------------- HIP graph capture
+@pytest.mark.parametrize("mode", ["sparse", "taylor"])
+def test_fused_call_replays_from_a_hip_graph(rdk, ragged, mode):
+    """The fused call only enqueues kernels on the caller's stream (no allocation, no memset, no synchronisation),
+    so a serving loop can capture it once and replay it.  Three replays on three different batches, with eager work
+    and synchronisations between them, each compared with the eager call on the same inputs."""
+    data = ragged
+    w = data["w"]
+    idx, wt, sw = data["sparse"]
+    if mode == "sparse":
+        kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.SPARSE_TOPK, k=w.k,
+                                    sparse=(dev(idx), dev(wt.astype(np.float32)), dev(sw.astype(np.float32))))
+        gmode = rdk.LINEAR_SPARSE
+    else:
+        kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.IDENTITY)
+        gmode = rdk.LINEAR_TAYLOR
+    seed, offset = 99, 5
+    p_static, q_static = dev(data["p"]).clone(), dev(data["q_hat"]).clone()
+    captured = rdk.VerifyOutputs(w.B, w.N, w.gamma, p_static.device)
+    eager = rdk.VerifyOutputs(w.B, w.N, w.gamma, p_static.device)
+    # one eager call first: sizes the workspaces outside the capture
+    rdk.rdk_redistribute_verify(kern, gmode, p_static, q_static, seed, offset, w.gamma, outputs=captured)
+    rdk.rdk_redistribute_verify(kern, gmode, p_static, q_static, seed, offset, w.gamma, outputs=eager)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rdk.rdk_redistribute_verify(kern, gmode, p_static, q_static, seed, offset, w.gamma, outputs=captured)
+    rng = np.random.default_rng(5)
+    for rep in range(3):
+        perm = rng.permutation(w.B)
+        p_static.copy_(dev(data["p"][perm]))
+        q_static.copy_(dev(data["q_hat"][perm]))
+        for name in ("draft_ids", "resid_ids"):
+            getattr(captured, name).fill_(-7)
+        captured.alpha.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        rdk.rdk_redistribute_verify(kern, gmode, p_static, q_static, seed, offset, w.gamma, outputs=eager)
+        torch.cuda.synchronize()
+        for name in ("draft_ids", "accept", "alpha", "resid_mass", "resid_ids", "n_accepted", "out_tokens"):
+            assert torch.equal(getattr(captured, name), getattr(eager, name)), "replay %d: %s" % (rep, name)
