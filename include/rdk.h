@@ -212,7 +212,7 @@ rdk_status_t rdk_verify_sample(const rdk_verify_desc_t *desc, const void *p, rdk
  * 1024 ids (Eq. 3), so fp32 rounding, and with it an id that sits on a prefix-sum step, can differ
  * from the two-call path within the tolerance stated at rdk_verify_sample.  desc->N must equal the
  * kernel's N; draft_ids is required (in/out as in rdk_verify_sample).  RDK_LINEAR_SPARSE needs a
- * RDK_SPARSE_TOPK kernel with k > 0.
+ * RDK_SPARSE_TOPK kernel (k = 0 included: token-level intersection).
  */
 rdk_status_t rdk_redistribute_verify_workspace_bytes(const rdk_kernel_t *kernel, rdk_linear_mode_t mode,
                                                      const rdk_verify_desc_t *desc, size_t *bytes);
@@ -230,9 +230,9 @@ rdk_status_t rdk_redistribute_verify(const rdk_kernel_t *kernel, rdk_linear_mode
  *   draft_ids[b] = smallest j with prefix_j(q'_b) > u0 * sum_j q'_b(j),  u0 = word 0 of Philox(seed, offset + b)
  * -- the draw rdk_verify_sample and rdk_redistribute_verify make when sample_draft = 1, so verifying later with
  * sample_draft = 0 and these ids gives what the fused call gives.  q_draft (optional, [B]) receives q'_b(draft_ids[b]).
- *   RDK_SPARSE_TOPK kernel with k > 0: q' is summed per 64-id block as it is produced and only the block of the
+ *   RDK_SPARSE_TOPK kernel: q' is summed per 64-id block as it is produced and only the block of the
  *     crossing is re-computed; q_prime (optional, [B, ldo]) receives the rows if given.
- *   any other kernel (identity, k = 0, dense fp32 / bf16): the rows are produced by the matching redistribution
+ *   any other kernel (identity, dense fp32 / bf16): the rows are produced by the matching redistribution
  *     into q_prime, which is then required, and drawn from there.
  * draft_ids[b] = -1 (and q_draft[b] = 0) for a row without mass.  Workspace: rdk_sample_draft_workspace_bytes.
  * Errors as rdk_redistribute_linear.

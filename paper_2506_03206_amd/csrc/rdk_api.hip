@@ -391,7 +391,8 @@ rdk_status_t rdk_redistribute_linear(const rdk_kernel_t *kernel, rdk_linear_mode
     return launch_sparse(h, qi, B, q_prime, ldo, workspace, (hipStream_t)stream);
 }
 
-static bool sparse_product_kernel_of(const KernelHandle &h) { return h.format == RDK_SPARSE_TOPK && h.k > 0; }
+// k = 0 is stored as one padded row of zero weights per pruned id, so the same kernels serve it
+static bool sparse_product_kernel_of(const KernelHandle &h) { return h.format == RDK_SPARSE_TOPK; }
 
 rdk_status_t rdk_sample_draft_workspace_bytes(const rdk_kernel_t *kernel, int32_t B, size_t *bytes)
 {
@@ -487,7 +488,7 @@ rdk_status_t rdk_redistribute_verify_workspace_bytes(const rdk_kernel_t *kernel,
     const KernelHandle &h = kernel->h;
     if (desc->N != h.N) return RDK_ERR_SHAPE;
     if (mode == RDK_LINEAR_TAYLOR) *bytes = taylor_fused_workspace_bytes(h, desc->B) + 256;
-    else if (mode == RDK_LINEAR_SPARSE && h.format == RDK_SPARSE_TOPK && h.k > 0)
+    else if (mode == RDK_LINEAR_SPARSE && h.format == RDK_SPARSE_TOPK)
         *bytes = sparse_fused_workspace_bytes(h, desc->B) + 256;
     else return mode == RDK_LINEAR_SPARSE ? RDK_ERR_UNSUPPORTED : RDK_ERR_DTYPE;
     return RDK_OK;

@@ -617,3 +617,64 @@ def test_fused_call_replays_from_a_hip_graph(rdk, ragged, mode):
         torch.cuda.synchronize()
         for name in ("draft_ids", "accept", "alpha", "resid_mass", "resid_ids", "n_accepted", "out_tokens"):
             assert torch.equal(getattr(captured, name), getattr(eager, name)), "replay %d: %s" % (rep, name)
+
+
+# --------------------------------------------------------------------------------------------- degenerate shapes
+DEGENERATE = {
+    "one_row": dict(N=40, n=7, k=3, seqs=1, gamma=1, d=8),                # a single position, a vocabulary below one tile
+    "nothing_pruned": dict(N=300, n=300, k=4, seqs=2, gamma=2, d=8),      # n = N: the kernel is the identity
+    "one_kept": dict(N=129, n=1, k=1, seqs=1, gamma=3, d=8),              # the drafter knows a single token
+    "no_neighbours": dict(N=1000, n=100, k=0, seqs=5, gamma=1, d=8),      # top-0: the sparse form is TLI
+}
+
+
+@pytest.mark.parametrize("shape", sorted(DEGENERATE))
+def test_degenerate_shapes(rdk, shape):
+    """The smallest and the limiting shapes the method allows, through every redistribution form and the fused call."""
+    w = synth.scaled(synth.WORKLOADS["tiny"], name=shape, seed=7, **DEGENERATE[shape])
+    data = synth.make(w)
+    data["w"] = w
+    kept = dev(data["kept_ids"])
+    idx, wt, sw = oracle.build_sparse(data["E"], data["kept_ids"], w.tau, w.k)
+    wt32, sw32 = wt.astype(np.float32), sw.astype(np.float32)
+    M32 = oracle.build_dense(data["E"], data["kept_ids"], w.tau).astype(np.float32)
+    p64 = data["p"].astype(np.float64)
+    q, p = dev(data["q_hat"]), dev(data["p"])
+
+    ks = rdk.rdk_build_kernel(w.N, kept, rdk.SPARSE_TOPK, k=w.k, sparse=(dev(idx), dev(wt32), dev(sw32)))
+    ref_sparse = oracle.redistribute_batch("sparse", data["q_hat"], data["kept_ids"], w.N, sparse=(idx, wt32, sw32))
+    assert_close(rdk.rdk_redistribute_linear(ks, rdk.LINEAR_SPARSE, q).cpu().numpy(), ref_sparse, what="sparse q'")
+    if w.k > 0 and w.n < w.N:   # the device-built kernel of the same shape
+        kb = rdk.rdk_build_kernel(w.N, kept, rdk.SPARSE_TOPK, embeddings=dev(data["E"]), tau=w.tau, k=w.k)
+        b_idx, b_w, b_sw = [t.cpu().numpy() for t in rdk.rdk_kernel_get_sparse(kb)]
+        assert np.array_equal(b_idx, idx)
+        assert_close(b_w, wt, what="neighbour weights")
+        assert_close(b_sw, sw, what="diagonal weights")
+    if w.k == 0 or w.n == w.N:   # nothing but the diagonal: token-level intersection
+        ref_tli = oracle.redistribute_batch("exact", data["q_hat"], data["kept_ids"], w.N,
+                                            M=np.eye(w.N)[data["kept_ids"]])
+        assert_close(ref_sparse, ref_tli, what="oracle: sparse form without neighbours is TLI")
+
+    ki = rdk.rdk_build_kernel(w.N, kept, rdk.IDENTITY)
+    ref_taylor = oracle.redistribute_batch("taylor", data["q_hat"], data["kept_ids"], w.N, p=data["p"])
+    assert_close(rdk.rdk_redistribute_linear(ki, rdk.LINEAR_TAYLOR, q, p=p).cpu().numpy(), ref_taylor, what="Eq. 3 q'")
+
+    ref_exact = oracle.redistribute_batch("exact", data["q_hat"], data["kept_ids"], w.N, M=M32)
+    kd = rdk.rdk_build_kernel(w.N, kept, rdk.DENSE_F32, dense_M=dev(M32))
+    assert_close(rdk.rdk_redistribute_exact(kd, q).cpu().numpy(), ref_exact, what="exact fp32")
+    kh = rdk.rdk_build_kernel(w.N, kept, rdk.DENSE_BF16, dense_M=dev(M32))
+    assert_close(rdk.rdk_redistribute_exact(kh, q).cpu().numpy(), ref_exact, rtol=RTOL_BF16 * 4, atol=1e-6, what="exact bf16")
+
+    seed, offset = 31, 2
+    for kern, gmode, ref_qp in ((ks, rdk.LINEAR_SPARSE, ref_sparse), (ki, rdk.LINEAR_TAYLOR, ref_taylor)):
+        o = rdk.rdk_redistribute_verify(kern, gmode, p, q, seed, offset, w.gamma)
+        ref = oracle.verify_batch(p64, ref_qp, seed, offset, gamma=w.gamma)
+        check_verify_outputs(o, ref, p64, ref_qp, seed, offset, w.gamma, "prob", min_exact=0.0)   # ids: near-ties only
+    qp32 = ref_sparse.astype(np.float32)
+    o = rdk.rdk_verify_sample(p, dev(qp32), seed, offset, w.gamma)
+    ref = oracle.verify_batch(p64, qp32.astype(np.float64), seed, offset, gamma=w.gamma)
+    check_verify_outputs(o, ref, p64, qp32.astype(np.float64), seed, offset, w.gamma, "prob", min_exact=0.0)
+    ids, _ = rdk.rdk_sample_draft(ks, q, seed, offset)
+    u0 = np.array([oracle.uniforms(seed, offset + b)[0] for b in range(w.B)])
+    ref_ids = np.array([oracle.sample_cdf(ref_sparse[b], u0[b]) for b in range(w.B)])
+    check_sampled_ids(ref_sparse, u0, ids.cpu().numpy(), ref_ids, what="draft from q'")
