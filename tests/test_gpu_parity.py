@@ -678,3 +678,34 @@ def test_degenerate_shapes(rdk, shape):
     u0 = np.array([oracle.uniforms(seed, offset + b)[0] for b in range(w.B)])
     ref_ids = np.array([oracle.sample_cdf(ref_sparse[b], u0[b]) for b in range(w.B)])
     check_sampled_ids(ref_sparse, u0, ids.cpu().numpy(), ref_ids, what="draft from q'")
+
+
+# --------------------------------------------------------------------------------------------- concurrent streams
+def test_calls_on_two_streams_with_their_own_workspaces(rdk, ragged):
+    """Two fused calls that share the kernel handle but not their workspaces, enqueued on two streams so that they
+    overlap, give what each gives alone."""
+    data = ragged
+    w = data["w"]
+    idx, wt, sw = data["sparse"]
+    ks = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.SPARSE_TOPK, k=w.k,
+                              sparse=(dev(idx), dev(wt.astype(np.float32)), dev(sw.astype(np.float32))))
+    ki = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.IDENTITY)
+    p, q = dev(data["p"]), dev(data["q_hat"])
+    p2, q2 = dev(data["p"][::-1].copy()), dev(data["q_hat"][::-1].copy())
+    alone = [rdk.rdk_redistribute_verify(ks, rdk.LINEAR_SPARSE, p, q, 5, 0, w.gamma),
+             rdk.rdk_redistribute_verify(ki, rdk.LINEAR_TAYLOR, p2, q2, 6, 100, w.gamma)]
+    torch.cuda.synchronize()
+    outs = [rdk.VerifyOutputs(w.B, w.N, w.gamma, p.device) for _ in range(2)]
+    for o in outs:   # sizes the fused workspaces before the streams start
+        rdk.rdk_redistribute_verify(ks, rdk.LINEAR_SPARSE, p, q, 5, 0, w.gamma, outputs=o)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(10):
+        with torch.cuda.stream(streams[0]):
+            rdk.rdk_redistribute_verify(ks, rdk.LINEAR_SPARSE, p, q, 5, 0, w.gamma, outputs=outs[0])
+        with torch.cuda.stream(streams[1]):
+            rdk.rdk_redistribute_verify(ki, rdk.LINEAR_TAYLOR, p2, q2, 6, 100, w.gamma, outputs=outs[1])
+    torch.cuda.synchronize()
+    for got, ref in zip(outs, alone):
+        for name in ("draft_ids", "accept", "alpha", "resid_mass", "resid_ids", "n_accepted", "out_tokens"):
+            assert torch.equal(getattr(got, name), getattr(ref, name)), name
