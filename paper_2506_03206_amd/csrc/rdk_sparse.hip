@@ -21,6 +21,7 @@ namespace {
 constexpr int kThreads = 512;     // product kernel: 8 wavefronts share one staged tile
 constexpr int kWaves = kThreads / kWave;
 constexpr int kPrepThreads = 256; // transposition kernel
+constexpr int kTSlots = 64;       // slots per workgroup of the transposition kernel (128 and 256 were slower)
 constexpr int kPosBlock = 32;    // positions per gather: 32 fp32 = one 128-byte line
 constexpr int kTileIds = 256;    // target ids per workgroup
 constexpr int kStageLd = kTileIds + 4;   // rows stay 16-byte aligned for the float4 read-out
@@ -64,10 +65,10 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
                                                                    const SoftStat *qpart, int q_splits, bool vec, float *zinv,
                                                                    float *qT)
 {
-    __shared__ float tile[64][kPosBlock + 1];
+    __shared__ float tile[kTSlots][kPosBlock + 1];
     __shared__ float rowmax[kPosBlock];
     const int pb = blockIdx.y;
-    const int s0 = blockIdx.x * 64;
+    const int s0 = blockIdx.x * kTSlots;
     const int r = threadIdx.x / 8, part = threadIdx.x % 8;     // 8 threads per position
     const int64_t b = (int64_t)pb * kPosBlock + r;
     if (QK != RDK_PROB_F32 || blockIdx.x == 0) {
@@ -94,30 +95,42 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
         }
         if (QK != RDK_PROB_F32) __syncthreads();
     }
-    {   // read 32 rows x 64 slots: 8 threads per row, 8 consecutive slots each
-        const int c8 = part * 8;
-        float v[8];
+    // read 32 rows x kTSlots slots: kTSlots / 8 threads per row, 8 consecutive slots each
+    {
+        const int grp = threadIdx.x % (kTSlots / 8), rsub = threadIdx.x / (kTSlots / 8);
+        constexpr int kRowsPerPass = kPrepThreads / (kTSlots / 8);
+        const int c8 = grp * 8;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = 0.f;
-        if (b < B) {
-            const void *qr = row_ptr<QK>(q, ldq, b);
-            const float qm = QK == RDK_PROB_F32 ? 0.f : rowmax[r];
-            const float4 a0 = load4<QK>(qr, s0 + c8, n, vec, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
-            const float4 a1 = load4<QK>(qr, s0 + c8 + 4, n, vec, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
-            const float raw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        for (int r0 = 0; r0 < kPosBlock; r0 += kRowsPerPass) {
+            const int rr = r0 + rsub;
+            const int64_t bb = (int64_t)pb * kPosBlock + rr;
+            float v[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = to_weight<QK>(raw[e], qm, 1.f);
+            for (int e = 0; e < 8; ++e) v[e] = 0.f;
+            if (bb < B) {
+                const void *qr = row_ptr<QK>(q, ldq, bb);
+                const float qm = QK == RDK_PROB_F32 ? 0.f : rowmax[rr];
+                const float4 a0 = load4<QK>(qr, s0 + c8, n, vec, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
+                const float4 a1 = load4<QK>(qr, s0 + c8 + 4, n, vec, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
+                const float raw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = to_weight<QK>(raw[e], qm, 1.f);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) tile[c8 + e][rr] = v[e];
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) tile[c8 + e][r] = v[e];
     }
     __syncthreads();
-    {   // write 64 slots x 32 positions: 4 threads per slot, 8 positions each
-        const int sl = threadIdx.x / 4, pq = (threadIdx.x % 4) * 8;
-        if (s0 + sl < n) {
-            float *dst = qT + ((int64_t)pb * n + s0 + sl) * kPosBlock + pq;
-            *(float4 *)dst = make_float4(tile[sl][pq], tile[sl][pq + 1], tile[sl][pq + 2], tile[sl][pq + 3]);
-            *(float4 *)(dst + 4) = make_float4(tile[sl][pq + 4], tile[sl][pq + 5], tile[sl][pq + 6], tile[sl][pq + 7]);
+    {   // write kTSlots slots x 32 positions: 4 threads per slot, 8 positions each, 64 slots per pass
+        const int pq = (threadIdx.x % 4) * 8;
+#pragma unroll
+        for (int sl0 = 0; sl0 < kTSlots; sl0 += kPrepThreads / 4) {
+            const int sl = sl0 + threadIdx.x / 4;
+            if (s0 + sl < n) {
+                float *dst = qT + ((int64_t)pb * n + s0 + sl) * kPosBlock + pq;
+                *(float4 *)dst = make_float4(tile[sl][pq], tile[sl][pq + 1], tile[sl][pq + 2], tile[sl][pq + 3]);
+                *(float4 *)(dst + 4) = make_float4(tile[sl][pq + 4], tile[sl][pq + 5], tile[sl][pq + 6], tile[sl][pq + 7]);
+            }
         }
     }
 }
@@ -486,7 +499,7 @@ rdk_status_t prepare_q(const KernelHandle &h, RowInput q, int32_t B, const Spars
     if (rc != RDK_OK) return rc;
     const int pbs = (B + kPosBlock - 1) / kPosBlock;
     {
-        RDK_TIMED_LAUNCH("q_transpose_kernel", (q_transpose_kernel<QK>), dim3((h.n + 63) / 64, pbs), dim3(kPrepThreads), 0, st,
+        RDK_TIMED_LAUNCH("q_transpose_kernel", (q_transpose_kernel<QK>), dim3((h.n + kTSlots - 1) / kTSlots, pbs), dim3(kPrepThreads), 0, st,
                          q.ptr, q.ld, h.n, B, w.qpart, w.q_splits, rows_vectorisable(q.ptr, q.ld, q.kind), w.zinv, w.qT);
     }
     RDK_LAUNCH_CHECK("q_transpose_kernel");
