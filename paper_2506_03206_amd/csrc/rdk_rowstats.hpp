@@ -24,10 +24,8 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(const void *x, 
     st.m = KIND == RDK_PROB_F32 ? 0.f : -INFINITY;
     st.s = 0.f;
     for (int c = c_begin + wid; c < c_end; c += kWaves) {
-        const int64_t base = (int64_t)c * kChunk + lane * 4;
-        float4 v[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = load4<KIND>(xr, base + i * 256, len, vec, KIND == RDK_PROB_F32 ? 0.f : -INFINITY);
+        float4 v[4];   // kept cacheable: the kernels that follow read the same rows again
+        load_chunk<KIND, false>(xr, (int64_t)c * kChunk, len, vec, KIND == RDK_PROB_F32 ? 0.f : -INFINITY, v);
         if (KIND == RDK_PROB_F32) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) st.s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
