@@ -55,22 +55,42 @@ __device__ __forceinline__ void stage_chunk(float *lds, const void *qr, bool vec
 #pragma unroll
     for (int i = 0; i < 4; ++i) l4[i * kWave + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
-    for (int s = (lo & ~3) + lane * 4; s < hi; s += 4 * kWave) {
-        int4 kv = make_int4(0, 0, 0, 0);
-        if (s + 3 < n) {
-            kv = *(const int4 *)(kept + s);
-        } else {
-            if (s + 0 < n) kv.x = kept[s + 0];
-            if (s + 1 < n) kv.y = kept[s + 1];
-            if (s + 2 < n) kv.z = kept[s + 2];
-        }
-        const float4 qv = load4<QK>(qr, s, n, vec_q, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
-        const int ke[4] = {kv.x, kv.y, kv.z, kv.w};
-        const float qe[4] = {qv.x, qv.y, qv.z, qv.w};
+    // All quads of the run lie inside the row (true for every chunk but, when n is not a multiple of four, the last):
+    // the same answer for the whole wavefront.  Then the sweep over the run is uniform too: lanes past its end are
+    // sent to the last quad of the row (they repeat what its own lane stores), and no load or store sits behind a
+    // per-lane branch.
+    if (vec_q && ((hi + 3) & ~3) <= n) {
+        const int last_quad = (n & ~3) - 4;
+        for (int s0 = lo & ~3; s0 < hi; s0 += 4 * kWave) {
+            const int s = min(s0 + lane * 4, last_quad);
+            const int4 kv = *(const int4 *)(kept + s);
+            const float4 qv = load4_full<QK>(qr, s);
+            const int ke[4] = {kv.x, kv.y, kv.z, kv.w};
+            const float qe[4] = {qv.x, qv.y, qv.z, qv.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {   // the weight is formed here, once per kept slot rather than once per target id
-            const bool mine = s + e >= lo && s + e < hi;   // others go to a spare word per lane: no branch
-            lds[mine ? ((ke[e] - base) & (kChunk - 1)) : kChunk + lane] = to_weight<QK>(qe[e], qm, 1.f);
+            for (int e = 0; e < 4; ++e) {
+                const bool mine = s + e >= lo && s + e < hi;
+                lds[mine ? ((ke[e] - base) & (kChunk - 1)) : kChunk + lane] = to_weight<QK>(qe[e], qm, 1.f);
+            }
+        }
+    } else {
+        for (int s = (lo & ~3) + lane * 4; s < hi; s += 4 * kWave) {
+            int4 kv = make_int4(0, 0, 0, 0);
+            if (s + 3 < n) {
+                kv = *(const int4 *)(kept + s);
+            } else {
+                if (s + 0 < n) kv.x = kept[s + 0];
+                if (s + 1 < n) kv.y = kept[s + 1];
+                if (s + 2 < n) kv.z = kept[s + 2];
+            }
+            const float4 qv = load4<QK>(qr, s, n, vec_q, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
+            const int ke[4] = {kv.x, kv.y, kv.z, kv.w};
+            const float qe[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {   // the weight is formed here, once per kept slot rather than once per target id
+                const bool mine = s + e >= lo && s + e < hi;   // others go to a spare word per lane: no branch
+                lds[mine ? ((ke[e] - base) & (kChunk - 1)) : kChunk + lane] = to_weight<QK>(qe[e], qm, 1.f);
+            }
         }
     }
     wave_lds_sync();
