@@ -296,6 +296,9 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
     const float pfill = PKIND == RDK_PROB_F32 ? 0.f : -INFINITY;
     const int jl = j0 + 4 * lane;
     float4 praw[kRowsPerWave];
+    // every lane's four ids exist (all tiles but the last): decided for the whole workgroup, so that the loads and
+    // stores of the common case sit behind no per-lane branch
+    const bool whole_tile = j0 + kTileIds <= a.N;
     if (FUSE) {
 #pragma unroll
         for (int rr = 0; rr < kRowsPerWave; ++rr) {
@@ -303,7 +306,7 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
             // streamed past the caches' replacement order: the L2 of this XCD should keep the drafter slab instead
             if (b >= a.B)
                 praw[rr] = make_float4(pfill, pfill, pfill, pfill);
-            else if (f.vec_p && jl + 3 < a.N)
+            else if (f.vec_p && whole_tile)
                 praw[rr] = load4_full<PKIND, true>(row_ptr<PKIND>(f.p, f.ldp, b), jl);
             else
                 praw[rr] = load4<PKIND>(row_ptr<PKIND>(f.p, f.ldp, b), jl, a.N, f.vec_p, pfill);
@@ -320,7 +323,7 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
                              jl + 3 < a.N ? sv.w : 0.f};
         if (WRITE_Q) {
             float *o = a.out + b * a.ldo + jl;
-            if (a.vec_o && jl + 3 < a.N) {
+            if (a.vec_o && whole_tile) {
                 const f32x4 v = {qv[0], qv[1], qv[2], qv[3]};
                 __builtin_nontemporal_store(v, (f32x4 *)o);
             } else {
