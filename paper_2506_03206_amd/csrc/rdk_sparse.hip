@@ -26,6 +26,7 @@ constexpr int kPosBlock = 32;    // positions per gather: 32 fp32 = one 128-byte
 constexpr int kTileIds = 256;    // target ids per workgroup
 constexpr int kStageLd = kTileIds + 4;   // rows stay 16-byte aligned for the float4 read-out
 constexpr int kSubIds = 64;       // ids per block of verification sums in the fused form: 16 lanes x 4 ids
+constexpr int kEllAhead = 2;      // rounds of neighbour pairs requested ahead of the gathers (1 or 4: +3 us per launch)
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -168,7 +169,7 @@ __device__ __forceinline__ int pruned_below(const int32_t *slot_of, int j, int N
 // sums).  Lane layout of a wavefront: lane = 8 * i + o; i = id within a group of 8, o = which four of
 // the 32 positions.  One 128-byte line holds the 16 (slot, weight) pairs of a round: lane o of an id's
 // group fetches pairs 2o and 2o+1, and the pairs go round the group through the swizzle crossbar.
-// The next line of pairs is requested before the current gathers are issued.  The kernel runs at the throughput
+// The lines of pairs are requested two rounds ahead of the gathers that use them.  The kernel runs at the throughput
 // of the CU's vector memory pipe (address and data-return units about 80 % busy); occupancy beyond two workgroups
 // per CU does not change its time.
 __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0, float (*stage)[kStageLd])
@@ -185,20 +186,26 @@ __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0,
 
     // pruned ids of the tile: pruned slots [u_lo, u_hi), 8 per wavefront step
     int u0 = u_lo + wid * 8;
-    i32x4 ev_next = {0, 0, 0, 0};
-    if (u0 < u_hi) ev_next = *(const i32x4 *)(nbr_lane + (int64_t)min(u0 + i, u_hi - 1) * a.kk);
+    // the lines of pairs are requested kEllAhead rounds ahead (a round = 16 neighbours of 8 ids)
+    int pf_u = u0, pf_rd = 0;   // where the next request points
+    i32x4 evq[kEllAhead];
+#pragma unroll
+    for (int t = 0; t < kEllAhead; ++t) {
+        evq[t] = i32x4{0, 0, 0, 0};
+        if (pf_u < u_hi) evq[t] = *((const i32x4 *)(nbr_lane + (int64_t)min(pf_u + i, u_hi - 1) * a.kk + pf_rd * 16));
+        if (++pf_rd == rounds) { pf_rd = 0; pf_u += 8 * kWaves; }
+    }
     for (; u0 < u_hi; u0 += 8 * kWaves) {
         const int u = u0 + i;
         const bool valid = u < u_hi;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int rd = 0; rd < rounds; ++rd) {
-            const i32x4 ev = ev_next;
-            {   // request the pairs of the next round (or of the next step) now
-                const bool more = rd + 1 < rounds;
-                const int un = more ? u0 : u0 + 8 * kWaves;
-                if (un < u_hi)
-                    ev_next = *(const i32x4 *)(nbr_lane + (int64_t)min(un + i, u_hi - 1) * a.kk + (more ? (rd + 1) * 16 : 0));
-            }
+            const i32x4 ev = evq[0];
+#pragma unroll
+            for (int t = 0; t + 1 < kEllAhead; ++t) evq[t] = evq[t + 1];
+            if (pf_u < u_hi)
+                evq[kEllAhead - 1] = *((const i32x4 *)(nbr_lane + (int64_t)min(pf_u + i, u_hi - 1) * a.kk + pf_rd * 16));
+            if (++pf_rd == rounds) { pf_rd = 0; pf_u += 8 * kWaves; }
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 float4 g[8];
