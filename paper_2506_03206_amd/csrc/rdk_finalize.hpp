@@ -54,7 +54,7 @@ struct QpMemory {
         {
             t.v = rdk::load4<RDK_PROB_F32>(qr, idx, N, vec, 0.f);
         }
-        __device__ __forceinline__ float4 result(const Pending &t, int64_t) const { return t.v; }
+        __device__ __forceinline__ float4 result(Pending &t, int64_t) const { return t.v; }
         __device__ __forceinline__ float load1(int j) const { return qr[j]; }
     };
     __device__ __forceinline__ Row row(int64_t b) const { return Row{q + b * ldq, vec, N}; }

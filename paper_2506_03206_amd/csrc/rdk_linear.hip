@@ -230,7 +230,7 @@ struct TaylorRow {
             for (int e = 0; e < 4; ++e) t.qraw[e] = rdk::load1<QK>(qr, max(se[e], 0));   // unconditional: loads stay batched
         }
     }
-    __device__ __forceinline__ float4 result(const Pending &t, int64_t idx) const
+    __device__ __forceinline__ float4 result(Pending &t, int64_t idx) const
     {
         const float pe[4] = {to_weight<PK>(t.pv.x, pm, pinv), to_weight<PK>(t.pv.y, pm, pinv), to_weight<PK>(t.pv.z, pm, pinv),
                              to_weight<PK>(t.pv.w, pm, pinv)};

@@ -407,7 +407,7 @@ struct QpSparse {
         }
         // Four consecutive ids in three steps: slots; the first sixteen table entries of each id (a kept id is
         // treated as a row whose entries all point at its own slot, the first with the diagonal weight); the
-        // gathers.  Rows longer than sixteen entries finish one id after the other in result().
+        // gathers.  Rows longer than sixteen entries are finished round by round in result().
         struct Pending {
             int se[4];
             int ii[4][16];
@@ -447,24 +447,42 @@ struct QpSparse {
                     for (int x = 0; x < 16; ++x) t.gg[e][x] = qcol[(int64_t)t.ii[e][x] * kPosBlock];
             }
         }
-        __device__ __forceinline__ float4 result(const Pending &t, int64_t idx) const
+        // The record is reused for the rounds beyond the first: all pairs of a round for the four ids, then all their
+        // gathers, then the sums -- two round trips per round, whatever the number of ids.  A kept id takes its own
+        // slot with zero weights there (its row has the diagonal only).
+        __device__ __forceinline__ float4 result(Pending &t, int64_t idx) const
         {
-            float out[4];
+            float acc[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float acc = 0.f;
+                acc[e] = 0.f;
 #pragma unroll
-                for (int x = 0; x < 16; ++x) acc += t.ww[e][x] * t.gg[e][x];   // same order of additions as the product kernel
-                if (kk > 16 && t.se[e] < 0) {
-                    const int64_t u = -t.se[e] - 1;
-                    for (int x = 16; x < kk; x += 2) {
-                        const int4 ev = *(const int4 *)(nbr + u * kk + x);
-                        acc += __int_as_float(ev.y) * qcol[(int64_t)ev.x * kPosBlock];
-                        acc += __int_as_float(ev.w) * qcol[(int64_t)ev.z * kPosBlock];
+                for (int x = 0; x < 16; ++x) acc[e] += t.ww[e][x] * t.gg[e][x];   // same order of additions as the product kernel
+            }
+            for (int x0 = 16; x0 < kk; x0 += 16) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool kept = t.se[e] >= 0;
+                    const int64_t u = kept ? 0 : -t.se[e] - 1;
+#pragma unroll
+                    for (int x = 0; x < 16; x += 2) {
+                        const int4 ev = *(const int4 *)(nbr + u * kk + x0 + x);
+                        t.ii[e][x] = kept ? t.se[e] : ev.x; t.ww[e][x] = kept ? 0.f : __int_as_float(ev.y);
+                        t.ii[e][x + 1] = kept ? t.se[e] : ev.z; t.ww[e][x + 1] = kept ? 0.f : __int_as_float(ev.w);
                     }
                 }
-                out[e] = idx + e < N ? acc * inv_z : 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) t.gg[e][x] = qcol[(int64_t)t.ii[e][x] * kPosBlock];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) acc[e] += t.ww[e][x] * t.gg[e][x];
             }
+            float out[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[e] = idx + e < N ? acc[e] * inv_z : 0.f;
             return make_float4(out[0], out[1], out[2], out[3]);
         }
         __device__ __forceinline__ float load1(int j) const { return value(j); }

@@ -709,3 +709,29 @@ def test_calls_on_two_streams_with_their_own_workspaces(rdk, ragged):
     for got, ref in zip(outs, alone):
         for name in ("draft_ids", "accept", "alpha", "resid_mass", "resid_ids", "n_accepted", "out_tokens"):
             assert torch.equal(getattr(got, name), getattr(ref, name)), name
+
+
+# --------------------------------------------------------------------------------------------- long neighbour rows
+@pytest.mark.parametrize("k", [17, 32, 40])
+def test_sparse_rows_longer_than_one_round(rdk, ragged, k):
+    """More than sixteen neighbours per pruned id: the product runs several rounds per id and the finish kernel
+    re-computes its two blocks round by round.  Fused call against the oracle, its q' bit-equal to the two-call rows,
+    and the draft draw bit-equal to the fused call's."""
+    data = ragged
+    w = data["w"]
+    idx, wt, sw = synth.random_sparse_kernel(np.random.default_rng(40 + k), w.N, data["kept_ids"], k)
+    kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.SPARSE_TOPK, k=k, sparse=(dev(idx), dev(wt), dev(sw)))
+    p, q = dev(data["p"]), dev(data["q_hat"])
+    seed, offset = 77, 9
+    qp = torch.zeros((w.B, w.N), dtype=torch.float32, device="cuda")
+    o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_SPARSE, p, q, seed, offset, w.gamma, q_prime=qp)
+    rows = rdk.rdk_redistribute_linear(kern, rdk.LINEAR_SPARSE, q)
+    assert torch.equal(qp, rows)
+    ref_qp = oracle.redistribute_batch("sparse", data["q_hat"], data["kept_ids"], w.N, sparse=(idx, wt, sw))
+    assert_close(qp.cpu().numpy(), ref_qp, what="sparse q', k=%d" % k)
+    p64 = data["p"].astype(np.float64)
+    ref = oracle.verify_batch(p64, ref_qp, seed, offset, gamma=w.gamma)
+    check_verify_outputs(o, ref, p64, ref_qp, seed, offset, w.gamma, "prob")
+    ids, qd = rdk.rdk_sample_draft(kern, q, seed, offset)
+    assert torch.equal(ids, o.draft_ids)
+    assert_close(qd.cpu().numpy(), ref_qp[np.arange(w.B), ids.cpu().numpy()], what="q' at the drafted id")
