@@ -106,12 +106,29 @@ __global__ void sequence_scan_kernel(int S, int gamma, const int32_t *draft_ids,
     const int s = blockIdx.x * blockDim.x + threadIdx.x;
     if (s >= S) return;
     const int64_t b0 = (int64_t)s * gamma;
-    int j = 0;
-    while (j < gamma && accept[b0 + j]) ++j;
+    // flags are read eight at a time so that the loads of a group are in flight together (one round trip per group
+    // instead of one per draft position)
+    int j = gamma;
+    for (int g0 = 0; g0 < gamma && j == gamma; g0 += 8) {
+        uint8_t f[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) f[t] = g0 + t < gamma ? accept[b0 + g0 + t] : (uint8_t)0;
+#pragma unroll
+        for (int t = 7; t >= 0; --t)
+            if (g0 + t < gamma && !f[t]) j = g0 + t;   // the lowest rejected position of the group wins
+    }
     if (n_accepted) n_accepted[s] = j;
     if (out_tokens) {
         int32_t *o = out_tokens + (int64_t)s * (gamma + 1);
-        for (int i = 0; i <= gamma; ++i) o[i] = i < j ? draft_ids[b0 + i] : (i == j && j < gamma) ? resid_ids[b0 + i] : -1;
+        const int32_t resid = j < gamma ? resid_ids[b0 + j] : -1;
+        for (int i0 = 0; i0 <= gamma; i0 += 8) {
+            int32_t d[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) d[t] = i0 + t < j ? draft_ids[b0 + i0 + t] : -1;
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                if (i0 + t <= gamma) o[i0 + t] = i0 + t < j ? d[t] : (i0 + t == j && j < gamma) ? resid : -1;
+        }
     }
 }
 
