@@ -16,7 +16,7 @@ constexpr int kWaves = kThreads / kWave;
 struct LinearWs {
     SoftStat *pstat;   // [B, p_splits]  target row softmax statistics (logit p only)
     SoftStat *qstat;   // [B]            drafter row: (max, sum exp) or (0, sum)
-    float *tpart;      // [B, t_splits, 4]  Taylor partial sums
+    float *tpart;      // [B, t_splits, 8]  Taylor partial sums (4 used by the two-pass form, 8 by the one-pass form)
     int p_splits, t_splits;
 };
 
@@ -181,6 +181,101 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) v
     }
 }
 
+// Eq. 3, first pass for LOGIT target rows without a softmax pass of its own.  The sums of the pass above need the
+// normalised p inside 1 / (N + p), i.e. the row maximum and normaliser first.  But p / N <= 1 / N, so with x = p / N
+//   N / (N + p) = 1 - x + x^2 - x^3 + O(N^-4),      p / (N + p) = x - x^2 + x^3 + O(N^-4),
+// and every term is a power sum of e = exp(z - m) that can be carried under a running maximum m and rescaled when
+// the maximum grows (a factor exp(k (m_old - m_new)) for the k-th power).  Per split of a row, relative to the
+// split's own maximum m:   S_k = sum_j e_j^k  and  Q_k = sum over kept ids of q^_s e_j^k,  k = 1..3,  and Q_0 = sum q^_s.
+// The record (m, S1, S2, S3, Q0, Q1, Q2, Q3) goes to tpart, and (m, S1) also to pstat: the softmax statistics every
+// later kernel reads, in the layout of the softmax pass this kernel replaces.  Used for N >= kOnePassMinN, where the
+// truncation (a relative N^-3 of the smaller sum) is far below fp32 rounding.
+constexpr int kOnePassMinN = 1024;
+
+template <int PK, int QK, bool KEEP_P>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) void taylor_stats_onepass_kernel(
+    const void *p, int64_t ldp, const void *q, int64_t ldq, const int32_t *kept, const int32_t *chunk_lo, int N, int n,
+    int splits, bool vec_p, bool vec_q, LinearWs w)
+{
+    static_assert(PK != RDK_PROB_F32, "probabilities need no normaliser: the two-pass kernel serves them");
+    __shared__ __attribute__((aligned(16))) float qchunk[kWaves][kChunk + kWave];
+    const int64_t row = blockIdx.x / splits;
+    const int split = blockIdx.x % splits;
+    const int nchunks = (N + kChunk - 1) / kChunk;
+    const int cpw = (nchunks + splits - 1) / splits;
+    const int c_begin = split * cpw, c_end = min(nchunks, c_begin + cpw);
+    const void *pr = row_ptr<PK>(p, ldp, row);
+    const void *qr = row_ptr<QK>(q, ldq, row);
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
+    const float qm = QK == RDK_PROB_F32 ? 0.f : w.qstat[row].m;
+    float m = -INFINITY;                                         // running maximum, the same in all lanes
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f, q0 = 0.f, q1 = 0.f, q2 = 0.f, q3 = 0.f;
+    int c = c_begin + wid;
+    int lo = 0, hi = 0;
+    if (c < c_end) {
+        lo = chunk_lo[c];
+        hi = chunk_lo[c + 1];
+    }
+    for (; c < c_end; c += kWaves) {
+        const int base = c * kChunk;
+        float4 pv[4], qd[4];
+        load_chunk<PK, !KEEP_P>(pr, base, N, vec_p, -INFINITY, pv);
+        const int lo_now = lo, hi_now = hi;
+        if (c + kWaves < c_end) {
+            lo = chunk_lo[c + kWaves];
+            hi = chunk_lo[c + kWaves + 1];
+        }
+        stage_chunk<QK>(qchunk[wid], qr, vec_q, n, qm, kept, lo_now, hi_now, base, qd);
+        float cm = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) cm = fmaxf(cm, fmaxf(fmaxf(pv[i].x, pv[i].y), fmaxf(pv[i].z, pv[i].w)));
+        cm = wave_max(cm);                                       // finite: a chunk holds at least one id
+        if (cm > m) {                                            // the same decision in all lanes
+            const float f = soft_exp(m - cm), f2 = f * f, f3 = f2 * f;   // 0 on the first chunk (m = -inf)
+            s1 *= f; s2 *= f2; s3 *= f3;
+            q1 *= f; q2 *= f2; q3 *= f3;
+            m = cm;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float pe[4] = {soft_exp(pv[i].x - m), soft_exp(pv[i].y - m), soft_exp(pv[i].z - m), soft_exp(pv[i].w - m)};
+            const float qe[4] = {qd[i].x, qd[i].y, qd[i].z, qd[i].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float e1 = pe[e], e2 = e1 * e1, e3 = e2 * e1;   // exp(-inf) = 0 beyond N
+                const float qh = qe[e];                                // zero on ids that are not kept
+                s1 += e1; s2 += e2; s3 += e3;
+                q0 += qh; q1 += qh * e1; q2 += qh * e2; q3 += qh * e3;
+            }
+        }
+    }
+    s1 = wave_sum(s1); s2 = wave_sum(s2); s3 = wave_sum(s3);
+    q0 = wave_sum(q0); q1 = wave_sum(q1); q2 = wave_sum(q2); q3 = wave_sum(q3);
+    __shared__ float sh[kWaves][8];
+    if (lane == 0) {
+        sh[wid][0] = m; sh[wid][1] = s1; sh[wid][2] = s2; sh[wid][3] = s3;
+        sh[wid][4] = q0; sh[wid][5] = q1; sh[wid][6] = q2; sh[wid][7] = q3;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {   // wavefronts without a chunk hold m = -inf and zeros: their factor is 0
+        float mm = sh[0][0];
+        for (int i = 1; i < kWaves; ++i) mm = fmaxf(mm, sh[i][0]);
+        float r[8] = {mm, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < kWaves; ++i) {
+            const float f = sh[i][0] > -INFINITY ? soft_exp(sh[i][0] - mm) : 0.f, f2 = f * f, f3 = f2 * f;
+            r[1] += sh[i][1] * f; r[2] += sh[i][2] * f2; r[3] += sh[i][3] * f3;
+            r[4] += sh[i][4]; r[5] += sh[i][5] * f; r[6] += sh[i][6] * f2; r[7] += sh[i][7] * f3;
+        }
+        float *dst = w.tpart + (row * splits + split) * 8;
+        *(float4 *)dst = make_float4(r[0], r[1], r[2], r[3]);
+        *(float4 *)(dst + 4) = make_float4(r[4], r[5], r[6], r[7]);
+        SoftStat st;
+        st.m = mm;
+        st.s = r[1];
+        w.pstat[row * splits + split] = st;
+    }
+}
+
 // Everything the second pass of Eq. 3 needs about one row; built by all lanes of a wavefront alike.
 struct TaylorArgs {
     const void *p, *q;
@@ -188,6 +283,7 @@ struct TaylorArgs {
     const int32_t *slot_of, *kept, *chunk_lo;
     int N, n, splits;
     bool vec_p, vec_q;
+    bool onepass;   // the first pass was the one-pass kernel: tpart holds its eight-word records
     LinearWs w;
 };
 
@@ -270,16 +366,36 @@ __device__ __forceinline__ TaylorRow<PK, QK> make_taylor_row(const TaylorArgs &a
     }
     r.qm = QK == RDK_PROB_F32 ? 0.f : a.w.qstat[row].m;
     // totals of the first pass, summed in split order by every wavefront alike
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    for (int i = lane_id(); i < a.splits; i += kWave) {
-        const float4 t = *(const float4 *)(a.w.tpart + (row * a.splits + i) * 4);
-        a0 += t.x; a1 += t.y; a2 += t.z; a3 += t.w;
+    r.fN = (float)a.N;
+    float zq, tn, an, bs;
+    if (PK != RDK_PROB_F32 && a.onepass) {
+        // power sums relative to each split's own maximum, brought to the row maximum; then the series in x = p / N
+        float s2 = 0.f, s3 = 0.f, q0 = 0.f, q1 = 0.f, q2 = 0.f, q3 = 0.f;
+        for (int i = lane_id(); i < a.splits; i += kWave) {
+            const float *rec = a.w.tpart + (row * a.splits + i) * 8;
+            const float4 t0 = *(const float4 *)rec, t1 = *(const float4 *)(rec + 4);
+            const float f = soft_exp(t0.x - r.pm), f2 = f * f, f3 = f2 * f;   // 0 for a split without ids
+            s2 += t0.z * f2; s3 += t0.w * f3;
+            q0 += t1.x; q1 += t1.y * f; q2 += t1.z * f2; q3 += t1.w * f3;
+        }
+        s2 = wave_sum(s2); s3 = wave_sum(s3);
+        q0 = wave_sum(q0); q1 = wave_sum(q1); q2 = wave_sum(q2); q3 = wave_sum(q3);
+        const float c = r.pinv / r.fN, c2 = c * c, c3 = c2 * c;               // x_j = e_j c
+        zq = q0;
+        tn = q1 * r.pinv;                                                     // sum q^ p
+        an = q0 - q1 * c + q2 * c2 - q3 * c3;                                 // sum q^ N / (N + p)
+        bs = 1.0f / r.fN - s2 * c2 + s3 * c3;                                 // sum p / (N + p);  sum x = 1 / N
+    } else {
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        for (int i = lane_id(); i < a.splits; i += kWave) {
+            const float4 t = *(const float4 *)(a.w.tpart + (row * a.splits + i) * 4);
+            a0 += t.x; a1 += t.y; a2 += t.z; a3 += t.w;
+        }
+        zq = wave_sum(a0); tn = wave_sum(a1); an = wave_sum(a2); bs = wave_sum(a3);
     }
-    const float zq = wave_sum(a0), tn = wave_sum(a1), an = wave_sum(a2), bs = wave_sum(a3);
     r.inv_zq = 1.0f / zq;
     r.theta = tn * r.inv_zq;
     r.inv_S = 1.0f / (an * r.inv_zq + r.theta * bs);
-    r.fN = (float)a.N;
     r.nzs = r.fN * r.inv_zq * r.inv_S;
     r.ths = r.theta * r.inv_S;
     return r;
@@ -394,7 +510,9 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
 {
     LinearWs w = carve(h, B, ws);
     rdk_status_t rc;
-    if (PK != RDK_PROB_F32) {
+    // logit target rows of a large vocabulary: the first pass of Eq. 3 also delivers the softmax statistics
+    const bool onepass = PK != RDK_PROB_F32 && h.N >= kOnePassMinN;
+    if (PK != RDK_PROB_F32 && !onepass) {
         rc = launch_row_stats<PK>(p, h.N, B, w.p_splits, w.pstat, st);
         if (rc != RDK_OK) return rc;
     }
@@ -407,19 +525,28 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
     a.slot_of = h.slot_of; a.kept = h.kept_ids; a.chunk_lo = h.chunk_lo; a.N = h.N; a.n = h.n; a.splits = w.t_splits;
     a.vec_p = rows_vectorisable(p.ptr, p.ld, p.kind);
     a.vec_q = rows_vectorisable(q.ptr, q.ld, q.kind);
+    a.onepass = onepass;
     a.w = w;
     const bool vec_o = out ? rows_vectorisable(out, ldo, RDK_PROB_F32) : false;
-    if (c) {
-        RDK_TIMED_LAUNCH("taylor_stats_kernel", (taylor_stats_kernel<PK, QK, true>), dim3((unsigned)B * w.t_splits),
-                         dim3(kThreads), 0, st, p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p,
-                         a.vec_q, w);
-    } else {
-        RDK_TIMED_LAUNCH("taylor_stats_kernel", (taylor_stats_kernel<PK, QK, false>), dim3((unsigned)B * w.t_splits),
-                         dim3(kThreads), 0, st, p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p,
-                         a.vec_q, w);
-    }
-    RDK_LAUNCH_CHECK("taylor_stats_kernel");
+    // first pass: one-pass or two-pass statistics; in the fused call (c != NULL) it leaves the target rows cacheable
     const dim3 grid((unsigned)B * w.t_splits);
+#define RDK_LAUNCH_STATS(KERNEL)                                                                                         \
+    RDK_TIMED_LAUNCH("taylor_stats_kernel", KERNEL, grid, dim3(kThreads), 0, st, p.ptr, p.ld, q.ptr, q.ld, h.kept_ids,  \
+                     h.chunk_lo, h.N, h.n, w.t_splits, a.vec_p, a.vec_q, w)
+    bool launched = false;
+    if constexpr (PK != RDK_PROB_F32) {
+        if (onepass) {
+            if (c) RDK_LAUNCH_STATS((taylor_stats_onepass_kernel<PK, QK, true>));
+            else RDK_LAUNCH_STATS((taylor_stats_onepass_kernel<PK, QK, false>));
+            launched = true;
+        }
+    }
+    if (!launched) {
+        if (c) RDK_LAUNCH_STATS((taylor_stats_kernel<PK, QK, true>));
+        else RDK_LAUNCH_STATS((taylor_stats_kernel<PK, QK, false>));
+    }
+#undef RDK_LAUNCH_STATS
+    RDK_LAUNCH_CHECK("taylor_stats_kernel");
     if (!c) {
         {
             RDK_TIMED_LAUNCH("taylor_write_kernel", (taylor_write_kernel<PK, QK, false>), grid, dim3(kThreads), 0, st, a, vec_o,
@@ -469,7 +596,7 @@ size_t taylor_workspace_bytes(const KernelHandle &h, int32_t B)
 {
     const int splits = row_splits(B, h.N, kWaves);
     return align_up((size_t)B * splits * sizeof(SoftStat), 256) + align_up((size_t)B * sizeof(SoftStat), 256) +
-           align_up((size_t)B * splits * 4 * sizeof(float), 256);
+           align_up((size_t)B * splits * 8 * sizeof(float), 256);
 }
 
 size_t taylor_fused_workspace_bytes(const KernelHandle &h, int32_t B)

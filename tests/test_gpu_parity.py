@@ -658,6 +658,11 @@ def test_degenerate_shapes(rdk, shape):
     ki = rdk.rdk_build_kernel(w.N, kept, rdk.IDENTITY)
     ref_taylor = oracle.redistribute_batch("taylor", data["q_hat"], data["kept_ids"], w.N, p=data["p"])
     assert_close(rdk.rdk_redistribute_linear(ki, rdk.LINEAR_TAYLOR, q, p=p).cpu().numpy(), ref_taylor, what="Eq. 3 q'")
+    # logit inputs at a vocabulary too small for the one-pass statistics: the softmax pass followed by the two-pass sums
+    ref_logit = oracle.redistribute_batch("taylor", oracle.probs_from(data["z_q"], "logit"), data["kept_ids"], w.N,
+                                          p=oracle.probs_from(data["z_p"], "logit"))
+    got = rdk.rdk_redistribute_linear(ki, rdk.LINEAR_TAYLOR, dev(data["z_q"]), "logit", p=dev(data["z_p"]), p_kind="logit")
+    assert_close(got.cpu().numpy(), ref_logit, what="Eq. 3 q' from logits")
 
     ref_exact = oracle.redistribute_batch("exact", data["q_hat"], data["kept_ids"], w.N, M=M32)
     kd = rdk.rdk_build_kernel(w.N, kept, rdk.DENSE_F32, dense_M=dev(M32))
