@@ -63,7 +63,8 @@ __device__ __forceinline__ float oct_sum(float v)
 template <int QK>
 __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q, int64_t ldq, int n, int B,
                                                                    const SoftStat *qpart, int q_splits, bool vec, float *zinv,
-                                                                   float *qT)
+                                                                   float *qT, const SoftStat *pstat, int p_splits,
+                                                                   SoftStat *pmerged)
 {
     __shared__ float tile[kTSlots][kPosBlock + 1];
     __shared__ float rowmax[kPosBlock];
@@ -71,6 +72,23 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
     const int s0 = blockIdx.x * kTSlots;
     const int r = threadIdx.x / 8, part = threadIdx.x % 8;     // 8 threads per position
     const int64_t b = (int64_t)pb * kPosBlock + r;
+    if (pstat != nullptr && blockIdx.x == 0) {
+        // softmax statistics of the logit TARGET rows of this position block, merged once here so that the product
+        // kernel and the finish kernel read one (max, sum) pair per row instead of merging the partials in every tile
+        SoftStat v;
+        v.m = -INFINITY;
+        v.s = 0.f;
+        if (b < B)
+            for (int i = part; i < p_splits; i += 8) v = soft_merge(v, pstat[b * p_splits + i]);
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) {
+            SoftStat o;
+            o.m = __shfl_xor(v.m, off, kWave);
+            o.s = __shfl_xor(v.s, off, kWave);
+            v = soft_merge(v, o);
+        }
+        if (part == 0 && b < B) pmerged[b] = v;
+    }
     if (QK != RDK_PROB_F32 || blockIdx.x == 0) {
         // row maximum (logits) and, in the first slot tile, 1 / row sum for the product kernel: partial sums of
         // logits are relative to each partial's own maximum and are brought to the row maximum first
@@ -267,8 +285,8 @@ struct FuseArgs {
     const void *p;
     int64_t ldp;
     bool vec_p;
-    const SoftStat *pstat;
-    int p_splits;
+    const SoftStat *pstat;             // [B] softmax statistics of the logit target rows, one merged pair per row
+    int p_splits;                      // = 1 (the layout the finish kernel expects: partials per row)
     float *part_q, *part_r, *part_a;   // [B, tiles * 4]: one entry per 64-id block
 };
 
@@ -344,7 +362,7 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
         if (SUMS) {
             float m = 0.f, inv = 1.f;
             if (FUSE && PKIND != RDK_PROB_F32) {
-                const SoftStat rs = merged_row_stat<PKIND>(f.pstat, f.p_splits, b);
+                const SoftStat rs = f.pstat[b];   // merged by the transposition kernel
                 m = rs.m;
                 inv = 1.0f / rs.s;
             }
@@ -504,7 +522,8 @@ struct SparseFusedWs {
 size_t fused_extra_bytes(const KernelHandle &h, int32_t B)
 {
     const size_t blocks = (size_t)((h.N + kTileIds - 1) / kTileIds) * (kTileIds / kSubIds);
-    return align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256) + 3 * align_up((size_t)B * blocks * sizeof(float), 256);
+    return align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256) + align_up((size_t)B * sizeof(SoftStat), 256) +
+           3 * align_up((size_t)B * blocks * sizeof(float), 256);
 }
 
 SparseArgs make_args(const KernelHandle &h, const SparseWs &w, int32_t B, float *out, int64_t ldo)
@@ -523,14 +542,16 @@ SparseArgs make_args(const KernelHandle &h, const SparseWs &w, int32_t B, float 
 }
 
 template <int QK>
-rdk_status_t prepare_q(const KernelHandle &h, RowInput q, int32_t B, const SparseWs &w, hipStream_t st)
+rdk_status_t prepare_q(const KernelHandle &h, RowInput q, int32_t B, const SparseWs &w, hipStream_t st,
+                       const SoftStat *pstat = nullptr, int p_splits = 0, SoftStat *pmerged = nullptr)
 {
     rdk_status_t rc = launch_row_stats<QK>(q, h.n, B, w.q_splits, w.qpart, st);
     if (rc != RDK_OK) return rc;
     const int pbs = (B + kPosBlock - 1) / kPosBlock;
     {
         RDK_TIMED_LAUNCH("q_transpose_kernel", (q_transpose_kernel<QK>), dim3((h.n + kTSlots - 1) / kTSlots, pbs), dim3(kPrepThreads), 0, st,
-                         q.ptr, q.ld, h.n, B, w.qpart, w.q_splits, rows_vectorisable(q.ptr, q.ld, q.kind), w.zinv, w.qT);
+                         q.ptr, q.ld, h.n, B, w.qpart, w.q_splits, rows_vectorisable(q.ptr, q.ld, q.kind), w.zinv, w.qT, pstat, p_splits,
+                         pmerged);
     }
     RDK_LAUNCH_CHECK("q_transpose_kernel");
     return RDK_OK;
@@ -559,8 +580,11 @@ rdk_status_t run_sparse_fused(const KernelHandle &h, const FusedCall &c, void *w
     char *p = (char *)ws + sparse_workspace_bytes(h, B);
     FuseArgs f{};
     f.p = c.p.ptr; f.ldp = c.p.ld; f.vec_p = rows_vectorisable(c.p.ptr, c.p.ld, c.p.kind);
-    f.p_splits = row_splits(B, h.N, kStatThreads / kWave);
-    f.pstat = (SoftStat *)p; p += align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256);
+    const int p_splits = row_splits(B, h.N, kStatThreads / kWave);
+    SoftStat *ppart = (SoftStat *)p; p += align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256);   // partials per split
+    SoftStat *pmerged = (SoftStat *)p; p += align_up((size_t)B * sizeof(SoftStat), 256);              // one per row
+    f.pstat = pmerged;
+    f.p_splits = 1;
     const size_t blocks = (size_t)((h.N + kTileIds - 1) / kTileIds) * (kTileIds / kSubIds);
     const size_t per = align_up((size_t)B * blocks * sizeof(float), 256);
     f.part_q = (float *)p; p += per;
@@ -568,10 +592,10 @@ rdk_status_t run_sparse_fused(const KernelHandle &h, const FusedCall &c, void *w
     f.part_a = (float *)p;
     rdk_status_t rc;
     if (PK != RDK_PROB_F32) {
-        rc = launch_row_stats<PK>(c.p, h.N, B, f.p_splits, const_cast<SoftStat *>(f.pstat), st);
+        rc = launch_row_stats<PK>(c.p, h.N, B, p_splits, ppart, st);
         if (rc != RDK_OK) return rc;
     }
-    rc = prepare_q<QK>(h, c.q, B, w, st);
+    rc = PK != RDK_PROB_F32 ? prepare_q<QK>(h, c.q, B, w, st, ppart, p_splits, pmerged) : prepare_q<QK>(h, c.q, B, w, st);
     if (rc != RDK_OK) return rc;
     const SparseArgs a = make_args(h, w, B, c.q_prime, c.ldo);
     {
