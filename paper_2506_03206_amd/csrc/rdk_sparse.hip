@@ -216,6 +216,7 @@ __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0,
     for (; u0 < u_hi; u0 += 8 * kWaves) {
         const int u = u0 + i;
         const bool valid = u < u_hi;
+        const int pid = a.pruned_ids[min(u, u_hi - 1)];   // asked for now, needed after the gathers of this step
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int rd = 0; rd < rounds; ++rd) {
             const i32x4 ev = evq[0];
@@ -245,7 +246,7 @@ __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0,
             }
         }
         if (valid) {
-            const int c = a.pruned_ids[u] - j0;
+            const int c = pid - j0;
             stage[o * 4 + 0][c] = acc.x * inv_z.x;
             stage[o * 4 + 1][c] = acc.y * inv_z.y;
             stage[o * 4 + 2][c] = acc.z * inv_z.z;
