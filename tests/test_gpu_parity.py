@@ -740,3 +740,108 @@ def test_sparse_rows_longer_than_one_round(rdk, ragged, k):
     ids, qd = rdk.rdk_sample_draft(kern, q, seed, offset)
     assert torch.equal(ids, o.draft_ids)
     assert_close(qd.cpu().numpy(), ref_qp[np.arange(w.B), ids.cpu().numpy()], what="q' at the drafted id")
+
+
+# --------------------------------------------------------------------------------------------- padded rows, random shapes
+def padded(a, pad, dtype=None, fill=float("nan")):
+    """Device view [B, width] of a wider tensor whose extra columns hold `fill`: a row stride above the width."""
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    big = torch.full((t.shape[0], t.shape[1] + pad), fill, dtype=t.dtype)
+    big[:, :t.shape[1]] = t
+    big = big.cuda()
+    return big[:, :t.shape[1]], big
+
+
+def draw_shape(seed):
+    rng = np.random.default_rng(1000 + seed)
+    edges = [63, 64, 65, 255, 257, 511, 512, 513, 1023, 1024, 1025, 1535, 2047, 2049, 4095, 4097]
+    N = int(rng.choice(edges)) if rng.random() < 0.6 else int(rng.integers(5, 5000))
+    n = int(rng.integers(1, N + 1)) if rng.random() < 0.8 else int(rng.choice([1, max(1, N // 2), N]))
+    k = min(n, int(rng.choice([0, 1, 3, 8, 15, 16, 17, 33])))
+    # row strides: the width itself, the next multiple of four (the 16-byte paths with a ragged end), and wider
+    pads = [int(rng.choice([0, (-w_) % 4, (-w_) % 4 + 4, 1, 3])) for w_ in (N, n, N)]
+    return dict(N=N, n=n, k=k, seqs=int(rng.integers(1, 7)), gamma=int(rng.integers(1, 5)), d=int(rng.integers(4, 33))), pads, rng
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_with_padded_rows(rdk, seed):
+    """Shapes drawn around the tile, block and vector-width boundaries, inputs and outputs as views of wider
+    tensors (row stride above the width, padding poisoned): nothing past a row's width may be read or written."""
+    shape, (pad_p, pad_q, pad_o), rng = draw_shape(seed)
+    w = synth.scaled(synth.WORKLOADS["tiny"], name="random%d" % seed, seed=100 + seed, **shape)
+    data = synth.make(w)
+    data["w"] = w
+    kinds = ("prob", "logit", "bf16")[int(rng.integers(0, 3))]
+    if kinds == "bf16":
+        data["z_p"], data["z_q"] = synth.bf16_round(data["z_p"]), synth.bf16_round(data["z_q"])
+    print("seed", seed, shape, "pads", (pad_p, pad_q, pad_o), kinds, flush=True)
+    kept = dev(data["kept_ids"])
+    if 0 < w.k <= w.n // 2:
+        idx, wt, sw = synth.random_sparse_kernel(rng, w.N, data["kept_ids"], w.k)
+    else:   # no neighbours, or most of the kept slots: the top-k kernel of the embeddings (distinct by construction)
+        idx, wt, sw = oracle.build_sparse(data["E"], data["kept_ids"], w.tau, w.k)
+    wt32, sw32 = np.asarray(wt, np.float32), np.asarray(sw, np.float32)
+    if kinds == "prob":
+        p_in, p_big = padded(data["p"], pad_p)
+        q_in, q_big = padded(data["q_hat"], pad_q)
+        pk = qk = "prob"
+        p64, q64 = data["p"].astype(np.float64), data["q_hat"].astype(np.float64)
+    else:
+        dt = torch.bfloat16 if kinds == "bf16" else None
+        p_in, p_big = padded(data["z_p"], pad_p, dt)
+        q_in, q_big = padded(data["z_q"], pad_q, dt)
+        pk = qk = "logit"
+        p64, q64 = oracle.probs_from(data["z_p"], "logit"), oracle.probs_from(data["z_q"], "logit")
+    sentinel = -123.0
+
+    def out_view():
+        big = torch.full((w.B, w.N + pad_o), sentinel, dtype=torch.float32, device="cuda")
+        return big[:, :w.N], big
+
+    def check_rows(view, big, ref, what):
+        assert_close(view.cpu().numpy(), ref, what=what)
+        assert bool((big[:, w.N:] == sentinel).all()), what + ": wrote past the row"
+
+    ks = rdk.rdk_build_kernel(w.N, kept, rdk.SPARSE_TOPK, k=w.k, sparse=(dev(idx), dev(wt32), dev(sw32)))
+    ki = rdk.rdk_build_kernel(w.N, kept, rdk.IDENTITY)
+    ref_sparse = oracle.redistribute_batch("sparse", q64, data["kept_ids"], w.N, sparse=(idx, wt32, sw32))
+    ref_taylor = oracle.redistribute_batch("taylor", q64, data["kept_ids"], w.N, p=p64)
+    seed_, offset = 77 + seed, 5
+    for kern, gmode, ref_qp, name in ((ks, rdk.LINEAR_SPARSE, ref_sparse, "sparse"), (ki, rdk.LINEAR_TAYLOR, ref_taylor, "Eq. 3")):
+        view, big = out_view()
+        rdk.rdk_redistribute_linear(kern, gmode, q_in, qk, p=p_in, p_kind=pk, out=view)
+        check_rows(view, big, ref_qp, name + " q'")
+        ref = oracle.verify_batch(p64, ref_qp, seed_, offset, gamma=w.gamma)
+        view2, big2 = out_view()
+        o1 = rdk.rdk_redistribute_verify(kern, gmode, p_in, q_in, seed_, offset, w.gamma, pk, qk, q_prime=view2)
+        check_rows(view2, big2, ref_qp, name + " fused q'")
+        assert torch.equal(view, view2)
+        o2 = rdk.rdk_redistribute_verify(kern, gmode, p_in, q_in, seed_, offset, w.gamma, pk, qk)
+        for o in (o1, o2):
+            check_verify_outputs(o, ref, p64, ref_qp, seed_, offset, w.gamma, pk, min_exact=0.0)
+        # the materialised rows (padded) through the stand-alone verification
+        qp32 = view.cpu().numpy()
+        o3 = rdk.rdk_verify_sample(p_in, view, seed_, offset, w.gamma, pk)
+        ref3 = oracle.verify_batch(p64, qp32.astype(np.float64), seed_, offset, gamma=w.gamma)
+        check_verify_outputs(o3, ref3, p64, qp32.astype(np.float64), seed_, offset, w.gamma, pk, min_exact=0.0)
+    # draft draw before any target row exists
+    view, big = out_view()
+    ids, _ = rdk.rdk_sample_draft(ks, q_in, seed_, offset, qk, q_prime=view)
+    check_rows(view, big, ref_sparse, "draft q'")
+    u0 = np.array([oracle.uniforms(seed_, offset + b)[0] for b in range(w.B)])
+    ref_ids = np.array([oracle.sample_cdf(ref_sparse[b], u0[b]) for b in range(w.B)])
+    check_sampled_ids(ref_sparse, u0, ids.cpu().numpy(), ref_ids, what="draft from q'")
+    # exact forms on a random row-stochastic kernel
+    if w.n * w.N <= 4_000_000:
+        M32 = synth.random_row_stochastic(rng, w.n, w.N).astype(np.float32)
+        ref_exact = oracle.redistribute_batch("exact", q64, data["kept_ids"], w.N, M=M32)
+        for fmt, tol in ((rdk.DENSE_F32, dict()), (rdk.DENSE_BF16, dict(rtol=RTOL_BF16 * 4, atol=1e-6))):
+            kd = rdk.rdk_build_kernel(w.N, kept, fmt, dense_M=dev(M32))
+            view, big = out_view()
+            rdk.rdk_redistribute_exact(kd, q_in, qk, out=view)
+            assert_close(view.cpu().numpy(), ref_exact, what="exact", **tol)
+            assert bool((big[:, w.N:] == sentinel).all()), "exact: wrote past the row"
+    # the inputs are untouched, padding included
+    assert bool(torch.isnan(p_big[:, w.N:].float()).all()) and bool(torch.isnan(q_big[:, w.n:].float()).all())
