@@ -140,7 +140,16 @@ def run_linear(args, rdk, synth, torch, w, vocab, batch, mode_name, path, steps,
         step_bytes = B * esz * (w.N + w.n) + (8 * (w.N - w.n) * kk if mode_name == "sparse" else 0)
     else:
         step_bytes = B * (esz * (w.n + w.N) + 8 * w.N) + (8 * (w.N - w.n) * kk if mode_name == "sparse" else B * esz * w.N)
-    return {"ms_per_step": ms_per_step, "value": B / (ms_per_step * 1e-3), "roofline": roofline,
+    res_extra = {}
+    if dominant == "sparse_product_kernel":
+        # what the kernel is limited by: 128-byte lines gathered from q^T through the vector L1 (one per neighbour and
+        # 32 positions), against 64 bytes per clock and compute unit (256 units, 2.4 GHz)
+        lines = (w.N - w.n) * kk * ((B + 31) // 32)
+        l1_peak = 256 * 64 * 2.4          # GB/s
+        res_extra["sparse_gather"] = {"lines_per_launch": lines, "achieved_GBs": round(lines * 128 / avg_s / 1e9, 1),
+                                      "vector_l1_peak_GBs": round(l1_peak, 1),
+                                      "frac": round(lines * 128 / avg_s / 1e9 / l1_peak, 4)}
+    return {"ms_per_step": ms_per_step, "value": B / (ms_per_step * 1e-3), "roofline": roofline, **res_extra,
             "kernels": {k: {"avg_us": round(v["avg_us"], 2), "per_step": v["launches_per_step"]} for k, v in per_kernel.items()},
             "step_algorithmic_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
             "step_frac_of_hbm_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -268,6 +277,8 @@ def main():
     extra = {k: r[k] for k in ("kernels", "step_algorithmic_GBs", "step_frac_of_hbm_peak", "kernel_build_s", "accept_rate",
                                "mean_alpha")}
     extra["input_gen_s"] = round(gen_s, 2)
+    if "sparse_gather" in r:
+        extra["sparse_gather"] = r["sparse_gather"]
     if not args.no_extra:
         other = "taylor" if args.mode == "sparse" else "sparse"
         torch.cuda.empty_cache()
@@ -275,6 +286,8 @@ def main():
         extra["other_linear_form"] = {"mode": other, "path": args.path, "positions_per_s": round(o["value"], 1),
                                       "ms_per_step": round(o["ms_per_step"], 5), "roofline": o["roofline"], "kernels": o["kernels"],
                                       "step_frac_of_hbm_peak": o["step_frac_of_hbm_peak"]}
+        if "sparse_gather" in o:
+            extra["other_linear_form"]["sparse_gather"] = o["sparse_gather"]
         extra["draft_sampling"] = run_draft(args, rdk, synth, torch, w, (bias, kept, E), batch, max(20, args.steps // 2))
         torch.cuda.empty_cache()
         extra["exact_bf16"] = run_exact(rdk, synth, torch, "dense256k", "bf16", calls=10)
