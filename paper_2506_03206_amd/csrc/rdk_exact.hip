@@ -311,6 +311,14 @@ __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t
 //   * requests run two (A) and three (B) stages ahead of the MFMAs; large batches use one wavefront per SIMD with
 //     the whole register file (accumulators in the AGPR half), which halves the LDS reads per MFMA.
 // M is streamed from HBM exactly once when all positions fit one row of workgroups (B <= 512).
+// A record of M: read exactly once per launch, so it is loaded non-temporally and leaves the L2 to the A records,
+// which every workgroup of an XCD reads again.
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 load_once(const bf16x8 *p)
+{
+    return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((const u32x4_t *)p));
+}
+
 template <int W, int RB>
 __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, const uint16_t *Mp, int KB, int N, int B,
                                                             const float *out_scale, float *out, int64_t ldo)
@@ -345,18 +353,25 @@ __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, 
     // it.  The B records come from HBM: they are requested three stages ahead and kept in a ring of registers.
     // The A records (L2) are requested two stages ahead, block by block as their registers fall free; the only
     // B request older than an A record at the time it is needed is then two whole stages old.
+    // The first requests are issued in the order the stages keep afterwards (A by slot block, at least as many
+    // requests behind every record as in the steady state): the wait counts the compiler derives for the first stages
+    // of the loop are the minimum over both ways into them, and a different order here would tighten them for good.
     bf16x8 a_even[RB][4], a_odd[RB][4], b_ring[3][RPW];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < RB; ++r) a_even[r][kb] = a_ptr[r][kb * 64];
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int t = 0; t < 3; ++t)
 #pragma unroll
-        for (int i = 0; i < RPW; ++i) b_ring[t][i] = b_src[i][(int64_t)min(t, stages - 1) * 4 * 64];
+        for (int i = 0; i < RPW; ++i) b_ring[t][i] = load_once(b_src[i] + (int64_t)min(t, stages - 1) * 4 * 64);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int r = 0; r < RB; ++r)
+    for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-            a_even[r][kb] = a_ptr[r][kb * 64];
-            a_odd[r][kb] = a_ptr[r][((int64_t)min(1, stages - 1) * 4 + kb) * 64];
-        }
+        for (int r = 0; r < RB; ++r) a_odd[r][kb] = a_ptr[r][((int64_t)min(1, stages - 1) * 4 + kb) * 64];
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < RPW; ++i) bbuf[0][b_rec[i]][lane] = b_ring[0][i];
     __syncthreads();
@@ -369,7 +384,7 @@ __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, 
     {                                                                                                                \
         const int cur = s & 1;                                                                                       \
         const int64_t sa = min(s + 2, stages - 1), sb = min(s + 3, stages - 1);                                      \
-        _Pragma("unroll") for (int i = 0; i < RPW; ++i) b_ring[SLOT][i] = b_src[i][sb * 4 * 64];                     \
+        _Pragma("unroll") for (int i = 0; i < RPW; ++i) b_ring[SLOT][i] = load_once(b_src[i] + sb * 4 * 64);         \
         __builtin_amdgcn_sched_barrier(0);                                                                           \
         bf16x8 bq[3];                        /* B fragments are read from LDS two MFMA groups ahead */               \
         bq[0] = bbuf[cur][0][lane];                                                                                  \
