@@ -79,6 +79,8 @@ def lib():
         L.orc_densify_sparse.restype = None
         L.orc_verify_position.argtypes = [_D, _D, _i64, _u64, _u64, ctypes.c_int, _I32, _U8, _D, _D, _I32]
         L.orc_verify_position.restype = None
+        L.orc_verify_multi.argtypes = [_D, _D, _i64, _i64, _u64, _u64, ctypes.c_int, _I32, _I32, _I32, _D]
+        L.orc_verify_multi.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -277,6 +279,31 @@ def verify_batch(p, q_prime, seed, offset, sample_draft=True, draft_ids=None, ga
     if gamma:
         out["n_accepted"], out["out_tokens"] = sequence_scan(acc, d, rid, gamma)
     return out
+
+
+def verify_multi_batch(p, q_prime, C, seed, offset, cand_ids=None):
+    """Several candidates per position (multi-step speculative sampling with q' as the drafter) for each row.
+
+    cand_ids [B,C] given -> they are verified instead of drawn.  Returns a dict of cand_ids [B,C], accepted [B]
+    (index of the accepted candidate, C if none), token [B], resid_mass [B,C]."""
+    p, qp = _f64(p), _f64(q_prime)
+    B, N = p.shape
+    cand = np.full((B, C), -1, np.int32) if cand_ids is None else _i32(cand_ids).copy().reshape(B, C)
+    acc, tok, rm = np.zeros(B, np.int32), np.zeros(B, np.int32), np.zeros((B, C))
+    L = lib()
+    for b in range(B):
+        rc = L.orc_verify_multi(_p(p[b], _D), _p(qp[b], _D), N, C, int(seed), int(offset) + b, 1 if cand_ids is None else 0,
+                                ctypes.cast(cand.ctypes.data + 4 * C * b, _I32), ctypes.cast(acc.ctypes.data + 4 * b, _I32),
+                                ctypes.cast(tok.ctypes.data + 4 * b, _I32), ctypes.cast(rm.ctypes.data + 8 * C * b, _D))
+        if rc != 0:
+            raise MemoryError("orc_verify_multi")
+    return dict(cand_ids=cand, accepted=acc, token=tok, resid_mass=rm)
+
+
+def multi_uniform(seed, index, m):
+    """The m-th uniform of a position in the multi-candidate stream: word m % 4 of Philox(counter=(index, m // 4, 0))."""
+    w = philox4x32_10([index & 0xFFFFFFFF, (index >> 32) & 0xFFFFFFFF, m // 4, 0], [seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF])
+    return float(int(w[m % 4]) >> 8) / 16777216.0
 
 
 def probs_from(x, kind):

@@ -16,7 +16,9 @@
  * identities of Lemma 2.3; Thm 4.1, Thm 4.2, Lemma B.1 inequalities; identity
  * kernel == TLI; library softmax / matmul on the same data; closed forms of
  * Eq. 3; Monte-Carlo acceptance and losslessness of Alg. 4; published
- * known-answer vectors of Philox4x32-10.
+ * known-answer vectors of Philox4x32-10; verification of several candidates:
+ * its reduction to Alg. 4 with one candidate, a hand-computed example, and the
+ * law of the emitted token (equal to p).
  * Parity unpinned: none of the functions below is without a pin; the size of the
  * exact-vs-first-order gap (Thm 4.4) is only reported, since the theorem's
  * constants are not given.
@@ -386,4 +388,69 @@ void orc_verify_position(const double *p, const double *q_prime, int64_t N, uint
     int32_t dtok = *draft_id;
     *accept = (dtok >= 0 && dtok < N) ? (uint8_t)orc_accept(u[1], q_prime[dtok], p[dtok]) : 0;
     *resid_id = (*resid_mass > 0.0) ? (int32_t)orc_sample_residual(p, q_prime, N, u[2]) : -1;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Verification of SEVERAL candidates for one position.  The paper names      */
+/* multi-candidate (tree) verification only among the related work of its     */
+/* introduction; the routine follows the publication cited there (Miao et     */
+/* al., "SpecInfer", ASPLOS 2024: multi-step speculative sampling) with the   */
+/* redistributed drafter q' in the drafter's place.  In that paper's steps:   */
+/*   r <- p                                                                    */
+/*   for i = 0 .. C-1:  x_i ~ q' (or the caller's);  accept x_i with           */
+/*        probability min(1, r(x_i) / q'(x_i));  on acceptance emit x_i, stop; */
+/*        otherwise  r <- normalize(max(0, r - q'))                            */
+/*   no candidate accepted: emit t ~ r.                                        */
+/* With C = 1 this is steps 2 and 6-8 of Alg. 4.  The emitted token follows p  */
+/* exactly (the pin of this routine).                                          */
+/* Uniforms: the m-th uniform of a position is word m % 4 of the Philox block  */
+/* with counter (index, m / 4, 0); m = i for the draw of candidate i, C + i    */
+/* for its acceptance test, 2C for the final draw (C = 1: the words of         */
+/* orc_uniforms in the order draft, accept, residual).                         */
+/* Outputs: cand_ids[C] (written when sampled), *accepted = index of the       */
+/* accepted candidate or C, *token = emitted id (-1 when the last residual is  */
+/* empty), resid_mass[C] = sum of max(0, r - q') after each rejection (0 for   */
+/* rounds that were not reached).  Returns 0, or -2 when memory runs out.      */
+static double multi_uniform(uint64_t seed, uint64_t index, int64_t m)
+{
+    uint32_t ctr[4] = {(uint32_t)index, (uint32_t)(index >> 32), (uint32_t)(m / 4), 0u};
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t w[4];
+    orc_philox4x32_10(ctr, key, w);
+    return (double)(w[m % 4] >> 8) * (1.0 / 16777216.0);
+}
+
+int orc_verify_multi(const double *p, const double *q_prime, int64_t N, int64_t C, uint64_t seed,
+                     uint64_t index, int sample_candidates, int32_t *cand_ids, int32_t *accepted,
+                     int32_t *token, double *resid_mass)
+{
+    double *r = (double *)malloc((size_t)N * sizeof(double));
+    if (!r) return -2;
+    for (int64_t j = 0; j < N; ++j) r[j] = p[j];
+    for (int64_t i = 0; i < C; ++i) resid_mass[i] = 0.0;
+    if (sample_candidates)
+        for (int64_t i = 0; i < C; ++i)
+            cand_ids[i] = (int32_t)orc_sample_cdf(q_prime, N, multi_uniform(seed, index, i));
+    *accepted = (int32_t)C;
+    *token = -1;
+    for (int64_t i = 0; i < C; ++i) {
+        int32_t x = cand_ids[i];
+        if (x >= 0 && x < N && orc_accept(multi_uniform(seed, index, C + i), q_prime[x], r[x])) {
+            *accepted = (int32_t)i;
+            *token = x;
+            free(r);
+            return 0;
+        }
+        double Z = 0.0;
+        for (int64_t j = 0; j < N; ++j) {
+            r[j] = r[j] > q_prime[j] ? r[j] - q_prime[j] : 0.0;
+            Z += r[j];
+        }
+        resid_mass[i] = Z;
+        if (Z > 0.0)
+            for (int64_t j = 0; j < N; ++j) r[j] /= Z;
+    }
+    *token = (int32_t)orc_sample_cdf(r, N, multi_uniform(seed, index, 2 * C));
+    free(r);
+    return 0;
 }

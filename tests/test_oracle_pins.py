@@ -408,3 +408,72 @@ def test_features_from_scores_give_the_correlation_matrix():
     M = oracle.build_dense(F, kept, tau)
     e = np.exp((corr[kept] - 1.0) / tau)
     assert np.abs(M - e / e.sum(1, keepdims=True)).max() < 1e-12
+
+
+# --------------------------------------------------------------------------- several candidates per position
+def test_multi_candidate_with_one_candidate_is_alg4():
+    """C = 1: the same draft, the same accept decision and the same residual token as Alg. 4, position by position."""
+    rng = np.random.default_rng(21)
+    N, B = 40, 300
+    P = np.stack([rand_dist(rng, N, 3) for _ in range(B)])
+    Q = np.stack([rand_dist(rng, N, 3) for _ in range(B)])
+    one = oracle.verify_batch(P, Q, seed=77, offset=123, sample_draft=True)
+    multi = oracle.verify_multi_batch(P, Q, 1, seed=77, offset=123)
+    assert np.array_equal(multi["cand_ids"][:, 0], one["draft_ids"])
+    assert np.array_equal(multi["accepted"] == 0, one["accept"] == 1)
+    assert np.array_equal(multi["token"], np.where(one["accept"] == 1, one["draft_ids"], one["resid_ids"]))
+    rej = one["accept"] == 0
+    np.testing.assert_allclose(multi["resid_mass"][rej, 0], one["resid_mass"][rej], rtol=1e-14)
+
+
+def test_multi_candidate_hand_example():
+    """N = 3, p = (1/2, 3/10, 1/5), q' = (1/5, 1/5, 3/5), candidates (2, 2), by hand from the published steps:
+    round 0 keeps id 2 with probability (1/5)/(3/5) = 1/3; else r = (3/10, 1/10, 0)/(2/5) = (3/4, 1/4, 0);
+    round 1 never keeps id 2 (r(2) = 0); then r = (11/20, 1/20, 0)/(3/5) = (11/12, 1/12, 0), from which the token is drawn.
+    Candidates (2, 0): round 1 always keeps id 0 (r(0)/q'(0) = 15/4 > 1)."""
+    p, q = np.array([[0.5, 0.3, 0.2]]), np.array([[0.2, 0.2, 0.6]])
+    n_acc0 = n_tok0 = n_rej = 0
+    for idx in range(3000):
+        u_acc0, u_fin = oracle.multi_uniform(5, idx, 2), oracle.multi_uniform(5, idx, 4)
+        r = oracle.verify_multi_batch(p, q, 2, seed=5, offset=idx, cand_ids=[[2, 2]])
+        if u_acc0 < 1 / 3 - 1e-9:
+            assert r["accepted"][0] == 0 and r["token"][0] == 2 and not r["resid_mass"].any()
+            n_acc0 += 1
+        elif u_acc0 > 1 / 3 + 1e-9:
+            n_rej += 1
+            assert r["accepted"][0] == 2
+            np.testing.assert_allclose(r["resid_mass"][0], [0.4, 0.6], rtol=1e-14)
+            assert r["token"][0] == (0 if u_fin < 11 / 12 - 1e-9 else 1 if u_fin > 11 / 12 + 1e-9 else r["token"][0])
+            n_tok0 += r["token"][0] == 0
+            r2 = oracle.verify_multi_batch(p, q, 2, seed=5, offset=idx, cand_ids=[[2, 0]])
+            assert r2["accepted"][0] == 1 and r2["token"][0] == 0
+            np.testing.assert_allclose(r2["resid_mass"][0], [0.4, 0.0], rtol=1e-14)
+    assert abs(n_acc0 / 3000 - 1 / 3) < 4 * math.sqrt(2 / 9 / 3000)
+    assert abs(n_tok0 / n_rej - 11 / 12) < 4 * math.sqrt(11 / 144 / n_rej)
+
+
+@pytest.mark.parametrize("C", [2, 4])
+def test_multi_candidate_losslessness(C):
+    """The emitted token follows p whatever q' is (the property the published method is built for); more candidates
+    raise the chance that one of them is kept; p = q' keeps the first candidate always."""
+    rng = np.random.default_rng(30 + C)
+    N, trials = 9, 150000
+    p = rand_dist(rng, N, 2)
+    qp = rand_dist(rng, N, 2)
+    qp[rng.integers(0, N)] = 0.0                          # an id the drafter never proposes
+    qp /= qp.sum()
+    P, Q = np.broadcast_to(p, (trials, N)), np.broadcast_to(qp, (trials, N))
+    res = oracle.verify_multi_batch(P, Q, C, seed=4321, offset=7_000_000_000)
+    count = np.bincount(res["token"], minlength=N)
+    assert np.all(count[p == 0] == 0)
+    chi = ((count - trials * p)[p > 0] ** 2 / (trials * p[p > 0])).sum()
+    assert chi < 40                                       # <= 8 dof, P ~ 1e-5
+    ccount = np.bincount(res["cand_ids"].ravel(), minlength=N)
+    chi_c = ((ccount - trials * C * qp)[qp > 0] ** 2 / (trials * C * qp[qp > 0])).sum()
+    assert chi_c < 40
+    alpha = oracle.overlap(p, qp)[0]
+    kept_first = (res["accepted"] == 0).mean()
+    assert abs(kept_first - alpha) < 4 * math.sqrt(alpha * (1 - alpha) / trials)
+    assert (res["accepted"] < C).mean() > kept_first + 0.01
+    same = oracle.verify_multi_batch(P[:2000], P[:2000], C, seed=1, offset=0)
+    assert not same["accepted"].any() and np.array_equal(same["token"], same["cand_ids"][:, 0])
