@@ -242,6 +242,35 @@ rdk_status_t rdk_sample_draft(const rdk_kernel_t *kernel, const void *q, rdk_inp
                               uint64_t seed, uint64_t offset, int32_t *draft_ids, float *q_draft, float *q_prime,
                               int64_t ldo, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Verification of several candidates per position.  The paper's introduction (Sec. 1) names multi-candidate / tree
+ * verification among the related work; the steps are those of the method cited there (multi-step speculative
+ * sampling) with the redistributed drafter q' in the drafter's place, per position b:
+ *   r <- p_b;  for i = 0 .. C-1:  candidate x_i;  keep x_i when  u * q'_b(x_i) < r(x_i)  and stop;
+ *              otherwise  r <- max(0, r - q'_b) / sum_j max(0, r(j) - q'_b(j));
+ *   no candidate kept:  t drawn from r by the inverse CDF (smallest j whose prefix exceeds u * total).
+ * With C = 1 this is rdk_verify_sample for one position (same draft, same decision, same residual token).  The
+ * emitted token follows p_b exactly whatever q'_b is.
+ *   sample_candidates = 1: the C candidates are drawn from q'_b by the inverse CDF and written to cand_ids;
+ *   sample_candidates = 0: cand_ids [B, C] is input (an id outside [0, N) is never kept).
+ * Uniforms: the m-th uniform of position b is word m % 4 of Philox4x32-10 with key = seed and counter
+ * (offset + b as two words, m / 4, 0);  m = i for the draw of candidate i, C + i for its test, 2C for the final draw.
+ * Outputs (device): accepted [B] = index of the kept candidate, or C; token [B] = the emitted id (-1 when the last
+ * residual is empty); resid_mass [B, C] (optional) = sum_j max(0, r(j) - q'_b(j)) after each rejection, 0 for rounds
+ * that were not reached.  p [B, ldp] of kind p_kind, q_prime [B, ldq] fp32; 1 <= C <= 16, N <= 2 097 152.
+ * Errors: RDK_ERR_NULL, RDK_ERR_SHAPE (B, N, C, strides), RDK_ERR_DTYPE, RDK_ERR_ALIGN (rows not 16-byte aligned),
+ * RDK_ERR_UNSUPPORTED (N or C above the limits), RDK_ERR_WORKSPACE, RDK_ERR_HIP.
+ */
+typedef struct {
+    int32_t B, N, C;            /* positions, target ids, candidates per position */
+    uint64_t seed, offset;      /* Philox key and counter base */
+    int sample_candidates;      /* 1: draw the candidates from q_prime; 0: cand_ids is input */
+} rdk_multi_desc_t;
+rdk_status_t rdk_verify_multi_workspace_bytes(const rdk_multi_desc_t *desc, rdk_input_kind_t p_kind, size_t *bytes);
+rdk_status_t rdk_verify_multi(const rdk_multi_desc_t *desc, const void *p, rdk_input_kind_t p_kind, int64_t ldp,
+                              const float *q_prime, int64_t ldq, int32_t *cand_ids, int32_t *accepted, int32_t *token,
+                              float *resid_mass, void *workspace, size_t workspace_bytes, void *stream);
+
 /* The four Philox words of `count` consecutive positions, [count, 4] uint32 on the device (for
  * checking the random stream against an independent implementation). */
 rdk_status_t rdk_philox_words(uint64_t seed, uint64_t offset, int32_t count, uint32_t *words,
@@ -254,7 +283,7 @@ rdk_status_t rdk_philox_words(uint64_t seed, uint64_t offset, int32_t count, uin
  * recorded events of that kernel, returns how many launches were recorded and their summed
  * elapsed time in milliseconds, and forgets them.  Both take HOST strings.  Names:
  * row_stats_kernel, row_block_sums_kernel, verify_stream_kernel, verify_finalize_kernel, draft_finalize_kernel,
- * sequence_scan_kernel, taylor_stats_kernel, taylor_write_kernel, tli_scatter_kernel,
+ * sequence_scan_kernel, taylor_stats_kernel, taylor_write_kernel, tli_scatter_kernel, verify_multi_kernel,
  * q_transpose_kernel, sparse_product_kernel, prep_a_split_kernel, exact_f32_split_kernel,
  * exact_reduce_kernel, prep_a_bf16_kernel, exact_bf16_kernel.
  */

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librdk_hip.so")
 CEILINGS = os.path.join(HERE, "ceilings")    # stand-alone microbenchmark of HBM and matrix-instruction rates
-SOURCES = ["rdk_api.hip", "rdk_build.hip", "rdk_linear.hip", "rdk_sparse.hip", "rdk_exact.hip", "rdk_verify.hip"]
+SOURCES = ["rdk_api.hip", "rdk_build.hip", "rdk_linear.hip", "rdk_sparse.hip", "rdk_exact.hip", "rdk_verify.hip", "rdk_multi.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
          # packed fp32 instructions are kept off for every device function
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -479,6 +479,40 @@ rdk_status_t rdk_verify_sample(const rdk_verify_desc_t *desc, const void *p, rdk
                          workspace, (hipStream_t)stream);
 }
 
+static rdk_status_t check_multi_desc(const rdk_multi_desc_t *d)
+{
+    if (!d) return RDK_ERR_NULL;
+    if (d->B <= 0 || d->N <= 0 || d->C <= 0) return RDK_ERR_SHAPE;
+    if (d->C > multi_max_candidates() || d->N > multi_max_ids()) return RDK_ERR_UNSUPPORTED;
+    return RDK_OK;
+}
+
+rdk_status_t rdk_verify_multi_workspace_bytes(const rdk_multi_desc_t *desc, rdk_input_kind_t p_kind, size_t *bytes)
+{
+    if (!bytes) return RDK_ERR_NULL;
+    rdk_status_t rc = check_multi_desc(desc);
+    if (rc != RDK_OK) return rc;
+    if (!kind_ok(p_kind)) return RDK_ERR_DTYPE;
+    *bytes = multi_workspace_bytes(*desc, p_kind) + 256;
+    return RDK_OK;
+}
+
+rdk_status_t rdk_verify_multi(const rdk_multi_desc_t *desc, const void *p, rdk_input_kind_t p_kind, int64_t ldp,
+                              const float *q_prime, int64_t ldq, int32_t *cand_ids, int32_t *accepted, int32_t *token,
+                              float *resid_mass, void *workspace, size_t workspace_bytes, void *stream)
+{
+    rdk_status_t rc = check_multi_desc(desc);
+    if (rc != RDK_OK) return rc;
+    rc = check_rows(p, p_kind, ldp, desc->N);
+    if (rc != RDK_OK) return rc;
+    if (!q_prime || !cand_ids || !accepted || !token || !workspace) return RDK_ERR_NULL;
+    if (ldq < desc->N) return RDK_ERR_SHAPE;
+    if (!aligned16(q_prime) || !aligned16(workspace)) return RDK_ERR_ALIGN;
+    if (workspace_bytes < multi_workspace_bytes(*desc, p_kind)) return RDK_ERR_WORKSPACE;
+    RowInput pi{p, p_kind, ldp};
+    return launch_verify_multi(*desc, pi, q_prime, ldq, cand_ids, accepted, token, resid_mass, workspace, (hipStream_t)stream);
+}
+
 rdk_status_t rdk_redistribute_verify_workspace_bytes(const rdk_kernel_t *kernel, rdk_linear_mode_t mode,
                                                      const rdk_verify_desc_t *desc, size_t *bytes)
 {

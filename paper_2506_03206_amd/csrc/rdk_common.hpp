@@ -133,6 +133,13 @@ rdk_status_t launch_unpack_bf16(const KernelHandle &h, float *M, int64_t ldm, hi
 rdk_status_t launch_exact(const KernelHandle &h, RowInput q, int32_t B, float *out, int64_t ldo, void *ws,
                           hipStream_t st);
 
+// rdk_multi.hip
+int multi_max_ids();
+int multi_max_candidates();
+size_t multi_workspace_bytes(const rdk_multi_desc_t &d, rdk_input_kind_t p_kind);
+rdk_status_t launch_verify_multi(const rdk_multi_desc_t &d, RowInput p, const float *q_prime, int64_t ldq, int32_t *cand_ids,
+                                 int32_t *accepted, int32_t *token, float *resid_mass, void *ws, hipStream_t st);
+
 // rdk_verify.hip
 size_t verify_workspace_bytes(const rdk_verify_desc_t &d);
 rdk_status_t launch_verify(const rdk_verify_desc_t &d, RowInput p, const float *q_prime, int64_t ldq,

@@ -24,6 +24,7 @@ EXPORTS = [
     "rdk_redistribute_linear", "rdk_verify_workspace_bytes", "rdk_verify_sample", "rdk_philox_words",
     "rdk_timing_select", "rdk_timing_read", "rdk_redistribute_verify_workspace_bytes", "rdk_redistribute_verify",
     "rdk_sample_draft_workspace_bytes", "rdk_sample_draft", "rdk_features_from_scores",
+    "rdk_verify_multi_workspace_bytes", "rdk_verify_multi",
 ]
 
 
@@ -37,6 +38,11 @@ class KernelDesc(ctypes.Structure):
 class VerifyDesc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("N", ctypes.c_int32), ("gamma", ctypes.c_int32),
                 ("sample_draft", ctypes.c_int32), ("seed", ctypes.c_uint64), ("offset", ctypes.c_uint64)]
+
+
+class MultiDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("N", ctypes.c_int32), ("C", ctypes.c_int32), ("seed", ctypes.c_uint64),
+                ("offset", ctypes.c_uint64), ("sample_candidates", ctypes.c_int)]
 
 
 class RdkError(RuntimeError):
@@ -83,6 +89,8 @@ def lib():
         L.rdk_sample_draft_workspace_bytes.argtypes = [vp, i32, psz]
         L.rdk_sample_draft.argtypes = [vp, vp, ctypes.c_int, i64, i32, ctypes.c_uint64, ctypes.c_uint64, vp, vp, vp, i64, vp, sz, vp]
         L.rdk_features_from_scores.argtypes = [vp, ctypes.c_int, i64, i32, i32, vp, i64, vp]
+        L.rdk_verify_multi_workspace_bytes.argtypes = [ctypes.POINTER(MultiDesc), ctypes.c_int, psz]
+        L.rdk_verify_multi.argtypes = [ctypes.POINTER(MultiDesc), vp, ctypes.c_int, i64, vp, i64, vp, vp, vp, vp, vp, sz, vp]
         L.rdk_timing_select.argtypes = [ctypes.c_char_p]
         L.rdk_timing_read.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
         for name in EXPORTS:
@@ -298,6 +306,36 @@ def rdk_sample_draft(kernel, q, seed, offset=0, q_kind="prob", q_prime=None, dra
                                   _ptr(q_draft), _ptr(q_prime), ldo, _ptr(kernel._draft_ws), kernel._draft_ws.numel(),
                                   _stream()), "rdk_sample_draft")
     return draft_ids, q_draft
+
+
+class MultiOutputs:
+    """Outputs of rdk_verify_multi: cand_ids [B,C], accepted [B], token [B], resid_mass [B,C]."""
+
+    def __init__(self, B, C, device):
+        self.cand_ids = torch.full((B, C), -1, dtype=torch.int32, device=device)
+        self.accepted = torch.zeros(B, dtype=torch.int32, device=device)
+        self.token = torch.full((B,), -1, dtype=torch.int32, device=device)
+        self.resid_mass = torch.zeros((B, C), dtype=torch.float32, device=device)
+        self.ws = None
+
+
+def rdk_verify_multi(p, q_prime, C, seed, offset=0, p_kind="prob", cand_ids=None, outputs=None):
+    """Several candidates per position: kept candidate (or the residual draw) for every row.
+    cand_ids [B,C] given -> they are verified instead of drawn from q_prime."""
+    B, N = p.shape
+    o = outputs or MultiOutputs(B, C, p.device)
+    if cand_ids is not None:
+        o.cand_ids.copy_(cand_ids.reshape(B, C))
+    d = MultiDesc(B=B, N=N, C=C, seed=seed, offset=offset, sample_candidates=0 if cand_ids is not None else 1)
+    kind = _kind_of(p, p_kind)
+    need = ctypes.c_size_t()
+    _check(lib().rdk_verify_multi_workspace_bytes(ctypes.byref(d), kind, ctypes.byref(need)), "rdk_verify_multi_workspace_bytes")
+    if o.ws is None or o.ws.numel() < need.value:
+        o.ws = torch.empty(need.value, dtype=torch.uint8, device=p.device)
+    _check(lib().rdk_verify_multi(ctypes.byref(d), _ptr(p), kind, _rows(p), _ptr(q_prime), _rows(q_prime), _ptr(o.cand_ids),
+                                  _ptr(o.accepted), _ptr(o.token), _ptr(o.resid_mass), _ptr(o.ws), o.ws.numel(), _stream()),
+           "rdk_verify_multi")
+    return o
 
 
 def rdk_philox_words(seed, offset, count, device="cuda"):

@@ -845,3 +845,112 @@ def test_random_shapes_with_padded_rows(rdk, seed):
             assert bool((big[:, w.N:] == sentinel).all()), "exact: wrote past the row"
     # the inputs are untouched, padding included
     assert bool(torch.isnan(p_big[:, w.N:].float()).all()) and bool(torch.isnan(q_big[:, w.n:].float()).all())
+
+
+# --------------------------------------------------------------------------------------------- several candidates per position
+def multi_chain(p, q, cand, seed, index):
+    """fp64 walk through the rounds of one position for given candidates: per round the two sides of the test
+    u q'(x) < r(x); then the weights of the final draw and its uniform.  Only used to tell near-ties apart."""
+    C = len(cand)
+    r = p.copy()
+    tests = []
+    for i, x in enumerate(cand):
+        u = oracle.multi_uniform(seed, index, C + i)
+        tests.append((u * q[x], r[x]) if 0 <= x < p.size else (1.0, 0.0))
+        r = np.maximum(r - q, 0.0)
+        z = r.sum()
+        if z > 0:
+            r = r / z
+    return tests, r, oracle.multi_uniform(seed, index, 2 * C)
+
+
+def check_multi(o, ref, p64, q64, seed, offset, C, min_exact=0.9):
+    """Device outputs of rdk_verify_multi (same candidates on both sides) against the oracle's."""
+    g_acc, g_tok, g_rm = o.accepted.cpu().numpy(), o.token.cpu().numpy(), o.resid_mass.cpu().numpy()
+    exact = 0
+    for b in range(p64.shape[0]):
+        cand = ref["cand_ids"][b]
+        if g_acc[b] == ref["accepted"][b] and g_tok[b] == ref["token"][b]:
+            exact += 1
+            nrej = int(g_acc[b])                     # rejections before the kept candidate (all C when none was kept)
+            if nrej:
+                assert_close(g_rm[b, :nrej], ref["resid_mass"][b, :nrej], rtol=5e-5, atol=1e-7, what="residual mass per round")
+            assert not g_rm[b, nrej:].any()
+            continue
+        tests, r_fin, u_fin = multi_chain(p64[b], q64[b], cand, seed, offset + b)
+        first = min(int(g_acc[b]), int(ref["accepted"][b]))
+        if g_acc[b] != ref["accepted"][b]:          # a decision flipped: it must have been a near-tie
+            lhs, rhs = tests[first]
+            assert abs(lhs - rhs) <= 5e-5 * max(rhs, 1e-30), (b, first, lhs, rhs)
+        else:                                       # same rounds, another final token: a prefix-sum step on the threshold
+            assert g_acc[b] == C
+            check_sampled_ids(r_fin[None], np.array([u_fin]), g_tok[b:b + 1], ref["token"][b:b + 1], tol=5e-5, what="final draw")
+    assert exact >= min_exact * p64.shape[0], exact
+    return exact
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+@pytest.mark.parametrize("p_kind", ["prob", "logit"])
+@pytest.mark.parametrize("C", [1, 3, 6])
+def test_verify_multi(rdk, tiny, ragged, case, p_kind, C):
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    idx, wt, sw = data["sparse"]
+    qp32 = oracle_rows(data, "sparse", kernel=(idx, wt.astype(np.float32), sw.astype(np.float32))).astype(np.float32)
+    q64 = qp32.astype(np.float64)
+    p64 = data["p"].astype(np.float64) if p_kind == "prob" else oracle.probs_from(data["z_p"], "logit")
+    p_in = dev(data["p"]) if p_kind == "prob" else dev(data["z_p"])
+    seed, offset = 900 + C, (1 << 33) + 5
+    ref = oracle.verify_multi_batch(p64, q64, C, seed, offset)
+    # candidates drawn by the library: each is the inverse-CDF draw of q' under its own uniform
+    o = rdk.rdk_verify_multi(p_in, dev(qp32), C, seed, offset, p_kind)
+    g_cand = o.cand_ids.cpu().numpy()
+    for i in range(C):
+        us = np.array([oracle.multi_uniform(seed, offset + b, i) for b in range(w.B)])
+        check_sampled_ids(q64, us, g_cand[:, i], ref["cand_ids"][:, i], what="candidate %d" % i)
+    if np.array_equal(g_cand, ref["cand_ids"]):
+        check_multi(o, ref, p64, q64, seed, offset, C)
+    # the oracle's candidates handed to the library: the rounds alone
+    o2 = rdk.rdk_verify_multi(p_in, dev(qp32), C, seed, offset, p_kind, cand_ids=dev(ref["cand_ids"]))
+    assert np.array_equal(o2.cand_ids.cpu().numpy(), ref["cand_ids"])
+    check_multi(o2, ref, p64, q64, seed, offset, C)
+    # candidates that can never be kept (outside the vocabulary, or without drafter mass): all rounds, then the residual
+    bad = np.full((w.B, C), -1, np.int32)
+    bad[:, ::2] = w.N + 7
+    ref3 = oracle.verify_multi_batch(p64, q64, C, seed, offset, cand_ids=bad)
+    o3 = rdk.rdk_verify_multi(p_in, dev(qp32), C, seed, offset, p_kind, cand_ids=dev(bad))
+    assert (o3.accepted.cpu().numpy() == C).all() and (ref3["accepted"] == C).all()
+    check_multi(o3, ref3, p64, q64, seed, offset, C, min_exact=0.8)
+
+
+def test_verify_multi_with_one_candidate_is_verify_sample(rdk, ragged):
+    """C = 1 through the new entry point and Alg. 4 through rdk_verify_sample: same draft, decision and token."""
+    w = ragged["w"]
+    idx, wt, sw = ragged["sparse"]
+    qp32 = oracle_rows(ragged, "sparse", kernel=(idx, wt.astype(np.float32), sw.astype(np.float32))).astype(np.float32)
+    p, qp = dev(ragged["p"]), dev(qp32)
+    one = rdk.rdk_verify_sample(p, qp, 55, 9, 0)
+    multi = rdk.rdk_verify_multi(p, qp, 1, 55, 9)
+    torch.cuda.synchronize()
+    assert torch.equal(multi.cand_ids[:, 0], one.draft_ids)
+    assert torch.equal(multi.accepted == 0, one.accept == 1)
+    assert torch.equal(multi.token, torch.where(one.accept == 1, one.draft_ids, one.resid_ids))
+
+
+def test_verify_multi_edges_and_errors(rdk, tiny):
+    w = tiny["w"]
+    p = dev(tiny["p"])
+    # p = q': the first candidate is always kept
+    o = rdk.rdk_verify_multi(p, p, 4, 3, 0)
+    assert not o.accepted.any() and torch.equal(o.token, o.cand_ids[:, 0]) and not o.resid_mass.any()
+    # a drafter row without mass: no candidate (-1), the token is drawn from p itself (first residual = p)
+    zero = torch.zeros_like(p)
+    o = rdk.rdk_verify_multi(p, zero, 2, 3, 0)
+    ref = oracle.verify_multi_batch(tiny["p"].astype(np.float64), np.zeros((w.B, w.N)), 2, 3, 0)
+    assert (o.cand_ids.cpu().numpy() == -1).all() and (ref["cand_ids"] == -1).all()
+    assert (o.accepted.cpu().numpy() == 2).all()
+    check_multi(o, ref, tiny["p"].astype(np.float64), np.zeros((w.B, w.N)), 3, 0, 2)
+    for kwargs, status in ((dict(C=0), 2), (dict(C=17), 7)):
+        with pytest.raises(rdk.RdkError) as e:
+            rdk.rdk_verify_multi(p, p, kwargs["C"], 1, 0)
+        assert e.value.status == status
