@@ -184,6 +184,47 @@ def run_draft(args, rdk, synth, torch, w, vocab, batch, steps):
             "positions_per_s": round(w.B / (ms * 1e-3), 1)}
 
 
+def run_multi(args, rdk, synth, torch, w, vocab, batch, steps, C=4):
+    """Several candidates per position (rdk_verify_multi) on the materialised rows of the sparse form: the candidates
+    drawn from q', then one pass over p and q' per rejected candidate."""
+    bias, kept, E = vocab
+    dev = torch.device("cuda:0")
+    kern = rdk.rdk_build_kernel(w.N, torch.from_numpy(kept).to(dev), rdk.SPARSE_TOPK, embeddings=torch.from_numpy(E).to(dev),
+                                tau=w.tau, k=w.k)
+    if w.logits_bf16:
+        p_host, q_host, kind = torch.from_numpy(batch["z_p"]).to(torch.bfloat16), torch.from_numpy(batch["z_q"]).to(torch.bfloat16), "logit"
+    else:
+        p_host, q_host, kind = torch.from_numpy(batch["p"]), torch.from_numpy(batch["q_hat"]), "prob"
+    n_copies = max(1, args.copies)
+    ps = [p_host.to(dev) for _ in range(n_copies)]
+    qp = [rdk.rdk_redistribute_linear(kern, rdk.LINEAR_SPARSE, q_host.to(dev), kind) for _ in range(n_copies)]
+    out = rdk.MultiOutputs(w.B, C, dev)
+    for i in range(5):
+        rdk.rdk_verify_multi(ps[i % n_copies], qp[i % n_copies], C, 2506, i * w.B, kind, outputs=out)
+    torch.cuda.synchronize()
+    rdk.rdk_timing_select("verify_multi_kernel")
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for i in range(steps):
+        rdk.rdk_verify_multi(ps[i % n_copies], qp[i % n_copies], C, 2506, i * w.B, kind, outputs=out)
+    stop.record()
+    torch.cuda.synchronize()
+    rdk.rdk_timing_select(None)
+    ms = start.elapsed_time(stop) / steps
+    cnt, kms = rdk.rdk_timing_read("verify_multi_kernel")
+    # passes of the last step: one over q' for the candidates, one over p and q' per rejection
+    rejections = float(torch.minimum(out.accepted, torch.full_like(out.accepted, C)).float().mean().item())
+    esz = 2 if w.logits_bf16 else 4
+    alg = w.B * (4.0 * w.N + rejections * (4.0 + esz) * w.N)
+    gbs = alg / (kms / cnt * 1e-3) / 1e9
+    return {"entry": "rdk_verify_multi, C=%d candidates per position, q' materialised" % C, "ms_per_step": round(ms, 5),
+            "positions_per_s": round(w.B / (ms * 1e-3), 1), "mean_rejections_per_position": round(rejections, 3),
+            "kept_one_of_C": round(float((out.accepted < C).float().mean().item()), 4),
+            "roofline": {"kernel": "verify_multi_kernel", "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                         "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                         "avg_launch_us": round(kms / cnt * 1e3, 2), "algorithmic_bytes_per_launch": alg}}
+
+
 def run_exact(rdk, synth, torch, wname, fmt, calls=5):
     """Exact dense redistribution (Alg. 1 with the full M): bf16 MFMA contraction at N=256000, n=32000, B=512 (bound by
     the matrix cores), or the fp32 one at N=32000, n=8000, B=64 (three bf16 parts per operand on the bf16 matrix cores:
@@ -289,6 +330,7 @@ def main():
         if "sparse_gather" in o:
             extra["other_linear_form"]["sparse_gather"] = o["sparse_gather"]
         extra["draft_sampling"] = run_draft(args, rdk, synth, torch, w, (bias, kept, E), batch, max(20, args.steps // 2))
+        extra["multi_candidate"] = run_multi(args, rdk, synth, torch, w, (bias, kept, E), batch, max(20, args.steps // 4))
         torch.cuda.empty_cache()
         extra["exact_bf16"] = run_exact(rdk, synth, torch, "dense256k", "bf16", calls=10)
         extra["exact_f32"] = run_exact(rdk, synth, torch, "n32k", "f32", calls=20)

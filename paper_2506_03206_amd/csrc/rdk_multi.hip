@@ -17,7 +17,7 @@ namespace rdk {
 
 namespace {
 
-constexpr int kMultiThreads = 512;
+constexpr int kMultiThreads = 1024;
 constexpr int kMultiWaves = kMultiThreads / kWave;
 constexpr int kMultiMaxBlocks = 2048;      // 1024-id blocks of a row held in LDS
 constexpr int kMultiMaxCandidates = 16;

@@ -71,3 +71,44 @@ def check_verify_outputs(o, ref, p64, q64, seed, offset, gamma, p_kind, min_exac
         assert np.array_equal(o.out_tokens.cpu().numpy(), toks)
         if same.all() and np.array_equal(g_acc, ref["accept"]) and np.array_equal(g_resid, ref["resid_ids"]):
             assert np.array_equal(o.out_tokens.cpu().numpy(), ref["out_tokens"])
+
+
+def multi_chain(p, q, cand, seed, index):
+    """fp64 walk through the rounds of one position for given candidates: per round the two sides of the test
+    u q'(x) < r(x); then the weights of the final draw and its uniform.  Only used to tell near-ties apart."""
+    C = len(cand)
+    r = p.copy()
+    tests = []
+    for i, x in enumerate(cand):
+        u = oracle.multi_uniform(seed, index, C + i)
+        tests.append((u * q[x], r[x]) if 0 <= x < p.size else (1.0, 0.0))
+        r = np.maximum(r - q, 0.0)
+        z = r.sum()
+        if z > 0:
+            r = r / z
+    return tests, r, oracle.multi_uniform(seed, index, 2 * C)
+
+
+def check_multi(o, ref, p64, q64, seed, offset, C, min_exact=0.9):
+    """Device outputs of rdk_verify_multi (same candidates on both sides) against the oracle's."""
+    g_acc, g_tok, g_rm = o.accepted.cpu().numpy(), o.token.cpu().numpy(), o.resid_mass.cpu().numpy()
+    exact = 0
+    for b in range(p64.shape[0]):
+        cand = ref["cand_ids"][b]
+        if g_acc[b] == ref["accepted"][b] and g_tok[b] == ref["token"][b]:
+            exact += 1
+            nrej = int(g_acc[b])                     # rejections before the kept candidate (all C when none was kept)
+            if nrej:
+                assert_close(g_rm[b, :nrej], ref["resid_mass"][b, :nrej], rtol=5e-5, atol=1e-7, what="residual mass per round")
+            assert not g_rm[b, nrej:].any()
+            continue
+        tests, r_fin, u_fin = multi_chain(p64[b], q64[b], cand, seed, offset + b)
+        first = min(int(g_acc[b]), int(ref["accepted"][b]))
+        if g_acc[b] != ref["accepted"][b]:          # a decision flipped: it must have been a near-tie
+            lhs, rhs = tests[first]
+            assert abs(lhs - rhs) <= 5e-5 * max(rhs, 1e-30), (b, first, lhs, rhs)
+        else:                                       # same rounds, another final token: a prefix-sum step on the threshold
+            assert g_acc[b] == C
+            check_sampled_ids(r_fin[None], np.array([u_fin]), g_tok[b:b + 1], ref["token"][b:b + 1], tol=5e-5, what="final draw")
+    assert exact >= min_exact * p64.shape[0], exact
+    return exact

@@ -10,7 +10,7 @@ import torch
 
 import oracle
 from paper_2506_03206_amd import synth
-from parity_util import ATOL, RTOL, assert_close, check_verify_outputs
+from parity_util import ATOL, RTOL, assert_close, check_multi, check_verify_outputs
 
 pytestmark = pytest.mark.gpu
 
@@ -181,3 +181,24 @@ def test_dense256k_exact_bf16(rdk):
     assert np.abs(sums - 1).max() < 2e-5 and out.min() >= 0 and np.isfinite(out).all()
     # bf16 rounding of q' breaks exact linearity by at most 2^-9 per term
     assert_close(out[18], 0.5 * out[16].astype(np.float64) + 0.5 * out[17], rtol=8e-3, atol=1e-7, what="linearity")
+
+
+def test_llama3_verify_multi(rdk, llama3):
+    """Several candidates per position at N=128256 on the whole batch of 256 positions (126 block sums per row,
+    up to five passes per position): the sparse form's rows, materialised by the oracle, on both sides."""
+    w, kept = llama3["w"], llama3["kept_ids"]
+    idx, wt, sw = synth.random_sparse_kernel(np.random.default_rng(1), w.N, kept, w.k)
+    q64 = oracle.redistribute_batch("sparse", llama3["q_hat"], kept, w.N, sparse=(idx, wt.astype(np.float32), sw.astype(np.float32)))
+    qp32 = q64.astype(np.float32)
+    q64 = qp32.astype(np.float64)
+    p64 = llama3["p"].astype(np.float64)
+    C, seed, offset = 4, 2506, 1 << 34
+    ref = oracle.verify_multi_batch(p64, q64, C, seed, offset)
+    p, qp = dev(llama3["p"]), dev(qp32)
+    o = rdk.rdk_verify_multi(p, qp, C, seed, offset)
+    g_cand = o.cand_ids.cpu().numpy()
+    assert (g_cand == ref["cand_ids"]).mean() > 0.98
+    o2 = rdk.rdk_verify_multi(p, qp, C, seed, offset, cand_ids=dev(ref["cand_ids"]))
+    exact = check_multi(o2, ref, p64, q64, seed, offset, C, min_exact=0.95)
+    print("verify_multi at llama3: %d of %d positions identical, mean candidates tried %.2f" % (
+        exact, w.B, float(np.minimum(ref["accepted"] + 1, C).mean())))

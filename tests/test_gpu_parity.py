@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2506_03206_amd import synth
-from parity_util import ATOL, RTOL, RTOL_BF16, assert_close, check_sampled_ids, check_verify_outputs
+from parity_util import ATOL, RTOL, RTOL_BF16, assert_close, check_multi, check_sampled_ids, check_verify_outputs
 
 pytestmark = pytest.mark.gpu
 
@@ -773,7 +773,7 @@ def test_random_shapes_with_padded_rows(rdk, seed):
     w = synth.scaled(synth.WORKLOADS["tiny"], name="random%d" % seed, seed=100 + seed, **shape)
     data = synth.make(w)
     data["w"] = w
-    kinds = ("prob", "logit", "bf16")[int(rng.integers(0, 3))]
+    kinds = ("prob", "logit", "bf16")[seed % 3]
     if kinds == "bf16":
         data["z_p"], data["z_q"] = synth.bf16_round(data["z_p"]), synth.bf16_round(data["z_q"])
     print("seed", seed, shape, "pads", (pad_p, pad_q, pad_o), kinds, flush=True)
@@ -826,6 +826,14 @@ def test_random_shapes_with_padded_rows(rdk, seed):
         o3 = rdk.rdk_verify_sample(p_in, view, seed_, offset, w.gamma, pk)
         ref3 = oracle.verify_batch(p64, qp32.astype(np.float64), seed_, offset, gamma=w.gamma)
         check_verify_outputs(o3, ref3, p64, qp32.astype(np.float64), seed_, offset, w.gamma, pk, min_exact=0.0)
+    # several candidates per position on the materialised (padded) rows of the sparse form
+    view, big = out_view()
+    rdk.rdk_redistribute_linear(ks, rdk.LINEAR_SPARSE, q_in, qk, out=view)
+    C = 1 + seed % 4
+    qp64 = view.cpu().numpy().astype(np.float64)
+    refm = oracle.verify_multi_batch(p64, qp64, C, seed_, offset)
+    om = rdk.rdk_verify_multi(p_in, view, C, seed_, offset, pk, cand_ids=dev(refm["cand_ids"]))
+    check_multi(om, refm, p64, qp64, seed_, offset, C, min_exact=0.0)
     # draft draw before any target row exists
     view, big = out_view()
     ids, _ = rdk.rdk_sample_draft(ks, q_in, seed_, offset, qk, q_prime=view)
@@ -848,47 +856,6 @@ def test_random_shapes_with_padded_rows(rdk, seed):
 
 
 # --------------------------------------------------------------------------------------------- several candidates per position
-def multi_chain(p, q, cand, seed, index):
-    """fp64 walk through the rounds of one position for given candidates: per round the two sides of the test
-    u q'(x) < r(x); then the weights of the final draw and its uniform.  Only used to tell near-ties apart."""
-    C = len(cand)
-    r = p.copy()
-    tests = []
-    for i, x in enumerate(cand):
-        u = oracle.multi_uniform(seed, index, C + i)
-        tests.append((u * q[x], r[x]) if 0 <= x < p.size else (1.0, 0.0))
-        r = np.maximum(r - q, 0.0)
-        z = r.sum()
-        if z > 0:
-            r = r / z
-    return tests, r, oracle.multi_uniform(seed, index, 2 * C)
-
-
-def check_multi(o, ref, p64, q64, seed, offset, C, min_exact=0.9):
-    """Device outputs of rdk_verify_multi (same candidates on both sides) against the oracle's."""
-    g_acc, g_tok, g_rm = o.accepted.cpu().numpy(), o.token.cpu().numpy(), o.resid_mass.cpu().numpy()
-    exact = 0
-    for b in range(p64.shape[0]):
-        cand = ref["cand_ids"][b]
-        if g_acc[b] == ref["accepted"][b] and g_tok[b] == ref["token"][b]:
-            exact += 1
-            nrej = int(g_acc[b])                     # rejections before the kept candidate (all C when none was kept)
-            if nrej:
-                assert_close(g_rm[b, :nrej], ref["resid_mass"][b, :nrej], rtol=5e-5, atol=1e-7, what="residual mass per round")
-            assert not g_rm[b, nrej:].any()
-            continue
-        tests, r_fin, u_fin = multi_chain(p64[b], q64[b], cand, seed, offset + b)
-        first = min(int(g_acc[b]), int(ref["accepted"][b]))
-        if g_acc[b] != ref["accepted"][b]:          # a decision flipped: it must have been a near-tie
-            lhs, rhs = tests[first]
-            assert abs(lhs - rhs) <= 5e-5 * max(rhs, 1e-30), (b, first, lhs, rhs)
-        else:                                       # same rounds, another final token: a prefix-sum step on the threshold
-            assert g_acc[b] == C
-            check_sampled_ids(r_fin[None], np.array([u_fin]), g_tok[b:b + 1], ref["token"][b:b + 1], tol=5e-5, what="final draw")
-    assert exact >= min_exact * p64.shape[0], exact
-    return exact
-
-
 @pytest.mark.parametrize("case", ["tiny", "ragged"])
 @pytest.mark.parametrize("p_kind", ["prob", "logit"])
 @pytest.mark.parametrize("C", [1, 3, 6])
