@@ -28,11 +28,12 @@ MFMA_F32_PEAK_TFLOPS = 157.3    # MI355X fp32 matrix, published
 # commands in profiles/), scaled by the 256 MiB yardstick pass below: bytes = 1024 * (2 * FETCH_SIZE + WRITE_SIZE).
 # Keyed by (workload, mode, path, kernel); valid for the kernels as committed with that summary.
 MEASURED_TRAFFIC = {
-    ("llama3", "sparse", "fused", "sparse_product_kernel"): 490.7e6,
+    ("llama3", "sparse", "fused", "sparse_product_kernel"): 490.6e6,
     ("llama3", "taylor", "fused", "taylor_stats_kernel"): 167.2e6,
     ("llama3", "taylor", "fused", "taylor_write_kernel"): 166.8e6,
-    ("dense256k", "exact", "bf16", "exact_bf16_kernel"): 19205.5e6,
-    ("n32k", "exact", "f32", "exact_f32_split_kernel"): 1085.1e6,
+    ("dense256k", "exact", "bf16", "exact_bf16_kernel"): 19205.4e6,
+    ("n32k", "exact", "f32", "exact_f32_split_kernel"): 1085.2e6,
+    ("llama3", "multi", "C4", "verify_multi_kernel"): 483.4e6,
 }
 
 
@@ -221,7 +222,8 @@ def run_multi(args, rdk, synth, torch, w, vocab, batch, steps, C=4):
             "positions_per_s": round(w.B / (ms * 1e-3), 1), "mean_rejections_per_position": round(rejections, 3),
             "kept_one_of_C": round(float((out.accepted < C).float().mean().item()), 4),
             "roofline": {"kernel": "verify_multi_kernel", "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
-                         "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                         "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                         "traffic": MEASURED_TRAFFIC.get((w.name, "multi", "C%d" % C, "verify_multi_kernel")),
                          "avg_launch_us": round(kms / cnt * 1e3, 2), "algorithmic_bytes_per_launch": alg}}
 
 
