@@ -110,3 +110,55 @@ def test_draft_and_feature_argument_checks(rdk):
     assert feat(kind=4) == 3
     assert feat(T=1) == 2 and feat(ldz=99) == 2 and feat(ldf=7) == 2 and feat(N=0) == 2
     assert feat(z=0x1008) == 9 and feat(F=0x2004) == 9
+
+
+def test_multi_candidate_argument_checks(rdk):
+    L = rdk.lib()
+    vp = ctypes.c_void_p
+    need = ctypes.c_size_t()
+    d = rdk.MultiDesc(B=256, N=128256, C=4, seed=1, offset=0, sample_candidates=1)
+    assert L.rdk_verify_multi_workspace_bytes(ctypes.byref(d), 0, ctypes.byref(need)) == 0 and need.value >= 256
+    assert L.rdk_verify_multi_workspace_bytes(ctypes.byref(d), 2, ctypes.byref(need)) == 0 and need.value >= 256 * 8
+    assert L.rdk_verify_multi_workspace_bytes(ctypes.byref(d), 7, ctypes.byref(need)) == 3
+    assert L.rdk_verify_multi_workspace_bytes(None, 0, ctypes.byref(need)) == 1
+    for field, value, status in (("C", 0, 2), ("C", 17, 7), ("B", 0, 2), ("N", 0, 2), ("N", (1 << 21) + 1, 7)):
+        bad = rdk.MultiDesc(B=256, N=128256, C=4, seed=1, offset=0, sample_candidates=1)
+        setattr(bad, field, value)
+        assert L.rdk_verify_multi_workspace_bytes(ctypes.byref(bad), 0, ctypes.byref(need)) == status, field
+    args = lambda p=0x1000, q=0x2000, cand=0x3000, acc=0x4000, tok=0x5000, ws=0x6000, wsb=1 << 20, ldp=128256, ldq=128256, kind=0: (
+        ctypes.byref(d), vp(p) if p else None, kind, ldp, vp(q) if q else None, ldq, vp(cand) if cand else None,
+        vp(acc) if acc else None, vp(tok) if tok else None, None, vp(ws) if ws else None, wsb, None)
+    assert L.rdk_verify_multi(*args(p=None)) == 1 and L.rdk_verify_multi(*args(q=None)) == 1
+    assert L.rdk_verify_multi(*args(cand=None)) == 1 and L.rdk_verify_multi(*args(tok=None)) == 1
+    assert L.rdk_verify_multi(*args(ldp=100)) == 2 and L.rdk_verify_multi(*args(ldq=100)) == 2
+    assert L.rdk_verify_multi(*args(kind=5)) == 3
+    assert L.rdk_verify_multi(*args(p=0x1004)) == 9 and L.rdk_verify_multi(*args(q=0x2008)) == 9
+    assert L.rdk_verify_multi(*args(wsb=16)) == 6
+
+
+def test_descriptor_layouts_match_the_header(rdk, tmp_path):
+    """The ctypes mirrors of the descriptor structs against the C compiler's view of include/rdk.h."""
+    import subprocess
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "rdk.h"\n'
+                   '#define F(T, f) printf(#T "." #f " %zu\\n", offsetof(T, f));\n'
+                   'int main(void) {\n'
+                   '  printf("rdk_verify_desc_t %zu\\n", sizeof(rdk_verify_desc_t));\n'
+                   '  F(rdk_verify_desc_t, B) F(rdk_verify_desc_t, N) F(rdk_verify_desc_t, gamma) F(rdk_verify_desc_t, sample_draft)\n'
+                   '  F(rdk_verify_desc_t, seed) F(rdk_verify_desc_t, offset)\n'
+                   '  printf("rdk_multi_desc_t %zu\\n", sizeof(rdk_multi_desc_t));\n'
+                   '  F(rdk_multi_desc_t, B) F(rdk_multi_desc_t, N) F(rdk_multi_desc_t, C) F(rdk_multi_desc_t, seed)\n'
+                   '  F(rdk_multi_desc_t, offset) F(rdk_multi_desc_t, sample_candidates)\n'
+                   '  printf("rdk_kernel_desc_t %zu\\n", sizeof(rdk_kernel_desc_t));\n'
+                   '  F(rdk_kernel_desc_t, kept_ids) F(rdk_kernel_desc_t, self_w) F(rdk_kernel_desc_t, tau) F(rdk_kernel_desc_t, format)\n'
+                   '  F(rdk_kernel_desc_t, validate)\n  return 0;\n}\n')
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = dict(line.rsplit(" ", 1) for line in subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.splitlines())
+    mirrors = {"rdk_verify_desc_t": rdk.VerifyDesc, "rdk_multi_desc_t": rdk.MultiDesc, "rdk_kernel_desc_t": rdk.KernelDesc}
+    for key, value in out.items():
+        if "." in key:
+            struct, field = key.split(".")
+            assert getattr(mirrors[struct], field).offset == int(value), key
+        else:
+            assert ctypes.sizeof(mirrors[key]) == int(value), key
