@@ -121,8 +121,9 @@ __global__ __launch_bounds__(kMultiThreads) void verify_multi_kernel(MultiArgs a
 {
     __shared__ float blk[kMultiMaxBlocks];
     __shared__ int32_t sh_cand[kMultiMaxCandidates];
+    __shared__ float sh_px[kMultiMaxCandidates], sh_qx[kMultiMaxCandidates];
+    __shared__ double sh_u[kMultiMaxCandidates];
     __shared__ double sh_total;
-    __shared__ int sh_keep;
     const int64_t row = blockIdx.x;
     const int wid = threadIdx.x / kWave, lane = lane_id();
     const int N = a.d.N, C = a.d.C;
@@ -163,24 +164,24 @@ __global__ __launch_bounds__(kMultiThreads) void verify_multi_kernel(MultiArgs a
         sh_cand[threadIdx.x] = a.cand_ids[row * C + threadIdx.x];
     }
     __syncthreads();
+    // both rows at every candidate and the uniforms of the tests, fetched together (one round trip instead of one per
+    // round); a candidate outside the vocabulary gets zero weights and is never kept (u * 0 < 0 is false)
+    if (threadIdx.x < C) {
+        const int x = sh_cand[threadIdx.x];
+        const bool valid = x >= 0 && x < N;
+        sh_px[threadIdx.x] = valid ? to_weight<KIND>(load1<KIND>(r.pr, valid ? x : 0), r.m, r.inv) : 0.f;
+        sh_qx[threadIdx.x] = valid ? r.qr[x] : 0.f;
+        sh_u[threadIdx.x] = multi_unit(a.d.seed, index, C + threadIdx.x);
+    }
+    __syncthreads();
 
     float ca = 1.f, cb = 0.f;   // r_i = max(0, ca p - cb q')
     float wa = 1.f, wb = 1.f;   // coefficients of the last pass
     int accepted = C, token = -1;
     double Z = 0.0;
     for (int i = 0; i < C; ++i) {
-        if (threadIdx.x == 0) {
-            const int x = sh_cand[i];
-            int keep = 0;
-            if (x >= 0 && x < N) {
-                const float px = to_weight<KIND>(load1<KIND>(r.pr, x), r.m, r.inv), qx = r.qr[x];
-                const float rho = fmaxf(px * ca - qx * cb, 0.f);
-                keep = multi_unit(a.d.seed, index, C + i) * (double)qx < (double)rho ? 1 : 0;
-            }
-            sh_keep = keep;
-        }
-        __syncthreads();
-        if (sh_keep) {   // the same for every thread
+        const float rho = fmaxf(sh_px[i] * ca - sh_qx[i] * cb, 0.f);
+        if (sh_u[i] * (double)sh_qx[i] < (double)rho) {   // the same for every thread
             accepted = i;
             token = sh_cand[i];
             break;
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(kMultiThreads) void verify_multi_kernel(MultiArgs a
             ca = 0.f;
             cb = 0.f;
         }
-        __syncthreads();   // sh_keep and sh_total are written again in the next round
+        __syncthreads();   // sh_total is written again in the next round
     }
     if (accepted == C && wid == 0) {
         // every candidate was rejected: t ~ r_C, whose un-normalised weights are those of the last pass
