@@ -81,6 +81,8 @@ def lib():
         L.orc_verify_position.restype = None
         L.orc_verify_multi.argtypes = [_D, _D, _i64, _i64, _u64, _u64, ctypes.c_int, _I32, _I32, _I32, _D]
         L.orc_verify_multi.restype = ctypes.c_int
+        L.orc_tree_walk.argtypes = [_I32, _I32, _I32, _i64, _i64, _i64, _I32, _I32]
+        L.orc_tree_walk.restype = None
         _lib = L
     return _lib
 
@@ -298,6 +300,14 @@ def verify_multi_batch(p, q_prime, C, seed, offset, cand_ids=None):
         if rc != 0:
             raise MemoryError("orc_verify_multi")
     return dict(cand_ids=cand, accepted=acc, token=tok, resid_mass=rm)
+
+
+def tree_walk(child_node, accepted, token, S, nodes, C):
+    """Walk through S verified token trees of `nodes` nodes each; returns (n_accepted [S], out_tokens [S, nodes])."""
+    cn, acc, tok = _i32(child_node).reshape(S * nodes * C), _i32(accepted), _i32(token)
+    n_acc, out = np.zeros(S, np.int32), np.zeros((S, nodes), np.int32)
+    lib().orc_tree_walk(_p(cn, _I32), _p(acc, _I32), _p(tok, _I32), S, nodes, C, _p(n_acc, _I32), _p(out, _I32))
+    return n_acc, out
 
 
 def multi_uniform(seed, index, m):

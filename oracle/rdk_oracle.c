@@ -18,7 +18,9 @@
  * Eq. 3; Monte-Carlo acceptance and losslessness of Alg. 4; published
  * known-answer vectors of Philox4x32-10; verification of several candidates:
  * its reduction to Alg. 4 with one candidate, a hand-computed example, and the
- * law of the emitted token (equal to p).
+ * law of the emitted token (equal to p), also for lists of any length; the
+ * walk through verified token trees: a chain is Alg. 4 on a sequence, and a
+ * hand-made tree.
  * Parity unpinned: none of the functions below is without a pin; the size of the
  * exact-vs-first-order gap (Thm 4.4) is only reported, since the theorem's
  * constants are not given.
@@ -407,6 +409,10 @@ void orc_verify_position(const double *p, const double *q_prime, int64_t N, uint
 /* with counter (index, m / 4, 0); m = i for the draw of candidate i, C + i    */
 /* for its acceptance test, 2C for the final draw (C = 1: the words of         */
 /* orc_uniforms in the order draft, accept, residual).                         */
+/* A position may have fewer than C candidates: a negative id ends its list    */
+/* (the token is then drawn from the r reached so far; an empty list gives     */
+/* t ~ p, the draw at a leaf of a token tree).  An id >= N is a candidate that */
+/* is never kept.  The uniforms keep the indices above whatever the length.    */
 /* Outputs: cand_ids[C] (written when sampled), *accepted = index of the       */
 /* accepted candidate or C, *token = emitted id (-1 when the last residual is  */
 /* empty), resid_mass[C] = sum of max(0, r - q') after each rejection (0 for   */
@@ -435,7 +441,8 @@ int orc_verify_multi(const double *p, const double *q_prime, int64_t N, int64_t 
     *token = -1;
     for (int64_t i = 0; i < C; ++i) {
         int32_t x = cand_ids[i];
-        if (x >= 0 && x < N && orc_accept(multi_uniform(seed, index, C + i), q_prime[x], r[x])) {
+        if (x < 0) break; /* end of this position's list */
+        if (x < N && orc_accept(multi_uniform(seed, index, C + i), q_prime[x], r[x])) {
             *accepted = (int32_t)i;
             *token = x;
             free(r);
@@ -453,4 +460,35 @@ int orc_verify_multi(const double *p, const double *q_prime, int64_t N, int64_t 
     *token = (int32_t)orc_sample_cdf(r, N, multi_uniform(seed, index, 2 * C));
     free(r);
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Walk through verified token trees.  Every tree has `nodes` nodes, node 0   */
+/* the root (the context so far); node v of tree s is position s * nodes + v  */
+/* of a batch that orc_verify_multi has gone through with the tokens of v's   */
+/* children as its candidates, so accepted[.] and token[.] hold, for every    */
+/* node, what the verification would emit if the walk came there.             */
+/* child_node[(s * nodes + v) * C + i] = node reached by candidate i of v.    */
+/* From the root: emit token[v]; if a candidate was kept (accepted < C) go to  */
+/* its node, else stop (token[v] was the residual draw, or the draw from p at  */
+/* a leaf).  n_accepted[s] = candidates kept on the way; out_tokens[s, 0 ..]   */
+/* = the emitted ids, -1 beyond them ([S, nodes]).                             */
+void orc_tree_walk(const int32_t *child_node, const int32_t *accepted, const int32_t *token,
+                   int64_t S, int64_t nodes, int64_t C, int32_t *n_accepted, int32_t *out_tokens)
+{
+    for (int64_t s = 0; s < S; ++s) {
+        for (int64_t i = 0; i < nodes; ++i) out_tokens[s * nodes + i] = -1;
+        int64_t v = 0, len = 0;
+        while (len < nodes) {
+            int64_t pos = s * nodes + v;
+            out_tokens[s * nodes + len] = token[pos];
+            ++len;
+            if (accepted[pos] >= C) break;
+            int32_t next = child_node[pos * C + accepted[pos]];
+            if (next <= v || next >= nodes) break; /* not a tree: stop rather than loop */
+            v = next;
+        }
+        /* the last emitted token is the residual / leaf draw unless the walk was cut short */
+        n_accepted[s] = (int32_t)(len - 1);
+    }
 }

@@ -477,3 +477,70 @@ def test_multi_candidate_losslessness(C):
     assert (res["accepted"] < C).mean() > kept_first + 0.01
     same = oracle.verify_multi_batch(P[:2000], P[:2000], C, seed=1, offset=0)
     assert not same["accepted"].any() and np.array_equal(same["token"], same["cand_ids"][:, 0])
+
+
+def test_candidate_lists_of_any_length_keep_the_law():
+    """A negative id ends a position's list: no candidates -> t ~ p (the draw at a leaf); two candidates in four
+    slots -> the same token as two slots when the uniforms are taken at the same indices; the law is p either way."""
+    rng = np.random.default_rng(41)
+    N, trials = 8, 120000
+    p, qp = rand_dist(rng, N, 1), rand_dist(rng, N, 1)
+    P, Q = np.broadcast_to(p, (trials, N)), np.broadcast_to(qp, (trials, N))
+    none = oracle.verify_multi_batch(P[:60000], Q[:60000], 3, seed=8, offset=0, cand_ids=np.full((60000, 3), -1))
+    assert (none["accepted"] == 3).all() and not none["resid_mass"].any()
+    for idx in (0, 1, 59999):
+        assert none["token"][idx] == oracle.sample_cdf(p, oracle.multi_uniform(8, idx, 6))
+    count = np.bincount(none["token"], minlength=N)
+    assert ((count - 60000 * p)[p > 0] ** 2 / (60000 * p[p > 0])).sum() < 40
+    # candidates drawn from q' (uniforms 0, 1 of a four-slot position), slots 2 and 3 empty
+    drawn = oracle.verify_multi_batch(P, Q, 4, seed=9, offset=0)["cand_ids"]
+    cand = drawn.copy()
+    cand[:, 2:] = -1
+    res = oracle.verify_multi_batch(P, Q, 4, seed=9, offset=0, cand_ids=cand)
+    assert set(np.unique(res["accepted"])) <= {0, 1, 4} and not res["resid_mass"][:, 2:].any()
+    count = np.bincount(res["token"], minlength=N)
+    assert ((count - trials * p)[p > 0] ** 2 / (trials * p[p > 0])).sum() < 40
+
+
+def test_tree_walk_chain_is_alg4_and_hand_tree():
+    """A chain (every node one child) is Alg. 4 on a sequence: accepted drafts, then the residual token of the first
+    rejected position, or the draw from the target row after the last draft.  Then a hand-made tree."""
+    rng = np.random.default_rng(43)
+    N, gamma, S = 30, 4, 200
+    nodes = gamma + 1
+    P = np.stack([rand_dist(rng, N, 2) for _ in range(S * nodes)])
+    Q = np.stack([rand_dist(rng, N, 2) for _ in range(S * nodes)])
+    seed, offset = 17, 1000
+    cand = np.full((S * nodes, 1), -1, np.int32)
+    child = np.full((S, nodes, 1), -1, np.int32)
+    for s in range(S):
+        for v in range(gamma):                                    # the child of node v is node v + 1, its token drawn from q'_v
+            cand[s * nodes + v, 0] = oracle.sample_cdf(Q[s * nodes + v], oracle.multi_uniform(seed, offset + s * nodes + v, 0))
+            child[s, v, 0] = v + 1
+    res = oracle.verify_multi_batch(P, Q, 1, seed, offset, cand_ids=cand)
+    n_acc, toks = oracle.tree_walk(child, res["accepted"], res["token"], S, nodes, 1)
+    seen_all, seen_some = False, False
+    for s in range(S):
+        rows = slice(s * nodes, s * nodes + gamma)
+        one = oracle.verify_batch(P[rows], Q[rows], seed, offset + s * nodes, sample_draft=False, draft_ids=cand[rows, 0], gamma=gamma)
+        j = int(one["n_accepted"][0])
+        assert n_acc[s] == j
+        assert np.array_equal(toks[s, :j], cand[rows, 0][:j])
+        if j < gamma:
+            assert toks[s, j] == one["resid_ids"][j] and (toks[s, j + 1:] == -1).all()
+            seen_some = True
+        else:                                                     # every draft kept: one more token from the row after them
+            leaf = s * nodes + gamma
+            assert toks[s, gamma] == oracle.sample_cdf(P[leaf], oracle.multi_uniform(seed, offset + leaf, 2))
+            seen_all = True
+    assert seen_some
+    # hand tree, C = 2: node 0 -> (1, 2), node 1 -> (3, -), node 2 -> (4, 5); results per node given
+    child = np.array([[[1, 2], [3, -1], [4, 5], [-1, -1], [-1, -1], [-1, -1]]], np.int32)
+    tok = np.array([70, 71, 72, 73, 74, 75], np.int32)
+    walk = lambda acc: oracle.tree_walk(child, np.array(acc, np.int32), tok, 1, 6, 2)
+    n, t = walk([1, 0, 2, 2, 2, 2])        # root keeps its second child (node 2); node 2 keeps none: residual token 72
+    assert n[0] == 1 and t[0].tolist() == [70, 72, -1, -1, -1, -1]
+    n, t = walk([0, 0, 2, 2, 2, 2])        # node 0 -> 1 -> 3 (leaf): two kept, then the leaf's draw
+    assert n[0] == 2 and t[0].tolist() == [70, 71, 73, -1, -1, -1]
+    n, t = walk([2, 0, 0, 2, 2, 2])        # nothing kept at the root
+    assert n[0] == 0 and t[0].tolist() == [70, -1, -1, -1, -1, -1]
