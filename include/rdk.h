@@ -252,7 +252,8 @@ rdk_status_t rdk_sample_draft(const rdk_kernel_t *kernel, const void *q, rdk_inp
  * With C = 1 this is rdk_verify_sample for one position (same draft, same decision, same residual token).  The
  * emitted token follows p_b exactly whatever q'_b is.
  *   sample_candidates = 1: the C candidates are drawn from q'_b by the inverse CDF and written to cand_ids;
- *   sample_candidates = 0: cand_ids [B, C] is input (an id outside [0, N) is never kept).
+ *   sample_candidates = 0: cand_ids [B, C] is input; an id >= N is a candidate that is never kept, a negative id
+ *     ends the list of the position (fewer than C candidates; none at all: the token is drawn from p_b).
  * Uniforms: the m-th uniform of position b is word m % 4 of Philox4x32-10 with key = seed and counter
  * (offset + b as two words, m / 4, 0);  m = i for the draw of candidate i, C + i for its test, 2C for the final draw.
  * Outputs (device): accepted [B] = index of the kept candidate, or C; token [B] = the emitted id (-1 when the last
@@ -271,6 +272,21 @@ rdk_status_t rdk_verify_multi(const rdk_multi_desc_t *desc, const void *p, rdk_i
                               const float *q_prime, int64_t ldq, int32_t *cand_ids, int32_t *accepted, int32_t *token,
                               float *resid_mass, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Verification of token trees (the other variant Sec. 1 names among the related work), in two calls: rdk_verify_multi
+ * on every node with the tokens of its children as the node's candidates (position s * nodes + v = node v of tree s,
+ * node 0 the root; p and q' of a node are the target and the redistributed drafter distribution after the prefix that
+ * ends at the node), then this walk: from the root, emit token[.] of the node; if its verification kept candidate i
+ * (accepted[.] = i < C) go on to child_node[., i], else stop -- the token was the residual draw, or the draw from p at
+ * a leaf.  A chain of nodes is Alg. 4 steps 4-10 on one sequence.
+ *   child_node [S, nodes, C] (device): node index of the child behind candidate slot i (> the node's own index).
+ *   accepted, token [S * nodes] (device): outputs of rdk_verify_multi.
+ *   n_accepted [S]: candidates kept along the path; out_tokens [S, nodes]: the emitted ids, -1 beyond them.
+ * Integer work only (bit-exact).  Errors: RDK_ERR_NULL, RDK_ERR_SHAPE, RDK_ERR_HIP.
+ */
+rdk_status_t rdk_tree_walk(int32_t S, int32_t nodes, int32_t C, const int32_t *child_node, const int32_t *accepted,
+                           const int32_t *token, int32_t *n_accepted, int32_t *out_tokens, void *stream);
+
 /* The four Philox words of `count` consecutive positions, [count, 4] uint32 on the device (for
  * checking the random stream against an independent implementation). */
 rdk_status_t rdk_philox_words(uint64_t seed, uint64_t offset, int32_t count, uint32_t *words,
@@ -283,7 +299,7 @@ rdk_status_t rdk_philox_words(uint64_t seed, uint64_t offset, int32_t count, uin
  * recorded events of that kernel, returns how many launches were recorded and their summed
  * elapsed time in milliseconds, and forgets them.  Both take HOST strings.  Names:
  * row_stats_kernel, row_block_sums_kernel, verify_stream_kernel, verify_finalize_kernel, draft_finalize_kernel,
- * sequence_scan_kernel, taylor_stats_kernel, taylor_write_kernel, tli_scatter_kernel, verify_multi_kernel,
+ * sequence_scan_kernel, taylor_stats_kernel, taylor_write_kernel, tli_scatter_kernel, tree_walk_kernel, verify_multi_kernel,
  * q_transpose_kernel, sparse_product_kernel, prep_a_split_kernel, exact_f32_split_kernel,
  * exact_reduce_kernel, prep_a_bf16_kernel, exact_bf16_kernel.
  */

@@ -513,6 +513,14 @@ rdk_status_t rdk_verify_multi(const rdk_multi_desc_t *desc, const void *p, rdk_i
     return launch_verify_multi(*desc, pi, q_prime, ldq, cand_ids, accepted, token, resid_mass, workspace, (hipStream_t)stream);
 }
 
+rdk_status_t rdk_tree_walk(int32_t S, int32_t nodes, int32_t C, const int32_t *child_node, const int32_t *accepted,
+                           const int32_t *token, int32_t *n_accepted, int32_t *out_tokens, void *stream)
+{
+    if (S <= 0 || nodes <= 0 || C <= 0) return RDK_ERR_SHAPE;
+    if (!child_node || !accepted || !token || !n_accepted || !out_tokens) return RDK_ERR_NULL;
+    return launch_tree_walk(S, nodes, C, child_node, accepted, token, n_accepted, out_tokens, (hipStream_t)stream);
+}
+
 rdk_status_t rdk_redistribute_verify_workspace_bytes(const rdk_kernel_t *kernel, rdk_linear_mode_t mode,
                                                      const rdk_verify_desc_t *desc, size_t *bytes)
 {

@@ -140,6 +140,9 @@ size_t multi_workspace_bytes(const rdk_multi_desc_t &d, rdk_input_kind_t p_kind)
 rdk_status_t launch_verify_multi(const rdk_multi_desc_t &d, RowInput p, const float *q_prime, int64_t ldq, int32_t *cand_ids,
                                  int32_t *accepted, int32_t *token, float *resid_mass, void *ws, hipStream_t st);
 
+rdk_status_t launch_tree_walk(int32_t S, int32_t nodes, int32_t C, const int32_t *child_node, const int32_t *accepted,
+                              const int32_t *token, int32_t *n_accepted, int32_t *out_tokens, hipStream_t st);
+
 // rdk_verify.hip
 size_t verify_workspace_bytes(const rdk_verify_desc_t &d);
 rdk_status_t launch_verify(const rdk_verify_desc_t &d, RowInput p, const float *q_prime, int64_t ldq,

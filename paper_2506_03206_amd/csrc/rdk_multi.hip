@@ -3,7 +3,9 @@
 // sampling, Miao et al., "SpecInfer", 2024) with the redistributed drafter q' in the drafter's place:
 //   r <- p;  for i = 0 .. C-1:  x_i ~ q' (or the caller's);  keep x_i with probability min(1, r(x_i) / q'(x_i)) and stop,
 //   else  r <- normalize(max(0, r - q'));  nothing kept: t ~ r.
-// With C = 1 these are steps 2 and 6-8 of Alg. 4.
+// With C = 1 these are steps 2 and 6-8 of Alg. 4.  A position may hold fewer than C candidates (a negative id ends its
+// list; none at all: t ~ p), which is what the nodes of a token tree need: verifying every node with its children as
+// candidates and then following the kept children from the root (tree_walk_kernel) verifies the tree.
 //
 // The residual is never stored.  Because q' >= 0,  max(0, max(0, x) - q') = max(0, x - q'),  so after i rejections
 //   r_i(j) = max(0, ca * p(j) - cb * q'(j))   with  (ca, cb) = (1, 0)  and  (ca, cb) <- (ca, cb + 1) / Z,
@@ -165,7 +167,8 @@ __global__ __launch_bounds__(kMultiThreads) void verify_multi_kernel(MultiArgs a
     }
     __syncthreads();
     // both rows at every candidate and the uniforms of the tests, fetched together (one round trip instead of one per
-    // round); a candidate outside the vocabulary gets zero weights and is never kept (u * 0 < 0 is false)
+    // round); a candidate beyond the vocabulary gets zero weights and is never kept (u * 0 < 0 is false); a negative
+    // id ends the list of the position
     if (threadIdx.x < C) {
         const int x = sh_cand[threadIdx.x];
         const bool valid = x >= 0 && x < N;
@@ -179,7 +182,9 @@ __global__ __launch_bounds__(kMultiThreads) void verify_multi_kernel(MultiArgs a
     float wa = 1.f, wb = 1.f;   // coefficients of the last pass
     int accepted = C, token = -1;
     double Z = 0.0;
+    bool any_pass = false;
     for (int i = 0; i < C; ++i) {
+        if (sh_cand[i] < 0) break;   // end of the list: the same for every thread
         const float rho = fmaxf(sh_px[i] * ca - sh_qx[i] * cb, 0.f);
         if (sh_u[i] * (double)sh_qx[i] < (double)rho) {   // the same for every thread
             accepted = i;
@@ -189,6 +194,7 @@ __global__ __launch_bounds__(kMultiThreads) void verify_multi_kernel(MultiArgs a
         wa = ca;
         wb = cb + 1.f;
         r.template pass<true>(blk, nblk, wa, wb);
+        any_pass = true;
         if (wid == 0) {
             const double total = wave_sum(lane_partial_sum(blk, nblk, per_lane));
             if (lane == 0) {
@@ -207,15 +213,44 @@ __global__ __launch_bounds__(kMultiThreads) void verify_multi_kernel(MultiArgs a
         }
         __syncthreads();   // sh_total is written again in the next round
     }
+    if (accepted == C && !any_pass) {
+        // a position without candidates (a leaf of a token tree): t ~ p, the residual with nothing taken off
+        wa = 1.f;
+        wb = 0.f;
+        r.template pass<true>(blk, nblk, wa, wb);
+    }
     if (accepted == C && wid == 0) {
-        // every candidate was rejected: t ~ r_C, whose un-normalised weights are those of the last pass
+        // every candidate was rejected: t ~ r, whose un-normalised weights are those of the last pass
         const double lane_sum = lane_partial_sum(blk, nblk, per_lane);
-        token = r.template draw<true>(blk, nblk, per_lane, lane_sum, Z, multi_unit(a.d.seed, index, 2 * C), wa, wb);
+        const double total = any_pass ? Z : wave_sum(lane_sum);
+        token = r.template draw<true>(blk, nblk, per_lane, lane_sum, total, multi_unit(a.d.seed, index, 2 * C), wa, wb);
     }
     if (threadIdx.x == 0) {
         a.accepted[row] = accepted;
         a.token[row] = token;
     }
+}
+
+// Walk through verified token trees: one thread per tree follows, from the root, the candidate that the verification
+// of each node kept, and emits that node's token; it stops at the first node that kept none (integer work only).
+__global__ void tree_walk_kernel(int S, int nodes, int C, const int32_t *child_node, const int32_t *accepted,
+                                 const int32_t *token, int32_t *n_accepted, int32_t *out_tokens)
+{
+    const int s = blockIdx.x * blockDim.x + threadIdx.x;
+    if (s >= S) return;
+    int32_t *out = out_tokens + (int64_t)s * nodes;
+    int v = 0, len = 0;
+    while (len < nodes) {
+        const int64_t pos = (int64_t)s * nodes + v;
+        out[len++] = token[pos];
+        const int kept = accepted[pos];
+        if (kept < 0 || kept >= C) break;
+        const int next = child_node[pos * C + kept];
+        if (next <= v || next >= nodes) break;   // not a tree: stop rather than loop
+        v = next;
+    }
+    n_accepted[s] = len - 1;
+    for (int i = len; i < nodes; ++i) out[i] = -1;
 }
 
 template <int KIND>
@@ -243,6 +278,17 @@ size_t multi_workspace_bytes(const rdk_multi_desc_t &d, rdk_input_kind_t p_kind)
 {
     if (p_kind == RDK_PROB_F32) return 256;
     return align_up((size_t)d.B * row_splits(d.B, d.N, kStatThreads / kWave) * sizeof(SoftStat), 256);
+}
+
+rdk_status_t launch_tree_walk(int32_t S, int32_t nodes, int32_t C, const int32_t *child_node, const int32_t *accepted,
+                              const int32_t *token, int32_t *n_accepted, int32_t *out_tokens, hipStream_t st)
+{
+    {
+        RDK_TIMED_LAUNCH("tree_walk_kernel", tree_walk_kernel, dim3((S + 63) / 64), dim3(64), 0, st, S, nodes, C, child_node,
+                         accepted, token, n_accepted, out_tokens);
+    }
+    RDK_LAUNCH_CHECK("tree_walk_kernel");
+    return RDK_OK;
 }
 
 rdk_status_t launch_verify_multi(const rdk_multi_desc_t &d, RowInput p, const float *q_prime, int64_t ldq, int32_t *cand_ids,

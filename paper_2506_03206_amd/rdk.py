@@ -24,7 +24,7 @@ EXPORTS = [
     "rdk_redistribute_linear", "rdk_verify_workspace_bytes", "rdk_verify_sample", "rdk_philox_words",
     "rdk_timing_select", "rdk_timing_read", "rdk_redistribute_verify_workspace_bytes", "rdk_redistribute_verify",
     "rdk_sample_draft_workspace_bytes", "rdk_sample_draft", "rdk_features_from_scores",
-    "rdk_verify_multi_workspace_bytes", "rdk_verify_multi",
+    "rdk_verify_multi_workspace_bytes", "rdk_verify_multi", "rdk_tree_walk",
 ]
 
 
@@ -91,6 +91,7 @@ def lib():
         L.rdk_features_from_scores.argtypes = [vp, ctypes.c_int, i64, i32, i32, vp, i64, vp]
         L.rdk_verify_multi_workspace_bytes.argtypes = [ctypes.POINTER(MultiDesc), ctypes.c_int, psz]
         L.rdk_verify_multi.argtypes = [ctypes.POINTER(MultiDesc), vp, ctypes.c_int, i64, vp, i64, vp, vp, vp, vp, vp, sz, vp]
+        L.rdk_tree_walk.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp]
         L.rdk_timing_select.argtypes = [ctypes.c_char_p]
         L.rdk_timing_read.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_double)]
         for name in EXPORTS:
@@ -336,6 +337,18 @@ def rdk_verify_multi(p, q_prime, C, seed, offset=0, p_kind="prob", cand_ids=None
                                   _ptr(o.accepted), _ptr(o.token), _ptr(o.resid_mass), _ptr(o.ws), o.ws.numel(), _stream()),
            "rdk_verify_multi")
     return o
+
+
+def rdk_tree_walk(child_node, accepted, token):
+    """Walk through verified token trees.  child_node [S, nodes, C] int32; accepted, token [S * nodes] from
+    rdk_verify_multi on the nodes.  Returns (n_accepted [S], out_tokens [S, nodes])."""
+    S, nodes, C = child_node.shape
+    assert child_node.is_contiguous() and accepted.numel() == S * nodes and token.numel() == S * nodes
+    n_acc = torch.zeros(S, dtype=torch.int32, device=child_node.device)
+    out = torch.full((S, nodes), -1, dtype=torch.int32, device=child_node.device)
+    _check(lib().rdk_tree_walk(S, nodes, C, _ptr(child_node), _ptr(accepted), _ptr(token), _ptr(n_acc), _ptr(out), _stream()),
+           "rdk_tree_walk")
+    return n_acc, out
 
 
 def rdk_philox_words(seed, offset, count, device="cuda"):

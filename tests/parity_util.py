@@ -80,6 +80,8 @@ def multi_chain(p, q, cand, seed, index):
     r = p.copy()
     tests = []
     for i, x in enumerate(cand):
+        if x < 0:                                   # end of the list
+            break
         u = oracle.multi_uniform(seed, index, C + i)
         tests.append((u * q[x], r[x]) if 0 <= x < p.size else (1.0, 0.0))
         r = np.maximum(r - q, 0.0)
@@ -112,3 +114,24 @@ def check_multi(o, ref, p64, q64, seed, offset, C, min_exact=0.9):
             check_sampled_ids(r_fin[None], np.array([u_fin]), g_tok[b:b + 1], ref["token"][b:b + 1], tol=5e-5, what="final draw")
     assert exact >= min_exact * p64.shape[0], exact
     return exact
+
+
+def random_trees(rng, S, nodes, C, q64, seed, offset):
+    """S random token trees of `nodes` nodes (node 0 the root, children after their parent, at most C per node); the
+    token of the i-th child of node v is drawn from q'_v with the i-th uniform of the node, as a drafter would.
+    Returns child_node [S, nodes, C] and the candidate lists cand [S * nodes, C] (-1 = no child)."""
+    child = np.full((S, nodes, C), -1, np.int32)
+    cand = np.full((S * nodes, C), -1, np.int32)
+    for s in range(S):
+        count = np.zeros(nodes, np.int64)
+        for v in range(1, nodes):
+            free = [u for u in range(v) if count[u] < C]
+            if count[0] < C:
+                parent = 0                                                                        # the root is full
+            else:
+                parent = free[int(rng.integers(0, len(free)))] if rng.random() < 0.6 else free[-1]   # bushy or deep
+            i = count[parent]
+            child[s, parent, i] = v
+            cand[s * nodes + parent, i] = oracle.sample_cdf(q64[s * nodes + parent], oracle.multi_uniform(seed, offset + s * nodes + parent, i))
+            count[parent] += 1
+    return child, cand

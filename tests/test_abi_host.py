@@ -134,6 +134,11 @@ def test_multi_candidate_argument_checks(rdk):
     assert L.rdk_verify_multi(*args(kind=5)) == 3
     assert L.rdk_verify_multi(*args(p=0x1004)) == 9 and L.rdk_verify_multi(*args(q=0x2008)) == 9
     assert L.rdk_verify_multi(*args(wsb=16)) == 6
+    walk = lambda S=4, nodes=5, C=2, child=0x1000, acc=0x2000, tok=0x3000, n=0x4000, out=0x5000: L.rdk_tree_walk(
+        S, nodes, C, vp(child) if child else None, vp(acc) if acc else None, vp(tok) if tok else None, vp(n) if n else None,
+        vp(out) if out else None, None)
+    assert walk(S=0) == 2 and walk(nodes=0) == 2 and walk(C=0) == 2
+    assert walk(child=None) == 1 and walk(acc=None) == 1 and walk(tok=None) == 1 and walk(n=None) == 1 and walk(out=None) == 1
 
 
 def test_descriptor_layouts_match_the_header(rdk, tmp_path):

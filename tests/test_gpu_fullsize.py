@@ -10,7 +10,7 @@ import torch
 
 import oracle
 from paper_2506_03206_amd import synth
-from parity_util import ATOL, RTOL, assert_close, check_multi, check_verify_outputs
+from parity_util import ATOL, RTOL, assert_close, check_multi, check_verify_outputs, random_trees
 
 pytestmark = pytest.mark.gpu
 
@@ -202,3 +202,23 @@ def test_llama3_verify_multi(rdk, llama3):
     exact = check_multi(o2, ref, p64, q64, seed, offset, C, min_exact=0.95)
     print("verify_multi at llama3: %d of %d positions identical, mean candidates tried %.2f" % (
         exact, w.B, float(np.minimum(ref["accepted"] + 1, C).mean())))
+
+
+def test_llama3_token_trees(rdk, llama3):
+    """32 token trees of 8 nodes (up to 3 children per node) at N=128256: all 256 nodes verified, then the walk."""
+    w, kept = llama3["w"], llama3["kept_ids"]
+    idx, wt, sw = synth.random_sparse_kernel(np.random.default_rng(1), w.N, kept, w.k)
+    qp32 = oracle.redistribute_batch("sparse", llama3["q_hat"], kept, w.N, sparse=(idx, wt.astype(np.float32), sw.astype(np.float32))).astype(np.float32)
+    q64, p64 = qp32.astype(np.float64), llama3["p"].astype(np.float64)
+    S, nodes, C, seed, offset = 32, 8, 3, 99, 1 << 35
+    child, cand = random_trees(np.random.default_rng(2), S, nodes, C, q64, seed, offset)
+    ref = oracle.verify_multi_batch(p64, q64, C, seed, offset, cand_ids=cand)
+    ref_n, ref_tok = oracle.tree_walk(child, ref["accepted"], ref["token"], S, nodes, C)
+    o = rdk.rdk_verify_multi(dev(llama3["p"]), dev(qp32), C, seed, offset, cand_ids=dev(cand))
+    check_multi(o, ref, p64, q64, seed, offset, C, min_exact=0.95)
+    n_acc, toks = rdk.rdk_tree_walk(dev(child), o.accepted, o.token)
+    own_n, own_tok = oracle.tree_walk(child, o.accepted.cpu().numpy(), o.token.cpu().numpy(), S, nodes, C)
+    assert np.array_equal(n_acc.cpu().numpy(), own_n) and np.array_equal(toks.cpu().numpy(), own_tok)
+    agree = (toks.cpu().numpy() == ref_tok).all(axis=1).mean()
+    assert agree >= 0.9, agree
+    print("token trees at llama3: %d of %d paths identical, mean path length %.2f" % (round(agree * S), S, float(ref_n.mean()) + 1))

@@ -6,7 +6,8 @@ import torch
 
 import oracle
 from paper_2506_03206_amd import synth
-from parity_util import ATOL, RTOL, RTOL_BF16, assert_close, check_multi, check_sampled_ids, check_verify_outputs
+from parity_util import (ATOL, RTOL, RTOL_BF16, assert_close, check_multi, check_sampled_ids, check_verify_outputs,
+                         random_trees)
 
 pytestmark = pytest.mark.gpu
 
@@ -921,3 +922,40 @@ def test_verify_multi_edges_and_errors(rdk, tiny):
         with pytest.raises(rdk.RdkError) as e:
             rdk.rdk_verify_multi(p, p, kwargs["C"], 1, 0)
         assert e.value.status == status
+
+
+@pytest.mark.parametrize("case", ["tiny", "ragged"])
+def test_tree_verification(rdk, tiny, ragged, case):
+    """Token trees: every node verified with its children as candidates (lists of 0 .. C ids), then the walk."""
+    data = tiny if case == "tiny" else ragged
+    w = data["w"]
+    nodes, C = (4, 2) if case == "tiny" else (7, 3)
+    S = w.B // nodes
+    B = S * nodes
+    idx, wt, sw = data["sparse"]
+    qp32 = oracle_rows(data, "sparse", kernel=(idx, wt.astype(np.float32), sw.astype(np.float32))).astype(np.float32)[:B]
+    q64, p64 = qp32.astype(np.float64), data["p"].astype(np.float64)[:B]
+    seed, offset = 321, 77
+    child, cand = random_trees(np.random.default_rng(8), S, nodes, C, q64, seed, offset)
+    assert (cand[:, 0] < 0).any() and (cand[:, -1] >= 0).any()          # leaves and full nodes both occur
+    ref = oracle.verify_multi_batch(p64, q64, C, seed, offset, cand_ids=cand)
+    ref_n, ref_tok = oracle.tree_walk(child, ref["accepted"], ref["token"], S, nodes, C)
+    o = rdk.rdk_verify_multi(dev(data["p"][:B]), dev(qp32), C, seed, offset, cand_ids=dev(cand))
+    check_multi(o, ref, p64, q64, seed, offset, C, min_exact=0.85)
+    # the walk is integer work: on the oracle's per-node results it must give the oracle's paths bit for bit
+    n_acc, toks = rdk.rdk_tree_walk(dev(child), dev(ref["accepted"]), dev(ref["token"]))
+    assert np.array_equal(n_acc.cpu().numpy(), ref_n) and np.array_equal(toks.cpu().numpy(), ref_tok)
+    # and on the device's own results, the oracle's walk of those results
+    n_acc, toks = rdk.rdk_tree_walk(dev(child), o.accepted, o.token)
+    own_n, own_tok = oracle.tree_walk(child, o.accepted.cpu().numpy(), o.token.cpu().numpy(), S, nodes, C)
+    assert np.array_equal(n_acc.cpu().numpy(), own_n) and np.array_equal(toks.cpu().numpy(), own_tok)
+    same = (o.accepted.cpu().numpy() == ref["accepted"]) & (o.token.cpu().numpy() == ref["token"])
+    if same.all():
+        assert np.array_equal(toks.cpu().numpy(), ref_tok)
+    # a walk that does not describe a tree stops instead of looping
+    loop = child.copy()
+    loop[:, :, :] = 0
+    n_acc, toks = rdk.rdk_tree_walk(dev(loop), dev(np.zeros(B, np.int32)), dev(ref["token"]))
+    assert not n_acc.any() and np.array_equal(toks.cpu().numpy()[:, 0], ref["token"][::nodes])
+    with pytest.raises(rdk.RdkError):
+        rdk.rdk_tree_walk(dev(child[:, :, :0].copy()), o.accepted, o.token)
