@@ -28,12 +28,12 @@ MFMA_F32_PEAK_TFLOPS = 157.3    # MI355X fp32 matrix, published
 # commands in profiles/), scaled by the 256 MiB yardstick pass below: bytes = 1024 * (2 * FETCH_SIZE + WRITE_SIZE).
 # Keyed by (workload, mode, path, kernel); valid for the kernels as committed with that summary.
 MEASURED_TRAFFIC = {
-    ("llama3", "sparse", "fused", "sparse_product_kernel"): 490.6e6,
+    ("llama3", "sparse", "fused", "sparse_product_kernel"): 490.7e6,
     ("llama3", "taylor", "fused", "taylor_stats_kernel"): 167.2e6,
     ("llama3", "taylor", "fused", "taylor_write_kernel"): 166.8e6,
-    ("dense256k", "exact", "bf16", "exact_bf16_kernel"): 19205.4e6,
-    ("n32k", "exact", "f32", "exact_f32_split_kernel"): 1085.2e6,
-    ("llama3", "multi", "C4", "verify_multi_kernel"): 483.4e6,
+    ("dense256k", "exact", "bf16", "exact_bf16_kernel"): 19206.4e6,
+    ("n32k", "exact", "f32", "exact_f32_split_kernel"): 1085.3e6,
+    ("llama3", "multi", "C4", "verify_multi_kernel"): 483.5e6,
 }
 
 

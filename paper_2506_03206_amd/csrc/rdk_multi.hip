@@ -63,14 +63,20 @@ struct MultiRow {
     float m, inv, pfill;
 
     // block sums of the weights into LDS (all wavefronts), ends with a barrier
-    template <bool RESID>
+    // (WITH_Q = false: the drafter row is not read and counts as zero -- the pass over p alone of a leaf)
+    template <bool RESID, bool WITH_Q = true>
     __device__ __forceinline__ void pass(float *blk, int nblk, float ca, float cb) const
     {
         const int wid = threadIdx.x / kWave, lane = lane_id();
         for (int c = wid; c < nblk; c += kMultiWaves) {
             float4 pv[4], qv[4];
             if (RESID) load_chunk<KIND, false>(pr, (int64_t)c * kChunk, N, vec_p, pfill, pv);
-            load_chunk<RDK_PROB_F32, false>(qr, (int64_t)c * kChunk, N, vec_q, 0.f, qv);
+            if (WITH_Q) {
+                load_chunk<RDK_PROB_F32, false>(qr, (int64_t)c * kChunk, N, vec_q, 0.f, qv);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) qv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -217,7 +223,7 @@ __global__ __launch_bounds__(kMultiThreads) void verify_multi_kernel(MultiArgs a
         // a position without candidates (a leaf of a token tree): t ~ p, the residual with nothing taken off
         wa = 1.f;
         wb = 0.f;
-        r.template pass<true>(blk, nblk, wa, wb);
+        r.template pass<true, false>(blk, nblk, wa, wb);
     }
     if (accepted == C && wid == 0) {
         // every candidate was rejected: t ~ r, whose un-normalised weights are those of the last pass
