@@ -359,6 +359,15 @@ def test_verify_very_large_vocab(rdk):
     run_verify_case(rdk, dev(p), "prob", p.astype(np.float64), q, 3, seed=41, offset=2)
     drafts = (np.arange(B, dtype=np.int32) * 50021) % N
     run_verify_case(rdk, dev(p), "prob", p.astype(np.float64), q, 3, seed=42, offset=0, draft_ids=drafts)
+    # several candidates per position at the same size: 586 block sums per row in LDS, ten per lane
+    p64, q64 = p.astype(np.float64), q.astype(np.float64)
+    ref = oracle.verify_multi_batch(p64, q64, 3, 43, 7)
+    o = rdk.rdk_verify_multi(dev(p), dev(q), 3, 43, 7)
+    for i in range(3):
+        us = np.array([oracle.multi_uniform(43, 7 + b, i) for b in range(B)])
+        check_sampled_ids(q64, us, o.cand_ids.cpu().numpy()[:, i], ref["cand_ids"][:, i], what="candidate %d" % i)
+    o = rdk.rdk_verify_multi(dev(p), dev(q), 3, 43, 7, cand_ids=dev(ref["cand_ids"]))
+    check_multi(o, ref, p64, q64, 43, 7, 3, min_exact=0.5)
 
 
 def test_pipeline_end_to_end(rdk, tiny):
