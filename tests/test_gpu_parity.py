@@ -1,5 +1,7 @@
 """GPU parity: every entry point of the C-ABI library against the CPU oracle, element by element, on
 seeded inputs small enough for the oracle yet spanning several tiles and a ragged tail."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -968,3 +970,50 @@ def test_tree_verification(rdk, tiny, ragged, case):
     assert not n_acc.any() and np.array_equal(toks.cpu().numpy()[:, 0], ref["token"][::nodes])
     with pytest.raises(rdk.RdkError):
         rdk.rdk_tree_walk(dev(child[:, :, :0].copy()), o.accepted, o.token)
+
+
+def test_tree_verification_replays_from_a_hip_graph(rdk, ragged):
+    """rdk_verify_multi + rdk_tree_walk recorded once and replayed on fresh inputs: every replay equals the eager calls."""
+    w = ragged["w"]
+    nodes, C = 7, 3
+    S = w.B // nodes
+    B = S * nodes
+    idx, wt, sw = ragged["sparse"]
+    qp32 = oracle_rows(ragged, "sparse", kernel=(idx, wt.astype(np.float32), sw.astype(np.float32))).astype(np.float32)[:B]
+    child, cand = random_trees(np.random.default_rng(8), S, nodes, C, qp32.astype(np.float64), 5, 0)
+    p_static, q_static, cand_d, child_d = dev(ragged["p"][:B]).clone(), dev(qp32).clone(), dev(cand), dev(child)
+    captured, eager = rdk.MultiOutputs(B, C, p_static.device), rdk.MultiOutputs(B, C, p_static.device)
+    n_cap = torch.zeros(S, dtype=torch.int32, device="cuda")
+    t_cap = torch.zeros((S, nodes), dtype=torch.int32, device="cuda")
+
+    def call(o, n_out=None, t_out=None):
+        o.cand_ids.copy_(cand_d)
+        d = rdk.MultiDesc(B=B, N=w.N, C=C, seed=5, offset=0, sample_candidates=0)
+        L = rdk.lib()
+        st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        P = lambda t: ctypes.c_void_p(t.data_ptr())
+        assert L.rdk_verify_multi(ctypes.byref(d), P(p_static), 0, w.N, P(q_static), w.N, P(o.cand_ids), P(o.accepted), P(o.token),
+                                  P(o.resid_mass), P(o.ws), o.ws.numel(), st) == 0
+        if n_out is not None:
+            assert L.rdk_tree_walk(S, nodes, C, P(child_d), P(o.accepted), P(o.token), P(n_out), P(t_out), st) == 0
+
+    for o in (captured, eager):      # sizes the workspaces outside the capture
+        rdk.rdk_verify_multi(p_static, q_static, C, 5, 0, cand_ids=cand_d, outputs=o)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(captured, n_cap, t_cap)
+    rng = np.random.default_rng(6)
+    for rep in range(3):
+        perm = rng.permutation(B)
+        p_static.copy_(dev(ragged["p"][:B][perm]))
+        captured.token.fill_(-9)
+        t_cap.fill_(-9)
+        graph.replay()
+        torch.cuda.synchronize()
+        call(eager)
+        n_e, t_e = rdk.rdk_tree_walk(child_d, eager.accepted, eager.token)
+        torch.cuda.synchronize()
+        for name in ("accepted", "token", "resid_mass"):
+            assert torch.equal(getattr(captured, name), getattr(eager, name)), "replay %d: %s" % (rep, name)
+        assert torch.equal(n_cap, n_e) and torch.equal(t_cap, t_e)
