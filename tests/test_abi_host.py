@@ -167,3 +167,11 @@ def test_descriptor_layouts_match_the_header(rdk, tmp_path):
             assert getattr(mirrors[struct], field).offset == int(value), key
         else:
             assert ctypes.sizeof(mirrors[key]) == int(value), key
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Everything here runs on one GPU: asking bench.py for more ends at once with a message that says so."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and not r.stdout.strip()
