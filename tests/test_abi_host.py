@@ -175,3 +175,15 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "one GPU" in r.stderr and not r.stdout.strip()
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/rdk.h on its own, as strict C99 and as C++: no torch or HIP types in the boundary."""
+    import subprocess
+    src = tmp_path / "only_header.c"
+    src.write_text('#include "rdk.h"\nint main(void) { return 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, "-fsyntax-only", str(src)], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-I", inc, "-fsyntax-only", "-x", "c++", str(src)], check=True)
+    text = open(os.path.join(inc, "rdk.h")).read()
+    assert "torch" not in text and "hip/" not in text
