@@ -147,9 +147,12 @@ def run_linear(args, rdk, synth, torch, w, vocab, batch, mode_name, path, steps,
         # 32 positions), against 64 bytes per clock and compute unit (256 units, 2.4 GHz)
         lines = (w.N - w.n) * kk * ((B + 31) // 32)
         l1_peak = 256 * 64 * 2.4          # GB/s
+        measured = 246.0e9 * 128 / 1e9    # GB/s: the bare line-gather loop of the `ceilings` program (profiles/ceilings_mi355x.md)
         res_extra["sparse_gather"] = {"lines_per_launch": lines, "achieved_GBs": round(lines * 128 / avg_s / 1e9, 1),
                                       "vector_l1_peak_GBs": round(l1_peak, 1),
-                                      "frac": round(lines * 128 / avg_s / 1e9 / l1_peak, 4)}
+                                      "frac": round(lines * 128 / avg_s / 1e9 / l1_peak, 4),
+                                      "bare_gather_loop_GBs": round(measured, 1),
+                                      "frac_of_bare_gather_loop": round(lines * 128 / avg_s / 1e9 / measured, 4)}
     return {"ms_per_step": ms_per_step, "value": B / (ms_per_step * 1e-3), "roofline": roofline, **res_extra,
             "kernels": {k: {"avg_us": round(v["avg_us"], 2), "per_step": v["launches_per_step"]} for k, v in per_kernel.items()},
             "step_algorithmic_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),

@@ -1,7 +1,9 @@
-// What this GPU sustains on the three resources that bound the redistribution kernels, measured with loops that do
+// What this GPU sustains on the resources that bound the redistribution kernels, measured with loops that do
 // nothing else: HBM streaming (read only, and read + write), the fp32 matrix instruction and the bf16 matrix
 // instruction (register operands only, independent accumulators, once with constant and once with varied data,
-// because the chip lowers its clock with the switching activity of the operands).  A stand-alone program:
+// because the chip lowers its clock with the switching activity of the operands), and gathers of whole 128-byte
+// lines at random out of a table that each XCD keeps in its own L2 (what the sparse product does with the
+// position-minor drafter table).  A stand-alone program:
 //   paper_2506_03206_amd/ceilings
 // The published peaks (8 TB/s, 157.3 TFLOP/s fp32, 2.5 PFLOP/s bf16) stay the denominators of every reported
 // fraction; these figures only say how much of the gap a kernel could close at all.
@@ -116,6 +118,31 @@ __global__ __launch_bounds__(256) void mfma_bf16_loop(float *out, const float *i
 // Mean kernel time over `reps` launches after one untimed launch, in milliseconds, from the dispatches' own begin and
 // end timestamps (no launch gaps).  The mean, not the best: under matrix load the clock settles over the first
 // launches, and the settled rate is the one a long kernel sees.  launch(r, start, stop) enqueues launch number r.
+// ---- line gathers -------------------------------------------------------------------------------------------------
+// Eight lanes share one random 128-byte line (16 bytes each), so a wavefront instruction asks for eight lines: the
+// access pattern of the sparse product.  Sixteen such loads are in flight per wavefront before the first is used.
+// Every XCD (consecutive workgroup ids go to consecutive XCDs) gathers from its own slab of `lines` lines.
+__global__ __launch_bounds__(512) void line_gather(const f32x4 *__restrict__ table, uint32_t lines, int iters,
+                                                   float *__restrict__ sink)
+{
+    const uint32_t lane = threadIdx.x & 63, part = lane & 7;
+    const f32x4 *slab = table + (size_t)(blockIdx.x % 8) * lines * 8;
+    uint32_t state = (blockIdx.x * 512u + threadIdx.x) / 8u * 2654435761u + 12345u;   // the same in the 8 lanes of a line
+    float acc = 0.f;
+    for (int it = 0; it < iters; ++it) {
+        f32x4 g[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            state = state * 1664525u + 1013904223u;
+            const uint32_t line = (state >> 8) % lines;
+            g[t] = slab[(size_t)line * 8 + part];
+        }
+#pragma unroll
+        for (int t = 0; t < 16; ++t) acc += g[t].x + g[t].y + g[t].z + g[t].w;
+    }
+    if (acc == 12345.678f) sink[0] = acc;
+}
+
 template <class F>
 static double mean_ms(F launch, int reps = 10)
 {
@@ -199,6 +226,20 @@ int main()
             });
             std::printf("mfma 32x32x16 bf16, %s data, %d waves/SIMD: %7.3f ms  %7.1f TFLOP/s\n", what, per_cu, ms,
                         (double)grid * 4 * iters16 * 4 * 8 * 32768.0 / ms / 1e9);
+        }
+    }
+    // line gathers: per-XCD slabs of 1, 2, 4 (the size of the sparse product's slab at n = 32064) and 8 MiB inside src
+    for (int mib : {1, 2, 4, 8}) {
+        const uint32_t lines = (uint32_t)((size_t(mib) << 20) / 128);
+        for (int per_cu : {2, 4}) {   // workgroups of 8 wavefronts per CU
+            const int grid = kCus * per_cu, iters = 64;
+            const double ms = mean_ms([&](int, hipEvent_t a, hipEvent_t b) {
+                hipExtLaunchKernelGGL(line_gather, dim3(grid), dim3(512), 0, 0, a, b, 0, src, lines, iters, sink);
+            });
+            const double n_lines = (double)grid * 8 * iters * 16 * 8;   // wavefronts x loads x lines per load
+            std::printf("128-byte line gathers, %d MiB slab per XCD, %d workgroups/CU: %7.3f ms  %6.1f G lines/s  %5.1f B/clk/CU  "
+                        "%4.2f clk per line and CU (at 2.4 GHz)\n", mib, per_cu, ms, n_lines / ms / 1e6,
+                        n_lines * 128 / kCus / (ms * 1e-3 * 2.4e9), ms * 1e-3 * 2.4e9 / (n_lines / kCus));
         }
     }
     CHECK(hipFree(src));
