@@ -117,7 +117,7 @@ rdk_status_t rdk_features_from_scores(const void *z, rdk_input_kind_t z_kind, in
                                       float *features, int64_t ldf, void *stream);
 
 /*
- * Build M into `storage` (Eq. 2; "calculated once at preprocessing time").  `storage` must stay
+ * Build M into `storage` (Eq. 2; a one-off preprocessing step, Sec. 3).  `storage` must stay
  * alive and untouched for the life of the kernel object; `workspace` may be reused once the
  * stream has passed the build.  *out receives the host handle.
  */
@@ -142,7 +142,10 @@ rdk_status_t rdk_workspace_bytes(const rdk_kernel_t *kernel, int32_t B, size_t *
 /*
  * Alg. 1, steps 1-2, exact form:  q_prime[b, :] = M^T TLI(q[b, :]).
  *   q        [B, ldq]  drafter weights or logits over the n kept slots (slot s <-> id kept_ids[s]).
- *            PROB: any non-negative row with a positive sum; step 1 (Eq. 1) divides by that sum.
+ *            PROB: any non-negative row; step 1 (Eq. 1) divides by its sum.  A row whose sum is zero has no
+ *            image under Eq. 1: every redistribution call (exact, both linear forms, the fused call and the
+ *            draft draw) returns the zero row for it, so that verification sees alpha = 0, resid_mass = sum(p),
+ *            draft_ids = -1, accept = 0, and draws resid_ids from the target row alone.
  *            LOGIT: the softmax over the n slots, which equals Eq. 1 applied to a full softmax.
  *   q_prime  [B, ldo]  fp32, the redistributed drafter over all N target ids.
  * Kernel format must be DENSE_F32, DENSE_BF16 or IDENTITY.  With DENSE_BF16 both operands are

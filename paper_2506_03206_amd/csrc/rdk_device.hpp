@@ -84,6 +84,10 @@ __device__ __forceinline__ double wave_inclusive_scan(double v)
 // and terms carry the same rounding.
 __device__ __forceinline__ float soft_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
 
+// 1 / (mass of a drafter row), and 0 for a row without mass: Eq. 1 is undefined there, and every redistribution
+// then returns the zero row (no token can be drafted from it; verification falls back on the target row alone).
+__device__ __forceinline__ float inv_mass(float z) { return z > 0.f ? 1.0f / z : 0.f; }
+
 // ---- softmax statistics (running maximum m and sum of exp(z - m)), merged pairwise
 struct SoftStat {
     float m, s;

@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kSplitWaves * kWave) __attribute__((amdgpu_waves_pe
         for (int v = 0; v < 16; ++v) {
             const int b = rg * kRowGroup + rb * 32 + 8 * (v / 4) + 4 * g + (v % 4);
             if (b >= B) continue;
-            const float sc = scale_here ? 1.0f / qstat[b].s : 1.f;
+            const float sc = scale_here ? inv_mass(qstat[b].s) : 1.f;
             const float o[4] = {acc[rb][0][v] * sc, acc[rb][1][v] * sc, acc[rb][2][v] * sc, acc[rb][3][v] * sc};
             float *drow = base + (int64_t)b * ldd + col;
             if (full && vec_d) {
@@ -192,7 +192,7 @@ __global__ void exact_reduce_kernel(const float *part, int64_t ldd, int64_t spli
                                     int N, float *out, int64_t ldo)
 {
     const int b = blockIdx.y;
-    const float sc = 1.0f / qstat[b].s;
+    const float sc = inv_mass(qstat[b].s);
     for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += (int64_t)gridDim.x * blockDim.x) {
         float s = 0.f;
         for (int z = 0; z < splits; ++z) s += part[(int64_t)z * split_stride + (int64_t)b * ldd + j];
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t
     const int rb = b / 32, r = b % 32;
     double mass = 0.0;
     const void *qr = b < B ? row_ptr<QK>(q, ldq, b) : nullptr;
-    const float qm = b < B ? qstat[b].m : 0.f, inv = b < B ? 1.0f / qstat[b].s : 0.f;
+    const float qm = b < B ? qstat[b].m : 0.f, inv = b < B ? inv_mass(qstat[b].s) : 0.f;
     for (int c = threadIdx.x; c < KB * 2; c += blockDim.x) {   // chunk of 8 consecutive slots
         const int kb = c / 2, g = c % 2;
         uint32_t w[4] = {0u, 0u, 0u, 0u};
@@ -299,7 +299,10 @@ __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t
     __shared__ double sh[4];
     if (lane_id() == 0) sh[threadIdx.x / kWave] = mass;
     __syncthreads();
-    if (threadIdx.x == 0 && b < B) out_scale[b] = (float)(1.0 / ((sh[0] + sh[1]) + (sh[2] + sh[3])));
+    if (threadIdx.x == 0 && b < B) {
+        const double total = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+        out_scale[b] = total > 0.0 ? (float)(1.0 / total) : 0.f;
+    }
 }
 
 // P'[512 x 128] per workgroup: W wavefronts, wavefront w owns RB row blocks (32 positions each) and all four

@@ -393,9 +393,9 @@ __device__ __forceinline__ TaylorRow<PK, QK> make_taylor_row(const TaylorArgs &a
         }
         zq = wave_sum(a0); tn = wave_sum(a1); an = wave_sum(a2); bs = wave_sum(a3);
     }
-    r.inv_zq = 1.0f / zq;
+    r.inv_zq = inv_mass(zq);                                   // a drafter row without mass gives the zero row
     r.theta = tn * r.inv_zq;
-    r.inv_S = 1.0f / (an * r.inv_zq + r.theta * bs);
+    r.inv_S = inv_mass(an * r.inv_zq + r.theta * bs);
     r.nzs = r.fN * r.inv_zq * r.inv_S;
     r.ths = r.theta * r.inv_S;
     return r;
@@ -496,7 +496,7 @@ __global__ __launch_bounds__(kThreads) void tli_scatter_kernel(const void *q, in
 {
     const int64_t row = blockIdx.y;
     const void *qr = row_ptr<QK>(q, ldq, row);
-    const float qm = qstat[row].m, inv = 1.0f / qstat[row].s;
+    const float qm = qstat[row].m, inv = inv_mass(qstat[row].s);
     for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < N; j += (int64_t)gridDim.x * kThreads) {
         const int s = slot_of[j];
         out[row * ldo + j] = s >= 0 ? to_weight<QK>(load1<QK>(qr, s), qm, 1.f) * inv : 0.f;

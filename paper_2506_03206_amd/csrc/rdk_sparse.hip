@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
                     if (st.s > 0.f) z += QK == RDK_PROB_F32 ? st.s : st.s * soft_exp(st.m - m);
                 }
             z = oct_sum(z);
-            if (part == 0) zinv[b] = (b < B && z > 0.f) ? 1.0f / z : 0.f;
+            if (part == 0) zinv[b] = b < B ? inv_mass(z) : 0.f;
         }
         if (QK != RDK_PROB_F32) __syncthreads();
     }

@@ -53,8 +53,8 @@ def check_verify_outputs(o, ref, p64, q64, seed, offset, gamma, p_kind, min_exac
         assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], what="sum p")
         assert not o.accept.any() and not o.alpha.any()
         return
-    assert_close(o.alpha.cpu().numpy(), ref["alpha"], rtol=2 * RTOL, what="alpha")
-    assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], rtol=2 * RTOL, atol=2e-7, what="residual mass")
+    assert_close(o.alpha.cpu().numpy(), ref["alpha"], what="alpha")
+    assert_close(o.resid_mass.cpu().numpy(), ref["resid_mass"], what="residual mass")
     g_draft = o.draft_ids.cpu().numpy()
     n_d = check_sampled_ids(q64, us[:, 0], g_draft, ref["draft_ids"], what="draft")
     n_r = check_sampled_ids(np.maximum(p64 - q64, 0), us[:, 2], g_resid, ref["resid_ids"], what="residual")
@@ -64,7 +64,7 @@ def check_verify_outputs(o, ref, p64, q64, seed, offset, gamma, p_kind, min_exac
     g_acc = o.accept.cpu().numpy()
     for b in np.nonzero(same & (g_acc != ref["accept"]))[0]:      # a flip is allowed only at a near-tie
         d_ = g_draft[b]
-        assert d_ >= 0 and abs(us[b, 1] * q64[b, d_] - p64[b, d_]) <= 2e-5 * p64[b, d_], (b, d_)
+        assert d_ >= 0 and abs(us[b, 1] * q64[b, d_] - p64[b, d_]) <= CDF_TOL * p64[b, d_], (b, d_)
     if gamma:
         n_acc, toks = oracle.sequence_scan(g_acc, g_draft, g_resid, gamma)     # scan of the device's own flags
         assert np.array_equal(o.n_accepted.cpu().numpy(), n_acc)
@@ -101,17 +101,17 @@ def check_multi(o, ref, p64, q64, seed, offset, C, min_exact=0.9):
             exact += 1
             nrej = int(g_acc[b])                     # rejections before the kept candidate (all C when none was kept)
             if nrej:
-                assert_close(g_rm[b, :nrej], ref["resid_mass"][b, :nrej], rtol=5e-5, atol=1e-7, what="residual mass per round")
+                assert_close(g_rm[b, :nrej], ref["resid_mass"][b, :nrej], what="residual mass per round")
             assert not g_rm[b, nrej:].any()
             continue
         tests, r_fin, u_fin = multi_chain(p64[b], q64[b], cand, seed, offset + b)
         first = min(int(g_acc[b]), int(ref["accepted"][b]))
         if g_acc[b] != ref["accepted"][b]:          # a decision flipped: it must have been a near-tie
             lhs, rhs = tests[first]
-            assert abs(lhs - rhs) <= 5e-5 * max(rhs, 1e-30), (b, first, lhs, rhs)
+            assert abs(lhs - rhs) <= CDF_TOL * max(rhs, 1e-30), (b, first, lhs, rhs)
         else:                                       # same rounds, another final token: a prefix-sum step on the threshold
             assert g_acc[b] == C
-            check_sampled_ids(r_fin[None], np.array([u_fin]), g_tok[b:b + 1], ref["token"][b:b + 1], tol=5e-5, what="final draw")
+            check_sampled_ids(r_fin[None], np.array([u_fin]), g_tok[b:b + 1], ref["token"][b:b + 1], what="final draw")
     assert exact >= min_exact * p64.shape[0], exact
     return exact
 
