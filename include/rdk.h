@@ -207,6 +207,21 @@ rdk_status_t rdk_verify_sample(const rdk_verify_desc_t *desc, const void *p, rdk
                                size_t workspace_bytes, void *stream);
 
 /*
+ * rdk_verify_sample for callers that can neither allocate device memory nor hand in a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation): same arguments without the workspace, same
+ * kernels, same outputs bit for bit.  The scratch (the per-block sums, and the softmax statistics of logit rows) lives
+ * in a device array inside the library, 4 MiB per GPU, held until the process ends; the call allocates and frees
+ * nothing.  A batch whose scratch need (rdk_verify_workspace_bytes minus its 256 bytes of slack, about
+ * 12 * B * ceil(N / 1024) bytes) exceeds 4 MiB is refused with RDK_ERR_WORKSPACE and nothing is launched.  All calls
+ * on one GPU share the one array: calls that overlap on one GPU (different streams, or different threads) race and
+ * must be ordered by the caller; nothing in it needs clearing between calls.  Runs on the current device.
+ */
+rdk_status_t rdk_verify_sample_static(const rdk_verify_desc_t *desc, const void *p, rdk_input_kind_t p_kind,
+                                      int64_t ldp, const float *q_prime, int64_t ldq, int32_t *draft_ids,
+                                      uint8_t *accept, float *alpha, float *resid_mass, int32_t *resid_ids,
+                                      int32_t *n_accepted, int32_t *out_tokens, void *stream);
+
+/*
  * Alg. 1 steps 1-2 and Alg. 4 steps 2, 4-10 in one call: the outputs of rdk_redistribute_linear(mode)
  * followed by rdk_verify_sample on its result, without the round trip of q' through HBM.  The
  * redistributed rows are produced tile by tile, summed against p on the spot, and re-computed for the

@@ -479,6 +479,30 @@ rdk_status_t rdk_verify_sample(const rdk_verify_desc_t *desc, const void *p, rdk
                          workspace, (hipStream_t)stream);
 }
 
+rdk_status_t rdk_verify_sample_static(const rdk_verify_desc_t *desc, const void *p, rdk_input_kind_t p_kind, int64_t ldp,
+                                      const float *q_prime, int64_t ldq, int32_t *draft_ids, uint8_t *accept, float *alpha,
+                                      float *resid_mass, int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens,
+                                      void *stream)
+{
+    rdk_status_t rc = check_verify_desc(desc);
+    if (rc != RDK_OK) return rc;
+    rc = check_rows(p, p_kind, ldp, desc->N);
+    if (rc != RDK_OK) return rc;
+    if (!accept || !resid_ids) return RDK_ERR_NULL;
+    if (q_prime) {
+        if (!draft_ids) return RDK_ERR_NULL;
+        if (ldq < desc->N) return RDK_ERR_SHAPE;
+        if (!aligned16(q_prime)) return RDK_ERR_ALIGN;
+    } else if (desc->gamma != 0 || n_accepted || out_tokens) {
+        return RDK_ERR_UNSUPPORTED;
+    }
+    if (desc->gamma == 0 && (n_accepted || out_tokens)) return RDK_ERR_SHAPE;
+    if (verify_workspace_bytes(*desc) > verify_static_scratch_limit()) return RDK_ERR_WORKSPACE;
+    RowInput pi{p, p_kind, ldp};
+    return launch_verify_static(*desc, pi, q_prime, ldq, draft_ids, accept, alpha, resid_mass, resid_ids, n_accepted,
+                                out_tokens, (hipStream_t)stream);
+}
+
 static rdk_status_t check_multi_desc(const rdk_multi_desc_t *d)
 {
     if (!d) return RDK_ERR_NULL;

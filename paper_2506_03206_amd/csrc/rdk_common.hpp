@@ -148,6 +148,10 @@ size_t verify_workspace_bytes(const rdk_verify_desc_t &d);
 rdk_status_t launch_verify(const rdk_verify_desc_t &d, RowInput p, const float *q_prime, int64_t ldq,
                            int32_t *draft_ids, uint8_t *accept, float *alpha, float *resid_mass,
                            int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens, void *ws, hipStream_t st);
+size_t verify_static_scratch_limit();
+rdk_status_t launch_verify_static(const rdk_verify_desc_t &d, RowInput p, const float *q_prime, int64_t ldq,
+                                  int32_t *draft_ids, uint8_t *accept, float *alpha, float *resid_mass,
+                                  int32_t *resid_ids, int32_t *n_accepted, int32_t *out_tokens, hipStream_t st);
 rdk_status_t launch_philox_words(uint64_t seed, uint64_t offset, int32_t count, uint32_t *words, hipStream_t st);
 
 }  // namespace rdk

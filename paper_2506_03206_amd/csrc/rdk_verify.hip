@@ -9,6 +9,8 @@
 //                     the partial sums, then re-read), the accept test, and the per-sequence scan
 // The streaming pass is bound by HBM: 8 bytes per (position, id), nothing is written but 12 bytes
 // per 1024 ids.
+#include <mutex>
+
 #include "rdk_finalize.hpp"
 
 namespace rdk {
@@ -236,6 +238,43 @@ rdk_status_t launch_verify(const rdk_verify_desc_t &d, RowInput p, const float *
     }
 #undef RDK_VERIFY_CASE
     return RDK_ERR_DTYPE;
+}
+
+// ---- verification without a caller workspace: the scratch of the two kernels lives in a device array of this
+// library, one copy per GPU, held until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+size_t verify_static_scratch_limit() { return kStaticScratchBytes; }
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up once per GPU
+}  // namespace
+
+rdk_status_t launch_verify_static(const rdk_verify_desc_t &d, RowInput p, const float *q_prime, int64_t ldq, int32_t *draft_ids,
+                                  uint8_t *accept, float *alpha, float *resid_mass, int32_t *resid_ids, int32_t *n_accepted,
+                                  int32_t *out_tokens, hipStream_t st)
+{
+    if (verify_workspace_bytes(d) > kStaticScratchBytes) return RDK_ERR_WORKSPACE;
+    int dev = -1;
+    RDK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return RDK_ERR_UNSUPPORTED;
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            // the array's name is a host-side handle, not a device address: every use below goes through `ptr`
+            void *sym = nullptr;
+            RDK_HIP(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+            if (!sym) return RDK_ERR_HIP;
+            g_scratch_ptr[dev] = sym;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    // nothing in the scratch has to start at zero: the streaming pass writes every block sum the finish step reads
+    return launch_verify(d, p, q_prime, ldq, draft_ids, accept, alpha, resid_mass, resid_ids, n_accepted, out_tokens, ptr, st);
 }
 
 rdk_status_t launch_sequence_scan(const rdk_verify_desc_t &d, const int32_t *draft_ids, const uint8_t *accept,

@@ -24,7 +24,7 @@ EXPORTS = [
     "rdk_redistribute_linear", "rdk_verify_workspace_bytes", "rdk_verify_sample", "rdk_philox_words",
     "rdk_timing_select", "rdk_timing_read", "rdk_redistribute_verify_workspace_bytes", "rdk_redistribute_verify",
     "rdk_sample_draft_workspace_bytes", "rdk_sample_draft", "rdk_features_from_scores",
-    "rdk_verify_multi_workspace_bytes", "rdk_verify_multi", "rdk_tree_walk",
+    "rdk_verify_multi_workspace_bytes", "rdk_verify_multi", "rdk_tree_walk", "rdk_verify_sample_static",
 ]
 
 
@@ -82,6 +82,8 @@ def lib():
         L.rdk_verify_workspace_bytes.argtypes = [ctypes.POINTER(VerifyDesc), psz]
         L.rdk_verify_sample.argtypes = [ctypes.POINTER(VerifyDesc), vp, ctypes.c_int, i64, vp, i64, vp, vp, vp, vp, vp, vp,
                                         vp, vp, sz, vp]
+        L.rdk_verify_sample_static.argtypes = [ctypes.POINTER(VerifyDesc), vp, ctypes.c_int, i64, vp, i64, vp, vp, vp, vp, vp,
+                                               vp, vp, vp]
         L.rdk_philox_words.argtypes = [ctypes.c_uint64, ctypes.c_uint64, i32, vp, vp]
         L.rdk_redistribute_verify_workspace_bytes.argtypes = [vp, ctypes.c_int, ctypes.POINTER(VerifyDesc), psz]
         L.rdk_redistribute_verify.argtypes = [vp, ctypes.c_int, ctypes.POINTER(VerifyDesc), vp, ctypes.c_int, i64, vp,
@@ -263,6 +265,23 @@ def rdk_verify_sample(p, q_prime, seed, offset=0, gamma=0, p_kind="prob", draft_
                                    _ptr(o.draft_ids), _ptr(o.accept), _ptr(o.alpha), _ptr(o.resid_mass), _ptr(o.resid_ids),
                                    _ptr(o.n_accepted), _ptr(o.out_tokens), _ptr(o.ws), o.ws.numel(), _stream()),
            "rdk_verify_sample")
+    return o
+
+
+def rdk_verify_sample_static(p, q_prime, seed, offset=0, gamma=0, p_kind="prob", draft_ids=None, outputs=None):
+    """rdk_verify_sample without a workspace: the scratch is a fixed device array inside the library.  `outputs` must
+    be given (the call itself allocates nothing); its own workspace tensor is not used."""
+    B, N = p.shape
+    o = outputs
+    assert o is not None and (o.B, o.N, o.gamma) == (B, N, gamma)
+    if draft_ids is not None:
+        o.draft_ids.copy_(draft_ids)
+    d = VerifyDesc(B=B, N=N, gamma=gamma, sample_draft=0 if draft_ids is not None else 1, seed=seed, offset=offset)
+    ldq = 0 if q_prime is None else _rows(q_prime)
+    _check(lib().rdk_verify_sample_static(ctypes.byref(d), _ptr(p), _kind_of(p, p_kind), _rows(p), _ptr(q_prime), ldq,
+                                          _ptr(o.draft_ids), _ptr(o.accept), _ptr(o.alpha), _ptr(o.resid_mass),
+                                          _ptr(o.resid_ids), _ptr(o.n_accepted), _ptr(o.out_tokens), _stream()),
+           "rdk_verify_sample_static")
     return o
 
 
