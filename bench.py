@@ -49,6 +49,7 @@ def algorithmic_bytes(kernel, w, B, kk, fused, esz):
         "sparse_product_kernel": B * ((esz if fused else 4) * N + 4 * n) + tables,   # read q^T, p (fused) or write q'
         "taylor_stats_kernel": B * esz * (N + n) + ids,                     # read p, q
         "taylor_write_kernel": B * (esz * (N + n) + (0 if fused else 4 * N)) + ids,
+        "taylor_row_kernel": B * esz * (N + n) + ids,                       # one pass: p and q read once
         "q_transpose_kernel": B * (esz + 4) * n,
         "row_stats_kernel": B * esz * n,
         "verify_finalize_kernel": B * 3 * 4 * ((N + 1023) // 1024),
@@ -100,7 +101,7 @@ def run_linear(args, rdk, synth, torch, w, vocab, batch, mode_name, path, steps,
 
     # which kernel dominates?  a short pass with every kernel bracketed by events
     names = ["row_stats_kernel", "q_transpose_kernel", "sparse_product_kernel", "taylor_stats_kernel", "taylor_write_kernel",
-             "verify_stream_kernel", "verify_finalize_kernel"]
+             "taylor_row_kernel", "verify_stream_kernel", "verify_finalize_kernel"]
     rdk.rdk_timing_select("*")
     for i in range(20):
         step(i)

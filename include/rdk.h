@@ -317,7 +317,7 @@ rdk_status_t rdk_philox_words(uint64_t seed, uint64_t offset, int32_t count, uin
  * recorded events of that kernel, returns how many launches were recorded and their summed
  * elapsed time in milliseconds, and forgets them.  Both take HOST strings.  Names:
  * row_stats_kernel, row_block_sums_kernel, verify_stream_kernel, verify_finalize_kernel, draft_finalize_kernel,
- * sequence_scan_kernel, taylor_stats_kernel, taylor_write_kernel, tli_scatter_kernel, tree_walk_kernel, verify_multi_kernel,
+ * sequence_scan_kernel, taylor_stats_kernel, taylor_write_kernel, taylor_row_kernel, tli_scatter_kernel, tree_walk_kernel, verify_multi_kernel,
  * q_transpose_kernel, sparse_product_kernel, prep_a_split_kernel, exact_f32_split_kernel,
  * exact_reduce_kernel, prep_a_bf16_kernel, exact_bf16_kernel.
  */

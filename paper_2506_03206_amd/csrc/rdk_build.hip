@@ -137,6 +137,26 @@ __global__ void pruned_ids_kernel(const int32_t *slot_of, int N, int32_t *pruned
     if (j < N && slot_of[j] < 0) pruned_ids[-slot_of[j] - 1] = j;
 }
 
+// Per chunk and lane the kept mask of the lane's 16 ids and the kept ids of the chunk below each of its four groups.
+__global__ void lane_map_kernel(const int32_t *slot_of, const int32_t *chunk_lo, int N, int n, uint64_t *lane_map)
+{
+    const int c = blockIdx.x, l = threadIdx.x;
+    const int lo = chunk_lo[c];
+    uint64_t rec = 0;
+    for (int i = 0; i < 4; ++i) {
+        const int j0 = c * kChunk + 256 * i + 4 * l;
+        int below = n;                                     // kept ids below j0 in the whole vocabulary
+        if (j0 < N) {
+            const int s = slot_of[j0];
+            below = s >= 0 ? s : j0 - (-s - 1);
+        }
+        rec |= (uint64_t)(below - lo) << (16 + 12 * i);
+        for (int e = 0; e < 4; ++e)
+            if (j0 + e < N && slot_of[j0 + e] >= 0) rec |= (uint64_t)1 << (4 * i + e);
+    }
+    lane_map[(int64_t)c * kWave + l] = rec;
+}
+
 // Cosine similarities of a 64 x 64 tile: rows = ids `row_ids[r0..]`, columns = ids `col_ids[c0..]`
 // (NULL id list = the identity).  256 threads, each a 4 x 4 micro-tile in fp64; the result is left in
 // om[64][65].  Entries outside the ranges are -2 (below any cosine).
@@ -413,6 +433,15 @@ rdk_status_t launch_features_from_scores(const void *z, rdk_input_kind_t kind, i
         default: return RDK_ERR_DTYPE;
     }
     RDK_LAUNCH_CHECK("features_from_scores_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_lane_map(const int32_t *slot_of, const int32_t *chunk_lo, int32_t N, int32_t n, uint64_t *lane_map,
+                             hipStream_t st)
+{
+    const int nchunks = (N + kChunk - 1) / kChunk;
+    hipLaunchKernelGGL(lane_map_kernel, dim3(nchunks), dim3(kWave), 0, st, slot_of, chunk_lo, N, n, lane_map);
+    RDK_LAUNCH_CHECK("lane_map_kernel");
     return RDK_OK;
 }
 

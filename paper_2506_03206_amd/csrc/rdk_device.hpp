@@ -45,6 +45,16 @@ __device__ __forceinline__ double lane_value(double v, int src)
     return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
 }
 
+// sum over each row of 16 lanes, the same bits in all 16
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    return v;
+}
+
 // sum over the 64 lanes, the same bits in every lane
 template <typename T>
 __device__ __forceinline__ T wave_sum(T v)

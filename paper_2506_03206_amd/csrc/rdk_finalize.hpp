@@ -215,6 +215,7 @@ __device__ __forceinline__ int search_block(const float4 (&wv)[SUB], int base, d
 }
 
 constexpr int kFinalizeRows = 8;   // rows (wavefronts) per workgroup at most: leaves 256 VGPRs per lane
+constexpr int kSpreadMinRows = 128;   // from this many rows on every row gets a workgroup of its own
 
 // BLOCK = ids per block of partial sums: a multiple of 256, or 64 (then only 16 lanes of the wavefront hold ids).
 template <int KIND, int BLOCK, bool HAS_Q, class QP>
@@ -464,8 +465,12 @@ rdk_status_t launch_finalize(FinalizeArgs a, QP qp, hipStream_t st)
 {
     const rdk_verify_desc_t &d = a.d;
     // a policy that re-computes q' is heavy on the vector memory pipe of its CU: give every row a CU of its own
-    a.scan_here = d.gamma >= 1 && d.gamma <= kFinalizeRows && !QP::kSpreadRows;
-    a.rows_per_block = a.scan_here ? d.gamma : (QP::kSpreadRows ? 1 : 4);
+    // One wavefront per row is bound by its own chain of dependent steps, and eight of them on one compute unit share
+    // its four vector units: a large batch gets a compute unit per row (and the per-sequence scan a launch of its own),
+    // a small one keeps a sequence together and scans it in place.
+    const bool spread = QP::kSpreadRows || d.B >= kSpreadMinRows;
+    a.scan_here = d.gamma >= 1 && d.gamma <= kFinalizeRows && !spread;
+    a.rows_per_block = a.scan_here ? d.gamma : (spread ? 1 : 4);
     const int blocks = (d.B + a.rows_per_block - 1) / a.rows_per_block;
     {
         RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_kernel<KIND, BLOCK, HAS_Q, QP>), dim3(blocks),

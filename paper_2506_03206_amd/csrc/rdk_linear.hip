@@ -479,6 +479,308 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) v
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Eq. 3 and the verification sums in ONE pass over the target row (the fused call on probability rows when q' is not
+// asked for).  The two-pass kernels above read p twice because the row constants (theta, sum of pt) are only known
+// after the whole row has been seen.  Here one workgroup of sixteen wavefronts owns one position and keeps what the
+// second step needs on chip:
+//   * an id j that is not kept has q'_j = (theta / S) p_j / (N + p_j), which is below p_j (theta <= 1, S >= 1/2,
+//     N >= 2), so its share of the three block sums is a closed form of  P = sum p_j  and  A = sum p_j / (N + p_j)
+//     over the not-kept ids of the block: sum q' = sum min(p, q') = (theta / S) A,  sum max(0, p - q') = P - (theta / S) A;
+//   * a kept id needs its own p and q^: while the row streams by, the target values of the kept ids are scattered
+//     into LDS in slot order (4 n bytes: one value per drafter slot) and the drafter row sits in registers
+//     (eight quads of slots per lane).
+// Step A streams p next to the id -> slot map (L2-resident, shared by all rows); step B sums q^, q^ p and q^ / (N + p)
+// over the slots out of LDS and registers; step C forms q', min and max for the kept slots and sums them per
+// 1024-id chunk (the slots of a chunk are a contiguous run, so a row of 256 slots meets few chunks; partial sums of
+// a chunk that spans several rows are added in row order).  HBM traffic: p and q once.
+constexpr int kRowThreads = 1024;
+constexpr int kRowWaves = kRowThreads / kWave;
+constexpr int kRowQuads = 8;             // quads of slots a lane parks: n <= 4 * kRowThreads * kRowQuads
+constexpr int kRowSpan = 5;              // rows of 256 slots that the run of one chunk can touch
+
+struct RowLds {      // offsets in floats into the dynamic LDS block
+    int pk, spare, blk_p, blk_a, kp, red, clo, total;
+};
+
+__host__ __device__ inline RowLds row_lds_layout(int n, int nchunks)
+{
+    RowLds L;
+    int off = 0;
+    L.pk = off; off += (n + 3) & ~3;                   // target values of the kept ids, by slot
+    L.spare = off; off += kWave;                       // where the lanes send the values of ids that are not kept
+    L.blk_p = off; off += (nchunks + 3) & ~3;          // per chunk: sum of p over the not-kept ids
+    L.blk_a = off; off += (nchunks + 3) & ~3;          //            sum of p / (N + p) over the not-kept ids
+    L.kp = off; off += 3 * nchunks * kRowSpan * 4;     // per chunk, row of slots and quarter wavefront: sums of q', max(0, p - q'), min(p, q')
+    L.red = off; off += kRowWaves * 4;
+    L.clo = off; off += (nchunks + 1 + 3) & ~3;        // chunk_lo, as integers
+    L.total = off;
+    return L;
+}
+
+// One chunk of target values (16 ids per lane, the layout of load_chunk), the lane's record of the kernel's lane map
+// for that chunk, and the chunk's first slot.
+struct RowChunk {
+    float4 p[4];
+    uint64_t map;
+    int lo;
+};
+
+__device__ __forceinline__ void row_fetch(const float *pr, const uint64_t *lane_map, const int32_t *chunk_lo, int c, int N,
+                                          bool vec_p, RowChunk &b)
+{
+    load_chunk<RDK_PROB_F32>(pr, (int64_t)c * kChunk, N, vec_p, 0.f, b.p);
+    b.map = lane_map[(int64_t)c * kWave + lane_id()];
+    b.lo = chunk_lo[c];
+}
+
+// 1 / (N + p) for 0 <= p <= 1.  For a large vocabulary the first two terms of the series in p / N are exact to fp32
+// rounding (the next term is (p / N)^2 <= 2^-24 of the result for N >= 4096) and cost one multiply-add instead of a
+// reciprocal, which the vector unit issues at a quarter of the rate.
+struct RowRcp {
+    float fN, invN, invN2;
+    bool series;
+    __device__ __forceinline__ float operator()(float p) const
+    {
+        return series ? fmaf(-p, invN2, invN) : __builtin_amdgcn_rcpf(fN + p);
+    }
+};
+
+// Step A for one chunk: target values of kept ids go to their slots in LDS (the others to a spare word of the lane),
+// the not-kept ones are summed.
+template <bool SERIES>
+__device__ __forceinline__ void row_scatter(const RowChunk &b, const RowRcp &rcp, float *pk, int spare_idx, float &sp, float &sa)
+{
+    const uint32_t mask = (uint32_t)b.map & 0xFFFFu;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int idx = b.lo + (int)((b.map >> (16 + 12 * i)) & 0xFFFu);   // slot of the lane's first kept id of this group
+        const float pe[4] = {b.p[i].x, b.p[i].y, b.p[i].z, b.p[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool is_kept = (mask >> (4 * i + e)) & 1u;
+            const float r = SERIES ? fmaf(-pe[e], rcp.invN2, rcp.invN) : __builtin_amdgcn_rcpf(rcp.fN + pe[e]);
+            pk[is_kept ? idx : spare_idx] = pe[e];
+            idx += is_kept ? 1 : 0;
+            const float pn = is_kept ? 0.f : pe[e];
+            sp += pn;
+            sa = fmaf(pn, r, sa);
+        }
+    }
+}
+
+template <int QK, bool SERIES>
+__global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p, int64_t ldp, const void *q, int64_t ldq,
+                                                                 const int32_t *kept, const uint64_t *lane_map,
+                                                                 const int32_t *chunk_lo, int N, int n, bool vec_p, bool vec_q,
+                                                                 const SoftStat *qstat, float *tpart, float *part_q,
+                                                                 float *part_r, float *part_a)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int nchunks = (N + kChunk - 1) / kChunk;
+    const RowLds L = row_lds_layout(n, nchunks);
+    float *pk = lds + L.pk;
+    const int64_t row = blockIdx.x;
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
+    const float *pr = p + row * ldp;
+    const void *qr = row_ptr<QK>(q, ldq, row);
+    const float qm = QK == RDK_PROB_F32 ? 0.f : qstat[row].m;
+    const float fN = (float)N;
+    RowRcp rcp;
+    rcp.fN = fN;
+    rcp.invN = 1.0f / fN;
+    rcp.invN2 = rcp.invN * rcp.invN;
+    rcp.series = SERIES;
+    const int spare_idx = (L.spare - L.pk) + lane;    // relative to pk
+
+    // ---- the small tables first (loads come back in issue order: behind the row they would wait for it): chunk_lo into
+    // LDS, and the first chunk of each of this wavefront's rows of 256 slots (row wid + 16 k; scalar loads, for step C)
+    int *clo = (int *)(lds + L.clo);
+    for (int i = threadIdx.x; i <= nchunks; i += kRowThreads) clo[i] = chunk_lo[i];
+    int c_first[kRowQuads];
+#pragma unroll
+    for (int k = 0; k < kRowQuads; ++k) c_first[k] = kept[min(256 * (wid + kRowWaves * k), n - 1)] >> 10;
+    // ---- then the first two chunks are asked for, and the drafter row goes into registers (lane t, quad k: slots
+    // 4 (t + 1024 k) .. + 3)
+    RowChunk b0, b1, b2;
+    int c = wid;
+    if (c < nchunks) row_fetch(pr, lane_map, chunk_lo, c, N, vec_p, b0);
+    if (c + kRowWaves < nchunks) row_fetch(pr, lane_map, chunk_lo, c + kRowWaves, N, vec_p, b1);
+    // the drafter weights: quads beyond n are read at a clamped address and zeroed, so that no load sits behind a branch
+    // (a branch would make every load wait for the one before it)
+    float4 qh[kRowQuads];
+    const bool whole_quads = vec_q && (n & 3) == 0 && n >= 4;   // the same for all lanes
+    if (whole_quads) {
+#pragma unroll
+        for (int k = 0; k < kRowQuads; ++k) {
+            const int s = 4 * ((int)threadIdx.x + kRowThreads * k);
+            qh[k] = load4_full<QK>(qr, min(s, n - 4));
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < kRowQuads; ++k) {
+            const int s = 4 * ((int)threadIdx.x + kRowThreads * k);
+            qh[k] = load4<QK>(qr, min(s, n), n, false, QK == RDK_PROB_F32 ? 0.f : -INFINITY);   // min: no overflow of the index
+        }
+    }
+    for (int i = threadIdx.x; i < 3 * nchunks * kRowSpan * 4; i += kRowThreads) lds[L.kp + i] = 0.f;
+    if ((int)threadIdx.x < ((n + 3) & ~3) - n) pk[n + threadIdx.x] = 0.f;   // the padding of the last quad
+    // (no barrier here: it would wait for the loads just issued; nothing of the above is read before the barrier behind step A)
+
+    // ---- step A: one pass over the row, two chunks requested ahead of the one being worked on
+    float bs = 0.f;                                   // sum of p / (N + p) over the ids that are not kept
+#define RDK_ROW_STEP(CUR, FREE)                                                                              \
+    {                                                                                                        \
+        if (c + 2 * kRowWaves < nchunks) row_fetch(pr, lane_map, chunk_lo, c + 2 * kRowWaves, N, vec_p, FREE); \
+        float sp = 0.f, sa = 0.f;                                                                            \
+        row_scatter<SERIES>(CUR, rcp, pk, spare_idx, sp, sa);                                                \
+        sp = wave_sum(sp);                                                                                   \
+        sa = wave_sum(sa);                                                                                   \
+        bs += sa;                                                                                            \
+        if (lane == 0) {                                                                                     \
+            lds[L.blk_p + c] = sp;                                                                           \
+            lds[L.blk_a + c] = sa;                                                                           \
+        }                                                                                                    \
+        c += kRowWaves;                                                                                      \
+    }
+    while (c < nchunks) {
+        RDK_ROW_STEP(b0, b2)
+        if (c >= nchunks) break;
+        RDK_ROW_STEP(b1, b0)
+        if (c >= nchunks) break;
+        RDK_ROW_STEP(b2, b1)
+    }
+#undef RDK_ROW_STEP
+    __syncthreads();
+
+    // ---- step B: sums over the kept slots, the row constants.  Weights become zero beyond n; the target values are read
+    // at a clamped slot there (finite), so those terms vanish.
+    const int n_pad = (n + 3) & ~3;
+    float zq = 0.f, tn = 0.f, an = 0.f, bk = 0.f;     // bk: sum of p / (N + p) over the kept ids
+#pragma unroll
+    for (int k = 0; k < kRowQuads; ++k) {
+        const int s = 4 * ((int)threadIdx.x + kRowThreads * k);
+        const float4 w4 = qh[k];
+        const float we[4] = {to_weight<QK>(w4.x, qm, 1.f), to_weight<QK>(w4.y, qm, 1.f), to_weight<QK>(w4.z, qm, 1.f),
+                             to_weight<QK>(w4.w, qm, 1.f)};
+        qh[k] = make_float4(s + 0 < n ? we[0] : 0.f, s + 1 < n ? we[1] : 0.f, s + 2 < n ? we[2] : 0.f, s + 3 < n ? we[3] : 0.f);
+        const float4 pv = *(const float4 *)(pk + min(s, n_pad - 4));
+        const float pe[4] = {pv.x, pv.y, pv.z, pv.w}, qe[4] = {qh[k].x, qh[k].y, qh[k].z, qh[k].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float r = rcp(pe[e]);
+            zq += qe[e];
+            tn = fmaf(qe[e], pe[e], tn);
+            an = fmaf(qe[e], r, an);
+            bk = fmaf(s + e < n ? pe[e] : 0.f, r, bk);   // the clamped reads beyond n must not count
+        }
+    }
+    zq = wave_sum(zq);
+    tn = wave_sum(tn);
+    an = wave_sum(an) * fN;
+    bk = wave_sum(bk);
+    if (lane == 0) *(float4 *)(lds + L.red + wid * 4) = make_float4(zq, tn, an, bs + bk);
+    __syncthreads();
+    float tot[4];
+    {
+        float4 t = *(const float4 *)(lds + L.red);
+        for (int i = 1; i < kRowWaves; ++i) {
+            const float4 o = *(const float4 *)(lds + L.red + i * 4);
+            t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w;
+        }
+        tot[0] = t.x; tot[1] = t.y; tot[2] = t.z; tot[3] = t.w;
+        if (threadIdx.x == 0) *(float4 *)(tpart + row * 4) = t;   // the finish step forms the same constants from these
+    }
+    const float inv_zq = inv_mass(tot[0]);
+    const float theta = tot[1] * inv_zq;
+    const float inv_S = inv_mass(tot[2] * inv_zq + theta * tot[3]);
+    const float nzs = fN * inv_zq * inv_S, ths = theta * inv_S;
+
+    // ---- step C: q' on the kept slots, summed per chunk.  A slot belongs to chunk cc when it lies in [clo[cc], clo[cc + 1]).
+#pragma unroll
+    for (int k = 0; k < kRowQuads; ++k) {
+        const int r256 = wid + kRowWaves * k;          // this wavefront's row of 256 slots
+        const int s_row = r256 * 256;
+        if (s_row >= n) break;                         // the same for the whole wavefront
+        const int s = s_row + 4 * lane;
+        const float4 pv = *(const float4 *)(pk + min(s, n_pad - 4));
+        const float pe[4] = {pv.x, pv.y, pv.z, pv.w}, qe[4] = {qh[k].x, qh[k].y, qh[k].z, qh[k].w};
+        float vq[4], vr[4], va[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float v = (nzs * qe[e] + ths * pe[e]) * rcp(pe[e]);
+            vq[e] = v;
+            vr[e] = fmaxf(pe[e] - v, 0.f);
+            va[e] = fminf(pe[e], v);
+        }
+        int cc = c_first[k];
+        int lo_c = __builtin_amdgcn_readfirstlane(clo[cc]);
+        const int row_first = lo_c >> 8;               // the first row of slots that the run of chunk c_first touches
+        while (cc < nchunks && lo_c < s_row + 256) {
+            const int hi_c = __builtin_amdgcn_readfirstlane(clo[cc + 1]);
+            float sq = 0.f, sr = 0.f, sa = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool in = s + e >= lo_c && s + e < hi_c;
+                sq += in ? vq[e] : 0.f;
+                sr += in ? vr[e] : 0.f;
+                sa += in ? va[e] : 0.f;
+            }
+            if (hi_c > lo_c) {                         // an empty chunk has nothing to add (the same for the whole wavefront)
+                // sums over each quarter of the wavefront only (register-speed lane exchange); the four quarters, and the
+                // rows of slots that a chunk spans, are added at the end in a fixed order
+                sq = row16_sum(sq);
+                sr = row16_sum(sr);
+                sa = row16_sum(sa);
+                const int j = cc == c_first[k] ? r256 - row_first : 0;   // a chunk behind the first one of this row starts in it
+                if ((lane & 15) == 0) {
+                    float *dst = lds + L.kp + ((cc * kRowSpan + j) * 4 + (lane >> 4));
+                    dst[0] = sq;
+                    dst[nchunks * kRowSpan * 4] = sr;
+                    dst[2 * nchunks * kRowSpan * 4] = sa;
+                }
+            }
+            ++cc;
+            lo_c = hi_c;
+        }
+    }
+    __syncthreads();
+    for (int cc = threadIdx.x; cc < nchunks; cc += kRowThreads) {
+        float sq = 0.f, sr = 0.f, sa = 0.f;
+        for (int j = 0; j < kRowSpan; ++j) {
+            const float *src = lds + L.kp + (cc * kRowSpan + j) * 4;
+            const float4 xq = *(const float4 *)src, xr = *(const float4 *)(src + nchunks * kRowSpan * 4),
+                         xa = *(const float4 *)(src + 2 * nchunks * kRowSpan * 4);
+            sq += (xq.x + xq.y) + (xq.z + xq.w);
+            sr += (xr.x + xr.y) + (xr.z + xr.w);
+            sa += (xa.x + xa.y) + (xa.z + xa.w);
+        }
+        const float ta = ths * lds[L.blk_a + cc];      // sum of q' (= sum of min(p, q')) over the not-kept ids
+        const int64_t o = row * nchunks + cc;
+        part_q[o] = ta + sq;
+        part_a[o] = ta + sa;
+        part_r[o] = (lds[L.blk_p + cc] - ta) + sr;
+    }
+}
+
+constexpr int kRowSeriesMinN = 4096;   // from here on 1 / (N + p) is taken from its series in p / N (exact to fp32 rounding)
+constexpr int kRowMinBatch = 64;   // below this the two-pass kernels, which split a row over workgroups, fill the chip better
+
+// LDS a workgroup may use on the current device (asked once).
+size_t row_lds_limit()
+{
+    static size_t limit = 0;
+    if (!limit) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0)
+            limit = (size_t)v;
+        else
+            limit = 64 * 1024;
+    }
+    return limit;
+}
+
 template <int PK, int QK>
 struct QpTaylor {
     static constexpr bool kSpreadRows = false;
@@ -510,6 +812,56 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
 {
     LinearWs w = carve(h, B, ws);
     rdk_status_t rc;
+    if constexpr (PK == RDK_PROB_F32) {
+        // the fused call without q': one pass over the target rows, one workgroup per position, when the kept target
+        // values of a row fit the LDS of a compute unit and there are enough positions to fill the chip
+        const int nchunks = (h.N + kChunk - 1) / kChunk;
+        const size_t lds_bytes = (size_t)row_lds_layout(h.n, nchunks).total * sizeof(float);
+        if (c && !out && h.N >= 2 && B >= kRowMinBatch && h.n <= 4 * kRowThreads * kRowQuads && lds_bytes <= row_lds_limit()) {
+            if (QK != RDK_PROB_F32) {
+                rc = launch_row_stats<QK>(q, h.n, B, 1, w.qstat, st);
+                if (rc != RDK_OK) return rc;
+            }
+            const size_t per = align_up((size_t)B * nchunks * sizeof(float), 256);
+            char *pp = (char *)ws + taylor_workspace_bytes(h, B);
+            float *part_q = (float *)pp, *part_r = (float *)(pp + per), *part_a = (float *)(pp + 2 * per);
+            const bool vec_p = rows_vectorisable(p.ptr, p.ld, p.kind), vec_q = rows_vectorisable(q.ptr, q.ld, q.kind);
+            static bool attr_set = false;     // per instantiation: dynamic LDS above the default limit has to be granted once
+            if (!attr_set) {
+                RDK_HIP(hipFuncSetAttribute((const void *)taylor_row_kernel<QK, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)row_lds_limit()));
+                RDK_HIP(hipFuncSetAttribute((const void *)taylor_row_kernel<QK, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)row_lds_limit()));
+                attr_set = true;
+            }
+            if (h.N >= kRowSeriesMinN) {
+                RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, true>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
+                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.lane_map, h.chunk_lo, h.N, h.n, vec_p,
+                                 vec_q, w.qstat, w.tpart, part_q, part_r, part_a);
+            } else {
+                RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, false>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
+                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.lane_map, h.chunk_lo, h.N, h.n, vec_p,
+                                 vec_q, w.qstat, w.tpart, part_q, part_r, part_a);
+            }
+            RDK_LAUNCH_CHECK("taylor_row_kernel");
+            TaylorArgs a;
+            a.p = p.ptr; a.q = q.ptr; a.ldp = p.ld; a.ldq = q.ld;
+            a.slot_of = h.slot_of; a.kept = h.kept_ids; a.chunk_lo = h.chunk_lo; a.N = h.N; a.n = h.n;
+            a.splits = 1;                     // one record of totals per row
+            a.vec_p = vec_p; a.vec_q = vec_q;
+            a.onepass = false;
+            a.w = w;
+            FinalizeArgs fa{};
+            fa.d = c->d;
+            fa.p = p.ptr; fa.ldp = p.ld; fa.vec_p = vec_p;
+            fa.pstat = w.pstat; fa.p_splits = w.p_splits;
+            fa.part_q = part_q; fa.part_r = part_r; fa.part_a = part_a;
+            fa.nblk = nchunks;
+            fa.draft_ids = c->draft_ids; fa.accept = c->accept; fa.alpha = c->alpha; fa.resid_mass = c->resid_mass;
+            fa.resid_ids = c->resid_ids; fa.n_accepted = c->n_accepted; fa.out_tokens = c->out_tokens;
+            return launch_finalize<PK, 1024, true, QpTaylor<PK, QK>>(fa, QpTaylor<PK, QK>{a}, st);
+        }
+    }
     // logit target rows of a large vocabulary: the first pass of Eq. 3 also delivers the softmax statistics
     const bool onepass = PK != RDK_PROB_F32 && h.N >= kOnePassMinN;
     if (PK != RDK_PROB_F32 && !onepass) {

@@ -291,16 +291,6 @@ struct FuseArgs {
     float *part_q, *part_r, *part_a;   // [B, tiles * 4]: one entry per 64-id block
 };
 
-// sum over each row of 16 lanes, the same bits in all 16
-__device__ __forceinline__ float row16_sum(float v)
-{
-    v += dpp_move<0xB1>(v);
-    v += dpp_move<0x4E>(v);
-    v += dpp_move<0x141>(v);
-    v += dpp_move<0x140>(v);
-    return v;
-}
-
 // PK = -1: plain product (q' is written).  PK = -2: also the sum of q' per 64-id block (draft draw without a
 // target row; q' written only if WRITE_Q).  PK >= 0: fused with the verification sums against the target
 // rows of kind PK -- per (position, 64-id block) the sums of q', max(0, p - q') and min(p, q') --

@@ -625,14 +625,16 @@ def test_fused_redistribute_verify(rdk, tiny, ragged, case, mode, kinds):
     torch.cuda.synchronize()
     two_call = rdk.rdk_redistribute_linear(kern, gmode, q_in, q_kind, p=p_in, p_kind=p_kind)
     assert torch.equal(qp_out, two_call)                    # the same kernel code produces q' in both entry points
-    for name in ("draft_ids", "accept", "alpha", "resid_mass", "resid_ids", "n_accepted", "out_tokens"):
-        assert torch.equal(getattr(o1, name), getattr(o2, name)), name
+    if mode == "sparse":      # the same block sums with and without the stores: identical outputs
+        for name in ("draft_ids", "accept", "alpha", "resid_mass", "resid_ids", "n_accepted", "out_tokens"):
+            assert torch.equal(getattr(o1, name), getattr(o2, name)), name
     # against the oracle chain
     p64 = data["p"].astype(np.float64) if p_kind == "prob" else oracle.probs_from(data["z_p"], "logit")
     ref_qp = oracle_rows(data, mode, q_kind, p_kind, kernel=(idx, wt32, sw32) if mode == "sparse" else None)
     assert_close(qp_out.cpu().numpy(), ref_qp, what="fused q'")
     ref = oracle.verify_batch(p64, ref_qp, seed, offset, gamma=w.gamma)
     check_verify_outputs(o2, ref, p64, ref_qp, seed, offset, w.gamma, p_kind)
+    check_verify_outputs(o1, ref, p64, ref_qp, seed, offset, w.gamma, p_kind)   # Eq. 3 without q' sums its blocks another way
     # caller-supplied drafts through the fused path
     drafts = (np.arange(w.B, dtype=np.int32) * 11) % w.N
     o3 = rdk.rdk_redistribute_verify(kern, gmode, p_in, q_in, seed, offset, w.gamma, p_kind, q_kind, draft_ids=dev(drafts))
