@@ -52,7 +52,7 @@ typedef enum {
 /* How the token-affinity kernel M (n x N, row = kept slot, column = target id) is stored. */
 typedef enum {
     RDK_DENSE_F32 = 0,   /* every entry, fp32 */
-    RDK_DENSE_BF16 = 1,  /* every entry, bf16, packed for the matrix cores */
+    RDK_DENSE_BF16 = 1,  /* every entry, rounded to bf16, 16 bits per entry, packed for the matrix cores */
     RDK_SPARSE_TOPK = 2, /* per pruned id its k strongest kept neighbours; per kept id itself only */
     RDK_IDENTITY = 3     /* M = identity on the kept ids: RDK reduces to token-level intersection */
 } rdk_kernel_format_t;
@@ -148,8 +148,10 @@ rdk_status_t rdk_workspace_bytes(const rdk_kernel_t *kernel, int32_t B, size_t *
  *            draft_ids = -1, accept = 0, and draws resid_ids from the target row alone.
  *            LOGIT: the softmax over the n slots, which equals Eq. 1 applied to a full softmax.
  *   q_prime  [B, ldo]  fp32, the redistributed drafter over all N target ids.
- * Kernel format must be DENSE_F32, DENSE_BF16 or IDENTITY.  With DENSE_BF16 both operands are
- * rounded to bf16, products accumulate in fp32 and each output row is rescaled to sum to one.
+ * Kernel format must be DENSE_F32, DENSE_BF16 or IDENTITY.  With DENSE_BF16 the kernel entries are rounded to
+ * bf16 and the normalised drafter rows to eleven significant bits (both are fed to the matrix cores as fp16 numbers
+ * scaled by 2^15; values below 2^-29 count as zero), products accumulate in fp32 and each output row is rescaled
+ * to sum to one: every output is within 2e-3 (relative, plus 1e-7) of the exact product with the kernel as stored.
  */
 rdk_status_t rdk_redistribute_exact(const rdk_kernel_t *kernel, const void *q,
                                     rdk_input_kind_t q_kind, int64_t ldq, int32_t B,

@@ -2,8 +2,8 @@
 //   fp32 kernel:  both operands split into three bf16 parts each, six part products per term on the bf16 matrix
 //                 cores (v_mfma_f32_32x32x16_bf16) with fp32 accumulation; M read straight from its row-major
 //                 rows, split over the kept slots, fixed-order reduction.
-//   bf16 kernel:  both operands rounded to bf16, fp32 accumulation on the matrix cores
-//                 (v_mfma_f32_32x32x16_bf16), rows rescaled so that they sum to one.
+//   bf16 kernel:  M rounded to bf16, the drafter rows to eleven significant bits; both held as scaled fp16 numbers,
+//                 fp32 accumulation on the matrix cores (v_mfma_f32_32x32x16_f16), rows rescaled so that they sum to one.
 // Step 1 (Eq. 1) is folded in: rows of Q' are the drafter rows divided by their sums.
 #include "rdk_rowstats.hpp"
 
@@ -214,6 +214,31 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x)
     return (uint16_t)(u >> 16);
 }
 
+// The 16-bit operands of the dense product.  A bf16 number keeps eight significant bits: rounding a peaked drafter row
+// to it moves single outputs by up to 2^-8, twice the tolerance this path states (2e-3).  The matrix cores run fp16
+// at the same rate, and fp16 keeps eleven bits, so both operands are held as fp16 numbers scaled by 2^15:
+//   * an entry of M is first rounded to bf16 (the format the kernel is specified in) and that value, times 2^15, is
+//     an fp16 number exactly as long as it is at least 2^-29;
+//   * an entry of a normalised drafter row is rounded to eleven significant bits (relative error at most 2^-12).
+// Values whose scaled magnitude is below the smallest normal fp16 number (2^-14, i.e. below 2^-29 = 1.9e-9 unscaled)
+// are stored as zero, whatever the denormal mode of the hardware; the products carry the factor 2^30, taken out
+// again by the row scale.
+constexpr float kOperandScale = 32768.0f;                 // 2^15
+constexpr float kOperandUnscale = 1.0f / 32768.0f;
+constexpr float kHalfMinNormal = 6.103515625e-05f;        // 2^-14
+
+__device__ __forceinline__ uint16_t f32_to_operand(float x)   // x >= 0, at most 1
+{
+    const float y = x * kOperandScale;
+    if (!(y >= kHalfMinNormal)) return 0;
+    return __builtin_bit_cast(uint16_t, (_Float16)y);   // round to nearest even
+}
+
+__device__ __forceinline__ float operand_to_f32(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h) * kOperandUnscale; }
+
+// an entry of M as stored: rounded to bf16, then held as a scaled fp16 number
+__device__ __forceinline__ uint16_t kernel_entry(float m) { return f32_to_operand(bf16_to_f32(f32_to_bf16_rne(m))); }
+
 // Packed layout of the bf16 kernel: for column block jb (32 ids) and slot block kb (16 slots) one
 // contiguous 1 KB record holding, for lane l = 32 * g + c (g = 0..1, c = 0..31), the eight values
 // M[kb*16 + g*8 + e, jb*32 + c], e = 0..7 -- exactly the B operand of one 32x32x16 MFMA, so that a
@@ -230,19 +255,19 @@ __global__ void pack_bf16_kernel(const float *M, int64_t ldm, int n, int N, int 
             const int s = kb * kKStep + g * 8 + e;
             const float v0 = (s < n && j < N) ? M[(int64_t)s * ldm + j] : 0.f;
             const float v1 = (s + 1 < n && j < N) ? M[(int64_t)(s + 1) * ldm + j] : 0.f;
-            w[e / 2] = (uint32_t)f32_to_bf16_rne(v0) | ((uint32_t)f32_to_bf16_rne(v1) << 16);
+            w[e / 2] = (uint32_t)kernel_entry(v0) | ((uint32_t)kernel_entry(v1) << 16);
         }
         *(uint4 *)(packed + (((int64_t)jb * KB + kb) * 64 + lane) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
-// fp32 sums of the bf16-rounded rows of M (needed to rescale output rows to unit mass).
+// fp32 sums of the rows of M as stored (needed to rescale output rows to unit mass).
 __global__ void rounded_row_sum_kernel(const float *M, int64_t ldm, int N, float *row_sum)
 {
     const int s = blockIdx.x;
     double sum = 0.0;
     for (int j = threadIdx.x; j < N; j += blockDim.x)
-        sum += (double)bf16_to_f32(f32_to_bf16_rne(M[(int64_t)s * ldm + j]));
+        sum += (double)operand_to_f32(kernel_entry(M[(int64_t)s * ldm + j]));
     sum = wave_sum(sum);
     __shared__ double sh[4];
     if (lane_id() == 0) sh[threadIdx.x / kWave] = sum;
@@ -260,15 +285,16 @@ __global__ void unpack_bf16_kernel(const uint16_t *packed, int n, int N, int KB,
         const uint16_t *rec = packed + (((int64_t)jb * KB + kb) * 64 + lane) * 8;
         for (int e = 0; e < 8; ++e) {
             const int s = kb * kKStep + g * 8 + e;
-            if (s < n) M[(int64_t)s * ldm + j] = bf16_to_f32(rec[e]);
+            if (s < n) M[(int64_t)s * ldm + j] = operand_to_f32(rec[e]);
         }
     }
 }
 
-// A operand: TLI-normalised drafter rows rounded to bf16, packed like M: for row block rb (32 positions) and
+// A operand: TLI-normalised drafter rows as 16-bit operands (see f32_to_operand), packed like M: for row block rb (32 positions) and
 // slot block kb (16 slots) one 1 KB record holding, for lane l = 32 * g + r, the eight values
 // q'[rb*32 + r, kb*16 + g*8 + e], e = 0..7 -- the A operand of one 32x32x16 MFMA.  Also per row the factor
-// 1 / sum_s bf16(q'_s) * row_sum[s], which makes the output row sum to one.  One workgroup per position.
+// 2^-30 / sum_s rounded(q'_s) * row_sum[s]: it takes the operand scales out and makes the output row sum to one.
+// One workgroup per position.
 template <int QK>
 __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t ldq, const SoftStat *qstat, const float *row_sum,
                                                           int n, int KB, int B, uint16_t *Ap, float *out_scale)
@@ -287,8 +313,8 @@ __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t
                 const int s = c * 8 + e;
                 uint16_t h = 0;
                 if (s < n) {
-                    h = f32_to_bf16_rne(to_weight<QK>(load1<QK>(qr, s), qm, 1.f) * inv);
-                    mass += (double)bf16_to_f32(h) * (double)row_sum[s];
+                    h = f32_to_operand(to_weight<QK>(load1<QK>(qr, s), qm, 1.f) * inv);
+                    mass += (double)operand_to_f32(h) * (double)row_sum[s];
                 }
                 w[e / 2] |= (uint32_t)h << (16 * (e % 2));
             }
@@ -301,7 +327,7 @@ __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t
     __syncthreads();
     if (threadIdx.x == 0 && b < B) {
         const double total = (sh[0] + sh[1]) + (sh[2] + sh[3]);
-        out_scale[b] = total > 0.0 ? (float)(1.0 / total) : 0.f;
+        out_scale[b] = total > 0.0 ? (float)((double)kOperandUnscale * (double)kOperandUnscale / total) : 0.f;
     }
 }
 
@@ -317,9 +343,10 @@ __global__ __launch_bounds__(256) void prep_a_bf16_kernel(const void *q, int64_t
 // A record of M: read exactly once per launch, so it is loaded non-temporally and leaves the L2 to the A records,
 // which every workgroup of an XCD reads again.
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ bf16x8 load_once(const bf16x8 *p)
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ f16x8 load_once(const f16x8 *p)
 {
-    return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((const u32x4_t *)p));
+    return __builtin_bit_cast(f16x8, __builtin_nontemporal_load((const u32x4_t *)p));
 }
 
 template <int W, int RB>
@@ -327,7 +354,7 @@ __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, 
                                                             const float *out_scale, float *out, int64_t ldo)
 {
     constexpr int RPW = 16 / W;   // B records a wavefront fetches per stage
-    __shared__ bf16x8 bbuf[2][16][64];
+    __shared__ f16x8 bbuf[2][16][64];
     const int wid = threadIdx.x / kWave, lane = lane_id();
     const int jb0 = blockIdx.x * kColBlocksPerWg;
     const int rb0 = (blockIdx.y * W + wid) * RB;
@@ -341,16 +368,16 @@ __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[r][c][v] = 0.f;
 
-    const bf16x8 *a_ptr[RB];
+    const f16x8 *a_ptr[RB];
 #pragma unroll
-    for (int r = 0; r < RB; ++r) a_ptr[r] = (const bf16x8 *)Ap + ((int64_t)(rb0 + r) * KB) * 64 + lane;
-    const bf16x8 *b_src[RPW];
+    for (int r = 0; r < RB; ++r) a_ptr[r] = (const f16x8 *)Ap + ((int64_t)(rb0 + r) * KB) * 64 + lane;
+    const f16x8 *b_src[RPW];
     int b_rec[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
         b_rec[i] = wid * RPW + i;                               // record = jb * 4 + kb within the stage
         const int jb = min(jb0 + b_rec[i] / 4, n_jb - 1);       // surplus column blocks recompute the last one
-        b_src[i] = (const bf16x8 *)Mp + ((int64_t)jb * KB + b_rec[i] % 4) * 64 + lane;
+        b_src[i] = (const f16x8 *)Mp + ((int64_t)jb * KB + b_rec[i] % 4) * 64 + lane;
     }
     // Loads return to a wavefront in issue order, so every load inherits the latency of the slowest one before
     // it.  The B records come from HBM: they are requested three stages ahead and kept in a ring of registers.
@@ -359,7 +386,7 @@ __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, 
     // The first requests are issued in the order the stages keep afterwards (A by slot block, at least as many
     // requests behind every record as in the steady state): the wait counts the compiler derives for the first stages
     // of the loop are the minimum over both ways into them, and a different order here would tighten them for good.
-    bf16x8 a_even[RB][4], a_odd[RB][4], b_ring[3][RPW];
+    f16x8 a_even[RB][4], a_odd[RB][4], b_ring[3][RPW];
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
@@ -389,14 +416,14 @@ __global__ __launch_bounds__(W * 64) void exact_bf16_kernel(const uint16_t *Ap, 
         const int64_t sa = min(s + 2, stages - 1), sb = min(s + 3, stages - 1);                                      \
         _Pragma("unroll") for (int i = 0; i < RPW; ++i) b_ring[SLOT][i] = load_once(b_src[i] + sb * 4 * 64);         \
         __builtin_amdgcn_sched_barrier(0);                                                                           \
-        bf16x8 bq[3];                        /* B fragments are read from LDS two MFMA groups ahead */               \
+        f16x8 bq[3];                        /* B fragments are read from LDS two MFMA groups ahead */               \
         bq[0] = bbuf[cur][0][lane];                                                                                  \
         bq[1] = bbuf[cur][4][lane];                                                                                  \
         _Pragma("unroll") for (int f = 0; f < 16; ++f) {     /* f = kb * 4 + c */                                    \
             const int kb = f / 4, c = f % 4;                                                                         \
             if (f + 2 < 16) bq[(f + 2) % 3] = bbuf[cur][((f + 2) % 4) * 4 + (f + 2) / 4][lane];                      \
             _Pragma("unroll") for (int r = 0; r < RB; ++r)                                                           \
-                acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ACUR[r][kb], bq[f % 3], acc[r][c], 0, 0, 0);     \
+                acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ACUR[r][kb], bq[f % 3], acc[r][c], 0, 0, 0);     \
             if (c == 3) {                                                                                            \
                 __builtin_amdgcn_sched_barrier(0);                                                                   \
                 _Pragma("unroll") for (int r = 0; r < RB; ++r) ACUR[r][kb] = a_ptr[r][(sa * 4 + kb) * 64];           \

@@ -214,6 +214,16 @@ __device__ __forceinline__ int search_block(const float4 (&wv)[SUB], int base, d
     return last_positive;
 }
 
+// The same for a block of 64 ids held one per lane (w = weight of id base + lane).
+__device__ __forceinline__ int search_block1(float w, int base, double thr_local)
+{
+    const double incl = wave_inclusive_scan((double)w);
+    const unsigned long long hits = __ballot(incl > thr_local);
+    if (hits != 0ull) return base + (__ffsll(hits) - 1);
+    const unsigned long long pos = __ballot(w > 0.f);
+    return pos != 0ull ? base + (63 - __clzll(pos)) : -1;
+}
+
 constexpr int kFinalizeRows = 8;   // rows (wavefronts) per workgroup at most: leaves 256 VGPRs per lane
 constexpr int kSpreadMinRows = 128;   // from this many rows on every row gets a workgroup of its own
 
@@ -288,9 +298,7 @@ __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) vo
 
         // 3. both blocks are fetched together (q' and the target weights of each), then scanned.  A draft token
         //    that the caller supplied may lie anywhere: its two values are requested in the same round trip.
-        float4 wd[SUB], pd[SUB], wp[SUB], wq[SUB];
         const int base_d = max(blk_d, 0) * BLOCK, base_r = max(blk_r, 0) * BLOCK;
-        const bool holds = lane < kLanes;
         const bool same = draw_draft && blk_r == blk_d;
         float pd_w = 0.f, qd = 0.f;
         const bool given = HAS_Q && !d.sample_draft && dtok >= 0 && dtok < N;
@@ -298,60 +306,96 @@ __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) vo
             pd_w = to_weight<KIND>(load1<KIND>(pr, dtok), m, inv);
             qd = qrow.load1(dtok);
         }
-        typename QP::Row::Pending td[SUB], tr[SUB];
         const bool want_r = HAS_Q && !same;
-        const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f), fill4 = make_float4(pfill, pfill, pfill, pfill);
-        stage_block<0, SUB>(qrow, td, base_d, draw_draft && holds);
-        stage_block<0, SUB>(qrow, tr, base_r, want_r && holds);
-#pragma unroll
-        for (int i = 0; i < SUB; ++i) {
-            if (draw_draft) pd[i] = holds ? load4<KIND>(pr, base_d + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
-            if (!same) wp[i] = holds ? load4<KIND>(pr, base_r + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
-        }
-        if (QP::kStages > 1) {
-            stage_block<1, SUB>(qrow, td, base_d, draw_draft && holds);
-            stage_block<1, SUB>(qrow, tr, base_r, want_r && holds);
-        }
-        if (QP::kStages > 2) {
-            stage_block<2, SUB>(qrow, td, base_d, draw_draft && holds);
-            stage_block<2, SUB>(qrow, tr, base_r, want_r && holds);
-        }
-#pragma unroll
-        for (int i = 0; i < SUB; ++i) {
-            if (draw_draft) wd[i] = holds ? qrow.result(td[i], (int64_t)base_d + i * 256 + lane * 4) : zero4;
-            if (want_r) wq[i] = holds ? qrow.result(tr[i], (int64_t)base_r + i * 256 + lane * 4) : zero4;
+        int32_t rtok = -1;
+        if constexpr (BLOCK == 64) {
+            // blocks of 64 ids, one id per lane: the policy's chain of dependent loads is as short as it gets (one
+            // slot, one table row, its gathers) and all 64 lanes share it
+            typename QP::Row::Pending1 td, tr;
+            const int id_d = base_d + lane, id_r = base_r + lane;
+            if (draw_draft) qrow.template stage1<0>(td, id_d);
+            if (want_r) qrow.template stage1<0>(tr, id_r);
+            float pdv = pfill, wpv = pfill;
+            if (draw_draft && id_d < N) pdv = load1<KIND>(pr, id_d);
+            if (!same && id_r < N) wpv = load1<KIND>(pr, id_r);
+            if (draw_draft) qrow.template stage1<1>(td, id_d);
+            if (want_r) qrow.template stage1<1>(tr, id_r);
+            if (draw_draft) qrow.template stage1<2>(td, id_d);
+            if (want_r) qrow.template stage1<2>(tr, id_r);
+            const float wdv = draw_draft ? qrow.result1(td, id_d) : 0.f;
+            float wqv = want_r ? qrow.result1(tr, id_r) : 0.f;
             if (same) {
-                wp[i] = pd[i];
-                wq[i] = wd[i];
+                wpv = pdv;
+                wqv = wdv;
             }
-        }
-        if (blk_d >= 0) {
-            dtok = search_block<SUB>(wd, base_d, thr_d - before_d);
-            // 4. the accept test needs p and q' at the draft token: both sit in the registers of one lane
-            if (dtok >= 0) {
-                const int off = dtok - base_d, i = off / 256, src = (off % 256) / 4, e = off % 4;
-                qd = lane_value(pick<SUB>(wd, i, e), src);
-                pd_w = to_weight<KIND>(lane_value(pick<SUB>(pd, i, e), src), m, inv);
+            if (blk_d >= 0) {
+                dtok = search_block1(wdv, base_d, thr_d - before_d);
+                if (dtok >= 0) {
+                    qd = lane_value(wdv, dtok - base_d);
+                    pd_w = to_weight<KIND>(lane_value(pdv, dtok - base_d), m, inv);
+                }
+            }
+            if (blk_r >= 0) {
+                wpv = to_weight<KIND>(wpv, m, inv);
+                if (HAS_Q) wpv = fmaxf(wpv - wqv, 0.f);
+                rtok = search_block1(wpv, base_r, thr_r - before_r);
+            }
+        } else {
+            float4 wd[SUB], pd[SUB], wp[SUB], wq[SUB];
+            const bool holds = lane < kLanes;
+            typename QP::Row::Pending td[SUB], tr[SUB];
+            const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f), fill4 = make_float4(pfill, pfill, pfill, pfill);
+            stage_block<0, SUB>(qrow, td, base_d, draw_draft && holds);
+            stage_block<0, SUB>(qrow, tr, base_r, want_r && holds);
+#pragma unroll
+            for (int i = 0; i < SUB; ++i) {
+                if (draw_draft) pd[i] = holds ? load4<KIND>(pr, base_d + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
+                if (!same) wp[i] = holds ? load4<KIND>(pr, base_r + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
+            }
+            if (QP::kStages > 1) {
+                stage_block<1, SUB>(qrow, td, base_d, draw_draft && holds);
+                stage_block<1, SUB>(qrow, tr, base_r, want_r && holds);
+            }
+            if (QP::kStages > 2) {
+                stage_block<2, SUB>(qrow, td, base_d, draw_draft && holds);
+                stage_block<2, SUB>(qrow, tr, base_r, want_r && holds);
+            }
+#pragma unroll
+            for (int i = 0; i < SUB; ++i) {
+                if (draw_draft) wd[i] = holds ? qrow.result(td[i], (int64_t)base_d + i * 256 + lane * 4) : zero4;
+                if (want_r) wq[i] = holds ? qrow.result(tr[i], (int64_t)base_r + i * 256 + lane * 4) : zero4;
+                if (same) {
+                    wp[i] = pd[i];
+                    wq[i] = wd[i];
+                }
+            }
+            if (blk_d >= 0) {
+                dtok = search_block<SUB>(wd, base_d, thr_d - before_d);
+                // 4. the accept test needs p and q' at the draft token: both sit in the registers of one lane
+                if (dtok >= 0) {
+                    const int off = dtok - base_d, i = off / 256, src = (off % 256) / 4, e = off % 4;
+                    qd = lane_value(pick<SUB>(wd, i, e), src);
+                    pd_w = to_weight<KIND>(lane_value(pick<SUB>(pd, i, e), src), m, inv);
+                }
+            }
+            if (blk_r >= 0) {
+#pragma unroll
+                for (int i = 0; i < SUB; ++i) {
+                    wp[i].x = to_weight<KIND>(wp[i].x, m, inv);
+                    wp[i].y = to_weight<KIND>(wp[i].y, m, inv);
+                    wp[i].z = to_weight<KIND>(wp[i].z, m, inv);
+                    wp[i].w = to_weight<KIND>(wp[i].w, m, inv);
+                    if (HAS_Q) {
+                        wp[i].x = fmaxf(wp[i].x - wq[i].x, 0.f);
+                        wp[i].y = fmaxf(wp[i].y - wq[i].y, 0.f);
+                        wp[i].z = fmaxf(wp[i].z - wq[i].z, 0.f);
+                        wp[i].w = fmaxf(wp[i].w - wq[i].w, 0.f);
+                    }
+                }
+                rtok = search_block<SUB>(wp, base_r, thr_r - before_r);
             }
         }
         const bool d_ok = HAS_Q && dtok >= 0 && dtok < N;
-        int32_t rtok = -1;
-        if (blk_r >= 0) {
-#pragma unroll
-            for (int i = 0; i < SUB; ++i) {
-                wp[i].x = to_weight<KIND>(wp[i].x, m, inv);
-                wp[i].y = to_weight<KIND>(wp[i].y, m, inv);
-                wp[i].z = to_weight<KIND>(wp[i].z, m, inv);
-                wp[i].w = to_weight<KIND>(wp[i].w, m, inv);
-                if (HAS_Q) {
-                    wp[i].x = fmaxf(wp[i].x - wq[i].x, 0.f);
-                    wp[i].y = fmaxf(wp[i].y - wq[i].y, 0.f);
-                    wp[i].z = fmaxf(wp[i].z - wq[i].z, 0.f);
-                    wp[i].w = fmaxf(wp[i].w - wq[i].w, 0.f);
-                }
-            }
-            rtok = search_block<SUB>(wp, base_r, thr_r - before_r);
-        }
         uint8_t acc = 0;
         if (d_ok) acc = (word_to_unit(words[1]) * (double)qd < (double)pd_w) ? 1 : 0;
         if (lane == 0) {
@@ -423,19 +467,30 @@ __global__ __launch_bounds__(kWave) void draft_finalize_kernel(DraftArgs a, QP q
     float qd = 0.f;
     if (blk >= 0) {
         const int base = blk * BLOCK;
-        const bool holds = lane < kLanes;
-        typename QP::Row::Pending td[SUB];
-        float4 wd[SUB];
-        stage_block<0, SUB>(qrow, td, base, holds);
-        if (QP::kStages > 1) stage_block<1, SUB>(qrow, td, base, holds);
-        if (QP::kStages > 2) stage_block<2, SUB>(qrow, td, base, holds);
+        if constexpr (BLOCK == 64) {
+            typename QP::Row::Pending1 td;
+            const int id = base + lane;
+            qrow.template stage1<0>(td, id);
+            qrow.template stage1<1>(td, id);
+            qrow.template stage1<2>(td, id);
+            const float wdv = qrow.result1(td, id);
+            dtok = search_block1(wdv, base, thr - before);
+            if (dtok >= 0) qd = lane_value(wdv, dtok - base);
+        } else {
+            const bool holds = lane < kLanes;
+            typename QP::Row::Pending td[SUB];
+            float4 wd[SUB];
+            stage_block<0, SUB>(qrow, td, base, holds);
+            if (QP::kStages > 1) stage_block<1, SUB>(qrow, td, base, holds);
+            if (QP::kStages > 2) stage_block<2, SUB>(qrow, td, base, holds);
 #pragma unroll
-        for (int i = 0; i < SUB; ++i)
-            wd[i] = holds ? qrow.result(td[i], (int64_t)base + i * 256 + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-        dtok = search_block<SUB>(wd, base, thr - before);
-        if (dtok >= 0) {
-            const int off = dtok - base;
-            qd = lane_value(pick<SUB>(wd, off / 256, off % 4), (off % 256) / 4);
+            for (int i = 0; i < SUB; ++i)
+                wd[i] = holds ? qrow.result(td[i], (int64_t)base + i * 256 + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            dtok = search_block<SUB>(wd, base, thr - before);
+            if (dtok >= 0) {
+                const int off = dtok - base;
+                qd = lane_value(pick<SUB>(wd, off / 256, off % 4), (off % 256) / 4);
+            }
         }
     }
     if (lane == 0) {

@@ -494,6 +494,62 @@ struct QpSparse {
             for (int e = 0; e < 4; ++e) out[e] = idx + e < N ? acc[e] * inv_z : 0.f;
             return make_float4(out[0], out[1], out[2], out[3]);
         }
+        // One id per lane (blocks of 64 ids): the slot, then the first sixteen table entries, then their gathers; a kept
+        // id is a row whose entries all point at its own slot, the first with the diagonal weight.
+        struct Pending1 {
+            int se;
+            int ii[16];
+            float ww[16], gg[16];
+        };
+        template <int K>
+        __device__ __forceinline__ void stage1(Pending1 &t, int64_t idx) const
+        {
+            if (K == 0) {
+                t.se = idx < N ? slot_of[idx] : 0;   // beyond N: computed, discarded
+            } else if (K == 1) {
+                const int s = t.se;
+                const bool kept = s >= 0;
+                const int64_t u = kept ? 0 : -s - 1;
+#pragma unroll
+                for (int x = 0; x < 16; x += 2) {
+                    const int4 ev = *(const int4 *)(nbr + u * kk + x);
+                    t.ii[x] = ev.x; t.ww[x] = __int_as_float(ev.y);
+                    t.ii[x + 1] = ev.z; t.ww[x + 1] = __int_as_float(ev.w);
+                }
+                const float sw = self_w[max(s, 0)];
+                if (kept) {
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) {
+                        t.ii[x] = s;
+                        t.ww[x] = x == 0 ? sw : 0.f;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int x = 0; x < 16; ++x) t.gg[x] = qcol[(int64_t)t.ii[x] * kPosBlock];
+            }
+        }
+        __device__ __forceinline__ float result1(Pending1 &t, int64_t idx) const
+        {
+            float acc = 0.f;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) acc += t.ww[x] * t.gg[x];   // same order of additions as the product kernel
+            const bool kept = t.se >= 0;
+            const int64_t u = kept ? 0 : -t.se - 1;
+            for (int x0 = 16; x0 < kk; x0 += 16) {
+#pragma unroll
+                for (int x = 0; x < 16; x += 2) {
+                    const int4 ev = *(const int4 *)(nbr + u * kk + x0 + x);
+                    t.ii[x] = kept ? t.se : ev.x; t.ww[x] = kept ? 0.f : __int_as_float(ev.y);
+                    t.ii[x + 1] = kept ? t.se : ev.z; t.ww[x + 1] = kept ? 0.f : __int_as_float(ev.w);
+                }
+#pragma unroll
+                for (int x = 0; x < 16; ++x) t.gg[x] = qcol[(int64_t)t.ii[x] * kPosBlock];
+#pragma unroll
+                for (int x = 0; x < 16; ++x) acc += t.ww[x] * t.gg[x];
+            }
+            return idx < N ? acc * inv_z : 0.f;
+        }
         __device__ __forceinline__ float load1(int j) const { return value(j); }
     };
     __device__ __forceinline__ Row row(int64_t b) const

@@ -6,9 +6,41 @@ import oracle
 # fp32 paths: |g - o| <= RTOL |o| + ATOL elementwise; bf16 dense path: RTOL_BF16.
 RTOL, ATOL = 1e-5, 1e-7
 RTOL_BF16 = 2e-3
+RTOL_DENSE = RTOL_BF16
+# Against a kernel that was NOT yet rounded to its 16-bit storage format the outputs also carry the format's own
+# rounding: bf16 keeps eight significant bits, so an entry of M moves by up to 2^-8 of itself (an output dominated
+# by one entry moves as much), on top of the path's own error.
+RTOL_DENSE_UNROUNDED = 2.0 ** -8 + RTOL_BF16
 # A sampled id is compared exactly unless the threshold lies within CDF_TOL * total of a step of the
 # prefix sum: there fp32 summation order may pick the neighbour, which is accepted if it is valid.
 CDF_TOL = 1e-5
+
+
+def bf16_round(x):
+    """fp32 values rounded to the nearest bf16 (ties to even), returned as fp64."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32).astype(np.uint64)
+    rounded = ((bits + 0x7FFF + ((bits >> 16) & 1)) >> 16) << 16
+    return rounded.astype(np.uint32).view(np.float32).reshape(x.shape).astype(np.float64)
+
+
+def _scaled_half(x):
+    """x >= 0 held as an fp16 number scaled by 2^15 (round to nearest even; zero below the smallest normal fp16)."""
+    y = np.asarray(x, dtype=np.float64).astype(np.float32) * np.float32(32768.0)
+    h = y.astype(np.float16).astype(np.float64)
+    h[y < 2.0 ** -14] = 0.0
+    return h / 32768.0
+
+
+def operand_round_M(M):
+    """The dense 16-bit kernel as stored: entries rounded from fp32 to bf16, then held as scaled fp16 numbers (exact
+    for every entry of at least 2^-29, zero below)."""
+    return _scaled_half(bf16_round(np.asarray(M, dtype=np.float64).astype(np.float32)))
+
+
+def operand_round_q(q_tli):
+    """The normalised drafter row as the dense 16-bit product takes it: rounded from fp32 to eleven significant bits."""
+    return _scaled_half(q_tli)
 
 
 def assert_close(g, o, rtol=RTOL, atol=ATOL, what=""):

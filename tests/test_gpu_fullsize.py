@@ -10,7 +10,8 @@ import torch
 
 import oracle
 from paper_2506_03206_amd import synth
-from parity_util import ATOL, RTOL, assert_close, check_multi, check_verify_outputs, random_trees
+from parity_util import (ATOL, RTOL, RTOL_DENSE, RTOL_DENSE_UNROUNDED, assert_close, check_multi, check_verify_outputs, operand_round_M,
+                         operand_round_q, random_trees)
 
 pytestmark = pytest.mark.gpu
 
@@ -167,22 +168,65 @@ def test_dense256k_exact_bf16(rdk):
     out = rdk.rdk_redistribute_exact(kern, dev(q)).cpu().numpy()
     # oracle: the eight rows of M in fp64, rounded to bf16 as the stored kernel is
     M_rows = oracle.build_dense(E, kept[slots], w.tau)                    # [8, N]
-    Mb = synth.bf16_round(M_rows.astype(np.float32)).astype(np.float64)
+    Mb = operand_round_M(M_rows)
     # The device stores M in fp32 before rounding it to bf16, the oracle's rows are fp64: where the two fp32 values
     # differ by an ulp next to a bf16 tie (a few entries in 10^5) the stored entries differ by one bf16 ulp, which
     # moves that one output by up to w_s * 2^-8.  So: all but 1e-4 of the outputs within 2e-5 of the product of the
-    # rounded operands, every output within 2e-3 of it, and within 8e-3 of the product with the unrounded rows.
+    # rounded operands, every output within 2e-3 of it, and within the storage format's rounding of the product with
+    # the unrounded rows.
     for b in range(16):
         r = np.roll(weights, b) @ Mb
         r /= r.sum()
         err = np.abs(out[b] - r) / (2e-5 * np.abs(r) + ATOL)
         assert (err > 1).mean() < 1e-4, "row %d: %.3g of the outputs off the rounded-operand product" % (b, (err > 1).mean())
         assert_close(out[b], r, rtol=2e-3, atol=ATOL, what="sparse-support row %d, rounded operands" % b)
-        assert_close(out[b], np.roll(weights, b) @ M_rows, rtol=8e-3, atol=1e-6, what="sparse-support row %d, exact M" % b)
+        assert_close(out[b], np.roll(weights, b) @ M_rows, rtol=RTOL_DENSE_UNROUNDED, atol=ATOL, what="sparse-support row %d, exact M" % b)
     sums = out.astype(np.float64).sum(1)
     assert np.abs(sums - 1).max() < 1e-5 and out.min() >= 0 and np.isfinite(out).all()
-    # bf16 rounding of q' breaks exact linearity by at most 2^-9 per term
-    assert_close(out[18], 0.5 * out[16].astype(np.float64) + 0.5 * out[17], rtol=8e-3, atol=1e-7, what="linearity")
+    # rounding q' to eleven significant bits breaks exact linearity by at most 2^-11 per term and row
+    assert_close(out[18], 0.5 * out[16].astype(np.float64) + 0.5 * out[17], rtol=RTOL_DENSE, atol=ATOL, what="linearity")
+
+
+def test_dense256k_exact_bf16_wide_support(rdk):
+    """N=256000, n=32000, B=512 as measured, with sixteen drafter rows supported on 512 slots each: 384 slots scattered
+    over the whole slot range (every stage of the product's pipeline carries some) and two runs of 64 consecutive slots
+    (whole stages without a zero), weights log-normal and unnormalised, so that neither the rows nor their normalised
+    form are bf16 numbers.  Every output of those rows accumulates 512 products across all 500 stages of the slot loop;
+    the oracle builds the 512 rows of Eq. 2 it needs from the same embeddings (about a minute of fp64 on the host)."""
+    w = synth.WORKLOADS["dense256k"]
+    bias, kept, E, rng = synth.make_vocab(w)
+    batch = synth.make_batch(w, bias, kept, rng)
+    kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.DENSE_BF16, embeddings=dev(E), tau=w.tau)
+    srng = np.random.default_rng(23)
+    scattered = srng.choice(w.n, 384, replace=False)
+    runs = np.concatenate([np.arange(4096 + 13, 4096 + 13 + 64), np.arange(w.n - 64, w.n)])
+    slots = np.unique(np.concatenate([scattered, runs]))
+    rows = np.arange(20, 36)
+    q = batch["q_hat"].copy()
+    for b in rows:
+        q[b] = 0
+        q[b, slots] = np.exp(srng.normal(0.0, 2.0, size=slots.size)).astype(np.float32)
+    out = rdk.rdk_redistribute_exact(kern, dev(q)).cpu().numpy()
+    M_rows = oracle.build_dense(E, kept[slots], w.tau)                    # [512, N] fp64
+    Mb = operand_round_M(M_rows)
+    worst_stored = 0.0
+    for b in rows:
+        qt = oracle.tli(q[b])[slots]                                      # Eq. 1 in fp64
+        r = operand_round_q(qt) @ Mb
+        r /= r.sum()
+        # the entries of the stored kernel whose fp32 value sits next to a rounding tie may differ from the oracle's by
+        # one unit in the last place of the storage format: all but 1e-4 of the outputs within 2e-5, all within 2e-3
+        err = np.abs(out[b] - r) / (2e-5 * np.abs(r) + ATOL)
+        assert (err > 1).mean() < 1e-4, "row %d: %.3g of the outputs off the product of the rounded operands" % (b, (err > 1).mean())
+        assert_close(out[b], r, rtol=2e-3, atol=ATOL, what="wide-support row %d, rounded operands" % b)
+        # the stated tolerance of the dense path: against the kernel as stored and the drafter row as given
+        r2 = qt @ Mb
+        r2 /= r2.sum()
+        assert_close(out[b], r2, rtol=RTOL_DENSE, atol=ATOL, what="wide-support row %d, stored kernel" % b)
+        worst_stored = max(worst_stored, float(np.max(np.abs(out[b] - r2) / (np.abs(r2) + 1e-30) * (np.abs(out[b] - r2) > ATOL))))
+    print("dense256k wide-support rows: worst relative error against the stored kernel %.3g" % worst_stored)
+    sums = out.astype(np.float64).sum(1)
+    assert np.abs(sums - 1).max() < 1e-5 and out.min() >= 0 and np.isfinite(out).all()
 
 
 def test_llama3_verify_multi(rdk, llama3):

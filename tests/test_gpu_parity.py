@@ -8,8 +8,8 @@ import torch
 
 import oracle
 from paper_2506_03206_amd import synth
-from parity_util import (ATOL, RTOL, RTOL_BF16, assert_close, check_multi, check_sampled_ids, check_verify_outputs,
-                         random_trees)
+from parity_util import (ATOL, RTOL, RTOL_DENSE, RTOL_DENSE_UNROUNDED, assert_close, check_multi, check_sampled_ids,
+                         check_verify_outputs, operand_round_M, operand_round_q, random_trees)
 
 pytestmark = pytest.mark.gpu
 
@@ -243,18 +243,23 @@ def test_exact_bf16(rdk, tiny, ragged, case):
     w = data["w"]
     M32 = data["dense"].astype(np.float32)
     kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.DENSE_BF16, dense_M=dev(M32))
-    assert np.array_equal(rdk.rdk_kernel_get_dense(kern).cpu().numpy(), synth.bf16_round(M32))
+    Mb = operand_round_M(M32)                    # the kernel as stored: bf16 values (zero below 2^-29)
+    assert np.array_equal(rdk.rdk_kernel_get_dense(kern).cpu().numpy().astype(np.float64), Mb)
+    assert np.array_equal(Mb[Mb >= 2.0 ** -29], synth.bf16_round(M32).astype(np.float64)[Mb >= 2.0 ** -29])
     out = rdk.rdk_redistribute_exact(kern, dev(data["q_hat"])).cpu().numpy()
-    # tight: fp64 on the same bf16-rounded operands, rows rescaled to unit mass
-    Mb = synth.bf16_round(M32).astype(np.float64)
-    ref = np.empty((w.B, w.N))
+    # tight: fp64 on the same rounded operands, rows rescaled to unit mass
+    ref, ref_stored = np.empty((w.B, w.N)), np.empty((w.B, w.N))
     for b in range(w.B):
-        qb = synth.bf16_round(oracle.tli(data["q_hat"][b]).astype(np.float32))
-        r = oracle.redistribute_dense(qb, Mb)
+        qt = oracle.tli(data["q_hat"][b])
+        r = oracle.redistribute_dense(operand_round_q(qt), Mb)
         ref[b] = r / r.sum()
+        r = oracle.redistribute_dense(qt, Mb)
+        ref_stored[b] = r / r.sum()
     assert_close(out, ref, rtol=2e-5, atol=ATOL, what="exact bf16 vs rounded operands")
-    # loose: against the unrounded fp32 kernel
-    assert_close(out, oracle_rows(data, "exact", kernel=M32), rtol=RTOL_BF16 * 4, atol=1e-6, what="exact bf16 vs fp32 operands")
+    # the stated tolerance of the dense path: the drafter rows as given, the kernel as stored
+    assert_close(out, ref_stored, rtol=RTOL_DENSE, atol=ATOL, what="exact bf16 vs the stored kernel")
+    # and against the kernel before it was rounded to its storage format
+    assert_close(out, oracle_rows(data, "exact", kernel=M32), rtol=RTOL_DENSE_UNROUNDED, atol=ATOL, what="exact bf16 vs fp32 kernel")
     assert np.abs(out.astype(np.float64).sum(1) - 1).max() < 1e-5
 
 
@@ -284,10 +289,10 @@ def test_exact_bf16_batch_shapes(rdk, ragged, B):
     q = (c / float(1 << 15)).astype(np.float32)
     assert np.all(q.sum(1, dtype=np.float64) == 1.0) and np.array_equal(synth.bf16_round(q), q)
     out = rdk.rdk_redistribute_exact(kern, dev(q)).cpu().numpy()
-    Mb = synth.bf16_round(M32).astype(np.float64)
+    Mb = operand_round_M(M32)
     ref = np.empty((B, w.N))
     for b in range(B):
-        qb = synth.bf16_round(oracle.tli(q[b]).astype(np.float32))
+        qb = operand_round_q(oracle.tli(q[b]))
         r = oracle.redistribute_dense(qb, Mb)
         ref[b] = r / r.sum()
     assert_close(out, ref, rtol=2e-5, atol=ATOL, what="exact bf16, B=%d" % B)
@@ -466,10 +471,10 @@ def test_sample_draft(rdk, tiny, ragged, case, form):
     else:   # bf16 storage: the reference rows are the product of the rounded operands, rescaled to unit mass
         M32 = data["dense"].astype(np.float32)
         kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.DENSE_BF16, dense_M=dev(M32))
-        Mb = synth.bf16_round(M32).astype(np.float64)
+        Mb = operand_round_M(M32)
         ref_qp = np.empty((w.B, w.N))
         for b in range(w.B):
-            r = oracle.redistribute_dense(synth.bf16_round(oracle.tli(data["q_hat"][b]).astype(np.float32)), Mb)
+            r = oracle.redistribute_dense(operand_round_q(oracle.tli(data["q_hat"][b])), Mb)
             ref_qp[b] = r / r.sum()
     rtol = 4e-5 if form == "dense_bf16" else RTOL
     seed, offset = 909, (1 << 35) + 3
@@ -734,7 +739,11 @@ def test_degenerate_shapes(rdk, shape):
     kd = rdk.rdk_build_kernel(w.N, kept, rdk.DENSE_F32, dense_M=dev(M32))
     assert_close(rdk.rdk_redistribute_exact(kd, q).cpu().numpy(), ref_exact, what="exact fp32")
     kh = rdk.rdk_build_kernel(w.N, kept, rdk.DENSE_BF16, dense_M=dev(M32))
-    assert_close(rdk.rdk_redistribute_exact(kh, q).cpu().numpy(), ref_exact, rtol=RTOL_BF16 * 4, atol=1e-6, what="exact bf16")
+    ref_stored = oracle.redistribute_batch("exact", data["q_hat"], data["kept_ids"], w.N, M=operand_round_M(M32))
+    ref_stored /= ref_stored.sum(1, keepdims=True)
+    got_h = rdk.rdk_redistribute_exact(kh, q).cpu().numpy()
+    assert_close(got_h, ref_stored, rtol=RTOL_DENSE, atol=ATOL, what="exact bf16 vs the stored kernel")
+    assert_close(got_h, ref_exact, rtol=RTOL_DENSE_UNROUNDED, atol=ATOL, what="exact bf16 vs fp32 kernel")
 
     seed, offset = 31, 2
     for kern, gmode, ref_qp in ((ks, rdk.LINEAR_SPARSE, ref_sparse), (ki, rdk.LINEAR_TAYLOR, ref_taylor)):
@@ -911,7 +920,7 @@ def test_random_shapes_with_padded_rows(rdk, seed):
     if w.n * w.N <= 4_000_000:
         M32 = synth.random_row_stochastic(rng, w.n, w.N).astype(np.float32)
         ref_exact = oracle.redistribute_batch("exact", q64, data["kept_ids"], w.N, M=M32)
-        for fmt, tol in ((rdk.DENSE_F32, dict()), (rdk.DENSE_BF16, dict(rtol=RTOL_BF16 * 4, atol=1e-6))):
+        for fmt, tol in ((rdk.DENSE_F32, dict()), (rdk.DENSE_BF16, dict(rtol=RTOL_DENSE_UNROUNDED, atol=ATOL))):
             kd = rdk.rdk_build_kernel(w.N, kept, fmt, dense_M=dev(M32))
             view, big = out_view()
             rdk.rdk_redistribute_exact(kd, q_in, qk, out=view)
