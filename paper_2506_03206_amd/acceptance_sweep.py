@@ -29,28 +29,36 @@ def make_inputs(N, B, sigma, zipf_s, seed):
 
 
 def sweep(N=200000, B=64, keep=(100000, 20000, 5000, 2000, 500), sigma=2.0, zipf_s=1.0, seed=0, device="cuda:0"):
+    """Every number below comes out of the library: torch only holds the buffers and picks columns.
+
+    The softmax of a logit row is the library's redistribution with the identity kernel over the whole vocabulary
+    (every id kept); a pruned drafter is its logits on the kept ids (the softmax over them is Eq. 1 applied to the full
+    softmax); the overlap of two sub-distributions on the kept ids is rdk_verify_sample on those columns."""
     import torch
     from . import rdk
     z_p, z_d, by_frequency = make_inputs(N, B, sigma, zipf_s, seed)
     dev = torch.device(device)
-    zp = torch.from_numpy(z_p).to(dev)
-    q_full = torch.softmax(torch.from_numpy(z_d).to(dev), dim=1)   # input preparation, not part of the method
+    zp, zd = torch.from_numpy(z_p).to(dev), torch.from_numpy(z_d).to(dev)
+    everything = rdk.rdk_build_kernel(N, torch.arange(N, dtype=torch.int32, device=dev), rdk.IDENTITY)
+    p_full = rdk.rdk_redistribute_linear(everything, rdk.LINEAR_SPARSE, zp, "logit")      # softmax(z_p)
+    q_full = rdk.rdk_redistribute_linear(everything, rdk.LINEAR_SPARSE, zd, "logit")      # softmax(z_d)
     rows = []
     for n in keep:
         kept = np.sort(by_frequency[:n])
         kept_d = torch.from_numpy(kept).to(dev)
-        q_hat = q_full[:, kept_d.long()].contiguous()             # the drafter's probabilities on its own vocabulary
+        cols = kept_d.long()
         kern = rdk.rdk_build_kernel(N, kept_d, rdk.IDENTITY)
-        # (a) masked only: the sub-distribution scattered to the target ids, no renormalisation
-        masked = torch.zeros((B, N), dtype=torch.float32, device=dev)
-        masked[:, kept_d.long()] = q_hat
-        a_masked = rdk.rdk_verify_sample(zp, masked, seed=1, offset=0, gamma=0, p_kind="logit").alpha
+        zq = zd[:, cols].contiguous()                               # what the pruned drafter head emits
+        # (a) masked only: the drafter's full-vocabulary probabilities on the kept ids, no renormalisation; its overlap
+        #     with the target is the sum of min(p, q) over the kept columns
+        a_masked = rdk.rdk_verify_sample(p_full[:, cols].contiguous(), q_full[:, cols].contiguous(), seed=1, offset=0,
+                                         gamma=0).alpha
         # (b) token-level intersection: the identity kernel
-        tli = rdk.rdk_redistribute_linear(kern, rdk.LINEAR_SPARSE, q_hat)
+        tli = rdk.rdk_redistribute_linear(kern, rdk.LINEAR_SPARSE, zq, "logit")
         a_tli = rdk.rdk_verify_sample(zp, tli, seed=1, offset=0, gamma=0, p_kind="logit").alpha
         # (c) Eq. 3, fused with the verification
-        a_taylor = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, zp, q_hat, seed=1, offset=0, gamma=0,
-                                               p_kind="logit", q_kind="prob").alpha
+        a_taylor = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, zp, zq, seed=1, offset=0, gamma=0,
+                                               p_kind="logit", q_kind="logit").alpha
         rows.append({"N": N, "n": int(n), "kept_fraction": n / N, "alpha_masked": float(a_masked.mean()),
                      "alpha_tli": float(a_tli.mean()), "alpha_taylor": float(a_taylor.mean())})
     return rows

@@ -497,11 +497,14 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) v
 constexpr int kRowThreads = 1024;
 constexpr int kRowWaves = kRowThreads / kWave;
 constexpr int kRowQuads = 8;             // quads of slots a lane parks: n <= 4 * kRowThreads * kRowQuads
-constexpr int kRowSpan = 5;              // rows of 256 slots that the run of one chunk can touch
 
 struct RowLds {      // offsets in floats into the dynamic LDS block
     int pk, spare, blk_p, blk_a, kp, red, clo, total;
 };
+
+// Pairs (row of 256 slots, chunk) that share slots: walking through the slots in order, every step to the next row or
+// to the next chunk adds one pair, so row + chunk numbers the pairs without gaps.
+__host__ __device__ inline int row_pairs(int n, int nchunks) { return (n + 255) / 256 + nchunks; }
 
 __host__ __device__ inline RowLds row_lds_layout(int n, int nchunks)
 {
@@ -511,7 +514,7 @@ __host__ __device__ inline RowLds row_lds_layout(int n, int nchunks)
     L.spare = off; off += kWave;                       // where the lanes send the values of ids that are not kept
     L.blk_p = off; off += (nchunks + 3) & ~3;          // per chunk: sum of p over the not-kept ids
     L.blk_a = off; off += (nchunks + 3) & ~3;          //            sum of p / (N + p) over the not-kept ids
-    L.kp = off; off += 3 * nchunks * kRowSpan * 4;     // per chunk, row of slots and quarter wavefront: sums of q', max(0, p - q'), min(p, q')
+    L.kp = off; off += 3 * row_pairs(n, nchunks) * 4;  // per (row of slots, chunk) pair and quarter wavefront: sums of q', max(0, p - q'), min(p, q')
     L.red = off; off += kRowWaves * 4;
     L.clo = off; off += (nchunks + 1 + 3) & ~3;        // chunk_lo, as integers
     L.total = off;
@@ -578,6 +581,7 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int nchunks = (N + kChunk - 1) / kChunk;
+    const int npairs = row_pairs(n, nchunks);
     const RowLds L = row_lds_layout(n, nchunks);
     float *pk = lds + L.pk;
     const int64_t row = blockIdx.x;
@@ -623,7 +627,6 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
             qh[k] = load4<QK>(qr, min(s, n), n, false, QK == RDK_PROB_F32 ? 0.f : -INFINITY);   // min: no overflow of the index
         }
     }
-    for (int i = threadIdx.x; i < 3 * nchunks * kRowSpan * 4; i += kRowThreads) lds[L.kp + i] = 0.f;
     if ((int)threadIdx.x < ((n + 3) & ~3) - n) pk[n + threadIdx.x] = 0.f;   // the padding of the last quad
     // (no barrier here: it would wait for the loads just issued; nothing of the above is read before the barrier behind step A)
 
@@ -715,7 +718,6 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
         }
         int cc = c_first[k];
         int lo_c = __builtin_amdgcn_readfirstlane(clo[cc]);
-        const int row_first = lo_c >> 8;               // the first row of slots that the run of chunk c_first touches
         while (cc < nchunks && lo_c < s_row + 256) {
             const int hi_c = __builtin_amdgcn_readfirstlane(clo[cc + 1]);
             float sq = 0.f, sr = 0.f, sa = 0.f;
@@ -732,12 +734,11 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
                 sq = row16_sum(sq);
                 sr = row16_sum(sr);
                 sa = row16_sum(sa);
-                const int j = cc == c_first[k] ? r256 - row_first : 0;   // a chunk behind the first one of this row starts in it
                 if ((lane & 15) == 0) {
-                    float *dst = lds + L.kp + ((cc * kRowSpan + j) * 4 + (lane >> 4));
+                    float *dst = lds + L.kp + ((r256 + cc) * 4 + (lane >> 4));
                     dst[0] = sq;
-                    dst[nchunks * kRowSpan * 4] = sr;
-                    dst[2 * nchunks * kRowSpan * 4] = sa;
+                    dst[npairs * 4] = sr;
+                    dst[2 * npairs * 4] = sa;
                 }
             }
             ++cc;
@@ -747,10 +748,12 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     __syncthreads();
     for (int cc = threadIdx.x; cc < nchunks; cc += kRowThreads) {
         float sq = 0.f, sr = 0.f, sa = 0.f;
-        for (int j = 0; j < kRowSpan; ++j) {
-            const float *src = lds + L.kp + (cc * kRowSpan + j) * 4;
-            const float4 xq = *(const float4 *)src, xr = *(const float4 *)(src + nchunks * kRowSpan * 4),
-                         xa = *(const float4 *)(src + 2 * nchunks * kRowSpan * 4);
+        // the rows of slots that the run of this chunk touches, first to last (none for a chunk without kept ids)
+        const int lo_c = clo[cc], hi_c = clo[cc + 1];
+        for (int r = lo_c >> 8; hi_c > lo_c && r <= (hi_c - 1) >> 8; ++r) {
+            const float *src = lds + L.kp + (r + cc) * 4;
+            const float4 xq = *(const float4 *)src, xr = *(const float4 *)(src + npairs * 4),
+                         xa = *(const float4 *)(src + 2 * npairs * 4);
             sq += (xq.x + xq.y) + (xq.z + xq.w);
             sr += (xr.x + xr.y) + (xr.z + xr.w);
             sa += (xa.x + xa.y) + (xa.z + xa.w);

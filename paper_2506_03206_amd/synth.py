@@ -3,8 +3,9 @@
 This module only *makes inputs*: target / drafter logits and probabilities with a
 long-tailed (Zipf) token bias, a kept-id set that imitates frequency-ranked
 pruning, and Gaussian token embeddings that stand in for the affinity statistics.
-It holds none of the method's arithmetic and imports neither the GPU library nor
-the CPU oracle, so both can be fed from it.
+It holds none of the method's arithmetic (no softmax, no normalisation of a kernel:
+logits and raw draws only) and imports neither the GPU library nor the CPU oracle,
+so both can be fed from it.
 
 Shapes and value distributions follow what section 5.1 of the paper reports for real
 models: a long-tailed token distribution (a small share of the ids carries almost
@@ -72,13 +73,6 @@ def bf16_bits(x):
     return (np.ascontiguousarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
 
 
-def _row_softmax(z):
-    z = z.astype(np.float64)
-    z -= z.max(axis=1, keepdims=True)
-    e = np.exp(z)
-    return e / e.sum(axis=1, keepdims=True)
-
-
 def make_vocab(w: Workload, rng=None):
     """Rank bias over ids, the kept-id set (ascending int32) and the embeddings [N,d] fp32."""
     rng = rng or np.random.default_rng(w.seed)
@@ -100,18 +94,17 @@ def make_vocab(w: Workload, rng=None):
 
 
 def make_batch(w: Workload, bias, kept, rng, B=None):
-    """Target and drafter inputs for B positions.
+    """Target and drafter logits for B positions (draws only; whoever wants probabilities applies its own softmax).
 
     Returns a dict with
-      z_p [B,N] fp32 target logits, z_q [B,n] fp32 drafter logits on the kept slots,
-      p [B,N] fp32 target probabilities, q_hat [B,n] fp32 = the drafter's full-vocabulary
-      probabilities restricted to the kept ids (so each row sums to less than 1).
-    With logits_bf16 the logits are bf16 values (held in fp32) and p, q_hat come from them.
+      z_p [B,N] fp32 target logits,
+      z_d [B,N] fp32 the drafter's logits over the whole vocabulary (the target's plus unit Gaussian noise),
+      z_q [B,n] fp32 = z_d on the kept slots (what a pruned drafter head emits).
+    With logits_bf16 the logits are bf16 values (held in fp32).
     """
     B = B or w.B
     n = kept.size
-    out = {"z_p": np.empty((B, w.N), np.float32), "z_q": np.empty((B, n), np.float32),
-           "p": np.empty((B, w.N), np.float32), "q_hat": np.empty((B, n), np.float32)}
+    out = {"z_p": np.empty((B, w.N), np.float32), "z_d": np.empty((B, w.N), np.float32), "z_q": np.empty((B, n), np.float32)}
     for r0 in range(0, B, 16):                       # 16 rows at a time: target noise, then drafter noise
         r1 = min(B, r0 + 16)
         z_p = rng.standard_normal((r1 - r0, w.N), dtype=np.float32) * np.float32(w.sigma) + bias[None, :]
@@ -119,9 +112,8 @@ def make_batch(w: Workload, bias, kept, rng, B=None):
         if w.logits_bf16:
             z_p, z_d = bf16_round(z_p), bf16_round(z_d)
         out["z_p"][r0:r1] = z_p
+        out["z_d"][r0:r1] = z_d
         out["z_q"][r0:r1] = z_d[:, kept]
-        out["p"][r0:r1] = _row_softmax(z_p)
-        out["q_hat"][r0:r1] = _row_softmax(z_d)[:, kept]
     return out
 
 
@@ -133,17 +125,10 @@ def make(w: Workload, B=None):
     return batch
 
 
-def random_row_stochastic(rng, n, N, concentration=0.3):
-    """A dense random row-stochastic matrix [n,N] (Dirichlet rows), fp64."""
-    g = rng.gamma(concentration, size=(n, N)) + 1e-300
-    return g / g.sum(axis=1, keepdims=True)
-
-
-def random_sparse_kernel(rng, N, kept, k):
-    """A row-stochastic top-k-shaped kernel with random neighbours: for each pruned id k distinct kept
-    slots drawn uniformly and positive weights; Eq. 2's normalisation over the retained entries of each
-    row is done here in fp64.  Returns (nbr_idx [N-n,k] int32, nbr_w [N-n,k] fp32, self_w [n] fp32);
-    the same shape and access pattern as a kernel built from embeddings, at no build cost."""
+def random_neighbour_draws(rng, N, kept, k):
+    """The raw material of a top-k-shaped kernel, draws only: for each pruned id k distinct kept slots drawn uniformly
+    (nbr_idx [N-n,k] int32) and a positive unnormalised affinity per entry (fp64, as small as real ones).  Turning them
+    into a row-stochastic kernel (Eq. 2 over the retained entries) is left to the caller."""
     n = kept.size
     P = N - n
     idx = rng.integers(0, n, size=(P, k), dtype=np.int32)
@@ -153,7 +138,5 @@ def random_sparse_kernel(rng, N, kept, k):
         if dup.size == 0:
             break
         idx[dup] = rng.integers(0, n, size=(dup.size, k), dtype=np.int32)
-    a = np.exp(-5.0 - 3.0 * rng.random((P, k)))              # unnormalised affinities, as small as real ones
-    Z = 1.0 + np.bincount(idx.ravel(), weights=a.ravel(), minlength=n)
-    w = (a / Z[idx]).astype(np.float32)
-    return idx, w, (1.0 / Z).astype(np.float32)
+    a = np.exp(-5.0 - 3.0 * rng.random((P, k)))
+    return idx, a

@@ -1,7 +1,9 @@
 """Shared helpers of the GPU parity tests: tolerances, and validity checks for sampled ids."""
 import numpy as np
+import scipy.special
 
 import oracle
+from paper_2506_03206_amd import synth
 
 # fp32 paths: |g - o| <= RTOL |o| + ATOL elementwise; bf16 dense path: RTOL_BF16.
 RTOL, ATOL = 1e-5, 1e-7
@@ -14,6 +16,45 @@ RTOL_DENSE_UNROUNDED = 2.0 ** -8 + RTOL_BF16
 # A sampled id is compared exactly unless the threshold lies within CDF_TOL * total of a step of the
 # prefix sum: there fp32 summation order may pick the neighbour, which is accepted if it is valid.
 CDF_TOL = 1e-5
+
+
+def softmax_rows(z):
+    """Test-side preparation of probability inputs: the library softmax routine in fp64."""
+    return scipy.special.softmax(np.asarray(z, dtype=np.float64), axis=1)
+
+
+def add_probabilities(batch, kept):
+    """p [B,N] fp32 target probabilities and q_hat [B,n] fp32 = the drafter's full-vocabulary probabilities restricted
+    to the kept ids (rows sum to less than 1, so Eq. 1 does real work), from the logits of a synthetic batch."""
+    batch["p"] = softmax_rows(batch["z_p"]).astype(np.float32)
+    batch["q_hat"] = np.ascontiguousarray(softmax_rows(batch["z_d"])[:, kept], dtype=np.float32)
+    return batch
+
+
+def make_inputs(w, B=None):
+    """Vocabulary + one batch of a workload, logits and probabilities."""
+    data = synth.make(w, B)
+    return add_probabilities(data, data["kept_ids"])
+
+
+def random_row_stochastic(rng, n, N, concentration=0.3):
+    """A dense random row-stochastic matrix [n,N] (Dirichlet rows), fp64: an input kernel for the exact forms."""
+    g = rng.gamma(concentration, size=(n, N)) + 1e-300
+    return g / g.sum(axis=1, keepdims=True)
+
+
+def stochastic_topk_kernel(rng, N, kept, k):
+    """A row-stochastic top-k-shaped kernel with random neighbours, as an INPUT for the redistribution calls: raw draws
+    normalised over the retained entries of each row; that every row of M sums to one is asserted here from the
+    definition (and again by the library's own validation when the kernel is imported).
+    Returns (nbr_idx [N-n,k] int32, nbr_w [N-n,k] fp64, self_w [n] fp64)."""
+    idx, a = synth.random_neighbour_draws(rng, N, kept, k)
+    n = kept.size
+    Z = 1.0 + np.bincount(idx.ravel(), weights=a.ravel(), minlength=n)
+    wts, self_w = a / Z[idx], 1.0 / Z
+    mass = self_w + np.bincount(idx.ravel(), weights=wts.ravel(), minlength=n)
+    assert np.abs(mass - 1.0).max() < 1e-12
+    return idx, wts, self_w
 
 
 def bf16_round(x):

@@ -10,8 +10,8 @@ import torch
 
 import oracle
 from paper_2506_03206_amd import synth
-from parity_util import (ATOL, RTOL, RTOL_DENSE, RTOL_DENSE_UNROUNDED, assert_close, check_multi, check_verify_outputs, operand_round_M,
-                         operand_round_q, random_trees)
+from parity_util import (ATOL, RTOL, RTOL_DENSE, RTOL_DENSE_UNROUNDED, add_probabilities, assert_close, check_multi,
+                         check_verify_outputs, operand_round_M, operand_round_q, random_row_stochastic, random_trees)
 
 pytestmark = pytest.mark.gpu
 
@@ -37,11 +37,15 @@ def rows_of(o, r0, r1, gamma):
 
 
 @pytest.fixture(scope="module")
-def llama3():
+def llama3(rdk):
+    """The headline workload.  Its top-k kernel is the one the benchmark times: built on the device from the embeddings
+    (compared with the oracle's construction in a test of its own) and handed to the oracle as an input."""
     w = synth.WORKLOADS["llama3"]
     bias, kept, E, rng = synth.make_vocab(w)
-    batch = synth.make_batch(w, bias, kept, rng)
-    batch.update(w=w, kept_ids=kept, E=E)
+    batch = add_probabilities(synth.make_batch(w, bias, kept, rng), kept)
+    kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.SPARSE_TOPK, embeddings=dev(E), tau=w.tau, k=w.k)
+    idx, wt, sw = [t.cpu().numpy() for t in rdk.rdk_kernel_get_sparse(kern)]
+    batch.update(w=w, kept_ids=kept, E=E, kernel=kern, sparse=(idx, wt, sw))
     return batch
 
 
@@ -51,10 +55,7 @@ def test_llama3_fused_whole_batch(rdk, llama3, mode):
     w, kept = llama3["w"], llama3["kept_ids"]
     p, q = llama3["p"], llama3["q_hat"]
     if mode == "sparse":
-        idx, wt, sw = synth.random_sparse_kernel(np.random.default_rng(1), w.N, kept, w.k)
-        wt32, sw32 = wt.astype(np.float32), sw.astype(np.float32)
-        kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.SPARSE_TOPK, k=w.k, sparse=(dev(idx), dev(wt32), dev(sw32)))
-        gmode, sparse = rdk.LINEAR_SPARSE, (idx, wt32, sw32)
+        kern, gmode, sparse = llama3["kernel"], rdk.LINEAR_SPARSE, llama3["sparse"]
     else:
         kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.IDENTITY)
         gmode, sparse = rdk.LINEAR_TAYLOR, None
@@ -85,8 +86,7 @@ def test_llama3_device_built_topk_kernel(rdk, llama3):
     against the oracle (a pruned id's list depends only on its own embedding and the kept ones), and the
     row-stochastic property of the whole kernel."""
     w, kept, E = llama3["w"], llama3["kept_ids"], llama3["E"]
-    kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.SPARSE_TOPK, embeddings=dev(E), tau=w.tau, k=w.k)
-    idx, wt, sw = [t.cpu().numpy() for t in rdk.rdk_kernel_get_sparse(kern)]
+    idx, wt, sw = llama3["sparse"]
     assert idx.shape == (w.N - w.n, w.k) and idx.min() >= 0 and idx.max() < w.n
     # every row of M sums to 1: the diagonal weight plus all retained entries that point at the slot
     mass = sw.astype(np.float64) + np.bincount(idx.ravel(), weights=wt.astype(np.float64).ravel(), minlength=w.n)
@@ -110,9 +110,8 @@ def test_qwen_extreme_fused_sequences(rdk):
     w = synth.WORKLOADS["qwen_extreme"]
     bias, kept, E, rng = synth.make_vocab(w)
     batch = synth.make_batch(w, bias, kept, rng)
-    idx, wt, sw = synth.random_sparse_kernel(np.random.default_rng(2), w.N, kept, w.k)
-    wt32, sw32 = wt.astype(np.float32), sw.astype(np.float32)
-    kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.SPARSE_TOPK, k=w.k, sparse=(dev(idx), dev(wt32), dev(sw32)))
+    kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.SPARSE_TOPK, embeddings=dev(E), tau=w.tau, k=w.k)   # as the benchmark builds it
+    idx, wt32, sw32 = [t.cpu().numpy() for t in rdk.rdk_kernel_get_sparse(kern)]
     zp = torch.from_numpy(batch["z_p"]).to(torch.bfloat16).cuda()
     zq = torch.from_numpy(batch["z_q"]).to(torch.bfloat16).cuda()
     seed, offset = 77, 5
@@ -135,8 +134,8 @@ def test_n32k_exact_fp32_sampled_rows(rdk):
     """N=32000, n=8000, B=64, dense fp32 kernel (1 GB): all 64 positions on the device, eight of them on the oracle."""
     w = synth.WORKLOADS["n32k"]
     bias, kept, E, rng = synth.make_vocab(w)
-    batch = synth.make_batch(w, bias, kept, rng)
-    M32 = synth.random_row_stochastic(np.random.default_rng(3), w.n, w.N).astype(np.float32)
+    batch = add_probabilities(synth.make_batch(w, bias, kept, rng), kept)
+    M32 = random_row_stochastic(np.random.default_rng(3), w.n, w.N).astype(np.float32)
     kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.DENSE_F32, dense_M=dev(M32))
     out = rdk.rdk_redistribute_exact(kern, dev(batch["q_hat"])).cpu().numpy()
     rows = np.arange(3, w.B, 8)
@@ -152,7 +151,7 @@ def test_dense256k_exact_bf16(rdk):
     checked for unit mass and sign, and against the linear identity q'(a+b) = q'(a)/2 + q'(b)/2 on the device."""
     w = synth.WORKLOADS["dense256k"]
     bias, kept, E, rng = synth.make_vocab(w)
-    batch = synth.make_batch(w, bias, kept, rng)
+    batch = add_probabilities(synth.make_batch(w, bias, kept, rng), kept)
     kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.DENSE_BF16, embeddings=dev(E), tau=w.tau)
     q = batch["q_hat"].copy()
     srng = np.random.default_rng(11)
@@ -195,7 +194,7 @@ def test_dense256k_exact_bf16_wide_support(rdk):
     the oracle builds the 512 rows of Eq. 2 it needs from the same embeddings (about a minute of fp64 on the host)."""
     w = synth.WORKLOADS["dense256k"]
     bias, kept, E, rng = synth.make_vocab(w)
-    batch = synth.make_batch(w, bias, kept, rng)
+    batch = add_probabilities(synth.make_batch(w, bias, kept, rng), kept)
     kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.DENSE_BF16, embeddings=dev(E), tau=w.tau)
     srng = np.random.default_rng(23)
     scattered = srng.choice(w.n, 384, replace=False)
@@ -233,8 +232,7 @@ def test_llama3_verify_multi(rdk, llama3):
     """Several candidates per position at N=128256 on the whole batch of 256 positions (126 block sums per row,
     up to five passes per position): the sparse form's rows, materialised by the oracle, on both sides."""
     w, kept = llama3["w"], llama3["kept_ids"]
-    idx, wt, sw = synth.random_sparse_kernel(np.random.default_rng(1), w.N, kept, w.k)
-    q64 = oracle.redistribute_batch("sparse", llama3["q_hat"], kept, w.N, sparse=(idx, wt.astype(np.float32), sw.astype(np.float32)))
+    q64 = oracle.redistribute_batch("sparse", llama3["q_hat"], kept, w.N, sparse=llama3["sparse"])
     qp32 = q64.astype(np.float32)
     q64 = qp32.astype(np.float64)
     p64 = llama3["p"].astype(np.float64)
@@ -253,8 +251,7 @@ def test_llama3_verify_multi(rdk, llama3):
 def test_llama3_token_trees(rdk, llama3):
     """32 token trees of 8 nodes (up to 3 children per node) at N=128256: all 256 nodes verified, then the walk."""
     w, kept = llama3["w"], llama3["kept_ids"]
-    idx, wt, sw = synth.random_sparse_kernel(np.random.default_rng(1), w.N, kept, w.k)
-    qp32 = oracle.redistribute_batch("sparse", llama3["q_hat"], kept, w.N, sparse=(idx, wt.astype(np.float32), sw.astype(np.float32))).astype(np.float32)
+    qp32 = oracle.redistribute_batch("sparse", llama3["q_hat"], kept, w.N, sparse=llama3["sparse"]).astype(np.float32)
     q64, p64 = qp32.astype(np.float64), llama3["p"].astype(np.float64)
     S, nodes, C, seed, offset = 32, 8, 3, 99, 1 << 35
     child, cand = random_trees(np.random.default_rng(2), S, nodes, C, q64, seed, offset)

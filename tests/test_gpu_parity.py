@@ -9,7 +9,8 @@ import torch
 import oracle
 from paper_2506_03206_amd import synth
 from parity_util import (ATOL, RTOL, RTOL_DENSE, RTOL_DENSE_UNROUNDED, assert_close, check_multi, check_sampled_ids,
-                         check_verify_outputs, operand_round_M, operand_round_q, random_trees)
+                         check_verify_outputs, make_inputs, operand_round_M, operand_round_q, random_row_stochastic,
+                         random_trees, stochastic_topk_kernel)
 
 pytestmark = pytest.mark.gpu
 
@@ -37,7 +38,7 @@ def bf16_tensor(x):
 @pytest.fixture(scope="module")
 def tiny():
     w = synth.WORKLOADS["tiny"]
-    data = synth.make(w)
+    data = make_inputs(w)
     data["w"] = w
     data["sparse"] = oracle.build_sparse(data["E"], data["kept_ids"], w.tau, w.k)
     data["dense"] = oracle.build_dense(data["E"], data["kept_ids"], w.tau)
@@ -50,7 +51,7 @@ RAGGED = synth.scaled(synth.WORKLOADS["tiny"], name="ragged", N=3001, n=517, seq
 
 @pytest.fixture(scope="module")
 def ragged():
-    data = synth.make(RAGGED)
+    data = make_inputs(RAGGED)
     data["w"] = RAGGED
     data["sparse"] = oracle.build_sparse(data["E"], data["kept_ids"], RAGGED.tau, RAGGED.k)
     data["dense"] = oracle.build_dense(data["E"], data["kept_ids"], RAGGED.tau)
@@ -442,9 +443,9 @@ def test_acceptance_sweep_matches_oracle(rdk):
         a_tli = np.mean([oracle.overlap(p64[b], tli[b])[0] for b in range(B)])
         tay = oracle.redistribute_batch("taylor", q_hat, kept, N, p=p64)
         a_tay = np.mean([oracle.overlap(p64[b], tay[b])[0] for b in range(B)])
-        # the device softmaxes fp32 logits itself; the drafter's probabilities come from a torch softmax (input preparation)
-        assert abs(row["alpha_masked"] - a_masked) < 2e-5 and abs(row["alpha_tli"] - a_tli) < 2e-5
-        assert abs(row["alpha_taylor"] - a_tay) < 2e-5
+        # every softmax and every sum ran in the library; the means of eight rows carry the stated tolerance
+        for name, ref_a in (("alpha_masked", a_masked), ("alpha_tli", a_tli), ("alpha_taylor", a_tay)):
+            assert abs(row[name] - ref_a) <= RTOL * ref_a + ATOL, (name, n, row[name], ref_a)
         assert row["alpha_tli"] >= row["alpha_masked"] - 1e-6          # Eq. 1 only scales the kept mass up
 
 
@@ -703,7 +704,7 @@ DEGENERATE = {
 def test_degenerate_shapes(rdk, shape):
     """The smallest and the limiting shapes the method allows, through every redistribution form and the fused call."""
     w = synth.scaled(synth.WORKLOADS["tiny"], name=shape, seed=7, **DEGENERATE[shape])
-    data = synth.make(w)
+    data = make_inputs(w)
     data["w"] = w
     kept = dev(data["kept_ids"])
     idx, wt, sw = oracle.build_sparse(data["E"], data["kept_ids"], w.tau, w.k)
@@ -799,7 +800,8 @@ def test_sparse_rows_longer_than_one_round(rdk, ragged, k):
     and the draft draw bit-equal to the fused call's."""
     data = ragged
     w = data["w"]
-    idx, wt, sw = synth.random_sparse_kernel(np.random.default_rng(40 + k), w.N, data["kept_ids"], k)
+    idx, wt, sw = stochastic_topk_kernel(np.random.default_rng(40 + k), w.N, data["kept_ids"], k)
+    wt, sw = wt.astype(np.float32), sw.astype(np.float32)          # the kernel as both sides store it
     kern = rdk.rdk_build_kernel(w.N, dev(data["kept_ids"]), rdk.SPARSE_TOPK, k=k, sparse=(dev(idx), dev(wt), dev(sw)))
     p, q = dev(data["p"]), dev(data["q_hat"])
     seed, offset = 77, 9
@@ -846,7 +848,7 @@ def test_random_shapes_with_padded_rows(rdk, seed):
     tensors (row stride above the width, padding poisoned): nothing past a row's width may be read or written."""
     shape, (pad_p, pad_q, pad_o), rng = draw_shape(seed)
     w = synth.scaled(synth.WORKLOADS["tiny"], name="random%d" % seed, seed=100 + seed, **shape)
-    data = synth.make(w)
+    data = make_inputs(w)
     data["w"] = w
     kinds = ("prob", "logit", "bf16")[seed % 3]
     if kinds == "bf16":
@@ -854,7 +856,7 @@ def test_random_shapes_with_padded_rows(rdk, seed):
     print("seed", seed, shape, "pads", (pad_p, pad_q, pad_o), kinds, flush=True)
     kept = dev(data["kept_ids"])
     if 0 < w.k <= w.n // 2:
-        idx, wt, sw = synth.random_sparse_kernel(rng, w.N, data["kept_ids"], w.k)
+        idx, wt, sw = stochastic_topk_kernel(rng, w.N, data["kept_ids"], w.k)
     else:   # no neighbours, or most of the kept slots: the top-k kernel of the embeddings (distinct by construction)
         idx, wt, sw = oracle.build_sparse(data["E"], data["kept_ids"], w.tau, w.k)
     wt32, sw32 = np.asarray(wt, np.float32), np.asarray(sw, np.float32)
@@ -918,7 +920,7 @@ def test_random_shapes_with_padded_rows(rdk, seed):
     check_sampled_ids(ref_sparse, u0, ids.cpu().numpy(), ref_ids, what="draft from q'")
     # exact forms on a random row-stochastic kernel
     if w.n * w.N <= 4_000_000:
-        M32 = synth.random_row_stochastic(rng, w.n, w.N).astype(np.float32)
+        M32 = random_row_stochastic(rng, w.n, w.N).astype(np.float32)
         ref_exact = oracle.redistribute_batch("exact", q64, data["kept_ids"], w.N, M=M32)
         for fmt, tol in ((rdk.DENSE_F32, dict()), (rdk.DENSE_BF16, dict(rtol=RTOL_DENSE_UNROUNDED, atol=ATOL))):
             kd = rdk.rdk_build_kernel(w.N, kept, fmt, dense_M=dev(M32))

@@ -16,6 +16,7 @@ import oracle
 from paper_2506_03206_amd import synth
 
 from conftest import read_golden
+from parity_util import make_inputs, random_row_stochastic
 
 
 def rand_dist(rng, N, zeros=0):
@@ -118,13 +119,13 @@ def test_thm43_worked_example():
 def test_dense_is_M_transpose_times_q():
     rng = np.random.default_rng(3)
     n, N = 13, 37
-    M = synth.random_row_stochastic(rng, n, N)
+    M = random_row_stochastic(rng, n, N)
     q = oracle.tli(rng.gamma(0.5, size=n))
     pp = oracle.redistribute_dense(q, M)
     np.testing.assert_allclose(pp, q @ M, rtol=1e-13)                     # library matmul
     assert pp.min() >= 0 and abs(pp.sum() - 1) < 1e-13                   # mass preserved (Assumption 3.1)
     # a square non-symmetric M tells M^T q from M q
-    Ms = synth.random_row_stochastic(rng, n, n)
+    Ms = random_row_stochastic(rng, n, n)
     qs = oracle.tli(rng.gamma(0.5, size=n))
     out = oracle.redistribute_dense(qs, Ms)
     np.testing.assert_allclose(out, Ms.T @ qs, rtol=1e-13)
@@ -154,7 +155,7 @@ def test_thm41_and_lemma_b1(n, N, seed):
     """Lemma B.1: M^T is non-expansive in L1.  Thm 4.1: ||p'-p||_1 <= ||q0-p||_1 + ||M^T p - p||_1."""
     rng = np.random.default_rng(seed)
     # square case of the theorem: every id is "kept" so that M^T p is defined
-    M = synth.random_row_stochastic(rng, N, N)
+    M = random_row_stochastic(rng, N, N)
     x, y = rand_dist(rng, N), rand_dist(rng, N)
     lhs = np.abs(oracle.redistribute_dense(x, M) - oracle.redistribute_dense(y, M)).sum()
     assert lhs <= np.abs(x - y).sum() + 1e-12
@@ -352,7 +353,7 @@ def test_monte_carlo_acceptance_and_losslessness():
     N, n, trials = 12, 5, 120000
     p = rand_dist(rng, N, 2)
     kept = np.sort(rng.choice(N, n, replace=False)).astype(np.int32)
-    M = synth.random_row_stochastic(rng, n, N, 0.8)
+    M = random_row_stochastic(rng, n, N, 0.8)
     qp = oracle.redistribute_dense(oracle.tli(rng.gamma(0.5, size=n)), M)
     P = np.broadcast_to(p, (trials, N))
     Q = np.broadcast_to(qp, (trials, N))
@@ -380,7 +381,7 @@ def test_monte_carlo_acceptance_and_losslessness():
 def test_rdk_beats_tli_when_the_target_lives_off_the_kept_ids():
     """Qualitative claim of section 3: redistribution raises alpha when p has mass on pruned ids."""
     w = synth.WORKLOADS["tiny"]
-    data = synth.make(w)
+    data = make_inputs(w)
     sp = oracle.build_sparse(data["E"], data["kept_ids"], w.tau, w.k)
     for b in range(3):
         q_tli = oracle.tli(data["q_hat"][b])
