@@ -25,6 +25,10 @@ def build(force=False):
         subprocess.check_call(
             ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-ffp-contract=off", "-shared", "-fPIC",
              _SRC, "-o", _LIB, "-lm"])
+        # the driver of the sanitizer test (tests/test_oracle_sanitizers.py builds it again with the sanitizers on)
+        subprocess.check_call(
+            ["gcc", "-O1", "-std=c11", "-Wall", "-Wextra", "-ffp-contract=off", _SRC, os.path.join(_HERE, "sanitize_driver.c"),
+             "-o", os.path.join(_HERE, "sanitize_driver.bin"), "-lm"])
     return _LIB
 
 

@@ -224,7 +224,7 @@ rdk_status_t rdk_build_kernel(const rdk_kernel_desc_t *desc, void *storage, size
     if (rc != RDK_OK) return rc;
     int32_t *pruned = (int32_t *)(sp + L.pruned_ids);
     h.pruned_ids = pruned;
-    rc = launch_pruned_ids(slot_of, d.N, pruned, st);
+    rc = launch_pruned_ids(slot_of, d.N, d.n, pruned, st);
     if (rc != RDK_OK) return rc;
     int32_t *chunk_lo = (int32_t *)(sp + L.chunk_lo);
     h.chunk_lo = chunk_lo;

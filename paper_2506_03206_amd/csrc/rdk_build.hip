@@ -131,10 +131,12 @@ __global__ void chunk_lo_kernel(const int32_t *kept_ids, int n, int nchunks, int
     chunk_lo[c] = lo;
 }
 
-__global__ void pruned_ids_kernel(const int32_t *slot_of, int N, int32_t *pruned_ids)
+__global__ void pruned_ids_kernel(const int32_t *slot_of, int N, int n, int32_t *pruned_ids)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j < N && slot_of[j] < 0) pruned_ids[-slot_of[j] - 1] = j;
+    if (j >= N || slot_of[j] >= 0) return;
+    const int u = -slot_of[j] - 1;
+    if (u < N - n) pruned_ids[u] = j;   // always true for ascending kept ids; an unchecked list must not write past the table
 }
 
 // Per chunk and lane the kept mask of the lane's 16 ids and the kept ids of the chunk below each of its four groups.
@@ -291,7 +293,8 @@ __global__ void sparse_import_kernel(int n_pruned, int n, int k, int kk, const i
     if (t >= (int64_t)n_pruned * kk) return;
     const int64_t u = t / kk;
     const int e = (int)(t % kk);
-    nbr[t] = make_int2(e < k ? sp_idx[u * k + e] : 0, __float_as_int(e < k ? sp_w[u * k + e] : 0.f));
+    // slots are clamped into [0, n): a table that was not validated cannot send a gather outside the drafter rows
+    nbr[t] = make_int2(e < k ? min(max(sp_idx[u * k + e], 0), n - 1) : 0, __float_as_int(e < k ? sp_w[u * k + e] : 0.f));
 }
 
 __global__ void sparse_export_kernel(int n_pruned, int n, int k, int kk, const int2 *nbr, const float *self_w,
@@ -337,10 +340,11 @@ __global__ __launch_bounds__(256) void dense_rows_kernel(const float *E, int d, 
 
 __global__ void dense_scale_kernel(float *M, int64_t ldm, int n, int N, const double *row_sum)
 {
-    const int s = blockIdx.y;
-    const double inv = 1.0 / row_sum[s];
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += (int64_t)gridDim.x * blockDim.x)
-        M[(int64_t)s * ldm + j] = (float)((double)M[(int64_t)s * ldm + j] * inv);
+    for (int s = blockIdx.y; s < n; s += gridDim.y) {   // rows beyond the grid's second dimension are looped over
+        const double inv = 1.0 / row_sum[s];
+        for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += (int64_t)gridDim.x * blockDim.x)
+            M[(int64_t)s * ldm + j] = (float)((double)M[(int64_t)s * ldm + j] * inv);
+    }
 }
 
 // Row sums and sign check of a supplied dense kernel.
@@ -453,9 +457,9 @@ rdk_status_t launch_chunk_lo(const int32_t *kept_ids, int32_t n, int32_t N, int3
     return RDK_OK;
 }
 
-rdk_status_t launch_pruned_ids(const int32_t *slot_of, int32_t N, int32_t *pruned_ids, hipStream_t st)
+rdk_status_t launch_pruned_ids(const int32_t *slot_of, int32_t N, int32_t n, int32_t *pruned_ids, hipStream_t st)
 {
-    hipLaunchKernelGGL(pruned_ids_kernel, dim3((N + 255) / 256), dim3(256), 0, st, slot_of, N, pruned_ids);
+    hipLaunchKernelGGL(pruned_ids_kernel, dim3((N + 255) / 256), dim3(256), 0, st, slot_of, N, n, pruned_ids);
     RDK_LAUNCH_CHECK("pruned_ids_kernel");
     return RDK_OK;
 }
@@ -515,7 +519,7 @@ rdk_status_t launch_build_dense(const rdk_kernel_desc_t &d, float *M, int64_t ld
     hipLaunchKernelGGL(dense_rows_kernel, dim3((d.n + kTile - 1) / kTile), dim3(256), 0, st, d.embeddings, d.d, w.inv_norm,
                        d.kept_ids, d.n, d.N, 1.0 / (double)d.tau, M, ldm, w.row_sum);
     RDK_LAUNCH_CHECK("dense_rows_kernel");
-    hipLaunchKernelGGL(dense_scale_kernel, dim3(64, d.n), dim3(256), 0, st, M, ldm, d.n, d.N, w.row_sum);
+    hipLaunchKernelGGL(dense_scale_kernel, dim3(64, d.n < 32768 ? d.n : 32768), dim3(256), 0, st, M, ldm, d.n, d.N, w.row_sum);
     RDK_LAUNCH_CHECK("dense_scale_kernel");
     return RDK_OK;
 }

@@ -98,7 +98,7 @@ rdk_status_t launch_features_from_scores(const void *z, rdk_input_kind_t kind, i
 rdk_status_t launch_chunk_lo(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *chunk_lo, hipStream_t st);
 rdk_status_t launch_lane_map(const int32_t *slot_of, const int32_t *chunk_lo, int32_t N, int32_t n, uint64_t *lane_map,
                              hipStream_t st);
-rdk_status_t launch_pruned_ids(const int32_t *slot_of, int32_t N, int32_t *pruned_ids, hipStream_t st);
+rdk_status_t launch_pruned_ids(const int32_t *slot_of, int32_t N, int32_t n, int32_t *pruned_ids, hipStream_t st);
 rdk_status_t launch_build_sparse(const rdk_kernel_desc_t &d, const int32_t *pruned_ids, int2 *nbr, float *self_w,
                                  int32_t kk, void *ws, hipStream_t st);
 rdk_status_t launch_import_sparse(const rdk_kernel_desc_t &d, int2 *nbr, float *self_w, int32_t kk, hipStream_t st);

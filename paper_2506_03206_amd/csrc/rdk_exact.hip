@@ -189,14 +189,15 @@ __global__ __launch_bounds__(kSplitWaves * kWave) __attribute__((amdgpu_waves_pe
 
 // Sum of the split partials in split order, divided by the drafter row sum (Eq. 1).
 __global__ void exact_reduce_kernel(const float *part, int64_t ldd, int64_t split_stride, int splits, const SoftStat *qstat,
-                                    int N, float *out, int64_t ldo)
+                                    int N, int B, float *out, int64_t ldo)
 {
-    const int b = blockIdx.y;
-    const float sc = inv_mass(qstat[b].s);
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += (int64_t)gridDim.x * blockDim.x) {
-        float s = 0.f;
-        for (int z = 0; z < splits; ++z) s += part[(int64_t)z * split_stride + (int64_t)b * ldd + j];
-        out[(int64_t)b * ldo + j] = s * sc;
+    for (int b = blockIdx.y; b < B; b += gridDim.y) {   // positions beyond the grid's second dimension are looped over
+        const float sc = inv_mass(qstat[b].s);
+        for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += (int64_t)gridDim.x * blockDim.x) {
+            float s = 0.f;
+            for (int z = 0; z < splits; ++z) s += part[(int64_t)z * split_stride + (int64_t)b * ldd + j];
+            out[(int64_t)b * ldo + j] = s * sc;
+        }
     }
 }
 
@@ -525,8 +526,8 @@ rdk_status_t run_exact(const KernelHandle &h, RowInput q, int32_t B, float *out,
             RDK_TIMED_LAUNCH("exact_f32_split_kernel", exact_f32_split_kernel, grid, dim3(kSplitWaves * kWave), 0, st, Ap, h.dense,
                              h.ldm, h.n, h.N, B, KB, blocks, w.qstat, w.part, ldd, (int64_t)B * ldd, false, true);
             RDK_LAUNCH_CHECK("exact_f32_split_kernel");
-            RDK_TIMED_LAUNCH("exact_reduce_kernel", exact_reduce_kernel, dim3((h.N + 1023) / 1024, B), dim3(256), 0, st, w.part,
-                             ldd, (int64_t)B * ldd, splits, w.qstat, h.N, out, ldo);
+            RDK_TIMED_LAUNCH("exact_reduce_kernel", exact_reduce_kernel, dim3((h.N + 1023) / 1024, B < 32768 ? B : 32768), dim3(256), 0,
+                             st, w.part, ldd, (int64_t)B * ldd, splits, w.qstat, h.N, B, out, ldo);
             RDK_LAUNCH_CHECK("exact_reduce_kernel");
         }
         return RDK_OK;

@@ -796,15 +796,16 @@ struct QpTaylor {
 // ------------------------------------------------------------------------------------------------
 // Identity kernel: q' scattered to the kept ids, zero elsewhere (token-level intersection, Eq. 1).
 template <int QK>
-__global__ __launch_bounds__(kThreads) void tli_scatter_kernel(const void *q, int64_t ldq, const int32_t *slot_of, int N,
+__global__ __launch_bounds__(kThreads) void tli_scatter_kernel(const void *q, int64_t ldq, const int32_t *slot_of, int N, int B,
                                                                const SoftStat *qstat, float *out, int64_t ldo)
 {
-    const int64_t row = blockIdx.y;
-    const void *qr = row_ptr<QK>(q, ldq, row);
-    const float qm = qstat[row].m, inv = inv_mass(qstat[row].s);
-    for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < N; j += (int64_t)gridDim.x * kThreads) {
-        const int s = slot_of[j];
-        out[row * ldo + j] = s >= 0 ? to_weight<QK>(load1<QK>(qr, s), qm, 1.f) * inv : 0.f;
+    for (int64_t row = blockIdx.y; row < B; row += gridDim.y) {   // positions beyond the grid's second dimension are looped over
+        const void *qr = row_ptr<QK>(q, ldq, row);
+        const float qm = qstat[row].m, inv = inv_mass(qstat[row].s);
+        for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < N; j += (int64_t)gridDim.x * kThreads) {
+            const int s = slot_of[j];
+            out[row * ldo + j] = s >= 0 ? to_weight<QK>(load1<QK>(qr, s), qm, 1.f) * inv : 0.f;
+        }
     }
 }
 
@@ -938,8 +939,8 @@ rdk_status_t run_tli(const KernelHandle &h, RowInput q, int32_t B, float *out, i
     if (rc != RDK_OK) return rc;
     const int bx = (h.N + kThreads * 4 - 1) / (kThreads * 4);
     {
-        RDK_TIMED_LAUNCH("tli_scatter_kernel", (tli_scatter_kernel<QK>), dim3(bx, B), dim3(kThreads), 0, st, q.ptr, q.ld,
-                         h.slot_of, h.N, w.qstat, out, ldo);
+        RDK_TIMED_LAUNCH("tli_scatter_kernel", (tli_scatter_kernel<QK>), dim3(bx, B < 32768 ? B : 32768), dim3(kThreads), 0, st, q.ptr,
+                         q.ld, h.slot_of, h.N, B, w.qstat, out, ldo);
     }
     RDK_LAUNCH_CHECK("tli_scatter_kernel");
     return RDK_OK;
