@@ -488,35 +488,37 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) v
 //     N >= 2), so its share of the three block sums is a closed form of  P = sum p_j  and  A = sum p_j / (N + p_j)
 //     over the not-kept ids of the block: sum q' = sum min(p, q') = (theta / S) A,  sum max(0, p - q') = P - (theta / S) A;
 //   * a kept id needs its own p and q^: while the row streams by, the target values of the kept ids are scattered
-//     into LDS in slot order (4 n bytes: one value per drafter slot) and the drafter row sits in registers
-//     (eight quads of slots per lane).
-// Step A streams p next to the id -> slot map (L2-resident, shared by all rows); step B sums q^, q^ p and q^ / (N + p)
-// over the slots out of LDS and registers; step C forms q', min and max for the kept slots and sums them per
-// 1024-id chunk (the slots of a chunk are a contiguous run, so a row of 256 slots meets few chunks; partial sums of
-// a chunk that spans several rows are added in row order).  HBM traffic: p and q once.
+//     into LDS, chunk by chunk in slot order (4 n bytes: one value per drafter slot; the run of every chunk starts
+//     on a 16-byte boundary).
+// Step A streams p, guided by the kernel's lane map (L2-resident, shared by all rows).  Steps B and C belong to the kept
+// slots: sixteen lanes own one chunk and sweep its run of slots, the drafter values straight from global memory (they
+// are held in registers from B to C), the target values from LDS.  B sums q^, q^ p, q^ / (N + p) and p / (N + p) for the
+// row constants; C forms q', max(0, p - q') and min(p, q') and, a chunk being the business of one group of lanes, adds
+// them up with four register-speed lane exchanges and writes the three block sums.  HBM traffic: p and q once.
 constexpr int kRowThreads = 1024;
 constexpr int kRowWaves = kRowThreads / kWave;
-constexpr int kRowQuads = 8;             // quads of slots a lane parks: n <= 4 * kRowThreads * kRowQuads
+constexpr int kRowGroups = kRowThreads / 16;   // groups of sixteen lanes: one chunk each per round of steps B and C
+constexpr int kRowSteps = 5;                   // quads per lane and chunk held in registers: runs of up to 320 kept ids per chunk
 
 struct RowLds {      // offsets in floats into the dynamic LDS block
-    int pk, spare, blk_p, blk_a, kp, red, clo, total;
+    int pk, spare, blk_p, blk_a, red, total;
 };
 
-// Pairs (row of 256 slots, chunk) that share slots: walking through the slots in order, every step to the next row or
-// to the next chunk adds one pair, so row + chunk numbers the pairs without gaps.
-__host__ __device__ inline int row_pairs(int n, int nchunks) { return (n + 255) / 256 + nchunks; }
+// Where the run of chunk c (first slot lo) starts in the LDS array of kept target values: a multiple of four floats, and
+// far enough from the run before it (align down costs at most 3, the 4 c make up for it).
+__host__ __device__ inline int row_run_start(int lo, int c) { return (lo & ~3) + 4 * c; }
 
 __host__ __device__ inline RowLds row_lds_layout(int n, int nchunks)
 {
     RowLds L;
     int off = 0;
-    L.pk = off; off += (n + 3) & ~3;                   // target values of the kept ids, by slot
+    // target values of the kept ids: runs of slots, one per chunk, and room for the quads that steps B and C read past the
+    // end of the last runs (their values are masked)
+    L.pk = off; off += ((n + 3) & ~3) + 4 * nchunks + 64 * kRowSteps + 4;
     L.spare = off; off += kWave;                       // where the lanes send the values of ids that are not kept
     L.blk_p = off; off += (nchunks + 3) & ~3;          // per chunk: sum of p over the not-kept ids
     L.blk_a = off; off += (nchunks + 3) & ~3;          //            sum of p / (N + p) over the not-kept ids
-    L.kp = off; off += 3 * row_pairs(n, nchunks) * 4;  // per (row of slots, chunk) pair and quarter wavefront: sums of q', max(0, p - q'), min(p, q')
     L.red = off; off += kRowWaves * 4;
-    L.clo = off; off += (nchunks + 1 + 3) & ~3;        // chunk_lo, as integers
     L.total = off;
     return L;
 }
@@ -540,29 +542,31 @@ __device__ __forceinline__ void row_fetch(const float *pr, const uint64_t *lane_
 // 1 / (N + p) for 0 <= p <= 1.  For a large vocabulary the first two terms of the series in p / N are exact to fp32
 // rounding (the next term is (p / N)^2 <= 2^-24 of the result for N >= 4096) and cost one multiply-add instead of a
 // reciprocal, which the vector unit issues at a quarter of the rate.
+template <bool SERIES>
 struct RowRcp {
     float fN, invN, invN2;
-    bool series;
     __device__ __forceinline__ float operator()(float p) const
     {
-        return series ? fmaf(-p, invN2, invN) : __builtin_amdgcn_rcpf(fN + p);
+        return SERIES ? fmaf(-p, invN2, invN) : __builtin_amdgcn_rcpf(fN + p);
     }
 };
 
-// Step A for one chunk: target values of kept ids go to their slots in LDS (the others to a spare word of the lane),
+// Step A for one chunk c: target values of kept ids go to their slots in LDS (the others to a spare word of the lane),
 // the not-kept ones are summed.
 template <bool SERIES>
-__device__ __forceinline__ void row_scatter(const RowChunk &b, const RowRcp &rcp, float *pk, int spare_idx, float &sp, float &sa)
+__device__ __forceinline__ void row_scatter(const RowChunk &b, int c, const RowRcp<SERIES> &rcp, float *pk, int spare_idx,
+                                            float &sp, float &sa)
 {
     const uint32_t mask = (uint32_t)b.map & 0xFFFFu;
+    const int run = row_run_start(b.lo, c);                       // where the chunk's first slot sits in LDS
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        int idx = b.lo + (int)((b.map >> (16 + 12 * i)) & 0xFFFu);   // slot of the lane's first kept id of this group
+        int idx = run + (int)((b.map >> (16 + 12 * i)) & 0xFFFu);   // slot of the lane's first kept id of this group
         const float pe[4] = {b.p[i].x, b.p[i].y, b.p[i].z, b.p[i].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const bool is_kept = (mask >> (4 * i + e)) & 1u;
-            const float r = SERIES ? fmaf(-pe[e], rcp.invN2, rcp.invN) : __builtin_amdgcn_rcpf(rcp.fN + pe[e]);
+            const float r = rcp(pe[e]);
             pk[is_kept ? idx : spare_idx] = pe[e];
             idx += is_kept ? 1 : 0;
             const float pn = is_kept ? 0.f : pe[e];
@@ -572,16 +576,65 @@ __device__ __forceinline__ void row_scatter(const RowChunk &b, const RowRcp &rcp
     }
 }
 
+// The raw drafter values of four consecutive slots from s on (unspecified at slots beyond the row: the caller masks by its
+// own bound).  One 16-byte load when the quad lies inside the row -- four bytes of alignment are all a global load of
+// that size needs -- and single loads for the quad that crosses the end of the row.  Every load writes the one result
+// under a one-sided branch, so a sequence of calls issues its loads back to back (loads merged from two code paths would
+// each be waited for at the merge).
+template <int QK>
+__device__ __forceinline__ float4 row_raw_quad(const void *qr, int s, int n)
+{
+    float4 raw = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (QK == RDK_LOGIT_BF16) {
+        const uint16_t *r = (const uint16_t *)qr;
+        if (s + 3 < n) {
+            typedef unsigned short u16x4a __attribute__((ext_vector_type(4), aligned(2)));
+            const u16x4a v = *(const u16x4a *)(r + s);
+            raw = make_float4(bf16_to_f32(v.x), bf16_to_f32(v.y), bf16_to_f32(v.z), bf16_to_f32(v.w));
+        }
+        if (s < n && s + 3 >= n) {
+            raw.x = bf16_to_f32(r[s]);
+            if (s + 1 < n) raw.y = bf16_to_f32(r[s + 1]);
+            if (s + 2 < n) raw.z = bf16_to_f32(r[s + 2]);
+        }
+    } else {
+        const float *r = (const float *)qr;
+        if (s + 3 < n) {
+            typedef float f32x4a __attribute__((ext_vector_type(4), aligned(4)));
+            const f32x4a v = *(const f32x4a *)(r + s);
+            raw = make_float4(v.x, v.y, v.z, v.w);
+        }
+        if (s < n && s + 3 >= n) {
+            raw.x = r[s];
+            if (s + 1 < n) raw.y = r[s + 1];
+            if (s + 2 < n) raw.z = r[s + 2];
+        }
+    }
+    return raw;
+}
+
+// The drafter weights of a raw quad: slots at or beyond `end` give zero.
+template <int QK>
+__device__ __forceinline__ float4 row_weights_of(const float4 raw, int s, int end, float qm)
+{
+    return make_float4(s + 0 < end ? to_weight<QK>(raw.x, qm, 1.f) : 0.f, s + 1 < end ? to_weight<QK>(raw.y, qm, 1.f) : 0.f,
+                       s + 2 < end ? to_weight<QK>(raw.z, qm, 1.f) : 0.f, s + 3 < end ? to_weight<QK>(raw.w, qm, 1.f) : 0.f);
+}
+
+template <int QK>
+__device__ __forceinline__ float4 row_weights(const void *qr, int s, int end, int n, float qm)
+{
+    return row_weights_of<QK>(row_raw_quad<QK>(qr, s, n), s, end, qm);
+}
+
 template <int QK, bool SERIES>
 __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p, int64_t ldp, const void *q, int64_t ldq,
-                                                                 const int32_t *kept, const uint64_t *lane_map,
-                                                                 const int32_t *chunk_lo, int N, int n, bool vec_p, bool vec_q,
-                                                                 const SoftStat *qstat, float *tpart, float *part_q,
+                                                                 const uint64_t *lane_map, const int32_t *chunk_lo, int N, int n,
+                                                                 bool vec_p, const SoftStat *qstat, float *tpart, float *part_q,
                                                                  float *part_r, float *part_a)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int nchunks = (N + kChunk - 1) / kChunk;
-    const int npairs = row_pairs(n, nchunks);
     const RowLds L = row_lds_layout(n, nchunks);
     float *pk = lds + L.pk;
     const int64_t row = blockIdx.x;
@@ -590,53 +643,42 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     const void *qr = row_ptr<QK>(q, ldq, row);
     const float qm = QK == RDK_PROB_F32 ? 0.f : qstat[row].m;
     const float fN = (float)N;
-    RowRcp rcp;
+    RowRcp<SERIES> rcp;
     rcp.fN = fN;
     rcp.invN = 1.0f / fN;
     rcp.invN2 = rcp.invN * rcp.invN;
-    rcp.series = SERIES;
     const int spare_idx = (L.spare - L.pk) + lane;    // relative to pk
 
-    // ---- the small tables first (loads come back in issue order: behind the row they would wait for it): chunk_lo into
-    // LDS, and the first chunk of each of this wavefront's rows of 256 slots (row wid + 16 k; scalar loads, for step C)
-    int *clo = (int *)(lds + L.clo);
-    for (int i = threadIdx.x; i <= nchunks; i += kRowThreads) clo[i] = chunk_lo[i];
-    int c_first[kRowQuads];
+    // ---- what steps B and C need first: the slot runs of this lane's chunks (group g of sixteen lanes takes the chunks
+    // g, g + 64, ...), asked for now so that nothing waits for them later, and one value of every 128-byte line of the
+    // drafter row, which brings the row into L2 while the target row streams
+    const int grp = threadIdx.x >> 4, li = threadIdx.x & 15;
+    constexpr int kHeld = 2;                                        // rounds of chunks whose drafter values stay in registers
+    int lo_h[kHeld], hi_h[kHeld];
 #pragma unroll
-    for (int k = 0; k < kRowQuads; ++k) c_first[k] = kept[min(256 * (wid + kRowWaves * k), n - 1)] >> 10;
-    // ---- then the first two chunks are asked for, and the drafter row goes into registers (lane t, quad k: slots
-    // 4 (t + 1024 k) .. + 3)
+    for (int t = 0; t < kHeld; ++t) {
+        const int cc = grp + kRowGroups * t;
+        lo_h[t] = cc < nchunks ? chunk_lo[cc] : 0;
+        hi_h[t] = cc < nchunks ? chunk_lo[cc + 1] : 0;
+    }
+    {
+        constexpr int kPerLine = QK == RDK_LOGIT_BF16 ? 64 : 32;
+        const int s = min((int)threadIdx.x * kPerLine, n - 1);
+        const float touched = load1<QK>(qr, s);
+        asm volatile("" ::"v"(touched));                            // the load is wanted for its side effect only
+    }
+
+    // ---- step A: one pass over the row, two chunks requested ahead of the one being worked on
     RowChunk b0, b1, b2;
     int c = wid;
     if (c < nchunks) row_fetch(pr, lane_map, chunk_lo, c, N, vec_p, b0);
     if (c + kRowWaves < nchunks) row_fetch(pr, lane_map, chunk_lo, c + kRowWaves, N, vec_p, b1);
-    // the drafter weights: quads beyond n are read at a clamped address and zeroed, so that no load sits behind a branch
-    // (a branch would make every load wait for the one before it)
-    float4 qh[kRowQuads];
-    const bool whole_quads = vec_q && (n & 3) == 0 && n >= 4;   // the same for all lanes
-    if (whole_quads) {
-#pragma unroll
-        for (int k = 0; k < kRowQuads; ++k) {
-            const int s = 4 * ((int)threadIdx.x + kRowThreads * k);
-            qh[k] = load4_full<QK>(qr, min(s, n - 4));
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < kRowQuads; ++k) {
-            const int s = 4 * ((int)threadIdx.x + kRowThreads * k);
-            qh[k] = load4<QK>(qr, min(s, n), n, false, QK == RDK_PROB_F32 ? 0.f : -INFINITY);   // min: no overflow of the index
-        }
-    }
-    if ((int)threadIdx.x < ((n + 3) & ~3) - n) pk[n + threadIdx.x] = 0.f;   // the padding of the last quad
-    // (no barrier here: it would wait for the loads just issued; nothing of the above is read before the barrier behind step A)
-
-    // ---- step A: one pass over the row, two chunks requested ahead of the one being worked on
     float bs = 0.f;                                   // sum of p / (N + p) over the ids that are not kept
 #define RDK_ROW_STEP(CUR, FREE)                                                                              \
     {                                                                                                        \
         if (c + 2 * kRowWaves < nchunks) row_fetch(pr, lane_map, chunk_lo, c + 2 * kRowWaves, N, vec_p, FREE); \
         float sp = 0.f, sa = 0.f;                                                                            \
-        row_scatter<SERIES>(CUR, rcp, pk, spare_idx, sp, sa);                                                \
+        row_scatter<SERIES>(CUR, c, rcp, pk, spare_idx, sp, sa);                                             \
         sp = wave_sum(sp);                                                                                   \
         sa = wave_sum(sa);                                                                                   \
         bs += sa;                                                                                            \
@@ -654,29 +696,50 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
         RDK_ROW_STEP(b2, b1)
     }
 #undef RDK_ROW_STEP
-    __syncthreads();
 
-    // ---- step B: sums over the kept slots, the row constants.  Weights become zero beyond n; the target values are read
-    // at a clamped slot there (finite), so those terms vanish.
-    const int n_pad = (n + 3) & ~3;
-    float zq = 0.f, tn = 0.f, an = 0.f, bk = 0.f;     // bk: sum of p / (N + p) over the kept ids
+    // ---- steps B and C share their loads: group g of sixteen lanes takes the chunks g, g + 64, ...; lane li of the group
+    // the slots lo + 4 li + 64 i .. + 3 of the chunk's run [lo, hi).  The drafter values of the first two rounds of chunks
+    // are asked for here, before the barrier, and stay in registers (as weights, once they have arrived).
+    float4 qh[kHeld][kRowSteps];
 #pragma unroll
-    for (int k = 0; k < kRowQuads; ++k) {
-        const int s = 4 * ((int)threadIdx.x + kRowThreads * k);
-        const float4 w4 = qh[k];
-        const float we[4] = {to_weight<QK>(w4.x, qm, 1.f), to_weight<QK>(w4.y, qm, 1.f), to_weight<QK>(w4.z, qm, 1.f),
-                             to_weight<QK>(w4.w, qm, 1.f)};
-        qh[k] = make_float4(s + 0 < n ? we[0] : 0.f, s + 1 < n ? we[1] : 0.f, s + 2 < n ? we[2] : 0.f, s + 3 < n ? we[3] : 0.f);
-        const float4 pv = *(const float4 *)(pk + min(s, n_pad - 4));
-        const float pe[4] = {pv.x, pv.y, pv.z, pv.w}, qe[4] = {qh[k].x, qh[k].y, qh[k].z, qh[k].w};
+    for (int t = 0; t < kHeld; ++t)
+#pragma unroll
+        for (int i = 0; i < kRowSteps; ++i) qh[t][i] = row_raw_quad<QK>(qr, lo_h[t] + 4 * li + 64 * i, n);
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < kHeld; ++t)
+#pragma unroll
+        for (int i = 0; i < kRowSteps; ++i) qh[t][i] = row_weights_of<QK>(qh[t][i], lo_h[t] + 4 * li + 64 * i, hi_h[t], qm);
+
+    // ---- step B: sums over the kept slots, the row constants.  A quad past the end of its run has zero weights and its
+    // target values are masked, so the quads held in registers are swept without a branch.
+    float zq = 0.f, tn = 0.f, an = 0.f, bk = 0.f;     // bk: sum of p / (N + p) over the kept ids
+    auto sums_of_quad = [&](const float4 w4, const float *run, int s0, int len) {
+        const float4 p4 = *(const float4 *)(run + s0);
+        const float qe[4] = {w4.x, w4.y, w4.z, w4.w}, pr4[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float r = rcp(pe[e]);
+            const float pe = s0 + e < len ? pr4[e] : 0.f;
+            const float r = rcp(pe);
             zq += qe[e];
-            tn = fmaf(qe[e], pe[e], tn);
+            tn = fmaf(qe[e], pe, tn);
             an = fmaf(qe[e], r, an);
-            bk = fmaf(s + e < n ? pe[e] : 0.f, r, bk);   // the clamped reads beyond n must not count
+            bk = fmaf(pe, r, bk);
         }
+    };
+#pragma unroll
+    for (int t = 0; t < kHeld; ++t) {
+        const int cc = grp + kRowGroups * t;
+        const float *run = pk + row_run_start(lo_h[t], min(cc, nchunks - 1));
+#pragma unroll
+        for (int i = 0; i < kRowSteps; ++i) sums_of_quad(qh[t][i], run, 4 * li + 64 * i, hi_h[t] - lo_h[t]);
+        for (int s0 = 4 * li + 64 * kRowSteps; s0 < hi_h[t] - lo_h[t]; s0 += 64)   // runs longer than the registers hold
+            sums_of_quad(row_weights<QK>(qr, lo_h[t] + s0, hi_h[t], n, qm), run, s0, hi_h[t] - lo_h[t]);
+    }
+    for (int cc = grp + kRowGroups * kHeld; cc < nchunks; cc += kRowGroups) {       // more chunks than two rounds of groups
+        const int lo = chunk_lo[cc], hi = chunk_lo[cc + 1];
+        const float *run = pk + row_run_start(lo, cc);
+        for (int s0 = 4 * li; s0 < hi - lo; s0 += 64) sums_of_quad(row_weights<QK>(qr, lo + s0, hi, n, qm), run, s0, hi - lo);
     }
     zq = wave_sum(zq);
     tn = wave_sum(tn);
@@ -699,70 +762,50 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     const float inv_S = inv_mass(tot[2] * inv_zq + theta * tot[3]);
     const float nzs = fN * inv_zq * inv_S, ths = theta * inv_S;
 
-    // ---- step C: q' on the kept slots, summed per chunk.  A slot belongs to chunk cc when it lies in [clo[cc], clo[cc + 1]).
-#pragma unroll
-    for (int k = 0; k < kRowQuads; ++k) {
-        const int r256 = wid + kRowWaves * k;          // this wavefront's row of 256 slots
-        const int s_row = r256 * 256;
-        if (s_row >= n) break;                         // the same for the whole wavefront
-        const int s = s_row + 4 * lane;
-        const float4 pv = *(const float4 *)(pk + min(s, n_pad - 4));
-        const float pe[4] = {pv.x, pv.y, pv.z, pv.w}, qe[4] = {qh[k].x, qh[k].y, qh[k].z, qh[k].w};
-        float vq[4], vr[4], va[4];
+    // ---- step C: q' on the kept slots of each chunk; with the closed form of the not-kept ids, the three block sums
+    float sq, sr, sa;
+    auto terms_of_quad = [&](const float4 w4, const float *run, int s0, int len) {
+        const float4 p4 = *(const float4 *)(run + s0);
+        const float qe[4] = {w4.x, w4.y, w4.z, w4.w}, pr4[4] = {p4.x, p4.y, p4.z, p4.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float v = (nzs * qe[e] + ths * pe[e]) * rcp(pe[e]);
-            vq[e] = v;
-            vr[e] = fmaxf(pe[e] - v, 0.f);
-            va[e] = fminf(pe[e], v);
+            const float pe = s0 + e < len ? pr4[e] : 0.f;
+            const float v = (nzs * qe[e] + ths * pe) * rcp(pe);
+            sq += v;
+            sr += fmaxf(pe - v, 0.f);
+            sa += fminf(pe, v);
         }
-        int cc = c_first[k];
-        int lo_c = __builtin_amdgcn_readfirstlane(clo[cc]);
-        while (cc < nchunks && lo_c < s_row + 256) {
-            const int hi_c = __builtin_amdgcn_readfirstlane(clo[cc + 1]);
-            float sq = 0.f, sr = 0.f, sa = 0.f;
+    };
+    auto write_block_sums = [&](int cc) {
+        // the sixteen lanes of the group hold the chunk: four lane exchanges at register speed
+        sq = row16_sum(sq);
+        sr = row16_sum(sr);
+        sa = row16_sum(sa);
+        if (li == 0 && cc < nchunks) {
+            const float ta = ths * lds[L.blk_a + cc];      // sum of q' (= sum of min(p, q')) over the not-kept ids
+            const int64_t o = row * nchunks + cc;
+            part_q[o] = ta + sq;
+            part_a[o] = ta + sa;
+            part_r[o] = (lds[L.blk_p + cc] - ta) + sr;
+        }
+    };
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool in = s + e >= lo_c && s + e < hi_c;
-                sq += in ? vq[e] : 0.f;
-                sr += in ? vr[e] : 0.f;
-                sa += in ? va[e] : 0.f;
-            }
-            if (hi_c > lo_c) {                         // an empty chunk has nothing to add (the same for the whole wavefront)
-                // sums over each quarter of the wavefront only (register-speed lane exchange); the four quarters, and the
-                // rows of slots that a chunk spans, are added at the end in a fixed order
-                sq = row16_sum(sq);
-                sr = row16_sum(sr);
-                sa = row16_sum(sa);
-                if ((lane & 15) == 0) {
-                    float *dst = lds + L.kp + ((r256 + cc) * 4 + (lane >> 4));
-                    dst[0] = sq;
-                    dst[npairs * 4] = sr;
-                    dst[2 * npairs * 4] = sa;
-                }
-            }
-            ++cc;
-            lo_c = hi_c;
-        }
+    for (int t = 0; t < kHeld; ++t) {
+        const int cc = grp + kRowGroups * t;
+        const float *run = pk + row_run_start(lo_h[t], min(cc, nchunks - 1));
+        sq = sr = sa = 0.f;
+#pragma unroll
+        for (int i = 0; i < kRowSteps; ++i) terms_of_quad(qh[t][i], run, 4 * li + 64 * i, hi_h[t] - lo_h[t]);
+        for (int s0 = 4 * li + 64 * kRowSteps; s0 < hi_h[t] - lo_h[t]; s0 += 64)
+            terms_of_quad(row_weights<QK>(qr, lo_h[t] + s0, hi_h[t], n, qm), run, s0, hi_h[t] - lo_h[t]);
+        write_block_sums(cc);
     }
-    __syncthreads();
-    for (int cc = threadIdx.x; cc < nchunks; cc += kRowThreads) {
-        float sq = 0.f, sr = 0.f, sa = 0.f;
-        // the rows of slots that the run of this chunk touches, first to last (none for a chunk without kept ids)
-        const int lo_c = clo[cc], hi_c = clo[cc + 1];
-        for (int r = lo_c >> 8; hi_c > lo_c && r <= (hi_c - 1) >> 8; ++r) {
-            const float *src = lds + L.kp + (r + cc) * 4;
-            const float4 xq = *(const float4 *)src, xr = *(const float4 *)(src + npairs * 4),
-                         xa = *(const float4 *)(src + 2 * npairs * 4);
-            sq += (xq.x + xq.y) + (xq.z + xq.w);
-            sr += (xr.x + xr.y) + (xr.z + xr.w);
-            sa += (xa.x + xa.y) + (xa.z + xa.w);
-        }
-        const float ta = ths * lds[L.blk_a + cc];      // sum of q' (= sum of min(p, q')) over the not-kept ids
-        const int64_t o = row * nchunks + cc;
-        part_q[o] = ta + sq;
-        part_a[o] = ta + sa;
-        part_r[o] = (lds[L.blk_p + cc] - ta) + sr;
+    for (int cc = grp + kRowGroups * kHeld; cc < nchunks; cc += kRowGroups) {
+        const int lo = chunk_lo[cc], hi = chunk_lo[cc + 1];
+        const float *run = pk + row_run_start(lo, cc);
+        sq = sr = sa = 0.f;
+        for (int s0 = 4 * li; s0 < hi - lo; s0 += 64) terms_of_quad(row_weights<QK>(qr, lo + s0, hi, n, qm), run, s0, hi - lo);
+        write_block_sums(cc);
     }
 }
 
@@ -821,7 +864,7 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
         // values of a row fit the LDS of a compute unit and there are enough positions to fill the chip
         const int nchunks = (h.N + kChunk - 1) / kChunk;
         const size_t lds_bytes = (size_t)row_lds_layout(h.n, nchunks).total * sizeof(float);
-        if (c && !out && h.N >= 2 && B >= kRowMinBatch && h.n <= 4 * kRowThreads * kRowQuads && lds_bytes <= row_lds_limit()) {
+        if (c && !out && h.N >= 2 && B >= kRowMinBatch && lds_bytes <= row_lds_limit()) {
             if (QK != RDK_PROB_F32) {
                 rc = launch_row_stats<QK>(q, h.n, B, 1, w.qstat, st);
                 if (rc != RDK_OK) return rc;
@@ -830,6 +873,7 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
             char *pp = (char *)ws + taylor_workspace_bytes(h, B);
             float *part_q = (float *)pp, *part_r = (float *)(pp + per), *part_a = (float *)(pp + 2 * per);
             const bool vec_p = rows_vectorisable(p.ptr, p.ld, p.kind), vec_q = rows_vectorisable(q.ptr, q.ld, q.kind);
+            if (q.kind != RDK_LOGIT_BF16 && ((uintptr_t)q.ptr % 4 != 0)) return RDK_ERR_ALIGN;
             static bool attr_set = false;     // per instantiation: dynamic LDS above the default limit has to be granted once
             if (!attr_set) {
                 RDK_HIP(hipFuncSetAttribute((const void *)taylor_row_kernel<QK, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -840,12 +884,12 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
             }
             if (h.N >= kRowSeriesMinN) {
                 RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, true>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
-                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.lane_map, h.chunk_lo, h.N, h.n, vec_p,
-                                 vec_q, w.qstat, w.tpart, part_q, part_r, part_a);
+                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.lane_map, h.chunk_lo, h.N, h.n, vec_p, w.qstat, w.tpart,
+                                 part_q, part_r, part_a);
             } else {
                 RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, false>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
-                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.kept_ids, h.lane_map, h.chunk_lo, h.N, h.n, vec_p,
-                                 vec_q, w.qstat, w.tpart, part_q, part_r, part_a);
+                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.lane_map, h.chunk_lo, h.N, h.n, vec_p, w.qstat, w.tpart,
+                                 part_q, part_r, part_a);
             }
             RDK_LAUNCH_CHECK("taylor_row_kernel");
             TaylorArgs a;

@@ -648,6 +648,39 @@ def test_fused_redistribute_verify(rdk, tiny, ragged, case, mode, kinds):
     check_verify_outputs(o3, ref3, p64, ref_qp, seed, offset, w.gamma, p_kind)
 
 
+@pytest.mark.parametrize("shape", [(4102, 1021, 70, 7), (2049, 2049, 64, 8), (1500, 3, 96, 4), (9000, 4401, 130, 5)])
+@pytest.mark.parametrize("q_kind", ["prob", "logit"])
+def test_fused_eq3_single_pass_ragged_shapes(rdk, shape, q_kind):
+    """The fused Eq. 3 call without q' takes one pass over the target rows once the batch has 64 positions (one workgroup
+    per position, kept target values parked on chip).  Shapes that end inside a chunk, inside a quad of slots and inside a
+    16-byte word; every id kept; three kept ids; more than half of the ids kept (slot runs longer than the registers
+    hold); rows at a stride that rules the 16-byte paths out.  Against the oracle, and against the two-pass kernels."""
+    N, n, B, gamma = shape
+    w = synth.scaled(synth.WORKLOADS["tiny"], name="rowshape", N=N, n=n, seqs=B // gamma, gamma=gamma, seed=N + n)
+    data = make_inputs(w)
+    kept = data["kept_ids"]
+    kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.IDENTITY)
+    p64 = data["p"].astype(np.float64)
+    q_in = data["q_hat"] if q_kind == "prob" else data["z_q"]
+    q64 = data["q_hat"].astype(np.float64) if q_kind == "prob" else oracle.probs_from(data["z_q"], "logit")
+    ref_qp = oracle.redistribute_batch("taylor", q64, kept, w.N, p=p64)
+    seed, offset = 515, 11
+    ref = oracle.verify_batch(p64, ref_qp, seed, offset, gamma=gamma)
+    for pad in (0, 3):                       # rows of a wider tensor: stride N + 3 keeps the rows off 16-byte boundaries
+        p_big = torch.full((B, N + pad), float("nan"), dtype=torch.float32, device="cuda")
+        q_big = torch.full((B, n + pad), float("nan"), dtype=torch.float32, device="cuda")
+        p_big[:, :N] = dev(data["p"])
+        q_big[:, :n] = dev(q_in)
+        o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, p_big[:, :N], q_big[:, :n], seed, offset, gamma, "prob", q_kind)
+        check_verify_outputs(o, ref, p64, ref_qp, seed, offset, gamma, "prob", min_exact=0.9)
+        qp = torch.empty((B, N), dtype=torch.float32, device="cuda")
+        o2 = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, p_big[:, :N], q_big[:, :n], seed, offset, gamma, "prob", q_kind,
+                                         q_prime=qp)
+        assert_close(o.alpha.cpu().numpy(), o2.alpha.cpu().numpy(), what="alpha, one pass against two")
+        assert_close(o.resid_mass.cpu().numpy(), o2.resid_mass.cpu().numpy(), what="residual mass, one pass against two")
+        assert (o.draft_ids == o2.draft_ids).float().mean().item() >= 0.95
+
+
 # --------------------------------------------------------------------------------------------- HIP graph capture
 @pytest.mark.parametrize("mode", ["sparse", "taylor"])
 def test_fused_call_replays_from_a_hip_graph(rdk, ragged, mode):
