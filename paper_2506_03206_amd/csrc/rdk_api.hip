@@ -63,7 +63,7 @@ bool kind_ok(rdk_input_kind_t k) { return k == RDK_PROB_F32 || k == RDK_LOGIT_F3
 int32_t nbr_row_len(int32_t k) { return ((k < 1 ? 1 : k) + 15) / 16 * 16; }
 
 struct StorageLayout {
-    size_t kept_ids, slot_of, pruned_ids, chunk_lo, lane_map, body, body2, body3, total;
+    size_t kept_ids, slot_of, pruned_ids, chunk_lo, lane_map, item_lo, row_items, body, body2, body3, total;
     int32_t kk, n_pad, N_pad;
     int64_t ldm;
 };
@@ -108,6 +108,8 @@ StorageLayout layout_of(const rdk_kernel_desc_t &d)
     L.pruned_ids = off; off += align_up((size_t)(d.N - d.n + 1) * 4, 256);
     L.chunk_lo = off; off += align_up((size_t)((d.N + kChunk - 1) / kChunk + 1) * 4, 256);
     L.lane_map = off; off += align_up((size_t)((d.N + kChunk - 1) / kChunk) * kWave * 8, 256);
+    L.item_lo = off; off += align_up((size_t)((d.N + kChunk - 1) / kChunk + 1) * 4, 256);
+    L.row_items = off; off += align_up((size_t)((d.N + kChunk - 1) / kChunk + d.n / 64 + 1) * 8, 256);
     L.kk = nbr_row_len(d.k);
     L.ldm = ((int64_t)d.N + 3) / 4 * 4;
     switch (d.format) {
@@ -233,6 +235,12 @@ rdk_status_t rdk_build_kernel(const rdk_kernel_desc_t *desc, void *storage, size
     uint64_t *lane_map = (uint64_t *)(sp + L.lane_map);
     h.lane_map = lane_map;
     rc = launch_lane_map(slot_of, chunk_lo, d.N, d.n, lane_map, st);
+    if (rc != RDK_OK) return rc;
+    int32_t *item_lo = (int32_t *)(sp + L.item_lo);
+    int2 *row_items = (int2 *)(sp + L.row_items);
+    h.item_lo = item_lo;
+    h.row_items = row_items;
+    rc = launch_row_items(chunk_lo, d.N, item_lo, row_items, st);
     if (rc != RDK_OK) return rc;
 
     if (d.format == RDK_SPARSE_TOPK) {

@@ -139,6 +139,45 @@ __global__ void pruned_ids_kernel(const int32_t *slot_of, int N, int n, int32_t 
     if (u < N - n) pruned_ids[u] = j;   // always true for ascending kept ids; an unchecked list must not write past the table
 }
 
+// The kept slots in pieces of at most 64 that stay inside one chunk (a chunk with m kept ids gives ceil(m / 64) pieces):
+// one workgroup counts the pieces of 1024 chunks at a time, numbers them with a prefix sum and writes them out.
+__global__ __launch_bounds__(1024) void row_items_kernel(const int32_t *chunk_lo, int nchunks, int32_t *item_lo, int2 *row_items)
+{
+    __shared__ int wave_total[1024 / kWave];
+    __shared__ int carry;
+    const int lane = lane_id(), wid = threadIdx.x / kWave;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < nchunks; base += 1024) {
+        const int c = base + threadIdx.x;
+        int lo = 0, hi = 0;
+        if (c < nchunks) {
+            lo = chunk_lo[c];
+            hi = chunk_lo[c + 1];
+        }
+        const int cnt = (hi - lo + 63) / 64;
+        int incl = cnt;
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int o = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += o;
+        }
+        if (lane == kWave - 1) wave_total[wid] = incl;
+        __syncthreads();
+        int before = carry;
+        for (int w = 0; w < wid; ++w) before += wave_total[w];
+        const int first = before + incl - cnt;
+        if (c < nchunks) {
+            item_lo[c] = first;
+            for (int k = 0; k < cnt; ++k)
+                row_items[first + k] = make_int2(lo + 64 * k, c | ((lo & 3) << 22) | (min(64, hi - lo - 64 * k) << 24));
+        }
+        __syncthreads();
+        if (threadIdx.x == 1023) carry = before + incl;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) item_lo[nchunks] = carry;
+}
+
 // Per chunk and lane the kept mask of the lane's 16 ids and the kept ids of the chunk below each of its four groups.
 __global__ void lane_map_kernel(const int32_t *slot_of, const int32_t *chunk_lo, int N, int n, uint64_t *lane_map)
 {
@@ -437,6 +476,14 @@ rdk_status_t launch_features_from_scores(const void *z, rdk_input_kind_t kind, i
         default: return RDK_ERR_DTYPE;
     }
     RDK_LAUNCH_CHECK("features_from_scores_kernel");
+    return RDK_OK;
+}
+
+rdk_status_t launch_row_items(const int32_t *chunk_lo, int32_t N, int32_t *item_lo, int2 *row_items, hipStream_t st)
+{
+    const int nchunks = (N + kChunk - 1) / kChunk;
+    hipLaunchKernelGGL(row_items_kernel, dim3(1), dim3(1024), 0, st, chunk_lo, nchunks, item_lo, row_items);
+    RDK_LAUNCH_CHECK("row_items_kernel");
     return RDK_OK;
 }
 

@@ -23,6 +23,11 @@ struct KernelHandle {
     // 256 i + 4 l + e, i, e = 0..3): bit 4 i + e = the id is kept; bits 16 + 12 i .. 27 + 12 i = kept ids of the chunk
     // below id c * kChunk + 256 i + 4 l.  The slot of a kept id follows from these and chunk_lo[c].
     const uint64_t *lane_map;
+    // The kept slots cut into pieces of at most 64 consecutive slots that never cross a chunk: piece k is
+    // row_items[k] = {first slot, chunk | (first slot of the chunk mod 4) << 22 | length << 24}, pieces ascend with the
+    // slots, and the pieces of chunk c are item_lo[c] .. item_lo[c + 1] - 1 (item_lo has ceil(N / kChunk) + 1 entries).
+    const int32_t *item_lo;
+    const int2 *row_items;
     // sparse: per pruned slot a row of kk (kept slot, weight) pairs, k real ones then (0, 0) padding
     const int32_t *pruned_ids;  // [N-n] ascending target ids that are not kept
     const int2 *nbr;            // [N-n, kk] pairs (kept slot, weight as fp32 bits): one 128-byte line per 16 entries
@@ -96,6 +101,7 @@ rdk_status_t launch_check_kept(const int32_t *kept_ids, int32_t n, int32_t N, in
 rdk_status_t launch_features_from_scores(const void *z, rdk_input_kind_t kind, int64_t ldz, int32_t T, int32_t N, float *F,
                                          int64_t ldf, hipStream_t st);
 rdk_status_t launch_chunk_lo(const int32_t *kept_ids, int32_t n, int32_t N, int32_t *chunk_lo, hipStream_t st);
+rdk_status_t launch_row_items(const int32_t *chunk_lo, int32_t N, int32_t *item_lo, int2 *row_items, hipStream_t st);
 rdk_status_t launch_lane_map(const int32_t *slot_of, const int32_t *chunk_lo, int32_t N, int32_t n, uint64_t *lane_map,
                              hipStream_t st);
 rdk_status_t launch_pruned_ids(const int32_t *slot_of, int32_t N, int32_t n, int32_t *pruned_ids, hipStream_t st);

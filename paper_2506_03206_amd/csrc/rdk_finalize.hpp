@@ -227,188 +227,202 @@ __device__ __forceinline__ int search_block1(float w, int base, double thr_local
 constexpr int kFinalizeRows = 8;   // rows (wavefronts) per workgroup at most: leaves 256 VGPRs per lane
 constexpr int kSpreadMinRows = 128;   // from this many rows on every row gets a workgroup of its own
 
-// BLOCK = ids per block of partial sums: a multiple of 256, or 64 (then only 16 lanes of the wavefront hold ids).
+// The finish of one row by one wavefront: pq, prr, pa = the row's block sums of q', max(0, p - q') and min(p, q').
+// Writes the row's outputs and hands back the drafted id, the residual id and the accept flag (for a scan by the caller).
+// BLOCK = ids per block of partial sums: a multiple of 256, or 64 (then one id per lane).
 template <int KIND, int BLOCK, bool HAS_Q, class QP>
-__global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) void verify_finalize_kernel(FinalizeArgs a, QP qp)
+__device__ __forceinline__ void finalize_row(const FinalizeArgs &a, const QP &qp, int64_t row, const float *pq, const float *prr,
+                                             const float *pa, int32_t &dtok_out, int32_t &rtok_out, uint8_t &acc_out)
 {
     constexpr int SUB = BLOCK >= 256 ? BLOCK / 256 : 1;
     constexpr int kLanes = BLOCK >= 256 ? kWave : BLOCK / 4;      // lanes that hold ids of a block
     constexpr int kRegBlocks = QP::kSpreadRows ? 32 : 8;          // block partials a lane keeps in registers
+    const rdk_verify_desc_t &d = a.d;
+    const int lane = lane_id();
+    const int N = d.N;
+    const void *pr = row_ptr<KIND>(a.p, a.ldp, row);
+    float m = 0.f, inv = 1.f;
+    if (KIND != RDK_PROB_F32) {
+        const SoftStat rs = merged_row_stat<KIND>(a.pstat, a.p_splits, row);
+        m = rs.m;
+        inv = 1.0f / rs.s;
+    }
+    const float pfill = KIND == RDK_PROB_F32 ? 0.f : -INFINITY;
+    const int per_lane = ((a.nblk + kWave - 1) / kWave + 3) & ~3;   // blocks per lane, in whole groups of four
+    const bool draw_draft = HAS_Q && d.sample_draft;
+
+    // 1. block partials (one round trip; kept in registers when they fit), the row's own constants and the
+    //    uniforms meanwhile
+    const bool in_regs = per_lane <= kRegBlocks;
+    float vq[kRegBlocks], vr[kRegBlocks], va[kRegBlocks];
+    double lane_r, lane_q = 0.0, lane_a = 0.0;
+    if (in_regs) {
+        load_partials(prr, a.nblk, per_lane, vr);
+        if (draw_draft) load_partials(pq, a.nblk, per_lane, vq);
+        if (HAS_Q) load_partials(pa, a.nblk, per_lane, va);
+    }
+    const typename QP::Row qrow = qp.row(row);
+    if (in_regs) {
+        lane_r = sum_partials(vr);
+        if (draw_draft) lane_q = sum_partials(vq);
+        if (HAS_Q) lane_a = sum_partials(va);
+    } else {
+        lane_r = lane_partial_sum(prr, a.nblk, per_lane);
+        if (draw_draft) lane_q = lane_partial_sum(pq, a.nblk, per_lane);
+        if (HAS_Q) lane_a = lane_partial_sum(pa, a.nblk, per_lane);
+    }
+    int32_t dtok = (HAS_Q && !d.sample_draft) ? a.draft_ids[row] : -1;
+    uint32_t words[4];
+    position_words(d.seed, d.offset + (uint64_t)row, words);
+    const double R = wave_sum(lane_r);
+    const double Q = draw_draft ? wave_sum(lane_q) : 0.0;
+    const double A = HAS_Q ? wave_sum(lane_a) : 0.0;
+
+    // 2. the blocks that hold the two prefix-sum crossings
+    double thr_d = 0.0, thr_r = 0.0, before_d = 0.0, before_r = 0.0;
+    int blk_d = -1, blk_r = -1;
+    if (draw_draft && Q > 0.0) {
+        thr_d = word_to_unit(words[0]) * Q;
+        blk_d = in_regs ? locate_block_regs(vq, a.nblk, per_lane, lane_q, thr_d, before_d)
+                        : locate_block(pq, a.nblk, per_lane, lane_q, thr_d, before_d);
+    }
+    if (R > 0.0) {
+        thr_r = word_to_unit(words[HAS_Q ? 2 : 3]) * R;
+        blk_r = in_regs ? locate_block_regs(vr, a.nblk, per_lane, lane_r, thr_r, before_r)
+                        : locate_block(prr, a.nblk, per_lane, lane_r, thr_r, before_r);
+    }
+
+    // 3. both blocks are fetched together (q' and the target weights of each), then scanned.  A draft token
+    //    that the caller supplied may lie anywhere: its two values are requested in the same round trip.
+    const int base_d = max(blk_d, 0) * BLOCK, base_r = max(blk_r, 0) * BLOCK;
+    const bool same = draw_draft && blk_r == blk_d;
+    float pd_w = 0.f, qd = 0.f;
+    const bool given = HAS_Q && !d.sample_draft && dtok >= 0 && dtok < N;
+    if (given) {
+        pd_w = to_weight<KIND>(load1<KIND>(pr, dtok), m, inv);
+        qd = qrow.load1(dtok);
+    }
+    const bool want_r = HAS_Q && !same;
+    int32_t rtok = -1;
+    if constexpr (BLOCK == 64) {
+        // blocks of 64 ids, one id per lane: the policy's chain of dependent loads is as short as it gets (one
+        // slot, one table row, its gathers) and all 64 lanes share it
+        typename QP::Row::Pending1 td, tr;
+        const int id_d = base_d + lane, id_r = base_r + lane;
+        if (draw_draft) qrow.template stage1<0>(td, id_d);
+        if (want_r) qrow.template stage1<0>(tr, id_r);
+        float pdv = pfill, wpv = pfill;
+        if (draw_draft && id_d < N) pdv = load1<KIND>(pr, id_d);
+        if (!same && id_r < N) wpv = load1<KIND>(pr, id_r);
+        if (draw_draft) qrow.template stage1<1>(td, id_d);
+        if (want_r) qrow.template stage1<1>(tr, id_r);
+        if (draw_draft) qrow.template stage1<2>(td, id_d);
+        if (want_r) qrow.template stage1<2>(tr, id_r);
+        const float wdv = draw_draft ? qrow.result1(td, id_d) : 0.f;
+        float wqv = want_r ? qrow.result1(tr, id_r) : 0.f;
+        if (same) {
+            wpv = pdv;
+            wqv = wdv;
+        }
+        if (blk_d >= 0) {
+            dtok = search_block1(wdv, base_d, thr_d - before_d);
+            if (dtok >= 0) {
+                qd = lane_value(wdv, dtok - base_d);
+                pd_w = to_weight<KIND>(lane_value(pdv, dtok - base_d), m, inv);
+            }
+        }
+        if (blk_r >= 0) {
+            wpv = to_weight<KIND>(wpv, m, inv);
+            if (HAS_Q) wpv = fmaxf(wpv - wqv, 0.f);
+            rtok = search_block1(wpv, base_r, thr_r - before_r);
+        }
+    } else {
+        float4 wd[SUB], pd[SUB], wp[SUB], wq[SUB];
+        const bool holds = lane < kLanes;
+        typename QP::Row::Pending td[SUB], tr[SUB];
+        const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f), fill4 = make_float4(pfill, pfill, pfill, pfill);
+        stage_block<0, SUB>(qrow, td, base_d, draw_draft && holds);
+        stage_block<0, SUB>(qrow, tr, base_r, want_r && holds);
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+            if (draw_draft) pd[i] = holds ? load4<KIND>(pr, base_d + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
+            if (!same) wp[i] = holds ? load4<KIND>(pr, base_r + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
+        }
+        if (QP::kStages > 1) {
+            stage_block<1, SUB>(qrow, td, base_d, draw_draft && holds);
+            stage_block<1, SUB>(qrow, tr, base_r, want_r && holds);
+        }
+        if (QP::kStages > 2) {
+            stage_block<2, SUB>(qrow, td, base_d, draw_draft && holds);
+            stage_block<2, SUB>(qrow, tr, base_r, want_r && holds);
+        }
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) {
+            if (draw_draft) wd[i] = holds ? qrow.result(td[i], (int64_t)base_d + i * 256 + lane * 4) : zero4;
+            if (want_r) wq[i] = holds ? qrow.result(tr[i], (int64_t)base_r + i * 256 + lane * 4) : zero4;
+            if (same) {
+                wp[i] = pd[i];
+                wq[i] = wd[i];
+            }
+        }
+        if (blk_d >= 0) {
+            dtok = search_block<SUB>(wd, base_d, thr_d - before_d);
+            // 4. the accept test needs p and q' at the draft token: both sit in the registers of one lane
+            if (dtok >= 0) {
+                const int off = dtok - base_d, i = off / 256, src = (off % 256) / 4, e = off % 4;
+                qd = lane_value(pick<SUB>(wd, i, e), src);
+                pd_w = to_weight<KIND>(lane_value(pick<SUB>(pd, i, e), src), m, inv);
+            }
+        }
+        if (blk_r >= 0) {
+#pragma unroll
+            for (int i = 0; i < SUB; ++i) {
+                wp[i].x = to_weight<KIND>(wp[i].x, m, inv);
+                wp[i].y = to_weight<KIND>(wp[i].y, m, inv);
+                wp[i].z = to_weight<KIND>(wp[i].z, m, inv);
+                wp[i].w = to_weight<KIND>(wp[i].w, m, inv);
+                if (HAS_Q) {
+                    wp[i].x = fmaxf(wp[i].x - wq[i].x, 0.f);
+                    wp[i].y = fmaxf(wp[i].y - wq[i].y, 0.f);
+                    wp[i].z = fmaxf(wp[i].z - wq[i].z, 0.f);
+                    wp[i].w = fmaxf(wp[i].w - wq[i].w, 0.f);
+                }
+            }
+            rtok = search_block<SUB>(wp, base_r, thr_r - before_r);
+        }
+    }
+    const bool d_ok = HAS_Q && dtok >= 0 && dtok < N;
+    uint8_t acc = 0;
+    if (d_ok) acc = (word_to_unit(words[1]) * (double)qd < (double)pd_w) ? 1 : 0;
+    if (lane == 0) {
+        if (draw_draft) a.draft_ids[row] = dtok;
+        a.accept[row] = acc;
+        if (a.alpha) a.alpha[row] = (float)A;
+        if (a.resid_mass) a.resid_mass[row] = (float)R;
+        a.resid_ids[row] = rtok;
+    }
+    dtok_out = dtok;
+    rtok_out = rtok;
+    acc_out = acc;
+}
+
+template <int KIND, int BLOCK, bool HAS_Q, class QP>
+__global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) void verify_finalize_kernel(FinalizeArgs a, QP qp)
+{
     __shared__ int32_t sh_draft[kFinalizeRows], sh_resid[kFinalizeRows];
     __shared__ uint8_t sh_acc[kFinalizeRows];
     const rdk_verify_desc_t &d = a.d;
     const int wid = threadIdx.x / kWave, lane = lane_id();
     const int64_t row = (int64_t)blockIdx.x * a.rows_per_block + wid;
-    const int N = d.N;
     if (row < d.B) {
-        const void *pr = row_ptr<KIND>(a.p, a.ldp, row);
-        float m = 0.f, inv = 1.f;
-        if (KIND != RDK_PROB_F32) {
-            const SoftStat rs = merged_row_stat<KIND>(a.pstat, a.p_splits, row);
-            m = rs.m;
-            inv = 1.0f / rs.s;
-        }
-        const float pfill = KIND == RDK_PROB_F32 ? 0.f : -INFINITY;
-        const int per_lane = ((a.nblk + kWave - 1) / kWave + 3) & ~3;   // blocks per lane, in whole groups of four
-        const float *pq = a.part_q + row * a.nblk;
-        const float *prr = a.part_r + row * a.nblk;
-        const float *pa = a.part_a + row * a.nblk;
-        const bool draw_draft = HAS_Q && d.sample_draft;
-
-        // 1. block partials (one round trip; kept in registers when they fit), the row's own constants and the
-        //    uniforms meanwhile
-        const bool in_regs = per_lane <= kRegBlocks;
-        float vq[kRegBlocks], vr[kRegBlocks], va[kRegBlocks];
-        double lane_r, lane_q = 0.0, lane_a = 0.0;
-        if (in_regs) {
-            load_partials(prr, a.nblk, per_lane, vr);
-            if (draw_draft) load_partials(pq, a.nblk, per_lane, vq);
-            if (HAS_Q) load_partials(pa, a.nblk, per_lane, va);
-        }
-        const typename QP::Row qrow = qp.row(row);
-        if (in_regs) {
-            lane_r = sum_partials(vr);
-            if (draw_draft) lane_q = sum_partials(vq);
-            if (HAS_Q) lane_a = sum_partials(va);
-        } else {
-            lane_r = lane_partial_sum(prr, a.nblk, per_lane);
-            if (draw_draft) lane_q = lane_partial_sum(pq, a.nblk, per_lane);
-            if (HAS_Q) lane_a = lane_partial_sum(pa, a.nblk, per_lane);
-        }
-        int32_t dtok = (HAS_Q && !d.sample_draft) ? a.draft_ids[row] : -1;
-        uint32_t words[4];
-        position_words(d.seed, d.offset + (uint64_t)row, words);
-        const double R = wave_sum(lane_r);
-        const double Q = draw_draft ? wave_sum(lane_q) : 0.0;
-        const double A = HAS_Q ? wave_sum(lane_a) : 0.0;
-
-        // 2. the blocks that hold the two prefix-sum crossings
-        double thr_d = 0.0, thr_r = 0.0, before_d = 0.0, before_r = 0.0;
-        int blk_d = -1, blk_r = -1;
-        if (draw_draft && Q > 0.0) {
-            thr_d = word_to_unit(words[0]) * Q;
-            blk_d = in_regs ? locate_block_regs(vq, a.nblk, per_lane, lane_q, thr_d, before_d)
-                            : locate_block(pq, a.nblk, per_lane, lane_q, thr_d, before_d);
-        }
-        if (R > 0.0) {
-            thr_r = word_to_unit(words[HAS_Q ? 2 : 3]) * R;
-            blk_r = in_regs ? locate_block_regs(vr, a.nblk, per_lane, lane_r, thr_r, before_r)
-                            : locate_block(prr, a.nblk, per_lane, lane_r, thr_r, before_r);
-        }
-
-        // 3. both blocks are fetched together (q' and the target weights of each), then scanned.  A draft token
-        //    that the caller supplied may lie anywhere: its two values are requested in the same round trip.
-        const int base_d = max(blk_d, 0) * BLOCK, base_r = max(blk_r, 0) * BLOCK;
-        const bool same = draw_draft && blk_r == blk_d;
-        float pd_w = 0.f, qd = 0.f;
-        const bool given = HAS_Q && !d.sample_draft && dtok >= 0 && dtok < N;
-        if (given) {
-            pd_w = to_weight<KIND>(load1<KIND>(pr, dtok), m, inv);
-            qd = qrow.load1(dtok);
-        }
-        const bool want_r = HAS_Q && !same;
-        int32_t rtok = -1;
-        if constexpr (BLOCK == 64) {
-            // blocks of 64 ids, one id per lane: the policy's chain of dependent loads is as short as it gets (one
-            // slot, one table row, its gathers) and all 64 lanes share it
-            typename QP::Row::Pending1 td, tr;
-            const int id_d = base_d + lane, id_r = base_r + lane;
-            if (draw_draft) qrow.template stage1<0>(td, id_d);
-            if (want_r) qrow.template stage1<0>(tr, id_r);
-            float pdv = pfill, wpv = pfill;
-            if (draw_draft && id_d < N) pdv = load1<KIND>(pr, id_d);
-            if (!same && id_r < N) wpv = load1<KIND>(pr, id_r);
-            if (draw_draft) qrow.template stage1<1>(td, id_d);
-            if (want_r) qrow.template stage1<1>(tr, id_r);
-            if (draw_draft) qrow.template stage1<2>(td, id_d);
-            if (want_r) qrow.template stage1<2>(tr, id_r);
-            const float wdv = draw_draft ? qrow.result1(td, id_d) : 0.f;
-            float wqv = want_r ? qrow.result1(tr, id_r) : 0.f;
-            if (same) {
-                wpv = pdv;
-                wqv = wdv;
-            }
-            if (blk_d >= 0) {
-                dtok = search_block1(wdv, base_d, thr_d - before_d);
-                if (dtok >= 0) {
-                    qd = lane_value(wdv, dtok - base_d);
-                    pd_w = to_weight<KIND>(lane_value(pdv, dtok - base_d), m, inv);
-                }
-            }
-            if (blk_r >= 0) {
-                wpv = to_weight<KIND>(wpv, m, inv);
-                if (HAS_Q) wpv = fmaxf(wpv - wqv, 0.f);
-                rtok = search_block1(wpv, base_r, thr_r - before_r);
-            }
-        } else {
-            float4 wd[SUB], pd[SUB], wp[SUB], wq[SUB];
-            const bool holds = lane < kLanes;
-            typename QP::Row::Pending td[SUB], tr[SUB];
-            const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f), fill4 = make_float4(pfill, pfill, pfill, pfill);
-            stage_block<0, SUB>(qrow, td, base_d, draw_draft && holds);
-            stage_block<0, SUB>(qrow, tr, base_r, want_r && holds);
-#pragma unroll
-            for (int i = 0; i < SUB; ++i) {
-                if (draw_draft) pd[i] = holds ? load4<KIND>(pr, base_d + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
-                if (!same) wp[i] = holds ? load4<KIND>(pr, base_r + i * 256 + lane * 4, N, a.vec_p, pfill) : fill4;
-            }
-            if (QP::kStages > 1) {
-                stage_block<1, SUB>(qrow, td, base_d, draw_draft && holds);
-                stage_block<1, SUB>(qrow, tr, base_r, want_r && holds);
-            }
-            if (QP::kStages > 2) {
-                stage_block<2, SUB>(qrow, td, base_d, draw_draft && holds);
-                stage_block<2, SUB>(qrow, tr, base_r, want_r && holds);
-            }
-#pragma unroll
-            for (int i = 0; i < SUB; ++i) {
-                if (draw_draft) wd[i] = holds ? qrow.result(td[i], (int64_t)base_d + i * 256 + lane * 4) : zero4;
-                if (want_r) wq[i] = holds ? qrow.result(tr[i], (int64_t)base_r + i * 256 + lane * 4) : zero4;
-                if (same) {
-                    wp[i] = pd[i];
-                    wq[i] = wd[i];
-                }
-            }
-            if (blk_d >= 0) {
-                dtok = search_block<SUB>(wd, base_d, thr_d - before_d);
-                // 4. the accept test needs p and q' at the draft token: both sit in the registers of one lane
-                if (dtok >= 0) {
-                    const int off = dtok - base_d, i = off / 256, src = (off % 256) / 4, e = off % 4;
-                    qd = lane_value(pick<SUB>(wd, i, e), src);
-                    pd_w = to_weight<KIND>(lane_value(pick<SUB>(pd, i, e), src), m, inv);
-                }
-            }
-            if (blk_r >= 0) {
-#pragma unroll
-                for (int i = 0; i < SUB; ++i) {
-                    wp[i].x = to_weight<KIND>(wp[i].x, m, inv);
-                    wp[i].y = to_weight<KIND>(wp[i].y, m, inv);
-                    wp[i].z = to_weight<KIND>(wp[i].z, m, inv);
-                    wp[i].w = to_weight<KIND>(wp[i].w, m, inv);
-                    if (HAS_Q) {
-                        wp[i].x = fmaxf(wp[i].x - wq[i].x, 0.f);
-                        wp[i].y = fmaxf(wp[i].y - wq[i].y, 0.f);
-                        wp[i].z = fmaxf(wp[i].z - wq[i].z, 0.f);
-                        wp[i].w = fmaxf(wp[i].w - wq[i].w, 0.f);
-                    }
-                }
-                rtok = search_block<SUB>(wp, base_r, thr_r - before_r);
-            }
-        }
-        const bool d_ok = HAS_Q && dtok >= 0 && dtok < N;
-        uint8_t acc = 0;
-        if (d_ok) acc = (word_to_unit(words[1]) * (double)qd < (double)pd_w) ? 1 : 0;
-        if (lane == 0) {
-            if (draw_draft) a.draft_ids[row] = dtok;
-            a.accept[row] = acc;
-            if (a.alpha) a.alpha[row] = (float)A;
-            if (a.resid_mass) a.resid_mass[row] = (float)R;
-            a.resid_ids[row] = rtok;
-            if (a.scan_here) {
-                sh_draft[wid] = dtok;
-                sh_resid[wid] = rtok;
-                sh_acc[wid] = acc;
-            }
+        int32_t dtok, rtok;
+        uint8_t acc;
+        finalize_row<KIND, BLOCK, HAS_Q, QP>(a, qp, row, a.part_q + row * a.nblk, a.part_r + row * a.nblk, a.part_a + row * a.nblk,
+                                             dtok, rtok, acc);
+        if (a.scan_here && lane == 0) {
+            sh_draft[wid] = dtok;
+            sh_resid[wid] = rtok;
+            sh_acc[wid] = acc;
         }
     }
     if (a.scan_here) {  // the workgroup holds exactly one sequence: steps 4-10 of Alg. 4

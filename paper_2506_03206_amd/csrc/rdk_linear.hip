@@ -490,45 +490,68 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8))) v
 //   * a kept id needs its own p and q^: while the row streams by, the target values of the kept ids are scattered
 //     into LDS, chunk by chunk in slot order (4 n bytes: one value per drafter slot; the run of every chunk starts
 //     on a 16-byte boundary).
-// Step A streams p, guided by the kernel's lane map (L2-resident, shared by all rows).  Steps B and C belong to the kept
-// slots: sixteen lanes own one chunk and sweep its run of slots, the drafter values straight from global memory (they
-// are held in registers from B to C), the target values from LDS.  B sums q^, q^ p, q^ / (N + p) and p / (N + p) for the
-// row constants; C forms q', max(0, p - q') and min(p, q') and, a chunk being the business of one group of lanes, adds
-// them up with four register-speed lane exchanges and writes the three block sums.  HBM traffic: p and q once.
+// Step A streams p, guided by the kernel's lane map (L2-resident, shared by all rows), a wavefront per chunk.  The chunk's
+// run of drafter values is fetched alongside (one contiguous piece of the drafter row); the wavefront reads its own
+// scattered target values back in slot order and adds up q^, q^ p and q^ / (N + p) -- the sums of the row constants cost
+// no pass of their own.  Step C, once the constants are known, forms q', max(0, p - q') and min(p, q') on the kept slots.
+// Its unit of work is a piece of at most 64 slots of one chunk (a table of the kernel), dealt out to groups of sixteen
+// lanes in turn, so that vocabularies whose kept ids crowd into a few chunks keep every lane busy; the drafter values of
+// the pieces are asked for before the constants are known, the sums of a piece take four register-speed lane exchanges,
+// and the pieces of a chunk are added up in their order.  HBM traffic: p and q once.
+// q' of Eq. 3 re-computed from the row constants (the finish step needs the two blocks of the crossings).
+template <int PK, int QK>
+struct QpTaylor {
+    static constexpr bool kSpreadRows = false;
+    static constexpr int kStages = 2;
+    TaylorArgs a;
+    typedef TaylorRow<PK, QK> Row;
+    __device__ __forceinline__ Row row(int64_t b) const { return make_taylor_row<PK, QK>(a, b); }
+};
+
 constexpr int kRowThreads = 1024;
 constexpr int kRowWaves = kRowThreads / kWave;
-constexpr int kRowGroups = kRowThreads / 16;   // groups of sixteen lanes: one chunk each per round of steps B and C
-constexpr int kRowSteps = 5;                   // quads per lane and chunk held in registers: runs of up to 320 kept ids per chunk
+constexpr int kRowGroups = kRowThreads / 16;   // groups of sixteen lanes: one piece of kept slots each per round of step C
+constexpr int kRowHeld = 10;                   // pieces per group whose drafter values are requested ahead of the row constants
 
 struct RowLds {      // offsets in floats into the dynamic LDS block
-    int pk, spare, blk_p, blk_a, red, total;
+    int pk, spare, blk_p, blk_a, red, items, isum, sum_q, sum_r, sum_a, fin, total;
 };
 
 // Where the run of chunk c (first slot lo) starts in the LDS array of kept target values: a multiple of four floats, and
 // far enough from the run before it (align down costs at most 3, the 4 c make up for it).
 __host__ __device__ inline int row_run_start(int lo, int c) { return (lo & ~3) + 4 * c; }
 
+// Upper bound on the number of pieces (the size of the kernel's table): one per chunk and one per 64 slots.
+__host__ __device__ inline int row_max_items(int n, int nchunks) { return nchunks + n / 64 + 1; }
+
 __host__ __device__ inline RowLds row_lds_layout(int n, int nchunks)
 {
     RowLds L;
     int off = 0;
-    // target values of the kept ids: runs of slots, one per chunk, and room for the quads that steps B and C read past the
-    // end of the last runs (their values are masked)
-    L.pk = off; off += ((n + 3) & ~3) + 4 * nchunks + 64 * kRowSteps + 4;
+    // target values of the kept ids: runs of slots, one per chunk, and room for the quads that a piece reads past its end
+    // (their values are masked)
+    L.pk = off; off += ((n + 3) & ~3) + 4 * nchunks + 64 + 4;
     L.spare = off; off += kWave;                       // where the lanes send the values of ids that are not kept
     L.blk_p = off; off += (nchunks + 3) & ~3;          // per chunk: sum of p over the not-kept ids
     L.blk_a = off; off += (nchunks + 3) & ~3;          //            sum of p / (N + p) over the not-kept ids
     L.red = off; off += kRowWaves * 4;
+    const int mi = (row_max_items(n, nchunks) + 1) & ~1;
+    L.items = off; off += 2 * mi;                      // the kernel's table of pieces
+    L.isum = off; off += 4 * mi;                       // per piece: sums of q', max(0, p - q'), min(p, q')
+    L.sum_q = off; off += (nchunks + 3) & ~3;          // per chunk: the three block sums the finish step draws from
+    L.sum_r = off; off += (nchunks + 3) & ~3;
+    L.sum_a = off; off += (nchunks + 3) & ~3;
+    L.fin = off; off += 64;                            // what the wavefronts of the finish step hand to each other
     L.total = off;
     return L;
 }
 
 // One chunk of target values (16 ids per lane, the layout of load_chunk), the lane's record of the kernel's lane map
-// for that chunk, and the chunk's first slot.
+// for that chunk, and the chunk's run of slots [lo, hi).
 struct RowChunk {
     float4 p[4];
     uint64_t map;
-    int lo;
+    int lo, hi;
 };
 
 __device__ __forceinline__ void row_fetch(const float *pr, const uint64_t *lane_map, const int32_t *chunk_lo, int c, int N,
@@ -537,6 +560,7 @@ __device__ __forceinline__ void row_fetch(const float *pr, const uint64_t *lane_
     load_chunk<RDK_PROB_F32>(pr, (int64_t)c * kChunk, N, vec_p, 0.f, b.p);
     b.map = lane_map[(int64_t)c * kWave + lane_id()];
     b.lo = chunk_lo[c];
+    b.hi = chunk_lo[c + 1];
 }
 
 // 1 / (N + p) for 0 <= p <= 1.  For a large vocabulary the first two terms of the series in p / N are exact to fp32
@@ -551,14 +575,14 @@ struct RowRcp {
     }
 };
 
-// Step A for one chunk c: target values of kept ids go to their slots in LDS (the others to a spare word of the lane),
-// the not-kept ones are summed.
+// Step A for one chunk c: target values of kept ids go to their slots in LDS (the others to a spare word of the lane);
+// sp, sa: sums of p and of p / (N + p) over the ids that are not kept; sall: p / (N + p) over all of them.
 template <bool SERIES>
-__device__ __forceinline__ void row_scatter(const RowChunk &b, int c, const RowRcp<SERIES> &rcp, float *pk, int spare_idx,
-                                            float &sp, float &sa)
+__device__ __forceinline__ void row_scatter(const RowChunk &b, int c, int lo, const RowRcp<SERIES> &rcp, float *pk, int spare_idx,
+                                            float &sp, float &sa, float &sall)
 {
     const uint32_t mask = (uint32_t)b.map & 0xFFFFu;
-    const int run = row_run_start(b.lo, c);                       // where the chunk's first slot sits in LDS
+    const int run = row_run_start(lo, c);                         // where the chunk's first slot sits in LDS
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int idx = run + (int)((b.map >> (16 + 12 * i)) & 0xFFFu);   // slot of the lane's first kept id of this group
@@ -566,48 +590,47 @@ __device__ __forceinline__ void row_scatter(const RowChunk &b, int c, const RowR
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const bool is_kept = (mask >> (4 * i + e)) & 1u;
-            const float r = rcp(pe[e]);
+            const float t = pe[e] * rcp(pe[e]);
             pk[is_kept ? idx : spare_idx] = pe[e];
             idx += is_kept ? 1 : 0;
-            const float pn = is_kept ? 0.f : pe[e];
-            sp += pn;
-            sa = fmaf(pn, r, sa);
+            sp += is_kept ? 0.f : pe[e];
+            sa += is_kept ? 0.f : t;
+            sall += t;
         }
     }
 }
 
-// The raw drafter values of four consecutive slots from s on (unspecified at slots beyond the row: the caller masks by its
-// own bound).  One 16-byte load when the quad lies inside the row -- four bytes of alignment are all a global load of
-// that size needs -- and single loads for the quad that crosses the end of the row.  Every load writes the one result
-// under a one-sided branch, so a sequence of calls issues its loads back to back (loads merged from two code paths would
-// each be waited for at the merge).
+// The raw drafter values of four consecutive slots from s on (zero at slots from `end` on; end <= n).  One 16-byte load
+// when the quad lies below `end` -- four bytes of alignment are all a global load of that size needs -- and single
+// loads for the quad that crosses it.  Every load writes the one result under a one-sided branch, so a sequence of calls
+// issues its loads back to back (loads merged from two code paths would each be waited for at the merge).
 template <int QK>
-__device__ __forceinline__ float4 row_raw_quad(const void *qr, int s, int n)
+__device__ __forceinline__ float4 row_raw_quad(const void *qr, int s, int end)
 {
     float4 raw = make_float4(0.f, 0.f, 0.f, 0.f);
     if (QK == RDK_LOGIT_BF16) {
         const uint16_t *r = (const uint16_t *)qr;
-        if (s + 3 < n) {
+        if (s + 3 < end) {
             typedef unsigned short u16x4a __attribute__((ext_vector_type(4), aligned(2)));
             const u16x4a v = *(const u16x4a *)(r + s);
             raw = make_float4(bf16_to_f32(v.x), bf16_to_f32(v.y), bf16_to_f32(v.z), bf16_to_f32(v.w));
         }
-        if (s < n && s + 3 >= n) {
+        if (s < end && s + 3 >= end) {
             raw.x = bf16_to_f32(r[s]);
-            if (s + 1 < n) raw.y = bf16_to_f32(r[s + 1]);
-            if (s + 2 < n) raw.z = bf16_to_f32(r[s + 2]);
+            if (s + 1 < end) raw.y = bf16_to_f32(r[s + 1]);
+            if (s + 2 < end) raw.z = bf16_to_f32(r[s + 2]);
         }
     } else {
         const float *r = (const float *)qr;
-        if (s + 3 < n) {
+        if (s + 3 < end) {
             typedef float f32x4a __attribute__((ext_vector_type(4), aligned(4)));
             const f32x4a v = *(const f32x4a *)(r + s);
             raw = make_float4(v.x, v.y, v.z, v.w);
         }
-        if (s < n && s + 3 >= n) {
+        if (s < end && s + 3 >= end) {
             raw.x = r[s];
-            if (s + 1 < n) raw.y = r[s + 1];
-            if (s + 2 < n) raw.z = r[s + 2];
+            if (s + 1 < end) raw.y = r[s + 1];
+            if (s + 2 < end) raw.z = r[s + 2];
         }
     }
     return raw;
@@ -621,22 +644,53 @@ __device__ __forceinline__ float4 row_weights_of(const float4 raw, int s, int en
                        s + 2 < end ? to_weight<QK>(raw.z, qm, 1.f) : 0.f, s + 3 < end ? to_weight<QK>(raw.w, qm, 1.f) : 0.f);
 }
 
+// The drafter values of a chunk's run of slots [lo, hi): lane l takes the quads lo + 4 l + 256 i (a run has at most
+// 1024 slots).
 template <int QK>
-__device__ __forceinline__ float4 row_weights(const void *qr, int s, int end, int n, float qm)
+__device__ __forceinline__ void row_q_fetch(const void *qr, int lo, int hi, float4 (&qv)[4])
 {
-    return row_weights_of<QK>(row_raw_quad<QK>(qr, s, n), s, end, qm);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) qv[i] = row_raw_quad<QK>(qr, lo + 4 * (lane_id() + 64 * i), hi);
+}
+
+// Sums over the kept ids of chunk c, in slot order: the wavefront reads back the target values it has just scattered.
+// A lane past the end of the run reads the run's first quad instead (its drafter weights are zero); the quad that crosses
+// the end reads what follows the run, which is zero or a target value of the next run.
+template <int QK, bool SERIES>
+__device__ __forceinline__ void row_kept_sums(int c, int lo, int hi, const float4 (&qv)[4], const float *pk,
+                                              const RowRcp<SERIES> &rcp, float qm, float &zq, float &tn, float &an)
+{
+    const float *run = pk + row_run_start(lo, c);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (lo + 256 * i < hi) {
+            const int o = 4 * (lane_id() + 64 * i);
+            const float4 p4 = *(const float4 *)(run + (lo + o < hi ? o : 0));
+            const float4 w4 = row_weights_of<QK>(qv[i], lo + o, hi, qm);
+            const float qe[4] = {w4.x, w4.y, w4.z, w4.w}, pe[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                zq += qe[e];
+                tn = fmaf(qe[e], pe[e], tn);
+                an = fmaf(qe[e], rcp(pe[e]), an);
+            }
+        }
+    }
 }
 
 template <int QK, bool SERIES>
 __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p, int64_t ldp, const void *q, int64_t ldq,
-                                                                 const uint64_t *lane_map, const int32_t *chunk_lo, int N, int n,
-                                                                 bool vec_p, const SoftStat *qstat, float *tpart, float *part_q,
-                                                                 float *part_r, float *part_a)
+                                                                 const uint64_t *lane_map, const int32_t *chunk_lo,
+                                                                 const int32_t *item_lo, const int2 *row_items, int N, int n,
+                                                                 bool vec_p, const SoftStat *qstat, const int32_t *slot_of,
+                                                                 FinalizeArgs fin)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int nchunks = (N + kChunk - 1) / kChunk;
     const RowLds L = row_lds_layout(n, nchunks);
     float *pk = lds + L.pk;
+    int2 *il = (int2 *)(lds + L.items);
+    float4 *isum = (float4 *)(lds + L.isum);
     const int64_t row = blockIdx.x;
     const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
     const float *pr = p + row * ldp;
@@ -649,103 +703,82 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     rcp.invN2 = rcp.invN * rcp.invN;
     const int spare_idx = (L.spare - L.pk) + lane;    // relative to pk
 
-    // ---- what steps B and C need first: the slot runs of this lane's chunks (group g of sixteen lanes takes the chunks
-    // g, g + 64, ...), asked for now so that nothing waits for them later, and one value of every 128-byte line of the
-    // drafter row, which brings the row into L2 while the target row streams
-    const int grp = threadIdx.x >> 4, li = threadIdx.x & 15;
-    constexpr int kHeld = 2;                                        // rounds of chunks whose drafter values stay in registers
-    int lo_h[kHeld], hi_h[kHeld];
-#pragma unroll
-    for (int t = 0; t < kHeld; ++t) {
-        const int cc = grp + kRowGroups * t;
-        lo_h[t] = cc < nchunks ? chunk_lo[cc] : 0;
-        hi_h[t] = cc < nchunks ? chunk_lo[cc + 1] : 0;
-    }
-    {
-        constexpr int kPerLine = QK == RDK_LOGIT_BF16 ? 64 : 32;
-        const int s = min((int)threadIdx.x * kPerLine, n - 1);
-        const float touched = load1<QK>(qr, s);
-        asm volatile("" ::"v"(touched));                            // the load is wanted for its side effect only
-    }
-
-    // ---- step A: one pass over the row, two chunks requested ahead of the one being worked on
+    // ---- the kernel's table of pieces goes to LDS (entries past the last piece are never used), the array of kept target
+    // values starts at zero, and the first two chunks of every wavefront are on their way meanwhile
+    const int max_items = row_max_items(n, nchunks);
+    const int nitems = item_lo[nchunks];
+    int2 it0 = make_int2(0, 0);
+    if ((int)threadIdx.x < max_items) it0 = row_items[threadIdx.x];
     RowChunk b0, b1, b2;
     int c = wid;
     if (c < nchunks) row_fetch(pr, lane_map, chunk_lo, c, N, vec_p, b0);
     if (c + kRowWaves < nchunks) row_fetch(pr, lane_map, chunk_lo, c + kRowWaves, N, vec_p, b1);
-    float bs = 0.f;                                   // sum of p / (N + p) over the ids that are not kept
-#define RDK_ROW_STEP(CUR, FREE)                                                                              \
+    if (threadIdx.x == 0) {                           // the position's four uniforms (Alg. 4: draft, accept, residual, bonus)
+        uint32_t words[4];
+        position_words(fin.d.seed, fin.d.offset + (uint64_t)row, words);
+        uint32_t *fw = (uint32_t *)(lds + L.fin + 26);
+        fw[0] = words[0]; fw[1] = words[1]; fw[2] = words[2]; fw[3] = words[3];
+    }
+    {
+        float4 *z = (float4 *)pk;
+        const int quads = (L.spare - L.pk) / 4;
+        for (int i = threadIdx.x; i < quads; i += kRowThreads) z[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if ((int)threadIdx.x < max_items) il[threadIdx.x] = it0;
+        for (int k = threadIdx.x + kRowThreads; k < max_items; k += kRowThreads) il[k] = row_items[k];
+    }
+    __syncthreads();
+
+    // ---- step A: one pass over the row, two chunks requested ahead of the one being worked on; the drafter values of a
+    // chunk's run are requested one chunk ahead, into the registers the sums of this chunk have just freed
+    float zq = 0.f, tn = 0.f, an = 0.f, ball = 0.f;   // ball: sum of p / (N + p) over all ids
+    float4 qv[4];
+    if (c < nchunks) row_q_fetch<QK>(qr, b0.lo, b0.hi, qv);
+#define RDK_ROW_STEP(CUR, NEXT, FREE)                                                                        \
     {                                                                                                        \
         if (c + 2 * kRowWaves < nchunks) row_fetch(pr, lane_map, chunk_lo, c + 2 * kRowWaves, N, vec_p, FREE); \
+        const int lo_c = __builtin_amdgcn_readfirstlane(CUR.lo), hi_c = __builtin_amdgcn_readfirstlane(CUR.hi); \
         float sp = 0.f, sa = 0.f;                                                                            \
-        row_scatter<SERIES>(CUR, c, rcp, pk, spare_idx, sp, sa);                                             \
+        row_scatter<SERIES>(CUR, c, lo_c, rcp, pk, spare_idx, sp, sa, ball);                                 \
         sp = wave_sum(sp);                                                                                   \
         sa = wave_sum(sa);                                                                                   \
-        bs += sa;                                                                                            \
         if (lane == 0) {                                                                                     \
             lds[L.blk_p + c] = sp;                                                                           \
             lds[L.blk_a + c] = sa;                                                                           \
         }                                                                                                    \
+        row_kept_sums<QK, SERIES>(c, lo_c, hi_c, qv, pk, rcp, qm, zq, tn, an);                               \
+        if (c + kRowWaves < nchunks)                                                                         \
+            row_q_fetch<QK>(qr, __builtin_amdgcn_readfirstlane(NEXT.lo), __builtin_amdgcn_readfirstlane(NEXT.hi), qv); \
         c += kRowWaves;                                                                                      \
     }
     while (c < nchunks) {
-        RDK_ROW_STEP(b0, b2)
+        RDK_ROW_STEP(b0, b1, b2)
         if (c >= nchunks) break;
-        RDK_ROW_STEP(b1, b0)
+        RDK_ROW_STEP(b1, b2, b0)
         if (c >= nchunks) break;
-        RDK_ROW_STEP(b2, b1)
+        RDK_ROW_STEP(b2, b0, b1)
     }
 #undef RDK_ROW_STEP
-
-    // ---- steps B and C share their loads: group g of sixteen lanes takes the chunks g, g + 64, ...; lane li of the group
-    // the slots lo + 4 li + 64 i .. + 3 of the chunk's run [lo, hi).  The drafter values of the first two rounds of chunks
-    // are asked for here, before the barrier, and stay in registers (as weights, once they have arrived).
-    float4 qh[kHeld][kRowSteps];
-#pragma unroll
-    for (int t = 0; t < kHeld; ++t)
-#pragma unroll
-        for (int i = 0; i < kRowSteps; ++i) qh[t][i] = row_raw_quad<QK>(qr, lo_h[t] + 4 * li + 64 * i, n);
-    __syncthreads();
-#pragma unroll
-    for (int t = 0; t < kHeld; ++t)
-#pragma unroll
-        for (int i = 0; i < kRowSteps; ++i) qh[t][i] = row_weights_of<QK>(qh[t][i], lo_h[t] + 4 * li + 64 * i, hi_h[t], qm);
-
-    // ---- step B: sums over the kept slots, the row constants.  A quad past the end of its run has zero weights and its
-    // target values are masked, so the quads held in registers are swept without a branch.
-    float zq = 0.f, tn = 0.f, an = 0.f, bk = 0.f;     // bk: sum of p / (N + p) over the kept ids
-    auto sums_of_quad = [&](const float4 w4, const float *run, int s0, int len) {
-        const float4 p4 = *(const float4 *)(run + s0);
-        const float qe[4] = {w4.x, w4.y, w4.z, w4.w}, pr4[4] = {p4.x, p4.y, p4.z, p4.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float pe = s0 + e < len ? pr4[e] : 0.f;
-            const float r = rcp(pe);
-            zq += qe[e];
-            tn = fmaf(qe[e], pe, tn);
-            an = fmaf(qe[e], r, an);
-            bk = fmaf(pe, r, bk);
-        }
-    };
-#pragma unroll
-    for (int t = 0; t < kHeld; ++t) {
-        const int cc = grp + kRowGroups * t;
-        const float *run = pk + row_run_start(lo_h[t], min(cc, nchunks - 1));
-#pragma unroll
-        for (int i = 0; i < kRowSteps; ++i) sums_of_quad(qh[t][i], run, 4 * li + 64 * i, hi_h[t] - lo_h[t]);
-        for (int s0 = 4 * li + 64 * kRowSteps; s0 < hi_h[t] - lo_h[t]; s0 += 64)   // runs longer than the registers hold
-            sums_of_quad(row_weights<QK>(qr, lo_h[t] + s0, hi_h[t], n, qm), run, s0, hi_h[t] - lo_h[t]);
-    }
-    for (int cc = grp + kRowGroups * kHeld; cc < nchunks; cc += kRowGroups) {       // more chunks than two rounds of groups
-        const int lo = chunk_lo[cc], hi = chunk_lo[cc + 1];
-        const float *run = pk + row_run_start(lo, cc);
-        for (int s0 = 4 * li; s0 < hi - lo; s0 += 64) sums_of_quad(row_weights<QK>(qr, lo + s0, hi, n, qm), run, s0, hi - lo);
-    }
     zq = wave_sum(zq);
     tn = wave_sum(tn);
     an = wave_sum(an) * fN;
-    bk = wave_sum(bk);
-    if (lane == 0) *(float4 *)(lds + L.red + wid * 4) = make_float4(zq, tn, an, bs + bk);
+    ball = wave_sum(ball);
+    if (lane == 0) *(float4 *)(lds + L.red + wid * 4) = make_float4(zq, tn, an, ball);
+
+    // ---- step C works on pieces: group g of sixteen lanes takes the pieces g, g + 64, ...; lane li of the group the slots
+    // 4 li .. 4 li + 3 of the piece.  The drafter values of the first rounds are asked for here, before the barrier.
+    const int grp = threadIdx.x >> 4, li = threadIdx.x & 15;
+    float4 qh[kRowHeld];
+#pragma unroll
+    for (int t = 0; t < kRowHeld; ++t) {
+        const int k = grp + kRowGroups * t;
+        const int2 it = k < nitems ? il[k] : make_int2(0, 0);
+        qh[t] = row_raw_quad<QK>(qr, it.x + 4 * li, it.x + (int)((uint32_t)it.y >> 24));
+    }
+    int k0 = 0, k1 = 0;                               // the pieces of the chunk whose block sums this thread will write
+    if ((int)threadIdx.x < nchunks) {
+        k0 = item_lo[threadIdx.x];
+        k1 = item_lo[threadIdx.x + 1];
+    }
     __syncthreads();
     float tot[4];
     {
@@ -755,57 +788,208 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
             t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w;
         }
         tot[0] = t.x; tot[1] = t.y; tot[2] = t.z; tot[3] = t.w;
-        if (threadIdx.x == 0) *(float4 *)(tpart + row * 4) = t;   // the finish step forms the same constants from these
     }
     const float inv_zq = inv_mass(tot[0]);
     const float theta = tot[1] * inv_zq;
     const float inv_S = inv_mass(tot[2] * inv_zq + theta * tot[3]);
     const float nzs = fN * inv_zq * inv_S, ths = theta * inv_S;
 
-    // ---- step C: q' on the kept slots of each chunk; with the closed form of the not-kept ids, the three block sums
-    float sq, sr, sa;
-    auto terms_of_quad = [&](const float4 w4, const float *run, int s0, int len) {
-        const float4 p4 = *(const float4 *)(run + s0);
+    // ---- step C: q' on the kept slots, piece by piece
+    auto piece_sums = [&](int k, const float4 raw) {
+        const int2 it = il[k];
+        const int len = (int)((uint32_t)it.y >> 24), cnk = it.y & 0x3FFFFF, lo3 = (it.y >> 22) & 3;
+        const float4 w4 = row_weights_of<QK>(raw, 4 * li, len, qm);
+        const float4 p4 = *(const float4 *)(pk + (it.x - lo3 + 4 * cnk + 4 * li));
         const float qe[4] = {w4.x, w4.y, w4.z, w4.w}, pr4[4] = {p4.x, p4.y, p4.z, p4.w};
+        float sq = 0.f, sr = 0.f, sa = 0.f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float pe = s0 + e < len ? pr4[e] : 0.f;
+            const float pe = 4 * li + e < len ? pr4[e] : 0.f;
             const float v = (nzs * qe[e] + ths * pe) * rcp(pe);
+            const float m = fminf(pe, v);
             sq += v;
-            sr += fmaxf(pe - v, 0.f);
-            sa += fminf(pe, v);
+            sa += m;
+            sr += pe - m;
         }
-    };
-    auto write_block_sums = [&](int cc) {
-        // the sixteen lanes of the group hold the chunk: four lane exchanges at register speed
+        // the sixteen lanes of the group hold the piece: four lane exchanges at register speed
         sq = row16_sum(sq);
         sr = row16_sum(sr);
         sa = row16_sum(sa);
-        if (li == 0 && cc < nchunks) {
-            const float ta = ths * lds[L.blk_a + cc];      // sum of q' (= sum of min(p, q')) over the not-kept ids
-            const int64_t o = row * nchunks + cc;
-            part_q[o] = ta + sq;
-            part_a[o] = ta + sa;
-            part_r[o] = (lds[L.blk_p + cc] - ta) + sr;
-        }
+        if (li == 0) isum[k] = make_float4(sq, sr, sa, 0.f);
     };
 #pragma unroll
-    for (int t = 0; t < kHeld; ++t) {
-        const int cc = grp + kRowGroups * t;
-        const float *run = pk + row_run_start(lo_h[t], min(cc, nchunks - 1));
-        sq = sr = sa = 0.f;
-#pragma unroll
-        for (int i = 0; i < kRowSteps; ++i) terms_of_quad(qh[t][i], run, 4 * li + 64 * i, hi_h[t] - lo_h[t]);
-        for (int s0 = 4 * li + 64 * kRowSteps; s0 < hi_h[t] - lo_h[t]; s0 += 64)
-            terms_of_quad(row_weights<QK>(qr, lo_h[t] + s0, hi_h[t], n, qm), run, s0, hi_h[t] - lo_h[t]);
-        write_block_sums(cc);
+    for (int t = 0; t < kRowHeld; ++t) {
+        const int k = grp + kRowGroups * t;
+        if (k < nitems) piece_sums(k, qh[t]);
     }
-    for (int cc = grp + kRowGroups * kHeld; cc < nchunks; cc += kRowGroups) {
-        const int lo = chunk_lo[cc], hi = chunk_lo[cc + 1];
-        const float *run = pk + row_run_start(lo, cc);
-        sq = sr = sa = 0.f;
-        for (int s0 = 4 * li; s0 < hi - lo; s0 += 64) terms_of_quad(row_weights<QK>(qr, lo + s0, hi, n, qm), run, s0, hi - lo);
-        write_block_sums(cc);
+    for (int k = grp + kRowGroups * kRowHeld; k < nitems; k += kRowGroups) {   // more pieces than the registers were given
+        const int2 it = il[k];
+        piece_sums(k, row_raw_quad<QK>(qr, it.x + 4 * li, it.x + (int)((uint32_t)it.y >> 24)));
+    }
+    __syncthreads();
+
+    // ---- the block sums of a chunk: its pieces in order, and the closed form of the not-kept ids
+    for (int cc = threadIdx.x; cc < nchunks; cc += kRowThreads) {
+        if (cc >= kRowThreads) {
+            k0 = item_lo[cc];
+            k1 = item_lo[cc + 1];
+        }
+        float sq = 0.f, sr = 0.f, sa = 0.f;
+        for (int k = k0; k < k1; ++k) {
+            const float4 f = isum[k];
+            sq += f.x;
+            sr += f.y;
+            sa += f.z;
+        }
+        const float ta = ths * lds[L.blk_a + cc];      // sum of q' (= sum of min(p, q')) over the not-kept ids
+        lds[L.sum_q + cc] = ta + sq;
+        lds[L.sum_a + cc] = ta + sa;
+        lds[L.sum_r + cc] = (lds[L.blk_p + cc] - ta) + sr;
+    }
+    __syncthreads();
+
+    // ---- the finish of the row (Alg. 4, steps 2 and 4-6 for this position), spread over the wavefronts:
+    //   1. three wavefronts add up one kind of block sum each in fp64 (sum q', residual mass, alpha) and find the chunk
+    //      in which the inverse-CDF threshold of the draft / of the residual draw is crossed;
+    //   2. eight wavefronts re-compute a quarter of one of the two chunks each (256 ids, four per lane: the target values
+    //      once more from memory, the drafter values of the kept ids through the lane map) and scan it in fp64;
+    //   3. with the totals of the quarters before its own, each finds the crossing in its quarter (or its last id with
+    //      a positive weight, the answer when rounding leaves no crossing);
+    //   4. the first wavefront picks the first crossing, tests acceptance in fp64 and writes the row's outputs.
+    // The arithmetic, its order and the conventions are those of the stand-alone finish step (search_block).
+    double *fd = (double *)(lds + L.fin);             // [0..1] local thresholds, [2] alpha, [3] residual mass, [4..11] quarter totals
+    int *fi = (int *)(lds + L.fin + 24);              // [0..1] the two chunks (-1: nothing to draw), [2..5] the uniforms
+    float4 *fc = (float4 *)(lds + L.fin + 32);        // per quarter: crossing id, last positive id, q' and p at the candidate
+    const rdk_verify_desc_t &d = fin.d;
+    const bool draw_draft = d.sample_draft;
+    if (wid < 3) {
+        const float *part = lds + (wid == 0 ? L.sum_q : wid == 1 ? L.sum_r : L.sum_a);
+        const bool wanted = wid == 0 ? draw_draft : true;
+        constexpr int kRegBlocks = 8;
+        const int per_lane = ((nchunks + kWave - 1) / kWave + 3) & ~3;
+        const bool in_regs = per_lane <= kRegBlocks;
+        float v[kRegBlocks];
+        double lane_s = 0.0;
+        if (wanted) {
+            if (in_regs) {
+                load_partials(part, nchunks, per_lane, v);
+                lane_s = sum_partials(v);
+            } else {
+                lane_s = lane_partial_sum(part, nchunks, per_lane);
+            }
+        }
+        const double T = wanted ? wave_sum(lane_s) : 0.0;
+        int blk = -1;
+        double thr = 0.0, before = 0.0;
+        if (wid < 2 && wanted && T > 0.0) {
+            thr = word_to_unit((uint32_t)fi[2 + (wid == 0 ? 0 : 2)]) * T;
+            blk = in_regs ? locate_block_regs(v, nchunks, per_lane, lane_s, thr, before)
+                          : locate_block(part, nchunks, per_lane, lane_s, thr, before);
+        }
+        if (lane == 0) {
+            if (wid < 2) {
+                fi[wid] = blk;
+                fd[wid] = thr - before;
+            }
+            if (wid >= 1) fd[4 - wid] = T;            // wavefront 1: residual mass -> [3], wavefront 2: alpha -> [2]
+        }
+    }
+    __syncthreads();
+    auto value = [&](float qh, float pe) { return (nzs * qh + ths * pe) * __builtin_amdgcn_rcpf(fN + pe); };   // Eq. 3 for one id
+    const int fb = wid >> 2, fq = wid & 3;            // which of the two chunks, which quarter of it
+    const int fblk = wid < 8 ? fi[fb] : -1;
+    const bool factive = fblk >= 0;
+    const int64_t fidx = (int64_t)max(fblk, 0) * kChunk + fq * 256 + lane * 4;
+    float qp4[4] = {0.f, 0.f, 0.f, 0.f}, pv4[4] = {0.f, 0.f, 0.f, 0.f}, wv4[4] = {0.f, 0.f, 0.f, 0.f};
+    double l0 = 0.0, l1 = 0.0, l2 = 0.0, l3 = 0.0, incl = 0.0;
+    int last_pos = -1;
+    if (factive) {
+        const uint64_t map = lane_map[(int64_t)fblk * kWave + lane];
+        const int lo = chunk_lo[fblk];
+        const float4 pl = load4<RDK_PROB_F32>(pr, fidx, N, vec_p, 0.f);
+        const uint32_t kb = (uint32_t)(map >> (4 * fq)) & 0xFu;
+        int sl = lo + (int)((map >> (16 + 12 * fq)) & 0xFFFu);
+        float qraw[4];
+        bool kept_e[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            kept_e[e] = (kb >> e) & 1u;
+            qraw[e] = load1<QK>(qr, kept_e[e] ? sl : 0);   // unconditional: the loads stay batched
+            sl += kept_e[e] ? 1 : 0;
+        }
+        pv4[0] = pl.x; pv4[1] = pl.y; pv4[2] = pl.z; pv4[3] = pl.w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float qh = kept_e[e] ? to_weight<QK>(qraw[e], qm, 1.f) : 0.f;
+            qp4[e] = fidx + e < N ? value(qh, pv4[e]) : 0.f;
+            wv4[e] = fb == 0 ? qp4[e] : fmaxf(pv4[e] - qp4[e], 0.f);
+        }
+        l0 = (double)wv4[0]; l1 = l0 + (double)wv4[1]; l2 = l1 + (double)wv4[2]; l3 = l2 + (double)wv4[3];
+        incl = wave_inclusive_scan(l3);
+        if (lane == kWave - 1) fd[4 + wid] = incl;
+        const int mine = wv4[3] > 0.f ? 3 : wv4[2] > 0.f ? 2 : wv4[1] > 0.f ? 1 : wv4[0] > 0.f ? 0 : -1;
+        const unsigned long long pos = __ballot(mine >= 0);
+        if (pos != 0ull) last_pos = lane_value((int)fidx + mine, 63 - __clzll(pos));
+    }
+    __syncthreads();
+    if (factive) {
+        double carried = 0.0;
+        for (int i = 0; i < fq; ++i) carried += fd[4 + 4 * fb + i];
+        const double thr_local = fd[fb];
+        const double excl = carried + (incl - l3);
+        const unsigned long long hits = __ballot(excl + l3 > thr_local);
+        int hit = -1;
+        if (hits != 0ull) {
+            const int e = (excl + l0 > thr_local) ? 0 : (excl + l1 > thr_local) ? 1 : (excl + l2 > thr_local) ? 2 : 3;
+            hit = lane_value((int)fidx + e, __ffsll(hits) - 1);
+        }
+        const int cand = hit >= 0 ? hit : last_pos;
+        float qc = 0.f, pc = 0.f;
+        if (cand >= 0) {
+            const int off = cand - (fblk * kChunk + fq * 256), src = off / 4, e = off % 4;
+            qc = lane_value(e == 0 ? qp4[0] : e == 1 ? qp4[1] : e == 2 ? qp4[2] : qp4[3], src);
+            pc = lane_value(e == 0 ? pv4[0] : e == 1 ? pv4[1] : e == 2 ? pv4[2] : pv4[3], src);
+        }
+        if (lane == 0) fc[wid] = make_float4(__int_as_float(hit), __int_as_float(last_pos), qc, pc);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tok[2] = {-1, -1};
+        float qd = 0.f, pd_w = 0.f;
+        for (int b = 0; b < 2; ++b) {
+            if (fi[b] < 0) continue;
+            int chosen = -1;
+            for (int i = 0; i < 4 && chosen < 0; ++i)
+                if (__float_as_int(fc[4 * b + i].x) >= 0) chosen = i;
+            if (chosen < 0)
+                for (int i = 3; i >= 0 && chosen < 0; --i)
+                    if (__float_as_int(fc[4 * b + i].y) >= 0) chosen = i;
+            if (chosen >= 0) {
+                const float4 c4 = fc[4 * b + chosen];
+                tok[b] = __float_as_int(c4.x) >= 0 ? __float_as_int(c4.x) : __float_as_int(c4.y);
+                if (b == 0) {
+                    qd = c4.z;
+                    pd_w = c4.w;
+                }
+            }
+        }
+        int32_t dtok = tok[0];
+        if (!draw_draft) {                            // the caller's draft: its two values are fetched here
+            dtok = fin.draft_ids[row];
+            if (dtok >= 0 && dtok < N) {
+                const int sg = slot_of[dtok];
+                pd_w = pr[dtok];
+                qd = value(sg >= 0 ? to_weight<QK>(load1<QK>(qr, sg), qm, 1.f) : 0.f, pd_w);
+            }
+        }
+        const bool d_ok = dtok >= 0 && dtok < N;
+        uint8_t acc = 0;
+        if (d_ok) acc = (word_to_unit((uint32_t)fi[3]) * (double)qd < (double)pd_w) ? 1 : 0;
+        if (draw_draft) fin.draft_ids[row] = dtok;
+        fin.accept[row] = acc;
+        if (fin.alpha) fin.alpha[row] = (float)fd[2];
+        if (fin.resid_mass) fin.resid_mass[row] = (float)fd[3];
+        fin.resid_ids[row] = tok[1];
     }
 }
 
@@ -826,15 +1010,6 @@ size_t row_lds_limit()
     }
     return limit;
 }
-
-template <int PK, int QK>
-struct QpTaylor {
-    static constexpr bool kSpreadRows = false;
-    static constexpr int kStages = 2;
-    TaylorArgs a;
-    typedef TaylorRow<PK, QK> Row;
-    __device__ __forceinline__ Row row(int64_t b) const { return make_taylor_row<PK, QK>(a, b); }
-};
 
 // ------------------------------------------------------------------------------------------------
 // Identity kernel: q' scattered to the kept ids, zero elsewhere (token-level intersection, Eq. 1).
@@ -869,10 +1044,7 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
                 rc = launch_row_stats<QK>(q, h.n, B, 1, w.qstat, st);
                 if (rc != RDK_OK) return rc;
             }
-            const size_t per = align_up((size_t)B * nchunks * sizeof(float), 256);
-            char *pp = (char *)ws + taylor_workspace_bytes(h, B);
-            float *part_q = (float *)pp, *part_r = (float *)(pp + per), *part_a = (float *)(pp + 2 * per);
-            const bool vec_p = rows_vectorisable(p.ptr, p.ld, p.kind), vec_q = rows_vectorisable(q.ptr, q.ld, q.kind);
+            const bool vec_p = rows_vectorisable(p.ptr, p.ld, p.kind);
             if (q.kind != RDK_LOGIT_BF16 && ((uintptr_t)q.ptr % 4 != 0)) return RDK_ERR_ALIGN;
             static bool attr_set = false;     // per instantiation: dynamic LDS above the default limit has to be granted once
             if (!attr_set) {
@@ -882,32 +1054,26 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
                                             (int)row_lds_limit()));
                 attr_set = true;
             }
-            if (h.N >= kRowSeriesMinN) {
-                RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, true>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
-                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.lane_map, h.chunk_lo, h.N, h.n, vec_p, w.qstat, w.tpart,
-                                 part_q, part_r, part_a);
-            } else {
-                RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, false>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
-                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.lane_map, h.chunk_lo, h.N, h.n, vec_p, w.qstat, w.tpart,
-                                 part_q, part_r, part_a);
-            }
-            RDK_LAUNCH_CHECK("taylor_row_kernel");
-            TaylorArgs a;
-            a.p = p.ptr; a.q = q.ptr; a.ldp = p.ld; a.ldq = q.ld;
-            a.slot_of = h.slot_of; a.kept = h.kept_ids; a.chunk_lo = h.chunk_lo; a.N = h.N; a.n = h.n;
-            a.splits = 1;                     // one record of totals per row
-            a.vec_p = vec_p; a.vec_q = vec_q;
-            a.onepass = false;
-            a.w = w;
-            FinalizeArgs fa{};
+            FinalizeArgs fa{};                // the block sums stay in the workgroup's LDS
             fa.d = c->d;
             fa.p = p.ptr; fa.ldp = p.ld; fa.vec_p = vec_p;
             fa.pstat = w.pstat; fa.p_splits = w.p_splits;
-            fa.part_q = part_q; fa.part_r = part_r; fa.part_a = part_a;
             fa.nblk = nchunks;
             fa.draft_ids = c->draft_ids; fa.accept = c->accept; fa.alpha = c->alpha; fa.resid_mass = c->resid_mass;
             fa.resid_ids = c->resid_ids; fa.n_accepted = c->n_accepted; fa.out_tokens = c->out_tokens;
-            return launch_finalize<PK, 1024, true, QpTaylor<PK, QK>>(fa, QpTaylor<PK, QK>{a}, st);
+            if (h.N >= kRowSeriesMinN) {
+                RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, true>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
+                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.lane_map, h.chunk_lo, h.item_lo, h.row_items, h.N, h.n,
+                                 vec_p, w.qstat, h.slot_of, fa);
+            } else {
+                RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, false>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
+                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.lane_map, h.chunk_lo, h.item_lo, h.row_items, h.N, h.n,
+                                 vec_p, w.qstat, h.slot_of, fa);
+            }
+            RDK_LAUNCH_CHECK("taylor_row_kernel");
+            if (c->d.gamma > 0 && (fa.n_accepted || fa.out_tokens))
+                return launch_sequence_scan(c->d, fa.draft_ids, fa.accept, fa.resid_ids, fa.n_accepted, fa.out_tokens, st);
+            return RDK_OK;
         }
     }
     // logit target rows of a large vocabulary: the first pass of Eq. 3 also delivers the softmax statistics

@@ -57,8 +57,9 @@ def test_storage_query_and_validation(rdk):
     q = lambda d: L.rdk_kernel_storage_bytes(ctypes.byref(d), ctypes.byref(sb), ctypes.byref(wb))
     assert q(_desc(rdk)) == 0
     up = lambda x: (x + 255) // 256 * 256
-    # kept ids, slot table, pruned ids, first slot per 1024-id chunk, lane map (64 records of 8 bytes per chunk)
-    head = 1024 + 4096 + up(769 * 4) + up(2 * 4) + up(1 * 64 * 8)
+    # kept ids, slot table, pruned ids, first slot per 1024-id chunk, lane map (64 records of 8 bytes per chunk), first
+    # piece per chunk, the pieces of at most 64 kept slots (one per chunk and one per 64 slots at most, 8 bytes each)
+    head = 1024 + 4096 + up(769 * 4) + up(2 * 4) + up(1 * 64 * 8) + up(2 * 4) + up((1 + 256 // 64 + 1) * 8)
     # [N-n, 16] (slot, weight) pairs (k = 8 padded to 16 entries) and the diagonal weights
     assert sb.value == head + up(768 * 16 * 8 + 512) + 1024
     assert q(_desc(rdk, format=rdk.DENSE_F32)) == 0 and sb.value == head + 256 * 1024 * 4
