@@ -175,7 +175,7 @@ def run_linear(args, rdk, torch, w, vocab, batch, mode_name, path, steps, warmup
     print("kernels of one %s step:" % mode_name, {k: round(v["avg_us"], 1) for k, v in per_kernel.items()}, file=sys.stderr)
 
     # the timed regions: K steps each, the dominant kernel's launches bracketed by events on the launch stream
-    rdk.rdk_timing_select(dominant)
+    rdk.rdk_timing_select(dominant + "/8")             # every eighth launch: an event pair per launch would slow the step
     regions = timed_regions(torch, step, steps, warmup)
     rdk.rdk_timing_select(None)
     cnt, kms = rdk.rdk_timing_read(dominant)

@@ -315,7 +315,9 @@ rdk_status_t rdk_philox_words(uint64_t seed, uint64_t offset, int32_t count, uin
 /*
  * Kernel timing for benchmarks.  After rdk_timing_select(name) every launch of the library kernel
  * of that name ("*" = every kernel of the redistribute / verify calls, NULL or "" = none) is
- * bracketed by two HIP events on the launch stream.  rdk_timing_read(name, ...) waits for the
+ * bracketed by two HIP events on the launch stream; "name/8" brackets every eighth launch only
+ * (an event pair costs the host and the stream several microseconds, which a short step would
+ * otherwise show).  rdk_timing_read(name, ...) waits for the
  * recorded events of that kernel, returns how many launches were recorded and their summed
  * elapsed time in milliseconds, and forgets them.  Both take HOST strings.  Names:
  * row_stats_kernel, row_block_sums_kernel, verify_stream_kernel, verify_finalize_kernel, draft_finalize_kernel,

@@ -1,4 +1,5 @@
 // C ABI of the RDK library: argument checks, storage / workspace carving, dispatch to the launchers.
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -25,6 +26,7 @@ struct TimedRecord {
 };
 std::mutex g_timing_mutex;
 std::string g_timing_selected;             // "" = off, "*" = every instrumented kernel
+long g_timing_every = 1, g_timing_seen = 0;   // of the launches of the selected kernel, every g_timing_every-th is timed
 std::vector<TimedRecord> g_timing_records;
 std::vector<hipEvent_t> g_timing_free;
 
@@ -46,6 +48,7 @@ bool timing_events(const char *kernel_name, hipEvent_t *start, hipEvent_t *stop)
     std::lock_guard<std::mutex> lock(g_timing_mutex);
     if (g_timing_selected.empty()) return false;
     if (g_timing_selected != "*" && g_timing_selected != kernel_name) return false;
+    if (g_timing_seen++ % g_timing_every != 0) return false;
     hipEvent_t a = timing_event(), b = timing_event();
     if (!a || !b) return false;
     g_timing_records.push_back(TimedRecord{kernel_name, a, b});
@@ -608,6 +611,14 @@ rdk_status_t rdk_timing_select(const char *kernel_name)
 {
     std::lock_guard<std::mutex> lock(g_timing_mutex);
     g_timing_selected = kernel_name ? kernel_name : "";
+    g_timing_every = 1;
+    g_timing_seen = 0;
+    const size_t slash = g_timing_selected.find('/');   // "name/8": every eighth launch
+    if (slash != std::string::npos) {
+        const long every = std::atol(g_timing_selected.c_str() + slash + 1);
+        g_timing_every = every > 0 ? every : 1;
+        g_timing_selected.resize(slash);
+    }
     return RDK_OK;
 }
 

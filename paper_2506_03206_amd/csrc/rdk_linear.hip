@@ -514,7 +514,7 @@ constexpr int kRowGroups = kRowThreads / 16;   // groups of sixteen lanes: one p
 constexpr int kRowHeld = 10;                   // pieces per group whose drafter values are requested ahead of the row constants
 
 struct RowLds {      // offsets in floats into the dynamic LDS block
-    int pk, spare, blk_p, blk_a, red, items, isum, sum_q, sum_r, sum_a, fin, total;
+    int pk, zero, blk_p, blk_a, blk_all, blk_aq, red, items, item_lo, isum, sum_q, sum_r, sum_a, fin, total;
 };
 
 // Where the run of chunk c (first slot lo) starts in the LDS array of kept target values: a multiple of four floats, and
@@ -530,17 +530,22 @@ __host__ __device__ inline RowLds row_lds_layout(int n, int nchunks)
     int off = 0;
     // target values of the kept ids: runs of slots, one per chunk, and room for the quads that a piece reads past its end
     // (their values are masked)
-    L.pk = off; off += ((n + 3) & ~3) + 4 * nchunks + 64 + 4;
-    L.spare = off; off += kWave;                       // where the lanes send the values of ids that are not kept
-    L.blk_p = off; off += (nchunks + 3) & ~3;          // per chunk: sum of p over the not-kept ids
-    L.blk_a = off; off += (nchunks + 3) & ~3;          //            sum of p / (N + p) over the not-kept ids
+    L.pk = off; off += ((n + 3) & ~3) + 4 * nchunks + 4;
+    L.zero = off; off += 4;                            // a quad of zeros for the lanes past the end of a piece
+    L.blk_p = off; off += 4 * nchunks;                 // per chunk, in four partial sums: p over the not-kept ids
+    L.blk_a = off; off += 4 * nchunks;                 //            p / (N + p) over the not-kept ids
+    L.blk_all = off; off += 4 * nchunks;               //            p / (N + p) over all ids
+    L.blk_aq = off; off += 4 * nchunks;                //            q^ / (N + p) over the kept ids
     L.red = off; off += kRowWaves * 4;
     const int mi = (row_max_items(n, nchunks) + 1) & ~1;
     L.items = off; off += 2 * mi;                      // the kernel's table of pieces
-    L.isum = off; off += 4 * mi;                       // per piece: sums of q', max(0, p - q'), min(p, q')
-    L.sum_q = off; off += (nchunks + 3) & ~3;          // per chunk: the three block sums the finish step draws from
-    L.sum_r = off; off += (nchunks + 3) & ~3;
-    L.sum_a = off; off += (nchunks + 3) & ~3;
+    L.item_lo = off; off += (nchunks + 1 + 3) & ~3;    // first piece of every chunk
+    L.isum = off; off += 2 * mi;                       // per piece: sums of max(0, p - q') and min(p, q')
+    // per chunk: the three block sums the finish step draws from.  They are formed when the kept target values have
+    // served their purpose, and take their place (4 nchunks + 8 floats are there at least).
+    L.sum_q = L.pk;
+    L.sum_r = L.sum_q + ((nchunks + 3) & ~3);
+    L.sum_a = L.sum_r + ((nchunks + 3) & ~3);
     L.fin = off; off += 64;                            // what the wavefronts of the finish step hand to each other
     L.total = off;
     return L;
@@ -575,104 +580,114 @@ struct RowRcp {
     }
 };
 
-// Step A for one chunk c: target values of kept ids go to their slots in LDS (the others to a spare word of the lane);
-// sp, sa: sums of p and of p / (N + p) over the ids that are not kept; sall: p / (N + p) over all of them.
+// Step A for one chunk c: target values of kept ids go to their slots in LDS; sp, sa: sums of p and of p / (N + p) over
+// the ids that are not kept; sall: p / (N + p) over all of them.
 template <bool SERIES>
-__device__ __forceinline__ void row_scatter(const RowChunk &b, int c, int lo, const RowRcp<SERIES> &rcp, float *pk, int spare_idx,
-                                            float &sp, float &sa, float &sall)
+__device__ __forceinline__ void row_scatter(const RowChunk &b, int c, int lo, const RowRcp<SERIES> &rcp, float *pk, float &sp,
+                                            float &sa, float &sall)
 {
     const uint32_t mask = (uint32_t)b.map & 0xFFFFu;
     const int run = row_run_start(lo, c);                         // where the chunk's first slot sits in LDS
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        int idx = run + (int)((b.map >> (16 + 12 * i)) & 0xFFFu);   // slot of the lane's first kept id of this group
+        char *at = (char *)(pk + run + (int)((b.map >> (16 + 12 * i)) & 0xFFFu));   // slot of the lane's first kept id of this group
         const float pe[4] = {b.p[i].x, b.p[i].y, b.p[i].z, b.p[i].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const bool is_kept = (mask >> (4 * i + e)) & 1u;
-            const float t = pe[e] * rcp(pe[e]);
-            pk[is_kept ? idx : spare_idx] = pe[e];
-            idx += is_kept ? 1 : 0;
-            sp += is_kept ? 0.f : pe[e];
-            sa += is_kept ? 0.f : t;
-            sall += t;
+            const uint32_t kept = (mask >> (4 * i + e)) & 1u;
+            if (kept) *(float *)at = pe[e];
+            at += 4 * kept;
+            const float r = rcp(pe[e]);
+            const float pn = kept ? 0.f : pe[e];
+            sp += pn;
+            sa = fmaf(pn, r, sa);
+            sall = fmaf(pe[e], r, sall);
         }
     }
 }
 
-// The raw drafter values of four consecutive slots from s on (zero at slots from `end` on; end <= n).  One 16-byte load
-// when the quad lies below `end` -- four bytes of alignment are all a global load of that size needs -- and single
-// loads for the quad that crosses it.  Every load writes the one result under a one-sided branch, so a sequence of calls
-// issues its loads back to back (loads merged from two code paths would each be waited for at the merge).
+// The raw drafter values of four consecutive slots from s on, for the lanes whose quad starts below `end` (the others get
+// the value of weight zero; n = slots in the row).  One 16-byte load when the quad lies inside the row -- four bytes of
+// alignment are all a global load of that size needs; its slots from `end` on belong to the row but not to the caller --
+// and single loads for the quad that crosses the end of the row.  Every load writes the one result under a one-sided
+// branch, so a sequence of calls issues its loads back to back (loads merged from two code paths would each be waited
+// for at the merge).
 template <int QK>
-__device__ __forceinline__ float4 row_raw_quad(const void *qr, int s, int end)
+__device__ __forceinline__ float4 row_raw_quad(const void *qr, int s, int end, int n)
 {
-    float4 raw = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float none = QK == RDK_PROB_F32 ? 0.f : -INFINITY;
+    float4 raw = make_float4(none, none, none, none);
     if (QK == RDK_LOGIT_BF16) {
         const uint16_t *r = (const uint16_t *)qr;
-        if (s + 3 < end) {
+        if (s < end && s + 3 < n) {
             typedef unsigned short u16x4a __attribute__((ext_vector_type(4), aligned(2)));
             const u16x4a v = *(const u16x4a *)(r + s);
             raw = make_float4(bf16_to_f32(v.x), bf16_to_f32(v.y), bf16_to_f32(v.z), bf16_to_f32(v.w));
         }
-        if (s < end && s + 3 >= end) {
+        if (s < end && s + 3 >= n) {
             raw.x = bf16_to_f32(r[s]);
-            if (s + 1 < end) raw.y = bf16_to_f32(r[s + 1]);
-            if (s + 2 < end) raw.z = bf16_to_f32(r[s + 2]);
+            if (s + 1 < n) raw.y = bf16_to_f32(r[s + 1]);
+            if (s + 2 < n) raw.z = bf16_to_f32(r[s + 2]);
         }
     } else {
         const float *r = (const float *)qr;
-        if (s + 3 < end) {
+        if (s < end && s + 3 < n) {
             typedef float f32x4a __attribute__((ext_vector_type(4), aligned(4)));
             const f32x4a v = *(const f32x4a *)(r + s);
             raw = make_float4(v.x, v.y, v.z, v.w);
         }
-        if (s < end && s + 3 >= end) {
+        if (s < end && s + 3 >= n) {
             raw.x = r[s];
-            if (s + 1 < end) raw.y = r[s + 1];
-            if (s + 2 < end) raw.z = r[s + 2];
+            if (s + 1 < n) raw.y = r[s + 1];
+            if (s + 2 < n) raw.z = r[s + 2];
         }
     }
     return raw;
 }
 
-// The drafter weights of a raw quad: slots at or beyond `end` give zero.
+// The drafter weights of a raw quad (a slot that was not loaded gives zero).
 template <int QK>
-__device__ __forceinline__ float4 row_weights_of(const float4 raw, int s, int end, float qm)
+__device__ __forceinline__ float4 row_weights_of(const float4 raw, float qm)
 {
-    return make_float4(s + 0 < end ? to_weight<QK>(raw.x, qm, 1.f) : 0.f, s + 1 < end ? to_weight<QK>(raw.y, qm, 1.f) : 0.f,
-                       s + 2 < end ? to_weight<QK>(raw.z, qm, 1.f) : 0.f, s + 3 < end ? to_weight<QK>(raw.w, qm, 1.f) : 0.f);
+    return make_float4(to_weight<QK>(raw.x, qm, 1.f), to_weight<QK>(raw.y, qm, 1.f), to_weight<QK>(raw.z, qm, 1.f),
+                       to_weight<QK>(raw.w, qm, 1.f));
 }
 
 // The drafter values of a chunk's run of slots [lo, hi): lane l takes the quads lo + 4 l + 256 i (a run has at most
 // 1024 slots).
 template <int QK>
-__device__ __forceinline__ void row_q_fetch(const void *qr, int lo, int hi, float4 (&qv)[4])
+__device__ __forceinline__ void row_q_fetch(const void *qr, int lo, int hi, int n, float4 (&qv)[4])
 {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) qv[i] = row_raw_quad<QK>(qr, lo + 4 * (lane_id() + 64 * i), hi);
+    for (int i = 0; i < 4; ++i) qv[i] = row_raw_quad<QK>(qr, lo + 4 * (lane_id() + 64 * i), hi, n);
 }
 
 // Sums over the kept ids of chunk c, in slot order: the wavefront reads back the target values it has just scattered.
-// A lane past the end of the run reads the run's first quad instead (its drafter weights are zero); the quad that crosses
-// the end reads what follows the run, which is zero or a target value of the next run.
+// A lane past the end of the run reads the run's first quad instead (its drafter weights are zero); in the one quad that
+// crosses the end, the weights of the slots past it are set to zero.
 template <int QK, bool SERIES>
 __device__ __forceinline__ void row_kept_sums(int c, int lo, int hi, const float4 (&qv)[4], const float *pk,
-                                              const RowRcp<SERIES> &rcp, float qm, float &zq, float &tn, float &an)
+                                              const RowRcp<SERIES> &rcp, float qm, float &zq, float &tn, float &aq)
 {
     const float *run = pk + row_run_start(lo, c);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         if (lo + 256 * i < hi) {
             const int o = 4 * (lane_id() + 64 * i);
-            const float4 p4 = *(const float4 *)(run + (lo + o < hi ? o : 0));
-            const float4 w4 = row_weights_of<QK>(qv[i], lo + o, hi, qm);
-            const float qe[4] = {w4.x, w4.y, w4.z, w4.w}, pe[4] = {p4.x, p4.y, p4.z, p4.w};
+            const int left = hi - lo - o;              // slots of the run from the lane's quad on
+            const float4 p4 = *(const float4 *)(run + (left > 0 ? o : 0));
+            const float4 w4 = row_weights_of<QK>(qv[i], qm);
+            float qe[4] = {w4.x, w4.y, w4.z, w4.w};
+            const float pe[4] = {p4.x, p4.y, p4.z, p4.w};
+            if (left > 0 && left < 4) {
+#pragma unroll
+                for (int e = 1; e < 4; ++e) qe[e] = e < left ? qe[e] : 0.f;
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 zq += qe[e];
                 tn = fmaf(qe[e], pe[e], tn);
-                an = fmaf(qe[e], rcp(pe[e]), an);
+                aq = fmaf(qe[e], rcp(pe[e]), aq);
             }
         }
     }
@@ -690,7 +705,8 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     const RowLds L = row_lds_layout(n, nchunks);
     float *pk = lds + L.pk;
     int2 *il = (int2 *)(lds + L.items);
-    float4 *isum = (float4 *)(lds + L.isum);
+    int *ilo = (int *)(lds + L.item_lo);
+    float2 *isum = (float2 *)(lds + L.isum);
     const int64_t row = blockIdx.x;
     const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
     const float *pr = p + row * ldp;
@@ -701,7 +717,6 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     rcp.fN = fN;
     rcp.invN = 1.0f / fN;
     rcp.invN2 = rcp.invN * rcp.invN;
-    const int spare_idx = (L.spare - L.pk) + lane;    // relative to pk
 
     // ---- the kernel's table of pieces goes to LDS (entries past the last piece are never used), the array of kept target
     // values starts at zero, and the first two chunks of every wavefront are on their way meanwhile
@@ -721,10 +736,11 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     }
     {
         float4 *z = (float4 *)pk;
-        const int quads = (L.spare - L.pk) / 4;
+        const int quads = (L.blk_p - L.pk) / 4;
         for (int i = threadIdx.x; i < quads; i += kRowThreads) z[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         if ((int)threadIdx.x < max_items) il[threadIdx.x] = it0;
         for (int k = threadIdx.x + kRowThreads; k < max_items; k += kRowThreads) il[k] = row_items[k];
+        for (int cc = threadIdx.x; cc <= nchunks; cc += kRowThreads) ilo[cc] = item_lo[cc];
     }
     __syncthreads();
 
@@ -732,22 +748,29 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     // chunk's run are requested one chunk ahead, into the registers the sums of this chunk have just freed
     float zq = 0.f, tn = 0.f, an = 0.f, ball = 0.f;   // ball: sum of p / (N + p) over all ids
     float4 qv[4];
-    if (c < nchunks) row_q_fetch<QK>(qr, b0.lo, b0.hi, qv);
+    if (c < nchunks) row_q_fetch<QK>(qr, b0.lo, b0.hi, n, qv);
 #define RDK_ROW_STEP(CUR, NEXT, FREE)                                                                        \
     {                                                                                                        \
         if (c + 2 * kRowWaves < nchunks) row_fetch(pr, lane_map, chunk_lo, c + 2 * kRowWaves, N, vec_p, FREE); \
         const int lo_c = __builtin_amdgcn_readfirstlane(CUR.lo), hi_c = __builtin_amdgcn_readfirstlane(CUR.hi); \
-        float sp = 0.f, sa = 0.f;                                                                            \
-        row_scatter<SERIES>(CUR, c, lo_c, rcp, pk, spare_idx, sp, sa, ball);                                 \
-        sp = wave_sum(sp);                                                                                   \
-        sa = wave_sum(sa);                                                                                   \
-        if (lane == 0) {                                                                                     \
-            lds[L.blk_p + c] = sp;                                                                           \
-            lds[L.blk_a + c] = sa;                                                                           \
+        float sp = 0.f, sa = 0.f, sall = 0.f, aq = 0.f;                                                      \
+        row_scatter<SERIES>(CUR, c, lo_c, rcp, pk, sp, sa, sall);                                            \
+        row_kept_sums<QK, SERIES>(c, lo_c, hi_c, qv, pk, rcp, qm, zq, tn, aq);                               \
+        ball += sall;                                                                                        \
+        an += aq;                                                                                            \
+        sp = row16_sum(sp);                           /* per chunk: four partial sums, one per row of sixteen lanes */ \
+        sa = row16_sum(sa);                                                                                  \
+        sall = row16_sum(sall);                                                                              \
+        aq = row16_sum(aq);                                                                                  \
+        if ((lane & 15) == 0) {                                                                              \
+            const int o = 4 * c + (lane >> 4);                                                               \
+            lds[L.blk_p + o] = sp;                                                                           \
+            lds[L.blk_a + o] = sa;                                                                           \
+            lds[L.blk_all + o] = sall;                                                                       \
+            lds[L.blk_aq + o] = aq;                                                                          \
         }                                                                                                    \
-        row_kept_sums<QK, SERIES>(c, lo_c, hi_c, qv, pk, rcp, qm, zq, tn, an);                               \
         if (c + kRowWaves < nchunks)                                                                         \
-            row_q_fetch<QK>(qr, __builtin_amdgcn_readfirstlane(NEXT.lo), __builtin_amdgcn_readfirstlane(NEXT.hi), qv); \
+            row_q_fetch<QK>(qr, __builtin_amdgcn_readfirstlane(NEXT.lo), __builtin_amdgcn_readfirstlane(NEXT.hi), n, qv); \
         c += kRowWaves;                                                                                      \
     }
     while (c < nchunks) {
@@ -765,19 +788,29 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     if (lane == 0) *(float4 *)(lds + L.red + wid * 4) = make_float4(zq, tn, an, ball);
 
     // ---- step C works on pieces: group g of sixteen lanes takes the pieces g, g + 64, ...; lane li of the group the slots
-    // 4 li .. 4 li + 3 of the piece.  The drafter values of the first rounds are asked for here, before the barrier.
+    // 4 li .. 4 li + 3 of the piece.  The drafter values of the first rounds are asked for here, before the barrier, and
+    // so is where the lane finds its target values in LDS: a lane wholly past the end of the piece is pointed at a quad of
+    // zeros; the quad that crosses the end runs into the zeros that separate the runs (a piece shorter than 64 ends its
+    // run).  Where the target value is zero, q' adds nothing to either sum whatever the drafter value, so nothing needs
+    // masking later.
     const int grp = threadIdx.x >> 4, li = threadIdx.x & 15;
     float4 qh[kRowHeld];
+    int pat[kRowHeld];
+    auto piece_of = [&](int k, int &len) {            // LDS offset of the lane's quad of piece k, and the piece's length
+        const int2 it = il[k];
+        len = (int)((uint32_t)it.y >> 24);
+        return 4 * li < len ? L.pk + it.x - ((it.y >> 22) & 3) + 4 * (it.y & 0x3FFFFF) + 4 * li : L.zero;
+    };
 #pragma unroll
     for (int t = 0; t < kRowHeld; ++t) {
         const int k = grp + kRowGroups * t;
-        const int2 it = k < nitems ? il[k] : make_int2(0, 0);
-        qh[t] = row_raw_quad<QK>(qr, it.x + 4 * li, it.x + (int)((uint32_t)it.y >> 24));
-    }
-    int k0 = 0, k1 = 0;                               // the pieces of the chunk whose block sums this thread will write
-    if ((int)threadIdx.x < nchunks) {
-        k0 = item_lo[threadIdx.x];
-        k1 = item_lo[threadIdx.x + 1];
+        int len = 0, first = 0;
+        pat[t] = L.zero;
+        if (k < nitems) {
+            pat[t] = piece_of(k, len);
+            first = il[k].x;
+        }
+        qh[t] = row_raw_quad<QK>(qr, first + 4 * li, first + len, n);
     }
     __syncthreads();
     float tot[4];
@@ -794,57 +827,51 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     const float inv_S = inv_mass(tot[2] * inv_zq + theta * tot[3]);
     const float nzs = fN * inv_zq * inv_S, ths = theta * inv_S;
 
-    // ---- step C: q' on the kept slots, piece by piece
-    auto piece_sums = [&](int k, const float4 raw) {
-        const int2 it = il[k];
-        const int len = (int)((uint32_t)it.y >> 24), cnk = it.y & 0x3FFFFF, lo3 = (it.y >> 22) & 3;
-        const float4 w4 = row_weights_of<QK>(raw, 4 * li, len, qm);
-        const float4 p4 = *(const float4 *)(pk + (it.x - lo3 + 4 * cnk + 4 * li));
-        const float qe[4] = {w4.x, w4.y, w4.z, w4.w}, pr4[4] = {p4.x, p4.y, p4.z, p4.w};
-        float sq = 0.f, sr = 0.f, sa = 0.f;
+    // ---- step C: max(0, p - q') and min(p, q') on the kept slots, piece by piece (the sum of q' over the kept ids of a
+    // chunk needs no pass: it is nzs * sum q^ / (N + p) + ths * sum p / (N + p), both known from step A)
+    auto piece_sums = [&](int k, const float4 raw, int at) {
+        const float4 w4 = row_weights_of<QK>(raw, qm);
+        const float4 p4 = *(const float4 *)(lds + at);
+        const float qe[4] = {w4.x, w4.y, w4.z, w4.w}, pe[4] = {p4.x, p4.y, p4.z, p4.w};
+        float sr = 0.f, sa = 0.f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float pe = 4 * li + e < len ? pr4[e] : 0.f;
-            const float v = (nzs * qe[e] + ths * pe) * rcp(pe);
-            const float m = fminf(pe, v);
-            sq += v;
+            const float v = (nzs * qe[e] + ths * pe[e]) * rcp(pe[e]);
+            const float m = __builtin_amdgcn_fmed3f(pe[e], v, -INFINITY);   // min(p, q'): neither is a NaN
             sa += m;
-            sr += pe - m;
+            sr += pe[e] - m;
         }
         // the sixteen lanes of the group hold the piece: four lane exchanges at register speed
-        sq = row16_sum(sq);
         sr = row16_sum(sr);
         sa = row16_sum(sa);
-        if (li == 0) isum[k] = make_float4(sq, sr, sa, 0.f);
+        if (li == 0) isum[k] = make_float2(sr, sa);
     };
 #pragma unroll
     for (int t = 0; t < kRowHeld; ++t) {
         const int k = grp + kRowGroups * t;
-        if (k < nitems) piece_sums(k, qh[t]);
+        if (k < nitems) piece_sums(k, qh[t], pat[t]);
     }
     for (int k = grp + kRowGroups * kRowHeld; k < nitems; k += kRowGroups) {   // more pieces than the registers were given
-        const int2 it = il[k];
-        piece_sums(k, row_raw_quad<QK>(qr, it.x + 4 * li, it.x + (int)((uint32_t)it.y >> 24)));
+        int len;
+        const int at = piece_of(k, len);
+        const int first = il[k].x;
+        piece_sums(k, row_raw_quad<QK>(qr, first + 4 * li, first + len, n), at);
     }
     __syncthreads();
 
-    // ---- the block sums of a chunk: its pieces in order, and the closed form of the not-kept ids
-    for (int cc = threadIdx.x; cc < nchunks; cc += kRowThreads) {
-        if (cc >= kRowThreads) {
-            k0 = item_lo[cc];
-            k1 = item_lo[cc + 1];
+    // ---- the block sums of a chunk: its pieces in order (at most sixteen: one lane each), and the closed forms
+    for (int cc = grp; cc < nchunks; cc += kRowGroups) {
+        const int k = ilo[cc] + li;
+        const float2 f = k < ilo[cc + 1] ? isum[k] : make_float2(0.f, 0.f);
+        const float sr = row16_sum(f.x), sa = row16_sum(f.y);
+        if (li == 0) {
+            const float4 bp = *(const float4 *)(lds + L.blk_p + 4 * cc), ba = *(const float4 *)(lds + L.blk_a + 4 * cc);
+            const float4 bl = *(const float4 *)(lds + L.blk_all + 4 * cc), bq = *(const float4 *)(lds + L.blk_aq + 4 * cc);
+            const float ta = ths * ((ba.x + ba.y) + (ba.z + ba.w));   // sum of q' (= sum of min(p, q')) over the not-kept ids
+            lds[L.sum_q + cc] = ths * ((bl.x + bl.y) + (bl.z + bl.w)) + nzs * ((bq.x + bq.y) + (bq.z + bq.w));
+            lds[L.sum_a + cc] = ta + sa;
+            lds[L.sum_r + cc] = (((bp.x + bp.y) + (bp.z + bp.w)) - ta) + sr;
         }
-        float sq = 0.f, sr = 0.f, sa = 0.f;
-        for (int k = k0; k < k1; ++k) {
-            const float4 f = isum[k];
-            sq += f.x;
-            sr += f.y;
-            sa += f.z;
-        }
-        const float ta = ths * lds[L.blk_a + cc];      // sum of q' (= sum of min(p, q')) over the not-kept ids
-        lds[L.sum_q + cc] = ta + sq;
-        lds[L.sum_a + cc] = ta + sa;
-        lds[L.sum_r + cc] = (lds[L.blk_p + cc] - ta) + sr;
     }
     __syncthreads();
 
