@@ -21,7 +21,8 @@ namespace {
 constexpr int kThreads = 512;     // product kernel: 8 wavefronts share one staged tile
 constexpr int kWaves = kThreads / kWave;
 constexpr int kPrepThreads = 256; // transposition kernel
-constexpr int kTSlots = 64;       // slots per workgroup of the transposition kernel (128 and 256 were slower)
+constexpr int kTSlots = 64;       // slots per LDS tile of the transposition kernel (128 and 256 were slower)
+constexpr int kTGroup = 8;        // tiles per workgroup of the transposition kernel: one partial row sum per 512 slots
 constexpr int kPosBlock = 32;    // positions per gather: 32 fp32 = one 128-byte line
 constexpr int kTileIds = 256;    // target ids per workgroup
 constexpr int kStageLd = kTileIds + 4;   // rows stay 16-byte aligned for the float4 read-out
@@ -32,7 +33,8 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 struct SparseWs {
     SoftStat *qpart;   // [B, q_splits]  drafter row statistics, a few partials per row
-    float *zinv;       // [ceil(B/32) * 32]  1 / drafter row sum (Eq. 1), 0 for padding positions
+    float *zpart;      // [B, zt]  partial sums of the drafter weights, one per 512 slots (Eq. 1 divides by their sum)
+    int zt;
     float *qT;         // [ceil(B/32), n, 32]
     int q_splits;
 };
@@ -43,7 +45,8 @@ SparseWs carve(const KernelHandle &h, int32_t B, void *ws)
     w.q_splits = row_splits(B, h.n, kPrepThreads / kWave);
     char *p = (char *)ws;
     w.qpart = (SoftStat *)p; p += align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256);
-    w.zinv = (float *)p; p += align_up((size_t)(B + kPosBlock) * sizeof(float), 256);
+    w.zt = (h.n + kTSlots * kTGroup - 1) / (kTSlots * kTGroup);
+    w.zpart = (float *)p; p += align_up((size_t)B * w.zt * sizeof(float), 256);
     w.qT = (float *)p;
     return w;
 }
@@ -59,18 +62,20 @@ __device__ __forceinline__ float oct_sum(float v)
 
 // ------------------------------------------------------------------------------------------------
 // qT[(pb * n + s) * 32 + r] = weight(q[pb*32 + r, s]); zero for positions beyond B.  weight = the raw
-// probability, or exp(z - row max) for logits; the division by the row sum (Eq. 1) happens in the product.
+// probability, or exp(z - row max) for logits; the division by the row sum (Eq. 1) happens in the product, from the
+// partial sums this kernel leaves: zpart[b, x] = sum of the weights of row b over the 512 slots of workgroup x (eight
+// threads per row, eight tiles of 64 slots each, all loads of a workgroup requested before the first is used).
 template <int QK>
 __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q, int64_t ldq, int n, int B,
-                                                                   const SoftStat *qpart, int q_splits, bool vec, float *zinv,
-                                                                   float *qT, const SoftStat *pstat, int p_splits,
+                                                                   const SoftStat *qpart, int q_splits, bool vec, float *zpart,
+                                                                   int zt, float *qT, const SoftStat *pstat, int p_splits,
                                                                    SoftStat *pmerged)
 {
-    __shared__ float tile[kTSlots][kPosBlock + 1];
+    __shared__ float tile[2][kTSlots][kPosBlock + 1];
     __shared__ float rowmax[kPosBlock];
     const int pb = blockIdx.y;
-    const int s0 = blockIdx.x * kTSlots;
-    const int r = threadIdx.x / 8, part = threadIdx.x % 8;     // 8 threads per position
+    const int g0 = blockIdx.x * kTSlots * kTGroup;
+    const int r = threadIdx.x / 8, part = threadIdx.x % 8;     // 8 threads per position, 8 consecutive slots of a tile each
     const int64_t b = (int64_t)pb * kPosBlock + r;
     if (pstat != nullptr && blockIdx.x == 0) {
         // softmax statistics of the logit TARGET rows of this position block, merged once here so that the product
@@ -89,68 +94,75 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
         }
         if (part == 0 && b < B) pmerged[b] = v;
     }
-    if (QK != RDK_PROB_F32 || blockIdx.x == 0) {
-        // row maximum (logits) and, in the first slot tile, 1 / row sum for the product kernel: partial sums of
-        // logits are relative to each partial's own maximum and are brought to the row maximum first
-        float m = QK == RDK_PROB_F32 ? 0.f : -INFINITY;
-        if (QK != RDK_PROB_F32) {
-            if (b < B)
-                for (int i = part; i < q_splits; i += 8) m = fmaxf(m, qpart[b * q_splits + i].m);
-            m = fmaxf(m, __shfl_xor(m, 1, kWave));
-            m = fmaxf(m, __shfl_xor(m, 2, kWave));
-            m = fmaxf(m, __shfl_xor(m, 4, kWave));
-            if (part == 0) rowmax[r] = m;
-        }
-        if (blockIdx.x == 0) {
-            float z = 0.f;
-            if (b < B)
-                for (int i = part; i < q_splits; i += 8) {
-                    const SoftStat st = qpart[b * q_splits + i];
-                    if (st.s > 0.f) z += QK == RDK_PROB_F32 ? st.s : st.s * soft_exp(st.m - m);
-                }
-            z = oct_sum(z);
-            if (part == 0) zinv[b] = b < B ? inv_mass(z) : 0.f;
-        }
-        if (QK != RDK_PROB_F32) __syncthreads();
+    float qm = 0.f;
+    if (QK != RDK_PROB_F32) {
+        // row maximum of the logit rows, from the partials of the statistics pass
+        float m = -INFINITY;
+        if (b < B)
+            for (int i = part; i < q_splits; i += 8) m = fmaxf(m, qpart[b * q_splits + i].m);
+        m = fmaxf(m, __shfl_xor(m, 1, kWave));
+        m = fmaxf(m, __shfl_xor(m, 2, kWave));
+        m = fmaxf(m, __shfl_xor(m, 4, kWave));
+        qm = m;
     }
-    // read 32 rows x kTSlots slots: kTSlots / 8 threads per row, 8 consecutive slots each
+    // the row's 512 slots of this workgroup: 8 slots per thread and tile
+    float v[kTGroup][8];
     {
-        const int grp = threadIdx.x % (kTSlots / 8), rsub = threadIdx.x / (kTSlots / 8);
-        constexpr int kRowsPerPass = kPrepThreads / (kTSlots / 8);
-        const int c8 = grp * 8;
+        const float fill = QK == RDK_PROB_F32 ? 0.f : -INFINITY;
+        float4 raw[kTGroup][2];
 #pragma unroll
-        for (int r0 = 0; r0 < kPosBlock; r0 += kRowsPerPass) {
-            const int rr = r0 + rsub;
-            const int64_t bb = (int64_t)pb * kPosBlock + rr;
-            float v[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = 0.f;
-            if (bb < B) {
-                const void *qr = row_ptr<QK>(q, ldq, bb);
-                const float qm = QK == RDK_PROB_F32 ? 0.f : rowmax[rr];
-                const float4 a0 = load4<QK>(qr, s0 + c8, n, vec, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
-                const float4 a1 = load4<QK>(qr, s0 + c8 + 4, n, vec, QK == RDK_PROB_F32 ? 0.f : -INFINITY);
-                const float raw[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = to_weight<QK>(raw[e], qm, 1.f);
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) tile[c8 + e][rr] = v[e];
-        }
-    }
-    __syncthreads();
-    {   // write kTSlots slots x 32 positions: 4 threads per slot, 8 positions each, 64 slots per pass
-        const int pq = (threadIdx.x % 4) * 8;
-#pragma unroll
-        for (int sl0 = 0; sl0 < kTSlots; sl0 += kPrepThreads / 4) {
-            const int sl = sl0 + threadIdx.x / 4;
-            if (s0 + sl < n) {
-                float *dst = qT + ((int64_t)pb * n + s0 + sl) * kPosBlock + pq;
-                *(float4 *)dst = make_float4(tile[sl][pq], tile[sl][pq + 1], tile[sl][pq + 2], tile[sl][pq + 3]);
-                *(float4 *)(dst + 4) = make_float4(tile[sl][pq + 4], tile[sl][pq + 5], tile[sl][pq + 6], tile[sl][pq + 7]);
+        for (int t = 0; t < kTGroup; ++t) {
+            raw[t][0] = raw[t][1] = make_float4(fill, fill, fill, fill);
+            if (b < B) {
+                const void *qr = row_ptr<QK>(q, ldq, b);
+                const int s = g0 + t * kTSlots + part * 8;
+                raw[t][0] = load4<QK>(qr, s, n, vec, fill);
+                raw[t][1] = load4<QK>(qr, s + 4, n, vec, fill);
             }
         }
+        float z = 0.f;
+#pragma unroll
+        for (int t = 0; t < kTGroup; ++t) {
+            const float x[8] = {raw[t][0].x, raw[t][0].y, raw[t][0].z, raw[t][0].w, raw[t][1].x, raw[t][1].y, raw[t][1].z, raw[t][1].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                v[t][e] = b < B ? to_weight<QK>(x[e], qm, 1.f) : 0.f;
+                z += v[t][e];
+            }
+        }
+        z = oct_sum(z);
+        if (part == 0 && b < B) zpart[b * zt + blockIdx.x] = z;
     }
+    // tile by tile through LDS: 4 threads per slot write 8 positions each; two tiles alternate, so one barrier per tile
+    const int pq = (threadIdx.x % 4) * 8, sl = threadIdx.x / 4;
+#pragma unroll
+    for (int t = 0; t < kTGroup; ++t) {
+        float (*tl)[kPosBlock + 1] = tile[t & 1];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tl[part * 8 + e][r] = v[t][e];
+        __syncthreads();
+        const int s = g0 + t * kTSlots + sl;
+        if (s < n) {
+            float *dst = qT + ((int64_t)pb * n + s) * kPosBlock + pq;
+            *(float4 *)dst = make_float4(tl[sl][pq], tl[sl][pq + 1], tl[sl][pq + 2], tl[sl][pq + 3]);
+            *(float4 *)(dst + 4) = make_float4(tl[sl][pq + 4], tl[sl][pq + 5], tl[sl][pq + 6], tl[sl][pq + 7]);
+        }
+    }
+}
+
+// 1 / (sum of the drafter weights of row b) from the partial sums of the transposition (0 for a row without mass), by
+// a whole wavefront: lane l adds the partials l, l + 64, ..., then the lanes are added up; the same bits wherever it is
+// called.  `first` = partial number lane_id() when the caller fetched it ahead of time.
+__device__ __forceinline__ float row_mass_rest(const float *zpart, int zt, int64_t b, float first)
+{
+    float z = first;
+    for (int i = lane_id() + kWave; i < zt; i += kWave) z += zpart[b * zt + i];
+    return inv_mass(wave_sum(z));
+}
+
+__device__ __forceinline__ float row_mass_inv(const float *zpart, int zt, int64_t b)
+{
+    return row_mass_rest(zpart, zt, b, lane_id() < zt ? zpart[b * zt + lane_id()] : 0.f);
 }
 
 // Broadcast within each group of four lanes: every lane receives the value held by lane `SRC` of its group.
@@ -166,7 +178,8 @@ struct SparseArgs {
     const float *self_w;
     int kk;
     const float *qT;
-    const float *zinv;
+    const float *zpart;
+    int zt;
     int N, n, B;
     int tiles, per_xcd, total_work;
     float *out;
@@ -182,7 +195,7 @@ __device__ __forceinline__ int pruned_below(const int32_t *slot_of, int j, int N
     return s < 0 ? -s - 1 : j - s;
 }
 
-// The product for one workgroup tile, left in `stage[position][id - j0]` (already divided by the row
+// The product for one workgroup tile, left in `stage[position][id - j0]` (not yet divided by the row
 // sums).  Lane layout of a wavefront: lane = 8 * i + o; i = id within a group of 8, o = which four of
 // the 32 positions.  One 128-byte line holds the 16 (slot, weight) pairs of a round: lane o of an id's
 // group fetches pairs 2o and 2o+1, and the pairs go round the group through the swizzle crossbar.
@@ -197,7 +210,6 @@ __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0,
     const int j1 = min(a.N, j0 + kTileIds);
     const int u_lo = pruned_below(a.slot_of, j0, a.N, a.n), u_hi = pruned_below(a.slot_of, j1, a.N, a.n);
     const int s_lo = j0 - u_lo, s_hi = j1 - u_hi;
-    const float4 inv_z = *(const float4 *)(a.zinv + pb * kPosBlock + o * 4);
     const float *qslab = a.qT + (int64_t)pb * a.n * kPosBlock + o * 4;
     const int rounds = a.kk / 16;
     const int2 *nbr_lane = a.nbr + 2 * o;
@@ -247,10 +259,10 @@ __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0,
         }
         if (valid) {
             const int c = pid - j0;
-            stage[o * 4 + 0][c] = acc.x * inv_z.x;
-            stage[o * 4 + 1][c] = acc.y * inv_z.y;
-            stage[o * 4 + 2][c] = acc.z * inv_z.z;
-            stage[o * 4 + 3][c] = acc.w * inv_z.w;
+            stage[o * 4 + 0][c] = acc.x;
+            stage[o * 4 + 1][c] = acc.y;
+            stage[o * 4 + 2][c] = acc.z;
+            stage[o * 4 + 3][c] = acc.w;
         }
     }
     // kept ids of the tile: kept slots [s_lo, s_hi) are consecutive rows of the slab
@@ -260,10 +272,10 @@ __device__ __forceinline__ void sparse_tile(const SparseArgs &a, int pb, int j0,
             const float sw = a.self_w[s];
             const float4 g = *(const float4 *)(qslab + (int64_t)s * kPosBlock);
             const int c = a.kept_ids[s] - j0;
-            stage[o * 4 + 0][c] = sw * g.x * inv_z.x;
-            stage[o * 4 + 1][c] = sw * g.y * inv_z.y;
-            stage[o * 4 + 2][c] = sw * g.z * inv_z.z;
-            stage[o * 4 + 3][c] = sw * g.w * inv_z.w;
+            stage[o * 4 + 0][c] = sw * g.x;
+            stage[o * 4 + 1][c] = sw * g.y;
+            stage[o * 4 + 2][c] = sw * g.z;
+            stage[o * 4 + 3][c] = sw * g.w;
         }
     }
     __syncthreads();
@@ -328,6 +340,13 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
                 praw[rr] = load4<PKIND>(row_ptr<PKIND>(f.p, f.ldp, b), jl, a.N, f.vec_p, pfill);
         }
     }
+    // Eq. 1: the row sums of the four rows this wavefront finishes, from the partials of the transposition (asked for now)
+    float zfirst[kRowsPerWave];
+#pragma unroll
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {
+        const int64_t b = (int64_t)pb * kPosBlock + wid * kRowsPerWave + rr;
+        zfirst[rr] = (b < a.B && lane < a.zt) ? a.zpart[b * a.zt + lane] : 0.f;
+    }
     // rounds of neighbour pairs requested ahead of their gathers: two when the target rows stream through the same
     // memory pipe (105 against 108 us per launch), one otherwise (92 against 99 us)
     sparse_tile<(PK >= 0 ? 2 : 1)>(a, pb, j0, stage);
@@ -336,9 +355,10 @@ __global__ __launch_bounds__(kThreads) void sparse_product_kernel(SparseArgs a, 
         const int r = wid * kRowsPerWave + rr;
         const int64_t b = (int64_t)pb * kPosBlock + r;
         if (b >= a.B) break;
+        const float inv_z = row_mass_rest(a.zpart, a.zt, b, zfirst[rr]);
         const float4 sv = *(const float4 *)&stage[r][4 * lane];
-        const float qv[4] = {jl + 0 < a.N ? sv.x : 0.f, jl + 1 < a.N ? sv.y : 0.f, jl + 2 < a.N ? sv.z : 0.f,
-                             jl + 3 < a.N ? sv.w : 0.f};
+        const float qv[4] = {jl + 0 < a.N ? sv.x * inv_z : 0.f, jl + 1 < a.N ? sv.y * inv_z : 0.f,
+                             jl + 2 < a.N ? sv.z * inv_z : 0.f, jl + 3 < a.N ? sv.w * inv_z : 0.f};
         if (WRITE_Q) {
             float *o = a.out + b * a.ldo + jl;
             if (a.vec_o && whole_tile) {
@@ -555,7 +575,7 @@ struct QpSparse {
     __device__ __forceinline__ Row row(int64_t b) const
     {
         const int pb = (int)(b / kPosBlock), r = (int)(b % kPosBlock);
-        return Row{a.slot_of, a.nbr, a.self_w, a.kk, a.N, a.qT + (int64_t)pb * a.n * kPosBlock + r, a.zinv[b]};
+        return Row{a.slot_of, a.nbr, a.self_w, a.kk, a.N, a.qT + (int64_t)pb * a.n * kPosBlock + r, row_mass_inv(a.zpart, a.zt, b)};
     }
 };
 
@@ -578,7 +598,7 @@ SparseArgs make_args(const KernelHandle &h, const SparseWs &w, int32_t B, float 
     SparseArgs a;
     a.slot_of = h.slot_of; a.pruned_ids = h.pruned_ids; a.kept_ids = h.kept_ids; a.nbr = h.nbr;
     a.self_w = h.self_w; a.kk = h.kk;
-    a.qT = w.qT; a.zinv = w.zinv;
+    a.qT = w.qT; a.zpart = w.zpart; a.zt = w.zt;
     a.N = h.N; a.n = h.n; a.B = B;
     const int pbs = (B + kPosBlock - 1) / kPosBlock;
     a.tiles = (h.N + kTileIds - 1) / kTileIds;
@@ -592,12 +612,14 @@ template <int QK>
 rdk_status_t prepare_q(const KernelHandle &h, RowInput q, int32_t B, const SparseWs &w, hipStream_t st,
                        const SoftStat *pstat = nullptr, int p_splits = 0, SoftStat *pmerged = nullptr)
 {
-    rdk_status_t rc = launch_row_stats<QK>(q, h.n, B, w.q_splits, w.qpart, st);
-    if (rc != RDK_OK) return rc;
+    if (QK != RDK_PROB_F32) {   // logit rows: the row maxima first; probability rows are summed by the transposition itself
+        const rdk_status_t rc = launch_row_stats<QK>(q, h.n, B, w.q_splits, w.qpart, st);
+        if (rc != RDK_OK) return rc;
+    }
     const int pbs = (B + kPosBlock - 1) / kPosBlock;
     {
-        RDK_TIMED_LAUNCH("q_transpose_kernel", (q_transpose_kernel<QK>), dim3((h.n + kTSlots - 1) / kTSlots, pbs), dim3(kPrepThreads), 0, st,
-                         q.ptr, q.ld, h.n, B, w.qpart, w.q_splits, rows_vectorisable(q.ptr, q.ld, q.kind), w.zinv, w.qT, pstat, p_splits,
+        RDK_TIMED_LAUNCH("q_transpose_kernel", (q_transpose_kernel<QK>), dim3(w.zt, pbs), dim3(kPrepThreads), 0, st,
+                         q.ptr, q.ld, h.n, B, w.qpart, w.q_splits, rows_vectorisable(q.ptr, q.ld, q.kind), w.zpart, w.zt, w.qT, pstat, p_splits,
                          pmerged);
     }
     RDK_LAUNCH_CHECK("q_transpose_kernel");
@@ -709,7 +731,8 @@ rdk_status_t launch_sparse_draft(const KernelHandle &h, RowInput q, int32_t B, u
 size_t sparse_workspace_bytes(const KernelHandle &h, int32_t B)
 {
     const size_t pbs = (B + kPosBlock - 1) / kPosBlock;
-    return align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256) + align_up((size_t)(B + kPosBlock) * sizeof(float), 256) +
+    const size_t zt = (h.n + kTSlots * kTGroup - 1) / (kTSlots * kTGroup);
+    return align_up((size_t)B * kMaxSplits * sizeof(SoftStat), 256) + align_up((size_t)B * zt * sizeof(float), 256) +
            align_up(pbs * h.n * kPosBlock * sizeof(float), 256);
 }
 
