@@ -3,7 +3,8 @@
 // instruction (register operands only, independent accumulators, once with constant and once with varied data,
 // because the chip lowers its clock with the switching activity of the operands), and gathers of whole 128-byte
 // lines at random out of a table that each XCD keeps in its own L2 (what the sparse product does with the
-// position-minor drafter table).  A stand-alone program:
+// position-minor drafter table), and gathers out of LDS (what a formulation with the drafter values on chip could do).
+// A stand-alone program:
 //   paper_2506_03206_amd/ceilings
 // The published peaks (8 TB/s, 157.3 TFLOP/s fp32, 2.5 PFLOP/s bf16) stay the denominators of every reported
 // fraction; these figures only say how much of the gap a kernel could close at all.
@@ -143,6 +144,36 @@ __global__ __launch_bounds__(512) void line_gather(const f32x4 *__restrict__ tab
     if (acc == 12345.678f) sink[0] = acc;
 }
 
+// ---- gathers out of LDS ----------------------------------------------------------------------------------------------
+// What a formulation of the sparse product with the drafter values of one position in LDS (128 KB: every kept slot of a
+// llama3-sized drafter row) could gather per clock.  WORDS = 1: every lane reads a random 4-byte word (one neighbour of
+// one id).  WORDS = 32: the 32 lanes of a half wavefront read the 32 consecutive words of a random 128-byte row (the
+// conflict-free pattern of a table bucketed by slot range).  Sixteen reads are in flight per lane before the first is used.
+template <int WORDS>
+__global__ __launch_bounds__(1024) void lds_gather(int iters, float *__restrict__ sink)
+{
+    extern __shared__ float slab[];
+    constexpr uint32_t kWords = 32768;                 // 128 KB
+    for (uint32_t i = threadIdx.x; i < kWords; i += 1024) slab[i] = (float)(i & 255u);
+    __syncthreads();
+    const uint32_t group = WORDS == 1 ? blockIdx.x * 1024u + threadIdx.x : (blockIdx.x * 1024u + threadIdx.x) / 32u;
+    uint32_t state = group * 2654435761u + 12345u;     // the same in the lanes that share a row
+    float acc = 0.f;
+    for (int it = 0; it < iters; ++it) {
+        float g[16];
+#pragma unroll
+        for (int t = 0; t < 16; t += 2) {              // two addresses per step of the generator: little besides the reads
+            state = state * 1664525u + 1013904223u;
+            const uint32_t a0 = state >> 17, a1 = (state >> 2) & 32767u;
+            g[t] = slab[WORDS == 1 ? a0 : (a0 & ~31u) + (threadIdx.x & 31u)];
+            g[t + 1] = slab[WORDS == 1 ? a1 : (a1 & ~31u) + (threadIdx.x & 31u)];
+        }
+#pragma unroll
+        for (int t = 0; t < 16; ++t) acc += g[t];
+    }
+    if (acc == 12345.678f) sink[0] = acc;
+}
+
 template <class F>
 static double mean_ms(F launch, int reps = 10)
 {
@@ -241,6 +272,22 @@ int main()
                         "%4.2f clk per line and CU (at 2.4 GHz)\n", mib, per_cu, ms, n_lines / ms / 1e6,
                         n_lines * 128 / kCus / (ms * 1e-3 * 2.4e9), ms * 1e-3 * 2.4e9 / (n_lines / kCus));
         }
+    }
+    // gathers out of a 128 KB LDS array, one workgroup of 16 wavefronts per CU
+    CHECK(hipFuncSetAttribute((const void *)lds_gather<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+    CHECK(hipFuncSetAttribute((const void *)lds_gather<32>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+    for (int words : {1, 32}) {
+        const int iters = 256;
+        const double ms = mean_ms([&](int, hipEvent_t a, hipEvent_t b) {
+            if (words == 1)
+                hipExtLaunchKernelGGL(lds_gather<1>, dim3(kCus), dim3(1024), 131072, 0, a, b, 0, iters, sink);
+            else
+                hipExtLaunchKernelGGL(lds_gather<32>, dim3(kCus), dim3(1024), 131072, 0, a, b, 0, iters, sink);
+        });
+        const double reads = (double)kCus * 1024 * iters * 16;   // 4-byte reads
+        std::printf("LDS gathers of %s out of 128 KB, 16 wavefronts/CU: %7.3f ms  %5.1f words per clock and CU (at 2.4 GHz), "
+                    "incl. filling the array\n", words == 1 ? "random 4-byte words " : "random 128-byte rows", ms,
+                    reads / kCus / (ms * 1e-3 * 2.4e9));
     }
     CHECK(hipFree(src));
     CHECK(hipFree(dst));
