@@ -225,6 +225,17 @@ __device__ __forceinline__ int search_block1(float w, int base, double thr_local
 }
 
 constexpr int kFinalizeRows = 8;   // rows (wavefronts) per workgroup at most: leaves 256 VGPRs per lane
+
+// Which row a one-row workgroup takes when the policy re-computes q' from tables that the kernel before it left in the
+// L2 of one XCD (the sparse product sweeps the rows of a 32-position block on one XCD when there are 8 k such blocks):
+// consecutive workgroup ids go to consecutive XCDs, so workgroup i takes a row of the blocks that XCD i % 8 has swept.
+// Any other batch shape keeps the identity; the mapping only decides which cache a row's lookups find warm.
+__device__ __forceinline__ int64_t xcd_row(int64_t i, int B)
+{
+    if (B % 256 != 0) return i;
+    const int64_t per_xcd = B / 8;
+    return (i % 8) * per_xcd + i / 8;
+}
 constexpr int kSpreadMinRows = 128;   // from this many rows on every row gets a workgroup of its own
 
 // The finish of one row by one wavefront: pq, prr, pa = the row's block sums of q', max(0, p - q') and min(p, q').
@@ -413,7 +424,7 @@ __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) vo
     __shared__ uint8_t sh_acc[kFinalizeRows];
     const rdk_verify_desc_t &d = a.d;
     const int wid = threadIdx.x / kWave, lane = lane_id();
-    const int64_t row = (int64_t)blockIdx.x * a.rows_per_block + wid;
+    const int64_t row = QP::kSpreadRows ? xcd_row(blockIdx.x, d.B) : (int64_t)blockIdx.x * a.rows_per_block + wid;
     if (row < d.B) {
         int32_t dtok, rtok;
         uint8_t acc;
@@ -440,6 +451,105 @@ __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) vo
     }
 }
 
+// The finish of one row by a workgroup of four wavefronts, for the policies that re-compute q' one id per lane (blocks
+// of 64 ids).  A lone wavefront pays the full latency of every dependent instruction, and half of its time went into
+// adding up and searching the three kinds of block sums one after the other; here wavefront 0 takes the sums of q' and
+// the draft's block, wavefront 1 the residual sums and the residual's block, wavefront 2 alpha (and the two values of a
+// draft the caller supplied), each with the routines of finalize_row, so the results are the same bits.
+template <int KIND, class QP>
+__global__ __launch_bounds__(4 * kWave) void verify_finalize_wide_kernel(FinalizeArgs a, QP qp)
+{
+    constexpr int kRegBlocks = 32;
+    __shared__ double sh_d[2];   // alpha, residual mass
+    __shared__ int sh_i[2];      // the drafted id, the residual id
+    __shared__ float sh_f[2];    // q' and p at the draft
+    const rdk_verify_desc_t &d = a.d;
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
+    const int64_t row = xcd_row(blockIdx.x, d.B);
+    const int N = d.N;
+    const void *pr = row_ptr<KIND>(a.p, a.ldp, row);
+    float m = 0.f, inv = 1.f;
+    if (KIND != RDK_PROB_F32) {
+        const SoftStat rs = merged_row_stat<KIND>(a.pstat, a.p_splits, row);
+        m = rs.m;
+        inv = 1.0f / rs.s;
+    }
+    const float pfill = KIND == RDK_PROB_F32 ? 0.f : -INFINITY;
+    const bool draw_draft = d.sample_draft;
+    const int per_lane = ((a.nblk + kWave - 1) / kWave + 3) & ~3;   // blocks per lane, in whole groups of four
+    const bool in_regs = per_lane <= kRegBlocks;
+    uint32_t words[4] = {0u, 0u, 0u, 0u};
+    int blk = -1;                // the block of this wavefront's draw (-1: nothing to draw) and the threshold inside it
+    double thr_local = 0.0;
+    // 1. one kind of block sums per wavefront
+    if (wid < 3) {
+        const float *part = (wid == 0 ? a.part_q : wid == 1 ? a.part_r : a.part_a) + row * a.nblk;
+        const bool wanted = wid == 0 ? draw_draft : true;
+        float v[kRegBlocks];
+        double lane_s = 0.0;
+        if (wanted && in_regs) load_partials(part, a.nblk, per_lane, v);
+        position_words(d.seed, d.offset + (uint64_t)row, words);   // while the sums are on their way
+        if (wanted) lane_s = in_regs ? sum_partials(v) : lane_partial_sum(part, a.nblk, per_lane);
+        const double T = wanted ? wave_sum(lane_s) : 0.0;
+        if (wid < 2 && wanted && T > 0.0) {
+            const double thr = word_to_unit(words[wid == 0 ? 0 : 2]) * T;
+            double before = 0.0;
+            blk = in_regs ? locate_block_regs(v, a.nblk, per_lane, lane_s, thr, before)
+                          : locate_block(part, a.nblk, per_lane, lane_s, thr, before);
+            thr_local = thr - before;
+        }
+        if (lane == 0 && wid >= 1) sh_d[2 - wid] = T;   // wavefront 1: residual mass -> [1], wavefront 2: alpha -> [0]
+    }
+    // 2. the block of the draft (wavefront 0) and of the residual draw (wavefront 1), one id per lane; the two values of
+    //    a caller's draft (wavefront 2)
+    const typename QP::Row qrow = qp.row(row);
+    if (wid < 2) {
+        int tok = -1;
+        if (blk >= 0) {
+            const int base = blk * 64, id = base + lane;
+            typename QP::Row::Pending1 t;
+            qrow.template stage1<0>(t, id);
+            float pv = pfill;
+            if (id < N) pv = load1<KIND>(pr, id);
+            qrow.template stage1<1>(t, id);
+            qrow.template stage1<2>(t, id);
+            const float wq = qrow.result1(t, id);
+            const float pw = to_weight<KIND>(pv, m, inv);
+            tok = search_block1(wid == 0 ? wq : fmaxf(pw - wq, 0.f), base, thr_local);
+            if (wid == 0 && tok >= 0) {
+                const float qd = lane_value(wq, tok - base), pd = lane_value(pw, tok - base);
+                if (lane == 0) {
+                    sh_f[0] = qd;
+                    sh_f[1] = pd;
+                }
+            }
+        }
+        if (lane == 0) sh_i[wid] = tok;
+    } else if (wid == 2 && !draw_draft) {
+        const int32_t dtok = a.draft_ids[row];
+        if (dtok >= 0 && dtok < N) {
+            const float pd = to_weight<KIND>(load1<KIND>(pr, dtok), m, inv), qd = qrow.load1(dtok);
+            if (lane == 0) {
+                sh_f[0] = qd;
+                sh_f[1] = pd;
+            }
+        }
+    }
+    __syncthreads();
+    // 3. the accept test and the row's outputs
+    if (threadIdx.x == 0) {
+        const int32_t dtok = draw_draft ? sh_i[0] : a.draft_ids[row];
+        const bool d_ok = dtok >= 0 && dtok < N;
+        uint8_t acc = 0;
+        if (d_ok) acc = (word_to_unit(words[1]) * (double)sh_f[0] < (double)sh_f[1]) ? 1 : 0;
+        if (draw_draft) a.draft_ids[row] = dtok;
+        a.accept[row] = acc;
+        if (a.alpha) a.alpha[row] = (float)sh_d[0];
+        if (a.resid_mass) a.resid_mass[row] = (float)sh_d[1];
+        a.resid_ids[row] = sh_i[1];
+    }
+}
+
 // ---- Draft draw alone (Alg. 4 step 2 on the drafter's side, before a target row exists): one wavefront per row,
 // block sums of q' in, the drafted id and q' at that id out.
 struct DraftArgs {
@@ -457,7 +567,7 @@ __global__ __launch_bounds__(kWave) void draft_finalize_kernel(DraftArgs a, QP q
     constexpr int SUB = BLOCK >= 256 ? BLOCK / 256 : 1;
     constexpr int kLanes = BLOCK >= 256 ? kWave : BLOCK / 4;
     constexpr int kRegBlocks = 32;
-    const int64_t row = blockIdx.x;
+    const int64_t row = QP::kSpreadRows ? xcd_row(blockIdx.x, a.B) : (int64_t)blockIdx.x;
     const int lane = lane_id();
     const int per_lane = ((a.nblk + kWave - 1) / kWave + 3) & ~3;   // blocks per lane, in whole groups of four
     const float *pq = a.part_q + row * a.nblk;
@@ -541,7 +651,10 @@ rdk_status_t launch_finalize(FinalizeArgs a, QP qp, hipStream_t st)
     a.scan_here = d.gamma >= 1 && d.gamma <= kFinalizeRows && !spread;
     a.rows_per_block = a.scan_here ? d.gamma : (spread ? 1 : 4);
     const int blocks = (d.B + a.rows_per_block - 1) / a.rows_per_block;
-    {
+    if constexpr (QP::kSpreadRows && BLOCK == 64 && HAS_Q) {
+        RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_wide_kernel<KIND, QP>), dim3((unsigned)d.B), dim3(4 * kWave), 0,
+                         st, a, qp);
+    } else {
         RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_kernel<KIND, BLOCK, HAS_Q, QP>), dim3(blocks),
                          dim3(a.rows_per_block * kWave), 0, st, a, qp);
     }
