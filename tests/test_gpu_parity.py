@@ -724,6 +724,76 @@ def test_fused_call_replays_from_a_hip_graph(rdk, ragged, mode):
             assert torch.equal(getattr(captured, name), getattr(eager, name)), "replay %d: %s" % (rep, name)
 
 
+@pytest.mark.parametrize("mode", ["sparse", "taylor"])
+def test_fused_call_of_a_large_batch_replays_from_a_hip_graph(rdk, mode):
+    """256 positions: the batch shape at which Eq. 3 takes its one-pass kernel (finish inside) and the sparse form finishes
+    every row on a workgroup of its own, rows dealt out by XCD, with the per-sequence scan as a launch of its own.  The
+    captured call against the oracle once, then three replays on permuted batches against the eager call."""
+    w = synth.scaled(synth.WORKLOADS["tiny"], name="graphbatch", N=4102, n=1021, k=16, seqs=32, gamma=8, seed=77)
+    data = make_inputs(w)
+    kept = data["kept_ids"]
+    if mode == "sparse":
+        idx, wt, sw = stochastic_topk_kernel(np.random.default_rng(3), w.N, kept, w.k)
+        kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.SPARSE_TOPK, k=w.k,
+                                    sparse=(dev(idx), dev(wt.astype(np.float32)), dev(sw.astype(np.float32))))
+        gmode = rdk.LINEAR_SPARSE
+        sparse32 = (idx, wt.astype(np.float32).astype(np.float64), sw.astype(np.float32).astype(np.float64))
+        ref_qp = oracle.redistribute_batch("sparse", data["q_hat"].astype(np.float64), kept, w.N, sparse=sparse32)
+    else:
+        kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.IDENTITY)
+        gmode = rdk.LINEAR_TAYLOR
+        ref_qp = oracle.redistribute_batch("taylor", data["q_hat"].astype(np.float64), kept, w.N, p=data["p"].astype(np.float64))
+    seed, offset = 4242, 9
+    p_static, q_static = dev(data["p"]).clone(), dev(data["q_hat"]).clone()
+    captured = rdk.VerifyOutputs(w.B, w.N, w.gamma, p_static.device)
+    eager = rdk.VerifyOutputs(w.B, w.N, w.gamma, p_static.device)
+    rdk.rdk_redistribute_verify(kern, gmode, p_static, q_static, seed, offset, w.gamma, outputs=captured)
+    rdk.rdk_redistribute_verify(kern, gmode, p_static, q_static, seed, offset, w.gamma, outputs=eager)
+    torch.cuda.synchronize()
+    p64 = data["p"].astype(np.float64)
+    check_verify_outputs(eager, oracle.verify_batch(p64, ref_qp, seed, offset, gamma=w.gamma), p64, ref_qp, seed, offset, w.gamma,
+                         "prob", min_exact=0.9)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rdk.rdk_redistribute_verify(kern, gmode, p_static, q_static, seed, offset, w.gamma, outputs=captured)
+    rng = np.random.default_rng(6)
+    for rep in range(3):
+        perm = rng.permutation(w.B)
+        p_static.copy_(dev(data["p"][perm]))
+        q_static.copy_(dev(data["q_hat"][perm]))
+        for name in ("draft_ids", "resid_ids"):
+            getattr(captured, name).fill_(-7)
+        captured.alpha.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        rdk.rdk_redistribute_verify(kern, gmode, p_static, q_static, seed, offset, w.gamma, outputs=eager)
+        torch.cuda.synchronize()
+        for name in ("draft_ids", "accept", "alpha", "resid_mass", "resid_ids", "n_accepted", "out_tokens"):
+            assert torch.equal(getattr(captured, name), getattr(eager, name)), "replay %d: %s" % (rep, name)
+
+
+def test_kernel_timing_brackets_every_nth_launch(rdk, ragged):
+    """rdk_timing_select("name/4"): of the launches of that kernel every fourth is bracketed by events."""
+    data = ragged
+    w = data["w"]
+    p, q = dev(data["p"]), dev(data["p"][::-1].copy())              # any q' rows will do
+    out = rdk.VerifyOutputs(w.B, w.N, w.gamma, p.device)
+    rdk.rdk_timing_select("verify_stream_kernel/4")
+    for i in range(8):
+        rdk.rdk_verify_sample(p, q, seed=1, offset=i, gamma=w.gamma, outputs=out)
+    torch.cuda.synchronize()
+    rdk.rdk_timing_select(None)
+    count, ms = rdk.rdk_timing_read("verify_stream_kernel")
+    assert count == 2 and ms > 0.0
+    rdk.rdk_timing_select("verify_stream_kernel")
+    for i in range(3):
+        rdk.rdk_verify_sample(p, q, seed=1, offset=i, gamma=w.gamma, outputs=out)
+    torch.cuda.synchronize()
+    rdk.rdk_timing_select(None)
+    assert rdk.rdk_timing_read("verify_stream_kernel")[0] == 3
+    assert rdk.rdk_timing_read("verify_stream_kernel")[0] == 0    # read forgets
+
+
 # --------------------------------------------------------------------------------------------- degenerate shapes
 DEGENERATE = {
     "one_row": dict(N=40, n=7, k=3, seqs=1, gamma=1, d=8),                # a single position, a vocabulary below one tile
