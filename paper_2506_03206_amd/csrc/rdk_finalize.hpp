@@ -459,7 +459,7 @@ __global__ __launch_bounds__(QP::kSpreadRows ? kWave : kFinalizeRows * kWave) vo
 template <int KIND, class QP>
 __global__ __launch_bounds__(4 * kWave) void verify_finalize_wide_kernel(FinalizeArgs a, QP qp)
 {
-    constexpr int kRegBlocks = 32;
+    constexpr int kRegBlocks = 64;   // block sums a lane keeps in registers: one kind per wavefront, so 4096 blocks (N = 262144) fit
     __shared__ double sh_d[2];   // alpha, residual mass
     __shared__ int sh_i[2];      // the drafted id, the residual id
     __shared__ float sh_f[2];    // q' and p at the draft
