@@ -922,7 +922,7 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
         }
     }
     __syncthreads();
-    auto value = [&](float qh, float pe) { return (nzs * qh + ths * pe) * __builtin_amdgcn_rcpf(fN + pe); };   // Eq. 3 for one id
+    auto value = [&](float qh, float pe) { return (nzs * qh + ths * pe) * rcp(pe); };   // Eq. 3 for one id, as in the sums
     const int fb = wid >> 2, fq = wid & 3;            // which of the two chunks, which quarter of it
     const int fblk = wid < 8 ? fi[fb] : -1;
     const bool factive = fblk >= 0;
