@@ -72,7 +72,6 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
                                                                    SoftStat *pmerged)
 {
     __shared__ float tile[2][kTSlots][kPosBlock + 1];
-    __shared__ float rowmax[kPosBlock];
     const int pb = blockIdx.y;
     const int g0 = blockIdx.x * kTSlots * kTGroup;
     const int r = threadIdx.x / 8, part = threadIdx.x % 8;     // 8 threads per position, 8 consecutive slots of a tile each

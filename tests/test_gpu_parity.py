@@ -681,6 +681,23 @@ def test_fused_eq3_single_pass_ragged_shapes(rdk, shape, q_kind):
         assert (o.draft_ids == o2.draft_ids).float().mean().item() >= 0.95
 
 
+def test_fused_eq3_single_pass_many_chunks(rdk):
+    """A vocabulary of 391 chunks with a few dozen kept ids in each: more pieces of kept slots (one per chunk and one per
+    64 slots, here about 700) than the groups of the one-pass kernel are handed before the row constants are known, so the
+    rest is fetched in the second step itself."""
+    w = synth.scaled(synth.WORKLOADS["tiny"], name="manychunks", N=400003, n=20011, seqs=8, gamma=8, seed=31)
+    data = make_inputs(w)
+    kept = data["kept_ids"]
+    assert np.unique(kept // 1024).size + kept.size // 64 > 640
+    kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.IDENTITY)
+    p64, q64 = data["p"].astype(np.float64), data["q_hat"].astype(np.float64)
+    ref_qp = oracle.redistribute_batch("taylor", q64, kept, w.N, p=p64)
+    seed, offset = 808, 3
+    ref = oracle.verify_batch(p64, ref_qp, seed, offset, gamma=w.gamma)
+    o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, dev(data["p"]), dev(data["q_hat"]), seed, offset, w.gamma)
+    check_verify_outputs(o, ref, p64, ref_qp, seed, offset, w.gamma, "prob", min_exact=0.9)
+
+
 # --------------------------------------------------------------------------------------------- HIP graph capture
 @pytest.mark.parametrize("mode", ["sparse", "taylor"])
 def test_fused_call_replays_from_a_hip_graph(rdk, ragged, mode):
