@@ -536,7 +536,7 @@ __host__ __device__ inline RowLds row_lds_layout(int n, int nchunks)
     L.blk_a = off; off += 4 * nchunks;                 //            p / (N + p) over the not-kept ids
     L.blk_all = off; off += 4 * nchunks;               //            p / (N + p) over all ids
     L.blk_aq = off; off += 4 * nchunks;                //            q^ / (N + p) over the kept ids
-    L.red = off; off += kRowWaves * 4;
+    L.red = off; off += kRowWaves * 9;                 // what the wavefronts hand to each other between the steps
     const int mi = (row_max_items(n, nchunks) + 1) & ~1;
     L.items = off; off += 2 * mi;                      // the kernel's table of pieces
     L.item_lo = off; off += (nchunks + 1 + 3) & ~3;    // first piece of every chunk
@@ -559,10 +559,11 @@ struct RowChunk {
     int lo, hi;
 };
 
-__device__ __forceinline__ void row_fetch(const float *pr, const uint64_t *lane_map, const int32_t *chunk_lo, int c, int N,
+template <int PK = RDK_PROB_F32>
+__device__ __forceinline__ void row_fetch(const void *pr, const uint64_t *lane_map, const int32_t *chunk_lo, int c, int N,
                                           bool vec_p, RowChunk &b)
 {
-    load_chunk<RDK_PROB_F32>(pr, (int64_t)c * kChunk, N, vec_p, 0.f, b.p);
+    load_chunk<PK>(pr, (int64_t)c * kChunk, N, vec_p, PK == RDK_PROB_F32 ? 0.f : -INFINITY, b.p);
     b.map = lane_map[(int64_t)c * kWave + lane_id()];
     b.lo = chunk_lo[c];
     b.hi = chunk_lo[c + 1];
@@ -690,6 +691,162 @@ __device__ __forceinline__ void row_kept_sums(int c, int lo, int hi, const float
                 aq = fmaf(qe[e], rcp(pe[e]), aq);
             }
         }
+    }
+}
+
+// The finish of a row inside the one-pass kernels (Alg. 4, steps 2 and 4-6 for this position), out of the three block sums
+// per chunk in LDS, spread over the wavefronts of the workgroup (all of them have to call it):
+//   1. three wavefronts add up one kind of block sum each in fp64 (sum q', residual mass, alpha) and find the chunk
+//      in which the inverse-CDF threshold of the draft / of the residual draw is crossed;
+//   2. eight wavefronts re-compute a quarter of one of the two chunks each (256 ids, four per lane: the target values
+//      once more from memory, the drafter values of the kept ids through the lane map) and scan it in fp64;
+//   3. with the totals of the quarters before its own, each finds the crossing in its quarter (or its last id with
+//      a positive weight, the answer when rounding leaves no crossing);
+//   4. the first wavefront picks the first crossing, tests acceptance in fp64 and writes the row's outputs.
+// The arithmetic, its order and the conventions are those of the stand-alone finish step (search_block).
+// pm, pinv: softmax maximum and 1 / normaliser of a logit target row (0 and 1 for probabilities); nzs, ths: the row
+// constants of Eq. 3; rcp: 1 / (N + p) as the block sums took it.
+template <int PK, int QK, class RCP>
+__device__ __forceinline__ void row_finish(float *lds, int l_fin, int l_sum_q, int l_sum_r, int l_sum_a,
+                                           const FinalizeArgs &fin, int64_t row, int nchunks,
+                                           const void *pr, float pm, float pinv, const void *qr, float qm,
+                                           const uint64_t *lane_map, const int32_t *chunk_lo, const int32_t *slot_of, int N,
+                                           bool vec_p, float nzs, float ths, const RCP &rcp, int wid, int lane)
+{
+    double *fd = (double *)(lds + l_fin);             // [0..1] local thresholds, [2] alpha, [3] residual mass, [4..11] quarter totals
+    int *fi = (int *)(lds + l_fin + 24);              // [0..1] the two chunks (-1: nothing to draw), [2..5] the uniforms
+    float4 *fc = (float4 *)(lds + l_fin + 32);        // per quarter: crossing id, last positive id, q' and p at the candidate
+    const rdk_verify_desc_t &d = fin.d;
+    const bool draw_draft = d.sample_draft;
+    if (wid < 3) {
+        const float *part = lds + (wid == 0 ? l_sum_q : wid == 1 ? l_sum_r : l_sum_a);
+        const bool wanted = wid == 0 ? draw_draft : true;
+        constexpr int kRegBlocks = 8;
+        const int per_lane = ((nchunks + kWave - 1) / kWave + 3) & ~3;
+        const bool in_regs = per_lane <= kRegBlocks;
+        float v[kRegBlocks];
+        double lane_s = 0.0;
+        if (wanted) {
+            if (in_regs) {
+                load_partials(part, nchunks, per_lane, v);
+                lane_s = sum_partials(v);
+            } else {
+                lane_s = lane_partial_sum(part, nchunks, per_lane);
+            }
+        }
+        const double T = wanted ? wave_sum(lane_s) : 0.0;
+        int blk = -1;
+        double thr = 0.0, before = 0.0;
+        if (wid < 2 && wanted && T > 0.0) {
+            thr = word_to_unit((uint32_t)fi[2 + (wid == 0 ? 0 : 2)]) * T;
+            blk = in_regs ? locate_block_regs(v, nchunks, per_lane, lane_s, thr, before)
+                          : locate_block(part, nchunks, per_lane, lane_s, thr, before);
+        }
+        if (lane == 0) {
+            if (wid < 2) {
+                fi[wid] = blk;
+                fd[wid] = thr - before;
+            }
+            if (wid >= 1) fd[4 - wid] = T;            // wavefront 1: residual mass -> [3], wavefront 2: alpha -> [2]
+        }
+    }
+    __syncthreads();
+    auto value = [&](float qh, float pe) { return (nzs * qh + ths * pe) * rcp(pe); };   // Eq. 3 for one id, as in the sums
+    const int fb = wid >> 2, fq = wid & 3;            // which of the two chunks, which quarter of it
+    const int fblk = wid < 8 ? fi[fb] : -1;
+    const bool factive = fblk >= 0;
+    const int64_t fidx = (int64_t)max(fblk, 0) * kChunk + fq * 256 + lane * 4;
+    float qp4[4] = {0.f, 0.f, 0.f, 0.f}, pv4[4] = {0.f, 0.f, 0.f, 0.f}, wv4[4] = {0.f, 0.f, 0.f, 0.f};
+    double l0 = 0.0, l1 = 0.0, l2 = 0.0, l3 = 0.0, incl = 0.0;
+    int last_pos = -1;
+    if (factive) {
+        const uint64_t map = lane_map[(int64_t)fblk * kWave + lane];
+        const int lo = chunk_lo[fblk];
+        const float4 pl = load4<PK>(pr, fidx, N, vec_p, PK == RDK_PROB_F32 ? 0.f : -INFINITY);
+        const uint32_t kb = (uint32_t)(map >> (4 * fq)) & 0xFu;
+        int sl = lo + (int)((map >> (16 + 12 * fq)) & 0xFFFu);
+        float qraw[4];
+        bool kept_e[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            kept_e[e] = (kb >> e) & 1u;
+            qraw[e] = load1<QK>(qr, kept_e[e] ? sl : 0);   // unconditional: the loads stay batched
+            sl += kept_e[e] ? 1 : 0;
+        }
+        pv4[0] = to_weight<PK>(pl.x, pm, pinv); pv4[1] = to_weight<PK>(pl.y, pm, pinv);
+        pv4[2] = to_weight<PK>(pl.z, pm, pinv); pv4[3] = to_weight<PK>(pl.w, pm, pinv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float qh = kept_e[e] ? to_weight<QK>(qraw[e], qm, 1.f) : 0.f;
+            qp4[e] = fidx + e < N ? value(qh, pv4[e]) : 0.f;
+            wv4[e] = fb == 0 ? qp4[e] : fmaxf(pv4[e] - qp4[e], 0.f);
+        }
+        l0 = (double)wv4[0]; l1 = l0 + (double)wv4[1]; l2 = l1 + (double)wv4[2]; l3 = l2 + (double)wv4[3];
+        incl = wave_inclusive_scan(l3);
+        if (lane == kWave - 1) fd[4 + wid] = incl;
+        const int mine = wv4[3] > 0.f ? 3 : wv4[2] > 0.f ? 2 : wv4[1] > 0.f ? 1 : wv4[0] > 0.f ? 0 : -1;
+        const unsigned long long pos = __ballot(mine >= 0);
+        if (pos != 0ull) last_pos = lane_value((int)fidx + mine, 63 - __clzll(pos));
+    }
+    __syncthreads();
+    if (factive) {
+        double carried = 0.0;
+        for (int i = 0; i < fq; ++i) carried += fd[4 + 4 * fb + i];
+        const double thr_local = fd[fb];
+        const double excl = carried + (incl - l3);
+        const unsigned long long hits = __ballot(excl + l3 > thr_local);
+        int hit = -1;
+        if (hits != 0ull) {
+            const int e = (excl + l0 > thr_local) ? 0 : (excl + l1 > thr_local) ? 1 : (excl + l2 > thr_local) ? 2 : 3;
+            hit = lane_value((int)fidx + e, __ffsll(hits) - 1);
+        }
+        const int cand = hit >= 0 ? hit : last_pos;
+        float qc = 0.f, pc = 0.f;
+        if (cand >= 0) {
+            const int off = cand - (fblk * kChunk + fq * 256), src = off / 4, e = off % 4;
+            qc = lane_value(e == 0 ? qp4[0] : e == 1 ? qp4[1] : e == 2 ? qp4[2] : qp4[3], src);
+            pc = lane_value(e == 0 ? pv4[0] : e == 1 ? pv4[1] : e == 2 ? pv4[2] : pv4[3], src);
+        }
+        if (lane == 0) fc[wid] = make_float4(__int_as_float(hit), __int_as_float(last_pos), qc, pc);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tok[2] = {-1, -1};
+        float qd = 0.f, pd_w = 0.f;
+        for (int b = 0; b < 2; ++b) {
+            if (fi[b] < 0) continue;
+            int chosen = -1;
+            for (int i = 0; i < 4 && chosen < 0; ++i)
+                if (__float_as_int(fc[4 * b + i].x) >= 0) chosen = i;
+            if (chosen < 0)
+                for (int i = 3; i >= 0 && chosen < 0; --i)
+                    if (__float_as_int(fc[4 * b + i].y) >= 0) chosen = i;
+            if (chosen >= 0) {
+                const float4 c4 = fc[4 * b + chosen];
+                tok[b] = __float_as_int(c4.x) >= 0 ? __float_as_int(c4.x) : __float_as_int(c4.y);
+                if (b == 0) {
+                    qd = c4.z;
+                    pd_w = c4.w;
+                }
+            }
+        }
+        int32_t dtok = tok[0];
+        if (!draw_draft) {                            // the caller's draft: its two values are fetched here
+            dtok = fin.draft_ids[row];
+            if (dtok >= 0 && dtok < N) {
+                const int sg = slot_of[dtok];
+                pd_w = to_weight<PK>(load1<PK>(pr, dtok), pm, pinv);
+                qd = value(sg >= 0 ? to_weight<QK>(load1<QK>(qr, sg), qm, 1.f) : 0.f, pd_w);
+            }
+        }
+        const bool d_ok = dtok >= 0 && dtok < N;
+        uint8_t acc = 0;
+        if (d_ok) acc = (word_to_unit((uint32_t)fi[3]) * (double)qd < (double)pd_w) ? 1 : 0;
+        if (draw_draft) fin.draft_ids[row] = dtok;
+        fin.accept[row] = acc;
+        if (fin.alpha) fin.alpha[row] = (float)fd[2];
+        if (fin.resid_mass) fin.resid_mass[row] = (float)fd[3];
+        fin.resid_ids[row] = tok[1];
     }
 }
 
@@ -875,149 +1032,295 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     }
     __syncthreads();
 
-    // ---- the finish of the row (Alg. 4, steps 2 and 4-6 for this position), spread over the wavefronts:
-    //   1. three wavefronts add up one kind of block sum each in fp64 (sum q', residual mass, alpha) and find the chunk
-    //      in which the inverse-CDF threshold of the draft / of the residual draw is crossed;
-    //   2. eight wavefronts re-compute a quarter of one of the two chunks each (256 ids, four per lane: the target values
-    //      once more from memory, the drafter values of the kept ids through the lane map) and scan it in fp64;
-    //   3. with the totals of the quarters before its own, each finds the crossing in its quarter (or its last id with
-    //      a positive weight, the answer when rounding leaves no crossing);
-    //   4. the first wavefront picks the first crossing, tests acceptance in fp64 and writes the row's outputs.
-    // The arithmetic, its order and the conventions are those of the stand-alone finish step (search_block).
-    double *fd = (double *)(lds + L.fin);             // [0..1] local thresholds, [2] alpha, [3] residual mass, [4..11] quarter totals
-    int *fi = (int *)(lds + L.fin + 24);              // [0..1] the two chunks (-1: nothing to draw), [2..5] the uniforms
-    float4 *fc = (float4 *)(lds + L.fin + 32);        // per quarter: crossing id, last positive id, q' and p at the candidate
-    const rdk_verify_desc_t &d = fin.d;
-    const bool draw_draft = d.sample_draft;
-    if (wid < 3) {
-        const float *part = lds + (wid == 0 ? L.sum_q : wid == 1 ? L.sum_r : L.sum_a);
-        const bool wanted = wid == 0 ? draw_draft : true;
-        constexpr int kRegBlocks = 8;
-        const int per_lane = ((nchunks + kWave - 1) / kWave + 3) & ~3;
-        const bool in_regs = per_lane <= kRegBlocks;
-        float v[kRegBlocks];
-        double lane_s = 0.0;
-        if (wanted) {
-            if (in_regs) {
-                load_partials(part, nchunks, per_lane, v);
-                lane_s = sum_partials(v);
-            } else {
-                lane_s = lane_partial_sum(part, nchunks, per_lane);
-            }
-        }
-        const double T = wanted ? wave_sum(lane_s) : 0.0;
-        int blk = -1;
-        double thr = 0.0, before = 0.0;
-        if (wid < 2 && wanted && T > 0.0) {
-            thr = word_to_unit((uint32_t)fi[2 + (wid == 0 ? 0 : 2)]) * T;
-            blk = in_regs ? locate_block_regs(v, nchunks, per_lane, lane_s, thr, before)
-                          : locate_block(part, nchunks, per_lane, lane_s, thr, before);
-        }
-        if (lane == 0) {
-            if (wid < 2) {
-                fi[wid] = blk;
-                fd[wid] = thr - before;
-            }
-            if (wid >= 1) fd[4 - wid] = T;            // wavefront 1: residual mass -> [3], wavefront 2: alpha -> [2]
-        }
-    }
-    __syncthreads();
-    auto value = [&](float qh, float pe) { return (nzs * qh + ths * pe) * rcp(pe); };   // Eq. 3 for one id, as in the sums
-    const int fb = wid >> 2, fq = wid & 3;            // which of the two chunks, which quarter of it
-    const int fblk = wid < 8 ? fi[fb] : -1;
-    const bool factive = fblk >= 0;
-    const int64_t fidx = (int64_t)max(fblk, 0) * kChunk + fq * 256 + lane * 4;
-    float qp4[4] = {0.f, 0.f, 0.f, 0.f}, pv4[4] = {0.f, 0.f, 0.f, 0.f}, wv4[4] = {0.f, 0.f, 0.f, 0.f};
-    double l0 = 0.0, l1 = 0.0, l2 = 0.0, l3 = 0.0, incl = 0.0;
-    int last_pos = -1;
-    if (factive) {
-        const uint64_t map = lane_map[(int64_t)fblk * kWave + lane];
-        const int lo = chunk_lo[fblk];
-        const float4 pl = load4<RDK_PROB_F32>(pr, fidx, N, vec_p, 0.f);
-        const uint32_t kb = (uint32_t)(map >> (4 * fq)) & 0xFu;
-        int sl = lo + (int)((map >> (16 + 12 * fq)) & 0xFFFu);
-        float qraw[4];
-        bool kept_e[4];
+    // ---- the finish of the row (draws, accept test), spread over the wavefronts
+    row_finish<RDK_PROB_F32, QK>(lds, L.fin, L.sum_q, L.sum_r, L.sum_a, fin, row, nchunks, pr, 0.f, 1.f, qr, qm, lane_map, chunk_lo, slot_of, N, vec_p, nzs, ths, rcp,
+                                 wid, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same for LOGIT target rows.  The softmax of the row is not known while it streams, so step A works relative to the
+// maximum of each chunk: e = exp(z - chunk maximum) goes to LDS for the kept ids, and instead of sums of p and p / (N + p)
+// the chunk keeps the power sums of e that their series in x = p / N need (p / (N + p) = x - x^2 + x^3 and
+// N / (N + p) = 1 - x + x^2 - x^3 up to x^4 <= N^-4; used from N = 1024 on): over the not-kept ids sum e, e^2, e^3, over the
+// kept ids the same and sum q^ e^k, k = 0..3.  After the barrier the row maximum is the largest chunk maximum, every
+// chunk's sums are brought to it (factor exp(chunk maximum - row maximum) to the power k), their totals give the softmax
+// normaliser and the row constants of Eq. 3, and steps C and the finish run as for probability rows with
+// p = e * factor / normaliser.  One read of the target row instead of the three of the two-pass path (statistics, sums,
+// verification sums), and one exp per id instead of two.
+enum { kLgMax = 0, kLgS1n, kLgS2n, kLgS3n, kLgS1k, kLgS2k, kLgS3k, kLgQ0, kLgQ1, kLgQ2, kLgQ3, kLgScale };   // chunk statistics
+
+// sum over the 64 lanes, valid in the lanes 48..63
+__device__ __forceinline__ float wave_sum_last(float v)
+{
+    v = row16_sum(v);
+    v += dpp_move<0x142, 0xa>(v);
+    v += dpp_move<0x143, 0xc>(v);
+    return v;
+}
+
+// Step A of the logit variant for one chunk: statistics to `stat` (arrays of nchunks floats), e of the kept ids to LDS.
+template <int QK>
+__device__ __forceinline__ void row_logit_chunk(const RowChunk &b, int c, int lo, int hi, const float4 (&qv)[4], float *pk,
+                                                const float *zero_quad, float *stat, float qm, int nchunks)
+{
+    const int lane = lane_id();
+    float mx = fmaxf(fmaxf(fmaxf(b.p[0].x, b.p[0].y), fmaxf(b.p[0].z, b.p[0].w)), fmaxf(fmaxf(b.p[1].x, b.p[1].y), fmaxf(b.p[1].z, b.p[1].w)));
+    mx = fmaxf(mx, fmaxf(fmaxf(fmaxf(b.p[2].x, b.p[2].y), fmaxf(b.p[2].z, b.p[2].w)), fmaxf(fmaxf(b.p[3].x, b.p[3].y), fmaxf(b.p[3].z, b.p[3].w))));
+    mx = fmaxf(wave_max(mx), -3.0e38f);
+    const uint32_t mask = (uint32_t)b.map & 0xFFFFu;
+    const int run = row_run_start(lo, c);
+    float s1 = 0.f, s2 = 0.f, s3 = 0.f;                // over the ids that are not kept
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        char *at = (char *)(pk + run + (int)((b.map >> (16 + 12 * i)) & 0xFFFu));
+        const float ze[4] = {b.p[i].x, b.p[i].y, b.p[i].z, b.p[i].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            kept_e[e] = (kb >> e) & 1u;
-            qraw[e] = load1<QK>(qr, kept_e[e] ? sl : 0);   // unconditional: the loads stay batched
-            sl += kept_e[e] ? 1 : 0;
+            const uint32_t kept = (mask >> (4 * i + e)) & 1u;
+            const float ev = soft_exp(ze[e] - mx);     // ids beyond N carry -inf: zero
+            if (kept) *(float *)at = ev;
+            at += 4 * kept;
+            const float en = kept ? 0.f : ev, en2 = en * en;
+            s1 += en;
+            s2 += en2;
+            s3 = fmaf(en2, en, s3);
         }
-        pv4[0] = pl.x; pv4[1] = pl.y; pv4[2] = pl.z; pv4[3] = pl.w;
+    }
+    float k1 = 0.f, k2 = 0.f, k3 = 0.f, q0 = 0.f, q1 = 0.f, q2 = 0.f, q3 = 0.f;   // over the kept ids, in slot order
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float qh = kept_e[e] ? to_weight<QK>(qraw[e], qm, 1.f) : 0.f;
-            qp4[e] = fidx + e < N ? value(qh, pv4[e]) : 0.f;
-            wv4[e] = fb == 0 ? qp4[e] : fmaxf(pv4[e] - qp4[e], 0.f);
+    for (int i = 0; i < 4; ++i) {
+        if (lo + 256 * i < hi) {
+            const int o = 4 * (lane + 64 * i);
+            const int left = hi - lo - o;              // slots of the run from the lane's quad on
+            const float4 e4 = *(const float4 *)(left > 0 ? pk + run + o : zero_quad);   // past the run: zeros
+            const float4 w4 = row_weights_of<QK>(qv[i], qm);
+            float qe[4] = {w4.x, w4.y, w4.z, w4.w};
+            const float ee[4] = {e4.x, e4.y, e4.z, e4.w};
+            if (left > 0 && left < 4) {
+#pragma unroll
+                for (int e = 1; e < 4; ++e) qe[e] = e < left ? qe[e] : 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float e2 = ee[e] * ee[e];
+                k1 += ee[e];
+                k2 += e2;
+                k3 = fmaf(e2, ee[e], k3);
+                q0 += qe[e];
+                q1 = fmaf(qe[e], ee[e], q1);
+                q2 = fmaf(qe[e], e2, q2);
+                q3 = fmaf(qe[e] * e2, ee[e], q3);
+            }
         }
-        l0 = (double)wv4[0]; l1 = l0 + (double)wv4[1]; l2 = l1 + (double)wv4[2]; l3 = l2 + (double)wv4[3];
-        incl = wave_inclusive_scan(l3);
-        if (lane == kWave - 1) fd[4 + wid] = incl;
-        const int mine = wv4[3] > 0.f ? 3 : wv4[2] > 0.f ? 2 : wv4[1] > 0.f ? 1 : wv4[0] > 0.f ? 0 : -1;
-        const unsigned long long pos = __ballot(mine >= 0);
-        if (pos != 0ull) last_pos = lane_value((int)fidx + mine, 63 - __clzll(pos));
     }
-    __syncthreads();
-    if (factive) {
-        double carried = 0.0;
-        for (int i = 0; i < fq; ++i) carried += fd[4 + 4 * fb + i];
-        const double thr_local = fd[fb];
-        const double excl = carried + (incl - l3);
-        const unsigned long long hits = __ballot(excl + l3 > thr_local);
-        int hit = -1;
-        if (hits != 0ull) {
-            const int e = (excl + l0 > thr_local) ? 0 : (excl + l1 > thr_local) ? 1 : (excl + l2 > thr_local) ? 2 : 3;
-            hit = lane_value((int)fidx + e, __ffsll(hits) - 1);
-        }
-        const int cand = hit >= 0 ? hit : last_pos;
-        float qc = 0.f, pc = 0.f;
-        if (cand >= 0) {
-            const int off = cand - (fblk * kChunk + fq * 256), src = off / 4, e = off % 4;
-            qc = lane_value(e == 0 ? qp4[0] : e == 1 ? qp4[1] : e == 2 ? qp4[2] : qp4[3], src);
-            pc = lane_value(e == 0 ? pv4[0] : e == 1 ? pv4[1] : e == 2 ? pv4[2] : pv4[3], src);
-        }
-        if (lane == 0) fc[wid] = make_float4(__int_as_float(hit), __int_as_float(last_pos), qc, pc);
+    s1 = wave_sum_last(s1); s2 = wave_sum_last(s2); s3 = wave_sum_last(s3);
+    k1 = wave_sum_last(k1); k2 = wave_sum_last(k2); k3 = wave_sum_last(k3);
+    q0 = wave_sum_last(q0); q1 = wave_sum_last(q1); q2 = wave_sum_last(q2); q3 = wave_sum_last(q3);
+    if (lane == kWave - 1) {
+        stat[kLgMax * nchunks + c] = mx;
+        stat[kLgS1n * nchunks + c] = s1; stat[kLgS2n * nchunks + c] = s2; stat[kLgS3n * nchunks + c] = s3;
+        stat[kLgS1k * nchunks + c] = k1; stat[kLgS2k * nchunks + c] = k2; stat[kLgS3k * nchunks + c] = k3;
+        stat[kLgQ0 * nchunks + c] = q0; stat[kLgQ1 * nchunks + c] = q1; stat[kLgQ2 * nchunks + c] = q2;
+        stat[kLgQ3 * nchunks + c] = q3;
     }
-    __syncthreads();
+}
+
+template <int PK, int QK, bool SERIES>
+__global__ __launch_bounds__(kRowThreads) void taylor_row_logit_kernel(const void *p, int64_t ldp, const void *q, int64_t ldq,
+                                                                       const uint64_t *lane_map, const int32_t *chunk_lo,
+                                                                       const int32_t *item_lo, const int2 *row_items, int N, int n,
+                                                                       bool vec_p, const SoftStat *qstat, const int32_t *slot_of,
+                                                                       FinalizeArgs fin)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const int nchunks = (N + kChunk - 1) / kChunk;
+    const RowLds L = row_lds_layout(n, nchunks);
+    float *pk = lds + L.pk, *stat = lds + L.blk_p;
+    int2 *il = (int2 *)(lds + L.items);
+    int *ilo = (int *)(lds + L.item_lo);
+    float2 *isum = (float2 *)(lds + L.isum);
+    const int64_t row = blockIdx.x;
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
+    const void *pr = row_ptr<PK>(p, ldp, row);
+    const void *qr = row_ptr<QK>(q, ldq, row);
+    const float qm = QK == RDK_PROB_F32 ? 0.f : qstat[row].m;
+    const float fN = (float)N;
+    RowRcp<SERIES> rcp;
+    rcp.fN = fN;
+    rcp.invN = 1.0f / fN;
+    rcp.invN2 = rcp.invN * rcp.invN;
+
+    // ---- prologue: as for probability rows
+    const int max_items = row_max_items(n, nchunks);
+    const int nitems = item_lo[nchunks];
+    int2 it0 = make_int2(0, 0);
+    if ((int)threadIdx.x < max_items) it0 = row_items[threadIdx.x];
+    RowChunk b0, b1, b2;
+    int c = wid;
+    if (c < nchunks) row_fetch<PK>(pr, lane_map, chunk_lo, c, N, vec_p, b0);
+    if (c + kRowWaves < nchunks) row_fetch<PK>(pr, lane_map, chunk_lo, c + kRowWaves, N, vec_p, b1);
     if (threadIdx.x == 0) {
-        int tok[2] = {-1, -1};
-        float qd = 0.f, pd_w = 0.f;
-        for (int b = 0; b < 2; ++b) {
-            if (fi[b] < 0) continue;
-            int chosen = -1;
-            for (int i = 0; i < 4 && chosen < 0; ++i)
-                if (__float_as_int(fc[4 * b + i].x) >= 0) chosen = i;
-            if (chosen < 0)
-                for (int i = 3; i >= 0 && chosen < 0; --i)
-                    if (__float_as_int(fc[4 * b + i].y) >= 0) chosen = i;
-            if (chosen >= 0) {
-                const float4 c4 = fc[4 * b + chosen];
-                tok[b] = __float_as_int(c4.x) >= 0 ? __float_as_int(c4.x) : __float_as_int(c4.y);
-                if (b == 0) {
-                    qd = c4.z;
-                    pd_w = c4.w;
-                }
-            }
-        }
-        int32_t dtok = tok[0];
-        if (!draw_draft) {                            // the caller's draft: its two values are fetched here
-            dtok = fin.draft_ids[row];
-            if (dtok >= 0 && dtok < N) {
-                const int sg = slot_of[dtok];
-                pd_w = pr[dtok];
-                qd = value(sg >= 0 ? to_weight<QK>(load1<QK>(qr, sg), qm, 1.f) : 0.f, pd_w);
-            }
-        }
-        const bool d_ok = dtok >= 0 && dtok < N;
-        uint8_t acc = 0;
-        if (d_ok) acc = (word_to_unit((uint32_t)fi[3]) * (double)qd < (double)pd_w) ? 1 : 0;
-        if (draw_draft) fin.draft_ids[row] = dtok;
-        fin.accept[row] = acc;
-        if (fin.alpha) fin.alpha[row] = (float)fd[2];
-        if (fin.resid_mass) fin.resid_mass[row] = (float)fd[3];
-        fin.resid_ids[row] = tok[1];
+        uint32_t words[4];
+        position_words(fin.d.seed, fin.d.offset + (uint64_t)row, words);
+        uint32_t *fw = (uint32_t *)(lds + L.fin + 26);
+        fw[0] = words[0]; fw[1] = words[1]; fw[2] = words[2]; fw[3] = words[3];
     }
+    {
+        float4 *z = (float4 *)pk;
+        const int quads = (L.blk_p - L.pk) / 4;
+        for (int i = threadIdx.x; i < quads; i += kRowThreads) z[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if ((int)threadIdx.x < max_items) il[threadIdx.x] = it0;
+        for (int k = threadIdx.x + kRowThreads; k < max_items; k += kRowThreads) il[k] = row_items[k];
+        for (int cc = threadIdx.x; cc <= nchunks; cc += kRowThreads) ilo[cc] = item_lo[cc];
+    }
+    __syncthreads();
+
+    // ---- step A
+    float4 qv[4];
+    if (c < nchunks) row_q_fetch<QK>(qr, b0.lo, b0.hi, n, qv);
+#define RDK_ROW_STEP(CUR, NEXT, FREE)                                                                        \
+    {                                                                                                        \
+        if (c + 2 * kRowWaves < nchunks) row_fetch<PK>(pr, lane_map, chunk_lo, c + 2 * kRowWaves, N, vec_p, FREE); \
+        const int lo_c = __builtin_amdgcn_readfirstlane(CUR.lo), hi_c = __builtin_amdgcn_readfirstlane(CUR.hi); \
+        row_logit_chunk<QK>(CUR, c, lo_c, hi_c, qv, pk, lds + L.zero, stat, qm, nchunks);                    \
+        if (c + kRowWaves < nchunks)                                                                         \
+            row_q_fetch<QK>(qr, __builtin_amdgcn_readfirstlane(NEXT.lo), __builtin_amdgcn_readfirstlane(NEXT.hi), n, qv); \
+        c += kRowWaves;                                                                                      \
+    }
+    while (c < nchunks) {
+        RDK_ROW_STEP(b0, b1, b2)
+        if (c >= nchunks) break;
+        RDK_ROW_STEP(b1, b2, b0)
+        if (c >= nchunks) break;
+        RDK_ROW_STEP(b2, b0, b1)
+    }
+#undef RDK_ROW_STEP
+
+    // ---- the pieces of step C: drafter values, LDS offsets and chunks of the first rounds, before the barrier
+    const int grp = threadIdx.x >> 4, li = threadIdx.x & 15;
+    float4 qh[kRowHeld];
+    int pat[kRowHeld], pch[kRowHeld];
+    auto piece_of = [&](int k, int &len, int &chunk) {
+        const int2 it = il[k];
+        len = (int)((uint32_t)it.y >> 24);
+        chunk = it.y & 0x3FFFFF;
+        return 4 * li < len ? L.pk + it.x - ((it.y >> 22) & 3) + 4 * chunk + 4 * li : L.zero;
+    };
+#pragma unroll
+    for (int t = 0; t < kRowHeld; ++t) {
+        const int k = grp + kRowGroups * t;
+        int len = 0, first = 0;
+        pat[t] = L.zero;
+        pch[t] = 0;
+        if (k < nitems) {
+            pat[t] = piece_of(k, len, pch[t]);
+            first = il[k].x;
+        }
+        qh[t] = row_raw_quad<QK>(qr, first + 4 * li, first + len, n);
+    }
+    __syncthreads();
+
+    // ---- the row maximum, the chunk statistics relative to it, their totals
+    float pm = -INFINITY;
+    for (int cc = threadIdx.x; cc < nchunks; cc += kRowThreads) pm = fmaxf(pm, stat[kLgMax * nchunks + cc]);
+    pm = wave_max(pm);
+    if (lane == 0) lds[L.red + wid] = pm;
+    __syncthreads();
+    pm = lds[L.red];
+    for (int i = 1; i < kRowWaves; ++i) pm = fmaxf(pm, lds[L.red + i]);
+    float t7[7] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // sum e, e^2, e^3 over all ids; sum q^ e^k, k = 0..3
+    for (int cc = threadIdx.x; cc < nchunks; cc += kRowThreads) {
+        const float f = soft_exp_fine(stat[kLgMax * nchunks + cc] - pm), f2 = f * f, f3 = f2 * f;   // shared by 1024 ids
+        const float s1n = stat[kLgS1n * nchunks + cc] * f, s2n = stat[kLgS2n * nchunks + cc] * f2, s3n = stat[kLgS3n * nchunks + cc] * f3;
+        const float s1k = stat[kLgS1k * nchunks + cc] * f, s2k = stat[kLgS2k * nchunks + cc] * f2, s3k = stat[kLgS3k * nchunks + cc] * f3;
+        const float q0 = stat[kLgQ0 * nchunks + cc], q1 = stat[kLgQ1 * nchunks + cc] * f, q2 = stat[kLgQ2 * nchunks + cc] * f2;
+        const float q3 = stat[kLgQ3 * nchunks + cc] * f3;
+        stat[kLgS1n * nchunks + cc] = s1n; stat[kLgS2n * nchunks + cc] = s2n; stat[kLgS3n * nchunks + cc] = s3n;
+        stat[kLgS1k * nchunks + cc] = s1k; stat[kLgS2k * nchunks + cc] = s2k; stat[kLgS3k * nchunks + cc] = s3k;
+        stat[kLgQ1 * nchunks + cc] = q1; stat[kLgQ2 * nchunks + cc] = q2; stat[kLgQ3 * nchunks + cc] = q3;
+        stat[kLgScale * nchunks + cc] = f;
+        t7[0] += s1n + s1k; t7[1] += s2n + s2k; t7[2] += s3n + s3k;
+        t7[3] += q0; t7[4] += q1; t7[5] += q2; t7[6] += q3;
+    }
+#pragma unroll
+    for (int j = 0; j < 7; ++j) {
+        const float v = wave_sum_last(t7[j]);
+        if (lane == kWave - 1) lds[L.red + kRowWaves + wid * 8 + j] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 7; ++j) t7[j] = 0.f;
+    for (int i = 0; i < kRowWaves; ++i) {
+        const float4 a4 = *(const float4 *)(lds + L.red + kRowWaves + i * 8), b4 = *(const float4 *)(lds + L.red + kRowWaves + i * 8 + 4);
+        t7[0] += a4.x; t7[1] += a4.y; t7[2] += a4.z; t7[3] += a4.w;
+        t7[4] += b4.x; t7[5] += b4.y; t7[6] += b4.z;
+    }
+    const float pinv = 1.0f / t7[0];                   // the row maximum itself contributes e = 1: never zero
+    const float c1 = pinv / fN, c2 = c1 * c1, c3 = c2 * c1;
+    const float zq = t7[3], tn = t7[4] * pinv;
+    const float an = t7[3] - t7[4] * c1 + t7[5] * c2 - t7[6] * c3;     // sum q^ N / (N + p)
+    const float bs = t7[0] * c1 - t7[1] * c2 + t7[2] * c3;             // sum p / (N + p)
+    const float inv_zq = inv_mass(zq);
+    const float theta = tn * inv_zq;
+    const float inv_S = inv_mass(an * inv_zq + theta * bs);
+    const float nzs = fN * inv_zq * inv_S, ths = theta * inv_S;
+
+    // ---- step C
+    auto piece_sums = [&](int k, const float4 raw, int at, int chunk) {
+        const float g = stat[kLgScale * nchunks + chunk] * pinv;       // e of this chunk -> p
+        const float4 w4 = row_weights_of<QK>(raw, qm);
+        const float4 e4 = *(const float4 *)(lds + at);
+        const float qe[4] = {w4.x, w4.y, w4.z, w4.w}, pe[4] = {e4.x * g, e4.y * g, e4.z * g, e4.w * g};
+        float sr = 0.f, sa = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float v = (nzs * qe[e] + ths * pe[e]) * rcp(pe[e]);
+            const float m = __builtin_amdgcn_fmed3f(pe[e], v, -INFINITY);
+            sa += m;
+            sr += pe[e] - m;
+        }
+        sr = row16_sum(sr);
+        sa = row16_sum(sa);
+        if (li == 0) isum[k] = make_float2(sr, sa);
+    };
+#pragma unroll
+    for (int t = 0; t < kRowHeld; ++t) {
+        const int k = grp + kRowGroups * t;
+        if (k < nitems) piece_sums(k, qh[t], pat[t], pch[t]);
+    }
+    for (int k = grp + kRowGroups * kRowHeld; k < nitems; k += kRowGroups) {
+        int len, chunk;
+        const int at = piece_of(k, len, chunk);
+        const int first = il[k].x;
+        piece_sums(k, row_raw_quad<QK>(qr, first + 4 * li, first + len, n), at, chunk);
+    }
+    __syncthreads();
+
+    // ---- the block sums of a chunk: its pieces in order, and the closed forms from the chunk's power sums.  The three
+    // results take the place of the kept values in LDS (no longer needed), the statistics are read before.
+    for (int cc = grp; cc < nchunks; cc += kRowGroups) {
+        const int k = ilo[cc] + li;
+        const float2 f = k < ilo[cc + 1] ? isum[k] : make_float2(0.f, 0.f);
+        const float sr = row16_sum(f.x), sa = row16_sum(f.y);
+        if (li == 0) {
+            const float s1n = stat[kLgS1n * nchunks + cc], s2n = stat[kLgS2n * nchunks + cc], s3n = stat[kLgS3n * nchunks + cc];
+            const float s1k = stat[kLgS1k * nchunks + cc], s2k = stat[kLgS2k * nchunks + cc], s3k = stat[kLgS3k * nchunks + cc];
+            const float q0 = stat[kLgQ0 * nchunks + cc], q1 = stat[kLgQ1 * nchunks + cc], q2 = stat[kLgQ2 * nchunks + cc];
+            const float q3 = stat[kLgQ3 * nchunks + cc];
+            const float a_nk = s1n * c1 - s2n * c2 + s3n * c3;         // sum p / (N + p), not-kept ids
+            const float a_k = s1k * c1 - s2k * c2 + s3k * c3;          //                  kept ids
+            const float aq = (q0 - q1 * c1 + q2 * c2 - q3 * c3) * rcp.invN;   // sum q^ / (N + p), kept ids
+            const float ta = ths * a_nk;                               // sum of q' (= sum of min(p, q')) over the not-kept ids
+            lds[L.sum_q + cc] = ths * (a_nk + a_k) + nzs * aq;
+            lds[L.sum_a + cc] = ta + sa;
+            lds[L.sum_r + cc] = (s1n * pinv - ta) + sr;
+        }
+    }
+    __syncthreads();
+
+    // ---- the finish of the row (draws, accept test), spread over the wavefronts
+    row_finish<PK, QK>(lds, L.fin, L.sum_q, L.sum_r, L.sum_a, fin, row, nchunks, pr, pm, pinv, qr, qm, lane_map, chunk_lo, slot_of, N, vec_p, nzs, ths, rcp, wid,
+                       lane);
 }
 
 constexpr int kRowSeriesMinN = 4096;   // from here on 1 / (N + p) is taken from its series in p / N (exact to fp32 rounding)
@@ -1061,12 +1364,14 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
 {
     LinearWs w = carve(h, B, ws);
     rdk_status_t rc;
-    if constexpr (PK == RDK_PROB_F32) {
+    {
         // the fused call without q': one pass over the target rows, one workgroup per position, when the kept target
-        // values of a row fit the LDS of a compute unit and there are enough positions to fill the chip
+        // values of a row fit the LDS of a compute unit and there are enough positions to fill the chip (logit rows: from
+        // the vocabulary size on at which the series of their chunk sums are exact to fp32 rounding)
         const int nchunks = (h.N + kChunk - 1) / kChunk;
         const size_t lds_bytes = (size_t)row_lds_layout(h.n, nchunks).total * sizeof(float);
-        if (c && !out && h.N >= 2 && B >= kRowMinBatch && lds_bytes <= row_lds_limit()) {
+        const int min_N = PK == RDK_PROB_F32 ? 2 : kOnePassMinN;
+        if (c && !out && h.N >= min_N && B >= kRowMinBatch && lds_bytes <= row_lds_limit()) {
             if (QK != RDK_PROB_F32) {
                 rc = launch_row_stats<QK>(q, h.n, B, 1, w.qstat, st);
                 if (rc != RDK_OK) return rc;
@@ -1075,10 +1380,17 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
             if (q.kind != RDK_LOGIT_BF16 && ((uintptr_t)q.ptr % 4 != 0)) return RDK_ERR_ALIGN;
             static bool attr_set = false;     // per instantiation: dynamic LDS above the default limit has to be granted once
             if (!attr_set) {
-                RDK_HIP(hipFuncSetAttribute((const void *)taylor_row_kernel<QK, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)row_lds_limit()));
-                RDK_HIP(hipFuncSetAttribute((const void *)taylor_row_kernel<QK, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)row_lds_limit()));
+                if constexpr (PK == RDK_PROB_F32) {
+                    RDK_HIP(hipFuncSetAttribute((const void *)taylor_row_kernel<QK, true>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_lds_limit()));
+                    RDK_HIP(hipFuncSetAttribute((const void *)taylor_row_kernel<QK, false>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_lds_limit()));
+                } else {
+                    RDK_HIP(hipFuncSetAttribute((const void *)taylor_row_logit_kernel<PK, QK, true>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_lds_limit()));
+                    RDK_HIP(hipFuncSetAttribute((const void *)taylor_row_logit_kernel<PK, QK, false>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_lds_limit()));
+                }
                 attr_set = true;
             }
             FinalizeArgs fa{};                // the block sums stay in the workgroup's LDS
@@ -1088,15 +1400,18 @@ rdk_status_t run_taylor(const KernelHandle &h, RowInput p, RowInput q, int32_t B
             fa.nblk = nchunks;
             fa.draft_ids = c->draft_ids; fa.accept = c->accept; fa.alpha = c->alpha; fa.resid_mass = c->resid_mass;
             fa.resid_ids = c->resid_ids; fa.n_accepted = c->n_accepted; fa.out_tokens = c->out_tokens;
-            if (h.N >= kRowSeriesMinN) {
-                RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, true>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
-                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.lane_map, h.chunk_lo, h.item_lo, h.row_items, h.N, h.n,
-                                 vec_p, w.qstat, h.slot_of, fa);
+            const bool series = h.N >= kRowSeriesMinN;
+#define RDK_ROW_LAUNCH(KERNEL, PPTR)                                                                                        \
+    RDK_TIMED_LAUNCH("taylor_row_kernel", KERNEL, dim3((unsigned)B), dim3(kRowThreads), lds_bytes, st, PPTR, p.ld, q.ptr, q.ld,  \
+                     h.lane_map, h.chunk_lo, h.item_lo, h.row_items, h.N, h.n, vec_p, w.qstat, h.slot_of, fa)
+            if constexpr (PK == RDK_PROB_F32) {
+                if (series) RDK_ROW_LAUNCH((taylor_row_kernel<QK, true>), (const float *)p.ptr);
+                else RDK_ROW_LAUNCH((taylor_row_kernel<QK, false>), (const float *)p.ptr);
             } else {
-                RDK_TIMED_LAUNCH("taylor_row_kernel", (taylor_row_kernel<QK, false>), dim3((unsigned)B), dim3(kRowThreads), lds_bytes,
-                                 st, (const float *)p.ptr, p.ld, q.ptr, q.ld, h.lane_map, h.chunk_lo, h.item_lo, h.row_items, h.N, h.n,
-                                 vec_p, w.qstat, h.slot_of, fa);
+                if (series) RDK_ROW_LAUNCH((taylor_row_logit_kernel<PK, QK, true>), p.ptr);
+                else RDK_ROW_LAUNCH((taylor_row_logit_kernel<PK, QK, false>), p.ptr);
             }
+#undef RDK_ROW_LAUNCH
             RDK_LAUNCH_CHECK("taylor_row_kernel");
             if (c->d.gamma > 0 && (fa.n_accepted || fa.out_tokens))
                 return launch_sequence_scan(c->d, fa.draft_ids, fa.accept, fa.resid_ids, fa.n_accepted, fa.out_tokens, st);

@@ -649,32 +649,42 @@ def test_fused_redistribute_verify(rdk, tiny, ragged, case, mode, kinds):
 
 
 @pytest.mark.parametrize("shape", [(4102, 1021, 70, 7), (2049, 2049, 64, 8), (1500, 3, 96, 4), (9000, 4401, 130, 5)])
-@pytest.mark.parametrize("q_kind", ["prob", "logit"])
-def test_fused_eq3_single_pass_ragged_shapes(rdk, shape, q_kind):
+@pytest.mark.parametrize("kinds", [("prob", "prob"), ("prob", "logit"), ("logit", "logit"), ("logit", "prob"), ("bf16", "bf16")])
+def test_fused_eq3_single_pass_ragged_shapes(rdk, shape, kinds):
     """The fused Eq. 3 call without q' takes one pass over the target rows once the batch has 64 positions (one workgroup
-    per position, kept target values parked on chip).  Shapes that end inside a chunk, inside a quad of slots and inside a
-    16-byte word; every id kept; three kept ids; more than half of the ids kept (slot runs longer than the registers
-    hold); rows at a stride that rules the 16-byte paths out.  Against the oracle, and against the two-pass kernels."""
+    per position, kept target values parked on chip; logit target rows from a vocabulary of 1024 ids on, with the softmax
+    folded in: chunk maxima, power sums, one exp per id).  Shapes that end inside a chunk, inside a quad of slots and
+    inside a 16-byte word; every id kept; three kept ids; more than half of the ids kept (slot runs longer than the
+    registers hold); rows at a stride that rules the 16-byte paths out; probability, fp32-logit and bf16-logit rows on
+    either side.  Against the oracle, and against the two-pass kernels."""
     N, n, B, gamma = shape
+    p_kind, q_kind = kinds
     w = synth.scaled(synth.WORKLOADS["tiny"], name="rowshape", N=N, n=n, seqs=B // gamma, gamma=gamma, seed=N + n)
     data = make_inputs(w)
     kept = data["kept_ids"]
     kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.IDENTITY)
-    p64 = data["p"].astype(np.float64)
-    q_in = data["q_hat"] if q_kind == "prob" else data["z_q"]
-    q64 = data["q_hat"].astype(np.float64) if q_kind == "prob" else oracle.probs_from(data["z_q"], "logit")
+    z_p, z_q = data["z_p"], data["z_q"]
+    if p_kind == "bf16":
+        z_p, z_q = synth.bf16_round(z_p), synth.bf16_round(z_q)
+    p64 = data["p"].astype(np.float64) if p_kind == "prob" else oracle.probs_from(z_p, "logit")
+    q64 = data["q_hat"].astype(np.float64) if q_kind == "prob" else oracle.probs_from(z_q, "logit")
+    p_src = data["p"] if p_kind == "prob" else z_p
+    q_src = data["q_hat"] if q_kind == "prob" else z_q
+    dt = torch.bfloat16 if p_kind == "bf16" else torch.float32
+    pk = "prob" if p_kind == "prob" else "logit"
+    qk = "prob" if q_kind == "prob" else "logit"
     ref_qp = oracle.redistribute_batch("taylor", q64, kept, w.N, p=p64)
     seed, offset = 515, 11
     ref = oracle.verify_batch(p64, ref_qp, seed, offset, gamma=gamma)
     for pad in (0, 3):                       # rows of a wider tensor: stride N + 3 keeps the rows off 16-byte boundaries
-        p_big = torch.full((B, N + pad), float("nan"), dtype=torch.float32, device="cuda")
-        q_big = torch.full((B, n + pad), float("nan"), dtype=torch.float32, device="cuda")
-        p_big[:, :N] = dev(data["p"])
-        q_big[:, :n] = dev(q_in)
-        o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, p_big[:, :N], q_big[:, :n], seed, offset, gamma, "prob", q_kind)
-        check_verify_outputs(o, ref, p64, ref_qp, seed, offset, gamma, "prob", min_exact=0.9)
+        p_big = torch.full((B, N + pad), float("nan"), dtype=dt, device="cuda")
+        q_big = torch.full((B, n + pad), float("nan"), dtype=dt, device="cuda")
+        p_big[:, :N] = dev(p_src).to(dt)
+        q_big[:, :n] = dev(q_src).to(dt)
+        o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, p_big[:, :N], q_big[:, :n], seed, offset, gamma, pk, qk)
+        check_verify_outputs(o, ref, p64, ref_qp, seed, offset, gamma, pk, min_exact=0.9)
         qp = torch.empty((B, N), dtype=torch.float32, device="cuda")
-        o2 = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, p_big[:, :N], q_big[:, :n], seed, offset, gamma, "prob", q_kind,
+        o2 = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, p_big[:, :N], q_big[:, :n], seed, offset, gamma, pk, qk,
                                          q_prime=qp)
         assert_close(o.alpha.cpu().numpy(), o2.alpha.cpu().numpy(), what="alpha, one pass against two")
         assert_close(o.resid_mass.cpu().numpy(), o2.resid_mass.cpu().numpy(), what="residual mass, one pass against two")
