@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
     __shared__ float tile[2][kTSlots][kPosBlock + 1];
     const int pb = blockIdx.y;
     const int g0 = blockIdx.x * kTSlots * kTGroup;
-    const int r = threadIdx.x / 8, part = threadIdx.x % 8;     // 8 threads per position, 8 consecutive slots of a tile each
+    const int r = threadIdx.x / 8, part = threadIdx.x % 8;     // 8 threads per position: slots 4 part .. + 3 and 32 + 4 part .. + 3 of a tile
     const int64_t b = (int64_t)pb * kPosBlock + r;
     if (pstat != nullptr && blockIdx.x == 0) {
         // softmax statistics of the logit TARGET rows of this position block, merged once here so that the product
@@ -114,9 +114,9 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
             raw[t][0] = raw[t][1] = make_float4(fill, fill, fill, fill);
             if (b < B) {
                 const void *qr = row_ptr<QK>(q, ldq, b);
-                const int s = g0 + t * kTSlots + part * 8;
+                const int s = g0 + t * kTSlots + part * 4;   // the eight threads of a row read 128 contiguous bytes per load
                 raw[t][0] = load4<QK>(qr, s, n, vec, fill);
-                raw[t][1] = load4<QK>(qr, s + 4, n, vec, fill);
+                raw[t][1] = load4<QK>(qr, s + 32, n, vec, fill);
             }
         }
         float z = 0.f;
@@ -132,19 +132,24 @@ __global__ __launch_bounds__(kPrepThreads) void q_transpose_kernel(const void *q
         z = oct_sum(z);
         if (part == 0 && b < B) zpart[b * zt + blockIdx.x] = z;
     }
-    // tile by tile through LDS: 4 threads per slot write 8 positions each; two tiles alternate, so one barrier per tile
-    const int pq = (threadIdx.x % 4) * 8, sl = threadIdx.x / 4;
+    // tile by tile through LDS: 8 threads per slot write 4 positions each (one 128-byte line per slot and store), 32 slots
+    // per pass; two tiles alternate, so one barrier per tile
+    const int pq = (threadIdx.x % 8) * 4, sl = threadIdx.x / 8;
 #pragma unroll
     for (int t = 0; t < kTGroup; ++t) {
         float (*tl)[kPosBlock + 1] = tile[t & 1];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) tl[part * 8 + e][r] = v[t][e];
+        for (int e = 0; e < 4; ++e) {
+            tl[part * 4 + e][r] = v[t][e];
+            tl[32 + part * 4 + e][r] = v[t][4 + e];
+        }
         __syncthreads();
-        const int s = g0 + t * kTSlots + sl;
-        if (s < n) {
-            float *dst = qT + ((int64_t)pb * n + s) * kPosBlock + pq;
-            *(float4 *)dst = make_float4(tl[sl][pq], tl[sl][pq + 1], tl[sl][pq + 2], tl[sl][pq + 3]);
-            *(float4 *)(dst + 4) = make_float4(tl[sl][pq + 4], tl[sl][pq + 5], tl[sl][pq + 6], tl[sl][pq + 7]);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int s = g0 + t * kTSlots + half * 32 + sl;
+            if (s < n)
+                *(float4 *)(qT + ((int64_t)pb * n + s) * kPosBlock + pq) =
+                    make_float4(tl[half * 32 + sl][pq], tl[half * 32 + sl][pq + 1], tl[half * 32 + sl][pq + 2], tl[half * 32 + sl][pq + 3]);
         }
     }
 }
