@@ -689,6 +689,12 @@ def test_fused_eq3_single_pass_ragged_shapes(rdk, shape, kinds):
         assert_close(o.alpha.cpu().numpy(), o2.alpha.cpu().numpy(), what="alpha, one pass against two")
         assert_close(o.resid_mass.cpu().numpy(), o2.resid_mass.cpu().numpy(), what="residual mass, one pass against two")
         assert (o.draft_ids == o2.draft_ids).float().mean().item() >= 0.95
+    # caller-supplied drafts through the same kernel (their two values are fetched in the finish)
+    drafts = (np.arange(B, dtype=np.int32) * 11) % N
+    o3 = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, p_big[:, :N], q_big[:, :n], seed, offset, gamma, pk, qk,
+                                     draft_ids=dev(drafts))
+    ref3 = oracle.verify_batch(p64, ref_qp, seed, offset, sample_draft=False, draft_ids=drafts, gamma=gamma)
+    check_verify_outputs(o3, ref3, p64, ref_qp, seed, offset, gamma, pk, min_exact=0.9)
 
 
 def test_fused_eq3_single_pass_many_chunks(rdk):
