@@ -356,6 +356,31 @@ def test_verify_degenerate_rows(rdk):
     assert (o.draft_ids.cpu().numpy()[10:20] == 1234).all()
 
 
+def test_fused_sparse_very_large_vocab(rdk):
+    """The sparse form sums per 64-id block; above 262144 ids a row has more block sums than the finish keeps in registers
+    (64 per lane), and they are re-read from memory when the crossings are located.  Drawn and caller-supplied drafts."""
+    w = synth.scaled(synth.WORKLOADS["tiny"], name="widevocab", N=300017, n=3001, k=5, seqs=2, gamma=4, seed=17)
+    data = make_inputs(w)
+    kept = data["kept_ids"]
+    idx, wt, sw = stochastic_topk_kernel(np.random.default_rng(4), w.N, kept, w.k)
+    wt32, sw32 = wt.astype(np.float32), sw.astype(np.float32)
+    kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.SPARSE_TOPK, k=w.k, sparse=(dev(idx), dev(wt32), dev(sw32)))
+    p64 = data["p"].astype(np.float64)
+    ref_qp = oracle.redistribute_batch("sparse", data["q_hat"].astype(np.float64), kept, w.N, sparse=(idx, wt32, sw32))
+    seed, offset = 71, 4
+    o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_SPARSE, dev(data["p"]), dev(data["q_hat"]), seed, offset, w.gamma)
+    check_verify_outputs(o, oracle.verify_batch(p64, ref_qp, seed, offset, gamma=w.gamma), p64, ref_qp, seed, offset, w.gamma, "prob")
+    drafts = (np.arange(w.B, dtype=np.int32) * 50021) % w.N
+    o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_SPARSE, dev(data["p"]), dev(data["q_hat"]), seed, offset, w.gamma,
+                                    draft_ids=dev(drafts))
+    ref = oracle.verify_batch(p64, ref_qp, seed, offset, sample_draft=False, draft_ids=drafts, gamma=w.gamma)
+    check_verify_outputs(o, ref, p64, ref_qp, seed, offset, w.gamma, "prob")
+    d, qd = rdk.rdk_sample_draft(kern, dev(data["q_hat"]), seed, offset)
+    u0 = np.array([oracle.uniforms(seed, offset + b)[0] for b in range(w.B)])
+    ref_d = np.array([oracle.sample_cdf(ref_qp[b], u0[b]) for b in range(w.B)])
+    check_sampled_ids(ref_qp, u0, d.cpu().numpy(), ref_d, what="draft from q'")
+
+
 def test_verify_very_large_vocab(rdk):
     """More 1024-id blocks per row than a wavefront keeps in registers (N > 2^19): the block partials are then
     re-read from memory when the prefix-sum crossings are located."""
