@@ -1059,7 +1059,8 @@ __device__ __forceinline__ float wave_sum_last(float v)
 }
 
 // Step A of the logit variant for one chunk: statistics to `stat` (arrays of nchunks floats), e of the kept ids to LDS.
-template <int QK>
+// CUBIC = false (N >= 4096): the third-order terms of the series are below 2^-24 of the first and are left out.
+template <int QK, bool CUBIC>
 __device__ __forceinline__ void row_logit_chunk(const RowChunk &b, int c, int lo, int hi, const float4 (&qv)[4], float *pk,
                                                 const float *zero_quad, float *stat, float qm, int nchunks)
 {
@@ -1083,7 +1084,7 @@ __device__ __forceinline__ void row_logit_chunk(const RowChunk &b, int c, int lo
             const float en = kept ? 0.f : ev, en2 = en * en;
             s1 += en;
             s2 += en2;
-            s3 = fmaf(en2, en, s3);
+            if (CUBIC) s3 = fmaf(en2, en, s3);
         }
     }
     float k1 = 0.f, k2 = 0.f, k3 = 0.f, q0 = 0.f, q1 = 0.f, q2 = 0.f, q3 = 0.f;   // over the kept ids, in slot order
@@ -1105,17 +1106,22 @@ __device__ __forceinline__ void row_logit_chunk(const RowChunk &b, int c, int lo
                 const float e2 = ee[e] * ee[e];
                 k1 += ee[e];
                 k2 += e2;
-                k3 = fmaf(e2, ee[e], k3);
                 q0 += qe[e];
                 q1 = fmaf(qe[e], ee[e], q1);
                 q2 = fmaf(qe[e], e2, q2);
-                q3 = fmaf(qe[e] * e2, ee[e], q3);
+                if (CUBIC) {
+                    k3 = fmaf(e2, ee[e], k3);
+                    q3 = fmaf(qe[e] * e2, ee[e], q3);
+                }
             }
         }
     }
-    s1 = wave_sum_last(s1); s2 = wave_sum_last(s2); s3 = wave_sum_last(s3);
-    k1 = wave_sum_last(k1); k2 = wave_sum_last(k2); k3 = wave_sum_last(k3);
-    q0 = wave_sum_last(q0); q1 = wave_sum_last(q1); q2 = wave_sum_last(q2); q3 = wave_sum_last(q3);
+    s1 = wave_sum_last(s1); s2 = wave_sum_last(s2);
+    k1 = wave_sum_last(k1); k2 = wave_sum_last(k2);
+    q0 = wave_sum_last(q0); q1 = wave_sum_last(q1); q2 = wave_sum_last(q2);
+    if (CUBIC) {
+        s3 = wave_sum_last(s3); k3 = wave_sum_last(k3); q3 = wave_sum_last(q3);
+    }
     if (lane == kWave - 1) {
         stat[kLgMax * nchunks + c] = mx;
         stat[kLgS1n * nchunks + c] = s1; stat[kLgS2n * nchunks + c] = s2; stat[kLgS3n * nchunks + c] = s3;
@@ -1182,7 +1188,7 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_logit_kernel(const voi
     {                                                                                                        \
         if (c + 2 * kRowWaves < nchunks) row_fetch<PK>(pr, lane_map, chunk_lo, c + 2 * kRowWaves, N, vec_p, FREE); \
         const int lo_c = __builtin_amdgcn_readfirstlane(CUR.lo), hi_c = __builtin_amdgcn_readfirstlane(CUR.hi); \
-        row_logit_chunk<QK>(CUR, c, lo_c, hi_c, qv, pk, lds + L.zero, stat, qm, nchunks);                    \
+        row_logit_chunk<QK, !SERIES>(CUR, c, lo_c, hi_c, qv, pk, lds + L.zero, stat, qm, nchunks);           \
         if (c + kRowWaves < nchunks)                                                                         \
             row_q_fetch<QK>(qr, __builtin_amdgcn_readfirstlane(NEXT.lo), __builtin_amdgcn_readfirstlane(NEXT.hi), n, qv); \
         c += kRowWaves;                                                                                      \
