@@ -550,6 +550,197 @@ __global__ __launch_bounds__(4 * kWave) void verify_finalize_wide_kernel(Finaliz
     }
 }
 
+// ---- The finish of one row by eight wavefronts, for block sums over 1024 ids (Alg. 4, steps 2 and 4-6 for one position).
+// A lone wavefront pays the full latency of every dependent step; here
+//   1. three wavefronts add up one kind of block sum each in fp64 (sum q', residual mass, alpha) and find the block
+//      in which the inverse-CDF threshold of the draft / of the residual draw is crossed;
+//   2. eight wavefronts take a quarter of one of the two blocks each (256 ids, four per lane: the target values from
+//      memory, q' from the policy) and scan it in fp64;
+//   3. with the totals of the quarters before its own, each finds the crossing in its quarter (or its last id with
+//      a positive weight, the answer when rounding leaves no crossing);
+//   4. the first wavefront picks the first crossing, tests acceptance in fp64 and writes the row's outputs.
+// The arithmetic, its order and the conventions are those of the one-wavefront finish (finalize_row, search_block).
+// Every wavefront of the workgroup calls it (more than eight may; the others only meet the barriers).
+//   scratch        kFinishFloats floats of LDS
+//   sq, sr, sa     the row's nblk block sums of q', max(0, p - q') and min(p, q') (LDS or memory)
+//   pm, pinv       softmax maximum and 1 / normaliser of a logit target row (0 and 1 for probabilities)
+//   words          the position's four uniforms (Alg. 4: draft, accept, residual, bonus)
+//   quads          where q' comes from: begin() issues the loads that need no target value, end() hands out q' of four
+//                  ids given their target weights, at() q' of one id
+constexpr int kFinishFloats = 64;
+
+template <int KIND, class Quads>
+__device__ __forceinline__ void finish_row_quarters(float *scratch, const float *sq, const float *sr, const float *sa, int nblk,
+                                                    const FinalizeArgs &fin, int64_t row, const void *pr, float pm, float pinv,
+                                                    int N, bool vec_p, const Quads &quads, const uint32_t (&words)[4], int wid,
+                                                    int lane)
+{
+    constexpr int kBlock = 1024;
+    double *fd = (double *)scratch;                   // [0..1] local thresholds, [2] alpha, [3] residual mass, [4..11] quarter totals
+    int *fi = (int *)(scratch + 24);                  // [0..1] the two blocks (-1: nothing to draw)
+    float4 *fc = (float4 *)(scratch + 32);            // per quarter: crossing id, last positive id, q' and p at the candidate
+    const rdk_verify_desc_t &d = fin.d;
+    const bool draw_draft = d.sample_draft;
+    if (wid < 3) {
+        const float *part = wid == 0 ? sq : wid == 1 ? sr : sa;
+        const bool wanted = wid == 0 ? draw_draft : true;
+        constexpr int kRegBlocks = 8;
+        const int per_lane = ((nblk + kWave - 1) / kWave + 3) & ~3;
+        const bool in_regs = per_lane <= kRegBlocks;
+        float v[kRegBlocks];
+        double lane_s = 0.0;
+        if (wanted) {
+            if (in_regs) {
+                load_partials(part, nblk, per_lane, v);
+                lane_s = sum_partials(v);
+            } else {
+                lane_s = lane_partial_sum(part, nblk, per_lane);
+            }
+        }
+        const double T = wanted ? wave_sum(lane_s) : 0.0;
+        int blk = -1;
+        double thr = 0.0, before = 0.0;
+        if (wid < 2 && wanted && T > 0.0) {
+            thr = word_to_unit(words[wid == 0 ? 0 : 2]) * T;
+            blk = in_regs ? locate_block_regs(v, nblk, per_lane, lane_s, thr, before)
+                          : locate_block(part, nblk, per_lane, lane_s, thr, before);
+        }
+        if (lane == 0) {
+            if (wid < 2) {
+                fi[wid] = blk;
+                fd[wid] = thr - before;
+            }
+            if (wid >= 1) fd[4 - wid] = T;            // wavefront 1: residual mass -> [3], wavefront 2: alpha -> [2]
+        }
+    }
+    __syncthreads();
+    const int fb = wid >> 2, fq = wid & 3;            // which of the two blocks, which quarter of it
+    const int fblk = wid < 8 ? fi[fb] : -1;
+    const bool factive = fblk >= 0;
+    const int64_t fidx = (int64_t)max(fblk, 0) * kBlock + fq * 256 + lane * 4;
+    float qp4[4] = {0.f, 0.f, 0.f, 0.f}, pv4[4] = {0.f, 0.f, 0.f, 0.f}, wv4[4] = {0.f, 0.f, 0.f, 0.f};
+    double l0 = 0.0, l1 = 0.0, l2 = 0.0, l3 = 0.0, incl = 0.0;
+    int last_pos = -1;
+    if (factive) {
+        typename Quads::Token t = quads.begin(fblk, fq, fidx);
+        const float4 pl = load4<KIND>(pr, fidx, N, vec_p, KIND == RDK_PROB_F32 ? 0.f : -INFINITY);
+        pv4[0] = to_weight<KIND>(pl.x, pm, pinv); pv4[1] = to_weight<KIND>(pl.y, pm, pinv);
+        pv4[2] = to_weight<KIND>(pl.z, pm, pinv); pv4[3] = to_weight<KIND>(pl.w, pm, pinv);
+        quads.end(t, fidx, pv4, qp4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wv4[e] = fb == 0 ? qp4[e] : fmaxf(pv4[e] - qp4[e], 0.f);
+        l0 = (double)wv4[0]; l1 = l0 + (double)wv4[1]; l2 = l1 + (double)wv4[2]; l3 = l2 + (double)wv4[3];
+        incl = wave_inclusive_scan(l3);
+        if (lane == kWave - 1) fd[4 + wid] = incl;
+        const int mine = wv4[3] > 0.f ? 3 : wv4[2] > 0.f ? 2 : wv4[1] > 0.f ? 1 : wv4[0] > 0.f ? 0 : -1;
+        const unsigned long long pos = __ballot(mine >= 0);
+        if (pos != 0ull) last_pos = lane_value((int)fidx + mine, 63 - __clzll(pos));
+    }
+    __syncthreads();
+    if (factive) {
+        double carried = 0.0;
+        for (int i = 0; i < fq; ++i) carried += fd[4 + 4 * fb + i];
+        const double thr_local = fd[fb];
+        const double excl = carried + (incl - l3);
+        const unsigned long long hits = __ballot(excl + l3 > thr_local);
+        int hit = -1;
+        if (hits != 0ull) {
+            const int e = (excl + l0 > thr_local) ? 0 : (excl + l1 > thr_local) ? 1 : (excl + l2 > thr_local) ? 2 : 3;
+            hit = lane_value((int)fidx + e, __ffsll(hits) - 1);
+        }
+        const int cand = hit >= 0 ? hit : last_pos;
+        float qc = 0.f, pc = 0.f;
+        if (cand >= 0) {
+            const int off = cand - (fblk * kBlock + fq * 256), src = off / 4, e = off % 4;
+            qc = lane_value(e == 0 ? qp4[0] : e == 1 ? qp4[1] : e == 2 ? qp4[2] : qp4[3], src);
+            pc = lane_value(e == 0 ? pv4[0] : e == 1 ? pv4[1] : e == 2 ? pv4[2] : pv4[3], src);
+        }
+        if (lane == 0) fc[wid] = make_float4(__int_as_float(hit), __int_as_float(last_pos), qc, pc);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int tok[2] = {-1, -1};
+        float qd = 0.f, pd_w = 0.f;
+        for (int b = 0; b < 2; ++b) {
+            if (fi[b] < 0) continue;
+            int chosen = -1;
+            for (int i = 0; i < 4 && chosen < 0; ++i)
+                if (__float_as_int(fc[4 * b + i].x) >= 0) chosen = i;
+            if (chosen < 0)
+                for (int i = 3; i >= 0 && chosen < 0; --i)
+                    if (__float_as_int(fc[4 * b + i].y) >= 0) chosen = i;
+            if (chosen >= 0) {
+                const float4 c4 = fc[4 * b + chosen];
+                tok[b] = __float_as_int(c4.x) >= 0 ? __float_as_int(c4.x) : __float_as_int(c4.y);
+                if (b == 0) {
+                    qd = c4.z;
+                    pd_w = c4.w;
+                }
+            }
+        }
+        int32_t dtok = tok[0];
+        if (!draw_draft) {                            // the caller's draft: its two values are fetched here
+            dtok = fin.draft_ids[row];
+            if (dtok >= 0 && dtok < N) {
+                pd_w = to_weight<KIND>(load1<KIND>(pr, dtok), pm, pinv);
+                qd = quads.at(dtok, pd_w);
+            }
+        }
+        const bool d_ok = dtok >= 0 && dtok < N;
+        uint8_t acc = 0;
+        if (d_ok) acc = (word_to_unit(words[1]) * (double)qd < (double)pd_w) ? 1 : 0;
+        if (draw_draft) fin.draft_ids[row] = dtok;
+        fin.accept[row] = acc;
+        if (fin.alpha) fin.alpha[row] = (float)fd[2];
+        if (fin.resid_mass) fin.resid_mass[row] = (float)fd[3];
+        fin.resid_ids[row] = tok[1];
+    }
+}
+
+// q' of four ids from a policy's row (its steps run back to back: one quarter of a block per wavefront).
+template <class Row, int STAGES>
+struct PolicyQuads {
+    const Row &r;
+    typedef typename Row::Pending Token;
+    __device__ __forceinline__ Token begin(int, int, int64_t fidx) const
+    {
+        Token t;
+        r.template stage<0>(t, fidx);
+        return t;
+    }
+    __device__ __forceinline__ void end(Token &t, int64_t fidx, const float (&)[4], float (&qp4)[4]) const
+    {
+        if (STAGES > 1) r.template stage<1>(t, fidx);
+        if (STAGES > 2) r.template stage<2>(t, fidx);
+        const float4 v = r.result(t, fidx);
+        qp4[0] = v.x; qp4[1] = v.y; qp4[2] = v.z; qp4[3] = v.w;
+    }
+    __device__ __forceinline__ float at(int dtok, float) const { return r.load1(dtok); }
+};
+
+// One row per workgroup of eight wavefronts, block sums over 1024 ids in memory.
+template <int KIND, class QP>
+__global__ __launch_bounds__(8 * kWave) void verify_finalize_quarters_kernel(FinalizeArgs a, QP qp)
+{
+    __shared__ __attribute__((aligned(16))) float scratch[kFinishFloats];
+    const rdk_verify_desc_t &d = a.d;
+    const int wid = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = lane_id();
+    const int64_t row = blockIdx.x;
+    const void *pr = row_ptr<KIND>(a.p, a.ldp, row);
+    float m = 0.f, inv = 1.f;
+    if (KIND != RDK_PROB_F32) {
+        const SoftStat rs = merged_row_stat<KIND>(a.pstat, a.p_splits, row);
+        m = rs.m;
+        inv = 1.0f / rs.s;
+    }
+    uint32_t words[4];
+    position_words(d.seed, d.offset + (uint64_t)row, words);
+    const typename QP::Row qrow = qp.row(row);
+    const PolicyQuads<typename QP::Row, QP::kStages> quads{qrow};
+    finish_row_quarters<KIND>(scratch, a.part_q + row * a.nblk, a.part_r + row * a.nblk, a.part_a + row * a.nblk, a.nblk, a, row, pr,
+                              m, inv, d.N, a.vec_p, quads, words, wid, lane);
+}
+
 // ---- Draft draw alone (Alg. 4 step 2 on the drafter's side, before a target row exists): one wavefront per row,
 // block sums of q' in, the drafted id and q' at that id out.
 struct DraftArgs {
@@ -654,6 +845,11 @@ rdk_status_t launch_finalize(FinalizeArgs a, QP qp, hipStream_t st)
     if constexpr (QP::kSpreadRows && BLOCK == 64 && HAS_Q) {
         RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_wide_kernel<KIND, QP>), dim3((unsigned)d.B), dim3(4 * kWave), 0,
                          st, a, qp);
+    } else if (BLOCK == 1024 && HAS_Q && spread) {
+        if constexpr (BLOCK == 1024 && HAS_Q) {
+            RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_quarters_kernel<KIND, QP>), dim3((unsigned)d.B),
+                             dim3(8 * kWave), 0, st, a, qp);
+        }
     } else {
         RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_kernel<KIND, BLOCK, HAS_Q, QP>), dim3(blocks),
                          dim3(a.rows_per_block * kWave), 0, st, a, qp);

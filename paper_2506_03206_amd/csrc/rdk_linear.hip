@@ -546,7 +546,7 @@ __host__ __device__ inline RowLds row_lds_layout(int n, int nchunks)
     L.sum_q = L.pk;
     L.sum_r = L.sum_q + ((nchunks + 3) & ~3);
     L.sum_a = L.sum_r + ((nchunks + 3) & ~3);
-    L.fin = off; off += 64;                            // what the wavefronts of the finish step hand to each other
+    L.fin = off; off += kFinishFloats + 4;             // what the wavefronts of the finish step hand to each other, the uniforms
     L.total = off;
     return L;
 }
@@ -694,77 +694,29 @@ __device__ __forceinline__ void row_kept_sums(int c, int lo, int hi, const float
     }
 }
 
-// The finish of a row inside the one-pass kernels (Alg. 4, steps 2 and 4-6 for this position), out of the three block sums
-// per chunk in LDS, spread over the wavefronts of the workgroup (all of them have to call it):
-//   1. three wavefronts add up one kind of block sum each in fp64 (sum q', residual mass, alpha) and find the chunk
-//      in which the inverse-CDF threshold of the draft / of the residual draw is crossed;
-//   2. eight wavefronts re-compute a quarter of one of the two chunks each (256 ids, four per lane: the target values
-//      once more from memory, the drafter values of the kept ids through the lane map) and scan it in fp64;
-//   3. with the totals of the quarters before its own, each finds the crossing in its quarter (or its last id with
-//      a positive weight, the answer when rounding leaves no crossing);
-//   4. the first wavefront picks the first crossing, tests acceptance in fp64 and writes the row's outputs.
-// The arithmetic, its order and the conventions are those of the stand-alone finish step (search_block).
-// pm, pinv: softmax maximum and 1 / normaliser of a logit target row (0 and 1 for probabilities); nzs, ths: the row
-// constants of Eq. 3; rcp: 1 / (N + p) as the block sums took it.
-template <int PK, int QK, class RCP>
-__device__ __forceinline__ void row_finish(float *lds, int l_fin, int l_sum_q, int l_sum_r, int l_sum_a,
-                                           const FinalizeArgs &fin, int64_t row, int nchunks,
-                                           const void *pr, float pm, float pinv, const void *qr, float qm,
-                                           const uint64_t *lane_map, const int32_t *chunk_lo, const int32_t *slot_of, int N,
-                                           bool vec_p, float nzs, float ths, const RCP &rcp, int wid, int lane)
-{
-    double *fd = (double *)(lds + l_fin);             // [0..1] local thresholds, [2] alpha, [3] residual mass, [4..11] quarter totals
-    int *fi = (int *)(lds + l_fin + 24);              // [0..1] the two chunks (-1: nothing to draw), [2..5] the uniforms
-    float4 *fc = (float4 *)(lds + l_fin + 32);        // per quarter: crossing id, last positive id, q' and p at the candidate
-    const rdk_verify_desc_t &d = fin.d;
-    const bool draw_draft = d.sample_draft;
-    if (wid < 3) {
-        const float *part = lds + (wid == 0 ? l_sum_q : wid == 1 ? l_sum_r : l_sum_a);
-        const bool wanted = wid == 0 ? draw_draft : true;
-        constexpr int kRegBlocks = 8;
-        const int per_lane = ((nchunks + kWave - 1) / kWave + 3) & ~3;
-        const bool in_regs = per_lane <= kRegBlocks;
-        float v[kRegBlocks];
-        double lane_s = 0.0;
-        if (wanted) {
-            if (in_regs) {
-                load_partials(part, nchunks, per_lane, v);
-                lane_s = sum_partials(v);
-            } else {
-                lane_s = lane_partial_sum(part, nchunks, per_lane);
-            }
-        }
-        const double T = wanted ? wave_sum(lane_s) : 0.0;
-        int blk = -1;
-        double thr = 0.0, before = 0.0;
-        if (wid < 2 && wanted && T > 0.0) {
-            thr = word_to_unit((uint32_t)fi[2 + (wid == 0 ? 0 : 2)]) * T;
-            blk = in_regs ? locate_block_regs(v, nchunks, per_lane, lane_s, thr, before)
-                          : locate_block(part, nchunks, per_lane, lane_s, thr, before);
-        }
-        if (lane == 0) {
-            if (wid < 2) {
-                fi[wid] = blk;
-                fd[wid] = thr - before;
-            }
-            if (wid >= 1) fd[4 - wid] = T;            // wavefront 1: residual mass -> [3], wavefront 2: alpha -> [2]
-        }
+// q' of Eq. 3 for the finish of a row inside the one-pass kernels (finish_row_quarters): the drafter values of the kept ids
+// of a quarter chunk through the lane map, the row constants nzs and ths, and 1 / (N + p) as the block sums took it.
+template <int QK, class RCP>
+struct Eq3Quads {
+    const uint64_t *lane_map;
+    const int32_t *chunk_lo, *slot_of;
+    const void *qr;
+    float qm, nzs, ths;
+    const RCP &rcp;
+    int N;
+    struct Token {
+        uint64_t map;
+        int lo, fq;
+    };
+    __device__ __forceinline__ float value(float qh, float pe) const { return (nzs * qh + ths * pe) * rcp(pe); }
+    __device__ __forceinline__ Token begin(int fblk, int fq, int64_t) const
+    {
+        return Token{lane_map[(int64_t)fblk * kWave + lane_id()], chunk_lo[fblk], fq};
     }
-    __syncthreads();
-    auto value = [&](float qh, float pe) { return (nzs * qh + ths * pe) * rcp(pe); };   // Eq. 3 for one id, as in the sums
-    const int fb = wid >> 2, fq = wid & 3;            // which of the two chunks, which quarter of it
-    const int fblk = wid < 8 ? fi[fb] : -1;
-    const bool factive = fblk >= 0;
-    const int64_t fidx = (int64_t)max(fblk, 0) * kChunk + fq * 256 + lane * 4;
-    float qp4[4] = {0.f, 0.f, 0.f, 0.f}, pv4[4] = {0.f, 0.f, 0.f, 0.f}, wv4[4] = {0.f, 0.f, 0.f, 0.f};
-    double l0 = 0.0, l1 = 0.0, l2 = 0.0, l3 = 0.0, incl = 0.0;
-    int last_pos = -1;
-    if (factive) {
-        const uint64_t map = lane_map[(int64_t)fblk * kWave + lane];
-        const int lo = chunk_lo[fblk];
-        const float4 pl = load4<PK>(pr, fidx, N, vec_p, PK == RDK_PROB_F32 ? 0.f : -INFINITY);
-        const uint32_t kb = (uint32_t)(map >> (4 * fq)) & 0xFu;
-        int sl = lo + (int)((map >> (16 + 12 * fq)) & 0xFFFu);
+    __device__ __forceinline__ void end(Token &t, int64_t fidx, const float (&pv4)[4], float (&qp4)[4]) const
+    {
+        const uint32_t kb = (uint32_t)(t.map >> (4 * t.fq)) & 0xFu;
+        int sl = t.lo + (int)((t.map >> (16 + 12 * t.fq)) & 0xFFFu);
         float qraw[4];
         bool kept_e[4];
 #pragma unroll
@@ -773,81 +725,34 @@ __device__ __forceinline__ void row_finish(float *lds, int l_fin, int l_sum_q, i
             qraw[e] = load1<QK>(qr, kept_e[e] ? sl : 0);   // unconditional: the loads stay batched
             sl += kept_e[e] ? 1 : 0;
         }
-        pv4[0] = to_weight<PK>(pl.x, pm, pinv); pv4[1] = to_weight<PK>(pl.y, pm, pinv);
-        pv4[2] = to_weight<PK>(pl.z, pm, pinv); pv4[3] = to_weight<PK>(pl.w, pm, pinv);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const float qh = kept_e[e] ? to_weight<QK>(qraw[e], qm, 1.f) : 0.f;
             qp4[e] = fidx + e < N ? value(qh, pv4[e]) : 0.f;
-            wv4[e] = fb == 0 ? qp4[e] : fmaxf(pv4[e] - qp4[e], 0.f);
         }
-        l0 = (double)wv4[0]; l1 = l0 + (double)wv4[1]; l2 = l1 + (double)wv4[2]; l3 = l2 + (double)wv4[3];
-        incl = wave_inclusive_scan(l3);
-        if (lane == kWave - 1) fd[4 + wid] = incl;
-        const int mine = wv4[3] > 0.f ? 3 : wv4[2] > 0.f ? 2 : wv4[1] > 0.f ? 1 : wv4[0] > 0.f ? 0 : -1;
-        const unsigned long long pos = __ballot(mine >= 0);
-        if (pos != 0ull) last_pos = lane_value((int)fidx + mine, 63 - __clzll(pos));
     }
-    __syncthreads();
-    if (factive) {
-        double carried = 0.0;
-        for (int i = 0; i < fq; ++i) carried += fd[4 + 4 * fb + i];
-        const double thr_local = fd[fb];
-        const double excl = carried + (incl - l3);
-        const unsigned long long hits = __ballot(excl + l3 > thr_local);
-        int hit = -1;
-        if (hits != 0ull) {
-            const int e = (excl + l0 > thr_local) ? 0 : (excl + l1 > thr_local) ? 1 : (excl + l2 > thr_local) ? 2 : 3;
-            hit = lane_value((int)fidx + e, __ffsll(hits) - 1);
-        }
-        const int cand = hit >= 0 ? hit : last_pos;
-        float qc = 0.f, pc = 0.f;
-        if (cand >= 0) {
-            const int off = cand - (fblk * kChunk + fq * 256), src = off / 4, e = off % 4;
-            qc = lane_value(e == 0 ? qp4[0] : e == 1 ? qp4[1] : e == 2 ? qp4[2] : qp4[3], src);
-            pc = lane_value(e == 0 ? pv4[0] : e == 1 ? pv4[1] : e == 2 ? pv4[2] : pv4[3], src);
-        }
-        if (lane == 0) fc[wid] = make_float4(__int_as_float(hit), __int_as_float(last_pos), qc, pc);
+    __device__ __forceinline__ float at(int dtok, float pd_w) const
+    {
+        const int sg = slot_of[dtok];
+        return value(sg >= 0 ? to_weight<QK>(load1<QK>(qr, sg), qm, 1.f) : 0.f, pd_w);
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int tok[2] = {-1, -1};
-        float qd = 0.f, pd_w = 0.f;
-        for (int b = 0; b < 2; ++b) {
-            if (fi[b] < 0) continue;
-            int chosen = -1;
-            for (int i = 0; i < 4 && chosen < 0; ++i)
-                if (__float_as_int(fc[4 * b + i].x) >= 0) chosen = i;
-            if (chosen < 0)
-                for (int i = 3; i >= 0 && chosen < 0; --i)
-                    if (__float_as_int(fc[4 * b + i].y) >= 0) chosen = i;
-            if (chosen >= 0) {
-                const float4 c4 = fc[4 * b + chosen];
-                tok[b] = __float_as_int(c4.x) >= 0 ? __float_as_int(c4.x) : __float_as_int(c4.y);
-                if (b == 0) {
-                    qd = c4.z;
-                    pd_w = c4.w;
-                }
-            }
-        }
-        int32_t dtok = tok[0];
-        if (!draw_draft) {                            // the caller's draft: its two values are fetched here
-            dtok = fin.draft_ids[row];
-            if (dtok >= 0 && dtok < N) {
-                const int sg = slot_of[dtok];
-                pd_w = to_weight<PK>(load1<PK>(pr, dtok), pm, pinv);
-                qd = value(sg >= 0 ? to_weight<QK>(load1<QK>(qr, sg), qm, 1.f) : 0.f, pd_w);
-            }
-        }
-        const bool d_ok = dtok >= 0 && dtok < N;
-        uint8_t acc = 0;
-        if (d_ok) acc = (word_to_unit((uint32_t)fi[3]) * (double)qd < (double)pd_w) ? 1 : 0;
-        if (draw_draft) fin.draft_ids[row] = dtok;
-        fin.accept[row] = acc;
-        if (fin.alpha) fin.alpha[row] = (float)fd[2];
-        if (fin.resid_mass) fin.resid_mass[row] = (float)fd[3];
-        fin.resid_ids[row] = tok[1];
-    }
+};
+
+// The finish of a row inside the one-pass kernels, out of the three block sums per chunk in LDS and the position's
+// uniforms that the kernel left behind them (all wavefronts of the workgroup have to call it).
+// pm, pinv: softmax maximum and 1 / normaliser of a logit target row (0 and 1 for probabilities).
+template <int PK, int QK, class RCP>
+__device__ __forceinline__ void row_finish(float *lds, int l_fin, int l_sum_q, int l_sum_r, int l_sum_a,
+                                           const FinalizeArgs &fin, int64_t row, int nchunks,
+                                           const void *pr, float pm, float pinv, const void *qr, float qm,
+                                           const uint64_t *lane_map, const int32_t *chunk_lo, const int32_t *slot_of, int N,
+                                           bool vec_p, float nzs, float ths, const RCP &rcp, int wid, int lane)
+{
+    const uint32_t *fw = (const uint32_t *)(lds + l_fin + kFinishFloats);
+    const uint32_t words[4] = {fw[0], fw[1], fw[2], fw[3]};
+    const Eq3Quads<QK, RCP> quads{lane_map, chunk_lo, slot_of, qr, qm, nzs, ths, rcp, N};
+    finish_row_quarters<PK>(lds + l_fin, lds + l_sum_q, lds + l_sum_r, lds + l_sum_a, nchunks, fin, row, pr, pm, pinv, N, vec_p,
+                            quads, words, wid, lane);
 }
 
 template <int QK, bool SERIES>
@@ -888,7 +793,7 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_kernel(const float *p,
     if (threadIdx.x == 0) {                           // the position's four uniforms (Alg. 4: draft, accept, residual, bonus)
         uint32_t words[4];
         position_words(fin.d.seed, fin.d.offset + (uint64_t)row, words);
-        uint32_t *fw = (uint32_t *)(lds + L.fin + 26);
+        uint32_t *fw = (uint32_t *)(lds + L.fin + kFinishFloats);
         fw[0] = words[0]; fw[1] = words[1]; fw[2] = words[2]; fw[3] = words[3];
     }
     {
@@ -1168,7 +1073,7 @@ __global__ __launch_bounds__(kRowThreads) void taylor_row_logit_kernel(const voi
     if (threadIdx.x == 0) {
         uint32_t words[4];
         position_words(fin.d.seed, fin.d.offset + (uint64_t)row, words);
-        uint32_t *fw = (uint32_t *)(lds + L.fin + 26);
+        uint32_t *fw = (uint32_t *)(lds + L.fin + kFinishFloats);
         fw[0] = words[0]; fw[1] = words[1]; fw[2] = words[2]; fw[3] = words[3];
     }
     {

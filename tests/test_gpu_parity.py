@@ -356,6 +356,37 @@ def test_verify_degenerate_rows(rdk):
     assert (o.draft_ids.cpu().numpy()[10:20] == 1234).all()
 
 
+@pytest.mark.parametrize("p_kind", ["prob", "logit", "bf16"])
+def test_verify_large_batch(rdk, p_kind):
+    """From 128 positions on every row is finished by a workgroup of its own (a quarter of a 1024-id block per
+    wavefront): ragged N with a short last block, drawn and caller-supplied drafts, and the same finish on q' of Eq. 3
+    when the fused call also writes the rows out."""
+    w = synth.scaled(synth.WORKLOADS["tiny"], name="manyrows", N=5003, n=1201, seqs=26, gamma=5, seed=23)
+    data = make_inputs(w)
+    kept = data["kept_ids"]
+    if p_kind == "prob":
+        p_in, p_dev = data["p"], dev(data["p"])
+    elif p_kind == "logit":
+        p_in, p_dev = data["z_p"], dev(data["z_p"])
+    else:
+        p_in = synth.bf16_round(data["z_p"])
+        p_dev = bf16_tensor(p_in)
+    kind = "prob" if p_kind == "prob" else "logit"
+    p64 = oracle.probs_from(p_in, kind)
+    q64 = data["q_hat"].astype(np.float64)
+    ref_qp = oracle.redistribute_batch("taylor", q64, kept, w.N, p=p64)
+    qp32 = ref_qp.astype(np.float32)
+    run_verify_case(rdk, p_dev, kind, p64, qp32, w.gamma, seed=61, offset=7)
+    drafts = (np.arange(w.B, dtype=np.int32) * 977) % w.N
+    drafts[3] = w.N                                              # out of range: never accepted
+    run_verify_case(rdk, p_dev, kind, p64, qp32, w.gamma, seed=62, offset=0, draft_ids=drafts)
+    ki = rdk.rdk_build_kernel(w.N, dev(kept), rdk.IDENTITY)
+    rows = torch.empty(w.B, w.N, device="cuda")
+    o = rdk.rdk_redistribute_verify(ki, rdk.LINEAR_TAYLOR, p_dev, dev(data["q_hat"]), 63, 1, w.gamma, kind, q_prime=rows)
+    assert_close(rows.cpu().numpy(), ref_qp, what="q' of the fused call")
+    check_verify_outputs(o, oracle.verify_batch(p64, ref_qp, 63, 1, gamma=w.gamma), p64, ref_qp, 63, 1, w.gamma, kind)
+
+
 def test_fused_sparse_very_large_vocab(rdk):
     """The sparse form sums per 64-id block; above 262144 ids a row has more block sums than the finish keeps in registers
     (64 per lane), and they are re-read from memory when the crossings are located.  Drawn and caller-supplied drafts."""
