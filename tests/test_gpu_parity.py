@@ -770,6 +770,35 @@ def test_fused_eq3_single_pass_many_chunks(rdk):
     check_verify_outputs(o, ref, p64, ref_qp, seed, offset, w.gamma, "prob", min_exact=0.9)
 
 
+def test_large_batch_with_more_block_sums_than_registers(rdk):
+    """586 block sums of 1024 ids per row (N > 2^19) in a batch of 128 positions: the finish that eight wavefronts share
+    then re-reads the block sums when it locates the crossings instead of keeping them in registers -- out of LDS in the
+    one-pass Eq. 3 kernel, out of memory in the stand-alone verification and in the two-pass Eq. 3 path."""
+    w = synth.scaled(synth.WORKLOADS["tiny"], name="wide128", N=600011, n=3001, seqs=16, gamma=8, seed=37)
+    data = make_inputs(w)
+    kept = data["kept_ids"]
+    kern = rdk.rdk_build_kernel(w.N, dev(kept), rdk.IDENTITY)
+    p64, q64 = data["p"].astype(np.float64), data["q_hat"].astype(np.float64)
+    ref_qp = oracle.redistribute_batch("taylor", q64, kept, w.N, p=p64)
+    seed, offset = 909, 6
+    ref = oracle.verify_batch(p64, ref_qp, seed, offset, gamma=w.gamma)
+    p_d, q_d = dev(data["p"]), dev(data["q_hat"])
+    rdk.rdk_timing_select("taylor_row_kernel")
+    o = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, p_d, q_d, seed, offset, w.gamma)
+    torch.cuda.synchronize()
+    rdk.rdk_timing_select(None)
+    assert rdk.rdk_timing_read("taylor_row_kernel")[0] == 1          # the one-pass kernel took this call
+    check_verify_outputs(o, ref, p64, ref_qp, seed, offset, w.gamma, "prob", min_exact=0.9)
+    rows = torch.empty(w.B, w.N, device="cuda")
+    o2 = rdk.rdk_redistribute_verify(kern, rdk.LINEAR_TAYLOR, p_d, q_d, seed, offset, w.gamma, q_prime=rows)
+    check_verify_outputs(o2, ref, p64, ref_qp, seed, offset, w.gamma, "prob", min_exact=0.9)
+    qp32 = rows.cpu().numpy()
+    assert_close(qp32, ref_qp, what="q' of the fused call")
+    run_verify_case(rdk, p_d, "prob", p64, qp32, w.gamma, seed=910, offset=0)
+    drafts = (np.arange(w.B, dtype=np.int32) * 50021) % w.N
+    run_verify_case(rdk, p_d, "prob", p64, qp32, w.gamma, seed=911, offset=1, draft_ids=drafts)
+
+
 # --------------------------------------------------------------------------------------------- HIP graph capture
 @pytest.mark.parametrize("mode", ["sparse", "taylor"])
 def test_fused_call_replays_from_a_hip_graph(rdk, ragged, mode):
