@@ -210,8 +210,8 @@ def run_linear(args, rdk, torch, w, vocab, batch, mode_name, path, steps, warmup
                                       "frac": round(lines * 128 / avg_s / 1e9 / l1_peak, 4),
                                       "bare_gather_loop_GBs": round(measured, 1),
                                       "frac_of_bare_gather_loop": round(lines * 128 / avg_s / 1e9 / measured, 4)}
-    if fused and w.name == "llama3":
-        # context, not the metric: two batches in flight on two streams (own outputs and workspaces), so that the
+    if fused and args.in_flight > 1:
+        # context, not the metric (opt-in: overlapping launches would blur the per-kernel averages of a profile): two batches in flight on two streams (own outputs and workspaces), so that the
         # latency-bound end of one batch's step overlaps the streaming start of the next one's
         streams = [torch.cuda.Stream() for _ in range(2)]
         vouts2 = [rdk.VerifyOutputs(B, w.N, w.gamma, dev) for _ in range(2)]
@@ -374,6 +374,7 @@ def main():
                     help="fused: rdk_redistribute_verify (q' never stored); twocall: rdk_redistribute_linear + rdk_verify_sample")
     ap.add_argument("--workload", default=None)
     ap.add_argument("--copies", type=int, default=4, help="input/output buffer sets rotated through (defeats the 256 MB cache)")
+    ap.add_argument("--in-flight", type=int, default=1, help="2: also time two batches in flight on two streams (extra.two_batches_in_flight)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the other forms and workloads")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of each of the two oracle timings")
