@@ -2,7 +2,8 @@
 // verify call and by the fused redistribute+verify calls.
 //
 // Input: for every row three partial sums per block of BLOCK ids (sum q', sum max(0, p - q'),
-// sum min(p, q')), written by a streaming pass.  One wavefront per row then
+// sum min(p, q')), written by a streaming pass.  One wavefront per row (small batches; large ones spread the same
+// steps over four or eight wavefronts, see verify_finalize_wide_kernel and finish_row_quarters) then
 //   1. adds the partials in fp64 (alpha, residual mass, sum q'), draws the Philox uniforms,
 //   2. finds the blocks in which the two inverse-CDF thresholds are crossed,
 //   3. re-reads (or re-computes) those blocks and scans them in fp64 for the exact ids,
@@ -834,23 +835,29 @@ template <int KIND, int BLOCK, bool HAS_Q, class QP>
 rdk_status_t launch_finalize(FinalizeArgs a, QP qp, hipStream_t st)
 {
     const rdk_verify_desc_t &d = a.d;
-    // a policy that re-computes q' is heavy on the vector memory pipe of its CU: give every row a CU of its own
     // One wavefront per row is bound by its own chain of dependent steps, and eight of them on one compute unit share
-    // its four vector units: a large batch gets a compute unit per row (and the per-sequence scan a launch of its own),
-    // a small one keeps a sequence together and scans it in place.
+    // its four vector units: a large batch gets a workgroup per row (and the per-sequence scan a launch of its own),
+    // a small one keeps a sequence together and scans it in place.  A policy that re-computes q' is heavy on the vector
+    // memory pipe of its compute unit and always gets one per row.
     const bool spread = QP::kSpreadRows || d.B >= kSpreadMinRows;
     a.scan_here = d.gamma >= 1 && d.gamma <= kFinalizeRows && !spread;
     a.rows_per_block = a.scan_here ? d.gamma : (spread ? 1 : 4);
     const int blocks = (d.B + a.rows_per_block - 1) / a.rows_per_block;
-    if constexpr (QP::kSpreadRows && BLOCK == 64 && HAS_Q) {
+    constexpr bool kWide = QP::kSpreadRows && BLOCK == 64 && HAS_Q;   // four wavefronts per row, one id per lane
+    constexpr bool kQuarters = BLOCK == 1024 && HAS_Q;                // eight wavefronts per row when rows are spread
+    bool launched = false;
+    if constexpr (kWide) {
         RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_wide_kernel<KIND, QP>), dim3((unsigned)d.B), dim3(4 * kWave), 0,
                          st, a, qp);
-    } else if (BLOCK == 1024 && HAS_Q && spread) {
-        if constexpr (BLOCK == 1024 && HAS_Q) {
+        launched = true;
+    } else if constexpr (kQuarters) {
+        if (spread) {
             RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_quarters_kernel<KIND, QP>), dim3((unsigned)d.B),
                              dim3(8 * kWave), 0, st, a, qp);
+            launched = true;
         }
-    } else {
+    }
+    if (!launched) {
         RDK_TIMED_LAUNCH("verify_finalize_kernel", (verify_finalize_kernel<KIND, BLOCK, HAS_Q, QP>), dim3(blocks),
                          dim3(a.rows_per_block * kWave), 0, st, a, qp);
     }
